@@ -1,0 +1,129 @@
+"""Network-level oracle (TEST INFRASTRUCTURE ONLY): the 3D U-Net of Sec. 2.2, Eq. 2.
+
+Topology as the paper states it: an encoder of L blocks e_1..e_L applied in sequence, skip
+connections s_l that concatenate e_l with the decoder feature coming from below along the channel
+axis, decoder blocks d_{L-1}..d_1, and a softmax after the decoder.  Channel schedule from Sec. 3:
+the first block has `base` filters, doubled at every further encoder block, decoder symmetric.
+
+Readings where the paper is silent (each also listed in the design notes):
+  * d_L is the encoder output itself; there are L-1 real decoder blocks.
+  * block(Ca->Cb) = [conv3x3x3 -> InstanceNorm -> ReLU] twice; no conv bias inside blocks.
+  * 2x2x2 max-pool after every encoder block but the last.
+  * d_l = block(concat[e_l , up(d_{l+1})]) with up = 2x2x2 stride-2 transposed conv (with bias)
+    halving the channels; skip first in the concat, in the argument order of s_l(e_l, d_{l+1}).
+  * 1x1x1 head with bias to `classes` logits; loss = mean softmax cross entropy over all voxels.
+  * Gradient of e_l = pool-path gradient + concat-slice gradient (the two copies e_{l,0}, e_{l,1}
+    of Eq. 3 are the same tensor).
+
+`store` is applied to every activation / gradient tensor the GPU path keeps in its storage
+dtype (identity for the pure fp64 oracle, oracle.round_bf16 to emulate bf16 storage).
+
+Parameters are a dict by name:
+  enc{l}.conv{1,2}.w [Co,3,3,3,Ci]   (+ .gamma [Co], .beta [Co] when affine)
+  dec{l}.up.w [2C_l,2,2,2,C_l], dec{l}.up.b [C_l], dec{l}.conv{1,2}.w (+ gamma/beta)
+  head.w [classes,C_1], head.b [classes]
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle as O
+
+
+def _ident(a):
+    return a
+
+
+def _block_fwd(params, prefix, a, eps, store, cache):
+    for i in (1, 2):
+        name = f"{prefix}.conv{i}"
+        z = store(O.conv3d_fwd(a, params[name + ".w"]))
+        y, stats = O.inorm_relu(z, params.get(name + ".gamma"), params.get(name + ".beta"), eps)
+        y = store(y)
+        cache[name] = dict(x=a, z=z, y=y, stats=stats)
+        a = y
+    return a
+
+
+def forward(params, x, levels, eps=1e-5, store=_ident, first_level=1, last_level=None):
+    """Whole net (default) -> (logits, cache).  With first_level/last_level set to an encoder
+    range it runs only that pipeline partition (Sec. 2.1: a part = consecutive layers) and
+    returns ((pooled_output, [skips...]), cache)."""
+    cache = {}
+    a = np.asarray(x, dtype=np.float64)
+    skips = {}
+    enc_last = levels if last_level is None else last_level
+    for l in range(first_level, enc_last + 1):
+        a = _block_fwd(params, f"enc{l}", a, eps, store, cache)
+        if l < levels:
+            skips[l] = a
+            p = store(O.maxpool2_fwd(a))
+            cache[f"pool{l}"] = dict(x=a)
+            a = p
+    if last_level is not None and last_level < levels:
+        return (a, [skips[l] for l in range(first_level, enc_last + 1)]), cache
+    for l in range(levels - 1, 0, -1):
+        up = store(O.convtr3d_fwd(a, params[f"dec{l}.up.w"], params[f"dec{l}.up.b"]))
+        cache[f"dec{l}.up"] = dict(x=a)
+        cat = np.concatenate([skips[l], up], axis=-1)
+        a = _block_fwd(params, f"dec{l}", cat, eps, store, cache)
+    logits = O.head_fwd(a, params["head.w"], params["head.b"])
+    cache["head"] = dict(x=a)
+    return logits, cache
+
+
+def _block_bwd(params, prefix, g, eps, store, cache, grads, need_dx=True):
+    for i in (2, 1):
+        name = f"{prefix}.conv{i}"
+        c = cache[name]
+        dz, dgam, dbet = O.inorm_relu_bwd(g, c["z"], params.get(name + ".gamma"), params.get(name + ".beta"), eps)
+        dz = store(dz)
+        if name + ".gamma" in params:
+            grads[name + ".gamma"] = dgam
+            grads[name + ".beta"] = dbet
+        grads[name + ".w"], _ = O.conv3d_wgrad(c["x"], dz)
+        if i == 1 and not need_dx:
+            return None
+        g = store(O.conv3d_dgrad(dz, params[name + ".w"]))
+    return g
+
+
+def backward(params, cache, dlogits, levels, eps=1e-5, store=_ident):
+    """Reverse composition of the adjoints; returns grads dict with the names of params."""
+    grads = {}
+    g, grads["head.w"], grads["head.b"] = O.head_bwd(cache["head"]["x"], params["head.w"], dlogits)
+    g = store(g)
+    skip_g = {}
+    for l in range(1, levels):
+        g = _block_bwd(params, f"dec{l}", g, eps, store, cache, grads)
+        C = g.shape[-1] // 2
+        skip_g[l] = g[..., :C]
+        gup = np.ascontiguousarray(g[..., C:])
+        c = cache[f"dec{l}.up"]
+        g, grads[f"dec{l}.up.w"], grads[f"dec{l}.up.b"] = O.convtr3d_bwd(c["x"], params[f"dec{l}.up.w"], gup)
+        g = store(g)
+    for l in range(levels, 0, -1):
+        if l < levels:
+            g = O.maxpool2_bwd(cache[f"pool{l}"]["x"], g) + skip_g[l]
+            g = store(g)
+        g = _block_bwd(params, f"enc{l}", g, eps, store, cache, grads, need_dx=(l > 1))
+    return grads
+
+
+def loss_and_grads(params, x, labels, levels, eps=1e-5, store=_ident):
+    logits, cache = forward(params, x, levels, eps, store)
+    loss, dlogits = O.cross_entropy(logits, labels)
+    grads = backward(params, cache, dlogits, levels, eps, store)
+    return loss, grads, logits, cache
+
+
+def stage_backward(params, cache, g_pool, g_skips, first_level, last_level, levels, eps=1e-5, store=_ident):
+    """Backward of an encoder-only partition given upstream gradients for its pooled output and
+    for each skip output (the e_{l,1} copies of Eq. 3).  Returns grads of its conv weights."""
+    grads = {}
+    g = g_pool
+    for l in range(last_level, first_level - 1, -1):
+        g = O.maxpool2_bwd(cache[f"pool{l}"]["x"], g) + g_skips[l - first_level]
+        g = store(g)
+        g = _block_bwd(params, f"enc{l}", g, eps, store, cache, grads, need_dx=(l > first_level or first_level > 1))
+    return grads, g
