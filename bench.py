@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on ONE MI355X.
+
+A "step" is one pass of the whole hot path over one batch of the headline workload:
+the single conv block of the benchmark configuration -- Conv3d 3x3x3 (64 -> 64 channels) on a
+1 x 128^3 NDHWC bf16 volume with InstanceNorm + ReLU, forward, data-gradient and weight-gradient:
+
+    z, stats = conv3d_fwd(x, W)            (matrix-core implicit GEMM, statistics in the epilogue)
+    y        = inorm_relu(z, stats)
+    dz       = inorm_relu_bwd(dy, z, stats)
+    dx       = conv3d_dgrad(dz, W)
+    dW       = conv3d_wgrad(x, dz)         (fp32)
+
+Inputs are synthetic (N(0,1) activations and upstream gradient, Kaiming-normal weights), resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--size", type=int, default=128, help="cubic volume side (default: the benchmark's 128)")
+    ap.add_argument("--channels", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
+              "(the path has no collectives; see DESIGN.md for how it would shard).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import lamp_synth as S
+    import paper_2006_12575_amd as L
+
+    L.lib()  # fails loudly when the HIP library is missing
+    dev = "cuda:0"
+    bf, f32 = torch.bfloat16, torch.float32
+    N, D, C = 1, args.size, args.channels
+    rx, rw, rg = S.streams(1002, 3)
+
+    def normal_dev(rng, shape):
+        # generated in slabs to keep host memory modest
+        t = torch.empty(shape, dtype=bf, device=dev)
+        for d in range(shape[1]):
+            t[:, d] = torch.from_numpy(S.normal(rng, (shape[0],) + tuple(shape[2:]))).to(bf).to(dev)
+        return t
+
+    x = normal_dev(rx, (N, D, D, D, C))
+    dy = normal_dev(rg, (N, D, D, D, C))
+    w = torch.from_numpy(S.kaiming_conv(rw, C, C)).to(bf).to(dev)
+    z = torch.empty_like(x)
+    y = torch.empty_like(x)
+    dz = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    dw = torch.empty(w.shape, dtype=f32, device=dev)
+    stats = torch.empty((N, C, 2), dtype=f32, device=dev)
+    xd, zd = L.desc(x), L.desc(z)
+    import ctypes
+    need = max(L.lib().lamp_conv3d_fwd_workspace_bytes(ctypes.byref(xd), ctypes.byref(zd), 1),
+               L.lib().lamp_conv3d_dgrad_workspace_bytes(ctypes.byref(zd), ctypes.byref(xd)),
+               L.lib().lamp_conv3d_wgrad_workspace_bytes(ctypes.byref(xd), ctypes.byref(zd)),
+               L.lib().lamp_inorm_relu_bwd_workspace_bytes(ctypes.byref(zd)))
+    ws = torch.empty(int(need) + 256, dtype=torch.uint8, device=dev)
+
+    def step():
+        L.lamp_conv3d_fwd(x, w, z, stats_out=stats, ws=ws)
+        L.lamp_inorm_relu(z, y, stats, stats_given=True, ws=ws)
+        L.lamp_inorm_relu_bwd(dy, z, stats, dz, ws=ws)
+        L.lamp_conv3d_dgrad(dz, w, dx, ws=ws)
+        L.lamp_conv3d_wgrad(x, dz, dw, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    V = N * D * D * D
+    flops_conv = 2.0 * V * 27 * C * C
+    tflops = 3 * flops_conv / dt / 1e12
+
+    # ---- roofline of the dominant kernel: the forward implicit-GEMM conv, timed alone with
+    # events on the launch stream (torch's current stream is the one the binding launches on)
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    reps = max(3, args.steps)
+    parts = {
+        "conv3d_fwd": timed(lambda: L.lamp_conv3d_fwd(x, w, z, stats_out=stats, ws=ws), reps),
+        "inorm_relu": timed(lambda: L.lamp_inorm_relu(z, y, stats, stats_given=True, ws=ws), reps),
+        "inorm_relu_bwd": timed(lambda: L.lamp_inorm_relu_bwd(dy, z, stats, dz, ws=ws), reps),
+        "conv3d_dgrad": timed(lambda: L.lamp_conv3d_dgrad(dz, w, dx, ws=ws), reps),
+        "conv3d_wgrad": timed(lambda: L.lamp_conv3d_wgrad(x, dz, dw, ws=ws), reps),
+    }
+    t_fwd = parts["conv3d_fwd"]
+    roof = {"bound": "mfma", "kernel": "conv3d_fwd (implicit GEMM 64->64, 128^3)",
+            "achieved": flops_conv / t_fwd / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": flops_conv / t_fwd / 1e12 / PEAK_BF16_TFLOPS, "traffic": None}
+    traffic_file = os.path.join(ROOT, "profiles", "conv3d_fwd_traffic_bytes.txt")
+    if os.path.exists(traffic_file) and args.size == 128 and args.channels == 64:
+        try:
+            roof["traffic"] = float(open(traffic_file).read().split()[0])
+        except Exception:
+            roof["traffic"] = None
+
+    out = {
+        "metric": "Conv3d fwd+bwd TFLOP/s (% MFMA peak); whole-U-Net voxels/sec at 1 GPU",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"conv block fwd+dgrad+wgrad, bf16/fp32-acc, N=1 C={C}->{C} {D}^3 NDHWC, "
+                               f"3x3x3 pad 1 + InstanceNorm + ReLU", "voxels": V,
+                   "flop_per_step": 3 * flops_conv},
+        "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "voxels_per_s": V / dt,
+        "ms_parts": {k: v * 1e3 for k, v in parts.items()},
+        "tflops_parts": {k: flops_conv / parts[k] / 1e12 for k in ("conv3d_fwd", "conv3d_dgrad", "conv3d_wgrad")},
+        "gbs_parts": {"inorm_relu": 2 * V * C * 2 / parts["inorm_relu"] / 1e9,
+                      "inorm_relu_bwd": (2 * 2 + 3) * V * C * 2 / 2 / parts["inorm_relu_bwd"] / 1e9},
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle as O
+        s = 48  # bounded sample: the same block on a 48^3 sub-volume, all 64 channels
+        xs = x[:, :s, :s, :s, :].to(torch.float64).cpu().numpy()
+        dys = dy[:, :s, :s, :s, :].to(torch.float64).cpu().numpy()
+        w64 = w.to(torch.float64).cpu().numpy()
+        O.num_threads()
+        t0 = time.perf_counter()
+        zz = O.conv3d_fwd(xs, w64)
+        yy, _ = O.inorm_relu(zz)
+        dzz, _, _ = O.inorm_relu_bwd(dys, zz)
+        O.conv3d_dgrad(dzz, w64)
+        O.conv3d_wgrad(xs, dzz)
+        tc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 3 * 2.0 * s ** 3 * 27 * C * C / tc / 1e12, "unit": "TFLOP/s",
+                               "cores": O.num_threads(), "kind": "oracle",
+                               "sample": f"same conv block (fwd+dgrad+wgrad, fp64) on a {s}^3 sub-volume of the "
+                                         f"workload, C={C}, {tc:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

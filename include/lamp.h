@@ -1,0 +1,276 @@
+/*
+ * lamp.h -- C ABI of the MI355X (gfx950) compute library for the per-device hot path of the
+ * large 3D U-Net of LAMP (arXiv 2006.12575).
+ *
+ * The paper pipelines a sequential U-Net over devices (Sec. 2.1, Eq. 1: a partition's forward
+ * F_k is the composition of its layers, its backward B_k the chain rule; Sec. 2.2, Eq. 2-3: the
+ * U-Net as encoder blocks, skip concatenations and decoder blocks).  This library is what runs
+ * on ONE device: the layers themselves, a whole U-Net forward / forward+backward, one encoder
+ * partition, and sliding-window inference (Sec. 3, Tables 3 and 5 compare windows with one
+ * whole-image pass).
+ *
+ * Conventions, valid for every entry point:
+ *   - All tensor pointers are DEVICE pointers unless a comment says "host".  Descriptor structs
+ *     and the `params` / `grads` pointer tables are HOST memory, read during the call only.
+ *   - Activations are NDHWC: element (n,d,h,w,c) lives at ((((n*D+d)*H+h)*W+w)*ldc + c).
+ *     ldc >= c is the channel stride of a voxel, so a tensor may be a channel slice of a wider
+ *     (concatenation) buffer.  Batch/spatial strides are dense in units of ldc.
+ *   - dtype LAMP_F32: 4-byte IEEE floats.  LAMP_BF16: 2-byte bfloat16 storage, fp32 accumulation,
+ *     round-to-nearest-even on store.  Weights have the activation dtype; gamma/beta, statistics,
+ *     logits, the loss and every weight gradient are fp32.
+ *   - Conv weight W[Co][3][3][3][Ci]; transposed-conv weight Wt[Ci][2][2][2][Co]; head Wh[K][C].
+ *   - Ownership: the caller owns every buffer including the workspace; the library allocates
+ *     nothing, frees nothing and keeps no pointer after the call returns.
+ *   - Asynchrony: a call only enqueues work on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream); outputs are valid once the caller has synchronised the stream.
+ *   - Errors: every argument error is detected on the host before anything is launched and
+ *     returned as a negative lamp_status; nothing is thrown, nothing aborts.  Device data is
+ *     never validated (an out-of-range label is the caller's bug).
+ *   - Determinism: the same inputs give bit-identical outputs from call to call (no
+ *     floating-point atomics; every reduction has a fixed order).
+ *   - Workspace: each call states its need through the matching *_workspace_bytes query;
+ *     pointers must be 16-byte aligned (hipMalloc / torch allocations are).
+ */
+#ifndef LAMP_H
+#define LAMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LAMP_OK = 0,
+    LAMP_ERR_NULL = -1,        /* a required pointer is NULL */
+    LAMP_ERR_SHAPE = -2,       /* non-positive / mismatching / unsupported dimension */
+    LAMP_ERR_ALIGN = -3,       /* pointer or channel stride not aligned as required */
+    LAMP_ERR_DTYPE = -4,       /* unknown or mismatching dtype */
+    LAMP_ERR_WORKSPACE = -5,   /* workspace missing or smaller than the query says */
+    LAMP_ERR_UNSUPPORTED = -6, /* valid request this build cannot serve */
+    LAMP_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
+} lamp_status;
+
+typedef enum { LAMP_F32 = 0, LAMP_BF16 = 1 } lamp_dtype;
+
+/* NDHWC tensor view. */
+typedef struct {
+    int32_t n, d, h, w, c;
+    int32_t ldc;   /* channel stride of a voxel, >= c */
+    int32_t dtype; /* lamp_dtype */
+} lamp_tensor_desc;
+
+/*
+ * Optional "normalise + ReLU while loading" of an input tensor: channels [0,c_norm) are read as
+ *   max(0, gamma[c]*(v - mean[n,c])*rstd[n,c] + beta[c])        (max skipped when relu == 0)
+ * and channels [c_norm, c) are read unchanged (the transposed-conv half of a concat buffer).
+ * Zero padding is applied AFTER the transform (out-of-volume reads are literal zeros).
+ * mean_rstd: fp32 [N][c_norm][2]; gamma, beta: fp32 [c_norm], NULL = 1 / 0.
+ */
+typedef struct {
+    const float *mean_rstd;
+    const float *gamma;
+    const float *beta;
+    int32_t c_norm;
+    int32_t relu;
+} lamp_norm_in;
+
+const char *lamp_status_string(lamp_status s);
+/* Library version and the GPU architecture its kernels were compiled for ("gfx950"). */
+const char *lamp_build_info(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * 3x3x3 convolution, padding 1, stride 1 (the conv of every U-Net block, Sec. 2.2 / Sec. 3).
+ *   z[n,d,h,w,co] = bias[co] + sum_{kd,kh,kw,ci} X[n,d+kd-1,h+kh-1,w+kw-1,ci] * W[co,kd,kh,kw,ci]
+ * with X = x, or x transformed by *xnorm.  Cross-correlation; out-of-volume reads are zero.
+ *   x, z      : activations described by xd, zd (same n,d,h,w; same dtype).
+ *   xnorm     : nullable.
+ *   bias      : nullable, fp32 [Co].
+ *   stats_out : nullable, fp32 [N][Co][2] = (mean, rstd = 1/sqrt(biased var + eps)) of the STORED
+ *               z over d,h,w -- the InstanceNorm statistics, produced in the conv epilogue.
+ * bf16 requires pointers 16-byte aligned; any Ci, Co >= 1 is accepted (multiples of 32 take the
+ * matrix-core kernels).
+ */
+size_t lamp_conv3d_fwd_workspace_bytes(const lamp_tensor_desc *xd, const lamp_tensor_desc *zd, int want_stats);
+lamp_status lamp_conv3d_fwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                            const void *w, const float *bias,
+                            const lamp_tensor_desc *zd, void *z,
+                            float *stats_out, float eps,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* Data gradient of the convolution (the adjoint in x; B_k of Sec. 2.1):
+ *   dx[n,i,j,k,ci] = sum_{kd,kh,kw,co} dz[n,i-kd+1,j-kh+1,k-kw+1,co] * W[co,kd,kh,kw,ci]  */
+size_t lamp_conv3d_dgrad_workspace_bytes(const lamp_tensor_desc *dzd, const lamp_tensor_desc *dxd);
+lamp_status lamp_conv3d_dgrad(const lamp_tensor_desc *dzd, const void *dz, const void *w,
+                              const lamp_tensor_desc *dxd, void *dx,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Weight gradient, always fp32:
+ *   dW[co,kd,kh,kw,ci] = beta*dW + sum_{n,d,h,w} dz[n,d,h,w,co] * X[n,d+kd-1,h+kh-1,w+kw-1,ci]
+ *   dbias[co]          = beta*dbias + sum dz[...,co]                       (dbias nullable)
+ * beta is 0 (overwrite; previous contents ignored) or 1 (accumulate: the synchronous gradient
+ * accumulation over micro-batches of Sec. 2.1).  X = x or x transformed by *xnorm. */
+size_t lamp_conv3d_wgrad_workspace_bytes(const lamp_tensor_desc *xd, const lamp_tensor_desc *dzd);
+lamp_status lamp_conv3d_wgrad(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                              const lamp_tensor_desc *dzd, const void *dz,
+                              float *dw, float *dbias, float beta,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * InstanceNorm + ReLU of a conv output (the normalisation/activation of every block).
+ * Per (n,c) over V = d*h*w: mean, biased variance, rstd = 1/sqrt(var+eps);
+ *   y = max(0, gamma[c]*(z-mean)*rstd + beta[c]).
+ *   stats     : fp32 [N][C][2] (mean, rstd).  If stats_given != 0 it is an INPUT (e.g. produced by
+ *               lamp_conv3d_fwd) and only the apply pass runs; otherwise it is computed and written.
+ *   y         : same shape/dtype as z (own descriptor: ldc may differ); may alias z.
+ *   gamma/beta: fp32 [C], NULL = 1 / 0.
+ */
+size_t lamp_inorm_relu_workspace_bytes(const lamp_tensor_desc *zd);
+lamp_status lamp_inorm_relu(const lamp_tensor_desc *zd, const void *z,
+                            const float *gamma, const float *beta, float eps,
+                            const lamp_tensor_desc *yd, void *y,
+                            float *stats, int stats_given,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* Backward of InstanceNorm + ReLU.  With zh = (z-mean)*rstd, u = gamma*zh+beta, g = dy*[u>0]:
+ *   dz = gamma*rstd*( g - mean_v(g) - zh*mean_v(g*zh) )        per (n,c)
+ *   dgamma[c] = beta_acc*dgamma + sum_{n,v} g*zh ; dbeta[c] = beta_acc*dbeta + sum_{n,v} g   (nullable)
+ *   dy, z, dz : same n,d,h,w,c; dz may alias dy.  stats: fp32 [N][C][2] from the forward. */
+size_t lamp_inorm_relu_bwd_workspace_bytes(const lamp_tensor_desc *zd);
+lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc *dyd, const void *dy,
+                                const lamp_tensor_desc *zd, const void *z, const float *stats,
+                                const float *gamma, const float *beta,
+                                const lamp_tensor_desc *dzd, void *dz,
+                                float *dgamma, float *dbeta, float beta_acc,
+                                void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * 2x2x2 max pooling, stride 2 (between encoder blocks).  d,h,w of x must be even.
+ *   y[n,d,h,w,c] = max_{i,j,k in {0,1}} X[n,2d+i,2h+j,2w+k,c]
+ * Backward: dx = dy at the arg-max (first in (i,j,k) raster order under strict '>'), 0 elsewhere,
+ * plus add[...] when `add` is given (the gradient arriving through the skip copy of the same
+ * tensor, Eq. 3).  x in the backward is the tensor the forward pooled (after *xnorm). */
+lamp_status lamp_maxpool2_fwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                              const lamp_tensor_desc *yd, void *y, void *stream);
+lamp_status lamp_maxpool2_bwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                              const lamp_tensor_desc *dyd, const void *dy,
+                              const lamp_tensor_desc *addd, const void *add,
+                              const lamp_tensor_desc *dxd, void *dx, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * 2x2x2 stride-2 transposed convolution (decoder upsampling; "decoder symmetric", Sec. 3).
+ *   y[n,2d+i,2h+j,2w+k,co] = bias[co] + sum_ci X[n,d,h,w,ci] * Wt[ci,i,j,k,co]
+ * yd may have ldc = 2*Co with y pointing at channel Co of a concat buffer (zero-copy skip concat).
+ * Backward (each output nullable):
+ *   dx[n,d,h,w,ci]   = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * Wt[ci,i,j,k,co]
+ *   dWt[ci,i,j,k,co] = beta*dWt + sum_{n,d,h,w} X[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]   (fp32)
+ *   dbias[co]        = beta*dbias + sum dy[...,co]                                          (fp32) */
+lamp_status lamp_convtr3d(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                          const void *wt, const float *bias,
+                          const lamp_tensor_desc *yd, void *y, void *stream);
+size_t lamp_convtr3d_bwd_workspace_bytes(const lamp_tensor_desc *xd, const lamp_tensor_desc *dyd);
+lamp_status lamp_convtr3d_bwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                              const void *wt, const lamp_tensor_desc *dyd, const void *dy,
+                              const lamp_tensor_desc *dxd, void *dx,
+                              float *dwt, float *dbias, float beta,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * 1x1x1 head + softmax (+ cross entropy): "a softmax function after decoder D" (Sec. 2.2).
+ *   logits[v,k] = bh[k] + sum_c X[v,c]*Wh[k,c]   (fp32 [N,D,H,W,K], dense)
+ * lamp_head_fwd writes logits only.  lamp_head_ce additionally takes int32 labels [N,D,H,W] and
+ * produces  loss = -(1/V) sum_v log softmax(logits_v)[label_v]  (V = n*d*h*w, device fp32 scalar),
+ *   dlogits = (softmax - onehot)/V, and from it dx[v,c] = sum_k dlogits[v,k]*Wh[k,c] (dtype of x),
+ *   dWh[k,c] = beta*dWh + sum_v dlogits[v,k]*X[v,c], dbh[k] = beta*dbh + sum_v dlogits[v,k].
+ * logits may be NULL in lamp_head_ce.  K <= 16. */
+size_t lamp_head_ce_workspace_bytes(const lamp_tensor_desc *xd, int classes);
+lamp_status lamp_head_fwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                          const void *wh, const float *bh, int classes, float *logits, void *stream);
+lamp_status lamp_head_ce(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
+                         const void *wh, const float *bh, int classes, const int32_t *labels,
+                         float *logits, float *loss,
+                         const lamp_tensor_desc *dxd, void *dx, float *dwh, float *dbh, float beta,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Whole U-Net (Sec. 2.2 Eq. 2; channel schedule of Sec. 3).
+ *   levels encoder blocks; block l has C_l = base*2^(l-1) filters; block = two
+ *   [conv3x3x3 (no bias) -> InstanceNorm -> ReLU]; 2x2x2 max-pool after every encoder block but the
+ *   last; decoder block l = block applied to concat[e_l , convtr(d_{l+1})] (skip first, Eq. 2's
+ *   argument order s_l(e_l, d_{l+1})); d_levels is the encoder output; 1x1x1 head to `classes`.
+ *   d, h, w must be divisible by 2^(levels-1).
+ * Parameter table (host array of device pointers), in this order:
+ *   for l = 1..levels:      enc l conv1 W [, gamma, beta], conv2 W [, gamma, beta]
+ *   for l = levels-1..1:    up Wt [2C_l][2][2][2][C_l], up bias [C_l] (fp32),
+ *                           dec l conv1 W [C_l][3][3][3][2C_l] [, gamma, beta], conv2 W [, gamma, beta]
+ *   head Wh [classes][C_1], head bias [classes] (fp32)
+ * gamma/beta entries exist only when affine != 0 (fp32 [C]).  W/Wt/Wh have dtype `dtype`.
+ * `grads` has the same order; every entry fp32 with the parameter's shape; beta = 0 overwrites,
+ * beta = 1 accumulates (micro-batch accumulation, Sec. 2.1).
+ */
+typedef struct {
+    int32_t levels, base, in_ch, classes;
+    int32_t n, d, h, w;
+    int32_t dtype; /* lamp_dtype of activations and weights */
+    float eps;
+    int32_t affine;
+} lamp_unet_desc;
+
+/* Number of entries of the parameter table, and the element count of entry idx (0 on bad idx). */
+int32_t lamp_unet_param_count(const lamp_unet_desc *desc);
+int64_t lamp_unet_param_numel(const lamp_unet_desc *desc, int32_t idx);
+size_t lamp_unet_workspace_bytes(const lamp_unet_desc *desc, int with_backward);
+
+/* x: [N,D,H,W,in_ch] dense, dtype desc->dtype.  logits: fp32 [N,D,H,W,classes]. */
+lamp_status lamp_unet_fwd(const lamp_unet_desc *desc, const void *const *params, const void *x,
+                          float *logits, void *ws, size_t ws_bytes, void *stream);
+/* Forward, mean softmax cross entropy against int32 labels [N,D,H,W], and the gradient of the loss
+ * with respect to every parameter.  loss: device fp32 scalar.  logits nullable. */
+lamp_status lamp_unet_fwd_bwd(const lamp_unet_desc *desc, const void *const *params, const void *x,
+                              const int32_t *labels, float *logits, float *loss,
+                              float *const *grads, float beta,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* One pipeline partition made of encoder blocks first_level..last_level (Sec. 2.1: a partition is a
+ * run of consecutive layers; Sec. 2.2 Eq. 3: each e_l leaves the partition twice, as the pooled
+ * tensor that feeds the next block and as the skip copy e_{l,1}).  Requires last_level < levels.
+ *   x          : input of block first_level ([N,D,H,W,in_ch] when first_level == 1), already at the
+ *                resolution of that level (desc->d,h,w are the partition's input dims).
+ *   params     : table of the partition's own conv parameters in the order above.
+ *   pooled     : output, pool(e_last) [N, D/2^k.., C_last], k = number of blocks.
+ *   skips[i]   : output, e_{first+i} (activated), dense.
+ * Backward takes x and skips again (the forward's input and outputs, unchanged), the gradients of
+ * all outputs, and the SAME workspace the forward ran in, untouched since (it holds the saved conv
+ * outputs and statistics); it returns the partition's weight gradients and, when dx != NULL and
+ * first_level > 1, the gradient of its input.  desc->d,h,w are the partition's input dims and must
+ * be divisible by 2^(number of blocks). */
+size_t lamp_unet_stage_workspace_bytes(const lamp_unet_desc *desc, int first_level, int last_level, int with_backward);
+lamp_status lamp_unet_stage_fwd(const lamp_unet_desc *desc, int first_level, int last_level,
+                                const void *const *params, const void *x,
+                                void *pooled, void *const *skips,
+                                void *ws, size_t ws_bytes, void *stream);
+lamp_status lamp_unet_stage_bwd(const lamp_unet_desc *desc, int first_level, int last_level,
+                                const void *const *params, const void *x, const void *const *skips,
+                                const void *d_pooled, const void *const *d_skips,
+                                float *const *grads, float beta, void *dx,
+                                void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Sliding-window inference (Sec. 3, Tables 3/5: windows versus one whole-image pass).
+ * The volume [1,D,H,W,in_ch] is covered by cubic windows of side `patch` with stride
+ * round(patch*(1-overlap)), the last window of an axis clamped to the border; the windows are run
+ * through the U-Net as one batch (patch_desc->n must equal the window count and d=h=w=patch), and
+ * the window logits are blended with a Gaussian weight of sigma = sigma_scale*patch centred on the
+ * window:  out[v] = sum_win g*logits_win[v] / sum_win g.   out: fp32 [1,D,H,W,classes]. */
+int32_t lamp_sliding_window_count(int32_t D, int32_t H, int32_t W, int32_t patch, float overlap);
+size_t lamp_sliding_window_workspace_bytes(const lamp_unet_desc *patch_desc, int32_t D, int32_t H, int32_t W);
+lamp_status lamp_sliding_window_fwd(const lamp_unet_desc *patch_desc, const void *const *params,
+                                    const void *vol, int32_t D, int32_t H, int32_t W,
+                                    float overlap, float sigma_scale, float *out,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAMP_H */

@@ -1,0 +1,205 @@
+// 3x3x3 convolution: public entry points, argument checking, kernel selection, and the generic
+// direct kernels (any dtype / channel count) that serve the fp32 path and odd channel counts.
+// Shapes with channel counts in multiples of 32 in bf16 go to the matrix-core kernels.
+#include "internal.h"
+
+namespace lamp {
+
+// out[v][oc] = bias[oc] + sum_t sum_ic in[v + t - 1][ic] * Wv(oc,t,ic)
+//   forward : Wv(oc,t,ic) = W[oc][t][ic]          (W is [Cout][27][Cin])
+//   dgrad   : Wv(oc,t,ic) = W[ic][26-t][oc]       (W is [Cin][27][Cout]: flipped taps, swapped roles)
+template <typename T, bool DGRAD>
+__global__ __launch_bounds__(256) void conv3d_direct_kernel(const T* __restrict__ x, int ldx, NormIn nm,
+                                                            const T* __restrict__ w, const float* __restrict__ bias,
+                                                            T* __restrict__ z, int ldz, int N, int D, int H, int W,
+                                                            int Cin, int Cout, int ocT, int vpb) {
+    const int oc = blockIdx.y * ocT + threadIdx.x % ocT;
+    const int vl = threadIdx.x / ocT;
+    if (vl >= vpb || oc >= Cout) return;
+    const int64_t total = (int64_t)N * D * H * W;
+    const int64_t v = (int64_t)blockIdx.x * vpb + vl;
+    if (v >= total) return;
+    int wv = (int)(v % W);
+    int64_t r = v / W;
+    int h = (int)(r % H);
+    r /= H;
+    int d = (int)(r % D);
+    int n = (int)(r / D);
+    float acc = bias ? bias[oc] : 0.f;
+    for (int t = 0; t < 27; ++t) {
+        int kd = t / 9, kh = (t / 3) % 3, kw = t % 3;
+        int id = d + kd - 1, ih = h + kh - 1, iw = wv + kw - 1;
+        if (id < 0 || id >= D || ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+        const T* xp = x + ((((int64_t)n * D + id) * H + ih) * W + iw) * ldx;
+        if (DGRAD) {
+            const T* wp = w + (int64_t)(26 - t) * Cout + oc;
+            for (int ic = 0; ic < Cin; ++ic)
+                acc = fmaf(load_norm(xp + ic, nm, n, ic), io<T>::ld(wp + (int64_t)ic * 27 * Cout), acc);
+        } else {
+            const T* wp = w + ((int64_t)oc * 27 + t) * Cin;
+            for (int ic = 0; ic < Cin; ++ic)
+                acc = fmaf(load_norm(xp + ic, nm, n, ic), io<T>::ld(wp + ic), acc);
+        }
+    }
+    io<T>::st(z + v * ldz + oc, acc);
+}
+
+// part[s][o] for o = (co*27 + t)*Ci + ci : sum over the voxels of split s.
+template <typename T>
+__global__ __launch_bounds__(256) void conv3d_wgrad_direct_kernel(const T* __restrict__ x, int ldx, NormIn nm,
+                                                                  const T* __restrict__ dz, int ldz,
+                                                                  float* __restrict__ part, int N, int D, int H, int W,
+                                                                  int Ci, int Co, int64_t vps) {
+    const int64_t O = (int64_t)Co * 27 * Ci;
+    const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (o >= O) return;
+    const int ci = (int)(o % Ci);
+    const int t = (int)((o / Ci) % 27);
+    const int co = (int)(o / ((int64_t)27 * Ci));
+    const int kd = t / 9 - 1, kh = (t / 3) % 3 - 1, kw = t % 3 - 1;
+    const int64_t total = (int64_t)N * D * H * W;
+    int64_t v0 = (int64_t)blockIdx.y * vps, v1 = v0 + vps;
+    if (v1 > total) v1 = total;
+    int wv = (int)(v0 % W);
+    int64_t r = v0 / W;
+    int h = (int)(r % H);
+    r /= H;
+    int d = (int)(r % D);
+    int n = (int)(r / D);
+    float acc = 0.f;
+    for (int64_t v = v0; v < v1; ++v) {
+        int id = d + kd, ih = h + kh, iw = wv + kw;
+        if (id >= 0 && id < D && ih >= 0 && ih < H && iw >= 0 && iw < W) {
+            const T* xp = x + ((((int64_t)n * D + id) * H + ih) * W + iw) * ldx + ci;
+            acc = fmaf(io<T>::ld(dz + v * ldz + co), load_norm(xp, nm, n, ci), acc);
+        }
+        if (++wv == W) { wv = 0; if (++h == H) { h = 0; if (++d == D) { d = 0; ++n; } } }
+    }
+    part[(int64_t)blockIdx.y * O + o] = acc;
+}
+
+static int wgrad_splits(int64_t V, int64_t O) {
+    int64_t s = (V + 255) / 256;
+    int64_t cap = (int64_t)(32u << 20) / (O * 4);
+    if (cap < 1) cap = 1;
+    if (s > cap) s = cap;
+    if (s > 8192) s = 8192;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+static lamp_status check_conv_pair(const lamp_tensor_desc* a, const void* pa, const lamp_tensor_desc* b, const void* pb) {
+    if (!a || !b || !pa || !pb) return LAMP_ERR_NULL;
+    if (!desc_ok(a) || !desc_ok(b) || !same_space(a, b)) return LAMP_ERR_SHAPE;
+    if (a->dtype != b->dtype) return LAMP_ERR_DTYPE;
+    if (a->dtype == LAMP_BF16 && (!aligned16(pa) || !aligned16(pb))) return LAMP_ERR_ALIGN;
+    return LAMP_OK;
+}
+
+template <bool DGRAD>
+static lamp_status launch_direct(const lamp_tensor_desc* xd, const void* x, NormIn nm, const void* w, const float* bias,
+                                 const lamp_tensor_desc* zd, void* z, hipStream_t s) {
+    const int Cout = zd->c, Cin = xd->c;
+    const int ocT = Cout < 256 ? Cout : 256;
+    const int vpb = 256 / ocT;
+    const int64_t total = nvox(zd);
+    dim3 grid(cdiv(total, vpb), cdiv(Cout, ocT));
+    if (xd->dtype == LAMP_BF16)
+        hipLaunchKernelGGL((conv3d_direct_kernel<bf16_t, DGRAD>), grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, nm,
+                           (const bf16_t*)w, bias, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, Cin, Cout, ocT, vpb);
+    else
+        hipLaunchKernelGGL((conv3d_direct_kernel<float, DGRAD>), grid, dim3(256), 0, s, (const float*)x, xd->ldc, nm,
+                           (const float*)w, bias, (float*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, Cin, Cout, ocT, vpb);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+}  // namespace lamp
+
+using namespace lamp;
+
+extern "C" size_t lamp_conv3d_fwd_workspace_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats) {
+    if (!desc_ok(xd) || !desc_ok(zd)) return 0;
+    size_t a = want_stats ? stats_ws_bytes(zd) : 0;
+    size_t b = mfma_conv_ws_bytes(xd, zd, want_stats);
+    return a > b ? a : b;
+}
+
+extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* w,
+                                       const float* bias, const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
+                                       void* ws, size_t ws_bytes, void* stream) {
+    lamp_status st = check_conv_pair(xd, x, zd, z);
+    if (st != LAMP_OK) return st;
+    if (!w) return LAMP_ERR_NULL;
+    if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
+    if (stats_out && !(eps >= 0.f)) return LAMP_ERR_SHAPE;
+    if (ws_bytes < lamp_conv3d_fwd_workspace_bytes(xd, zd, stats_out != nullptr) || (ws_bytes && !ws))
+        return LAMP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (mfma_conv_supported(xd, zd, xnorm, bias))
+        return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s);
+    st = launch_direct<false>(xd, x, make_norm(xnorm), w, bias, zd, z, s);
+    if (st != LAMP_OK) return st;
+    if (stats_out) return launch_stats(zd, z, eps, stats_out, ws, ws_bytes, s);
+    return LAMP_OK;
+}
+
+extern "C" size_t lamp_conv3d_dgrad_workspace_bytes(const lamp_tensor_desc* dzd, const lamp_tensor_desc* dxd) {
+    if (!desc_ok(dzd) || !desc_ok(dxd)) return 0;
+    return mfma_conv_ws_bytes(dzd, dxd, 0);
+}
+
+extern "C" lamp_status lamp_conv3d_dgrad(const lamp_tensor_desc* dzd, const void* dz, const void* w,
+                                         const lamp_tensor_desc* dxd, void* dx, void* ws, size_t ws_bytes, void* stream) {
+    lamp_status st = check_conv_pair(dzd, dz, dxd, dx);
+    if (st != LAMP_OK) return st;
+    if (!w) return LAMP_ERR_NULL;
+    if (ws_bytes < lamp_conv3d_dgrad_workspace_bytes(dzd, dxd) || (ws_bytes && !ws)) return LAMP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (mfma_conv_supported(dzd, dxd, nullptr, nullptr))
+        return mfma_conv_fwd(dzd, dz, w, true, dxd, dx, nullptr, 0.f, ws, ws_bytes, s);
+    return launch_direct<true>(dzd, dz, make_norm(nullptr), w, nullptr, dxd, dx, s);
+}
+
+extern "C" size_t lamp_conv3d_wgrad_workspace_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
+    if (!desc_ok(xd) || !desc_ok(dzd)) return 0;
+    const int64_t O = (int64_t)dzd->c * 27 * xd->c;
+    size_t a = align_up((size_t)wgrad_splits(nvox(xd), O) * O * sizeof(float));
+    size_t b = mfma_wgrad_ws_bytes(xd, dzd);
+    size_t c = colsum_ws_bytes(nvox(dzd), dzd->c);
+    return (a > b ? a : b) + c;
+}
+
+extern "C" lamp_status lamp_conv3d_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm,
+                                         const lamp_tensor_desc* dzd, const void* dz, float* dw, float* dbias, float beta,
+                                         void* ws, size_t ws_bytes, void* stream) {
+    lamp_status st = check_conv_pair(xd, x, dzd, dz);
+    if (st != LAMP_OK) return st;
+    if (!dw) return LAMP_ERR_NULL;
+    if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
+    if (beta != 0.f && beta != 1.f) return LAMP_ERR_SHAPE;
+    if (!ws || ws_bytes < lamp_conv3d_wgrad_workspace_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t O = (int64_t)dzd->c * 27 * xd->c;
+    const size_t cs = colsum_ws_bytes(nvox(dzd), dzd->c);
+    char* wsb = (char*)ws;
+    if (dbias) {
+        st = launch_colsum(dz, dzd->dtype, nvox(dzd), dzd->c, dzd->ldc, dbias, beta, wsb + (ws_bytes - cs), cs, s);
+        if (st != LAMP_OK) return st;
+    }
+    if (mfma_wgrad_supported(xd, dzd, xnorm)) return mfma_wgrad(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
+    const int64_t V = nvox(xd);
+    const int S = wgrad_splits(V, O);
+    const int64_t vps = (V + S - 1) / S;
+    float* part = (float*)ws;
+    dim3 grid(cdiv(O, 256), S);
+    NormIn nm = make_norm(xnorm);
+    if (xd->dtype == LAMP_BF16)
+        hipLaunchKernelGGL((conv3d_wgrad_direct_kernel<bf16_t>), grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, nm,
+                           (const bf16_t*)dz, dzd->ldc, part, xd->n, xd->d, xd->h, xd->w, xd->c, dzd->c, vps);
+    else
+        hipLaunchKernelGGL((conv3d_wgrad_direct_kernel<float>), grid, dim3(256), 0, s, (const float*)x, xd->ldc, nm,
+                           (const float*)dz, dzd->ldc, part, xd->n, xd->d, xd->h, xd->w, xd->c, dzd->c, vps);
+    LAMP_CHECK_LAUNCH();
+    return launch_reduce_partials(part, S, O, dw, beta, s);
+}

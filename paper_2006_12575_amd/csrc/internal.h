@@ -1,0 +1,42 @@
+// Cross-file internal entry points of liblamp (host side).  Not part of the ABI.
+#pragma once
+#include "common.h"
+
+namespace lamp {
+
+// ---- norm.hip -------------------------------------------------------------------------------
+// Number of row chunks the stand-alone statistics pass uses for a tensor of `v` voxels per sample.
+int stats_chunks(int64_t v);
+// Bytes of workspace for the stand-alone statistics pass (partials [N][chunks][C][2] fp32).
+size_t stats_ws_bytes(const lamp_tensor_desc* zd);
+// Two-kernel statistics of z: writes stats[N][C][2] = (mean, rstd).
+lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, float* stats,
+                         void* ws, size_t ws_bytes, hipStream_t s);
+// Combine per-part (sum, sumsq) fp32 partials [N][parts][C][2] with per-part voxel counts
+// cnt[parts] (int32, same for every sample) into stats[N][C][2]; fp64 pairwise merging.
+lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
+                                  float eps, float* stats, hipStream_t s);
+
+// ---- reduce.hip -----------------------------------------------------------------------------
+// out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.
+lamp_status launch_reduce_partials(const float* part, int S, int64_t O, float* out, float beta, hipStream_t s);
+// Column sums of a [rows, C] tensor with row stride ld: out[c] = beta*out[c] + sum_r t[r][c].
+size_t colsum_ws_bytes(int64_t rows, int C);
+lamp_status launch_colsum(const void* t, int dtype, int64_t rows, int C, int ld, float* out, float beta,
+                          void* ws, size_t ws_bytes, hipStream_t s);
+
+// ---- conv3d_mfma.hip ------------------------------------------------------------------------
+// Matrix-core implicit-GEMM paths; each returns LAMP_ERR_UNSUPPORTED when the shape is not one
+// they serve, and the caller falls back to the generic kernels.
+bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm,
+                         const float* bias);
+size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats);
+lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
+                          const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
+                          void* ws, size_t ws_bytes, hipStream_t s);
+bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm);
+size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd);
+lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,
+                       float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s);
+
+}  // namespace lamp

@@ -1,0 +1,376 @@
+// InstanceNorm + ReLU: statistics (two-stage, deterministic), apply, and backward.
+// Bandwidth-bound kernels on NDHWC tensors; fp32 arithmetic, fp64 merging of partial moments.
+#include <initializer_list>
+#include "internal.h"
+#include "vec.h"
+
+namespace lamp {
+
+
+static const int kRowsPerChunk = 2048;
+
+int stats_chunks(int64_t v) { return (int)((v + kRowsPerChunk - 1) / kRowsPerChunk); }
+
+size_t stats_ws_bytes(const lamp_tensor_desc* zd) {
+    int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    int ch = stats_chunks(V);
+    return align_up((size_t)zd->n * ch * zd->c * 2 * sizeof(float)) + align_up((size_t)ch * sizeof(int32_t));
+}
+
+// ---- forward statistics ---------------------------------------------------------------------
+// partial[((n*chunks + chunk)*C + c)*2] = (sum, sum of squares) over the chunk's rows.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void stats_partial_kernel(const T* __restrict__ z, int ld, int64_t V, int C,
+                                                            int cthreads, int rl, int rows_per_chunk,
+                                                            float* __restrict__ partial, int32_t* __restrict__ counts) {
+    __shared__ float red[2][256 * VEC];
+    const int tid = threadIdx.x;
+    const int cl = tid % cthreads, r0 = tid / cthreads;
+    const int cv = blockIdx.z * 256 + cl;
+    const int chunk = blockIdx.x, n = blockIdx.y, chunks = gridDim.x;
+    const int64_t rbeg = (int64_t)chunk * rows_per_chunk;
+    int64_t rend = rbeg + rows_per_chunk;
+    if (rend > V) rend = V;
+    float s[VEC], q[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { s[i] = 0.f; q[i] = 0.f; }
+    const bool active = r0 < rl && cv * VEC < C;
+    if (active) {
+        const T* base = z + ((int64_t)n * V) * ld + (int64_t)cv * VEC;
+        for (int64_t r = rbeg + r0; r < rend; r += rl) {
+            float v[VEC];
+            Vec<T, VEC>::load(base + r * ld, v);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { s[i] += v[i]; q[i] = fmaf(v[i], v[i], q[i]); }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { red[0][tid * VEC + i] = s[i]; red[1][tid * VEC + i] = q[i]; }
+    __syncthreads();
+    if (r0 == 0 && cv * VEC < C) {
+        for (int i = 0; i < VEC; ++i) {
+            float ss = 0.f, qq = 0.f;
+            for (int r = 0; r < rl; ++r) {
+                ss += red[0][(r * cthreads + cl) * VEC + i];
+                qq += red[1][(r * cthreads + cl) * VEC + i];
+            }
+            size_t o = (((size_t)n * chunks + chunk) * C + (size_t)cv * VEC + i) * 2;
+            partial[o] = ss;
+            partial[o + 1] = qq;
+        }
+    }
+    if (counts && n == 0 && blockIdx.z == 0 && tid == 0) counts[chunk] = (int32_t)(rend - rbeg);
+}
+
+// One 64-lane wave per (n,c): Chan/Welford merging of the parts in fp64, fixed order.
+__global__ __launch_bounds__(64) void stats_finalize_kernel(const float* __restrict__ partial,
+                                                            const int32_t* __restrict__ counts, int parts, int C,
+                                                            float eps, float* __restrict__ stats) {
+    const int c = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
+    double cnt = 0.0, mean = 0.0, m2 = 0.0;
+    for (int p = lane; p < parts; p += 64) {
+        double k = (double)counts[p];
+        if (k <= 0.0) continue;
+        size_t o = (((size_t)n * parts + p) * C + c) * 2;
+        double sm = (double)partial[o], sq = (double)partial[o + 1];
+        double mp = sm / k;
+        double m2p = sq - sm * mp;
+        if (m2p < 0.0) m2p = 0.0;
+        double tot = cnt + k, dlt = mp - mean;
+        mean += dlt * (k / tot);
+        m2 += m2p + dlt * dlt * (cnt * k / tot);
+        cnt = tot;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        double c2 = __shfl_down(cnt, off), mn2 = __shfl_down(mean, off), mm2 = __shfl_down(m2, off);
+        if (c2 > 0.0) {
+            double tot = cnt + c2, dlt = mn2 - mean;
+            mean += dlt * (c2 / tot);
+            m2 += mm2 + dlt * dlt * (cnt * c2 / tot);
+            cnt = tot;
+        }
+    }
+    if (lane == 0) {
+        double var = cnt > 0.0 ? m2 / cnt : 0.0;
+        stats[((size_t)n * C + c) * 2 + 0] = (float)mean;
+        stats[((size_t)n * C + c) * 2 + 1] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+}
+
+lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
+                                  float eps, float* stats, hipStream_t s) {
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(64), 0, s, partials, counts, parts, C, eps, stats);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, float* stats,
+                         void* ws, size_t ws_bytes, hipStream_t s) {
+    const int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    const int chunks = stats_chunks(V);
+    if (!ws || ws_bytes < stats_ws_bytes(zd)) return LAMP_ERR_WORKSPACE;
+    float* partial = (float*)ws;
+    int32_t* counts = (int32_t*)((char*)ws + align_up((size_t)zd->n * chunks * zd->c * 2 * sizeof(float)));
+    const int vec = pick_vec(zd->dtype, zd->c, {zd->ldc}, {z});
+    LAMP_DISPATCH_TV(zd->dtype, vec, {
+        RowMap m = make_rowmap(zd->c, VEC);
+        hipLaunchKernelGGL((stats_partial_kernel<T, VEC>), dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s,
+                           (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, kRowsPerChunk, partial, counts);
+    });
+    LAMP_CHECK_LAUNCH();
+    return launch_stats_finalize(partial, counts, chunks, zd->n, zd->c, eps, stats, s);
+}
+
+// ---- apply ----------------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void inorm_apply_kernel(const T* __restrict__ z, int ldz, T* __restrict__ y, int ldy,
+                                                          int64_t V, int C, int cthreads, int rl,
+                                                          const float* __restrict__ stats,
+                                                          const float* __restrict__ gamma, const float* __restrict__ beta) {
+    const int tid = threadIdx.x;
+    const int cl = tid % cthreads, r0 = tid / cthreads;
+    const int cv = blockIdx.z * 256 + cl;
+    const int n = blockIdx.y;
+    if (r0 >= rl || cv * VEC >= C) return;
+    NormIn nm{stats, gamma, beta, C, 1};
+    float a[VEC], b[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) norm_coeffs(nm, n, cv * VEC + i, a[i], b[i]);
+    const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
+    T* yb = y + ((int64_t)n * V) * ldy + (int64_t)cv * VEC;
+    for (int64_t r = (int64_t)blockIdx.x * rl + r0; r < V; r += (int64_t)gridDim.x * rl) {
+        float v[VEC];
+        Vec<T, VEC>::load(zb + r * ldz, v);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float u = norm_u(v[i], a[i], b[i]);
+            v[i] = u > 0.f ? u : 0.f;
+        }
+        Vec<T, VEC>::store(yb + r * ldy, v);
+    }
+}
+
+// ---- backward -------------------------------------------------------------------------------
+// partial[((n*chunks+chunk)*C + c)*2] = (sum g, sum g*zh) over the chunk's rows.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void inorm_bwd_partial_kernel(const T* __restrict__ dy, int ldg, const T* __restrict__ z,
+                                                                int ldz, int64_t V, int C, int cthreads, int rl,
+                                                                int rows_per_chunk, const float* __restrict__ stats,
+                                                                const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta,
+                                                                float* __restrict__ partial) {
+    __shared__ float red[2][256 * VEC];
+    const int tid = threadIdx.x;
+    const int cl = tid % cthreads, r0 = tid / cthreads;
+    const int cv = blockIdx.z * 256 + cl;
+    const int chunk = blockIdx.x, n = blockIdx.y, chunks = gridDim.x;
+    const int64_t rbeg = (int64_t)chunk * rows_per_chunk;
+    int64_t rend = rbeg + rows_per_chunk;
+    if (rend > V) rend = V;
+    float s[VEC], q[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { s[i] = 0.f; q[i] = 0.f; }
+    if (r0 < rl && cv * VEC < C) {
+        NormIn nm{stats, gamma, beta, C, 1};
+        float a[VEC], b[VEC], mean[VEC], rstd[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            norm_coeffs(nm, n, cv * VEC + i, a[i], b[i]);
+            mean[i] = stats[((size_t)n * C + cv * VEC + i) * 2];
+            rstd[i] = stats[((size_t)n * C + cv * VEC + i) * 2 + 1];
+        }
+        const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
+        const T* gb = dy + ((int64_t)n * V) * ldg + (int64_t)cv * VEC;
+        for (int64_t r = rbeg + r0; r < rend; r += rl) {
+            float v[VEC], g[VEC];
+            Vec<T, VEC>::load(zb + r * ldz, v);
+            Vec<T, VEC>::load(gb + r * ldg, g);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                float u = norm_u(v[i], a[i], b[i]);
+                float gg = u > 0.f ? g[i] : 0.f;
+                float zh = (v[i] - mean[i]) * rstd[i];
+                s[i] += gg;
+                q[i] = fmaf(gg, zh, q[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) { red[0][tid * VEC + i] = s[i]; red[1][tid * VEC + i] = q[i]; }
+    __syncthreads();
+    if (r0 == 0 && cv * VEC < C) {
+        for (int i = 0; i < VEC; ++i) {
+            float ss = 0.f, qq = 0.f;
+            for (int r = 0; r < rl; ++r) {
+                ss += red[0][(r * cthreads + cl) * VEC + i];
+                qq += red[1][(r * cthreads + cl) * VEC + i];
+            }
+            size_t o = (((size_t)n * chunks + chunk) * C + (size_t)cv * VEC + i) * 2;
+            partial[o] = ss;
+            partial[o + 1] = qq;
+        }
+    }
+}
+
+// sums[n][c][2] = (sum g, sum g*zh) over all parts, fp64, fixed order.
+__global__ __launch_bounds__(64) void inorm_bwd_finalize_kernel(const float* __restrict__ partial, int parts, int C,
+                                                                float* __restrict__ sums) {
+    const int c = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
+    double s = 0.0, q = 0.0;
+    for (int p = lane; p < parts; p += 64) {
+        size_t o = (((size_t)n * parts + p) * C + c) * 2;
+        s += (double)partial[o];
+        q += (double)partial[o + 1];
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        s += __shfl_down(s, off);
+        q += __shfl_down(q, off);
+    }
+    if (lane == 0) {
+        sums[((size_t)n * C + c) * 2 + 0] = (float)s;
+        sums[((size_t)n * C + c) * 2 + 1] = (float)q;
+    }
+}
+
+__global__ void inorm_dgb_kernel(const float* __restrict__ sums, int N, int C, float* dgamma, float* dbeta,
+                                 float beta_acc) {
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double s = 0.0, q = 0.0;
+    for (int n = 0; n < N; ++n) {
+        s += (double)sums[((size_t)n * C + c) * 2 + 0];
+        q += (double)sums[((size_t)n * C + c) * 2 + 1];
+    }
+    if (dbeta) dbeta[c] = (beta_acc != 0.f ? beta_acc * dbeta[c] : 0.f) + (float)s;
+    if (dgamma) dgamma[c] = (beta_acc != 0.f ? beta_acc * dgamma[c] : 0.f) + (float)q;
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void inorm_bwd_apply_kernel(const T* __restrict__ dy, int ldg, const T* __restrict__ z,
+                                                              int ldz, T* __restrict__ dz, int ldo, int64_t V, int C,
+                                                              int cthreads, int rl, const float* __restrict__ stats,
+                                                              const float* __restrict__ gamma,
+                                                              const float* __restrict__ beta,
+                                                              const float* __restrict__ sums) {
+    const int tid = threadIdx.x;
+    const int cl = tid % cthreads, r0 = tid / cthreads;
+    const int cv = blockIdx.z * 256 + cl;
+    const int n = blockIdx.y;
+    if (r0 >= rl || cv * VEC >= C) return;
+    NormIn nm{stats, gamma, beta, C, 1};
+    float a[VEC], b[VEC], mean[VEC], rstd[VEC], c1[VEC], c2[VEC];
+    const float invV = 1.0f / (float)V;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        norm_coeffs(nm, n, cv * VEC + i, a[i], b[i]);
+        mean[i] = stats[((size_t)n * C + cv * VEC + i) * 2];
+        rstd[i] = stats[((size_t)n * C + cv * VEC + i) * 2 + 1];
+        c1[i] = sums[((size_t)n * C + cv * VEC + i) * 2] * invV;
+        c2[i] = sums[((size_t)n * C + cv * VEC + i) * 2 + 1] * invV;
+    }
+    const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
+    const T* gb = dy + ((int64_t)n * V) * ldg + (int64_t)cv * VEC;
+    T* ob = dz + ((int64_t)n * V) * ldo + (int64_t)cv * VEC;
+    for (int64_t r = (int64_t)blockIdx.x * rl + r0; r < V; r += (int64_t)gridDim.x * rl) {
+        float v[VEC], g[VEC];
+        Vec<T, VEC>::load(zb + r * ldz, v);
+        Vec<T, VEC>::load(gb + r * ldg, g);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float u = norm_u(v[i], a[i], b[i]);
+            float gg = u > 0.f ? g[i] : 0.f;
+            float zh = (v[i] - mean[i]) * rstd[i];
+            v[i] = a[i] * (gg - c1[i] - zh * c2[i]);
+        }
+        Vec<T, VEC>::store(ob + r * ldo, v);
+    }
+}
+
+static int apply_blocks(int64_t V, int rl) {
+    int64_t b = (V + rl - 1) / rl;
+    int64_t cap = 256 * 16;
+    b = (b + 3) / 4;  // a few rows per thread
+    if (b < 1) b = 1;
+    return (int)(b > cap ? cap : b);
+}
+
+}  // namespace lamp
+
+using namespace lamp;
+
+extern "C" size_t lamp_inorm_relu_workspace_bytes(const lamp_tensor_desc* zd) {
+    if (!desc_ok(zd)) return 0;
+    return stats_ws_bytes(zd);
+}
+
+extern "C" lamp_status lamp_inorm_relu(const lamp_tensor_desc* zd, const void* z, const float* gamma,
+                                       const float* beta, float eps, const lamp_tensor_desc* yd, void* y,
+                                       float* stats, int stats_given, void* ws, size_t ws_bytes, void* stream) {
+    if (!zd || !yd || !z || !y || !stats) return LAMP_ERR_NULL;
+    if (!desc_ok(zd) || !desc_ok(yd) || !same_space(zd, yd) || zd->c != yd->c) return LAMP_ERR_SHAPE;
+    if (zd->dtype != yd->dtype) return LAMP_ERR_DTYPE;
+    if (!(eps >= 0.f)) return LAMP_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    if (!stats_given) {
+        if (!ws || ws_bytes < stats_ws_bytes(zd)) return LAMP_ERR_WORKSPACE;
+        lamp_status st = launch_stats(zd, z, eps, stats, ws, ws_bytes, s);
+        if (st != LAMP_OK) return st;
+    }
+    const int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    const int vec = pick_vec(zd->dtype, zd->c, {zd->ldc, yd->ldc}, {z, y});
+    LAMP_DISPATCH_TV(zd->dtype, vec, {
+        RowMap m = make_rowmap(zd->c, VEC);
+        hipLaunchKernelGGL((inorm_apply_kernel<T, VEC>), dim3(apply_blocks(V, m.rl), zd->n, m.ctiles), dim3(256), 0, s,
+                           (const T*)z, zd->ldc, (T*)y, yd->ldc, V, zd->c, m.cthreads, m.rl, stats, gamma, beta);
+    });
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+extern "C" size_t lamp_inorm_relu_bwd_workspace_bytes(const lamp_tensor_desc* zd) {
+    if (!desc_ok(zd)) return 0;
+    int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    int ch = stats_chunks(V);
+    return align_up((size_t)zd->n * ch * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * zd->c * 2 * sizeof(float));
+}
+
+extern "C" lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc* dyd, const void* dy, const lamp_tensor_desc* zd,
+                                           const void* z, const float* stats, const float* gamma, const float* beta,
+                                           const lamp_tensor_desc* dzd, void* dz, float* dgamma, float* dbeta,
+                                           float beta_acc, void* ws, size_t ws_bytes, void* stream) {
+    if (!dyd || !zd || !dzd || !dy || !z || !stats || !dz) return LAMP_ERR_NULL;
+    if (!desc_ok(dyd) || !desc_ok(zd) || !desc_ok(dzd) || !same_space(zd, dyd) || !same_space(zd, dzd) ||
+        zd->c != dyd->c || zd->c != dzd->c)
+        return LAMP_ERR_SHAPE;
+    if (zd->dtype != dyd->dtype || zd->dtype != dzd->dtype) return LAMP_ERR_DTYPE;
+    if (beta_acc != 0.f && beta_acc != 1.f) return LAMP_ERR_SHAPE;
+    if (!ws || ws_bytes < lamp_inorm_relu_bwd_workspace_bytes(zd)) return LAMP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    const int chunks = stats_chunks(V);
+    float* partial = (float*)ws;
+    float* sums = (float*)((char*)ws + align_up((size_t)zd->n * chunks * zd->c * 2 * sizeof(float)));
+    const int vec = pick_vec(zd->dtype, zd->c, {zd->ldc, dyd->ldc, dzd->ldc}, {z, dy, dz});
+    LAMP_DISPATCH_TV(zd->dtype, vec, {
+        RowMap m = make_rowmap(zd->c, VEC);
+        hipLaunchKernelGGL((inorm_bwd_partial_kernel<T, VEC>), dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s,
+                           (const T*)dy, dyd->ldc, (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, kRowsPerChunk,
+                           stats, gamma, beta, partial);
+    });
+    LAMP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(zd->c, zd->n), dim3(64), 0, s, partial, chunks, zd->c, sums);
+    LAMP_CHECK_LAUNCH();
+    if (dgamma || dbeta) {
+        hipLaunchKernelGGL(inorm_dgb_kernel, dim3(cdiv(zd->c, 64)), dim3(64), 0, s, sums, zd->n, zd->c, dgamma, dbeta,
+                           beta_acc);
+        LAMP_CHECK_LAUNCH();
+    }
+    LAMP_DISPATCH_TV(zd->dtype, vec, {
+        RowMap m = make_rowmap(zd->c, VEC);
+        hipLaunchKernelGGL((inorm_bwd_apply_kernel<T, VEC>), dim3(apply_blocks(V, m.rl), zd->n, m.ctiles), dim3(256), 0,
+                           s, (const T*)dy, dyd->ldc, (const T*)z, zd->ldc, (T*)dz, dzd->ldc, V, zd->c, m.cthreads,
+                           m.rl, stats, gamma, beta, sums);
+    });
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}

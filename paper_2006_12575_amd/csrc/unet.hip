@@ -1,0 +1,562 @@
+// Whole U-Net, one encoder partition, and sliding-window inference: host-side composition of the
+// library's own entry points plus the window gather / Gaussian blend kernels.
+//
+// Data flow of a block  [conv -> InstanceNorm -> ReLU] x 2 : every conv writes its raw output z
+// and the InstanceNorm statistics (conv epilogue); the activated tensor y is written once by the
+// apply kernel -- for an encoder block's second conv straight into channels [0,C) of that level's
+// concat buffer (zero-copy skip), where the transposed conv later writes channels [C,2C).
+// The backward recomputes the ReLU mask from z and the statistics.
+#include <math.h>
+#include <vector>
+#include "internal.h"
+
+namespace lamp {
+
+struct ConvBuf {
+    void* z; void* y; int ldy; float* stats;
+};
+
+struct Net {
+    const lamp_unet_desc* u;
+    int L, dt;
+    size_t es;
+    hipStream_t s;
+    void* scratch; size_t scratch_bytes;
+    int chan(int l) const { return u->base << (l - 1); }
+    void dims(int l, int& d, int& h, int& w) const { d = u->d >> (l - 1); h = u->h >> (l - 1); w = u->w >> (l - 1); }
+    int64_t vox(int l) const { int d, h, w; dims(l, d, h, w); return (int64_t)u->n * d * h * w; }
+    lamp_tensor_desc td(int l, int c, int ldc) const {
+        lamp_tensor_desc t; t.n = u->n; dims(l, t.d, t.h, t.w); t.c = c; t.ldc = ldc; t.dtype = dt; return t;
+    }
+};
+
+static lamp_status unet_desc_ok(const lamp_unet_desc* u) {
+    if (!u) return LAMP_ERR_NULL;
+    if (u->levels < 1 || u->levels > 8 || u->base < 1 || u->in_ch < 1 || u->classes < 1 || u->classes > 16 || u->n < 1 ||
+        u->d < 1 || u->h < 1 || u->w < 1)
+        return LAMP_ERR_SHAPE;
+    if (u->dtype != LAMP_F32 && u->dtype != LAMP_BF16) return LAMP_ERR_DTYPE;
+    const int m = 1 << (u->levels - 1);
+    if (u->d % m || u->h % m || u->w % m) return LAMP_ERR_SHAPE;
+    if (!(u->eps >= 0.f)) return LAMP_ERR_SHAPE;
+    return LAMP_OK;
+}
+
+static int per_conv(const lamp_unet_desc* u) { return u->affine ? 3 : 1; }
+
+// ---- scratch requirement: the largest per-call workspace of any layer ------------------------
+static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
+    lamp_tensor_desc xi = nt.td(l, Cin, Cin), xo = nt.td(l, Cout, Cout);
+    size_t m = lamp_conv3d_fwd_workspace_bytes(&xi, &xo, 1);
+    size_t t = lamp_conv3d_fwd_workspace_bytes(&xo, &xo, 1);
+    m = t > m ? t : m;
+    if (bwd) {
+        size_t c[] = {lamp_conv3d_wgrad_workspace_bytes(&xi, &xo), lamp_conv3d_wgrad_workspace_bytes(&xo, &xo),
+                      lamp_conv3d_dgrad_workspace_bytes(&xo, &xi), lamp_conv3d_dgrad_workspace_bytes(&xo, &xo),
+                      lamp_inorm_relu_bwd_workspace_bytes(&xo)};
+        for (size_t v : c) m = v > m ? v : m;
+    }
+    return m;
+}
+
+static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, int Cout, const void* const* P, int pi,
+                             ConvBuf& c1, ConvBuf& c2) {
+    const lamp_unet_desc* u = nt.u;
+    const int pc = per_conv(u);
+    lamp_tensor_desc xd = nt.td(l, Cin, ldx), zd = nt.td(l, Cout, Cout);
+    lamp_status st = lamp_conv3d_fwd(&xd, x, nullptr, P[pi], nullptr, &zd, c1.z, c1.stats, u->eps, nt.scratch,
+                                     nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    lamp_tensor_desc y1 = nt.td(l, Cout, c1.ldy);
+    st = lamp_inorm_relu(&zd, c1.z, u->affine ? (const float*)P[pi + 1] : nullptr,
+                         u->affine ? (const float*)P[pi + 2] : nullptr, u->eps, &y1, c1.y, c1.stats, 1, nullptr, 0, nt.s);
+    if (st != LAMP_OK) return st;
+    st = lamp_conv3d_fwd(&y1, c1.y, nullptr, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch,
+                         nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    lamp_tensor_desc y2 = nt.td(l, Cout, c2.ldy);
+    return lamp_inorm_relu(&zd, c2.z, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
+                           u->affine ? (const float*)P[pi + pc + 2] : nullptr, u->eps, &y2, c2.y, c2.stats, 1, nullptr, 0,
+                           nt.s);
+}
+
+// g: gradient w.r.t. c2.y, dense [.., Cout], overwritten.  gtmp: dense [.., Cout] scratch tensor.
+// gx (nullable): receives the gradient w.r.t. the block input, channel stride ldgx.
+static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, int Cout, const void* const* P,
+                             float* const* G, int pi, ConvBuf& c1, ConvBuf& c2, void* g, void* gtmp, void* gx, int ldgx,
+                             float beta) {
+    const lamp_unet_desc* u = nt.u;
+    const int pc = per_conv(u);
+    const bool af = u->affine != 0;
+    lamp_tensor_desc zd = nt.td(l, Cout, Cout), xd = nt.td(l, Cin, ldx), y1 = nt.td(l, Cout, c1.ldy);
+    lamp_status st = lamp_inorm_relu_bwd(&zd, g, &zd, c2.z, c2.stats, af ? (const float*)P[pi + pc + 1] : nullptr,
+                                         af ? (const float*)P[pi + pc + 2] : nullptr, &zd, g, af ? G[pi + pc + 1] : nullptr,
+                                         af ? G[pi + pc + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    st = lamp_conv3d_wgrad(&y1, c1.y, nullptr, &zd, g, G[pi + pc], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    st = lamp_conv3d_dgrad(&zd, g, P[pi + pc], &zd, gtmp, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    st = lamp_inorm_relu_bwd(&zd, gtmp, &zd, c1.z, c1.stats, af ? (const float*)P[pi + 1] : nullptr,
+                             af ? (const float*)P[pi + 2] : nullptr, &zd, gtmp, af ? G[pi + 1] : nullptr,
+                             af ? G[pi + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    st = lamp_conv3d_wgrad(&xd, x, nullptr, &zd, gtmp, G[pi], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    if (gx) {
+        lamp_tensor_desc gxd = nt.td(l, Cin, ldgx);
+        st = lamp_conv3d_dgrad(&zd, gtmp, P[pi], &gxd, gx, nt.scratch, nt.scratch_bytes, nt.s);
+    }
+    return st;
+}
+
+// ---- workspace layout -------------------------------------------------------------------------
+struct Layout {
+    // encoder level l (1-based index l-1), decoder level l (index l-1, l < L)
+    std::vector<ConvBuf> e1, e2, d1, d2;
+    std::vector<void*> cat, pooled, gcat;
+    void *g0, *g1;
+    void* scratch; size_t scratch_bytes;
+    size_t total;
+};
+
+// Lays out every buffer of levels [first, last] of the encoder and (whole == true) the decoder.
+static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void* base, Layout& lay,
+                        void* const* ext_skips, void* ext_pooled) {
+    const lamp_unet_desc* u = nt.u;
+    const int L = nt.L;
+    Carver cv(base ? base : (void*)256, (size_t)1 << 62);
+    auto take = [&](size_t b) -> void* { void* p = cv.take(b); return base ? p : nullptr; };
+    lay.e1.assign(L, ConvBuf{}); lay.e2.assign(L, ConvBuf{}); lay.d1.assign(L, ConvBuf{}); lay.d2.assign(L, ConvBuf{});
+    lay.cat.assign(L, nullptr); lay.pooled.assign(L, nullptr); lay.gcat.assign(L, nullptr);
+    const size_t es = nt.es;
+    size_t scratch = 0, gmax = 0;
+    for (int l = first; l <= last; ++l) {
+        const int C = nt.chan(l);
+        const int Cin = l == 1 ? u->in_ch : nt.chan(l - 1);
+        const size_t tb = (size_t)nt.vox(l) * C * es, sb = (size_t)u->n * C * 2 * sizeof(float);
+        ConvBuf &a = lay.e1[l - 1], &b = lay.e2[l - 1];
+        a.z = take(tb); a.stats = (float*)take(sb);
+        a.y = bwd ? take(tb) : a.z; a.ldy = C;
+        b.z = take(tb); b.stats = (float*)take(sb);
+        if (whole && l < L) {
+            lay.cat[l - 1] = take(2 * tb);
+            b.y = lay.cat[l - 1]; b.ldy = 2 * C;
+            if (bwd) lay.gcat[l - 1] = take(2 * tb);
+        } else if (!whole) {
+            b.y = ext_skips ? ext_skips[l - first] : nullptr; b.ldy = C;
+        } else {
+            b.y = bwd ? take(tb) : b.z; b.ldy = C;
+        }
+        if (l < L) {
+            const size_t pb = (size_t)nt.vox(l + 1) * C * es;
+            if (!whole && l == last) lay.pooled[l - 1] = ext_pooled;
+            else lay.pooled[l - 1] = take(pb);
+        }
+        size_t sc = block_scratch(nt, l, Cin, C, bwd);
+        scratch = sc > scratch ? sc : scratch;
+        gmax = tb > gmax ? tb : gmax;
+    }
+    if (whole) {
+        for (int l = L - 1; l >= 1; --l) {
+            const int C = nt.chan(l);
+            const size_t tb = (size_t)nt.vox(l) * C * es, sb = (size_t)u->n * C * 2 * sizeof(float);
+            ConvBuf &a = lay.d1[l - 1], &b = lay.d2[l - 1];
+            a.z = take(tb); a.stats = (float*)take(sb); a.y = bwd ? take(tb) : a.z; a.ldy = C;
+            b.z = take(tb); b.stats = (float*)take(sb); b.y = bwd ? take(tb) : b.z; b.ldy = C;
+            size_t sc = block_scratch(nt, l, 2 * C, C, bwd);
+            scratch = sc > scratch ? sc : scratch;
+            if (bwd) {
+                lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
+                size_t t = lamp_convtr3d_bwd_workspace_bytes(&xd, &yd);
+                scratch = t > scratch ? t : scratch;
+            }
+        }
+        if (bwd) {
+            lamp_tensor_desc hd = nt.td(1, nt.chan(1), nt.chan(1));
+            size_t t = lamp_head_ce_workspace_bytes(&hd, u->classes);
+            scratch = t > scratch ? t : scratch;
+        }
+    }
+    lay.g0 = lay.g1 = nullptr;
+    if (bwd) { lay.g0 = take(gmax); lay.g1 = take(gmax); }
+    lay.scratch_bytes = align_up(scratch);
+    lay.scratch = take(lay.scratch_bytes);
+    lay.total = align_up(cv.off) + 256;
+}
+
+static int enc_pi(const lamp_unet_desc* u, int l) { return (l - 1) * 2 * per_conv(u); }
+static int dec_pi(const lamp_unet_desc* u, int l) {  // index of "up Wt" of decoder level l
+    return u->levels * 2 * per_conv(u) + (u->levels - 1 - l) * (2 + 2 * per_conv(u));
+}
+static int head_pi(const lamp_unet_desc* u) { return u->levels * 2 * per_conv(u) + (u->levels - 1) * (2 + 2 * per_conv(u)); }
+
+static lamp_status encoder_fwd(Net& nt, Layout& lay, int first, int last, const void* const* P, int pbase, const void* x) {
+    const lamp_unet_desc* u = nt.u;
+    const void* cur = x;
+    int cur_c = first == 1 ? u->in_ch : nt.chan(first - 1);
+    for (int l = first; l <= last; ++l) {
+        const int C = nt.chan(l);
+        lamp_status st = block_fwd(nt, l, cur_c, cur_c, cur, C, P, enc_pi(u, l) - pbase, lay.e1[l - 1], lay.e2[l - 1]);
+        if (st != LAMP_OK) return st;
+        if (l < nt.L) {
+            lamp_tensor_desc xd = nt.td(l, C, lay.e2[l - 1].ldy), yd = nt.td(l + 1, C, C);
+            st = lamp_maxpool2_fwd(&xd, lay.e2[l - 1].y, nullptr, &yd, lay.pooled[l - 1], nt.s);
+            if (st != LAMP_OK) return st;
+            cur = lay.pooled[l - 1];
+        }
+        cur_c = C;
+    }
+    return LAMP_OK;
+}
+
+// g_init: gradient w.r.t. the pooled output of level `last` (any buffer, read only), or, when
+// last == L, w.r.t. e_L's activated output, in which case it must be lay.g0 (it is overwritten).
+// skip_g[l-1] / ldsg[l-1]: gradient arriving through the skip copy of e_l (levels below L).
+// dx_out (nullable): receives the gradient w.r.t. the partition's input.
+static lamp_status encoder_bwd(Net& nt, Layout& lay, int first, int last, const void* const* P, float* const* G,
+                               int pbase, const void* x, const void* g_init, const void* const* skip_g, const int* ldsg,
+                               void* dx_out, float beta) {
+    const lamp_unet_desc* u = nt.u;
+    const void* gin = g_init;
+    void* bufA = lay.g0;
+    void* bufB = lay.g1;
+    for (int l = last; l >= first; --l) {
+        const int C = nt.chan(l);
+        void *g, *other;
+        if (l < nt.L) {
+            lamp_tensor_desc xd = nt.td(l, C, lay.e2[l - 1].ldy), gd = nt.td(l + 1, C, C), ad = nt.td(l, C, ldsg[l - 1]),
+                             od = nt.td(l, C, C);
+            lamp_status st = lamp_maxpool2_bwd(&xd, lay.e2[l - 1].y, nullptr, &gd, gin, &ad, skip_g[l - 1], &od, bufA, nt.s);
+            if (st != LAMP_OK) return st;
+            g = bufA; other = bufB;
+        } else {
+            g = lay.g0; other = lay.g1;
+        }
+        const int Cin = l == 1 ? u->in_ch : nt.chan(l - 1);
+        const void* xin = l == first ? x : lay.pooled[l - 2];
+        // the input gradient may reuse g: g is dead once the first conv's dz sits in `other`
+        void* dst = l > first ? g : dx_out;
+        lamp_status st = block_bwd(nt, l, Cin, Cin, xin, C, P, G, enc_pi(u, l) - pbase, lay.e1[l - 1], lay.e2[l - 1], g,
+                                   other, dst, Cin, beta);
+        if (st != LAMP_OK) return st;
+        gin = g;
+        bufA = other; bufB = g;
+    }
+    return LAMP_OK;
+}
+
+}  // namespace lamp
+
+using namespace lamp;
+
+extern "C" int32_t lamp_unet_param_count(const lamp_unet_desc* u) {
+    if (unet_desc_ok(u) != LAMP_OK) return 0;
+    return head_pi(u) + 2;
+}
+
+extern "C" int64_t lamp_unet_param_numel(const lamp_unet_desc* u, int32_t idx) {
+    if (unet_desc_ok(u) != LAMP_OK || idx < 0 || idx >= lamp_unet_param_count(u)) return 0;
+    const int pc = per_conv(u), L = u->levels;
+    auto ch = [&](int l) { return (int64_t)u->base << (l - 1); };
+    auto conv_entry = [&](int64_t Cin, int64_t Cout, int k) -> int64_t {  // k: position inside a block
+        int which = k / pc, sub = k % pc;
+        if (sub) return Cout;
+        return Cout * 27 * (which == 0 ? Cin : Cout);
+    };
+    if (idx < L * 2 * pc) {
+        int l = idx / (2 * pc) + 1;
+        return conv_entry(l == 1 ? u->in_ch : ch(l - 1), ch(l), idx % (2 * pc));
+    }
+    idx -= L * 2 * pc;
+    const int per = 2 + 2 * pc;
+    if (idx < (L - 1) * per) {
+        int l = L - 1 - idx / per, k = idx % per;
+        if (k == 0) return ch(l + 1) * 8 * ch(l);
+        if (k == 1) return ch(l);
+        return conv_entry(2 * ch(l), ch(l), k - 2);
+    }
+    idx -= (L - 1) * per;
+    return idx == 0 ? (int64_t)u->classes * ch(1) : u->classes;
+}
+
+extern "C" size_t lamp_unet_workspace_bytes(const lamp_unet_desc* u, int with_backward) {
+    if (unet_desc_ok(u) != LAMP_OK) return 0;
+    Net nt{u, u->levels, u->dtype, esize(u->dtype), nullptr, nullptr, 0};
+    Layout lay;
+    make_layout(nt, 1, u->levels, true, with_backward != 0, nullptr, lay, nullptr, nullptr);
+    return lay.total;
+}
+
+static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const void* x, const int32_t* labels,
+                            float* logits, float* loss, float* const* G, float beta, bool bwd, void* ws, size_t ws_bytes,
+                            void* stream) {
+    lamp_status st = unet_desc_ok(u);
+    if (st != LAMP_OK) return st;
+    if (!P || !x) return LAMP_ERR_NULL;
+    const int np = lamp_unet_param_count(u);
+    for (int i = 0; i < np; ++i)
+        if (!P[i]) return LAMP_ERR_NULL;
+    if (bwd) {
+        if (!labels || !loss || !G) return LAMP_ERR_NULL;
+        for (int i = 0; i < np; ++i)
+            if (!G[i]) return LAMP_ERR_NULL;
+        if (beta != 0.f && beta != 1.f) return LAMP_ERR_SHAPE;
+    } else if (!logits) return LAMP_ERR_NULL;
+    if (!aligned16(x) || !aligned16(ws)) return LAMP_ERR_ALIGN;
+    if (!ws || ws_bytes < lamp_unet_workspace_bytes(u, bwd)) return LAMP_ERR_WORKSPACE;
+    Net nt{u, u->levels, u->dtype, esize(u->dtype), (hipStream_t)stream, nullptr, 0};
+    const int L = nt.L;
+    Layout lay;
+    make_layout(nt, 1, L, true, bwd, ws, lay, nullptr, nullptr);
+    nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+
+    if ((st = encoder_fwd(nt, lay, 1, L, P, 0, x)) != LAMP_OK) return st;
+    const void* cur = lay.e2[L - 1].y;
+    for (int l = L - 1; l >= 1; --l) {
+        const int C = nt.chan(l), pi = dec_pi(u, l);
+        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
+        st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, (char*)lay.cat[l - 1] + (size_t)C * nt.es,
+                           nt.s);
+        if (st != LAMP_OK) return st;
+        st = block_fwd(nt, l, 2 * C, 2 * C, lay.cat[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1]);
+        if (st != LAMP_OK) return st;
+        cur = lay.d2[l - 1].y;
+    }
+    const int C1 = nt.chan(1), hp = head_pi(u);
+    lamp_tensor_desc hd = nt.td(1, C1, C1);
+    const void* top = L > 1 ? lay.d2[0].y : lay.e2[0].y;
+    const int ldtop = L > 1 ? lay.d2[0].ldy : lay.e2[0].ldy;
+    hd.ldc = ldtop;
+    if (!bwd) return lamp_head_fwd(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, logits, nt.s);
+
+    // ---- backward ----
+    lamp_tensor_desc gd = nt.td(1, C1, C1);
+    st = lamp_head_ce(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, labels, logits, loss, &gd, lay.g0,
+                      G[hp], G[hp + 1], beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (st != LAMP_OK) return st;
+    std::vector<const void*> skip_g(L, nullptr);
+    std::vector<int> ldsg(L, 0);
+    for (int l = 1; l <= L - 1; ++l) {
+        const int C = nt.chan(l), pi = dec_pi(u, l);
+        st = block_bwd(nt, l, 2 * C, 2 * C, lay.cat[l - 1], C, P, G, pi + 2, lay.d1[l - 1], lay.d2[l - 1], lay.g0, lay.g1,
+                       lay.gcat[l - 1], 2 * C, beta);
+        if (st != LAMP_OK) return st;
+        skip_g[l - 1] = lay.gcat[l - 1];
+        ldsg[l - 1] = 2 * C;
+        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), dyd = nt.td(l, C, 2 * C), dxd = nt.td(l + 1, 2 * C, 2 * C);
+        const void* xin = l + 1 == L ? lay.e2[L - 1].y : lay.d2[l].y;
+        xd.ldc = l + 1 == L ? lay.e2[L - 1].ldy : lay.d2[l].ldy;
+        st = lamp_convtr3d_bwd(&xd, xin, nullptr, P[pi], &dyd, (char*)lay.gcat[l - 1] + (size_t)C * nt.es, &dxd, lay.g0,
+                               G[pi], G[pi + 1], beta, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+    }
+    return encoder_bwd(nt, lay, 1, L, P, G, 0, x, lay.g0, skip_g.data(), ldsg.data(), nullptr, beta);
+}
+
+extern "C" lamp_status lamp_unet_fwd(const lamp_unet_desc* u, const void* const* params, const void* x, float* logits,
+                                     void* ws, size_t ws_bytes, void* stream) {
+    return unet_run(u, params, x, nullptr, logits, nullptr, nullptr, 0.f, false, ws, ws_bytes, stream);
+}
+
+extern "C" lamp_status lamp_unet_fwd_bwd(const lamp_unet_desc* u, const void* const* params, const void* x,
+                                         const int32_t* labels, float* logits, float* loss, float* const* grads, float beta,
+                                         void* ws, size_t ws_bytes, void* stream) {
+    return unet_run(u, params, x, labels, logits, loss, grads, beta, true, ws, ws_bytes, stream);
+}
+
+// ---- one encoder partition --------------------------------------------------------------------
+static lamp_status stage_ok(const lamp_unet_desc* u, int first, int last) {
+    lamp_status st = unet_desc_ok(u);
+    if (st != LAMP_OK) return st;
+    if (first < 1 || last < first || last >= u->levels) return LAMP_ERR_SHAPE;
+    return LAMP_OK;
+}
+
+// The stage works on a descriptor whose level numbering is the whole net's but whose d,h,w are the
+// partition's input dims: shift them so that level `first` has those dims.
+static lamp_unet_desc stage_desc(const lamp_unet_desc* u, int first) {
+    lamp_unet_desc v = *u;
+    v.d = u->d << (first - 1); v.h = u->h << (first - 1); v.w = u->w << (first - 1);
+    return v;
+}
+
+extern "C" size_t lamp_unet_stage_workspace_bytes(const lamp_unet_desc* u, int first, int last, int with_backward) {
+    if (stage_ok(u, first, last) != LAMP_OK) return 0;
+    const int m = 1 << (last - first + 1);
+    if (u->d % m || u->h % m || u->w % m) return 0;
+    lamp_unet_desc v = stage_desc(u, first);
+    Net nt{&v, v.levels, v.dtype, esize(v.dtype), nullptr, nullptr, 0};
+    Layout lay;
+    make_layout(nt, first, last, false, with_backward != 0, nullptr, lay, nullptr, nullptr);
+    return lay.total;
+}
+
+extern "C" lamp_status lamp_unet_stage_fwd(const lamp_unet_desc* u, int first, int last, const void* const* params,
+                                           const void* x, void* pooled, void* const* skips, void* ws, size_t ws_bytes,
+                                           void* stream) {
+    lamp_status st = stage_ok(u, first, last);
+    if (st != LAMP_OK) return st;
+    const int m = 1 << (last - first + 1);
+    if (u->d % m || u->h % m || u->w % m) return LAMP_ERR_SHAPE;
+    if (!params || !x || !pooled || !skips) return LAMP_ERR_NULL;
+    for (int i = 0; i <= last - first; ++i)
+        if (!skips[i]) return LAMP_ERR_NULL;
+    for (int i = 0; i < (last - first + 1) * 2 * per_conv(u); ++i)
+        if (!params[i]) return LAMP_ERR_NULL;
+    if (!aligned16(x) || !aligned16(ws) || !aligned16(pooled)) return LAMP_ERR_ALIGN;
+    // the backward needs what the forward leaves behind, so the forward always lays out for it
+    if (!ws || ws_bytes < lamp_unet_stage_workspace_bytes(u, first, last, 1)) return LAMP_ERR_WORKSPACE;
+    lamp_unet_desc v = stage_desc(u, first);
+    Net nt{&v, v.levels, v.dtype, esize(v.dtype), (hipStream_t)stream, nullptr, 0};
+    Layout lay;
+    make_layout(nt, first, last, false, true, ws, lay, skips, pooled);
+    nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    return encoder_fwd(nt, lay, first, last, params, enc_pi(&v, first), x);
+}
+
+extern "C" lamp_status lamp_unet_stage_bwd(const lamp_unet_desc* u, int first, int last, const void* const* params,
+                                           const void* x, const void* const* skips, const void* d_pooled,
+                                           const void* const* d_skips, float* const* grads, float beta, void* dx, void* ws,
+                                           size_t ws_bytes, void* stream) {
+    lamp_status st = stage_ok(u, first, last);
+    if (st != LAMP_OK) return st;
+    const int m = 1 << (last - first + 1);
+    if (u->d % m || u->h % m || u->w % m) return LAMP_ERR_SHAPE;
+    if (!params || !x || !skips || !d_pooled || !d_skips || !grads) return LAMP_ERR_NULL;
+    for (int i = 0; i <= last - first; ++i)
+        if (!skips[i] || !d_skips[i]) return LAMP_ERR_NULL;
+    for (int i = 0; i < (last - first + 1) * 2 * per_conv(u); ++i)
+        if (!params[i] || !grads[i]) return LAMP_ERR_NULL;
+    if (beta != 0.f && beta != 1.f) return LAMP_ERR_SHAPE;
+    if (dx && first == 1) return LAMP_ERR_UNSUPPORTED;  // the first block's input is data
+    if (!aligned16(x) || !aligned16(ws) || !aligned16(d_pooled)) return LAMP_ERR_ALIGN;
+    if (!ws || ws_bytes < lamp_unet_stage_workspace_bytes(u, first, last, 1)) return LAMP_ERR_WORKSPACE;
+    lamp_unet_desc v = stage_desc(u, first);
+    Net nt{&v, v.levels, v.dtype, esize(v.dtype), (hipStream_t)stream, nullptr, 0};
+    Layout lay;
+    make_layout(nt, first, last, false, true, ws, lay, (void* const*)skips, nullptr);
+    nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    std::vector<const void*> sg(v.levels, nullptr);
+    std::vector<int> ld(v.levels, 0);
+    for (int l = first; l <= last; ++l) { sg[l - 1] = d_skips[l - first]; ld[l - 1] = nt.chan(l); }
+    return encoder_bwd(nt, lay, first, last, params, grads, enc_pi(&v, first), x, d_pooled, sg.data(), ld.data(), dx, beta);
+}
+
+// ---- sliding-window inference -------------------------------------------------------------------
+namespace lamp {
+
+static int sw_stride(int patch, float overlap) { return (int)lroundf(patch * (1.0f - overlap)); }
+static int sw_count1(int len, int patch, int stride) { return len <= patch ? 1 : (len - patch + stride - 1) / stride + 1; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void sw_gather_kernel(const T* __restrict__ vol, T* __restrict__ win, int D, int H, int W,
+                                                        int C, int P, int stride, int cd, int ch, int cw) {
+    const int64_t per = (int64_t)P * P * P * C;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= per * cd * ch * cw) return;
+    const int wi = (int)(idx / per);
+    int64_t r = idx % per;
+    const int c = (int)(r % C); r /= C;
+    const int k = (int)(r % P); r /= P;
+    const int j = (int)(r % P);
+    const int i = (int)(r / P);
+    const int iw = wi % cw, ih = (wi / cw) % ch, id = wi / (cw * ch);
+    int d0 = id * stride; if (d0 > D - P) d0 = D - P;
+    int h0 = ih * stride; if (h0 > H - P) h0 = H - P;
+    int w0 = iw * stride; if (w0 > W - P) w0 = W - P;
+    win[idx] = vol[((((int64_t)(d0 + i)) * H + (h0 + j)) * W + (w0 + k)) * C + c];
+}
+
+// One thread per volume voxel: gathers every covering window in d-major, h, w order.
+__global__ __launch_bounds__(256) void sw_blend_kernel(const float* __restrict__ wl, float* __restrict__ out, int D, int H,
+                                                       int W, int K, int P, int stride, int cd, int ch, int cw,
+                                                       float inv2s2) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= (int64_t)D * H * W) return;
+    const int w = (int)(v % W), h = (int)((v / W) % H), d = (int)(v / ((int64_t)W * H));
+    const float m = 0.5f * (P - 1);
+    float acc[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+    float wsum = 0.f;
+    for (int id = 0; id < cd; ++id) {
+        int d0 = id * stride; if (d0 > D - P) d0 = D - P;
+        if (d < d0 || d >= d0 + P) continue;
+        const float fd = (d - d0) - m;
+        for (int ih = 0; ih < ch; ++ih) {
+            int h0 = ih * stride; if (h0 > H - P) h0 = H - P;
+            if (h < h0 || h >= h0 + P) continue;
+            const float fh = (h - h0) - m;
+            for (int iw = 0; iw < cw; ++iw) {
+                int w0 = iw * stride; if (w0 > W - P) w0 = W - P;
+                if (w < w0 || w >= w0 + P) continue;
+                const float fw = (w - w0) - m;
+                const float g = expf(-(fd * fd + fh * fh + fw * fw) * inv2s2);
+                const int wi = (id * ch + ih) * cw + iw;
+                const float* p = wl + ((((int64_t)wi * P + (d - d0)) * P + (h - h0)) * P + (w - w0)) * K;
+#pragma unroll
+                for (int k = 0; k < 16; ++k)
+                    if (k < K) acc[k] = fmaf(g, p[k], acc[k]);
+                wsum += g;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+        if (k < K) out[v * K + k] = acc[k] / wsum;
+}
+
+}  // namespace lamp
+
+extern "C" int32_t lamp_sliding_window_count(int32_t D, int32_t H, int32_t W, int32_t patch, float overlap) {
+    if (patch < 1 || D < patch || H < patch || W < patch || !(overlap >= 0.f) || !(overlap < 1.f)) return 0;
+    const int s = sw_stride(patch, overlap);
+    if (s < 1) return 0;
+    return sw_count1(D, patch, s) * sw_count1(H, patch, s) * sw_count1(W, patch, s);
+}
+
+extern "C" size_t lamp_sliding_window_workspace_bytes(const lamp_unet_desc* pd, int32_t D, int32_t H, int32_t W) {
+    if (unet_desc_ok(pd) != LAMP_OK) return 0;
+    const int64_t per = (int64_t)pd->d * pd->h * pd->w;
+    return align_up((size_t)pd->n * per * pd->in_ch * esize(pd->dtype)) +
+           align_up((size_t)pd->n * per * pd->classes * sizeof(float)) + lamp_unet_workspace_bytes(pd, 0) + 512;
+}
+
+extern "C" lamp_status lamp_sliding_window_fwd(const lamp_unet_desc* pd, const void* const* params, const void* vol,
+                                               int32_t D, int32_t H, int32_t W, float overlap, float sigma_scale,
+                                               float* out, void* ws, size_t ws_bytes, void* stream) {
+    lamp_status st = unet_desc_ok(pd);
+    if (st != LAMP_OK) return st;
+    if (!params || !vol || !out) return LAMP_ERR_NULL;
+    const int P = pd->d;
+    if (pd->h != P || pd->w != P) return LAMP_ERR_SHAPE;
+    const int cnt = lamp_sliding_window_count(D, H, W, P, overlap);
+    if (cnt < 1 || cnt != pd->n || !(sigma_scale > 0.f)) return LAMP_ERR_SHAPE;
+    if (!ws || ws_bytes < lamp_sliding_window_workspace_bytes(pd, D, H, W)) return LAMP_ERR_WORKSPACE;
+    if (!aligned16(ws) || !aligned16(vol)) return LAMP_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const int stride = sw_stride(P, overlap);
+    const int cd = sw_count1(D, P, stride), ch = sw_count1(H, P, stride), cw = sw_count1(W, P, stride);
+    const int64_t per = (int64_t)P * P * P;
+    Carver cv(ws, ws_bytes);
+    void* win = cv.take((size_t)cnt * per * pd->in_ch * esize(pd->dtype));
+    float* wl = (float*)cv.take((size_t)cnt * per * pd->classes * sizeof(float));
+    const size_t ub = lamp_unet_workspace_bytes(pd, 0);
+    void* uws = cv.take(ub);
+    if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+    const int64_t tot = (int64_t)cnt * per * pd->in_ch;
+    if (pd->dtype == LAMP_BF16)
+        hipLaunchKernelGGL((sw_gather_kernel<bf16_t>), dim3(cdiv(tot, 256)), dim3(256), 0, s, (const bf16_t*)vol,
+                           (bf16_t*)win, D, H, W, pd->in_ch, P, stride, cd, ch, cw);
+    else
+        hipLaunchKernelGGL((sw_gather_kernel<float>), dim3(cdiv(tot, 256)), dim3(256), 0, s, (const float*)vol, (float*)win,
+                           D, H, W, pd->in_ch, P, stride, cd, ch, cw);
+    LAMP_CHECK_LAUNCH();
+    if ((st = lamp_unet_fwd(pd, params, win, wl, uws, ub, stream)) != LAMP_OK) return st;
+    const float sg = sigma_scale * P;
+    hipLaunchKernelGGL(sw_blend_kernel, dim3(cdiv((int64_t)D * H * W, 256)), dim3(256), 0, s, wl, out, D, H, W, pd->classes,
+                       P, stride, cd, ch, cw, 0.5f / (sg * sg));
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}

@@ -1,0 +1,181 @@
+"""The U-Net data flow replayed layer by layer through the library's layer entry points, with
+every layer's output checked against the oracle applied to the GPU's OWN inputs of that layer
+(teacher forcing).
+
+Why: two bf16 realisations of a deep net legitimately drift apart (a one-ulp difference in a
+stored activation flips a ReLU mask or a pooling arg-max at a near-tie, and each flip changes a
+gradient element by its full size), so an end-to-end gradient cannot be held to the per-layer
+tolerance.  Instead (a) each layer is held to it given identical inputs, and (b) the whole-network
+entry point must reproduce this chain bit for bit (same kernels, same order).
+"""
+import numpy as np
+import torch
+
+import oracle as O
+from gpu_util import DEV, as64, check
+
+F32 = torch.float32
+
+
+class Chain:
+    def __init__(self, L, levels, base, in_ch, classes, affine, dtype, names, params, eps=1e-5, verify=True):
+        self.L, self.levels, self.base, self.in_ch, self.K = L, levels, base, in_ch, classes
+        self.affine, self.dtype, self.eps, self.verify = affine, dtype, eps, verify
+        self.P = dict(zip(names, params))
+        self.names = names
+        self.worst = {}
+
+    def _chk(self, gpu, ref, what, ignore=None, tol=None):
+        if self.verify:
+            e = check(as64(gpu), ref, self.dtype, what, ignore=ignore, tol=tol)
+            self.worst[what.split(":")[0]] = max(self.worst.get(what.split(":")[0], 0.0), e)
+
+    def chan(self, l):
+        return self.base << (l - 1)
+
+    # ---- forward ------------------------------------------------------------------------------
+    def conv_in_relu(self, name, x, y_out=None):
+        L, P = self.L, self.P
+        w = P[name + ".w"]
+        g, b = P.get(name + ".gamma"), P.get(name + ".beta")
+        N, D, H, W, _ = x.shape
+        Co = w.shape[0]
+        z = torch.empty((N, D, H, W, Co), dtype=self.dtype, device=DEV)
+        st = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+        L.lamp_conv3d_fwd(x, w, z, stats_out=st, eps=self.eps)
+        y = y_out if y_out is not None else torch.empty_like(z)
+        L.lamp_inorm_relu(z, y, st, gamma=g, beta=b, eps=self.eps, stats_given=True)
+        if self.verify:
+            self._chk(z, O.conv3d_fwd(as64(x), as64(w)), f"conv fwd: {name}")
+            y_ref, st_ref = O.inorm_relu(as64(z), None if g is None else as64(g), None if b is None else as64(b), self.eps)
+            self._chk(y, y_ref, f"inorm+relu: {name}")
+            np.testing.assert_allclose(as64(st)[..., 0], st_ref[..., 0], atol=1e-4 * max(1.0, np.abs(st_ref[..., 0]).max()))
+            np.testing.assert_allclose(as64(st)[..., 1], st_ref[..., 1], rtol=2e-4)
+        return dict(x=x, z=z, st=st, y=y, name=name)
+
+    def block(self, prefix, x, y2_out=None):
+        c1 = self.conv_in_relu(prefix + ".conv1", x)
+        c2 = self.conv_in_relu(prefix + ".conv2", c1["y"], y2_out)
+        return c1, c2
+
+    def forward(self, x):
+        L, Lv = self.L, self.levels
+        N = x.shape[0]
+        self.enc, self.dec, self.cat, self.pooled = {}, {}, {}, {}
+        cur = x
+        for l in range(1, Lv + 1):
+            C = self.chan(l)
+            y2 = None
+            if l < Lv:
+                _, D, H, W, _ = cur.shape
+                self.cat[l] = torch.zeros((N, D, H, W, 2 * C), dtype=self.dtype, device=DEV)
+                y2 = self.cat[l][..., :C]
+            self.enc[l] = self.block(f"enc{l}", cur, y2)
+            if l < Lv:
+                yv = self.enc[l][1]["y"]
+                p = torch.empty((N, yv.shape[1] // 2, yv.shape[2] // 2, yv.shape[3] // 2, C), dtype=self.dtype, device=DEV)
+                L.lamp_maxpool2_fwd(yv, p)
+                if self.verify:
+                    np.testing.assert_array_equal(as64(p), O.maxpool2_fwd(as64(yv)))
+                self.pooled[l] = p
+                cur = p
+        cur = self.enc[Lv][1]["y"]
+        for l in range(Lv - 1, 0, -1):
+            C = self.chan(l)
+            up = self.cat[l][..., C:]
+            wt, bt = self.P[f"dec{l}.up.w"], self.P[f"dec{l}.up.b"]
+            L.lamp_convtr3d(cur, wt, up, bias=bt)
+            self._chk(up, O.convtr3d_fwd(as64(cur), as64(wt), as64(bt)) if self.verify else None, f"convtr fwd: dec{l}")
+            self.dec[l] = self.block(f"dec{l}", self.cat[l])
+            self.dec[l] = self.dec[l] + (cur,)
+            cur = self.dec[l][1]["y"]
+        self.top = cur
+        logits = torch.empty(tuple(cur.shape[:4]) + (self.K,), dtype=F32, device=DEV)
+        L.lamp_head_fwd(cur, self.P["head.w"], self.P["head.b"], logits)
+        if self.verify:
+            check(as64(logits), O.head_fwd(as64(cur), as64(self.P["head.w"]), as64(self.P["head.b"])), F32, "head fwd", tol=1e-5)
+        return logits
+
+    # ---- backward -----------------------------------------------------------------------------
+    def conv_bwd(self, c, g, grads, want_dx, dx_out=None):
+        """g: gradient w.r.t. c['y'] (overwritten with dz).  Returns dx (or None)."""
+        L, P, name = self.L, self.P, c["name"]
+        w = P[name + ".w"]
+        gm, bt = P.get(name + ".gamma"), P.get(name + ".beta")
+        dg = torch.empty_like(gm) if gm is not None else None
+        db = torch.empty_like(bt) if bt is not None else None
+        g_in = as64(g) if self.verify else None
+        L.lamp_inorm_relu_bwd(g, c["z"], c["st"], g, gamma=gm, beta=bt, dgamma=dg, dbeta=db)
+        if self.verify:
+            g64 = None if gm is None else as64(gm)
+            b64 = None if bt is None else as64(bt)
+            dz_ref, dg_ref, db_ref = O.inorm_relu_bwd(g_in, as64(c["z"]), g64, b64, self.eps)
+            u_ref, _ = O.inorm_relu(as64(c["z"]), g64, b64, self.eps, relu=False)
+            near = np.abs(u_ref) <= 1e-3
+            self._chk(g, dz_ref, f"inorm bwd: {name}", ignore=near)
+        if gm is not None:
+            grads[name + ".gamma"], grads[name + ".beta"] = dg, db
+        dw = torch.empty(w.shape, dtype=F32, device=DEV)
+        L.lamp_conv3d_wgrad(c["x"], g, dw)
+        if self.verify:
+            self._chk(dw, O.conv3d_wgrad(as64(c["x"]), as64(g))[0], f"conv wgrad: {name}",
+                      tol=2e-3 if self.dtype != F32 else 1e-4)
+        grads[name + ".w"] = dw
+        if not want_dx:
+            return None
+        dx = dx_out if dx_out is not None else torch.empty_like(c["x"])
+        L.lamp_conv3d_dgrad(g, w, dx)
+        if self.verify:
+            self._chk(dx, O.conv3d_dgrad(as64(g), as64(w)), f"conv dgrad: {name}")
+        return dx
+
+    def backward(self, labels):
+        L, Lv = self.L, self.levels
+        grads = {}
+        loss = torch.empty((), dtype=F32, device=DEV)
+        top = self.top
+        g = torch.empty(top.shape, dtype=self.dtype, device=DEV)
+        dwh = torch.empty(self.P["head.w"].shape, dtype=F32, device=DEV)
+        dbh = torch.empty(self.P["head.b"].shape, dtype=F32, device=DEV)
+        logits = torch.empty(tuple(top.shape[:4]) + (self.K,), dtype=F32, device=DEV)
+        L.lamp_head_ce(top, self.P["head.w"], self.P["head.b"], labels, loss, logits=logits, dx=g, dwh=dwh, dbh=dbh)
+        if self.verify:
+            loss_ref, dl = O.cross_entropy(as64(logits), labels.cpu().numpy())
+            assert abs(loss.item() - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref))
+            gy, gw, gb = O.head_bwd(as64(top), as64(self.P["head.w"]), dl)
+            self._chk(g, gy, "head dx")
+            self._chk(dwh, gw, "head dW", tol=1e-4)
+            self._chk(dbh, gb, "head db", tol=1e-4)
+        grads["head.w"], grads["head.b"] = dwh, dbh
+        skip_g = {}
+        for l in range(1, Lv):
+            C = self.chan(l)
+            c1, c2, upx = self.dec[l]
+            g = self.conv_bwd(c2, g, grads, True)
+            gcat = torch.empty_like(self.cat[l])
+            self.conv_bwd(c1, g, grads, True, dx_out=gcat)
+            skip_g[l] = gcat[..., :C]
+            gup = gcat[..., C:]
+            wt = self.P[f"dec{l}.up.w"]
+            g = torch.empty_like(upx)
+            dwt = torch.empty(wt.shape, dtype=F32, device=DEV)
+            dbt = torch.empty((C,), dtype=F32, device=DEV)
+            L.lamp_convtr3d_bwd(upx, wt, gup, dx=g, dwt=dwt, dbias=dbt)
+            if self.verify:
+                dx_ref, dwt_ref, db_ref = O.convtr3d_bwd(as64(upx), as64(wt), as64(gup))
+                self._chk(g, dx_ref, f"convtr dgrad: dec{l}")
+                self._chk(dwt, dwt_ref, f"convtr wgrad: dec{l}", tol=2e-3 if self.dtype != F32 else 1e-4)
+                self._chk(dbt, db_ref, f"convtr dbias: dec{l}", tol=1e-4)
+            grads[f"dec{l}.up.w"], grads[f"dec{l}.up.b"] = dwt, dbt
+        for l in range(Lv, 0, -1):
+            c1, c2 = self.enc[l]
+            if l < Lv:
+                gy = torch.empty(c2["y"].shape, dtype=self.dtype, device=DEV)
+                L.lamp_maxpool2_bwd(c2["y"], g, gy, add=skip_g[l])
+                if self.verify:
+                    ref = O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(skip_g[l])
+                    self._chk(gy, ref, f"pool bwd: enc{l}", tol=4e-3 if self.dtype != F32 else 1e-6)
+                g = gy
+            g = self.conv_bwd(c2, g, grads, True)
+            g = self.conv_bwd(c1, g, grads, l > 1)
+        return loss, grads

@@ -1,0 +1,105 @@
+"""Host-only checks of the C-ABI boundary: the library loads, exports every symbol that
+include/lamp.h declares, and its host logic (parameter table, window count, argument errors that
+are detected before any launch) behaves.  No compute call is made: no GPU is needed."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import lamp_synth as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2006_12575_amd as L
+    if not os.path.exists(L.LIB_PATH):
+        from paper_2006_12575_amd import build
+        build.build(verbose=False)
+    return L
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lamp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lamp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(L):
+    lib = ctypes.CDLL(L.LIB_PATH)
+    names = declared_symbols()
+    assert len(names) >= 28
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lamp.h but not exported"
+    assert set(L.EXPORTS) == set(names), set(L.EXPORTS) ^ set(names)
+    assert "gfx950" in L.build_info()
+
+
+def test_param_table_matches_documented_order(L):
+    for levels, base, in_ch, classes, affine in [(5, 32, 1, 10, False), (3, 8, 1, 5, False), (3, 4, 2, 3, True), (1, 8, 1, 2, True)]:
+        ud = L.unet_desc(levels, base, in_ch, classes, 1, 16, 16, 16, torch.float32, affine=affine)
+        p = S.unet_params(S.streams(0, 1)[0], levels, base, in_ch, classes, affine)
+        assert L.lamp_unet_param_count(ud) == len(p)
+        for i, (k, v) in enumerate(p.items()):
+            assert L.lamp_unet_param_numel(ud, i) == v.size, (i, k)
+        assert L.lamp_unet_param_numel(ud, len(p)) == 0 and L.lamp_unet_param_numel(ud, -1) == 0
+
+
+def test_window_count(L):
+    assert L.lamp_sliding_window_count(256, 256, 160, 64, 0.25) == 75
+    assert L.lamp_sliding_window_count(64, 64, 64, 64, 0.25) == 1
+    assert L.lamp_sliding_window_count(100, 64, 64, 64, 0.25) == 2
+    assert L.lamp_sliding_window_count(32, 64, 64, 64, 0.25) == 0  # volume smaller than the patch
+
+
+def test_workspace_queries_and_bad_descriptors(L):
+    ud = L.unet_desc(5, 32, 1, 10, 2, 128, 128, 128, torch.bfloat16)
+    fwd, bwd = L.lamp_unet_workspace_bytes(ud, False), L.lamp_unet_workspace_bytes(ud, True)
+    assert 0 < fwd < bwd < 16 * 2 ** 30
+    bad = L.unet_desc(5, 32, 1, 10, 2, 120, 128, 128, torch.bfloat16)  # 120 not divisible by 16
+    assert L.lamp_unet_workspace_bytes(bad, False) == 0 and L.lamp_unet_param_count(bad) == 0
+    assert L.status_string(0) == "ok" and "NULL" in L.status_string(-1)
+
+
+def test_argument_errors_are_caught_on_the_host(L):
+    """Every call below must return its error before touching the device (there is none here)."""
+    lib = L.lib()
+    TD = L.binding.TensorDesc
+    d = TD(1, 4, 4, 4, 8, 8, L.binding.BF16)
+    fake = ctypes.c_void_p(4096)  # 16-byte aligned, never dereferenced
+    by = ctypes.byref
+    # NULL required pointer
+    assert lib.lamp_conv3d_fwd(by(d), None, None, fake, None, by(d), fake, None, 1e-5, None, 0, None) == -1
+    # shape mismatch between x and z
+    d2 = TD(1, 4, 4, 5, 8, 8, L.binding.BF16)
+    assert lib.lamp_conv3d_fwd(by(d), fake, None, fake, None, by(d2), fake, None, 1e-5, None, 0, None) == -2
+    # ldc < c
+    d3 = TD(1, 4, 4, 4, 8, 4, L.binding.BF16)
+    assert lib.lamp_conv3d_fwd(by(d3), fake, None, fake, None, by(d), fake, None, 1e-5, None, 0, None) == -2
+    # dtype mismatch
+    d4 = TD(1, 4, 4, 4, 8, 8, L.binding.F32)
+    assert lib.lamp_conv3d_fwd(by(d), fake, None, fake, None, by(d4), fake, None, 1e-5, None, 0, None) == -4
+    # misaligned bf16 pointer
+    assert lib.lamp_conv3d_fwd(by(d), ctypes.c_void_p(4098), None, fake, None, by(d), fake, None, 1e-5, None, 0, None) == -3
+    # statistics requested without a workspace
+    assert lib.lamp_conv3d_fwd(by(d), fake, None, fake, None, by(d), fake, fake, 1e-5, None, 0, None) == -5
+    # wgrad: beta other than 0/1
+    assert lib.lamp_conv3d_wgrad(by(d), fake, None, by(d), fake, fake, None, 0.5, fake, 1 << 30, None) == -2
+    # pool: odd dimension
+    odd = TD(1, 3, 4, 4, 8, 8, L.binding.BF16)
+    half = TD(1, 1, 2, 2, 8, 8, L.binding.BF16)
+    assert lib.lamp_maxpool2_fwd(by(odd), fake, None, by(half), fake, None) == -2
+    # head: too many classes
+    assert lib.lamp_head_fwd(by(d), fake, None, fake, None, 17, fake, None) == -2
+    # unet: spatial dims not divisible by 2^(levels-1); missing workspace
+    ud = L.unet_desc(3, 8, 1, 5, 1, 30, 32, 32, torch.float32)
+    tbl = (ctypes.c_void_p * 32)(*([4096] * 32))
+    assert lib.lamp_unet_fwd(by(ud), tbl, fake, fake, fake, 1 << 40, None) == -2
+    ud = L.unet_desc(3, 8, 1, 5, 1, 32, 32, 32, torch.float32)
+    assert lib.lamp_unet_fwd(by(ud), tbl, fake, fake, fake, 16, None) == -5
+    # sliding window: batch of the patch descriptor must equal the window count
+    pd = L.unet_desc(3, 8, 1, 5, 7, 64, 64, 64, torch.float32)
+    assert lib.lamp_sliding_window_fwd(by(pd), tbl, fake, 256, 256, 160, 0.25, 0.125, fake, fake, 1 << 40, None) == -2

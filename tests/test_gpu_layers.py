@@ -1,0 +1,269 @@
+"""GPU parity of every layer entry point against the CPU oracle, through the C ABI.
+
+Same seeded inputs on both sides; inputs are rounded to the storage dtype first and the oracle
+gets exactly those values widened to fp64, so only the kernel's own error is measured.
+Shapes span several tiles with ragged tails, odd channel counts and channel-sliced views.
+"""
+import numpy as np
+import pytest
+import torch
+
+import lamp_synth as S
+import oracle as O
+from gpu_util import DEV, as64, check, to_dev
+
+pytestmark = pytest.mark.gpu
+
+BF, F32 = torch.bfloat16, torch.float32
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2006_12575_amd as L
+    L.lib()
+    return L
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+CONV_SHAPES = [
+    # N, D, H, W, Ci, Co
+    (1, 5, 6, 7, 3, 5),       # odd everything
+    (2, 4, 9, 17, 1, 8),      # first-layer style, ragged W
+    (1, 8, 8, 16, 32, 32),    # exactly one matrix-core tile
+    (1, 9, 13, 21, 32, 64),   # ragged tiles
+    (2, 6, 10, 18, 64, 32),
+    (1, 4, 8, 16, 128, 64),   # several K chunks
+    (1, 3, 5, 33, 64, 128),
+    (1, 12, 20, 36, 64, 64),
+    (1, 4, 8, 16, 96, 96),    # multiple of 32 but not of 64
+]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_fwd_dgrad_wgrad(L, dtype, shape):
+    N, D, H, W, Ci, Co = shape
+    r = rng(100 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)), dtype)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), dtype)
+    b = to_dev(S.normal(r, (Co,), 0.1), F32)
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)), dtype)
+    # forward with bias and fused statistics
+    z = torch.empty((N, D, H, W, Co), dtype=dtype, device=DEV)
+    stats = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, bias=b, stats_out=stats)
+    z_ref = O.conv3d_fwd(as64(x), as64(w), as64(b))
+    check(as64(z), z_ref, dtype, "conv fwd")
+    # statistics are those of the stored z
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "stats mean", tol=1e-4 * max(1.0, 1.0))
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-4)
+    # no bias, no stats
+    z2 = torch.empty_like(z)
+    L.lamp_conv3d_fwd(x, w, z2)
+    check(as64(z2), O.conv3d_fwd(as64(x), as64(w)), dtype, "conv fwd (no bias)")
+    # data gradient
+    dx = torch.empty_like(x)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), dtype, "conv dgrad")
+    # weight gradient (fp32 out), bias gradient, accumulation
+    dw = torch.full((Co, 3, 3, 3, Ci), float("nan"), dtype=F32, device=DEV)
+    db = torch.full((Co,), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_wgrad(x, dz, dw, dbias=db, beta=0.0)
+    dw_ref, db_ref = O.conv3d_wgrad(as64(x), as64(dz), want_db=True)
+    check(as64(dw), dw_ref, dtype, "conv wgrad", tol=1e-4 if dtype == F32 else 2e-3)
+    check(as64(db), db_ref, dtype, "conv dbias", tol=1e-4)
+    L.lamp_conv3d_wgrad(x, dz, dw, dbias=db, beta=1.0)
+    check(as64(dw), 2 * dw_ref, dtype, "conv wgrad beta=1", tol=1e-4 if dtype == F32 else 2e-3)
+    check(as64(db), 2 * db_ref, dtype, "conv dbias beta=1", tol=1e-4)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+def test_conv3d_on_channel_slices_and_norm_on_load(L, dtype):
+    """Input read from a channel slice of a wider buffer with normalise+ReLU on load for the first
+    c_norm channels (the concat case), output written into a channel slice."""
+    N, D, H, W, Ci, Co, cn = 2, 5, 6, 9, 64, 32, 32
+    r = rng(7)
+    buf = to_dev(S.normal(r, (N, D, H, W, Ci + 16)), dtype)
+    x = buf[..., 16:]
+    w = to_dev(S.kaiming_conv(r, Co, Ci), dtype)
+    st = torch.stack([to_dev(S.normal(r, (N, cn), 0.3), F32), to_dev(r.uniform(0.5, 2.0, (N, cn)), F32)], dim=-1).contiguous()
+    g = to_dev(r.uniform(0.5, 1.5, cn), F32)
+    bt = to_dev(r.uniform(-0.5, 0.5, cn), F32)
+    obuf = torch.zeros((N, D, H, W, 2 * Co), dtype=dtype, device=DEV)
+    z = obuf[..., Co:]
+    nm = dict(mean_rstd=st, gamma=g, beta=bt, c_norm=cn, relu=1)
+    L.lamp_conv3d_fwd(x, w, z, xnorm=nm)
+    xs = as64(x).copy()
+    s64, g64, b64 = as64(st), as64(g), as64(bt)
+    u = g64 * ((xs[..., :cn] - s64[:, None, None, None, :, 0]) * s64[:, None, None, None, :, 1]) + b64
+    xs[..., :cn] = np.maximum(u, 0.0)
+    if dtype == BF:
+        xs[..., :cn] = O.round_bf16(xs[..., :cn])
+    check(as64(z), O.conv3d_fwd(xs, as64(w)), dtype, "conv fwd sliced + norm-on-load")
+    assert torch.all(obuf[..., :Co] == 0), "wrote outside the channel slice"
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)), dtype)
+    dw = torch.empty((Co, 3, 3, 3, Ci), dtype=F32, device=DEV)
+    L.lamp_conv3d_wgrad(x, dz, dw, xnorm=nm)
+    check(as64(dw), O.conv3d_wgrad(xs, as64(dz))[0], dtype, "conv wgrad sliced + norm-on-load",
+          tol=1e-4 if dtype == F32 else 2e-3)
+    dxb = torch.zeros_like(buf)
+    L.lamp_conv3d_dgrad(dz, w, dxb[..., 16:])
+    check(as64(dxb[..., 16:]), O.conv3d_dgrad(as64(dz), as64(w)), dtype, "conv dgrad into slice")
+    assert torch.all(dxb[..., :16] == 0)
+
+
+NORM_SHAPES = [(2, 3, 5, 7, 5), (1, 8, 8, 8, 8), (2, 16, 20, 24, 64), (1, 17, 9, 33, 32), (1, 4, 4, 4, 512), (1, 6, 6, 6, 24)]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", NORM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("affine", [False, True], ids=["plain", "affine"])
+def test_inorm_relu_fwd_bwd(L, dtype, shape, affine):
+    N, D, H, W, C = shape
+    r = rng(200 + sum(shape))
+    z = to_dev(S.normal(r, shape, 1.7) + 0.4, dtype)
+    dy = to_dev(S.normal(r, shape), dtype)
+    g = to_dev(r.uniform(0.5, 1.5, C), F32) if affine else None
+    b = to_dev(r.uniform(-0.5, 0.5, C), F32) if affine else None
+    y = torch.empty_like(z)
+    stats = torch.empty((N, C, 2), dtype=F32, device=DEV)
+    L.lamp_inorm_relu(z, y, stats, gamma=g, beta=b)
+    g64 = as64(g) if affine else None
+    b64 = as64(b) if affine else None
+    y_ref, st_ref = O.inorm_relu(as64(z), g64, b64)
+    check(as64(y), y_ref, dtype, "inorm+relu")
+    np.testing.assert_allclose(as64(stats)[..., 0], st_ref[..., 0], atol=2e-5)
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=1e-4)
+    # apply-only with given statistics, in place
+    y2 = z.clone()
+    L.lamp_inorm_relu(y2, y2, stats, gamma=g, beta=b, stats_given=True)
+    assert torch.equal(y2, y)
+    # backward; elements whose pre-activation is within 1e-3 of the ReLU kink may legitimately
+    # take either side of the mask: excluded from the element-wise bound
+    u_ref, _ = O.inorm_relu(as64(z), g64, b64, relu=False)
+    near = np.abs(u_ref) <= 1e-3
+    dz = torch.empty_like(z)
+    dg = torch.empty(C, dtype=F32, device=DEV) if affine else None
+    db = torch.empty(C, dtype=F32, device=DEV) if affine else None
+    L.lamp_inorm_relu_bwd(dy, z, stats, dz, gamma=g, beta=b, dgamma=dg, dbeta=db)
+    dz_ref, dg_ref, db_ref = O.inorm_relu_bwd(as64(dy), as64(z), g64, b64)
+    check(as64(dz), dz_ref, dtype, "inorm bwd dz", ignore=near)
+    assert near.mean() < 0.01
+    if affine:
+        V = N * D * H * W
+        slack = (np.abs(as64(dy)) * near).reshape(-1, C).sum(0)  # what flipped masks could move
+        assert np.all(np.abs(as64(db) - db_ref) <= 1e-4 * np.abs(db_ref).max() + slack + 1e-3 * np.sqrt(V) * (dtype == BF))
+        assert np.all(np.abs(as64(dg) - dg_ref) <= 1e-4 * np.abs(dg_ref).max() + 3 * slack + 1e-3 * np.sqrt(V) * (dtype == BF))
+    # in-place backward gives the same bits
+    dz2 = dy.clone()
+    L.lamp_inorm_relu_bwd(dz2, z, stats, dz2, gamma=g, beta=b)
+    assert torch.equal(dz2, dz)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 4, 6, 10, 5), (1, 8, 8, 8, 32), (2, 6, 10, 14, 64), (1, 2, 2, 2, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_maxpool2_fwd_bwd(L, dtype, shape):
+    N, D, H, W, C = shape
+    r = rng(300 + sum(shape))
+    x = to_dev(S.normal(r, shape), dtype)
+    y = torch.empty((N, D // 2, H // 2, W // 2, C), dtype=dtype, device=DEV)
+    L.lamp_maxpool2_fwd(x, y)
+    np.testing.assert_array_equal(as64(y), O.maxpool2_fwd(as64(x)))  # exact: a selection
+    dy = to_dev(S.normal(r, y.shape), dtype)
+    dx = torch.empty_like(x)
+    L.lamp_maxpool2_bwd(x, dy, dx)
+    np.testing.assert_array_equal(as64(dx), O.maxpool2_bwd(as64(x), as64(dy)))
+    # with the skip gradient added, through channel-sliced views
+    addbuf = to_dev(S.normal(r, (N, D, H, W, 2 * C)), dtype)
+    add = addbuf[..., :C]
+    L.lamp_maxpool2_bwd(x, dy, dx, add=add)
+    ref = O.maxpool2_bwd(as64(x), as64(dy)) + as64(add)
+    check(as64(dx), ref, dtype, "pool bwd + skip", tol=4e-3 if dtype == BF else 1e-6)
+    # ties: constant input -> first position of each window takes the gradient
+    xc = torch.ones_like(x)
+    L.lamp_maxpool2_bwd(xc, dy, dx)
+    np.testing.assert_array_equal(as64(dx), O.maxpool2_bwd(as64(xc), as64(dy)))
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 6, 3), (1, 4, 4, 8, 64, 32), (1, 2, 3, 9, 16, 8), (2, 2, 2, 2, 128, 64)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_convtr3d_fwd_bwd(L, dtype, shape):
+    N, D, H, W, Ci, Co = shape
+    r = rng(400 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)), dtype)
+    wt = to_dev(S.kaiming_convtr(r, Ci, Co), dtype)
+    b = to_dev(S.normal(r, (Co,), 0.1), F32)
+    cat = torch.zeros((N, 2 * D, 2 * H, 2 * W, 2 * Co), dtype=dtype, device=DEV)
+    y = cat[..., Co:]  # written into the upper half of a concat buffer
+    L.lamp_convtr3d(x, wt, y, bias=b)
+    check(as64(y), O.convtr3d_fwd(as64(x), as64(wt), as64(b)), dtype, "convtr fwd")
+    assert torch.all(cat[..., :Co] == 0)
+    dcat = to_dev(S.normal(r, cat.shape), dtype)
+    dy = dcat[..., Co:]
+    dx = torch.empty_like(x)
+    dwt = torch.full(wt.shape, float("nan"), dtype=F32, device=DEV)
+    db = torch.full((Co,), float("nan"), dtype=F32, device=DEV)
+    L.lamp_convtr3d_bwd(x, wt, dy, dx=dx, dwt=dwt, dbias=db)
+    dx_ref, dwt_ref, db_ref = O.convtr3d_bwd(as64(x), as64(wt), as64(dy))
+    check(as64(dx), dx_ref, dtype, "convtr dgrad")
+    check(as64(dwt), dwt_ref, dtype, "convtr wgrad", tol=1e-4 if dtype == F32 else 2e-3)
+    check(as64(db), db_ref, dtype, "convtr dbias", tol=1e-4)
+    L.lamp_convtr3d_bwd(x, wt, dy, dwt=dwt, dbias=db, beta=1.0)
+    check(as64(dwt), 2 * dwt_ref, dtype, "convtr wgrad beta=1", tol=1e-4 if dtype == F32 else 2e-3)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 8, 5), (1, 8, 8, 8, 32, 10), (1, 5, 7, 9, 6, 1), (1, 4, 4, 4, 64, 16)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_head_softmax_ce(L, dtype, shape):
+    N, D, H, W, C, K = shape
+    r = rng(500 + sum(shape))
+    x = to_dev(np.maximum(S.normal(r, (N, D, H, W, C)), 0), dtype)
+    wh = to_dev(S.normal(r, (K, C), np.sqrt(2.0 / C)), dtype)
+    bh = to_dev(S.normal(r, (K,), 0.1), F32)
+    lab = torch.from_numpy(r.integers(0, K, (N, D, H, W)).astype(np.int32)).to(DEV)
+    logits = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
+    L.lamp_head_fwd(x, wh, bh, logits)
+    lg_ref = O.head_fwd(as64(x), as64(wh), as64(bh))
+    check(as64(logits), lg_ref, F32, "head logits", tol=1e-5)
+    loss = torch.empty((), dtype=F32, device=DEV)
+    lg2 = torch.empty_like(logits)
+    dx = torch.empty_like(x)
+    dwh = torch.empty((K, C), dtype=F32, device=DEV)
+    dbh = torch.empty((K,), dtype=F32, device=DEV)
+    L.lamp_head_ce(x, wh, bh, lab, loss, logits=lg2, dx=dx, dwh=dwh, dbh=dbh)
+    assert torch.equal(lg2, logits)
+    loss_ref, dl_ref = O.cross_entropy(lg_ref, lab.cpu().numpy())
+    assert abs(loss.item() - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref))
+    dx_ref, dwh_ref, dbh_ref = O.head_bwd(as64(x), as64(wh), dl_ref)
+    check(as64(dx), dx_ref, dtype, "head dx")
+    check(as64(dwh), dwh_ref, dtype, "head dW", tol=1e-4)
+    check(as64(dbh), dbh_ref, dtype, "head db", tol=1e-4)
+    # uniform logits: loss = ln K
+    L.lamp_head_ce(x, torch.zeros_like(wh), torch.full_like(bh, 0.3), lab, loss)
+    assert abs(loss.item() - np.log(K)) < 1e-5
+
+
+def test_determinism_bitwise(L):
+    r = rng(9)
+    x = to_dev(S.normal(r, (1, 12, 20, 36, 64)), BF)
+    w = to_dev(S.kaiming_conv(r, 64, 64), BF)
+    dz = to_dev(S.normal(r, (1, 12, 20, 36, 64)), BF)
+    outs = []
+    for _ in range(2):
+        z = torch.empty_like(dz)
+        st = torch.empty((1, 64, 2), dtype=F32, device=DEV)
+        dx = torch.empty_like(x)
+        dw = torch.empty((64, 3, 3, 3, 64), dtype=F32, device=DEV)
+        L.lamp_conv3d_fwd(x, w, z, stats_out=st)
+        L.lamp_conv3d_dgrad(dz, w, dx)
+        L.lamp_conv3d_wgrad(x, dz, dw)
+        outs.append((z, st, dx, dw))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

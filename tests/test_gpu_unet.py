@@ -1,0 +1,173 @@
+"""GPU parity of the network-level entry points (whole U-Net forward / forward+backward, one
+encoder partition, sliding-window inference) against the network oracle.
+
+bf16 runs are compared with the oracle that rounds every stored activation / gradient tensor to
+bf16 at the same tensor boundaries (storage emulation); fp32 runs with the pure fp64 oracle.
+End-to-end gradients are judged on the weight gradients (sums over >= 10^3 voxels, where an
+isolated ReLU-mask or arg-max flip at a near-tie averages out) and on the loss.
+"""
+import numpy as np
+import pytest
+import torch
+
+import lamp_synth as S
+import oracle as O
+from gpu_util import DEV, as64, check, e2, to_dev
+from oracle import sliding, unet
+
+pytestmark = pytest.mark.gpu
+BF, F32 = torch.bfloat16, torch.float32
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2006_12575_amd as L
+    L.lib()
+    return L
+
+
+def make_net(levels, base, in_ch, classes, affine, dtype, seed):
+    rp = S.streams(seed, 1)[0]
+    p = S.unet_params(rp, levels, base, in_ch, classes, affine, test_mode=True)
+    dev, ora = [], {}
+    for k, v in p.items():
+        small = k.endswith((".b", ".gamma", ".beta"))
+        t = to_dev(v, F32 if small else dtype)
+        dev.append(t)
+        ora[k] = as64(t)
+    return list(p.keys()), dev, ora
+
+
+def test_config1_tiny_unet_forward_fp32(L):
+    """Tiny 3-level base-8 U-Net forward in fp32 on 1x1x32x32x32 N(0,1) voxels, 5 classes."""
+    rx = S.streams(1001, 2)[0]
+    names, dev, ora = make_net(3, 8, 1, 5, False, F32, 1001)
+    x = to_dev(S.normal(rx, (1, 32, 32, 32, 1)), F32)
+    ud = L.unet_desc(3, 8, 1, 5, 1, 32, 32, 32, F32)
+    logits = torch.empty((1, 32, 32, 32, 5), dtype=F32, device=DEV)
+    L.lamp_unet_fwd(ud, dev, x, logits)
+    ref, _ = unet.forward(ora, as64(x), 3)
+    e = check(as64(logits), ref, F32, "config 1 logits")
+    print(f"config1 E_inf={e:.2e} E2={e2(as64(logits), ref):.2e}")
+    # run-to-run determinism
+    l2 = torch.empty_like(logits)
+    L.lamp_unet_fwd(ud, dev, x, l2)
+    assert torch.equal(l2, logits)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(levels=3, base=32, in_ch=1, classes=10, affine=False, dtype=BF, dims=(2, 16, 16, 32)),
+    dict(levels=2, base=8, in_ch=2, classes=5, affine=True, dtype=F32, dims=(1, 8, 12, 16)),
+    dict(levels=3, base=32, in_ch=1, classes=4, affine=True, dtype=BF, dims=(1, 16, 24, 16)),
+    dict(levels=1, base=32, in_ch=1, classes=3, affine=False, dtype=BF, dims=(1, 8, 8, 16)),
+], ids=["bf16-3lvl", "f32-affine", "bf16-affine", "bf16-1lvl"])
+def test_unet_fwd_bwd(L, cfg):
+    """(a) every layer of the replayed chain matches the oracle given the GPU's own inputs,
+    (b) lamp_unet_fwd_bwd reproduces the chain bit for bit, (c) end to end, logits and loss match the
+    storage-emulating oracle to the path's tolerance; end-to-end gradients are only sanity-checked
+    (two bf16 realisations of a deep net drift apart through mask / arg-max flips at near-ties)."""
+    from gpu_chain import Chain
+    levels, dtype = cfg["levels"], cfg["dtype"]
+    N, D, H, W = cfg["dims"]
+    names, dev, ora = make_net(levels, cfg["base"], cfg["in_ch"], cfg["classes"], cfg["affine"], dtype, 77)
+    rx, rl = S.streams(78, 2)
+    x = to_dev(S.ct_volume(rx, N, D, H, W) if cfg["in_ch"] == 1 else S.normal(rx, (N, D, H, W, cfg["in_ch"])), dtype)
+    lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, cfg["classes"])).to(DEV)
+    ud = L.unet_desc(levels, cfg["base"], cfg["in_ch"], cfg["classes"], N, D, H, W, dtype, affine=cfg["affine"])
+    grads = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev]
+    loss = torch.empty((), dtype=F32, device=DEV)
+    logits = torch.empty((N, D, H, W, cfg["classes"]), dtype=F32, device=DEV)
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
+    # (a) + (b)
+    ch = Chain(L, levels, cfg["base"], cfg["in_ch"], cfg["classes"], cfg["affine"], dtype, names, dev)
+    lg_chain = ch.forward(x)
+    loss_chain, g_chain = ch.backward(lab)
+    assert torch.equal(lg_chain, logits), "whole-net logits differ from the layer-by-layer chain"
+    assert torch.equal(loss_chain, loss)
+    for k, g in zip(names, grads):
+        assert torch.equal(g_chain[k], g), f"whole-net grad {k} differs from the layer-by-layer chain"
+    print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
+    # (c)
+    store = O.round_bf16 if dtype == BF else (lambda a: a)
+    loss_ref, g_ref, lg_ref, _ = unet.loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, store=store)
+    check(as64(logits), lg_ref, dtype, "logits", tol=1e-2 if dtype == BF else 1e-4)
+    assert abs(loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
+    for k, g in zip(names, grads):
+        a, b = as64(g).ravel(), g_ref[k].ravel()
+        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+        if dtype == F32:
+            check(as64(g), g_ref[k], dtype, f"grad {k}", tol=1e-3)
+        else:
+            assert cos > 0.9, f"grad {k}: cosine {cos:.3f} to the storage-emulating oracle"
+    # forward-only entry point gives the same logits; beta=1 accumulates
+    l2 = torch.empty_like(logits)
+    L.lamp_unet_fwd(ud, dev, x, l2)
+    assert torch.equal(l2, logits)
+    g2 = [g.clone() for g in grads]
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, g2, beta=1.0)
+    for a, b in zip(grads, g2):
+        assert torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
+
+
+def test_stage_partition_fwd_bwd(L):
+    """One pipeline partition = encoder blocks 1-2 (Sec. 2.1 / Eq. 3): outputs pool(e_2), e_1, e_2;
+    backward from N(0,1) upstream gradients of all three outputs.  The partition must reproduce the
+    whole net's own tensors bit for bit (Eq. 3 == Eq. 2), and its backward the layer-by-layer chain."""
+    from gpu_chain import Chain
+    levels, base, dtype = 3, 32, BF
+    N, D, H, W = 1, 16, 16, 32
+    names, dev, ora = make_net(levels, base, 1, 4, False, dtype, 5)
+    sp = dev[:4]
+    rx, rg = S.streams(6, 2)
+    x = to_dev(S.ct_volume(rx, N, D, H, W), dtype)
+    ud = L.unet_desc(levels, base, 1, 4, N, D, H, W, dtype)
+    ws = torch.empty(L.lamp_unet_stage_workspace_bytes(ud, 1, 2), dtype=torch.uint8, device=DEV)
+    pooled = torch.empty((N, D // 4, H // 4, W // 4, 2 * base), dtype=dtype, device=DEV)
+    skips = [torch.empty((N, D, H, W, base), dtype=dtype, device=DEV),
+             torch.empty((N, D // 2, H // 2, W // 2, 2 * base), dtype=dtype, device=DEV)]
+    L.lamp_unet_stage_fwd(ud, 1, 2, sp, x, pooled, skips, ws)
+    ch = Chain(L, levels, base, 1, 4, False, dtype, names, dev)
+    ch.forward(x)  # whole net, every layer verified against the oracle
+    assert torch.equal(skips[0], ch.enc[1][1]["y"]) and torch.equal(skips[1], ch.enc[2][1]["y"])
+    assert torch.equal(pooled, ch.pooled[2])
+    (p_ref, s_ref), cache = unet.forward(ora, as64(x), levels, store=O.round_bf16, first_level=1, last_level=2)
+    check(as64(pooled), p_ref, dtype, "stage pooled")
+    check(as64(skips[0]), s_ref[0], dtype, "stage skip 1")
+    check(as64(skips[1]), s_ref[1], dtype, "stage skip 2")
+    gp = to_dev(S.normal(rg, pooled.shape), dtype)
+    gs = [to_dev(S.normal(rg, s.shape), dtype) for s in skips]
+    grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in sp]
+    L.lamp_unet_stage_bwd(ud, 1, 2, sp, x, skips, gp, gs, grads, ws)
+    # the same backward replayed layer by layer (each layer verified), then bitwise comparison
+    cg = {}
+    g = gp
+    for l in (2, 1):
+        c1, c2 = ch.enc[l]
+        gy = torch.empty(c2["y"].shape, dtype=dtype, device=DEV)
+        L.lamp_maxpool2_bwd(c2["y"], g, gy, add=gs[l - 1])
+        np.testing.assert_allclose(as64(gy), O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(gs[l - 1]), rtol=2 ** -8, atol=1e-30)
+        g = ch.conv_bwd(c2, gy, cg, True)
+        g = ch.conv_bwd(c1, g, cg, l > 1)
+    for k, gr in zip(names[:4], grads):
+        assert torch.equal(gr, cg[k]), f"stage grad {k} differs from the chain"
+    g_ref, _ = unet.stage_backward(ora, cache, as64(gp), [as64(t) for t in gs], 1, 2, levels, store=O.round_bf16)
+    for k, gr in zip(names[:4], grads):
+        a, b = as64(gr).ravel(), g_ref[k].ravel()
+        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
+        assert cos > 0.95, f"stage grad {k}: cosine {cos:.3f}"
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+def test_sliding_window_vs_oracle(L, dtype):
+    levels, base, K, P = 2, 8 if dtype == F32 else 32, 3, 8
+    D, H, W = 20, 8, 12
+    names, dev, ora = make_net(levels, base, 1, K, False, dtype, 11)
+    vol = to_dev(S.ct_volume(S.streams(12, 1)[0], 1, D, H, W), dtype)
+    cnt = L.lamp_sliding_window_count(D, H, W, P, 0.25)
+    assert cnt == len(sliding.window_starts(D, P)) * len(sliding.window_starts(H, P)) * len(sliding.window_starts(W, P)) == 6
+    pd = L.unet_desc(levels, base, 1, K, cnt, P, P, P, dtype)
+    out = torch.empty((1, D, H, W, K), dtype=F32, device=DEV)
+    L.lamp_sliding_window_fwd(pd, dev, vol, out)
+    store = O.round_bf16 if dtype == BF else (lambda a: a)
+    ref = sliding.sliding_window(lambda win: unet.forward(ora, win, levels, store=store)[0], as64(vol), patch=P)
+    check(as64(out), ref, dtype, "sliding-window logits")
