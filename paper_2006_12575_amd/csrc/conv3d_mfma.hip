@@ -375,9 +375,266 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     return LAMP_OK;
 }
 
-bool mfma_wgrad_supported(const lamp_tensor_desc*, const lamp_tensor_desc*, const lamp_norm_in*) { return false; }
-size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc*, const lamp_tensor_desc*) { return 0; }
-lamp_status mfma_wgrad(const lamp_tensor_desc*, const void*, const lamp_tensor_desc*, const void*, float*, float, void*,
-                       size_t, hipStream_t) { return LAMP_ERR_UNSUPPORTED; }
+// ------------------------------------------------------------------------------------------------
+// Weight gradient:  dW[co][tap][ci] = sum_v dz[v][co] * x[v + tap][ci]
+//
+// GEMM view: M = co (A = dz^T), N = ci (B = x shifted by the tap), K = voxels.  Both operands are
+// needed K-major per lane but live channel-major (NDHWC) in LDS, so fragments are read with the
+// transposing LDS load (ds_read_b64_tr_b16): inside each 16-lane group, source lane s supplies
+// 4 channels of voxel row s/4 and lane t receives channel t of 4 consecutive voxel rows.
+// A workgroup (8 waves) owns one 32-wide ci block and 32*COB output channels for all 27 taps, the
+// taps dealt round-robin to the waves (<= 4 each, accumulators 2*4*16 registers), and walks a
+// contiguous range of 2 x 8 x 16 voxel tiles, accumulating in registers; tiles are double
+// buffered in LDS.  Per-workgroup partials are summed by a second, fixed-order kernel.
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+
+static constexpr int WTD = 2, WTH = 8, WTW = 16;
+static constexpr int WHD = WTD + 2, WHH = WTH + 2, WHW = WTW + 2;
+static constexpr int WTILE_VOX = WTD * WTH * WTW;             // 256
+static constexpr int WX_VOX = WHD * WHH * WHW;                // 720
+static constexpr int WX_BYTES = WX_VOX * 64;                  // 32 ci per row
+static constexpr int WDZ_HALF_BYTES = WTILE_VOX * 64;         // one 32-co half, 64-byte rows
+static constexpr int WBUF_STAGE = WX_BYTES + 2 * WDZ_HALF_BYTES;  // 78848
+static constexpr int WG_LDS_BYTES = 2 * WBUF_STAGE;           // 157696
+
+struct WgradArgs {
+    const bf16_t* x; int ldx;
+    const bf16_t* dz; int lddz;
+    float* part;  // [S][Cout][27][Cin]
+    int N, D, H, W, Cin, Cout;
+    int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_wg;
+};
+
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
+    // two transposing loads: voxel rows +0..3 and +4..7 (4 rows of 64 bytes further on)
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 256));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int COB>
+__global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int ci0 = blockIdx.y * 32, co0 = blockIdx.z * (32 * COB);
+    const int tile_lo = blockIdx.x * a.tiles_per_wg;
+    const int tile_hi = min(tile_lo + a.tiles_per_wg, a.tiles_total);
+
+    // taps of this wave: wv, wv+8, wv+16, wv+24 (the last only for waves 0..2)
+    uint32_t tapoff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = wv + 8 * i;
+        const int kd = t / 9, kh = (t / 3) % 3, kw = t % 3;
+        tapoff[i] = (uint32_t)(((kd * WHH + kh) * WHW + kw) * 64);
+    }
+    const bool has4 = wv + 24 < 27;
+
+    // lane part of a transposing fragment read: voxel row 8*(b/2) + s/4, channel bytes 32*(b%2) + 8*(s%4)
+    const int b16 = lane >> 4, s16 = lane & 15;
+    const uint32_t loff = (uint32_t)((8 * (b16 >> 1) + (s16 >> 2)) * 64 + 32 * (b16 & 1) + 8 * (s16 & 3));
+
+    f32x16 acc[COB][4];
+#pragma unroll
+    for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][i][r] = 0.f;
+
+    // ---- staging: 16-byte pieces.  dz: 256 voxels x (4*COB) pieces ; x: 720 voxels x 4 pieces
+    constexpr int DZ_PIECES = WTILE_VOX * 4 * COB;
+    constexpr int DZ_ITERS = DZ_PIECES / 512;          // 4 (COB=2) or 2
+    constexpr int X_PIECES = WX_VOX * 4;               // 2880
+    constexpr int X_ITERS = (X_PIECES + 511) / 512;    // 6
+    auto tile_coords = [&](int tile, int& n, int& d0, int& h0, int& w0) {
+        n = tile / a.tiles_per_n;
+        int r = tile - n * a.tiles_per_n;
+        w0 = (r % a.tiles_w) * WTW;
+        r /= a.tiles_w;
+        h0 = (r % a.tiles_h) * WTH;
+        d0 = (r / a.tiles_h) * WTD;
+    };
+    auto dz_load = [&](int i, int tile, uint4& v) {
+        const int p = tid + i * 512;
+        const int part = p % (4 * COB), vx = p / (4 * COB);
+        const int w = vx % WTW, h = (vx / WTW) % WTH, d = vx / (WTW * WTH);
+        int n, d0, h0, w0;
+        tile_coords(tile, n, d0, h0, w0);
+        const int gd = d0 + d, gh = h0 + h, gw = w0 + w;
+        v = make_uint4(0, 0, 0, 0);
+        if (gd < a.D && gh < a.H && gw < a.W)
+            v = *reinterpret_cast<const uint4*>(a.dz + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.lddz + co0 + part * 8);
+    };
+    auto dz_store = [&](int i, char* st, const uint4& v) {
+        const int p = tid + i * 512;
+        const int part = p % (4 * COB), vx = p / (4 * COB);
+        // 32-co half (part / 4) in its own array of 64-byte rows
+        *reinterpret_cast<uint4*>(st + WX_BYTES + (part >> 2) * WDZ_HALF_BYTES + vx * 64 + (part & 3) * 16) = v;
+    };
+    auto x_load = [&](int i, int tile, uint4& v) {
+        const int p = tid + i * 512;
+        v = make_uint4(0, 0, 0, 0);
+        if (p < X_PIECES) {
+            const int part = p & 3, hv = p >> 2;
+            const int hw = hv % WHW, hh = (hv / WHW) % WHH, hd = hv / (WHW * WHH);
+            int n, d0, h0, w0;
+            tile_coords(tile, n, d0, h0, w0);
+            const int gd = d0 + hd - 1, gh = h0 + hh - 1, gw = w0 + hw - 1;
+            if (gd >= 0 && gd < a.D && gh >= 0 && gh < a.H && gw >= 0 && gw < a.W)
+                v = *reinterpret_cast<const uint4*>(a.x + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldx + ci0 + part * 8);
+        }
+    };
+    auto x_store = [&](int i, char* st, const uint4& v) {
+        const int p = tid + i * 512;
+        if (p < X_PIECES) *reinterpret_cast<uint4*>(st + (p >> 2) * 64 + (p & 3) * 16) = v;
+    };
+
+    if (tile_lo < tile_hi) {
+        // prologue: first tile synchronously
+        for (int i = 0; i < DZ_ITERS; ++i) { uint4 v; dz_load(i, tile_lo, v); dz_store(i, lds, v); }
+        for (int i = 0; i < X_ITERS; ++i) { uint4 v; x_load(i, tile_lo, v); x_store(i, lds, v); }
+    }
+    __syncthreads();
+
+    int par = 0;
+    for (int tile = tile_lo; tile < tile_hi; ++tile, par ^= 1) {
+        const char* st = lds + par * WBUF_STAGE;
+        char* st_next = lds + (par ^ 1) * WBUF_STAGE;
+        const bool pf = tile + 1 < tile_hi;
+        const char* xb = st + loff;
+        const char* dzb = st + WX_BYTES + loff;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            // first half of the k-steps carries the dz prefetch, second half the x prefetch
+            uint4 pv[X_ITERS];
+            if (pf) {
+                if (hf == 0) {
+#pragma unroll
+                    for (int i = 0; i < DZ_ITERS; ++i) dz_load(i, tile + 1, pv[i]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < X_ITERS; ++i) x_load(i, tile + 1, pv[i]);
+                }
+            }
+#pragma unroll
+            for (int k8 = 0; k8 < 8; ++k8) {
+                const int ks = hf * 8 + k8;            // k-step = one 16-voxel w-row: d = ks/8, h = ks%8
+                const int d = ks >> 3, h = ks & 7;
+                bf16x8 af[COB], bfr[4];
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb) af[cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
+                const uint32_t rowoff = (uint32_t)((d * WHH + h) * WHW * 64);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) bfr[i] = lds_frag_tr(xb + rowoff + tapoff[i]);
+                if (has4) bfr[3] = lds_frag_tr(xb + rowoff + tapoff[3]);
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+#pragma unroll
+                    for (int cb = 0; cb < COB; ++cb)
+                        acc[cb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb], bfr[i], acc[cb][i], 0, 0, 0);
+                if (has4) {
+#pragma unroll
+                    for (int cb = 0; cb < COB; ++cb)
+                        acc[cb][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb], bfr[3], acc[cb][3], 0, 0, 0);
+                }
+            }
+            if (pf) {
+                if (hf == 0) {
+#pragma unroll
+                    for (int i = 0; i < DZ_ITERS; ++i) dz_store(i, st_next, pv[i]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < X_ITERS; ++i) x_store(i, st_next, pv[i]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- write this workgroup's partial: part[slot][co][tap][ci]
+    float* pb = a.part + (int64_t)blockIdx.x * a.Cout * 27 * a.Cin;
+    const int l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = wv + 8 * i;
+        if (t < 27) {
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int co = co0 + cb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    pb[((int64_t)co * 27 + t) * a.Cin + ci0 + l32] = acc[cb][i][r];
+                }
+        }
+    }
+}
+
+static void wtile_dims(const lamp_tensor_desc* t, int& td, int& th, int& tw) {
+    td = (t->d + WTD - 1) / WTD; th = (t->h + WTH - 1) / WTH; tw = (t->w + WTW - 1) / WTW;
+}
+
+static int wgrad_slots(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
+    int td, th, tw;
+    wtile_dims(xd, td, th, tw);
+    const int64_t tiles = (int64_t)td * th * tw * xd->n;
+    const int cob = (dzd->c % 64 == 0) ? 2 : 1;
+    const int types = (xd->c / 32) * (dzd->c / (32 * cob));
+    int64_t s = 256 / types;
+    if (s < 1) s = 1;
+    if (s >= 8) s = s / 8 * 8;  // keep the types of one tile range on one XCD
+    if (s > tiles) s = tiles;
+    return (int)s;
+}
+
+bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm) {
+    if (xd->dtype != LAMP_BF16) return false;
+    if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
+    if (xd->c % 32 || dzd->c % 32 || xd->ldc % 8 || dzd->ldc % 8) return false;
+    return true;
+}
+
+size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
+    if (!mfma_wgrad_supported(xd, dzd, nullptr)) return 0;
+    return align_up((size_t)wgrad_slots(xd, dzd) * dzd->c * 27 * xd->c * sizeof(float));
+}
+
+lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz, float* dw,
+                       float beta, void* ws, size_t ws_bytes, hipStream_t s) {
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)dz) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if (ws_bytes < mfma_wgrad_ws_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
+    WgradArgs a;
+    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dz = (const bf16_t*)dz; a.lddz = dzd->ldc; a.part = (float*)ws;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Cin = xd->c; a.Cout = dzd->c;
+    wtile_dims(xd, a.tiles_d, a.tiles_h, a.tiles_w);
+    a.tiles_per_n = a.tiles_d * a.tiles_h * a.tiles_w;
+    a.tiles_total = a.tiles_per_n * xd->n;
+    const int S = wgrad_slots(xd, dzd);
+    a.tiles_per_wg = (a.tiles_total + S - 1) / S;
+    const int cob = (dzd->c % 64 == 0) ? 2 : 1;
+    dim3 grid(S, xd->c / 32, dzd->c / (32 * cob));
+    static bool attr_done[2] = {false, false};
+    if (cob == 2) {
+        if (!attr_done[1]) {
+            if (hipFuncSetAttribute((const void*)conv3d_wgrad_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_BYTES) != hipSuccess)
+                return LAMP_ERR_HIP;
+            attr_done[1] = true;
+        }
+        hipLaunchKernelGGL((conv3d_wgrad_kernel<2>), grid, dim3(512), WG_LDS_BYTES, s, a);
+    } else {
+        if (!attr_done[0]) {
+            if (hipFuncSetAttribute((const void*)conv3d_wgrad_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_BYTES) != hipSuccess)
+                return LAMP_ERR_HIP;
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL((conv3d_wgrad_kernel<1>), grid, dim3(512), WG_LDS_BYTES, s, a);
+    }
+    LAMP_CHECK_LAUNCH();
+    return launch_reduce_partials((const float*)ws, S, (int64_t)dzd->c * 27 * xd->c, dw, beta, s);
+}
 
 }  // namespace lamp
