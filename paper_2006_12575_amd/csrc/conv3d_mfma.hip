@@ -4,14 +4,15 @@
 // spatially flipped taps and swapped channel roles, done by the weight repack).
 //
 // GEMM view per workgroup tile:  D[co][voxel] += sum_{tap, ci} Wp[tap][co][ci] * X[voxel + tap][ci]
-//   M = 32*COB output channels (A operand = weights), N = 512 voxels (B operand = activations),
-//   K = 27 taps x Cin, walked as (Cin chunk of 32) x (9 tap groups of 3) x (2 k-steps of 16).
-// Tile: 4 x 8 x 16 output voxels (d,h,w); wave w of the 4 owns d-slice w = 4 blocks of 32 voxels
-// (2 h-rows x 16 w), so a 16-lane group always reads 16 consecutive halo voxels from LDS.
-// LDS: two halo buffers (6 x 10 x 18 voxels x 32 channels, 64-byte rows, XOR-swizzled 16-byte parts)
-// so the next chunk / next tile streams in while the current one is multiplied, and two small
-// weight buffers (3 taps x 64 co x 32 ci).  Workgroups are persistent and walk an XCD-contiguous
-// range of tiles.
+//   M = 32*COB output channels (A operand = weights), N = 1024 voxels (B operand = activations),
+//   K = 27 taps x Cin, walked as (Cin chunk of 16 = one MFMA k-step) x (3 kd groups) x (9 taps).
+// Tile: 8 x 8 x 16 output voxels (d,h,w); 8 waves (2 per SIMD), wave w owns d-slice w = 4 blocks
+// of 32 voxels (2 h-rows x 16 w), so a 16-lane group always reads 16 consecutive halo voxels.
+// LDS holds a halo chunk as two planes (channels 0-7 / 8-15 of the chunk) of 16-byte voxel
+// entries: every fragment read is a conflict-free 16-byte load at lane base + immediate offset.
+// Two halo buffers (10 x 10 x 18 voxels) let the next chunk / next tile stream in while the
+// current one is multiplied; two weight buffers hold one kd group (9 taps x 64 co x 16 ci) each.
+// Workgroups are persistent and walk an XCD-contiguous range of tiles.
 #include "internal.h"
 
 namespace lamp {
@@ -19,17 +20,16 @@ namespace lamp {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-static constexpr int TD = 4, TH = 8, TW = 16;
+static constexpr int TD = 8, TH = 8, TW = 16;
 static constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
-static constexpr int HALO_VOX = HD * HH * HW;          // 1080
-static constexpr int HALO_BYTES = HALO_VOX * 64;       // one 32-channel chunk
-static constexpr int HALO_PIECES = HALO_VOX * 4;       // 16-byte pieces
-static constexpr int HALO_ITERS = (HALO_PIECES + 255) / 256;  // 17
-static constexpr int PIECES_PER_GROUP = 2;             // 9 groups x 2 >= 17
-static constexpr int WBUF_BYTES = 3 * 64 * 64;         // 3 taps x 64 co x 32 ci bf16
-static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES;
-
-__device__ __forceinline__ uint32_t swz(uint32_t row) { return (row >> 2) & 3u; }
+static constexpr int HALO_VOX = HD * HH * HW;              // 1800
+static constexpr int PLANE_BYTES = HALO_VOX * 16;          // 8 channels per voxel entry
+static constexpr int HALO_BYTES = 2 * PLANE_BYTES;         // one 16-channel chunk: 57600
+static constexpr int HALO_PIECES = HALO_VOX * 2;           // 16-byte pieces
+static constexpr int HALO_ITERS = (HALO_PIECES + 511) / 512;  // 8
+static constexpr int WPLANE_BYTES = 64 * 16;               // 64 co rows of 16 bytes
+static constexpr int WBUF_BYTES = 9 * 2 * WPLANE_BYTES;    // one kd group: 18432
+static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES;  // 152064
 
 __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
     uint4 q = *reinterpret_cast<const uint4*>(p);
@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const bf16_t* __res
                                                              int Cout, int Cin, int dgrad) {
     const int64_t total = (int64_t)27 * Cout * Cin;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < 8) wp[total + i] = 0;  // 16 zero bytes behind the weights: the source of the zero padding
     if (i >= total) return;
     const int ic = (int)(i % Cin);
     const int oc = (int)((i / Cin) % Cout);
@@ -53,94 +54,96 @@ struct ConvArgs {
     const bf16_t* wp;
     bf16_t* z; int ldz;
     float* part;        // [N][tiles_per_n][Cout][2] or nullptr
+    int32_t* counts;    // [tiles_per_n] in-volume voxels per tile (written when part != nullptr)
+    const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
 };
 
+// 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
+// (lds_base must be wave-uniform); inactive lanes write nothing.
+__device__ __forceinline__ void g2lds16(const void* g, char* lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
 template <int COB>
-__global__ __launch_bounds__(256) void conv3d_igemm_kernel(ConvArgs a) {
+__global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* hbuf0 = lds;
     char* wbuf0 = lds + 2 * HALO_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int co0 = blockIdx.y * (32 * COB);
-    const int nchunks = a.Cin >> 5;
+    const int nchunks = a.Cin >> 4;
+    constexpr int WROWS = 32 * COB;
+    constexpr int WPLANE = WROWS * 16;            // one (tap, plane): WROWS rows of 16 bytes
+    constexpr int WENTRIES = 18;                  // 9 taps x 2 planes per kd group
+    constexpr int WINSTR = WENTRIES * WROWS / 64; // wave-wide copies per group: 18 or 9
 
     // persistent walk over an XCD-contiguous range of tiles
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
     const int tile_lo = xcd * a.tiles_per_xcd;
     const int tile_hi = min(tile_lo + a.tiles_per_xcd, a.tiles_total);
 
-    // ---- per-lane constants of the fragment reads
-    // A (weights): row = co within the 64-row buffer; part = ks*2 + half
-    uint32_t a_off[2];
-    {
-        const uint32_t s = swz((uint32_t)l32);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) a_off[ks] = (uint32_t)l32 * 64u + ((((uint32_t)(ks * 2 + half)) ^ s) << 4);
-    }
-    // B (activations): halo row of this lane's voxel in block vb, tap (0,0,0)
-    const int bw = l32 & 15, bh = l32 >> 4;
-    const uint32_t hv_base = (uint32_t)((wv * HH + bh) * HW + bw);
+    // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read is serviced
+    // for lanes {0-7,24-31}, {8-15,16-23} (and the same in the upper half) together, so those
+    // pairs must fall into opposite 128-byte halves of the bank space: groups of 8 lanes take
+    // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15).
+    const int g8 = l32 >> 3;
+    const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
+    const uint32_t b_base = (uint32_t)(half * PLANE_BYTES + ((wv * HH + bh) * HW + bw) * 16);
+    const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
-    // ---- staging helpers
-    auto halo_piece_load = [&](int p, int tile, int chunk, uint4& v) {
-        v = make_uint4(0, 0, 0, 0);
-        if (p < HALO_PIECES) {
-            const int hv = p >> 2, part = p & 3;
-            const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
-            const int n = tile / a.tiles_per_n;
-            int r = tile - n * a.tiles_per_n;
-            const int tw = r % a.tiles_w;
-            r /= a.tiles_w;
-            const int th = r % a.tiles_h, tdd = r / a.tiles_h;
-            const int gd = tdd * TD + hd - 1, gh = th * TH + hh - 1, gw = tw * TW + hw - 1;
-            if (gd >= 0 && gd < a.D && gh >= 0 && gh < a.H && gw >= 0 && gw < a.W) {
-                const bf16_t* src = a.x + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldx + chunk * 32 + part * 8;
-                v = *reinterpret_cast<const uint4*>(src);
+    // ---- staging: register-free global -> LDS copies, one 1-KiB row of 64 entries per wave copy
+    auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
+        n = tile / a.tiles_per_n;
+        int r = tile - n * a.tiles_per_n;
+        w0 = (r % a.tiles_w) * TW;
+        r /= a.tiles_w;
+        h0 = (r % a.tiles_h) * TH;
+        d0 = (r / a.tiles_h) * TD;
+    };
+    // halo copy q of a chunk: plane q / 29, voxels (q % 29)*64 .. +63
+    constexpr int HBLK = (HALO_VOX + 63) / 64;   // 29
+    constexpr int HCOPIES = 2 * HBLK;            // 58, dealt to the 8 waves: q = wv + 8*i, i < 8
+    auto halo_copy = [&](int i, int tile, int chunk, char* hb) {
+        const int q = wv + 8 * i;
+        if (q < HCOPIES) {
+            const int plane = q / HBLK, blk = q - plane * HBLK;
+            const int hv = blk * 64 + lane;
+            if (hv < HALO_VOX) {
+                const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
+                int n, d0, h0, w0;
+                tile_origin(tile, n, d0, h0, w0);
+                const int gd = d0 + hd - 1, gh = h0 + hh - 1, gw = w0 + hw - 1;
+                const bf16_t* src = a.zero16;
+                if (gd >= 0 && gd < a.D && gh >= 0 && gh < a.H && gw >= 0 && gw < a.W)
+                    src = a.x + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldx + chunk * 16 + plane * 8;
+                g2lds16(src, hb + plane * PLANE_BYTES + blk * 1024);
             }
         }
     };
-    auto halo_piece_store = [&](int p, char* hb, const uint4& v) {
-        if (p < HALO_PIECES) {
-            const uint32_t hv = (uint32_t)p >> 2, part = (uint32_t)p & 3u;
-            *reinterpret_cast<uint4*>(hb + hv * 64u + ((part ^ swz(hv)) << 4)) = v;
+    // weight copy q of kd group g: 64 consecutive (entry,row) pairs; entry = tap9*2 + plane
+    auto w_copy = [&](int i, int g, int chunk, char* wb) {
+        const int q = wv + 8 * i;
+        if (q < WINSTR) {
+            const int er = q * 64 + lane;
+            const int entry = er / WROWS, row = er - entry * WROWS;
+            const int t9 = entry >> 1, plane = entry & 1;
+            const bf16_t* src = a.wp + ((int64_t)(9 * g + t9) * a.Cout + co0 + row) * a.Cin + chunk * 16 + plane * 8;
+            g2lds16(src, wb + q * 1024);
         }
     };
-    // weights of tap group g (taps 3g..3g+2) of a chunk: 3 x (32*COB) rows x 4 parts
-    constexpr int WPIECES = 3 * 32 * COB * 4;
-    constexpr int WITERS = (WPIECES + 255) / 256;
-    auto w_piece_load = [&](int i, int g, int chunk, uint4& v) {
-        const int p = tid + i * 256;
-        if (p < WPIECES) {
-            const int part = p & 3, row = (p >> 2) % (32 * COB), t = p / (4 * 32 * COB);
-            const bf16_t* src = a.wp + ((int64_t)(3 * g + t) * a.Cout + co0 + row) * a.Cin + chunk * 32 + part * 8;
-            v = *reinterpret_cast<const uint4*>(src);
-        }
-    };
-    auto w_piece_store = [&](int i, char* wb, const uint4& v) {
-        const int p = tid + i * 256;
-        if (p < WPIECES) {
-            const uint32_t part = p & 3, row = (p >> 2) % (32 * COB), t = p / (4 * 32 * COB);
-            *reinterpret_cast<uint4*>(wb + (t * 64u + row) * 64u + ((part ^ swz(row)) << 4)) = v;
-        }
-    };
+    constexpr int WCOPY_ITERS = (WINSTR + 7) / 8;  // 3 or 2
 
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
 
-    // ---- prologue: first halo chunk and first weight group, synchronously
-    for (int i = 0; i < HALO_ITERS; ++i) {
-        uint4 v;
-        halo_piece_load(tid + i * 256, tile, 0, v);
-        halo_piece_store(tid + i * 256, hbuf0, v);
-    }
-    for (int i = 0; i < WITERS; ++i) {
-        uint4 v;
-        w_piece_load(i, 0, 0, v);
-        w_piece_store(i, wbuf0, v);
-    }
+    // ---- prologue: first halo chunk and first weight group
+    for (int i = 0; i < 8; ++i) halo_copy(i, tile, 0, hbuf0);
+    for (int i = 0; i < WCOPY_ITERS; ++i) w_copy(i, 0, 0, wbuf0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     int stage = 0;  // parity selects the halo buffer
@@ -156,88 +159,84 @@ __global__ __launch_bounds__(256) void conv3d_igemm_kernel(ConvArgs a) {
 
         const int next_tile = tile + wg_per_xcd;
         for (int chunk = 0; chunk < nchunks; ++chunk, ++stage) {
-            const char* hb = hbuf0 + (stage & 1) * HALO_BYTES;
+            const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
             char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
             // what streams in during this stage
             const bool last_chunk = chunk + 1 == nchunks;
             const int pf_tile = last_chunk ? next_tile : tile;
             const int pf_chunk = last_chunk ? 0 : chunk + 1;
             const bool pf = !last_chunk || next_tile < tile_hi;
-#pragma unroll 1
-            for (int g = 0; g < 9; ++g, wpar ^= 1) {
-                const char* wb = wbuf0 + wpar * WBUF_BYTES;
+#pragma unroll
+            for (int g = 0; g < 3; ++g, wpar ^= 1) {
+                const char* wb = wbuf0 + wpar * WBUF_BYTES + a_base;
                 char* wb_next = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
-                // issue the global loads of this group's share of the prefetch
-                uint4 hp[PIECES_PER_GROUP], wpv[WITERS];
+                // this group's share of the prefetch: 3 + 3 + 2 halo copies, the next weight group
                 if (pf) {
 #pragma unroll
-                    for (int i = 0; i < PIECES_PER_GROUP; ++i)
-                        halo_piece_load(tid + (g * PIECES_PER_GROUP + i) * 256, pf_tile, pf_chunk, hp[i]);
+                    for (int i = 0; i < 3; ++i)
+                        if (g * 3 + i < 8) halo_copy(g * 3 + i, pf_tile, pf_chunk, hb_next);
                 }
-                // next weight group: (chunk, g+1), or (next stage, 0)
-                const bool wlast = g == 8;
-                const bool wpf = !wlast || pf;
-                if (wpf) {
+                const bool wlast = g == 2;
+                if (!wlast || pf) {
 #pragma unroll
-                    for (int i = 0; i < WITERS; ++i) w_piece_load(i, wlast ? 0 : g + 1, wlast ? pf_chunk : chunk, wpv[i]);
+                    for (int i = 0; i < WCOPY_ITERS; ++i) w_copy(i, wlast ? 0 : g + 1, wlast ? pf_chunk : chunk, wb_next);
                 }
-                // ---- multiply: 3 taps x 2 k-steps
-                const int kd = g / 3, kh = g - 3 * kd;
+                // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched
+                // while tap t is multiplied
+                bf16x8 af[2][COB], bfr[2][4];
+                auto load_frags = [&](int t9, int slot) {
+                    const int kh = t9 / 3, kw = t9 - 3 * kh;
+                    const int tapoff = ((g * HH + kh) * HW + kw) * 16;
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
-                    const uint32_t tapoff = (uint32_t)(kd * HH * HW + kh * HW + kw);
-                    bf16x8 af[COB][2], bfr[4][2];
+                    for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
+#pragma unroll
+                    for (int vb = 0; vb < 4; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
+                };
+                load_frags(0, 0);
+#pragma unroll
+                for (int t9 = 0; t9 < 9; ++t9) {
+                    if (t9 < 8) load_frags(t9 + 1, (t9 + 1) & 1);
 #pragma unroll
                     for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-                        for (int ks = 0; ks < 2; ++ks) af[cb][ks] = lds_frag(wb + (kw * 64 + cb * 32) * 64 + a_off[ks]);
+                        for (int vb = 0; vb < 4; ++vb)
+                            acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
+                    if (t9 < 8) {
+                        // interleave: one LDS read behind each MFMA while both last
+                        constexpr int NM = 4 * COB, NR = COB + 4, NP = NM < NR ? NM : NR;
 #pragma unroll
-                    for (int vb = 0; vb < 4; ++vb) {
-                        const uint32_t hv = hv_base + (uint32_t)(vb * 2 * HW) + tapoff;
-                        const uint32_t s = swz(hv);
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-                            bfr[vb][ks] = lds_frag(hb + hv * 64u + ((((uint32_t)(ks * 2 + half)) ^ s) << 4));
+                        for (int k = 0; k < NP; ++k) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                        if (NM > NP) __builtin_amdgcn_sched_group_barrier(0x008, NM - NP, 0);
+                        if (NR > NP) __builtin_amdgcn_sched_group_barrier(0x100, NR - NP, 0);
                     }
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                        for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-                            for (int vb = 0; vb < 4; ++vb)
-                                acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][ks], bfr[vb][ks], acc[cb][vb], 0, 0, 0);
                 }
-                // ---- land the prefetched pieces
-                if (pf) {
-#pragma unroll
-                    for (int i = 0; i < PIECES_PER_GROUP; ++i)
-                        halo_piece_store(tid + (g * PIECES_PER_GROUP + i) * 256, hb_next, hp[i]);
-                }
-                if (wpf) {
-#pragma unroll
-                    for (int i = 0; i < WITERS; ++i) w_piece_store(i, wb_next, wpv[i]);
-                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
             }
         }
 
-        // ---- epilogue: bf16 store of z and per-tile channel sums of the stored values
-        const int n = tile / a.tiles_per_n;
-        int r0 = tile - n * a.tiles_per_n;
-        const int tw = r0 % a.tiles_w;
-        r0 /= a.tiles_w;
-        const int th = r0 % a.tiles_h, tdd = r0 / a.tiles_h;
-        const int gd = tdd * TD + wv;
-        float ssum[COB][16], ssq[COB][16];
+        // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
+        // register group) into voxel rows through a private LDS patch, so that 8 lanes store one
+        // full row of 64 channels; the channel sums of the stored values come from the same pass.
+        // Scratch: the halo buffer of the stage just finished (free until the next prefetch).
+        int n, d0, h0, w0;
+        tile_origin(tile, n, d0, h0, w0);
+        const int gd = d0 + wv;
+        char* fbuf = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
+        constexpr int ROWB = WROWS * 2 + 16;          // padded row of the patch
+        constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
+        constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
+        char* patch = fbuf + wv * (32 * ROWB);
+        float* sred = reinterpret_cast<float*>(fbuf + 8 * 32 * (64 * 2 + 16));
+        const int part = lane % PARTS, prow = lane / PARTS;
+        float csum[8], csq[8];
 #pragma unroll
-        for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { ssum[cb][r] = 0.f; ssq[cb][r] = 0.f; }
+        for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; }
 #pragma unroll
         for (int vb = 0; vb < 4; ++vb) {
-            const int gh = th * TH + vb * 2 + bh, gw = tw * TW + bw;
-            const bool ok = gd < a.D && gh < a.H && gw < a.W;
-            bf16_t* zp = a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + 4 * half;
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
@@ -245,54 +244,63 @@ __global__ __launch_bounds__(256) void conv3d_igemm_kernel(ConvArgs a) {
                     uint32_t pk[2];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const bf16_t b = f2bf(acc[cb][vb][rg * 4 + e]);
-                        const float fv = ok ? bf2f(b) : 0.f;
-                        ssum[cb][rg * 4 + e] += fv;
-                        ssq[cb][rg * 4 + e] = fmaf(fv, fv, ssq[cb][rg * 4 + e]);
-                        if (e & 1) pk[e >> 1] |= ((uint32_t)b) << 16; else pk[e >> 1] = b;
+                        const uint32_t b = f2bf(acc[cb][vb][rg * 4 + e]);
+                        if (e & 1) pk[e >> 1] |= b << 16; else pk[e >> 1] = b;
                     }
-                    if (ok) *reinterpret_cast<uint2*>(zp + cb * 32 + rg * 8) = make_uint2(pk[0], pk[1]);
+                    *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(pk[0], pk[1]);
                 }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
+                const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
+                const int rg8 = row >> 3;
+                const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
+                const int gh = h0 + vb * 2 + rh, gw = w0 + rw;
+                const bool ok = gd < a.D && gh < a.H && gw < a.W;
+                if (ok) {
+                    *reinterpret_cast<uint4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8) = q;
+                    const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
+                        csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
+                        csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
         }
         if (a.part) {
-            // reduce over the 32 lanes that share `half` (xor 1,2,4,8,16), then across the 4 waves
-            // scratch: the halo buffer of the stage just finished (free until the next stage's prefetch)
-            float* sred = reinterpret_cast<float*>(hbuf0 + ((stage + 1) & 1) * HALO_BYTES);
+            // lanes with equal `part` hold the same 8 channels: fold them (lane bits above log2(PARTS))
 #pragma unroll
-            for (int cb = 0; cb < COB; ++cb)
+            for (int e = 0; e < 8; ++e) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float s = ssum[cb][r], q = ssq[cb][r];
-#pragma unroll
-                    for (int m = 1; m < 32; m <<= 1) {
-                        s += __shfl_xor(s, m);
-                        q += __shfl_xor(q, m);
-                    }
-                    if (l32 == 0) {
-                        const int c = cb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                        sred[(wv * 64 + c) * 2 + 0] = s;
-                        sred[(wv * 64 + c) * 2 + 1] = q;
-                    }
+                for (int m = PARTS; m < 64; m <<= 1) {
+                    csum[e] += __shfl_xor(csum[e], m);
+                    csq[e] += __shfl_xor(csq[e], m);
                 }
-            __syncthreads();
-            if (tid < 32 * COB * 2) {
-                const int c = tid >> 1, k = tid & 1;
-                const float v = sred[(0 * 64 + c) * 2 + k] + sred[(1 * 64 + c) * 2 + k] + sred[(2 * 64 + c) * 2 + k] +
-                                sred[(3 * 64 + c) * 2 + k];
-                a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
+            }
+            if (lane < PARTS) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    sred[(wv * 64 + part * 8 + e) * 2 + 0] = csum[e];
+                    sred[(wv * 64 + part * 8 + e) * 2 + 1] = csq[e];
+                }
             }
             __syncthreads();
+            if (tid < WROWS * 2) {
+                const int c = tid >> 1, k = tid & 1;
+                float v = 0.f;
+#pragma unroll
+                for (int w8 = 0; w8 < 8; ++w8) v += sred[(w8 * 64 + c) * 2 + k];
+                a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
+            }
+            if (a.counts && tid == 0 && n == 0 && blockIdx.y == 0)
+                a.counts[tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
         }
+        __syncthreads();  // the patch buffer is the next stage's prefetch target
     }
-}
-
-// counts[p] = voxels of tile p that lie inside the volume (same for every sample)
-__global__ void tile_counts_kernel(int32_t* counts, int D, int H, int W, int tiles_d, int tiles_h, int tiles_w) {
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= tiles_d * tiles_h * tiles_w) return;
-    const int tw = p % tiles_w, th = (p / tiles_w) % tiles_h, tdd = p / (tiles_w * tiles_h);
-    const int d = min(TD, D - tdd * TD), h = min(TH, H - th * TH), w = min(TW, W - tw * TW);
-    counts[p] = d * h * w;
 }
 
 static void tile_dims(const lamp_tensor_desc* t, int& td, int& th, int& tw) {
@@ -304,7 +312,7 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
     if (xd->dtype != LAMP_BF16) return false;
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
     if (bias) return false;
-    if (xd->c % 32 || zd->c % 32 || xd->ldc % 8 || zd->ldc % 4) return false;
+    if (xd->c % 16 || zd->c % 32 || xd->ldc % 8 || zd->ldc % 8) return false;
     return true;
 }
 
@@ -313,7 +321,7 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     int td, th, tw;
     tile_dims(zd, td, th, tw);
     const size_t tiles = (size_t)td * th * tw;
-    size_t b = align_up((size_t)27 * xd->c * zd->c * 2);
+    size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 16);
     if (want_stats) b += align_up((size_t)zd->n * tiles * zd->c * 2 * sizeof(float)) + align_up(tiles * sizeof(int32_t));
     return b;
 }
@@ -321,12 +329,12 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
                           hipStream_t s) {
-    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 7u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
     int td, th, tw;
     tile_dims(zd, td, th, tw);
     const int tiles_per_n = td * th * tw;
     Carver cv(ws, ws_bytes);
-    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2);
+    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 16);
     float* part = nullptr;
     int32_t* counts = nullptr;
     if (stats_out) {
@@ -339,7 +347,8 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                        dgrad ? 1 : 0);
     LAMP_CHECK_LAUNCH();
     ConvArgs a;
-    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part;
+    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
+    a.zero16 = wp + (size_t)27 * xd->c * zd->c;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
     a.tiles_total = tiles_per_n * zd->n;
@@ -356,22 +365,17 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                 return LAMP_ERR_HIP;
             attr_done[1] = true;
         }
-        hipLaunchKernelGGL((conv3d_igemm_kernel<2>), grid, dim3(256), shm, s, a);
+        hipLaunchKernelGGL((conv3d_igemm_kernel<2>), grid, dim3(512), shm, s, a);
     } else {
         if (!attr_done[0]) {
             if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
                 return LAMP_ERR_HIP;
             attr_done[0] = true;
         }
-        hipLaunchKernelGGL((conv3d_igemm_kernel<1>), grid, dim3(256), shm, s, a);
+        hipLaunchKernelGGL((conv3d_igemm_kernel<1>), grid, dim3(512), shm, s, a);
     }
     LAMP_CHECK_LAUNCH();
-    if (stats_out) {
-        hipLaunchKernelGGL(tile_counts_kernel, dim3(cdiv(tiles_per_n, 256)), dim3(256), 0, s, counts, zd->d, zd->h, zd->w, td,
-                           th, tw);
-        LAMP_CHECK_LAUNCH();
-        return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);
-    }
+    if (stats_out) return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);
     return LAMP_OK;
 }
 
