@@ -67,6 +67,104 @@ __device__ __forceinline__ void g2lds16(const void* g, char* lds_base) {
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+static constexpr int HBLK = (HALO_VOX + 63) / 64;  // 29 wave-wide copies per halo plane
+
+// Per-lane constants of the halo copies.  A wave copies halo blocks wv, wv+8, wv+16, wv+24 (64
+// voxels each, both planes back to back so the two 16-byte halves of a voxel's 32 bytes meet in
+// the L1): rel = element offset of the voxel from the tile's halo origin, pk = its halo coords.
+struct HaloLane {
+    int rel[4];
+    int pk[4];
+};
+// Per-tile constants of the halo copies.
+struct HaloTile {
+    const bf16_t* origin;            // x at the halo origin (d0-1, h0-1, w0-1) of the tile (may be out of range)
+    int dlo, dhi, hlo, hhi, wlo, whi;  // halo coords inside the volume: lo <= c <= hi
+};
+
+// One kd group of one chunk: issue this group's share of the prefetch (weights of the next group
+// first, then halo blocks of the next chunk), multiply 9 taps, wait for the weight copies and
+// meet at the barrier.  The four LDS regions are distinct, and saying so (__restrict__) matters:
+// otherwise the compiler must assume the fragment reads alias the in-flight copies and waits for
+// them before the first read.
+//   HALO_FIRST, HALO_CNT : halo copy slots (block j = slot/2, plane = slot%2) issued in this group
+template <int COB, int G, int HALO_FIRST, int HALO_CNT>
+__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][4], const char* __restrict__ hb, const char* __restrict__ wb,
+                                           char* __restrict__ hb_next, char* __restrict__ wb_next, bool pf_halo,
+                                           bool pf_w, const HaloLane& hl, const HaloTile& ht, int pf_choff,
+                                           const bf16_t* zero16, const bf16_t* wsrc, const int (&wrel)[3], int wv,
+                                           int lane) {
+    constexpr int WROWS = 32 * COB;
+    constexpr int WPLANE = WROWS * 16;
+    constexpr int WINSTR = 18 * WROWS / 64;
+    constexpr int WCOPY_ITERS = (WINSTR + 7) / 8;
+    if (pf_w) {
+#pragma unroll
+        for (int i = 0; i < WCOPY_ITERS; ++i) {
+            const int q = wv + 8 * i;
+            if (q < WINSTR) g2lds16(wsrc + wrel[i], wb_next + q * 1024);
+        }
+    }
+    if (pf_halo) {
+#pragma unroll
+        for (int sl = HALO_FIRST; sl < HALO_FIRST + HALO_CNT; ++sl) {
+            const int j = sl >> 1, plane = sl & 1;
+            const int blk = wv + 8 * j;
+            if (blk < HBLK && blk * 64 + lane < HALO_VOX) {
+                const int pk = hl.pk[j];
+                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+                const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+                const bf16_t* src = in ? ht.origin + hl.rel[j] + pf_choff + plane * 8 : zero16;
+                g2lds16(src, hb_next + plane * PLANE_BYTES + blk * 1024);
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched while
+    // tap t is multiplied
+    bf16x8 af[2][COB], bfr[2][4];
+    auto load_frags = [&](int t9, int slot) {
+        const int kh = t9 / 3, kw = t9 - 3 * kh;
+        const int tapoff = ((G * HH + kh) * HW + kw) * 16;
+#pragma unroll
+        for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int t9 = 0; t9 < 9; ++t9) {
+        if (t9 < 8) load_frags(t9 + 1, (t9 + 1) & 1);
+#pragma unroll
+        for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb)
+                acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
+        if (t9 < 8) {
+            // interleave: one LDS read behind each MFMA while both last
+            constexpr int NM = 4 * COB, NR = COB + 4, NP = NM < NR ? NM : NR;
+#pragma unroll
+            for (int k = 0; k < NP; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            if (NM > NP) __builtin_amdgcn_sched_group_barrier(0x008, NM - NP, 0);
+            if (NR > NP) __builtin_amdgcn_sched_group_barrier(0x100, NR - NP, 0);
+        }
+    }
+    // The weight copies are older than this group's halo copies: leaving HALO_CNT copies in flight
+    // still guarantees the weights have landed.  (Every wave issues all HALO_CNT copies of groups
+    // 0 and 1; the last group drains everything because the next stage reads the halo.)
+    if (G < 2 && pf_halo) wait_vmcnt<(G < 2 ? HALO_CNT : 0)>();
+    else wait_vmcnt<0>();
+    // bare barrier: __syncthreads() would add a release fence that drains every copy in flight
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <int COB>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -78,8 +176,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const int nchunks = a.Cin >> 4;
     constexpr int WROWS = 32 * COB;
     constexpr int WPLANE = WROWS * 16;            // one (tap, plane): WROWS rows of 16 bytes
-    constexpr int WENTRIES = 18;                  // 9 taps x 2 planes per kd group
-    constexpr int WINSTR = WENTRIES * WROWS / 64; // wave-wide copies per group: 18 or 9
+    constexpr int WINSTR = 18 * WROWS / 64;       // wave-wide copies per kd group: 18 or 9
 
     // persistent walk over an XCD-contiguous range of tiles
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
@@ -95,7 +192,24 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const uint32_t b_base = (uint32_t)(half * PLANE_BYTES + ((wv * HH + bh) * HW + bw) * 16);
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
-    // ---- staging: register-free global -> LDS copies, one 1-KiB row of 64 entries per wave copy
+    // ---- per-lane constants of the register-free global -> LDS copies
+    HaloLane hl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int hv = (wv + 8 * j) * 64 + lane;
+        if (hv >= HALO_VOX) hv = 0;
+        const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
+        hl.rel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx;
+        hl.pk[j] = hd | (hh << 8) | (hw << 16);
+    }
+    // weight copy q = wv + 8*i of a kd group: 64 consecutive (entry,row) pairs, entry = tap9*2 + plane
+    int wrel[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int er = (wv + 8 * i) * 64 + lane;
+        const int entry = er / WROWS, row = er - entry * WROWS;
+        wrel[i] = ((entry >> 1) * a.Cout + row) * a.Cin + (entry & 1) * 8;
+    }
     auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
@@ -104,47 +218,39 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         h0 = (r % a.tiles_h) * TH;
         d0 = (r / a.tiles_h) * TD;
     };
-    // halo copy q of a chunk: plane q / 29, voxels (q % 29)*64 .. +63
-    constexpr int HBLK = (HALO_VOX + 63) / 64;   // 29
-    constexpr int HCOPIES = 2 * HBLK;            // 58, dealt to the 8 waves: q = wv + 8*i, i < 8
-    auto halo_copy = [&](int i, int tile, int chunk, char* hb) {
-        const int q = wv + 8 * i;
-        if (q < HCOPIES) {
-            const int plane = q / HBLK, blk = q - plane * HBLK;
-            const int hv = blk * 64 + lane;
-            if (hv < HALO_VOX) {
-                const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
-                int n, d0, h0, w0;
-                tile_origin(tile, n, d0, h0, w0);
-                const int gd = d0 + hd - 1, gh = h0 + hh - 1, gw = w0 + hw - 1;
-                const bf16_t* src = a.zero16;
-                if (gd >= 0 && gd < a.D && gh >= 0 && gh < a.H && gw >= 0 && gw < a.W)
-                    src = a.x + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldx + chunk * 16 + plane * 8;
-                g2lds16(src, hb + plane * PLANE_BYTES + blk * 1024);
-            }
-        }
+    auto halo_tile = [&](int tile) {
+        int n, d0, h0, w0;
+        tile_origin(tile, n, d0, h0, w0);
+        HaloTile t;
+        t.origin = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
+        t.dlo = 1 - d0; t.dhi = a.D - d0; t.hlo = 1 - h0; t.hhi = a.H - h0; t.wlo = 1 - w0; t.whi = a.W - w0;
+        return t;
     };
-    // weight copy q of kd group g: 64 consecutive (entry,row) pairs; entry = tap9*2 + plane
-    auto w_copy = [&](int i, int g, int chunk, char* wb) {
-        const int q = wv + 8 * i;
-        if (q < WINSTR) {
-            const int er = q * 64 + lane;
-            const int entry = er / WROWS, row = er - entry * WROWS;
-            const int t9 = entry >> 1, plane = entry & 1;
-            const bf16_t* src = a.wp + ((int64_t)(9 * g + t9) * a.Cout + co0 + row) * a.Cin + chunk * 16 + plane * 8;
-            g2lds16(src, wb + q * 1024);
-        }
-    };
-    constexpr int WCOPY_ITERS = (WINSTR + 7) / 8;  // 3 or 2
+    const bf16_t* wbase = a.wp + (int64_t)co0 * a.Cin;   // + (9*g*Cout)*Cin + chunk*16 per group
+    const int wgstride = 9 * a.Cout * a.Cin;
 
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
 
     // ---- prologue: first halo chunk and first weight group
-    for (int i = 0; i < 8; ++i) halo_copy(i, tile, 0, hbuf0);
-    for (int i = 0; i < WCOPY_ITERS; ++i) w_copy(i, 0, 0, wbuf0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    {
+        const HaloTile t0 = halo_tile(tile);
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+            const int j = sl >> 1, plane = sl & 1, blk = wv + 8 * j;
+            if (blk < HBLK && blk * 64 + lane < HALO_VOX) {
+                const int pk = hl.pk[j];
+                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+                const bool in = hd >= t0.dlo && hd <= t0.dhi && hh >= t0.hlo && hh <= t0.hhi && hw >= t0.wlo && hw <= t0.whi;
+                g2lds16(in ? t0.origin + hl.rel[j] + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (wv + 8 * i < WINSTR) g2lds16(wbase + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
 
     int stage = 0;  // parity selects the halo buffer
     int wpar = 0;   // parity selects the weight buffer
@@ -158,64 +264,29 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
 
         const int next_tile = tile + wg_per_xcd;
+        const HaloTile ht_cur = halo_tile(tile);
+        const HaloTile ht_next = halo_tile(next_tile < tile_hi ? next_tile : tile);
         for (int chunk = 0; chunk < nchunks; ++chunk, ++stage) {
             const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
             char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
-            // what streams in during this stage
+            // what streams in during this stage: the next chunk of this tile, or chunk 0 of the next
             const bool last_chunk = chunk + 1 == nchunks;
-            const int pf_tile = last_chunk ? next_tile : tile;
             const int pf_chunk = last_chunk ? 0 : chunk + 1;
             const bool pf = !last_chunk || next_tile < tile_hi;
-#pragma unroll
-            for (int g = 0; g < 3; ++g, wpar ^= 1) {
-                const char* wb = wbuf0 + wpar * WBUF_BYTES + a_base;
-                char* wb_next = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
-                // this group's share of the prefetch: 3 + 3 + 2 halo copies, the next weight group
-                if (pf) {
-#pragma unroll
-                    for (int i = 0; i < 3; ++i)
-                        if (g * 3 + i < 8) halo_copy(g * 3 + i, pf_tile, pf_chunk, hb_next);
-                }
-                const bool wlast = g == 2;
-                if (!wlast || pf) {
-#pragma unroll
-                    for (int i = 0; i < WCOPY_ITERS; ++i) w_copy(i, wlast ? 0 : g + 1, wlast ? pf_chunk : chunk, wb_next);
-                }
-                // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched
-                // while tap t is multiplied
-                bf16x8 af[2][COB], bfr[2][4];
-                auto load_frags = [&](int t9, int slot) {
-                    const int kh = t9 / 3, kw = t9 - 3 * kh;
-                    const int tapoff = ((g * HH + kh) * HW + kw) * 16;
-#pragma unroll
-                    for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
-#pragma unroll
-                    for (int vb = 0; vb < 4; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
-                };
-                load_frags(0, 0);
-#pragma unroll
-                for (int t9 = 0; t9 < 9; ++t9) {
-                    if (t9 < 8) load_frags(t9 + 1, (t9 + 1) & 1);
-#pragma unroll
-                    for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-                        for (int vb = 0; vb < 4; ++vb)
-                            acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
-                    if (t9 < 8) {
-                        // interleave: one LDS read behind each MFMA while both last
-                        constexpr int NM = 4 * COB, NR = COB + 4, NP = NM < NR ? NM : NR;
-#pragma unroll
-                        for (int k = 0; k < NP; ++k) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        }
-                        if (NM > NP) __builtin_amdgcn_sched_group_barrier(0x008, NM - NP, 0);
-                        if (NR > NP) __builtin_amdgcn_sched_group_barrier(0x100, NR - NP, 0);
-                    }
-                }
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-            }
+            const HaloTile& ht = last_chunk ? ht_next : ht_cur;
+            const char* w0p = wbuf0 + wpar * WBUF_BYTES + a_base;
+            const char* w1p = wbuf0 + (wpar ^ 1) * WBUF_BYTES + a_base;
+            char* w0n = wbuf0 + wpar * WBUF_BYTES;
+            char* w1n = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
+            const bf16_t* wc = wbase + chunk * 16;
+            // halo copy slots per group: 4 + 2 + 2 (slot = block j * 2 + plane)
+            conv_group<COB, 0, 0, 4>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+                                     wc + wgstride, wrel, wv, lane);
+            conv_group<COB, 1, 4, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+                                     wc + 2 * wgstride, wrel, wv, lane);
+            conv_group<COB, 2, 6, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_chunk * 16, a.zero16,
+                                     wbase + pf_chunk * 16, wrel, wv, lane);
+            wpar ^= 1;
         }
 
         // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
