@@ -67,6 +67,16 @@ __device__ __forceinline__ void g2lds16(const void* g, char* lds_base) {
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+// Scheduling hint: NM MFMAs with NR LDS reads spread evenly behind them.
+template <int K, int NM, int NR> __device__ __forceinline__ void sched_interleave() {
+    if constexpr (K < NM) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        constexpr int R = (NR * (K + 1)) / NM - (NR * K) / NM;
+        if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+        sched_interleave<K + 1, NM, NR>();
+    }
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 static constexpr int HBLK = (HALO_VOX + 63) / 64;  // 29 wave-wide copies per halo plane
@@ -477,6 +487,7 @@ struct WgradArgs {
     const bf16_t* x; int ldx;
     const bf16_t* dz; int lddz;
     float* part;  // [S][Cout][27][Cin]
+    const bf16_t* zero16;  // 16 zero bytes in global memory
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_wg;
 };
@@ -489,6 +500,78 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
     typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
     s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
+}
+
+// Per-lane constants of the wgrad tile copies (register-free global -> LDS, 16 voxels x 64 bytes per
+// wave copy: lane = voxel*4 + 16-byte part).
+//   dz: 2*COB/2... one copy = 16 voxels of one 32-channel half; x: 16 halo voxels of the 32-ci block.
+struct WgradLane {
+    int xrel[6];   // element offset of this lane's x halo voxel from the tile's halo origin, per copy slot
+    int xpk[6];    // its halo coords (d | h<<8 | w<<16), or -1 when the slot has no voxel for this lane
+    int zrel[4];   // element offset of this lane's dz voxel from the tile origin, per copy slot
+    int zpk[4];    // its tile coords
+};
+
+template <int COB, int NT>
+__device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __restrict__ st, char* __restrict__ st_next,
+                                           bool pf, const WgradLane& wl, const bf16_t* xorg, const bf16_t* zorg,
+                                           int dlo, int dhi, int hlo, int hhi, int wlo, int whi, int zd, int zh, int zw,
+                                           const bf16_t* zero16, const uint32_t (&tapoff)[4], uint32_t loff, int wv) {
+    constexpr int XCOPIES = WX_VOX / 16;            // 45
+    constexpr int ZCOPIES = COB * WTILE_VOX / 16;   // 32 or 16
+    if (pf) {
+        // x halo: copy q = wv + 8*i covers halo voxels 16q..16q+15
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int q = wv + 8 * i;
+            if (q < XCOPIES) {
+                const int pk = wl.xpk[i];
+                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+                const bool in = hd >= dlo && hd <= dhi && hh >= hlo && hh <= hhi && hw >= wlo && hw <= whi;
+                g2lds16(in ? xorg + wl.xrel[i] : zero16, st_next + q * 1024);
+            }
+        }
+        // dz: copy q covers half q / 16, voxels 16*(q%16) .. +15
+#pragma unroll
+        for (int i = 0; i < ZCOPIES / 8; ++i) {
+            const int q = wv + 8 * i;
+            const int pk = wl.zpk[i];
+            const int d = pk & 255, h = (pk >> 8) & 255, w = pk >> 16;
+            const bool in = d < zd && h < zh && w < zw;
+            g2lds16(in ? zorg + wl.zrel[i] : zero16, st_next + WX_BYTES + q * 1024);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const char* xb = st + loff;
+    const char* dzb = st + WX_BYTES + loff;
+    // fragments of k-step k+1 are fetched while k-step k is multiplied
+    bf16x8 af[2][COB], bfr[2][NT];
+    auto load_frags = [&](int ks, int slot) {
+        const int d = ks >> 3, h = ks & 7;  // k-step = one 16-voxel w-row of the tile
+        const uint32_t rowoff = (uint32_t)((d * WHH + h) * WHW * 64);
+#pragma unroll
+        for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
+#pragma unroll
+        for (int i = 0; i < NT; ++i) bfr[slot][i] = lds_frag_tr(xb + rowoff + tapoff[i]);
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+        if (ks < 15) load_frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb)
+                acc[cb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], bfr[ks & 1][i], acc[cb][i], 0, 0, 0);
+        if (ks < 15) {
+            constexpr int NM = NT * COB, NR = 2 * (COB + NT);  // MFMAs and LDS reads per k-step
+            sched_interleave<0, NM, NR>();
+        }
+    }
+    wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 template <int COB>
@@ -521,11 +604,25 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[cb][i][r] = 0.f;
 
-    // ---- staging: 16-byte pieces.  dz: 256 voxels x (4*COB) pieces ; x: 720 voxels x 4 pieces
-    constexpr int DZ_PIECES = WTILE_VOX * 4 * COB;
-    constexpr int DZ_ITERS = DZ_PIECES / 512;          // 4 (COB=2) or 2
-    constexpr int X_PIECES = WX_VOX * 4;               // 2880
-    constexpr int X_ITERS = (X_PIECES + 511) / 512;    // 6
+    // ---- per-lane constants of the tile copies
+    WgradLane wl;
+    const int cv = lane >> 2, cp = lane & 3;   // voxel within the copy, 16-byte part
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        int hv = (wv + 8 * i) * 16 + cv;
+        if (hv >= WX_VOX) hv = 0;
+        const int hw = hv % WHW, hh = (hv / WHW) % WHH, hd = hv / (WHW * WHH);
+        wl.xrel[i] = ((hd * a.H + hh) * a.W + hw) * a.ldx + cp * 8;
+        wl.xpk[i] = hd | (hh << 8) | (hw << 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = wv + 8 * i;
+        const int hf = q / 16, vx = (q % 16) * 16 + cv;   // (for COB == 1 only q < 16 is used: hf = 0)
+        const int w = vx % WTW, h = (vx / WTW) % WTH, d = vx / (WTW * WTH);
+        wl.zrel[i] = ((d * a.H + h) * a.W + w) * a.lddz + hf * 32 + cp * 8;
+        wl.zpk[i] = d | (h << 8) | (w << 16);
+    }
     auto tile_coords = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
@@ -534,101 +631,53 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         h0 = (r % a.tiles_h) * WTH;
         d0 = (r / a.tiles_h) * WTD;
     };
-    auto dz_load = [&](int i, int tile, uint4& v) {
-        const int p = tid + i * 512;
-        const int part = p % (4 * COB), vx = p / (4 * COB);
-        const int w = vx % WTW, h = (vx / WTW) % WTH, d = vx / (WTW * WTH);
+
+    // one tile's copies + multiply; `cur` selects the LDS stage holding `tile`
+    auto run_tile = [&](int tile_to_fetch, bool pf, const char* st, char* st_next) {
         int n, d0, h0, w0;
-        tile_coords(tile, n, d0, h0, w0);
-        const int gd = d0 + d, gh = h0 + h, gw = w0 + w;
-        v = make_uint4(0, 0, 0, 0);
-        if (gd < a.D && gh < a.H && gw < a.W)
-            v = *reinterpret_cast<const uint4*>(a.dz + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.lddz + co0 + part * 8);
-    };
-    auto dz_store = [&](int i, char* st, const uint4& v) {
-        const int p = tid + i * 512;
-        const int part = p % (4 * COB), vx = p / (4 * COB);
-        // 32-co half (part / 4) in its own array of 64-byte rows
-        *reinterpret_cast<uint4*>(st + WX_BYTES + (part >> 2) * WDZ_HALF_BYTES + vx * 64 + (part & 3) * 16) = v;
-    };
-    auto x_load = [&](int i, int tile, uint4& v) {
-        const int p = tid + i * 512;
-        v = make_uint4(0, 0, 0, 0);
-        if (p < X_PIECES) {
-            const int part = p & 3, hv = p >> 2;
-            const int hw = hv % WHW, hh = (hv / WHW) % WHH, hd = hv / (WHW * WHH);
-            int n, d0, h0, w0;
-            tile_coords(tile, n, d0, h0, w0);
-            const int gd = d0 + hd - 1, gh = h0 + hh - 1, gw = w0 + hw - 1;
-            if (gd >= 0 && gd < a.D && gh >= 0 && gh < a.H && gw >= 0 && gw < a.W)
-                v = *reinterpret_cast<const uint4*>(a.x + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldx + ci0 + part * 8);
-        }
-    };
-    auto x_store = [&](int i, char* st, const uint4& v) {
-        const int p = tid + i * 512;
-        if (p < X_PIECES) *reinterpret_cast<uint4*>(st + (p >> 2) * 64 + (p & 3) * 16) = v;
+        tile_coords(tile_to_fetch, n, d0, h0, w0);
+        const bf16_t* xorg = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx + ci0;
+        const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
+        if (has4)
+            wgrad_tile<COB, 4>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
+                               a.D - d0, a.H - h0, a.W - w0, a.zero16, tapoff, loff, wv);
+        else
+            wgrad_tile<COB, 3>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
+                               a.D - d0, a.H - h0, a.W - w0, a.zero16, tapoff, loff, wv);
     };
 
     if (tile_lo < tile_hi) {
-        // prologue: first tile synchronously
-        for (int i = 0; i < DZ_ITERS; ++i) { uint4 v; dz_load(i, tile_lo, v); dz_store(i, lds, v); }
-        for (int i = 0; i < X_ITERS; ++i) { uint4 v; x_load(i, tile_lo, v); x_store(i, lds, v); }
+        // prologue: fetch the first tile into stage 0 (the multiply part runs on zero-filled... no:
+        // only the copies are wanted here, so issue them directly)
+        int n, d0, h0, w0;
+        tile_coords(tile_lo, n, d0, h0, w0);
+        const bf16_t* xorg = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx + ci0;
+        const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int q = wv + 8 * i;
+            if (q < WX_VOX / 16) {
+                const int pk = wl.xpk[i];
+                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+                const bool in = hd >= 1 - d0 && hd <= a.D - d0 && hh >= 1 - h0 && hh <= a.H - h0 && hw >= 1 - w0 && hw <= a.W - w0;
+                g2lds16(in ? xorg + wl.xrel[i] : a.zero16, lds + q * 1024);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < COB * WTILE_VOX / 128; ++i) {
+            const int q = wv + 8 * i;
+            const int pk = wl.zpk[i];
+            const bool in = (pk & 255) < a.D - d0 && ((pk >> 8) & 255) < a.H - h0 && (pk >> 16) < a.W - w0;
+            g2lds16(in ? zorg + wl.zrel[i] : a.zero16, lds + WX_BYTES + q * 1024);
+        }
     }
+    wait_vmcnt<0>();
     __syncthreads();
 
     int par = 0;
     for (int tile = tile_lo; tile < tile_hi; ++tile, par ^= 1) {
-        const char* st = lds + par * WBUF_STAGE;
-        char* st_next = lds + (par ^ 1) * WBUF_STAGE;
         const bool pf = tile + 1 < tile_hi;
-        const char* xb = st + loff;
-        const char* dzb = st + WX_BYTES + loff;
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-            // first half of the k-steps carries the dz prefetch, second half the x prefetch
-            uint4 pv[X_ITERS];
-            if (pf) {
-                if (hf == 0) {
-#pragma unroll
-                    for (int i = 0; i < DZ_ITERS; ++i) dz_load(i, tile + 1, pv[i]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < X_ITERS; ++i) x_load(i, tile + 1, pv[i]);
-                }
-            }
-#pragma unroll
-            for (int k8 = 0; k8 < 8; ++k8) {
-                const int ks = hf * 8 + k8;            // k-step = one 16-voxel w-row: d = ks/8, h = ks%8
-                const int d = ks >> 3, h = ks & 7;
-                bf16x8 af[COB], bfr[4];
-#pragma unroll
-                for (int cb = 0; cb < COB; ++cb) af[cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
-                const uint32_t rowoff = (uint32_t)((d * WHH + h) * WHW * 64);
-#pragma unroll
-                for (int i = 0; i < 3; ++i) bfr[i] = lds_frag_tr(xb + rowoff + tapoff[i]);
-                if (has4) bfr[3] = lds_frag_tr(xb + rowoff + tapoff[3]);
-#pragma unroll
-                for (int i = 0; i < 3; ++i)
-#pragma unroll
-                    for (int cb = 0; cb < COB; ++cb)
-                        acc[cb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb], bfr[i], acc[cb][i], 0, 0, 0);
-                if (has4) {
-#pragma unroll
-                    for (int cb = 0; cb < COB; ++cb)
-                        acc[cb][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb], bfr[3], acc[cb][3], 0, 0, 0);
-                }
-            }
-            if (pf) {
-                if (hf == 0) {
-#pragma unroll
-                    for (int i = 0; i < DZ_ITERS; ++i) dz_store(i, st_next, pv[i]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < X_ITERS; ++i) x_store(i, st_next, pv[i]);
-                }
-            }
-        }
-        __syncthreads();
+        run_tile(pf ? tile + 1 : tile, pf, lds + par * WBUF_STAGE, lds + (par ^ 1) * WBUF_STAGE);
     }
 
     // ---- write this workgroup's partial: part[slot][co][tap][ci]
@@ -675,8 +724,10 @@ bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dz
 
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
     if (!mfma_wgrad_supported(xd, dzd, nullptr)) return 0;
-    return align_up((size_t)wgrad_slots(xd, dzd) * dzd->c * 27 * xd->c * sizeof(float));
+    return align_up((size_t)wgrad_slots(xd, dzd) * dzd->c * 27 * xd->c * sizeof(float)) + 256;
 }
+
+__global__ void zero16_kernel(uint32_t* p) { if (threadIdx.x < 4) p[threadIdx.x] = 0u; }
 
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz, float* dw,
                        float beta, void* ws, size_t ws_bytes, hipStream_t s) {
@@ -690,6 +741,10 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
     a.tiles_total = a.tiles_per_n * xd->n;
     const int S = wgrad_slots(xd, dzd);
     a.tiles_per_wg = (a.tiles_total + S - 1) / S;
+    uint32_t* z16 = (uint32_t*)((char*)ws + align_up((size_t)S * dzd->c * 27 * xd->c * sizeof(float)));
+    hipLaunchKernelGGL(zero16_kernel, dim3(1), dim3(64), 0, s, z16);
+    LAMP_CHECK_LAUNCH();
+    a.zero16 = (const bf16_t*)z16;
     const int cob = (dzd->c % 64 == 0) ? 2 : 1;
     dim3 grid(S, xd->c / 32, dzd->c / (32 * cob));
     static bool attr_done[2] = {false, false};
