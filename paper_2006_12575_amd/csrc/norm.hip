@@ -62,44 +62,50 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(const T* __restrict_
     if (counts && n == 0 && blockIdx.z == 0 && tid == 0) counts[chunk] = (int32_t)(rend - rbeg);
 }
 
-// One 64-lane wave per (n,c): Chan/Welford merging of the parts in fp64, fixed order.
-__global__ __launch_bounds__(64) void stats_finalize_kernel(const float* __restrict__ partial,
-                                                            const int32_t* __restrict__ counts, int parts, int C,
-                                                            float eps, float* __restrict__ stats) {
-    const int c = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
-    double cnt = 0.0, mean = 0.0, m2 = 0.0;
-    for (int p = lane; p < parts; p += 64) {
-        double k = (double)counts[p];
+// One 256-thread block per (n,c): Chan/Welford merging of the parts in fp64 in a fixed order
+// (strided per thread, then a fixed tree over lanes and waves).
+struct Moments { double cnt, mean, m2; };
+__device__ __forceinline__ void merge_moments(Moments& a, double c2, double mn2, double mm2) {
+    if (c2 > 0.0) {
+        const double tot = a.cnt + c2, dlt = mn2 - a.mean;
+        a.mean += dlt * (c2 / tot);
+        a.m2 += mm2 + dlt * dlt * (a.cnt * c2 / tot);
+        a.cnt = tot;
+    }
+}
+__global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __restrict__ partial,
+                                                             const int32_t* __restrict__ counts, int parts, int C,
+                                                             float eps, float* __restrict__ stats) {
+    __shared__ double sh[4][3];
+    const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    Moments m{0.0, 0.0, 0.0};
+    for (int p = tid; p < parts; p += 256) {
+        const double k = (double)counts[p];
         if (k <= 0.0) continue;
-        size_t o = (((size_t)n * parts + p) * C + c) * 2;
-        double sm = (double)partial[o], sq = (double)partial[o + 1];
-        double mp = sm / k;
+        const size_t o = (((size_t)n * parts + p) * C + c) * 2;
+        const double sm = (double)partial[o], sq = (double)partial[o + 1];
+        const double mp = sm / k;
         double m2p = sq - sm * mp;
         if (m2p < 0.0) m2p = 0.0;
-        double tot = cnt + k, dlt = mp - mean;
-        mean += dlt * (k / tot);
-        m2 += m2p + dlt * dlt * (cnt * k / tot);
-        cnt = tot;
+        merge_moments(m, k, mp, m2p);
     }
     for (int off = 32; off > 0; off >>= 1) {
-        double c2 = __shfl_down(cnt, off), mn2 = __shfl_down(mean, off), mm2 = __shfl_down(m2, off);
-        if (c2 > 0.0) {
-            double tot = cnt + c2, dlt = mn2 - mean;
-            mean += dlt * (c2 / tot);
-            m2 += mm2 + dlt * dlt * (cnt * c2 / tot);
-            cnt = tot;
-        }
+        const double c2 = __shfl_down(m.cnt, off), mn2 = __shfl_down(m.mean, off), mm2 = __shfl_down(m.m2, off);
+        merge_moments(m, c2, mn2, mm2);
     }
-    if (lane == 0) {
-        double var = cnt > 0.0 ? m2 / cnt : 0.0;
-        stats[((size_t)n * C + c) * 2 + 0] = (float)mean;
+    if (lane == 0) { sh[wv][0] = m.cnt; sh[wv][1] = m.mean; sh[wv][2] = m.m2; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) merge_moments(m, sh[w][0], sh[w][1], sh[w][2]);
+        const double var = m.cnt > 0.0 ? m.m2 / m.cnt : 0.0;
+        stats[((size_t)n * C + c) * 2 + 0] = (float)m.mean;
         stats[((size_t)n * C + c) * 2 + 1] = (float)(1.0 / sqrt(var + (double)eps));
     }
 }
 
 lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
                                   float eps, float* stats, hipStream_t s) {
-    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(64), 0, s, partials, counts, parts, C, eps, stats);
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(256), 0, s, partials, counts, parts, C, eps, stats);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
