@@ -13,6 +13,7 @@
 // Two halo buffers (10 x 10 x 18 voxels) let the next chunk / next tile stream in while the
 // current one is multiplied; two weight buffers hold one kd group (9 taps x 64 co x 16 ci) each.
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
+#include <stdlib.h>
 #include "internal.h"
 
 namespace lamp {
@@ -20,16 +21,27 @@ namespace lamp {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-static constexpr int TD = 8, TH = 8, TW = 16;
-static constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
-static constexpr int HALO_VOX = HD * HH * HW;              // 1800
-static constexpr int PLANE_BYTES = HALO_VOX * 16;          // 8 channels per voxel entry
-static constexpr int HALO_BYTES = 2 * PLANE_BYTES;         // one 16-channel chunk: 57600
-static constexpr int HALO_PIECES = HALO_VOX * 2;           // 16-byte pieces
-static constexpr int HALO_ITERS = (HALO_PIECES + 511) / 512;  // 8
+static constexpr int TH = 8, TW = 16;
+static constexpr int HH = TH + 2, HW = TW + 2;
 static constexpr int WPLANE_BYTES = 64 * 16;               // 64 co rows of 16 bytes
 static constexpr int WBUF_BYTES = 9 * 2 * WPLANE_BYTES;    // one kd group: 18432
-static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES;  // 152064
+
+// Tile geometry for a tile depth of TDT (8 or 4) output d-slices.  The 8 waves split the tile as
+// TDT d-slices x (8/TDT) h-parts; a wave owns NVB blocks of 32 voxels (2 h-rows x 16 w).
+template <int TDT> struct Geo {
+    static constexpr int TD = TDT, HD = TDT + 2;
+    static constexpr int HSPLIT = 8 / TDT, NVB = 4 / HSPLIT;
+    static constexpr int HALO_VOX = HD * HH * HW;            // 1800 / 1080
+    static constexpr int PLANE_BYTES = HALO_VOX * 16;        // 8 channels per voxel entry
+    static constexpr int HALO_BYTES = 2 * PLANE_BYTES;       // one 16-channel chunk
+    static constexpr int HBLK = (HALO_VOX + 63) / 64;        // wave-wide copies per halo plane: 29 / 17
+    static constexpr int HJ = (HBLK + 7) / 8;                // halo blocks per wave: 4 / 3
+    // epilogue scratch (8 wave patches of 32 rows x 144 bytes + channel sums): the 8-deep tile reuses
+    // the halo buffer of the finished stage, the 4-deep one is too small for that and gets its own
+    static constexpr int EPI_BYTES = 8 * 32 * 144 + 8 * 64 * 2 * 4;
+    static constexpr bool EPI_OWN = HALO_BYTES < EPI_BYTES;
+    static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? EPI_BYTES : 0);
+};
 
 __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
     uint4 q = *reinterpret_cast<const uint4*>(p);
@@ -79,7 +91,6 @@ template <int K, int NM, int NR> __device__ __forceinline__ void sched_interleav
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-static constexpr int HBLK = (HALO_VOX + 63) / 64;  // 29 wave-wide copies per halo plane
 
 // Per-lane constants of the halo copies.  A wave copies halo blocks wv, wv+8, wv+16, wv+24 (64
 // voxels each, both planes back to back so the two 16-byte halves of a voxel's 32 bytes meet in
@@ -100,12 +111,14 @@ struct HaloTile {
 // otherwise the compiler must assume the fragment reads alias the in-flight copies and waits for
 // them before the first read.
 //   HALO_FIRST, HALO_CNT : halo copy slots (block j = slot/2, plane = slot%2) issued in this group
-template <int COB, int G, int HALO_FIRST, int HALO_CNT>
-__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][4], const char* __restrict__ hb, const char* __restrict__ wb,
+template <int COB, int TDT, int G, int HALO_FIRST, int HALO_CNT>
+__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], const char* __restrict__ hb, const char* __restrict__ wb,
                                            char* __restrict__ hb_next, char* __restrict__ wb_next, bool pf_halo,
                                            bool pf_w, const HaloLane& hl, const HaloTile& ht, int pf_choff,
                                            const bf16_t* zero16, const bf16_t* wsrc, const int (&wrel)[3], int wv,
                                            int lane) {
+    typedef Geo<TDT> GE;
+    constexpr int NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES;
     constexpr int WROWS = 32 * COB;
     constexpr int WPLANE = WROWS * 16;
     constexpr int WINSTR = 18 * WROWS / 64;
@@ -134,14 +147,14 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][4], const char* __
     __builtin_amdgcn_sched_barrier(0);
     // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched while
     // tap t is multiplied
-    bf16x8 af[2][COB], bfr[2][4];
+    bf16x8 af[2][COB], bfr[2][NVB];
     auto load_frags = [&](int t9, int slot) {
         const int kh = t9 / 3, kw = t9 - 3 * kh;
         const int tapoff = ((G * HH + kh) * HW + kw) * 16;
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
+        for (int vb = 0; vb < NVB; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
     };
     load_frags(0, 0);
 #pragma unroll
@@ -150,19 +163,9 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][4], const char* __
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-            for (int vb = 0; vb < 4; ++vb)
+            for (int vb = 0; vb < NVB; ++vb)
                 acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
-        if (t9 < 8) {
-            // interleave: one LDS read behind each MFMA while both last
-            constexpr int NM = 4 * COB, NR = COB + 4, NP = NM < NR ? NM : NR;
-#pragma unroll
-            for (int k = 0; k < NP; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            if (NM > NP) __builtin_amdgcn_sched_group_barrier(0x008, NM - NP, 0);
-            if (NR > NP) __builtin_amdgcn_sched_group_barrier(0x100, NR - NP, 0);
-        }
+        if (t9 < 8) sched_interleave<0, NVB * COB, COB + NVB>();
     }
     // The weight copies are older than this group's halo copies: leaving HALO_CNT copies in flight
     // still guarantees the weights have landed.  (Every wave issues all HALO_CNT copies of groups
@@ -175,8 +178,11 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][4], const char* __
     asm volatile("" ::: "memory");
 }
 
-template <int COB>
+template <int COB, int TDT>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
+    typedef Geo<TDT> GE;
+    constexpr int TD = GE::TD, NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES,
+                  HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* hbuf0 = lds;
     char* wbuf0 = lds + 2 * HALO_BYTES;
@@ -199,13 +205,14 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15).
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
-    const uint32_t b_base = (uint32_t)(half * PLANE_BYTES + ((wv * HH + bh) * HW + bw) * 16);
+    const int ds = wv % TDT, hs = wv / TDT;   // this wave's d-slice and h-part of the tile
+    const uint32_t b_base = (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB * 2 + bh) * HW + bw) * 16);
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
     // ---- per-lane constants of the register-free global -> LDS copies
     HaloLane hl;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < HJ; ++j) {
         int hv = (wv + 8 * j) * 64 + lane;
         if (hv >= HALO_VOX) hv = 0;
         const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     {
         const HaloTile t0 = halo_tile(tile);
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) {
+        for (int sl = 0; sl < 2 * HJ; ++sl) {
             const int j = sl >> 1, plane = sl & 1, blk = wv + 8 * j;
             if (blk < HBLK && blk * 64 + lane < HALO_VOX) {
                 const int pk = hl.pk[j];
@@ -265,11 +272,11 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     int stage = 0;  // parity selects the halo buffer
     int wpar = 0;   // parity selects the weight buffer
     for (; tile < tile_hi; tile += wg_per_xcd) {
-        f32x16 acc[COB][4];
+        f32x16 acc[COB][NVB];
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-            for (int vb = 0; vb < 4; ++vb)
+            for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
 
@@ -289,13 +296,14 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             char* w0n = wbuf0 + wpar * WBUF_BYTES;
             char* w1n = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
             const bf16_t* wc = wbase + chunk * 16;
-            // halo copy slots per group: 4 + 2 + 2 (slot = block j * 2 + plane)
-            conv_group<COB, 0, 0, 4>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
-                                     wc + wgstride, wrel, wv, lane);
-            conv_group<COB, 1, 4, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
-                                     wc + 2 * wgstride, wrel, wv, lane);
-            conv_group<COB, 2, 6, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_chunk * 16, a.zero16,
-                                     wbase + pf_chunk * 16, wrel, wv, lane);
+            // halo copy slots per group (slot = block j * 2 + plane): 4 + 2 + 2 of 8, or 2 + 2 + 2 of 6
+            constexpr int S0 = 2 * HJ - 4;
+            conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+                                           wc + wgstride, wrel, wv, lane);
+            conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+                                           wc + 2 * wgstride, wrel, wv, lane);
+            conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_chunk * 16, a.zero16,
+                                               wbase + pf_chunk * 16, wrel, wv, lane);
             wpar ^= 1;
         }
 
@@ -305,8 +313,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         // Scratch: the halo buffer of the stage just finished (free until the next prefetch).
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
-        const int gd = d0 + wv;
-        char* fbuf = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
+        const int gd = d0 + ds;
+        char* fbuf = GE::EPI_OWN ? lds + 2 * HALO_BYTES + 2 * WBUF_BYTES : hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
         constexpr int ROWB = WROWS * 2 + 16;          // padded row of the patch
         constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
         constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
@@ -317,7 +325,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; }
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb) {
+        for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
                 const int rg8 = row >> 3;
                 const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
-                const int gh = h0 + vb * 2 + rh, gw = w0 + rw;
+                const int gh = h0 + hs * NVB * 2 + vb * 2 + rh, gw = w0 + rw;
                 const bool ok = gd < a.D && gh < a.H && gw < a.W;
                 if (ok) {
                     *reinterpret_cast<uint4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8) = q;
@@ -384,7 +392,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     }
 }
 
-static void tile_dims(const lamp_tensor_desc* t, int& td, int& th, int& tw) {
+static void tile_dims(const lamp_tensor_desc* t, int TD, int& td, int& th, int& tw) {
     td = (t->d + TD - 1) / TD; th = (t->h + TH - 1) / TH; tw = (t->w + TW - 1) / TW;
 }
 
@@ -397,22 +405,53 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
     return true;
 }
 
+// Tile depth.  The 8-deep tile gives each wave a 128-voxel x 64-channel register tile (fewest LDS
+// bytes and barriers per MFMA) and is used when it still yields at least two tiles per CU; smaller
+// volumes take the 4-deep tile so that more workgroups exist.  (The 4-deep tile also halves the
+// HBM re-fetch -- its per-XCD working set fits the 4 MiB L2 between chunk passes -- but is slower
+// per MFMA.)  LAMP_CONV_TILE_DEPTH=4|8 forces one for experiments.
+static int conv_tile_depth(const lamp_tensor_desc* zd) {
+    static int forced = -1;
+    if (forced < 0) {
+        const char* e = getenv("LAMP_CONV_TILE_DEPTH");
+        forced = e ? atoi(e) : 0;
+    }
+    if (forced == 4 || forced == 8) return forced;
+    const int64_t tiles8 = (int64_t)zd->n * ((zd->d + 7) / 8) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
+    return tiles8 >= 512 ? 8 : 4;
+}
+
 size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return 0;
     int td, th, tw;
-    tile_dims(zd, td, th, tw);
+    tile_dims(zd, 4, td, th, tw);  // the finer tiling bounds the partial count
     const size_t tiles = (size_t)td * th * tw;
     size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 16);
     if (want_stats) b += align_up((size_t)zd->n * tiles * zd->c * 2 * sizeof(float)) + align_up(tiles * sizeof(int32_t));
     return b;
 }
 
+template <int COB, int TDT>
+static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
+    static bool attr_done = false;
+    const int shm = Geo<TDT>::LDS_BYTES;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<COB, TDT>, hipFuncAttributeMaxDynamicSharedMemorySize, shm) != hipSuccess)
+            return LAMP_ERR_HIP;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT>), grid, dim3(512), shm, s, a);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
                           hipStream_t s) {
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    const int TDT = conv_tile_depth(zd);
     int td, th, tw;
-    tile_dims(zd, td, th, tw);
+    tile_dims(zd, TDT, td, th, tw);
     const int tiles_per_n = td * th * tw;
     Carver cv(ws, ws_bytes);
     bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 16);
@@ -437,25 +476,11 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
     int wgx = 256;  // one persistent workgroup per CU (LDS-limited), 32 per XCD
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
-    const size_t shm = LDS_BYTES;
     dim3 grid(wgx, zd->c / (32 * cob));
-    static bool attr_done[2] = {false, false};
-    if (cob == 2) {
-        if (!attr_done[1]) {
-            if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
-                return LAMP_ERR_HIP;
-            attr_done[1] = true;
-        }
-        hipLaunchKernelGGL((conv3d_igemm_kernel<2>), grid, dim3(512), shm, s, a);
-    } else {
-        if (!attr_done[0]) {
-            if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
-                return LAMP_ERR_HIP;
-            attr_done[0] = true;
-        }
-        hipLaunchKernelGGL((conv3d_igemm_kernel<1>), grid, dim3(512), shm, s, a);
-    }
-    LAMP_CHECK_LAUNCH();
+    lamp_status st;
+    if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
+    else st = cob == 2 ? launch_igemm<2, 4>(a, grid, s) : launch_igemm<1, 4>(a, grid, s);
+    if (st != LAMP_OK) return st;
     if (stats_out) return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);
     return LAMP_OK;
 }
