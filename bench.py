@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--size", type=int, default=128, help="cubic volume side (default: the benchmark's 128)")
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny"],
+                    help="block (default): the headline conv block (config 2). The others time the network-level "
+                         "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic) so that a counter "
                          "profile of this run can scale FETCH_SIZE / WRITE_SIZE")
@@ -56,6 +59,8 @@ def main():
     import paper_2006_12575_amd as L
 
     L.lib()  # fails loudly when the HIP library is missing
+    if args.workload != "block":
+        return net_bench(args, torch, np, S, L)
     dev = "cuda:0"
     bf, f32 = torch.bfloat16, torch.float32
     N, D, C = 1, args.size, args.channels
@@ -181,6 +186,102 @@ def main():
                                "cores": O.num_threads(), "kind": "oracle",
                                "sample": f"same conv block (fwd+dgrad+wgrad, fp64) on a {s}^3 sub-volume of the "
                                          f"workload, C={C}, {tc:.1f} s"}
+    print(json.dumps(out))
+
+
+def unet_flops(levels, base, in_ch, classes, n, d, h, w):
+    """Model FLOPs of one forward pass (2 per multiply-add; padding taps counted)."""
+    fl = 0.0
+    ch = [base << l for l in range(levels)]
+    vox = [n * (d >> l) * (h >> l) * (w >> l) for l in range(levels)]
+    for l in range(levels):
+        cin = in_ch if l == 0 else ch[l - 1]
+        fl += 2.0 * vox[l] * 27 * (cin * ch[l] + ch[l] * ch[l])
+    for l in range(levels - 2, -1, -1):
+        fl += 2.0 * vox[l + 1] * 8 * ch[l + 1] * ch[l]              # transposed conv
+        fl += 2.0 * vox[l] * 27 * (2 * ch[l] * ch[l] + ch[l] * ch[l])
+    fl += 2.0 * vox[0] * ch[0] * classes
+    return fl
+
+
+def net_bench(args, torch, np, S, L):
+    dev = "cuda:0"
+    bf, f32 = torch.bfloat16, torch.float32
+    wl = args.workload
+    cfg = {
+        "tiny": dict(levels=3, base=8, in_ch=1, classes=5, dims=(1, 32, 32, 32), dtype=f32, seed=1001),
+        "stage": dict(levels=3, base=64, in_ch=1, classes=10, dims=(1, 192, 192, 192), dtype=bf, seed=1003),
+        "unet_train": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
+        "unet_infer": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
+        "sliding": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
+    }[wl]
+    levels, base, K, dt = cfg["levels"], cfg["base"], cfg["classes"], cfg["dtype"]
+    N, D, H, W = cfg["dims"]
+    rp, rx, rl = S.streams(cfg["seed"], 3)
+    p = S.unet_params(rp, levels, base, 1, K, False)
+    names = list(p.keys())
+    params = [torch.from_numpy(v).to(f32 if k.endswith(".b") else dt).to(dev) for k, v in p.items()]
+    x = torch.from_numpy(S.ct_volume(rx, N, D, H, W) if wl != "tiny" else S.normal(rx, (N, D, H, W, 1))).to(dt).to(dev)
+    V = N * D * H * W
+    steps, warm = max(1, args.steps), max(1, args.warmup)
+    if wl in ("tiny", "unet_infer"):
+        ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
+        logits = torch.empty((N, D, H, W, K), dtype=f32, device=dev)
+        ws = torch.empty(L.lamp_unet_workspace_bytes(ud, False), dtype=torch.uint8, device=dev)
+        run = lambda: L.lamp_unet_fwd(ud, params, x, logits, ws=ws)
+        flops = unet_flops(levels, base, 1, K, N, D, H, W)
+        what = f"{levels}-level base-{base} U-Net forward, {N}x{D}x{H}x{W}"
+    elif wl == "unet_train":
+        ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
+        lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(dev)
+        grads = [torch.empty(t.shape, dtype=f32, device=dev) for t in params]
+        loss = torch.empty((), dtype=f32, device=dev)
+        ws = torch.empty(L.lamp_unet_workspace_bytes(ud, True), dtype=torch.uint8, device=dev)
+        run = lambda: L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
+        flops = 3.0 * unet_flops(levels, base, 1, K, N, D, H, W)
+        what = f"{levels}-level base-{base} U-Net forward+backward (softmax CE), {N}x{D}x{H}x{W}"
+    elif wl == "sliding":
+        P = 64
+        cnt = L.lamp_sliding_window_count(D, H, W, P, 0.25)
+        pd = L.unet_desc(levels, base, 1, K, cnt, P, P, P, dt)
+        out = torch.empty((1, D, H, W, K), dtype=f32, device=dev)
+        import ctypes
+        ws = torch.empty(int(L.lib().lamp_sliding_window_workspace_bytes(ctypes.byref(pd), D, H, W)), dtype=torch.uint8, device=dev)
+        run = lambda: L.lamp_sliding_window_fwd(pd, params, x, out, ws=ws)
+        flops = unet_flops(levels, base, 1, K, cnt, P, P, P)
+        what = f"{cnt} sliding windows of {P}^3 (overlap 0.25, Gaussian blend) over {D}x{H}x{W}, {levels}-level base-{base} U-Net"
+    else:  # stage: encoder blocks 1-2 of a base-64 net, forward + backward
+        ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
+        sp = params[:4]
+        ws = torch.empty(L.lamp_unet_stage_workspace_bytes(ud, 1, 2), dtype=torch.uint8, device=dev)
+        pooled = torch.empty((N, D // 4, H // 4, W // 4, 2 * base), dtype=dt, device=dev)
+        skips = [torch.empty((N, D, H, W, base), dtype=dt, device=dev),
+                 torch.empty((N, D // 2, H // 2, W // 2, 2 * base), dtype=dt, device=dev)]
+        gp = torch.randn(pooled.shape, device=dev, generator=torch.Generator(dev).manual_seed(1)).to(dt)
+        gs = [torch.randn(t.shape, device=dev, generator=torch.Generator(dev).manual_seed(2 + i)).to(dt) for i, t in enumerate(skips)]
+        grads = [torch.empty(t.shape, dtype=f32, device=dev) for t in sp]
+
+        def run():
+            L.lamp_unet_stage_fwd(ud, 1, 2, sp, x, pooled, skips, ws)
+            L.lamp_unet_stage_bwd(ud, 1, 2, sp, x, skips, gp, gs, grads, ws)
+        v1, v2 = V, V // 8
+        fwd = 2.0 * 27 * (v1 * (1 * base + base * base) + v2 * (base * 2 * base + 4 * base * base))
+        flops = 3.0 * fwd - 2.0 * 27 * v1 * base  # no data gradient for the first conv
+        what = f"encoder partition (blocks 1-2, base {base}) forward+backward, {N}x{D}x{H}x{W}"
+    for _ in range(warm):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dtm = (time.perf_counter() - t0) / steps
+    out = {"metric": "Conv3d fwd+bwd TFLOP/s (% MFMA peak); whole-U-Net voxels/sec at 1 GPU", "value": V / dtm,
+           "unit": "voxels/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": dtm * 1e3,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if dt == bf else "f32", "data": "synthetic",
+           "config": {"workload": what, "voxels": V, "flop_per_step": flops},
+           "tflops": flops / dtm / 1e12, "pct_mfma_peak": 100.0 * flops / dtm / 1e12 / PEAK_BF16_TFLOPS}
     print(json.dumps(out))
 
 

@@ -166,9 +166,11 @@ lamp_status lamp_maxpool2_bwd(const lamp_tensor_desc *xd, const void *x, const l
  *   dx[n,d,h,w,ci]   = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * Wt[ci,i,j,k,co]
  *   dWt[ci,i,j,k,co] = beta*dWt + sum_{n,d,h,w} X[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]   (fp32)
  *   dbias[co]        = beta*dbias + sum dy[...,co]                                          (fp32) */
+size_t lamp_convtr3d_workspace_bytes(const lamp_tensor_desc *xd, const lamp_tensor_desc *yd);
 lamp_status lamp_convtr3d(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
                           const void *wt, const float *bias,
-                          const lamp_tensor_desc *yd, void *y, void *stream);
+                          const lamp_tensor_desc *yd, void *y,
+                          void *ws, size_t ws_bytes, void *stream);
 size_t lamp_convtr3d_bwd_workspace_bytes(const lamp_tensor_desc *xd, const lamp_tensor_desc *dyd);
 lamp_status lamp_convtr3d_bwd(const lamp_tensor_desc *xd, const void *x, const lamp_norm_in *xnorm,
                               const void *wt, const lamp_tensor_desc *dyd, const void *dy,

@@ -63,7 +63,8 @@ _SIGS = {
     "lamp_inorm_relu_bwd": (c_int, [_PD, _VP, _PD, _VP, _VP, _VP, _VP, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_maxpool2_fwd": (c_int, [_PD, _VP, _PN, _PD, _VP, _VP]),
     "lamp_maxpool2_bwd": (c_int, [_PD, _VP, _PN, _PD, _VP, _PD, _VP, _PD, _VP, _VP]),
-    "lamp_convtr3d": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP]),
+    "lamp_convtr3d_workspace_bytes": (c_size_t, [_PD, _PD]),
+    "lamp_convtr3d": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP, c_size_t, _VP]),
     "lamp_convtr3d_bwd_workspace_bytes": (c_size_t, [_PD, _PD]),
     "lamp_convtr3d_bwd": (c_int, [_PD, _VP, _PN, _VP, _PD, _VP, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_head_ce_workspace_bytes": (c_size_t, [_PD, c_int]),
@@ -232,10 +233,12 @@ def lamp_maxpool2_bwd(x, dy, dx, add=None, xnorm=None):
     return dx
 
 
-def lamp_convtr3d(x, wt, y, bias=None, xnorm=None):
+def lamp_convtr3d(x, wt, y, bias=None, xnorm=None, ws=None):
     xd, yd = desc(x), desc(y)
+    need = lib().lamp_convtr3d_workspace_bytes(ctypes.byref(xd), ctypes.byref(yd))
+    ws = ws if ws is not None else _ws(need, x.device)
     _check(lib().lamp_convtr3d(ctypes.byref(xd), _ptr(x), _norm(xnorm), _ptr(wt), _ptr(bias), ctypes.byref(yd), _ptr(y),
-                               _stream()), "lamp_convtr3d")
+                               _ptr(ws), ws.numel(), _stream()), "lamp_convtr3d")
     return y
 
 

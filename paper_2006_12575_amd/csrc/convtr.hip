@@ -106,12 +106,21 @@ static lamp_status convtr_shapes(const lamp_tensor_desc* xd, const lamp_tensor_d
 
 using namespace lamp;
 
+extern "C" size_t lamp_convtr3d_workspace_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd) {
+    if (!desc_ok(xd) || !desc_ok(yd)) return 0;
+    return mfma_convtr_ws_bytes(xd, yd);
+}
+
 extern "C" lamp_status lamp_convtr3d(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wt,
-                                     const float* bias, const lamp_tensor_desc* yd, void* y, void* stream) {
+                                     const float* bias, const lamp_tensor_desc* yd, void* y, void* ws, size_t ws_bytes,
+                                     void* stream) {
     if (!xd || !yd || !x || !wt || !y) return LAMP_ERR_NULL;
     lamp_status st = convtr_shapes(xd, yd);
     if (st != LAMP_OK) return st;
     if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
+    if (ws_bytes < lamp_convtr3d_workspace_bytes(xd, yd) || (ws_bytes && !ws)) return LAMP_ERR_WORKSPACE;
+    if (mfma_convtr_supported(xd, yd, xnorm) && aligned16(x) && aligned16(ws) && ((((uintptr_t)y) & 7u) == 0))
+        return mfma_convtr_fwd(xd, x, wt, bias, yd, y, ws, ws_bytes, (hipStream_t)stream);
     NormIn nm = make_norm(xnorm);
     const int64_t total = nvox(yd) * yd->c;
     if (xd->dtype == LAMP_BF16)
@@ -129,7 +138,10 @@ extern "C" lamp_status lamp_convtr3d(const lamp_tensor_desc* xd, const void* x, 
 extern "C" size_t lamp_convtr3d_bwd_workspace_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd) {
     if (!desc_ok(xd) || !desc_ok(dyd)) return 0;
     const int64_t O = (int64_t)xd->c * 8 * dyd->c;
-    return align_up((size_t)convtr_splits(nvox(xd), O) * O * sizeof(float)) + colsum_ws_bytes(nvox(dyd), dyd->c);
+    size_t a = align_up((size_t)convtr_splits(nvox(xd), O) * O * sizeof(float));
+    const size_t b = mfma_convtr_wgrad_ws_bytes(xd, dyd);
+    if (b > a) a = align_up(b);
+    return a + colsum_ws_bytes(nvox(dyd), dyd->c);
 }
 
 extern "C" lamp_status lamp_convtr3d_bwd(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm,
@@ -149,7 +161,9 @@ extern "C" lamp_status lamp_convtr3d_bwd(const lamp_tensor_desc* xd, const void*
     if ((dwt || dbias) && (!ws || ws_bytes < lamp_convtr3d_bwd_workspace_bytes(xd, dyd))) return LAMP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int Ci = xd->c, Co = dyd->c;
-    if (dx) {
+    if (dx && mfma_convtr_dgrad_supported(xd, dyd, dxd) && aligned16(dy) && aligned16(wt) && ((((uintptr_t)dx) & 7u) == 0)) {
+        if ((st = mfma_convtr_dgrad(xd, wt, dyd, dy, dxd, dx, s)) != LAMP_OK) return st;
+    } else if (dx) {
         const int64_t total = nvox(xd) * Ci;
         if (xd->dtype == LAMP_BF16)
             hipLaunchKernelGGL((convtr_dgrad_kernel<bf16_t>), dim3(cdiv(total, 256)), dim3(256), 0, s, (const bf16_t*)dy,
@@ -160,8 +174,11 @@ extern "C" lamp_status lamp_convtr3d_bwd(const lamp_tensor_desc* xd, const void*
         LAMP_CHECK_LAUNCH();
     }
     const int64_t O = (int64_t)Ci * 8 * Co;
-    const size_t pbytes = align_up((size_t)convtr_splits(nvox(xd), O) * O * sizeof(float));
-    if (dwt) {
+    const size_t csb = colsum_ws_bytes(nvox(dyd), Co);
+    const size_t pbytes = lamp_convtr3d_bwd_workspace_bytes(xd, dyd) - csb;
+    if (dwt && mfma_convtr_wgrad_supported(xd, dyd, xnorm) && aligned16(x) && aligned16(dy) && aligned16(ws)) {
+        if ((st = mfma_convtr_wgrad(xd, x, dyd, dy, dwt, beta, ws, pbytes, s)) != LAMP_OK) return st;
+    } else if (dwt) {
         const int64_t V = nvox(xd);
         const int S = convtr_splits(V, O);
         const int64_t vps = (V + S - 1) / S;

@@ -1,0 +1,369 @@
+// Matrix-core kernels for the 2x2x2 stride-2 transposed convolution (bf16, fp32 accumulate).
+//
+// Every output voxel depends on one input voxel and one tap, so forward and data gradient are plain
+// GEMMs over voxels with a gather / scatter to the 2x2x2 sub-positions:
+//   forward : Y[(tap,co)][v] = sum_ci  Wt'[(tap,co)][ci] * X[v][ci]        -> y[up(v,tap)][co]
+//   dgrad   : DX[ci][v]      = sum_{(tap,co)} Wt[ci][(tap,co)] * DY[up(v,tap)][co]
+// Operands are read straight from global memory into MFMA fragments (16 contiguous bytes per lane:
+// the weights are small and cache-resident, the activations are streamed once); the op is bound by
+// writing / reading the fine-resolution tensor, not by the matrix cores.
+// The weight gradient has voxels as its reduction dimension and reads both operands through LDS with
+// the transposing load, like the 3x3x3 weight gradient.
+#include "internal.h"
+
+namespace lamp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+
+struct CtArgs {
+    const bf16_t* a;      // row-major A[rows][K]
+    const bf16_t* b;      // activations (x for forward, dy for dgrad)
+    bf16_t* out;
+    const float* bias;    // forward only, [Co] or nullptr
+    int rows, K;
+    int N, D, H, W;       // coarse (input-resolution) dims
+    int Ci, Co;
+    int ldb, ldo;         // channel strides of b and out
+};
+
+// wt'[(tap*Co + co)][ci] = wt[ci][tap][co]
+__global__ __launch_bounds__(256) void convtr_repack_kernel(const bf16_t* __restrict__ wt, bf16_t* __restrict__ wp, int Ci,
+                                                            int Co) {
+    const int64_t total = (int64_t)Ci * 8 * Co;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int ci = (int)(i % Ci);
+    const int r = (int)(i / Ci);  // tap*Co + co
+    wp[i] = wt[(int64_t)ci * 8 * Co + r];
+}
+
+__device__ __forceinline__ bf16x8 gfrag(const bf16_t* p, bool ok) {
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (ok) q = *reinterpret_cast<const uint4*>(p);
+    return __builtin_bit_cast(bf16x8, q);
+}
+
+// MODE 0: forward, MODE 1: data gradient.  One wave = 64 coarse voxels x up to 128 rows.
+template <int MODE>
+__global__ __launch_bounds__(256) void convtr_gemm_kernel(CtArgs a) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t nvox = (int64_t)a.N * a.D * a.H * a.W;
+    const int64_t v0 = ((int64_t)blockIdx.x * 4 + wv) * 64;
+    if (v0 >= nvox) return;
+    const int r0 = blockIdx.y * 128;
+    const int nrb = min(4, (a.rows - r0 + 31) / 32);
+
+    // the lane's two voxels (column j of voxel blocks 0 and 1) and their fine-resolution origin
+    int64_t vq[2], fine[2];
+    bool vok[2];
+#pragma unroll
+    for (int vb = 0; vb < 2; ++vb) {
+        const int64_t v = v0 + vb * 32 + l32;
+        vok[vb] = v < nvox;
+        const int64_t vc = vok[vb] ? v : 0;
+        const int w = (int)(vc % a.W);
+        int64_t r = vc / a.W;
+        const int h = (int)(r % a.H);
+        r /= a.H;
+        const int d = (int)(r % a.D);
+        const int n = (int)(r / a.D);
+        vq[vb] = vc;
+        fine[vb] = (((int64_t)n * 2 * a.D + 2 * d) * 2 * a.H + 2 * h) * 2 * a.W + 2 * w;  // voxel (2d,2h,2w)
+    }
+    auto tap_off = [&](int tap) -> int64_t {
+        const int i = tap >> 2, j = (tap >> 1) & 1, k = tap & 1;
+        return ((int64_t)i * 2 * a.H + j) * 2 * a.W + k;
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][vb][r] = 0.f;
+
+    for (int k0 = 0; k0 < a.K; k0 += 16) {
+        const int k = k0 + 8 * half;
+        bf16x8 bf[2], af[4];
+        if (MODE == 0) {
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb) bf[vb] = gfrag(a.b + vq[vb] * a.ldb + k, vok[vb]);
+        } else {
+            const int tap = k / a.Co, co = k - tap * a.Co;
+            const int64_t to = tap_off(tap);
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb) bf[vb] = gfrag(a.b + (fine[vb] + to) * a.ldb + co, vok[vb]);
+        }
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int row = r0 + rb * 32 + l32;
+            af[rb] = gfrag(a.a + (int64_t)row * a.K + k, rb < nrb && row < a.rows);
+        }
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb)
+                if (rb < nrb) acc[rb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb], bf[vb], acc[rb][vb], 0, 0, 0);
+    }
+
+    // lane holds, for its voxel of each block, rows r0 + rb*32 + 8*(r/4) + 4*half + (r%4)
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        if (rb >= nrb) continue;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int row = r0 + rb * 32 + rg * 8 + half * 4;
+            if (row >= a.rows) continue;
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb) {
+                if (!vok[vb]) continue;
+                uint32_t pk[2];
+                if (MODE == 0) {
+                    const int tap = row / a.Co, co = row - tap * a.Co;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float bv = a.bias ? a.bias[co + e] : 0.f;
+                        const uint32_t b = f2bf(acc[rb][vb][rg * 4 + e] + bv);
+                        if (e & 1) pk[e >> 1] |= b << 16; else pk[e >> 1] = b;
+                    }
+                    *reinterpret_cast<uint2*>(a.out + (fine[vb] + tap_off(tap)) * a.ldo + co) = make_uint2(pk[0], pk[1]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t b = f2bf(acc[rb][vb][rg * 4 + e]);
+                        if (e & 1) pk[e >> 1] |= b << 16; else pk[e >> 1] = b;
+                    }
+                    *reinterpret_cast<uint2*>(a.out + vq[vb] * a.ldo + row) = make_uint2(pk[0], pk[1]);
+                }
+            }
+        }
+    }
+}
+
+bool mfma_convtr_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd, const lamp_norm_in* xnorm) {
+    if (xd->dtype != LAMP_BF16) return false;
+    if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
+    if (xd->c % 16 || yd->c % 8 || xd->ldc % 8 || yd->ldc % 4) return false;
+    return true;
+}
+
+size_t mfma_convtr_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd) {
+    if (!mfma_convtr_supported(xd, yd, nullptr)) return 0;
+    return align_up((size_t)xd->c * 8 * yd->c * 2);
+}
+
+lamp_status mfma_convtr_fwd(const lamp_tensor_desc* xd, const void* x, const void* wt, const float* bias,
+                            const lamp_tensor_desc* yd, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)y) & 7u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if (ws_bytes < mfma_convtr_ws_bytes(xd, yd)) return LAMP_ERR_WORKSPACE;
+    const int Ci = xd->c, Co = yd->c;
+    bf16_t* wp = (bf16_t*)ws;
+    hipLaunchKernelGGL(convtr_repack_kernel, dim3(cdiv((int64_t)Ci * 8 * Co, 256)), dim3(256), 0, s, (const bf16_t*)wt, wp, Ci, Co);
+    LAMP_CHECK_LAUNCH();
+    CtArgs a;
+    a.a = wp; a.b = (const bf16_t*)x; a.out = (bf16_t*)y; a.bias = bias; a.rows = 8 * Co; a.K = Ci;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = Ci; a.Co = Co; a.ldb = xd->ldc; a.ldo = yd->ldc;
+    dim3 grid(cdiv(nvox(xd), 256), cdiv(a.rows, 128));
+    hipLaunchKernelGGL((convtr_gemm_kernel<0>), grid, dim3(256), 0, s, a);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+bool mfma_convtr_dgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd, const lamp_tensor_desc* dxd) {
+    if (xd->dtype != LAMP_BF16) return false;
+    if (xd->c % 4 || dyd->c % 8 || dyd->ldc % 8 || dxd->ldc % 4) return false;
+    return true;
+}
+
+lamp_status mfma_convtr_dgrad(const lamp_tensor_desc* xd, const void* wt, const lamp_tensor_desc* dyd, const void* dy,
+                              const lamp_tensor_desc* dxd, void* dx, hipStream_t s) {
+    if ((((uintptr_t)dy) & 15u) || (((uintptr_t)dx) & 7u) || (((uintptr_t)wt) & 15u)) return LAMP_ERR_ALIGN;
+    CtArgs a;
+    a.a = (const bf16_t*)wt; a.b = (const bf16_t*)dy; a.out = (bf16_t*)dx; a.bias = nullptr; a.rows = xd->c; a.K = 8 * dyd->c;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c; a.ldb = dyd->ldc; a.ldo = dxd->ldc;
+    dim3 grid(cdiv(nvox(xd), 256), cdiv(a.rows, 128));
+    hipLaunchKernelGGL((convtr_gemm_kernel<1>), grid, dim3(256), 0, s, a);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight gradient  dWt[ci][tap][co] = sum_v x[v][ci] * dy[up(v,tap)][co]   (K = coarse voxels).
+// Workgroup = 4 waves on (split s, 64-wide ci block, 32-wide co block); wave w owns taps 2w, 2w+1.
+// Chunks of 64 coarse voxels are staged in LDS (x rows of 128 bytes, dy rows of 64 bytes per tap,
+// double buffered, register-free copies) and read with the transposing LDS load.
+__device__ __forceinline__ void g2lds16_ct(const void* g, char* lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+template <int ROWB> __device__ __forceinline__ bf16x8 frag_tr(const char* p) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * ROWB));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+struct CtWArgs {
+    const bf16_t* x; int ldx;
+    const bf16_t* dy; int ldy;
+    float* part;              // [S][Ci][8][Co]
+    const bf16_t* zero16;
+    int N, D, H, W, Ci, Co;
+    int chunks_per_split;     // 64-voxel chunks per split
+};
+
+static constexpr int CTW_X = 64 * 128;            // x tile bytes
+static constexpr int CTW_DY = 8 * 64 * 64;        // dy tile bytes (8 taps)
+static constexpr int CTW_STAGE = CTW_X + CTW_DY;  // 40960
+
+__device__ __forceinline__ void ctw_stage(const CtWArgs& a, char* __restrict__ st, int64_t v0, int64_t nvox, int ci0,
+                                          int co0, int wv, int lane) {
+    // x: copy q = wv*2 + i covers voxels 8q..8q+7, 8 pieces of 16 bytes each
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = wv * 2 + i;
+        const int64_t v = v0 + q * 8 + (lane >> 3);
+        const int pc = lane & 7;
+        const bool ok = v < nvox && ci0 + pc * 8 < a.Ci;
+        g2lds16_ct(ok ? a.x + v * a.ldx + ci0 + pc * 8 : a.zero16, st + q * 1024);
+    }
+    // dy: copy q = wv*8 + i: tap q/4, voxels 16*(q%4) .. +15, 4 pieces each
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int q = wv * 8 + i;
+        const int tap = q >> 2;
+        const int64_t v = v0 + (q & 3) * 16 + (lane >> 2);
+        const int pc = lane & 3;
+        const bf16_t* src = a.zero16;
+        if (v < nvox) {
+            const int vi = (int)v;  // host guarantees nvox < 2^31
+            const int w = vi % a.W;
+            int r = vi / a.W;
+            const int h = r % a.H;
+            r /= a.H;
+            const int d = r % a.D, n = r / a.D;
+            const int64_t ov = (((int64_t)n * 2 * a.D + 2 * d + (tap >> 2)) * 2 * a.H + 2 * h + ((tap >> 1) & 1)) * 2 * a.W + 2 * w + (tap & 1);
+            src = a.dy + ov * a.ldy + co0 + pc * 8;
+        }
+        g2lds16_ct(src, st + CTW_X + q * 1024);
+    }
+}
+
+__device__ __forceinline__ void ctw_compute(f32x16 (&acc)[2][2], const char* __restrict__ st, int wv, int lane) {
+    const int b16 = lane >> 4, s16 = lane & 15;
+    const uint32_t lx = (uint32_t)((8 * (b16 >> 1) + (s16 >> 2)) * 128 + 32 * (b16 & 1) + 8 * (s16 & 3));
+    const uint32_t ly = (uint32_t)((8 * (b16 >> 1) + (s16 >> 2)) * 64 + 32 * (b16 & 1) + 8 * (s16 & 3));
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 af[2], bf[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) af[rb] = frag_tr<128>(st + ks * 16 * 128 + rb * 64 + lx);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) bf[t] = frag_tr<64>(st + CTW_X + ((wv * 2 + t) * 64 + ks * 16) * 64 + ly);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) acc[rb][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb], bf[t], acc[rb][t], 0, 0, 0);
+    }
+}
+
+__global__ __launch_bounds__(256) void convtr_wgrad_mfma_kernel(CtWArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int ci0 = blockIdx.y * 64, co0 = blockIdx.z * 32;
+    const int64_t nvox = (int64_t)a.N * a.D * a.H * a.W;
+    const int64_t nchunks = (nvox + 63) / 64;
+    const int64_t c_lo = (int64_t)blockIdx.x * a.chunks_per_split;
+    int64_t c_hi = c_lo + a.chunks_per_split;
+    if (c_hi > nchunks) c_hi = nchunks;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][t][r] = 0.f;
+    if (c_lo < c_hi) ctw_stage(a, lds, c_lo * 64, nvox, ci0, co0, wv, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int par = 0;
+    for (int64_t c = c_lo; c < c_hi; ++c, par ^= 1) {
+        if (c + 1 < c_hi) ctw_stage(a, lds + (par ^ 1) * CTW_STAGE, (c + 1) * 64, nvox, ci0, co0, wv, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        ctw_compute(acc, lds + par * CTW_STAGE, wv, lane);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+    float* pb = a.part + (int64_t)blockIdx.x * a.Ci * 8 * a.Co;
+    const int l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ci = ci0 + rb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (ci < a.Ci) pb[((int64_t)ci * 8 + wv * 2 + t) * a.Co + co0 + l32] = acc[rb][t][r];
+            }
+}
+
+__global__ void zero16_ct_kernel(uint32_t* p) { if (threadIdx.x < 4) p[threadIdx.x] = 0u; }
+
+static int ctw_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd) {
+    const int64_t chunks = (nvox(xd) + 63) / 64;
+    const int types = ((xd->c + 63) / 64) * (dyd->c / 32);
+    int64_t s = 1024 / types;
+    if (s < 1) s = 1;
+    if (s > chunks) s = chunks;
+    return (int)s;
+}
+
+bool mfma_convtr_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd, const lamp_norm_in* xnorm) {
+    if (xd->dtype != LAMP_BF16) return false;
+    if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
+    if (xd->c % 32 || dyd->c % 32 || xd->ldc % 8 || dyd->ldc % 8) return false;
+    if (nvox(xd) >= ((int64_t)1 << 31)) return false;
+    return true;
+}
+
+size_t mfma_convtr_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd) {
+    if (!mfma_convtr_wgrad_supported(xd, dyd, nullptr)) return 0;
+    return align_up((size_t)ctw_splits(xd, dyd) * xd->c * 8 * dyd->c * sizeof(float)) + 256;
+}
+
+lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dyd, const void* dy,
+                              float* dwt, float beta, void* ws, size_t ws_bytes, hipStream_t s) {
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)dy) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if (ws_bytes < mfma_convtr_wgrad_ws_bytes(xd, dyd)) return LAMP_ERR_WORKSPACE;
+    const int S = ctw_splits(xd, dyd);
+    const int64_t O = (int64_t)xd->c * 8 * dyd->c;
+    CtWArgs a;
+    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dy = (const bf16_t*)dy; a.ldy = dyd->ldc; a.part = (float*)ws;
+    uint32_t* z16 = (uint32_t*)((char*)ws + align_up((size_t)S * O * sizeof(float)));
+    a.zero16 = (const bf16_t*)z16;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c;
+    const int64_t chunks = (nvox(xd) + 63) / 64;
+    a.chunks_per_split = (int)((chunks + S - 1) / S);
+    hipLaunchKernelGGL(zero16_ct_kernel, dim3(1), dim3(64), 0, s, z16);
+    LAMP_CHECK_LAUNCH();
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)convtr_wgrad_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * CTW_STAGE) != hipSuccess)
+            return LAMP_ERR_HIP;
+        attr_done = true;
+    }
+    dim3 grid(S, (xd->c + 63) / 64, dyd->c / 32);
+    hipLaunchKernelGGL(convtr_wgrad_mfma_kernel, grid, dim3(256), 2 * CTW_STAGE, s, a);
+    LAMP_CHECK_LAUNCH();
+    return launch_reduce_partials((const float*)ws, S, O, dwt, beta, s);
+}
+
+}  // namespace lamp

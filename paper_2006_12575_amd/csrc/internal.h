@@ -39,4 +39,18 @@ size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* d
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,
                        float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s);
 
+// ---- convtr_mfma.hip ------------------------------------------------------------------------
+bool mfma_convtr_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd, const lamp_norm_in* xnorm);
+size_t mfma_convtr_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd);
+lamp_status mfma_convtr_fwd(const lamp_tensor_desc* xd, const void* x, const void* wt, const float* bias,
+                            const lamp_tensor_desc* yd, void* y, void* ws, size_t ws_bytes, hipStream_t s);
+bool mfma_convtr_dgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd, const lamp_tensor_desc* dxd);
+lamp_status mfma_convtr_dgrad(const lamp_tensor_desc* xd, const void* wt, const lamp_tensor_desc* dyd, const void* dy,
+                              const lamp_tensor_desc* dxd, void* dx, hipStream_t s);
+
+bool mfma_convtr_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd, const lamp_norm_in* xnorm);
+size_t mfma_convtr_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd);
+lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dyd, const void* dy,
+                              float* dwt, float beta, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace lamp

@@ -166,10 +166,14 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
             b.z = take(tb); b.stats = (float*)take(sb); b.y = bwd ? take(tb) : b.z; b.ldy = C;
             size_t sc = block_scratch(nt, l, 2 * C, C, bwd);
             scratch = sc > scratch ? sc : scratch;
-            if (bwd) {
+            {
                 lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
-                size_t t = lamp_convtr3d_bwd_workspace_bytes(&xd, &yd);
+                size_t t = lamp_convtr3d_workspace_bytes(&xd, &yd);
                 scratch = t > scratch ? t : scratch;
+                if (bwd) {
+                    t = lamp_convtr3d_bwd_workspace_bytes(&xd, &yd);
+                    scratch = t > scratch ? t : scratch;
+                }
             }
         }
         if (bwd) {
@@ -317,7 +321,7 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
         const int C = nt.chan(l), pi = dec_pi(u, l);
         lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
         st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, (char*)lay.cat[l - 1] + (size_t)C * nt.es,
-                           nt.s);
+                           nt.scratch, nt.scratch_bytes, nt.s);
         if (st != LAMP_OK) return st;
         st = block_fwd(nt, l, 2 * C, 2 * C, lay.cat[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1]);
         if (st != LAMP_OK) return st;
