@@ -78,6 +78,123 @@ __global__ __launch_bounds__(256) void conv3d_wgrad_direct_kernel(const T* __res
     part[(int64_t)blockIdx.y * O + o] = acc;
 }
 
+// ---- single-input-channel first layer (the network input is one CT channel), bf16 ----------------
+// Forward: one thread per output voxel computes all Cout channels from its 27 neighbours; the op
+// is bound by writing the output (2*Cout bytes per voxel against 2 bytes read).
+__global__ __launch_bounds__(256) void conv3d_cin1_fwd_kernel(const bf16_t* __restrict__ x, int ldx,
+                                                              const bf16_t* __restrict__ w, bf16_t* __restrict__ z, int ldz,
+                                                              int N, int D, int H, int W, int Cout) {
+    __shared__ float wsh[27 * 128];  // [tap][co]
+    for (int i = threadIdx.x; i < 27 * Cout; i += 256) {
+        const int co = i / 27, t = i - co * 27;
+        wsh[t * Cout + co] = bf2f(w[i]);
+    }
+    __syncthreads();
+    const int64_t total = (int64_t)N * D * H * W;
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= total) return;
+    const int wv = (int)(v % W);
+    int64_t r = v / W;
+    const int h = (int)(r % H);
+    r /= H;
+    const int d = (int)(r % D);
+    const int n = (int)(r / D);
+    float xv[27];
+#pragma unroll
+    for (int t = 0; t < 27; ++t) {
+        const int id = d + t / 9 - 1, ih = h + (t / 3) % 3 - 1, iw = wv + t % 3 - 1;
+        const bool in = id >= 0 && id < D && ih >= 0 && ih < H && iw >= 0 && iw < W;
+        xv[t] = in ? bf2f(x[((((int64_t)n * D + id) * H + ih) * W + iw) * ldx]) : 0.f;
+    }
+    bf16_t* zp = z + v * ldz;
+    for (int c8 = 0; c8 < Cout; c8 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 27; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(xv[t], wsh[t * Cout + c8 + e], acc[e]);
+        uint32_t pk[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (uint32_t)f2bf(acc[2 * e]) | ((uint32_t)f2bf(acc[2 * e + 1]) << 16);
+        *reinterpret_cast<uint4*>(zp + c8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    }
+}
+
+// Weight gradient for Cin == 1: dW[co][tap] = sum_v dz[v][co] * x[v + tap], as a matrix-core product
+// with the voxels as the reduction dimension.  Per step a wave multiplies A = dz^T (32 channels x 16
+// voxels of one W-row) by B = the gathered neighbours (16 voxels x 32 taps, taps 27..31 zero); both
+// fragments come straight from global memory (dz is read once, x is cache-resident).  Every wave
+// owns a run of 16-voxel groups and writes its own partial [Co][27] slab.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+struct U16x8 { unsigned short e[8]; };
+
+__global__ __launch_bounds__(256) void conv3d_cin1_wgrad_kernel(const bf16_t* __restrict__ x, int ldx,
+                                                                const bf16_t* __restrict__ dz, int lddz,
+                                                                float* __restrict__ part, int N, int D, int H, int W, int Co,
+                                                                int64_t groups, int gpw) {
+    const int lane = threadIdx.x & 63, l32 = lane & 31, kg = lane >> 5;
+    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int cob = blockIdx.y * 32;
+    const int tap = l32;
+    const int kd = tap / 9 - 1, kh = (tap / 3) % 3 - 1, kw = tap % 3 - 1;
+    int64_t g0 = wid * gpw, g1 = g0 + gpw;
+    if (g1 > groups) g1 = groups;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int64_t g = g0; g < g1; ++g) {
+        const int64_t v = g * 16 + 8 * kg;  // the lane's 8 voxels v..v+7 lie in one W-row
+        const int w0 = (int)(v % W);
+        int64_t r = v / W;
+        const int h = (int)(r % H);
+        r /= H;
+        const int d = (int)(r % D);
+        const int n = (int)(r / D);
+        U16x8 a, b;
+        const bf16_t* dp = dz + v * lddz + cob + l32;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a.e[e] = dp[(int64_t)e * lddz];
+        const int id = d + kd, ih = h + kh;
+        const bool rowok = tap < 27 && id >= 0 && id < D && ih >= 0 && ih < H;
+        const int64_t base = rowok ? (((int64_t)n * D + id) * H + ih) * W : 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int iw = w0 + e + kw;
+            const bool ok = rowok && iw >= 0 && iw < W;
+            b.e[e] = ok ? x[(base + iw) * ldx] : (bf16_t)0;
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0,
+                                                      0);
+    }
+    if (tap < 27) {
+        float* pb = part + wid * Co * 27;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int co = cob + 8 * (r / 4) + 4 * kg + (r % 4);
+            pb[(int64_t)co * 27 + tap] = acc[r];
+        }
+    }
+}
+
+static bool cin1_fwd_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm, const float* bias,
+                        const void* z) {
+    const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+    return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && !bias && zd->c % 8 == 0 && zd->c <= 128 && zd->ldc % 8 == 0 &&
+           aligned16(z);
+}
+static bool cin1_wgrad_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm) {
+    const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+    return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && dzd->c % 32 == 0 && xd->w % 16 == 0;
+}
+// thread blocks (4 waves, one partial slab per wave) of the Cin == 1 weight gradient
+static int cin1_wgrad_blocks(int64_t V) {
+    int64_t b = (V / 16 + 3) / 4;
+    return (int)(b > 512 ? 512 : (b < 1 ? 1 : b));
+}
+
 static int wgrad_splits(int64_t V, int64_t O) {
     int64_t s = (V + 255) / 256;
     int64_t cap = (int64_t)(32u << 20) / (O * 4);
@@ -138,8 +255,14 @@ extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x
     hipStream_t s = (hipStream_t)stream;
     if (mfma_conv_supported(xd, zd, xnorm, bias))
         return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s);
-    st = launch_direct<false>(xd, x, make_norm(xnorm), w, bias, zd, z, s);
-    if (st != LAMP_OK) return st;
+    if (cin1_fwd_ok(xd, zd, xnorm, bias, z)) {
+        hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                           (const bf16_t*)w, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
+        LAMP_CHECK_LAUNCH();
+    } else {
+        st = launch_direct<false>(xd, x, make_norm(xnorm), w, bias, zd, z, s);
+        if (st != LAMP_OK) return st;
+    }
     if (stats_out) return launch_stats(zd, z, eps, stats_out, ws, ws_bytes, s);
     return LAMP_OK;
 }
@@ -167,6 +290,10 @@ extern "C" size_t lamp_conv3d_wgrad_workspace_bytes(const lamp_tensor_desc* xd, 
     size_t a = align_up((size_t)wgrad_splits(nvox(xd), O) * O * sizeof(float));
     size_t b = mfma_wgrad_ws_bytes(xd, dzd);
     size_t c = colsum_ws_bytes(nvox(dzd), dzd->c);
+    if (cin1_wgrad_ok(xd, dzd, nullptr)) {
+        const size_t e = align_up((size_t)cin1_wgrad_blocks(nvox(xd)) * 4 * dzd->c * 27 * sizeof(float));
+        if (e > a) a = e;
+    }
     return (a > b ? a : b) + c;
 }
 
@@ -188,6 +315,15 @@ extern "C" lamp_status lamp_conv3d_wgrad(const lamp_tensor_desc* xd, const void*
         if (st != LAMP_OK) return st;
     }
     if (mfma_wgrad_supported(xd, dzd, xnorm)) return mfma_wgrad(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
+    if (cin1_wgrad_ok(xd, dzd, xnorm)) {
+        const int64_t groups = nvox(xd) / 16;
+        const int blocks = cin1_wgrad_blocks(nvox(xd));
+        const int gpw = (int)((groups + blocks * 4 - 1) / (blocks * 4));
+        hipLaunchKernelGGL(conv3d_cin1_wgrad_kernel, dim3(blocks, dzd->c / 32), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                           (const bf16_t*)dz, dzd->ldc, (float*)ws, xd->n, xd->d, xd->h, xd->w, dzd->c, groups, gpw);
+        LAMP_CHECK_LAUNCH();
+        return launch_reduce_partials((const float*)ws, blocks * 4, (int64_t)dzd->c * 27, dw, beta, s);
+    }
     const int64_t V = nvox(xd);
     const int S = wgrad_splits(V, O);
     const int64_t vps = (V + S - 1) / S;

@@ -1,13 +1,15 @@
 // 1x1x1 head, softmax and cross entropy (forward and backward).  One thread per voxel; the
 // op is bound by reading the activations and writing the fp32 logits.
 #include "internal.h"
+#include "vec.h"
 
 namespace lamp {
 
 static const int kMaxClasses = 16;
 
+// KM: compile-time bound on the class count (4, 8 or 16).
 // MODE 0: logits only.  MODE 1: + loss partials, dlogits, dx.
-template <typename T, int MODE>
+template <typename T, int VEC, int MODE, int KM>
 __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, int ldx, NormIn nm, const T* __restrict__ wh,
                                                    const float* __restrict__ bh, int K, int C, int64_t Vs, int64_t Vtot,
                                                    const int32_t* __restrict__ labels, float* __restrict__ logits,
@@ -21,35 +23,38 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, int 
     const float invV = 1.0f / (float)Vtot;
     for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < Vtot; v += (int64_t)gridDim.x * 256) {
         const int n = (int)(v / Vs);
-        float acc[kMaxClasses];
+        float acc[KM];
 #pragma unroll
-        for (int k = 0; k < kMaxClasses; ++k) acc[k] = (k < K && bh) ? bh[k] : 0.f;
+        for (int k = 0; k < KM; ++k) acc[k] = (k < K && bh) ? bh[k] : 0.f;
         const T* xp = x + v * ldx;
-        for (int c = 0; c < C; ++c) {
-            float xv = load_norm(xp + c, nm, n, c);
+        for (int c0 = 0; c0 < C; c0 += VEC) {
+            float xv[VEC];
+            load_norm_vec<T, VEC>(xp + c0, nm, n, c0, xv);
 #pragma unroll
-            for (int k = 0; k < kMaxClasses; ++k)
-                if (k < K) acc[k] = fmaf(xv, wsh[k * C + c], acc[k]);
+            for (int i = 0; i < VEC; ++i)
+#pragma unroll
+                for (int k = 0; k < KM; ++k)
+                    if (k < K) acc[k] = fmaf(xv[i], wsh[k * C + c0 + i], acc[k]);
         }
         if (logits) {
 #pragma unroll
-            for (int k = 0; k < kMaxClasses; ++k)
+            for (int k = 0; k < KM; ++k)
                 if (k < K) logits[v * K + k] = acc[k];
         }
         if (MODE == 1) {
             float m = acc[0];
 #pragma unroll
-            for (int k = 1; k < kMaxClasses; ++k)
+            for (int k = 1; k < KM; ++k)
                 if (k < K) m = acc[k] > m ? acc[k] : m;
             float se = 0.f;
 #pragma unroll
-            for (int k = 0; k < kMaxClasses; ++k)
+            for (int k = 0; k < KM; ++k)
                 if (k < K) se += expf(acc[k] - m);
             const float lse = m + logf(se);
             const int lab = labels[v];
             float ll = 0.f;
 #pragma unroll
-            for (int k = 0; k < kMaxClasses; ++k) {
+            for (int k = 0; k < KM; ++k) {
                 if (k < K) {
                     if (k == lab) ll = acc[k];
                     float p = expf(acc[k] - lse);
@@ -59,12 +64,16 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, int 
             }
             lsum += (lse - ll) * invV;
             if (dx) {
-                for (int c = 0; c < C; ++c) {
-                    float g = 0.f;
+                for (int c0 = 0; c0 < C; c0 += VEC) {
+                    float g[VEC];
 #pragma unroll
-                    for (int k = 0; k < kMaxClasses; ++k)
-                        if (k < K) g = fmaf(acc[k], wsh[k * C + c], g);
-                    io<T>::st(dx + v * lddx + c, g);
+                    for (int i = 0; i < VEC; ++i) {
+                        g[i] = 0.f;
+#pragma unroll
+                        for (int k = 0; k < KM; ++k)
+                            if (k < K) g[i] = fmaf(acc[k], wsh[k * C + c0 + i], g[i]);
+                    }
+                    Vec<T, VEC>::store(dx + v * lddx + c0, g);
                 }
             }
         }
@@ -80,20 +89,41 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, int 
     }
 }
 
-// part[s][k*C + c] = sum over the voxels of split s of dlogits[v][k] * X[v][c]
-template <typename T>
+// part[s][k*C + c] = sum over the voxels of split s of dlogits[v][k] * X[v][c].  Threads side by
+// side cover the channels of one voxel row (coalesced), 256/C voxel rows are in flight per block and
+// every thread keeps K sums; the row lanes are then added in order through LDS.
+template <typename T, int KM>
 __global__ __launch_bounds__(256) void head_wgrad_kernel(const T* __restrict__ x, int ldx, NormIn nm,
                                                          const float* __restrict__ dlogits, int K, int C, int64_t Vs,
                                                          int64_t Vtot, int64_t vps, float* __restrict__ part) {
-    const int o = blockIdx.x * 256 + threadIdx.x;
-    if (o >= K * C) return;
-    const int k = o / C, c = o % C;
-    int64_t v0 = (int64_t)blockIdx.y * vps, v1 = v0 + vps;
+    __shared__ float red[KM * 256];
+    const int cthreads = C < 256 ? C : 256;
+    const int rl = 256 / cthreads;
+    const int cl = threadIdx.x % cthreads, r0 = threadIdx.x / cthreads;
+    const int c = blockIdx.y * 256 + cl;
+    int64_t v0 = (int64_t)blockIdx.x * vps, v1 = v0 + vps;
     if (v1 > Vtot) v1 = Vtot;
-    float acc = 0.f;
-    for (int64_t v = v0; v < v1; ++v)
-        acc = fmaf(dlogits[v * K + k], load_norm(x + v * ldx + c, nm, (int)(v / Vs), c), acc);
-    part[(int64_t)blockIdx.y * K * C + o] = acc;
+    float acc[KM];
+#pragma unroll
+    for (int k = 0; k < KM; ++k) acc[k] = 0.f;
+    if (r0 < rl && c < C)
+        for (int64_t v = v0 + r0; v < v1; v += rl) {
+            const float xv = load_norm(x + v * ldx + c, nm, (int)(v / Vs), c);
+            const float* dl = dlogits + v * K;
+#pragma unroll
+            for (int k = 0; k < KM; ++k)
+                if (k < K) acc[k] = fmaf(dl[k], xv, acc[k]);
+        }
+#pragma unroll
+    for (int k = 0; k < KM; ++k)
+        if (k < K) red[k * 256 + threadIdx.x] = acc[k];
+    __syncthreads();
+    if (r0 == 0 && c < C)
+        for (int k = 0; k < K; ++k) {
+            float t = 0.f;
+            for (int r = 0; r < rl; ++r) t += red[k * 256 + r * cthreads + cl];
+            part[(int64_t)blockIdx.x * K * C + (int64_t)k * C + c] = t;
+        }
 }
 
 static int head_blocks(int64_t V) {
@@ -116,6 +146,13 @@ static lamp_status head_check(const lamp_tensor_desc* xd, const void* x, const v
 
 using namespace lamp;
 
+#define LAMP_DISPATCH_KM(k, BODY)                      \
+    do {                                               \
+        if ((k) <= 4) { constexpr int KM = 4; BODY }   \
+        else if ((k) <= 8) { constexpr int KM = 8; BODY } \
+        else { constexpr int KM = 16; BODY }           \
+    } while (0)
+
 extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh,
                                      const float* bh, int classes, float* logits, void* stream) {
     lamp_status st = head_check(xd, x, wh, classes);
@@ -125,14 +162,14 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
     const size_t shm = (size_t)classes * xd->c * sizeof(float);
     NormIn nm = make_norm(xnorm);
-    if (xd->dtype == LAMP_BF16)
-        hipLaunchKernelGGL((head_kernel<bf16_t, 0>), dim3(head_blocks(Vt)), dim3(256), shm, (hipStream_t)stream,
-                           (const bf16_t*)x, xd->ldc, nm, (const bf16_t*)wh, bh, classes, xd->c, Vs, Vt, nullptr, logits,
-                           nullptr, nullptr, 0, nullptr);
-    else
-        hipLaunchKernelGGL((head_kernel<float, 0>), dim3(head_blocks(Vt)), dim3(256), shm, (hipStream_t)stream,
-                           (const float*)x, xd->ldc, nm, (const float*)wh, bh, classes, xd->c, Vs, Vt, nullptr, logits,
-                           nullptr, nullptr, 0, nullptr);
+    const int vec = pick_vec(xd->dtype, xd->c, {xd->ldc}, {x});
+    LAMP_DISPATCH_TV(xd->dtype, vec, {
+        LAMP_DISPATCH_KM(classes, {
+            hipLaunchKernelGGL((head_kernel<T, VEC, 0, KM>), dim3(head_blocks(Vt)), dim3(256), shm, (hipStream_t)stream,
+                               (const T*)x, xd->ldc, nm, (const T*)wh, bh, classes, xd->c, Vs, Vt, nullptr, logits,
+                               nullptr, (T*)nullptr, 0, nullptr);
+        });
+    });
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
@@ -175,23 +212,26 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const size_t shm = (size_t)K * C * sizeof(float);
     NormIn nm = make_norm(xnorm);
-    if (xd->dtype == LAMP_BF16)
-        hipLaunchKernelGGL((head_kernel<bf16_t, 1>), dim3(nb), dim3(256), shm, s, (const bf16_t*)x, xd->ldc, nm,
-                           (const bf16_t*)wh, bh, K, C, Vs, Vt, labels, logits, dlogits, (bf16_t*)dx, lddx, lpart);
-    else
-        hipLaunchKernelGGL((head_kernel<float, 1>), dim3(nb), dim3(256), shm, s, (const float*)x, xd->ldc, nm,
-                           (const float*)wh, bh, K, C, Vs, Vt, labels, logits, dlogits, (float*)dx, lddx, lpart);
+    const int vec = pick_vec(xd->dtype, C, {xd->ldc, lddx}, {x, dx});
+    LAMP_DISPATCH_TV(xd->dtype, vec, {
+        LAMP_DISPATCH_KM(K, {
+            hipLaunchKernelGGL((head_kernel<T, VEC, 1, KM>), dim3(nb), dim3(256), shm, s, (const T*)x, xd->ldc, nm,
+                               (const T*)wh, bh, K, C, Vs, Vt, labels, logits, dlogits, (T*)dx, lddx, lpart);
+        });
+    });
     LAMP_CHECK_LAUNCH();
     if ((st = launch_reduce_partials(lpart, nb, 1, loss, 0.f, s)) != LAMP_OK) return st;
     if (dwh) {
         const int64_t vps = (Vt + S - 1) / S;
-        dim3 grid(cdiv(K * C, 256), S);
-        if (xd->dtype == LAMP_BF16)
-            hipLaunchKernelGGL((head_wgrad_kernel<bf16_t>), grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, nm, dlogits,
-                               K, C, Vs, Vt, vps, wpart);
-        else
-            hipLaunchKernelGGL((head_wgrad_kernel<float>), grid, dim3(256), 0, s, (const float*)x, xd->ldc, nm, dlogits, K,
-                               C, Vs, Vt, vps, wpart);
+        dim3 grid(S, cdiv(C, 256));
+        LAMP_DISPATCH_KM(K, {
+            if (xd->dtype == LAMP_BF16)
+                hipLaunchKernelGGL((head_wgrad_kernel<bf16_t, KM>), grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, nm,
+                                   dlogits, K, C, Vs, Vt, vps, wpart);
+            else
+                hipLaunchKernelGGL((head_wgrad_kernel<float, KM>), grid, dim3(256), 0, s, (const float*)x, xd->ldc, nm,
+                                   dlogits, K, C, Vs, Vt, vps, wpart);
+        });
         LAMP_CHECK_LAUNCH();
         if ((st = launch_reduce_partials(wpart, S, (int64_t)K * C, dwh, beta, s)) != LAMP_OK) return st;
     }

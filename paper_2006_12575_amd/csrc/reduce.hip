@@ -1,64 +1,98 @@
 // Deterministic second-stage reductions shared by the weight-gradient paths.
 #include "internal.h"
+#include "vec.h"
 
 namespace lamp {
 
+// Block = (256/SL) outputs x SL lanes over the parts; every lane adds its strided parts in order,
+// then the lanes are added in order: a fixed summation tree, fp64.
+template <int SL>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int S, int64_t O,
                                                               float* __restrict__ out, float beta) {
-    int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (o >= O) return;
+    constexpr int OPB = 256 / SL;
+    __shared__ double sh[SL][OPB];
+    const int ol = threadIdx.x % OPB, sl = threadIdx.x / OPB;
+    const int64_t o = (int64_t)blockIdx.x * OPB + ol;
     double acc = 0.0;
-    for (int s = 0; s < S; ++s) acc += (double)part[(int64_t)s * O + o];
-    out[o] = (beta != 0.f ? beta * out[o] : 0.f) + (float)acc;
+    if (o < O)
+        for (int s = sl; s < S; s += SL) acc += (double)part[(int64_t)s * O + o];
+    sh[sl][ol] = acc;
+    __syncthreads();
+    if (sl == 0 && o < O) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < SL; ++k) t += sh[k][ol];
+        out[o] = (beta != 0.f ? beta * out[o] : 0.f) + (float)t;
+    }
 }
 
 lamp_status launch_reduce_partials(const float* part, int S, int64_t O, float* out, float beta, hipStream_t s) {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(O, 256)), dim3(256), 0, s, part, S, O, out, beta);
+    if (O <= 16384 && S >= 64)
+        hipLaunchKernelGGL((reduce_partials_kernel<64>), dim3(cdiv(O, 4)), dim3(256), 0, s, part, S, O, out, beta);
+    else if (S >= 8)
+        hipLaunchKernelGGL((reduce_partials_kernel<8>), dim3(cdiv(O, 32)), dim3(256), 0, s, part, S, O, out, beta);
+    else
+        hipLaunchKernelGGL((reduce_partials_kernel<1>), dim3(cdiv(O, 256)), dim3(256), 0, s, part, S, O, out, beta);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
 
-static const int kColRows = 4096;
+// rows per chunk: about 2048 chunks, at least 32 rows each
+static int col_rows(int64_t rows) {
+    int64_t r = (rows + 2047) / 2048;
+    return (int)(r < 32 ? 32 : r);
+}
 
-template <typename T>
+// Threads side by side cover the channel vectors of one row; the row lanes are added in order.
+template <typename T, int VEC>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ t, int64_t rows, int C, int ld,
-                                                             int rows_per_chunk, float* __restrict__ part) {
-    __shared__ float red[256];
-    const int cthreads = C < 256 ? C : 256;
-    const int rl = 256 / cthreads;
-    const int tid = threadIdx.x, cl = tid % cthreads, r0 = tid / cthreads;
-    const int c = blockIdx.y * 256 + cl;
+                                                             int rows_per_chunk, float* __restrict__ part, RowMap m) {
+    __shared__ float red[VEC][256];
+    const int tid = threadIdx.x, cl = tid % m.cthreads, r0 = tid / m.cthreads;
+    const int c0 = (blockIdx.y * 256 + cl) * VEC;
     int64_t rbeg = (int64_t)blockIdx.x * rows_per_chunk, rend = rbeg + rows_per_chunk;
     if (rend > rows) rend = rows;
-    float s = 0.f;
-    if (r0 < rl && c < C)
-        for (int64_t r = rbeg + r0; r < rend; r += rl) s += io<T>::ld(t + r * ld + c);
-    red[tid] = s;
+    float s[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s[i] = 0.f;
+    if (r0 < m.rl && c0 < C)
+        for (int64_t r = rbeg + r0; r < rend; r += m.rl) {
+            float v[VEC];
+            Vec<T, VEC>::load(t + r * ld + c0, v);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) s[i] += v[i];
+        }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) red[i][tid] = s[i];
     __syncthreads();
-    if (r0 == 0 && c < C) {
-        float ss = 0.f;
-        for (int r = 0; r < rl; ++r) ss += red[r * cthreads + cl];
-        part[(int64_t)blockIdx.x * C + c] = ss;
+    if (r0 == 0 && c0 < C) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float ss = 0.f;
+            for (int r = 0; r < m.rl; ++r) ss += red[i][r * m.cthreads + cl];
+            part[(int64_t)blockIdx.x * C + c0 + i] = ss;
+        }
     }
 }
 
 size_t colsum_ws_bytes(int64_t rows, int C) {
-    int64_t chunks = (rows + kColRows - 1) / kColRows;
+    const int cr = col_rows(rows);
+    int64_t chunks = (rows + cr - 1) / cr;
     return align_up((size_t)chunks * C * sizeof(float));
 }
 
 lamp_status launch_colsum(const void* t, int dtype, int64_t rows, int C, int ld, float* out, float beta, void* ws,
                           size_t ws_bytes, hipStream_t s) {
-    int chunks = (int)((rows + kColRows - 1) / kColRows);
+    const int cr = col_rows(rows);
+    int chunks = (int)((rows + cr - 1) / cr);
     if (!ws || ws_bytes < colsum_ws_bytes(rows, C)) return LAMP_ERR_WORKSPACE;
     float* part = (float*)ws;
-    dim3 grid(chunks, cdiv(C, 256));
-    if (dtype == LAMP_BF16)
-        hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), grid, dim3(256), 0, s, (const bf16_t*)t, rows, C, ld,
-                           kColRows, part);
-    else
-        hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, s, (const float*)t, rows, C, ld, kColRows,
-                           part);
+    const int vec = pick_vec(dtype, C, {ld}, {t});
+    const RowMap m = make_rowmap(C, vec);
+    dim3 grid(chunks, m.ctiles);
+    LAMP_DISPATCH_TV(dtype, vec, {
+        hipLaunchKernelGGL((colsum_partial_kernel<T, VEC>), grid, dim3(256), 0, s, (const T*)t, rows, C, ld, cr, part, m);
+    });
     LAMP_CHECK_LAUNCH();
     return launch_reduce_partials(part, chunks, C, out, beta, s);
 }
