@@ -449,6 +449,14 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
                           hipStream_t s) {
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    {
+        static int ring = -1;
+        if (ring < 0) {
+            const char* e = getenv("LAMP_CONV_KERNEL");
+            ring = (e && e[0] == 'r') ? 1 : 0;
+        }
+        if (ring) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
+    }
     const int TDT = conv_tile_depth(zd);
     int td, th, tw;
     tile_dims(zd, TDT, td, th, tw);

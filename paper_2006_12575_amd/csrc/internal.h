@@ -39,6 +39,12 @@ size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* d
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,
                        float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s);
 
+// ---- conv3d_mfma_ring.hip -------------------------------------------------------------------
+// Ring variant of the matrix-core convolution (same contract and workspace as mfma_conv_fwd).
+lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
+                          const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
+                          void* ws, size_t ws_bytes, hipStream_t s);
+
 // ---- convtr_mfma.hip ------------------------------------------------------------------------
 bool mfma_convtr_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd, const lamp_norm_in* xnorm);
 size_t mfma_convtr_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd);
