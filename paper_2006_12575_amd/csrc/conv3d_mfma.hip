@@ -73,10 +73,12 @@ struct ConvArgs {
 };
 
 // 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
-// (lds_base must be wave-uniform); inactive lanes write nothing.
+// (lds_base must be wave-uniform); inactive lanes write nothing.  Issued as inline assembly so that
+// the compiler's wait-count bookkeeping does not see it: with the builtin form every later wait for an
+// LDS fragment read degrades to "wait for all reads".  Completion is tracked by hand with wait_vmcnt.
 __device__ __forceinline__ void g2lds16(const void* g, char* lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+    const uint32_t m = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m), "v"(g) : "memory", "m0");
 }
 
 // Scheduling hint: NM MFMAs with NR LDS reads spread evenly behind them.
@@ -173,7 +175,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
     if (G < 2 && pf_halo) wait_vmcnt<(G < 2 ? HALO_CNT : 0)>();
     else wait_vmcnt<0>();
     // bare barrier: __syncthreads() would add a release fence that drains every copy in flight
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
@@ -602,7 +604,7 @@ __device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __
         }
     }
     wait_vmcnt<0>();
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }

@@ -117,60 +117,102 @@ struct HaloTile {
     int dlo, dhi, hlo, hhi, wlo, whi;  // halo coords inside the volume: lo <= c <= hi
 };
 
-// One step: in-plane tap J = kh*3 + kw of the current chunk.
-//   acur          : weight fragments of this step (read during the previous step)
-//   b0, b1, b2    : slice fragments 0..2 of this step (read during the previous step)
-// On return acur / b0 / b1 / b2 hold the same for the next step.
-// Straight-line code (no branches), so that the scheduler can slide the copies of this step -- three
-// per wave: two weight copies and one halo copy, always issued -- into the MFMA stream.
+// ---- one step = in-plane tap J = kh*3 + kw of the current chunk: 12*COB MFMAs, 6 + 3*COB fragment
+// reads (3 slices of this step, then the weights and the first 3 slices of the next step) and 3 copies.
+// With one wave per SIMD nothing else hides a stall, so the instruction order is fixed by hand: the
+// step is cut into slots of one MFMA each, every read, copy and piece of address arithmetic is
+// assigned to a slot, and a scheduling fence closes each slot.
+template <int COB> struct StepPlan {
+    static constexpr int NM = 12 * COB, NR = 6 + 3 * COB;
+    struct M { int s, kd, cb; };
+    // MFMA k in slice-major order: slice s meets the weights of kd for output slice d = s - kd
+    static constexpr M mfma(int k) {
+        int i = 0;
+        for (int s = 0; s < 6; ++s)
+            for (int kd = 0; kd < 3; ++kd) {
+                if (s - kd < 0 || s - kd > 3) continue;
+                for (int cb = 0; cb < COB; ++cb) {
+                    if (i == k) return M{s, kd, cb};
+                    ++i;
+                }
+            }
+        return M{0, 0, 0};
+    }
+    // slot of fragment read r: spread over the step (the four waves share one LDS port), the slices 3..5
+    // first (needed from MFMA 6*COB on), the last one early enough to land before the step ends
+    static constexpr int read_slot(int r) { return COB == 2 ? (r < 9 ? 2 * r : 8 + r) : r; }
+    // slots of the copies: weight copy 0, weight copy 1, halo copy (address arithmetic in the slots before)
+    static constexpr int WC0 = COB == 2 ? 9 : 3, WC1 = COB == 2 ? 11 : 5, HC = COB == 2 ? 15 : 8;
+};
+
+template <int COB> struct StepCtx {
+    f32x16 (&acc)[COB][4];
+    bf16x8 (&acur)[3][COB];
+    bf16x8 (&b)[6];
+    bf16x8 (&an)[3][COB];
+    bf16x8 (&nb)[3];
+    const char* hb;          // this step's region + lane offset + tap offset
+    const char* hbn;         // the next step's
+    const char* wn;          // the next step's weight block + lane offset
+    uint32_t wd0, wd1, hd;   // LDS targets of the three copies
+    const bf16_t* wb0;       // weight copy sources = wb + woff
+    const bf16_t* wb1;
+    size_t woff;
+    const HaloTile& ht;      // halo copy: tile, this lane's halo coordinates / offset, chunk offset
+    int pk, rel, choff;
+    const bf16_t* zero16;
+    const bf16_t* p0; const bf16_t* p1; const bf16_t* ph; bool in;   // temporaries carried between slots
+};
+
+template <int COB, int K>
+__device__ __forceinline__ void step_slot(StepCtx<COB>& c) {
+    typedef StepPlan<COB> P;
+    typedef RW<COB> G;
+    constexpr typename P::M m = P::mfma(K);
+    c.acc[m.cb][m.s - m.kd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.acur[m.kd][m.cb], c.b[m.s], c.acc[m.cb][m.s - m.kd], 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < P::NR; ++r) {
+        if (P::read_slot(r) != K) continue;
+        if (r < 3) c.b[3 + r] = lds_frag(c.hb + (3 + r) * RSLICE);
+        else if (r < 3 + 3 * COB) c.an[(r - 3) / COB][(r - 3) % COB] = lds_frag(c.wn + ((r - 3) / COB) * 2 * G::WPLANE + ((r - 3) % COB) * 512);
+        else c.nb[r - 3 - 3 * COB] = lds_frag(c.hbn + (r - 3 - 3 * COB) * RSLICE);
+    }
+    if constexpr (K == P::WC0 - 1) c.p0 = c.wb0 + c.woff;
+    if constexpr (K == P::WC0) g2lds16(c.p0, c.wd0);
+    if constexpr (K == P::WC1 - 1) c.p1 = c.wb1 + c.woff;
+    if constexpr (K == P::WC1) g2lds16(c.p1, c.wd1);
+    if constexpr (K == P::HC - 2) {
+        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = c.pk >> 16;
+        c.in = (hd >= c.ht.dlo) & (hd <= c.ht.dhi) & (hh >= c.ht.hlo) & (hh <= c.ht.hhi) & (hw >= c.ht.wlo) & (hw <= c.ht.whi);
+    }
+    if constexpr (K == P::HC - 1) c.ph = c.in ? c.ht.origin + c.rel + c.choff : c.zero16;
+    if constexpr (K == P::HC) g2lds16(c.ph, c.hd);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (K + 1 < P::NM) step_slot<COB, K + 1>(c);
+}
+
+// acur / b0..b2: the fragments of this step that were read during the previous one; on return they
+// hold the same for the next step.
 template <int COB, int J>
 __device__ __forceinline__ void ring_step(f32x16 (&acc)[COB][4], bf16x8 (&acur)[3][COB], bf16x8& b0, bf16x8& b1, bf16x8& b2,
                                           const char* hb, const char* hb_nextstep, const char* w_nextstep,
-                                          uint32_t w_dst0, uint32_t w_dst1, uint32_t h_dst, const bf16_t* wsrc0,
-                                          const bf16_t* wsrc1, const bf16_t* hsrc, bool after_epilogue) {
-    typedef RW<COB> G;
+                                          uint32_t w_dst0, uint32_t w_dst1, uint32_t h_dst, const bf16_t* wb0,
+                                          const bf16_t* wb1, size_t woff, const HaloTile& ht, int pk, int rel, int choff,
+                                          const bf16_t* zero16, bool after_epilogue) {
     constexpr int kh = J / 3, kw = J % 3;
     constexpr int tapoff = (kh * RHW + kw) * 16;
     constexpr int JN = (J + 1) % 9;
     constexpr int tapoff_n = ((JN / 3) * RHW + JN % 3) * 16;
-    bf16x8 b[6], an[3][COB];
+    bf16x8 b[6], an[3][COB], nb[3];
     b[0] = b0; b[1] = b1; b[2] = b2;
-#pragma unroll
-    for (int s = 3; s < 6; ++s) b[s] = lds_frag(hb + tapoff + s * RSLICE);
-#pragma unroll
-    for (int kd = 0; kd < 3; ++kd)
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb) an[kd][cb] = lds_frag(w_nextstep + kd * 2 * G::WPLANE + cb * 512);
-    const bf16x8 nb0 = lds_frag(hb_nextstep + tapoff_n);
-    const bf16x8 nb1 = lds_frag(hb_nextstep + tapoff_n + RSLICE);
-    const bf16x8 nb2 = lds_frag(hb_nextstep + tapoff_n + 2 * RSLICE);
-    // first half: slices 0..2 (fragments carried in) with one fragment read behind each MFMA
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-#pragma unroll
-        for (int kd = 0; kd <= s; ++kd)
-#pragma unroll
-            for (int cb = 0; cb < COB; ++cb)
-                acc[cb][s - kd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(acur[kd][cb], b[s], acc[cb][s - kd], 0, 0, 0);
-    sched_interleave<0, 6 * COB, 6 + 3 * COB>();
-    __builtin_amdgcn_sched_barrier(0);
-    // second half: slices 3..5, with this step's copies and their address arithmetic in between
-    g2lds16(wsrc0, w_dst0);
-    g2lds16(wsrc1, w_dst1);
-    g2lds16(hsrc, h_dst);
-#pragma unroll
-    for (int s = 3; s < 6; ++s)
-#pragma unroll
-        for (int kd = s - 3; kd < 3; ++kd)
-#pragma unroll
-            for (int cb = 0; cb < COB; ++cb)
-                acc[cb][s - kd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(acur[kd][cb], b[s], acc[cb][s - kd], 0, 0, 0);
+    StepCtx<COB> c{acc, acur, b, an, nb, hb + tapoff, hb_nextstep + tapoff_n, w_nextstep, w_dst0, w_dst1, h_dst, wb0, wb1, woff,
+                   ht, pk, rel, choff, zero16, nullptr, nullptr, nullptr, false};
+    step_slot<COB, 0>(c);
 #pragma unroll
     for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) acur[kd][cb] = an[kd][cb];
-    b0 = nb0; b1 = nb1; b2 = nb2;
-    __builtin_amdgcn_sched_barrier(0);  // keep this step's MFMAs above the waits
+    b0 = nb[0]; b1 = nb[1]; b2 = nb[2];
     // Vector memory operations complete in issue order: leaving RINFLIGHT steps' worth in flight
     // guarantees that everything issued RINFLIGHT or more steps ago has landed -- the weight block two
     // steps ahead (issued 7 steps ago) and every older halo copy.  In the first RINFLIGHT steps after an
@@ -313,9 +355,8 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         const int wsl1 = wsl == RNWSLOT - 1 ? 0 : wsl + 1;                                                            \
         const uint32_t wd = wring_a + wsl * G::WBLOCK;                                                                \
         ring_step<COB, J>(acc, acur, b0, b1, b2, hb, (J < 8 ? hb : hbn), wring + wsl1 * G::WBLOCK + a_base,            \
-                          wd + we0 * 16, wd + we1 * 16, hdst + hoff[J], wslab0 + (size_t)t9 * G::WBLOCK_ELEMS,          \
-                          wslab1 + (size_t)t9 * G::WBLOCK_ELEMS, halo_src(ht, J, choff),                            \
-                          J < RINFLIGHT && chunk == 0 && epi_full);                             \
+                          wd + we0 * 16, wd + we1 * 16, hdst + hoff[J], wslab0, wslab1, (size_t)t9 * G::WBLOCK_ELEMS,  \
+                          ht, hpk[J], hrel[J], choff, a.zero16, J < RINFLIGHT && chunk == 0 && epi_full);             \
         wsl = wsl1;                                                                                                   \
     }
             RING_STEP(0) RING_STEP(1) RING_STEP(2) RING_STEP(3) RING_STEP(4) RING_STEP(5) RING_STEP(6) RING_STEP(7)

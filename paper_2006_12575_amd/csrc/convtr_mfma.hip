@@ -196,9 +196,11 @@ lamp_status mfma_convtr_dgrad(const lamp_tensor_desc* xd, const void* wt, const 
 // Workgroup = 4 waves on (split s, 64-wide ci block, 32-wide co block); wave w owns taps 2w, 2w+1.
 // Chunks of 64 coarse voxels are staged in LDS (x rows of 128 bytes, dy rows of 64 bytes per tap,
 // double buffered, register-free copies) and read with the transposing LDS load.
+// (inline assembly, so that the compiler's wait-count bookkeeping does not see the copies and keeps
+// partial waits for the fragment reads; completion is tracked by hand)
 __device__ __forceinline__ void g2lds16_ct(const void* g, char* lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+    const uint32_t m = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m), "v"(g) : "memory", "m0");
 }
 template <int ROWB> __device__ __forceinline__ bf16x8 frag_tr(const char* p) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(256) void convtr_wgrad_mfma_kernel(CtWArgs a) {
         __builtin_amdgcn_sched_barrier(0);
         ctw_compute(acc, lds + par * CTW_STAGE, wv, lane);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     }
