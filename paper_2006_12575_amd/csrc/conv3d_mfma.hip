@@ -428,8 +428,12 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     int td, th, tw;
     tile_dims(zd, 4, td, th, tw);  // the finer tiling bounds the partial count
     const size_t tiles = (size_t)td * th * tw;
-    size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 16);
-    if (want_stats) b += align_up((size_t)zd->n * tiles * zd->c * 2 * sizeof(float)) + align_up(tiles * sizeof(int32_t));
+    size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 64);  // + 16 zero bytes + 16 bytes that absorb masked stores
+    if (want_stats) {
+        // partial statistics: one per tile (tiled kernel) or one per wave of a workgroup (ring kernel, <= 1024)
+        const size_t parts = tiles > 1024 ? tiles : 1024;
+        b += align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * parts * sizeof(int32_t));
+    }
     return b;
 }
 

@@ -9,16 +9,21 @@
 //    slice s = d + kd serves output slices d = s, s-1, s-2 with the weights of kd = 0, 1, 2: six slice
 //    fragments and 3*COB weight fragments feed 12*COB MFMAs.
 //  * LDS holds a ring of 3 halo regions, each one 16-channel chunk of a tile's 6 x 10 x 18 halo (two
-//    planes of 16-byte voxel entries), and a ring of 9 weight blocks (3 taps x 16 ci x 32*COB co).
-//    Region (q+2)%3 is refilled for chunk-step q+2 while chunk-step q is multiplied, weight block s%9
-//    for step s+9 while step s is multiplied, both by register-free global -> LDS copies.  Copies
+//    planes of 16-byte voxel entries), and a ring of 8 weight blocks (3 taps x 16 ci x 32*COB co).
+//    Region (q+2)%3 is refilled for chunk-step q+2 while chunk-step q is multiplied, weight block s%8
+//    for step s+8 while step s is multiplied, both by register-free global -> LDS copies.  Copies
 //    complete in issue order, so the long weight ring is what lets a halo copy that misses every
-//    cache stay in flight for 7 steps without holding up the weights behind it.
+//    cache stay in flight for 6 steps without holding up the weights behind it.
 //  * One step = one (chunk, kh, kw); a barrier per step publishes the copies two steps ahead of their
 //    use, so fragment reads for step s+1 are issued inside step s and the MFMA stream never drains.
+//  * With one wave per SIMD nothing runs while a wave converts and stores its results, so the epilogue
+//    of a tile is cut into small units (convert + write to a private LDS patch; read a voxel row back,
+//    store it, add it to the channel sums) that ride in the steps of the NEXT tile, which accumulates
+//    into a second set of registers.
 //  * A persistent workgroup walks a run of tiles that is contiguous in d, so the two halo slices shared
 //    by successive tiles are re-read from cache soon after their first use.
 #include <stdlib.h>
+#include <type_traits>
 #include "internal.h"
 
 namespace lamp {
@@ -36,9 +41,10 @@ constexpr int RNREG = 3;
 constexpr int RSLICE = RHH * RHW * 16;       // bytes between halo d-slices of a plane
 constexpr int RHENTRIES = 2 * RHALO_VOX;     // 16-byte entries of a region: 36 wave copies, 9 per wave, copy k
 constexpr int RHSTEP = 60;                   // starts at entry min(60k, 2160-64) (neighbours overlap by 4 entries)
-constexpr int RNWSLOT = 9;                  // weight ring: block of step s + 9 replaces block s
-constexpr int RINFLIGHT = 7;                // steps whose copies may still be in flight at a step's end
-constexpr int REPI_STORES = 16;             // output stores a wave issues in the epilogue of a tile inside the volume
+constexpr int RNWSLOT = 8;                  // weight ring: block of step s + 8 replaces block s
+constexpr int RINFLIGHT = 6;                // steps whose copies may still be in flight at a step's end
+constexpr int RPATCH_ROW = 80;              // epilogue patch row: 32 channels (64 bytes) + 16 bytes of padding
+constexpr int RPATCH = 32 * RPATCH_ROW;     // one wave's patch: the 32 voxels of a block
 
 template <int COB> struct RW {
     static constexpr int WROWS = 32 * COB;
@@ -47,16 +53,17 @@ template <int COB> struct RW {
     static constexpr int WBLOCK_ELEMS = WBLOCK / 2;
     static constexpr int WENTRIES = 6 * WROWS;       // 16-byte entries of a block: 8 wave copies, 2 per wave, copy u
     static constexpr int USTEP = WENTRIES / 8;       // starts at entry min(u * USTEP, WENTRIES - 64)
-    static constexpr int LDS_BYTES = RNREG * RREGION + RNWSLOT * WBLOCK;
+    static constexpr int LDS_BYTES = RNREG * RREGION + RNWSLOT * WBLOCK + 4 * RPATCH;
 };
 
 struct RingArgs {
     const bf16_t* x; int ldx;
     const bf16_t* wp;
     bf16_t* z; int ldz;
-    float* part;           // [N][tiles_per_n][Cout][2] or nullptr
-    int32_t* counts;       // [tiles_per_n] in-volume voxels per tile (written when part != nullptr)
+    float* part;           // [N][4 * workgroups][Cout][2]: per-wave partial (sum, sum of squares), or nullptr
+    int32_t* counts;       // [N][4 * workgroups]: voxels behind each partial (written when part != nullptr)
     const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
+    bf16_t* dump;          // 16 bytes in global memory that absorb the stores of voxels outside the volume
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd, tiles_per_wg;
 };
@@ -145,6 +152,100 @@ template <int COB> struct StepPlan {
     static constexpr int WC0 = COB == 2 ? 9 : 3, WC1 = COB == 2 ? 11 : 5, HC = COB == 2 ? 15 : 8;
 };
 
+// ---- epilogue of the previous ("pending") tile.  Its results, converted to bf16 pairs when the tile
+// ended, sit in a second register set `pend` (lane = voxel of a 32-voxel block, 4 consecutive channels
+// = 2 registers per register group).  The epilogue runs in 2*COB phases, one per chunk-step: phase p
+// handles channel block p / 2 and d-slices 2 * (p % 2), 2 * (p % 2) + 1, three steps each:
+//   unit A(rg), rg = 0..3 : write 4 channels to the wave's LDS patch (32 voxel rows of 64 bytes)
+//   unit B(i),  i = 0..1  : 4 lanes read back one voxel row (16 rows per instruction), store its 64 bytes
+//                           and add the stored values to this lane's channel sums
+// There is one copy of the code for all phases: `pend` is rotated after every phase so that the data
+// of the next one sits in front, and the channel sums of the two blocks swap places when the block
+// changes.  With nothing pending the units still run, on a dump address and with the sums masked off.
+// The channel sums run on across the tiles of the walk and are written once per sample.
+template <int COB> struct EpiCtx {
+    uint32_t (&pend)[2 * COB][2][8];
+    float (&csum)[8];
+    float (&csq)[8];
+    char* patch_w;        // patch + l32 * RPATCH_ROW + half * 8      (unit A adds rg * 16)
+    const char* patch_r;  // patch + (lane / 4) * RPATCH_ROW + (lane % 4) * 16   (unit B adds i * 16 rows)
+    bf16_t* zp[2];        // output address of this lane's row of group i in d-slice 0, channel block 0
+    bool okl[2];          // that row's (h, w) lies inside the volume (and a phase is in progress)
+    int64_t dstride;      // elements between d-slices of the output
+    int64_t poff;         // element offset of the phase: first d-slice and channel block
+    int dleft;            // d-slices inside the volume, counted from the phase's first
+    bf16_t* dump;
+    uint4 q;              // row in flight between the slots of a unit B
+    bf16_t* qp;
+};
+
+template <int COB, int DD, int RG>
+__device__ __forceinline__ void epi_unit_a(EpiCtx<COB>& e) {
+    *reinterpret_cast<uint2*>(e.patch_w + RG * 16) = make_uint2(e.pend[0][DD][RG * 2], e.pend[0][DD][RG * 2 + 1]);
+}
+template <int COB, int I> __device__ __forceinline__ void epi_unit_b_read(EpiCtx<COB>& e) {
+    e.q = *reinterpret_cast<const uint4*>(e.patch_r + I * 16 * RPATCH_ROW);
+}
+template <int COB, int DD, int I> __device__ __forceinline__ void epi_unit_b_addr(EpiCtx<COB>& e) {
+    const bool ok = e.okl[I] & (DD < e.dleft);
+    e.qp = ok ? e.zp[I] + (e.poff + DD * e.dstride) : e.dump;
+}
+// store the row, then clear it unless it counts for the channel sums
+template <int COB, int DD, int I> __device__ __forceinline__ void epi_unit_b_store(EpiCtx<COB>& e) {
+    // streaming store: the output is not read again by this kernel and should not displace the input
+    // lines that the next chunk passes and the neighbouring tiles still need
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    const u32x4 sv = {e.q.x, e.q.y, e.q.z, e.q.w};
+    __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(e.qp));
+    const uint32_t m = (e.okl[I] & (DD < e.dleft)) ? 0xFFFFFFFFu : 0u;
+    e.q.x &= m; e.q.y &= m; e.q.z &= m; e.q.w &= m;
+}
+template <int COB, int E> __device__ __forceinline__ void epi_unit_b_stats(EpiCtx<COB>& e) {
+    const uint32_t r = E == 0 ? e.q.x : E == 1 ? e.q.y : E == 2 ? e.q.z : e.q.w;
+    const float f0 = __uint_as_float(r << 16), f1 = __uint_as_float(r & 0xFFFF0000u);
+    e.csum[2 * E] += f0;
+    e.csq[2 * E] = fmaf(f0, f0, e.csq[2 * E]);
+    e.csum[2 * E + 1] += f1;
+    e.csq[2 * E + 1] = fmaf(f1, f1, e.csq[2 * E + 1]);
+}
+// A whole phase in one go (used where no step is left to carry the units).
+template <int COB> __device__ __forceinline__ void epi_phase_serial(EpiCtx<COB>& e) {
+    auto one_d = [&](auto dt) __attribute__((always_inline)) {
+        constexpr int DD = decltype(dt)::value;
+        epi_unit_a<COB, DD, 0>(e); epi_unit_a<COB, DD, 1>(e); epi_unit_a<COB, DD, 2>(e); epi_unit_a<COB, DD, 3>(e);
+        epi_unit_b_read<COB, 0>(e); epi_unit_b_addr<COB, DD, 0>(e); epi_unit_b_store<COB, DD, 0>(e);
+        epi_unit_b_stats<COB, 0>(e); epi_unit_b_stats<COB, 1>(e); epi_unit_b_stats<COB, 2>(e); epi_unit_b_stats<COB, 3>(e);
+        epi_unit_b_read<COB, 1>(e); epi_unit_b_addr<COB, DD, 1>(e); epi_unit_b_store<COB, DD, 1>(e);
+        epi_unit_b_stats<COB, 0>(e); epi_unit_b_stats<COB, 1>(e); epi_unit_b_stats<COB, 2>(e); epi_unit_b_stats<COB, 3>(e);
+    };
+    one_d(std::integral_constant<int, 0>{});
+    one_d(std::integral_constant<int, 1>{});
+}
+// The share of slot K of step J: steps 0..2 carry unit A x 4, unit B(0), unit B(1) of the phase's first
+// d-slice, steps 3..5 those of its second.
+template <int COB, int J, int K>
+__device__ __forceinline__ void epi_slot(EpiCtx<COB>& e) {
+    if constexpr (J < 6) {
+        constexpr int DD = J / 3, PH = J % 3;
+        constexpr int S = COB == 2 ? 2 : 1;   // slot stride: the step has 24 or 12 slots
+        if constexpr (PH == 0) {
+            if constexpr (K == 1 * S) epi_unit_a<COB, DD, 0>(e);
+            if constexpr (K == 3 * S) epi_unit_a<COB, DD, 1>(e);
+            if constexpr (K == 5 * S) epi_unit_a<COB, DD, 2>(e);
+            if constexpr (K == 7 * S) epi_unit_a<COB, DD, 3>(e);
+        } else {
+            constexpr int I = PH - 1;
+            if constexpr (K == 0) epi_unit_b_read<COB, I>(e);
+            if constexpr (K == 1 * S) epi_unit_b_addr<COB, DD, I>(e);
+            if constexpr (K == 3 * S) epi_unit_b_store<COB, DD, I>(e);
+            if constexpr (K == 4 * S) epi_unit_b_stats<COB, 0>(e);
+            if constexpr (K == 5 * S) epi_unit_b_stats<COB, 1>(e);
+            if constexpr (K == 8 * S) epi_unit_b_stats<COB, 2>(e);
+            if constexpr (K == 9 * S) epi_unit_b_stats<COB, 3>(e);
+        }
+    }
+}
+
 template <int COB> struct StepCtx {
     f32x16 (&acc)[COB][4];
     bf16x8 (&acur)[3][COB];
@@ -159,13 +260,14 @@ template <int COB> struct StepCtx {
     const bf16_t* wb1;
     size_t woff;
     const HaloTile& ht;      // halo copy: tile, this lane's halo coordinates / offset, chunk offset
-    int pk, rel, choff;
+    int pk, choff;           //   (pk = hd | hh << 8 | hw << 16 | plane << 24)
+    int H, W, ldx;
     const bf16_t* zero16;
     const bf16_t* p0; const bf16_t* p1; const bf16_t* ph; bool in;   // temporaries carried between slots
 };
 
-template <int COB, int K>
-__device__ __forceinline__ void step_slot(StepCtx<COB>& c) {
+template <int COB, int J, int K>
+__device__ __forceinline__ void step_slot(StepCtx<COB>& c, EpiCtx<COB>& e) {
     typedef StepPlan<COB> P;
     typedef RW<COB> G;
     constexpr typename P::M m = P::mfma(K);
@@ -182,13 +284,20 @@ __device__ __forceinline__ void step_slot(StepCtx<COB>& c) {
     if constexpr (K == P::WC1 - 1) c.p1 = c.wb1 + c.woff;
     if constexpr (K == P::WC1) g2lds16(c.p1, c.wd1);
     if constexpr (K == P::HC - 2) {
-        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = c.pk >> 16;
+        // (opaque to the optimiser: otherwise the address arithmetic below, which does not change from
+        // tile to tile, is hoisted out of the loops for all nine steps and costs dozens of registers)
+        asm volatile("" : "+v"(c.pk));
+        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255;
         c.in = (hd >= c.ht.dlo) & (hd <= c.ht.dhi) & (hh >= c.ht.hlo) & (hh <= c.ht.hhi) & (hw >= c.ht.wlo) & (hw <= c.ht.whi);
     }
-    if constexpr (K == P::HC - 1) c.ph = c.in ? c.ht.origin + c.rel + c.choff : c.zero16;
+    if constexpr (K == P::HC - 1) {
+        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255, plane = c.pk >> 24;
+        c.ph = c.in ? c.ht.origin + (((hd * c.H + hh) * c.W + hw) * c.ldx + plane * 8 + c.choff) : c.zero16;
+    }
     if constexpr (K == P::HC) g2lds16(c.ph, c.hd);
+    epi_slot<COB, J, K>(e);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (K + 1 < P::NM) step_slot<COB, K + 1>(c);
+    if constexpr (K + 1 < P::NM) step_slot<COB, J, K + 1>(c, e);
 }
 
 // acur / b0..b2: the fragments of this step that were read during the previous one; on return they
@@ -197,8 +306,8 @@ template <int COB, int J>
 __device__ __forceinline__ void ring_step(f32x16 (&acc)[COB][4], bf16x8 (&acur)[3][COB], bf16x8& b0, bf16x8& b1, bf16x8& b2,
                                           const char* hb, const char* hb_nextstep, const char* w_nextstep,
                                           uint32_t w_dst0, uint32_t w_dst1, uint32_t h_dst, const bf16_t* wb0,
-                                          const bf16_t* wb1, size_t woff, const HaloTile& ht, int pk, int rel, int choff,
-                                          const bf16_t* zero16, bool after_epilogue) {
+                                          const bf16_t* wb1, size_t woff, const HaloTile& ht, int pk, int choff, int H,
+                                          int W, int ldx, const bf16_t* zero16, EpiCtx<COB>& e) {
     constexpr int kh = J / 3, kw = J % 3;
     constexpr int tapoff = (kh * RHW + kw) * 16;
     constexpr int JN = (J + 1) % 9;
@@ -206,19 +315,18 @@ __device__ __forceinline__ void ring_step(f32x16 (&acc)[COB][4], bf16x8 (&acur)[
     bf16x8 b[6], an[3][COB], nb[3];
     b[0] = b0; b[1] = b1; b[2] = b2;
     StepCtx<COB> c{acc, acur, b, an, nb, hb + tapoff, hb_nextstep + tapoff_n, w_nextstep, w_dst0, w_dst1, h_dst, wb0, wb1, woff,
-                   ht, pk, rel, choff, zero16, nullptr, nullptr, nullptr, false};
-    step_slot<COB, 0>(c);
+                   ht, pk, choff, H, W, ldx, zero16, nullptr, nullptr, nullptr, false};
+    step_slot<COB, J, 0>(c, e);
 #pragma unroll
     for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) acur[kd][cb] = an[kd][cb];
     b0 = nb[0]; b1 = nb[1]; b2 = nb[2];
-    // Vector memory operations complete in issue order: leaving RINFLIGHT steps' worth in flight
+    // Vector memory operations complete in issue order: leaving the copies of RINFLIGHT steps in flight
     // guarantees that everything issued RINFLIGHT or more steps ago has landed -- the weight block two
-    // steps ahead (issued 7 steps ago) and every older halo copy.  In the first RINFLIGHT steps after an
-    // epilogue the window also holds that epilogue's output stores, which need not be waited for.
-    if (after_epilogue) wait_vmcnt<3 * RINFLIGHT + REPI_STORES>();
-    else wait_vmcnt<3 * RINFLIGHT>();
+    // steps ahead (issued 6 steps ago) and every older halo copy.  (Output stores issued in between only
+    // make the wait reach further back.)
+    wait_vmcnt<3 * RINFLIGHT>();
     // bare barrier: __syncthreads() would add a release fence that drains every copy in flight
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
@@ -246,6 +354,9 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile_lo = xcd * a.tiles_per_xcd + local * a.tiles_per_wg;
     const int tile_hi = min(tile_lo + a.tiles_per_wg, min((xcd + 1) * a.tiles_per_xcd, a.tiles_total));
+    // voxel counts behind this wave's partial statistics: zero for the samples it never visits
+    if (a.counts && lane == 0 && blockIdx.y == 0)
+        for (int n = 0; n < a.N; ++n) a.counts[n * (gridDim.x * 4) + blockIdx.x * 4 + wv] = 0;
     if (tile_lo >= tile_hi) return;
 
     // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read is serviced for
@@ -259,7 +370,7 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
 
     // ---- per-lane constants of the copies.  Halo copy slot k = J*4 + wv covers entries 60k .. 60k+59 of
     // a region (entry = plane*1080 + halo voxel): rel = element offset from the tile's halo origin.
-    int hrel[9], hpk[9], hoff[9];
+    int hpk[9], hoff[9];   // hd | hh << 8 | hw << 16 | plane << 24 of this lane's entry; LDS offset of the copy
 #pragma unroll
     for (int j = 0; j < 9; ++j) {
         const int e0 = min((j * 4 + wv) * RHSTEP, RHENTRIES - 64);
@@ -267,14 +378,13 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         hoff[j] = e0 * 16;
         const int plane = e / RHALO_VOX, hv = e - plane * RHALO_VOX;
         const int hw = hv % RHW, hh = (hv / RHW) % RHH, hd = hv / (RHW * RHH);
-        hrel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx + plane * 8;
-        hpk[j] = hd | (hh << 8) | (hw << 16);
+        hpk[j] = hd | (hh << 8) | (hw << 16) | (plane << 24);
     }
     const int we0 = min(wv * G::USTEP, G::WENTRIES - 64), we1 = min((wv + 4) * G::USTEP, G::WENTRIES - 64);
     const bf16_t* wslab0 = a.wp + (size_t)blockIdx.y * 27 * a.Cin * WROWS + (we0 + lane) * 8;
     const bf16_t* wslab1 = a.wp + (size_t)blockIdx.y * 27 * a.Cin * WROWS + (we1 + lane) * 8;
 
-    auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
+    auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) __attribute__((always_inline)) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
         d0 = (r % a.tiles_d) * RTD;
@@ -282,7 +392,7 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         w0 = (r % a.tiles_w) * RTW;
         h0 = (r / a.tiles_w) * RTH;
     };
-    auto halo_tile = [&](int tile) {
+    auto halo_tile = [&](int tile) __attribute__((always_inline)) {
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
         HaloTile t;
@@ -292,9 +402,9 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     };
     auto halo_src = [&](const HaloTile& t, int j, int choff) -> const bf16_t* {
         const int pk = hpk[j];
-        const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+        const int hd = pk & 255, hh = (pk >> 8) & 255, hw = (pk >> 16) & 255, plane = pk >> 24;
         const bool in = (hd >= t.dlo) & (hd <= t.dhi) & (hh >= t.hlo) & (hh <= t.hhi) & (hw >= t.wlo) & (hw <= t.whi);
-        return in ? t.origin + hrel[j] + choff : a.zero16;
+        return in ? t.origin + (((hd * a.H + hh) * a.W + hw) * a.ldx + plane * 8 + choff) : a.zero16;
     };
 
     // ---- prologue: halo of chunk-steps 0 and 1, weights of steps 0..8
@@ -326,18 +436,114 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     b2 = lds_frag(hreg + b_base + 2 * RSLICE);
 
     int rq = 0;                                  // chunk-step counter mod 3: the region being multiplied
-    int wsl = 0;                                 // step counter mod 9: the weight slot being multiplied
+    int wsl = 0;                                 // step counter mod 8: the weight slot being multiplied
     int pf_tile = tile_lo + 2 / nchunks, pf_chunk = 2 % nchunks;   // halo prefetch cursor = chunk-step q + 2
-    bool epi_full = false;   // the previous tile of the walk lay inside the volume (all its output stores were issued)
-    for (int tile = tile_lo; tile < tile_hi; ++tile) {
-        f32x16 acc[COB][4];
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[cb][d][r] = 0.f;
 
+    // ---- the pending tile: results of the previous tile of the walk, on their way out
+    constexpr int NPH = 2 * COB;
+    f32x16 acc[COB][4];
+    uint32_t pend[NPH][2][8];        // phase-major: pend[cb * 2 + dp][dd] = block cb of d-slice 2 * dp + dd
+    float csum[8], csq[8];           // channel sums of the block in progress ...
+    float osum[8], osq[8];           // ... and of the other block (COB == 2)
+    char* const patch = lds + RNREG * RREGION + RNWSLOT * G::WBLOCK + wv * RPATCH;
+    EpiCtx<COB> ec{pend, csum, csq, patch + l32 * RPATCH_ROW + half * 8, patch + (lane >> 2) * RPATCH_ROW + (lane & 3) * 16,
+                   {a.dump, a.dump}, {false, false}, (int64_t)a.H * a.W * a.ldz, 0, 0, a.dump, make_uint4(0, 0, 0, 0), a.dump};
+    bool okt[2] = {false, false};   // (h, w) of this lane's two rows of the pending tile lie inside the volume
+    int dvalid = 0;                  // d-slices of the pending tile inside the volume
+    int epi_p = NPH;                 // next phase of the pending tile to go out (NPH: nothing pending)
+    int stat_n = -1;                 // sample the running channel sums belong to
+    int stat_vox = 0;                // voxels (of this wave) in them
+    const int spart = blockIdx.x * 4 + wv, sparts = gridDim.x * 4;   // this wave's slot in the partial statistics
+
+    // set the context up for phase epi_p
+    auto phase_setup = [&]() __attribute__((always_inline)) {
+        const bool act = epi_p < NPH;
+        const int cb = epi_p >> 1, dp = epi_p & 1;
+        ec.okl[0] = okt[0] && act;
+        ec.okl[1] = okt[1] && act;
+        ec.poff = (int64_t)(2 * dp) * ec.dstride + cb * 32;
+        ec.dleft = dvalid - 2 * dp;
+    };
+    // a phase is done: bring the next one's data to the front
+    auto phase_advance = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p + 1 < NPH; ++p)
+#pragma unroll
+            for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+                for (int r = 0; r < 8; ++r) pend[p][dd][r] = pend[p + 1][dd][r];
+        if (epi_p < NPH) {
+            if (COB == 2 && (epi_p & 1)) {   // the channel block changes
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float t0 = csum[e], t1 = csq[e];
+                    csum[e] = osum[e]; csq[e] = osq[e];
+                    osum[e] = t0; osq[e] = t1;
+                }
+            }
+            ++epi_p;
+        }
+        phase_setup();
+    };
+    // Flush what is left of the pending tile.
+    auto finish_pending = [&]() __attribute__((always_inline)) {
+        while (epi_p < NPH) {
+            epi_phase_serial<COB>(ec);
+            phase_advance();
+        }
+    };
+    // Write the running channel sums as this wave's partial statistics of sample stat_n and clear them.
+    // (Called between tiles only: csum/csq then hold block 0 and osum/osq block 1.)
+    auto flush_stats = [&]() __attribute__((always_inline)) {
+        if (a.part && stat_n >= 0) {
+            // lanes with equal lane % 4 hold the same 8 channels of a block: fold the other lane bits
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int m = 4; m < 64; m <<= 1) {
+                    csum[e] += __shfl_xor(csum[e], m);
+                    csq[e] += __shfl_xor(csq[e], m);
+                    if (COB == 2) {
+                        osum[e] += __shfl_xor(osum[e], m);
+                        osq[e] += __shfl_xor(osq[e], m);
+                    }
+                }
+            if (lane < 4) {
+                float* pp = a.part + (((int64_t)stat_n * sparts + spart) * a.Cout + co0 + lane * 8) * 2;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pp[e * 2 + 0] = csum[e];
+                    pp[e * 2 + 1] = csq[e];
+                    if (COB == 2) {
+                        pp[(32 + e) * 2 + 0] = osum[e];
+                        pp[(32 + e) * 2 + 1] = osq[e];
+                    }
+                }
+            }
+            if (lane == 0 && blockIdx.y == 0) a.counts[stat_n * sparts + spart] = stat_vox;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; osum[e] = 0.f; osq[e] = 0.f; }
+        stat_vox = 0;
+    };
+
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; osum[e] = 0.f; osq[e] = 0.f; }
+#pragma unroll
+    for (int p = 0; p < NPH; ++p)
+#pragma unroll
+        for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) pend[p][dd][r] = 0u;
+#pragma unroll
+    for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][d][r] = 0.f;
+    phase_setup();
+
+    for (int tile = tile_lo; tile < tile_hi; ++tile) {
         for (int chunk = 0; chunk < nchunks; ++chunk) {
             const int rq1 = rq == 2 ? 0 : rq + 1, rq2 = rq == 0 ? 2 : rq - 1;
             const char* hb = hreg + rq * RREGION + b_base;
@@ -350,110 +556,53 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
             const int t0 = chunk * 9;
 #define RING_STEP(J)                                                                                                  \
     {                                                                                                                 \
-        int t9 = t0 + J + RNWSLOT;                                                                                    \
-        if (t9 >= spt) t9 -= spt;                                                                                     \
+        int t8 = t0 + J + RNWSLOT;                                                                                    \
+        if (t8 >= spt) t8 -= spt;                                                                                     \
         const int wsl1 = wsl == RNWSLOT - 1 ? 0 : wsl + 1;                                                            \
         const uint32_t wd = wring_a + wsl * G::WBLOCK;                                                                \
         ring_step<COB, J>(acc, acur, b0, b1, b2, hb, (J < 8 ? hb : hbn), wring + wsl1 * G::WBLOCK + a_base,            \
-                          wd + we0 * 16, wd + we1 * 16, hdst + hoff[J], wslab0, wslab1, (size_t)t9 * G::WBLOCK_ELEMS,  \
-                          ht, hpk[J], hrel[J], choff, a.zero16, J < RINFLIGHT && chunk == 0 && epi_full);             \
+                          wd + we0 * 16, wd + we1 * 16, hdst + hoff[J], wslab0, wslab1, (size_t)t8 * G::WBLOCK_ELEMS,  \
+                          ht, hpk[J], choff, a.H, a.W, a.ldx, a.zero16, ec);                                          \
         wsl = wsl1;                                                                                                   \
     }
             RING_STEP(0) RING_STEP(1) RING_STEP(2) RING_STEP(3) RING_STEP(4) RING_STEP(5) RING_STEP(6) RING_STEP(7)
             RING_STEP(8)
 #undef RING_STEP
+            phase_advance();
             if (++pf_chunk == nchunks) { pf_chunk = 0; ++pf_tile; }
             rq = rq1;
         }
 
-        // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
-        // register group) into voxel rows through a private LDS patch, so that 8 lanes store one full
-        // row of 64 channels; the channel sums of the stored values come from the same pass.
-        // Scratch: the region of the chunk-step just finished (its refill starts with the next step).
+        // ---- tile end: the previous tile must be out before this one takes its place
+        finish_pending();
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
-        char* fbuf = hreg + (rq == 0 ? 2 : rq - 1) * RREGION;   // rq was advanced past the last chunk-step
-        constexpr int ROWB = WROWS * 2 + 16;           // padded row of the patch
-        constexpr int PARTS = WROWS / 8;               // 16-byte parts per row: 8 or 4
-        constexpr int RPI = 64 / PARTS;                // rows covered per read instruction
-        char* patch = fbuf + wv * (32 * ROWB);
-        float* sred = reinterpret_cast<float*>(fbuf + 4 * 32 * (64 * 2 + 16));
-        const int part = lane % PARTS, prow = lane / PARTS;
-        float csum[8], csq[8];
+        if (n != stat_n) { flush_stats(); stat_n = n; }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; }
+        for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int gd = d0 + d;
+            for (int d = 0; d < 4; ++d) {
 #pragma unroll
-            for (int cb = 0; cb < COB; ++cb)
+                for (int r = 0; r < 8; ++r) pend[cb * 2 + (d >> 1)][d & 1][r] = pack_bf16(acc[cb][d][2 * r], acc[cb][d][2 * r + 1]);
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const uint32_t p0 = pack_bf16(acc[cb][d][rg * 4 + 0], acc[cb][d][rg * 4 + 1]);
-                    const uint32_t p1 = pack_bf16(acc[cb][d][rg * 4 + 2], acc[cb][d][rg * 4 + 3]);
-                    *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
-                }
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
-                const uint4 qv = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
-                const int rg8 = row >> 3;
-                const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
-                const int gh = h0 + 2 * wv + rh, gw = w0 + rw;
-                const bool ok = gd < a.D && gh < a.H && gw < a.W;
-                if (ok) {
-                    // streaming store: the output is not read again by this kernel and should not displace the
-                    // input lines that the next chunk passes and the neighbouring tiles still need
-                    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-                    const u32x4 sv = {qv.x, qv.y, qv.z, qv.w};
-                    __builtin_nontemporal_store(
-                        sv, reinterpret_cast<u32x4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8));
-                    const uint32_t r4[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
-                        csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
-                        csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
-                    }
-                }
+                for (int r = 0; r < 16; ++r) acc[cb][d][r] = 0.f;
             }
-            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = (lane >> 2) + 16 * i;   // voxel index inside the 32-voxel block
+            const int rg8 = row >> 3;
+            const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
+            const int gh = h0 + 2 * wv + rh, gw = w0 + rw;
+            okt[i] = gh < a.H && gw < a.W;
+            ec.zp[i] = a.z + ((((int64_t)n * a.D + d0) * a.H + gh) * a.W + gw) * a.ldz + co0 + (lane & 3) * 8;
         }
-        if (a.part) {
-            // lanes with equal `part` hold the same 8 channels: fold them (lane bits above log2(PARTS))
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-#pragma unroll
-                for (int m = PARTS; m < 64; m <<= 1) {
-                    csum[e] += __shfl_xor(csum[e], m);
-                    csq[e] += __shfl_xor(csq[e], m);
-                }
-            }
-            if (lane < PARTS) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    sred[(wv * 64 + part * 8 + e) * 2 + 0] = csum[e];
-                    sred[(wv * 64 + part * 8 + e) * 2 + 1] = csq[e];
-                }
-            }
-            __builtin_amdgcn_s_waitcnt(0xC07F);  // LDS writes done; a bare barrier leaves the output stores in flight
-            __builtin_amdgcn_s_barrier();
-            if (tid < WROWS * 2) {
-                const int c = tid >> 1, k = tid & 1;
-                float v = 0.f;
-#pragma unroll
-                for (int w4 = 0; w4 < 4; ++w4) v += sred[(w4 * 64 + c) * 2 + k];
-                a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
-            }
-            if (a.counts && tid == 0 && n == 0 && blockIdx.y == 0)
-                a.counts[tile] = min(RTD, a.D - d0) * min(RTH, a.H - h0) * min(RTW, a.W - w0);
-        }
-        // the patch region is the next step's prefetch target (bare barrier: the output stores stay in flight)
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __builtin_amdgcn_s_barrier();
-        epi_full = d0 + RTD <= a.D && h0 + RTH <= a.H && w0 + RTW <= a.W;
+        dvalid = min(RTD, a.D - d0);
+        stat_vox += dvalid * max(0, min(2, a.H - (h0 + 2 * wv))) * min(RTW, a.W - w0);
+        epi_p = 0;
+        phase_setup();
     }
+    finish_pending();
+    flush_stats();
     wait_vmcnt<0>();  // the last steps' copies may still be in flight
 }
 
@@ -479,12 +628,19 @@ lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     const int td = (zd->d + RTD - 1) / RTD, th = (zd->h + RTH - 1) / RTH, tw = (zd->w + RTW - 1) / RTW;
     const int tiles_per_n = td * th * tw;
     Carver cv(ws, ws_bytes);
-    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 16);
+    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 64);
+    // launch shape first: the statistics partials are per wave of a workgroup ([N][4 * workgroups][C][2])
+    const int tiles_total = tiles_per_n * zd->n;
+    const int tiles_per_xcd = (tiles_total + 7) / 8;
+    int wg_per_xcd = tiles_per_xcd < 32 ? tiles_per_xcd : 32;  // one persistent workgroup per CU (LDS-limited)
+    const int tiles_per_wg = (tiles_per_xcd + wg_per_xcd - 1) / wg_per_xcd;
+    wg_per_xcd = (tiles_per_xcd + tiles_per_wg - 1) / tiles_per_wg;
+    const int sparts = 8 * wg_per_xcd * 4;
     float* part = nullptr;
     int32_t* counts = nullptr;
     if (stats_out) {
-        part = (float*)cv.take((size_t)zd->n * tiles_per_n * zd->c * 2 * sizeof(float));
-        counts = (int32_t*)cv.take((size_t)tiles_per_n * sizeof(int32_t));
+        part = (float*)cv.take((size_t)zd->n * sparts * zd->c * 2 * sizeof(float));
+        counts = (int32_t*)cv.take((size_t)zd->n * sparts * sizeof(int32_t));
     }
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
@@ -495,17 +651,14 @@ lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     RingArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;
+    a.dump = wp + (size_t)27 * xd->c * zd->c + 16;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
-    a.tiles_total = tiles_per_n * zd->n;
-    a.tiles_per_xcd = (a.tiles_total + 7) / 8;
-    int wg_per_xcd = a.tiles_per_xcd < 32 ? a.tiles_per_xcd : 32;  // one persistent workgroup per CU (LDS-limited)
-    a.tiles_per_wg = (a.tiles_per_xcd + wg_per_xcd - 1) / wg_per_xcd;
-    wg_per_xcd = (a.tiles_per_xcd + a.tiles_per_wg - 1) / a.tiles_per_wg;
+    a.tiles_total = tiles_total; a.tiles_per_xcd = tiles_per_xcd; a.tiles_per_wg = tiles_per_wg;
     dim3 grid(8 * wg_per_xcd, zd->c / (32 * cob));
     lamp_status st = cob == 2 ? launch_ring<2>(a, grid, s) : launch_ring<1>(a, grid, s);
     if (st != LAMP_OK) return st;
-    if (stats_out) return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);
+    if (stats_out) return launch_stats_finalize(part, counts, sparts, zd->n, zd->c, eps, stats_out, s, true);
     return LAMP_OK;
 }
 

@@ -12,10 +12,11 @@ size_t stats_ws_bytes(const lamp_tensor_desc* zd);
 // Two-kernel statistics of z: writes stats[N][C][2] = (mean, rstd).
 lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, float* stats,
                          void* ws, size_t ws_bytes, hipStream_t s);
-// Combine per-part (sum, sumsq) fp32 partials [N][parts][C][2] with per-part voxel counts
-// cnt[parts] (int32, same for every sample) into stats[N][C][2]; fp64 pairwise merging.
+// Combine per-part (sum, sumsq) fp32 partials [N][parts][C][2] with per-part voxel counts (int32;
+// cnt[parts], the same for every sample, or cnt[N][parts] when counts_per_sample) into
+// stats[N][C][2]; fp64 pairwise merging.
 lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
-                                  float eps, float* stats, hipStream_t s);
+                                  float eps, float* stats, hipStream_t s, bool counts_per_sample = false);
 
 // ---- reduce.hip -----------------------------------------------------------------------------
 // out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.

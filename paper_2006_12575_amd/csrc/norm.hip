@@ -75,12 +75,12 @@ __device__ __forceinline__ void merge_moments(Moments& a, double c2, double mn2,
 }
 __global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __restrict__ partial,
                                                              const int32_t* __restrict__ counts, int parts, int C,
-                                                             float eps, float* __restrict__ stats) {
+                                                             float eps, float* __restrict__ stats, int counts_per_sample) {
     __shared__ double sh[4][3];
     const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     Moments m{0.0, 0.0, 0.0};
     for (int p = tid; p < parts; p += 256) {
-        const double k = (double)counts[p];
+        const double k = (double)counts[counts_per_sample ? (size_t)n * parts + p : (size_t)p];
         if (k <= 0.0) continue;
         const size_t o = (((size_t)n * parts + p) * C + c) * 2;
         const double sm = (double)partial[o], sq = (double)partial[o + 1];
@@ -104,8 +104,9 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __rest
 }
 
 lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
-                                  float eps, float* stats, hipStream_t s) {
-    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(256), 0, s, partials, counts, parts, C, eps, stats);
+                                  float eps, float* stats, hipStream_t s, bool counts_per_sample) {
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(256), 0, s, partials, counts, parts, C, eps, stats,
+                       counts_per_sample ? 1 : 0);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
