@@ -428,7 +428,8 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     int td, th, tw;
     tile_dims(zd, 4, td, th, tw);  // the finer tiling bounds the partial count
     const size_t tiles = (size_t)td * th * tw;
-    size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 64);  // + 16 zero bytes + 16 bytes that absorb masked stores
+    // repacked weights + a run of zeros (source of the zero padding) + 16 bytes that absorb masked stores
+    size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
     if (want_stats) {
         // partial statistics: one per tile (tiled kernel) or one per wave of a workgroup (ring kernel, <= 1024)
         const size_t parts = tiles > 1024 ? tiles : 1024;
@@ -456,11 +457,16 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                           hipStream_t s) {
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
     {
-        static int ring = -1;
-        if (ring < 0) {
+        // Kernel choice.  The ring kernel wins where every CU gets a long run of 64-channel tiles; the tiled
+        // kernel (two waves per SIMD) copes better with short walks and 32-channel outputs.
+        // LAMP_CONV_KERNEL=ring|tile forces one for experiments.
+        static int forced = -1;
+        if (forced < 0) {
             const char* e = getenv("LAMP_CONV_KERNEL");
-            ring = (e && e[0] == 'r') ? 1 : 0;
+            forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
         }
+        const int64_t tiles4 = (int64_t)zd->n * ((zd->d + 3) / 4) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
+        const bool ring = forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c >= 64 && tiles4 >= 2048);
         if (ring) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     }
     const int TDT = conv_tile_depth(zd);

@@ -8,8 +8,8 @@
 //    = four 32-voxel blocks for all 32*COB output channels.  For a fixed in-plane tap (kh,kw) the input
 //    slice s = d + kd serves output slices d = s, s-1, s-2 with the weights of kd = 0, 1, 2: six slice
 //    fragments and 3*COB weight fragments feed 12*COB MFMAs.
-//  * LDS holds a ring of 3 halo regions, each one 16-channel chunk of a tile's 6 x 10 x 18 halo (two
-//    planes of 16-byte voxel entries), and a ring of 8 weight blocks (3 taps x 16 ci x 32*COB co).
+//  * LDS holds a ring of 3 halo regions, each one 16-channel chunk of a tile's 6 x 10 x 18 halo (32 bytes
+//    per voxel, fetched as one request), and a ring of 8 weight blocks (3 taps x 16 ci x 32*COB co).
 //    Region (q+2)%3 is refilled for chunk-step q+2 while chunk-step q is multiplied, weight block s%8
 //    for step s+8 while step s is multiplied, both by register-free global -> LDS copies.  Copies
 //    complete in issue order, so the long weight ring is what lets a halo copy that misses every
@@ -20,8 +20,9 @@
 //    of a tile is cut into small units (convert + write to a private LDS patch; read a voxel row back,
 //    store it, add it to the channel sums) that ride in the steps of the NEXT tile, which accumulates
 //    into a second set of registers.
-//  * A persistent workgroup walks a run of tiles that is contiguous in d, so the two halo slices shared
-//    by successive tiles are re-read from cache soon after their first use.
+//  * Tiles are numbered d-fastest, an XCD owns a contiguous range of them and its persistent workgroups
+//    take them in turn: at any time the workgroups of an XCD work on neighbouring tiles (a column in d
+//    first), whose shared halo voxels are then fetched from memory once and re-read from the XCD's L2.
 #include <stdlib.h>
 #include <type_traits>
 #include "internal.h"
@@ -35,10 +36,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 constexpr int RTD = 4, RTH = 8, RTW = 16;
 constexpr int RHD = RTD + 2, RHH = RTH + 2, RHW = RTW + 2;
 constexpr int RHALO_VOX = RHD * RHH * RHW;   // 1080
-constexpr int RPLANE = RHALO_VOX * 16;       // 8 channels per voxel entry
-constexpr int RREGION = 2 * RPLANE;          // one 16-channel chunk: 34560
+constexpr int RREGION = RHALO_VOX * 32;      // one 16-channel chunk (32 bytes per voxel): 34560
 constexpr int RNREG = 3;
-constexpr int RSLICE = RHH * RHW * 16;       // bytes between halo d-slices of a plane
+constexpr int RSLICE = RHH * RHW * 32;       // bytes between halo d-slices
+constexpr int RROW = RHW * 32;               // bytes between halo h-rows
 constexpr int RHENTRIES = 2 * RHALO_VOX;     // 16-byte entries of a region: 36 wave copies, 9 per wave, copy k
 constexpr int RHSTEP = 60;                   // starts at entry min(60k, 2160-64) (neighbours overlap by 4 entries)
 constexpr int RNWSLOT = 8;                  // weight ring: block of step s + 8 replaces block s
@@ -62,7 +63,7 @@ struct RingArgs {
     bf16_t* z; int ldz;
     float* part;           // [N][4 * workgroups][Cout][2]: per-wave partial (sum, sum of squares), or nullptr
     int32_t* counts;       // [N][4 * workgroups]: voxels behind each partial (written when part != nullptr)
-    const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
+    const bf16_t* zero16;  // 2 * Cin + 16 zero bytes in global memory (source of the zero padding, any chunk offset)
     bf16_t* dump;          // 16 bytes in global memory that absorb the stores of voxels outside the volume
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd, tiles_per_wg;
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(256) void ring_repack_kernel(const bf16_t* __restri
                                                           int Cin, int wrows, int dgrad) {
     const int64_t total = (int64_t)27 * Cout * Cin;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < 8) wp[total + i] = 0;  // 16 zero bytes behind the weights: the source of the zero padding
+    if (i < Cin + 8) wp[total + i] = 0;  // zeros behind the weights: the source of the zero padding
     if (i >= total) return;
     const int nchunks = Cin >> 4;
     int64_t r = i;
@@ -159,12 +160,13 @@ template <int COB> struct StepPlan {
 //   unit A(rg), rg = 0..3 : write 4 channels to the wave's LDS patch (32 voxel rows of 64 bytes)
 //   unit B(i),  i = 0..1  : 4 lanes read back one voxel row (16 rows per instruction), store its 64 bytes
 //                           and add the stored values to this lane's channel sums
-// There is one copy of the code for all phases: `pend` is rotated after every phase so that the data
-// of the next one sits in front, and the channel sums of the two blocks swap places when the block
-// changes.  With nothing pending the units still run, on a dump address and with the sums masked off.
+// There is one copy of the code for all phases: they all take their data from `front`, which is
+// reloaded from `pend` after every phase, and the channel sums of the two blocks swap places when the
+// block changes.  Voxels outside the volume are zeroed when the tile ends, so they add nothing to the
+// sums; their rows are stored to a dump address.  With nothing pending the units still run, on zeros.
 // The channel sums run on across the tiles of the walk and are written once per sample.
 template <int COB> struct EpiCtx {
-    uint32_t (&pend)[2 * COB][2][8];
+    uint32_t (&front)[2][8];
     float (&csum)[8];
     float (&csq)[8];
     char* patch_w;        // patch + l32 * RPATCH_ROW + half * 8      (unit A adds rg * 16)
@@ -181,7 +183,7 @@ template <int COB> struct EpiCtx {
 
 template <int COB, int DD, int RG>
 __device__ __forceinline__ void epi_unit_a(EpiCtx<COB>& e) {
-    *reinterpret_cast<uint2*>(e.patch_w + RG * 16) = make_uint2(e.pend[0][DD][RG * 2], e.pend[0][DD][RG * 2 + 1]);
+    *reinterpret_cast<uint2*>(e.patch_w + RG * 16) = make_uint2(e.front[DD][RG * 2], e.front[DD][RG * 2 + 1]);
 }
 template <int COB, int I> __device__ __forceinline__ void epi_unit_b_read(EpiCtx<COB>& e) {
     e.q = *reinterpret_cast<const uint4*>(e.patch_r + I * 16 * RPATCH_ROW);
@@ -190,15 +192,12 @@ template <int COB, int DD, int I> __device__ __forceinline__ void epi_unit_b_add
     const bool ok = e.okl[I] & (DD < e.dleft);
     e.qp = ok ? e.zp[I] + (e.poff + DD * e.dstride) : e.dump;
 }
-// store the row, then clear it unless it counts for the channel sums
 template <int COB, int DD, int I> __device__ __forceinline__ void epi_unit_b_store(EpiCtx<COB>& e) {
     // streaming store: the output is not read again by this kernel and should not displace the input
     // lines that the next chunk passes and the neighbouring tiles still need
     typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
     const u32x4 sv = {e.q.x, e.q.y, e.q.z, e.q.w};
     __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(e.qp));
-    const uint32_t m = (e.okl[I] & (DD < e.dleft)) ? 0xFFFFFFFFu : 0u;
-    e.q.x &= m; e.q.y &= m; e.q.z &= m; e.q.w &= m;
 }
 template <int COB, int E> __device__ __forceinline__ void epi_unit_b_stats(EpiCtx<COB>& e) {
     const uint32_t r = E == 0 ? e.q.x : E == 1 ? e.q.y : E == 2 ? e.q.z : e.q.w;
@@ -259,11 +258,13 @@ template <int COB> struct StepCtx {
     const bf16_t* wb0;       // weight copy sources = wb + woff
     const bf16_t* wb1;
     size_t woff;
-    const HaloTile& ht;      // halo copy: tile, this lane's halo coordinates / offset, chunk offset
-    int pk, choff;           //   (pk = hd | hh << 8 | hw << 16 | plane << 24)
+    const HaloTile& ht;      // halo copy: tile, this lane's halo coordinates (pk = hd | hh << 8 | hw << 16 |
+    int pk, choff;           //   plane << 24), chunk offset; hptr = source address for chunk 0, kept per tile
     int H, W, ldx;
-    const bf16_t* zero16;
-    const bf16_t* p0; const bf16_t* p1; const bf16_t* ph; bool in;   // temporaries carried between slots
+    const bf16_t* zeros;
+    const bf16_t*& hptr;
+    bool newtile;            // hptr must be computed (the prefetched tile changed)
+    const bf16_t* p0; const bf16_t* p1; bool in;   // temporaries carried between slots
 };
 
 template <int COB, int J, int K>
@@ -283,18 +284,21 @@ __device__ __forceinline__ void step_slot(StepCtx<COB>& c, EpiCtx<COB>& e) {
     if constexpr (K == P::WC0) g2lds16(c.p0, c.wd0);
     if constexpr (K == P::WC1 - 1) c.p1 = c.wb1 + c.woff;
     if constexpr (K == P::WC1) g2lds16(c.p1, c.wd1);
+    // the halo source of this lane changes only with the prefetched tile: voxels outside the volume read
+    // from a run of zeros that is long enough for every chunk offset
     if constexpr (K == P::HC - 2) {
-        // (opaque to the optimiser: otherwise the address arithmetic below, which does not change from
-        // tile to tile, is hoisted out of the loops for all nine steps and costs dozens of registers)
-        asm volatile("" : "+v"(c.pk));
-        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255;
-        c.in = (hd >= c.ht.dlo) & (hd <= c.ht.dhi) & (hh >= c.ht.hlo) & (hh <= c.ht.hhi) & (hw >= c.ht.wlo) & (hw <= c.ht.whi);
+        if (c.newtile) {
+            const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255;
+            c.in = (hd >= c.ht.dlo) & (hd <= c.ht.dhi) & (hh >= c.ht.hlo) & (hh <= c.ht.hhi) & (hw >= c.ht.wlo) & (hw <= c.ht.whi);
+        }
     }
     if constexpr (K == P::HC - 1) {
-        const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255, plane = c.pk >> 24;
-        c.ph = c.in ? c.ht.origin + (((hd * c.H + hh) * c.W + hw) * c.ldx + plane * 8 + c.choff) : c.zero16;
+        if (c.newtile) {
+            const int hd = c.pk & 255, hh = (c.pk >> 8) & 255, hw = (c.pk >> 16) & 255, plane = c.pk >> 24;
+            c.hptr = c.in ? c.ht.origin + (((hd * c.H + hh) * c.W + hw) * c.ldx + plane * 8) : c.zeros;
+        }
     }
-    if constexpr (K == P::HC) g2lds16(c.ph, c.hd);
+    if constexpr (K == P::HC) g2lds16(c.hptr + c.choff, c.hd);
     epi_slot<COB, J, K>(e);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (K + 1 < P::NM) step_slot<COB, J, K + 1>(c, e);
@@ -304,18 +308,19 @@ __device__ __forceinline__ void step_slot(StepCtx<COB>& c, EpiCtx<COB>& e) {
 // hold the same for the next step.
 template <int COB, int J>
 __device__ __forceinline__ void ring_step(f32x16 (&acc)[COB][4], bf16x8 (&acur)[3][COB], bf16x8& b0, bf16x8& b1, bf16x8& b2,
-                                          const char* hb, const char* hb_nextstep, const char* w_nextstep,
+                                          const char* hr, const char* hr_nextstep, const uint32_t (&bb)[3],
+                                          const char* w_nextstep,
                                           uint32_t w_dst0, uint32_t w_dst1, uint32_t h_dst, const bf16_t* wb0,
                                           const bf16_t* wb1, size_t woff, const HaloTile& ht, int pk, int choff, int H,
-                                          int W, int ldx, const bf16_t* zero16, EpiCtx<COB>& e) {
+                                          int W, int ldx, const bf16_t* zeros, const bf16_t*& hptr, bool newtile,
+                                          EpiCtx<COB>& e) {
     constexpr int kh = J / 3, kw = J % 3;
-    constexpr int tapoff = (kh * RHW + kw) * 16;
     constexpr int JN = (J + 1) % 9;
-    constexpr int tapoff_n = ((JN / 3) * RHW + JN % 3) * 16;
+    constexpr int khn = JN / 3, kwn = JN % 3;
     bf16x8 b[6], an[3][COB], nb[3];
     b[0] = b0; b[1] = b1; b[2] = b2;
-    StepCtx<COB> c{acc, acur, b, an, nb, hb + tapoff, hb_nextstep + tapoff_n, w_nextstep, w_dst0, w_dst1, h_dst, wb0, wb1, woff,
-                   ht, pk, choff, H, W, ldx, zero16, nullptr, nullptr, nullptr, false};
+    StepCtx<COB> c{acc, acur, b, an, nb, hr + (bb[kw] + kh * RROW), hr_nextstep + (bb[kwn] + khn * RROW), w_nextstep, w_dst0, w_dst1, h_dst, wb0, wb1, woff,
+                   ht, pk, choff, H, W, ldx, zeros, hptr, newtile, nullptr, nullptr, false};
     step_slot<COB, J, 0>(c, e);
 #pragma unroll
     for (int kd = 0; kd < 3; ++kd)
@@ -352,8 +357,9 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
 
     // persistent walk: the XCD owns a contiguous range of tiles, the workgroup a contiguous run of it
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int tile_lo = xcd * a.tiles_per_xcd + local * a.tiles_per_wg;
-    const int tile_hi = min(tile_lo + a.tiles_per_wg, min((xcd + 1) * a.tiles_per_xcd, a.tiles_total));
+    const int tstep = (int)(gridDim.x >> 3);   // the workgroups of an XCD take its tiles in turn, so that at any
+    const int tile_lo = xcd * a.tiles_per_xcd + local;   // time they work on neighbours (in d first) and share halos in L2
+    const int tile_hi = min((xcd + 1) * a.tiles_per_xcd, a.tiles_total);
     // voxel counts behind this wave's partial statistics: zero for the samples it never visits
     if (a.counts && lane == 0 && blockIdx.y == 0)
         for (int n = 0; n < a.N; ++n) a.counts[n * (gridDim.x * 4) + blockIdx.x * 4 + wv] = 0;
@@ -365,19 +371,27 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15).
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
-    const uint32_t b_base = (uint32_t)(half * RPLANE + ((2 * wv + bh) * RHW + bw) * 16);
+    // A region holds, per halo voxel, the 32 bytes of the chunk as two 16-byte halves (channels 0-7 / 8-15),
+    // swapped for voxels whose w coordinate has bit 3 set: the two lanes of a copy that fetch one voxel
+    // are neighbours (one 32-byte request), and a fragment read -- 16 consecutive w per row, one half --
+    // still spreads over all banks.  bb[kw]: this lane's read offset for the in-plane tap column kw.
+    uint32_t bb[3];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw)
+        bb[kw] = (uint32_t)((((2 * wv + bh) * RHW + bw + kw) * 32) + ((half ^ (((bw + kw) >> 3) & 1)) * 16));
     const uint32_t a_base = (uint32_t)(half * G::WPLANE + l32 * 16);
 
-    // ---- per-lane constants of the copies.  Halo copy slot k = J*4 + wv covers entries 60k .. 60k+59 of
-    // a region (entry = plane*1080 + halo voxel): rel = element offset from the tile's halo origin.
+    // ---- per-lane constants of the copies.  Halo copy slot k = J*4 + wv covers the 16-byte entries
+    // 60k .. 60k+63 of a region (entry = 2 * halo voxel + half).
     int hpk[9], hoff[9];   // hd | hh << 8 | hw << 16 | plane << 24 of this lane's entry; LDS offset of the copy
 #pragma unroll
     for (int j = 0; j < 9; ++j) {
         const int e0 = min((j * 4 + wv) * RHSTEP, RHENTRIES - 64);
         const int e = e0 + lane;
         hoff[j] = e0 * 16;
-        const int plane = e / RHALO_VOX, hv = e - plane * RHALO_VOX;
+        const int hv = e >> 1;
         const int hw = hv % RHW, hh = (hv / RHW) % RHH, hd = hv / (RHW * RHH);
+        const int plane = (e & 1) ^ ((hw >> 3) & 1);   // which 8 channels of the chunk this entry holds
         hpk[j] = hd | (hh << 8) | (hw << 16) | (plane << 24);
     }
     const int we0 = min(wv * G::USTEP, G::WENTRIES - 64), we1 = min((wv + 4) * G::USTEP, G::WENTRIES - 64);
@@ -408,11 +422,11 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     };
 
     // ---- prologue: halo of chunk-steps 0 and 1, weights of steps 0..8
-    const int total_q = (tile_hi - tile_lo) * nchunks;
+    const int total_q = ((tile_hi - tile_lo + tstep - 1) / tstep) * nchunks;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         if (i < total_q) {
-            const int t = tile_lo + i / nchunks, c = i % nchunks;
+            const int t = tile_lo + (i / nchunks) * tstep, c = i % nchunks;
             const HaloTile ht = halo_tile(t);
 #pragma unroll
             for (int j = 0; j < 9; ++j) g2lds16(halo_src(ht, j, c * 16), hreg_a + i * RREGION + hoff[j]);
@@ -431,22 +445,25 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
     for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) acur[kd][cb] = lds_frag(wring + a_base + kd * 2 * G::WPLANE + cb * 512);
-    b0 = lds_frag(hreg + b_base);
-    b1 = lds_frag(hreg + b_base + RSLICE);
-    b2 = lds_frag(hreg + b_base + 2 * RSLICE);
+    b0 = lds_frag(hreg + bb[0]);
+    b1 = lds_frag(hreg + bb[0] + RSLICE);
+    b2 = lds_frag(hreg + bb[0] + 2 * RSLICE);
 
     int rq = 0;                                  // chunk-step counter mod 3: the region being multiplied
     int wsl = 0;                                 // step counter mod 8: the weight slot being multiplied
-    int pf_tile = tile_lo + 2 / nchunks, pf_chunk = 2 % nchunks;   // halo prefetch cursor = chunk-step q + 2
+    int pf_tile = tile_lo + (2 / nchunks) * tstep, pf_chunk = 2 % nchunks;   // halo prefetch cursor = chunk-step q + 2
 
     // ---- the pending tile: results of the previous tile of the walk, on their way out
     constexpr int NPH = 2 * COB;
     f32x16 acc[COB][4];
-    uint32_t pend[NPH][2][8];        // phase-major: pend[cb * 2 + dp][dd] = block cb of d-slice 2 * dp + dd
+    uint32_t front[2][8];            // data of the phase in progress: [dd] = d-slice 2 * dp + dd of block cb
+    uint32_t pend[NPH - 1][2][8];    // data of the phases 1 .. NPH-1 (phase p = cb * 2 + dp)
+    const bf16_t* hptr[9];           // halo copy sources of the prefetched tile (chunk 0), one per step
+    int hptr_tile = -1;              // the tile they belong to
     float csum[8], csq[8];           // channel sums of the block in progress ...
     float osum[8], osq[8];           // ... and of the other block (COB == 2)
     char* const patch = lds + RNREG * RREGION + RNWSLOT * G::WBLOCK + wv * RPATCH;
-    EpiCtx<COB> ec{pend, csum, csq, patch + l32 * RPATCH_ROW + half * 8, patch + (lane >> 2) * RPATCH_ROW + (lane & 3) * 16,
+    EpiCtx<COB> ec{front, csum, csq, patch + l32 * RPATCH_ROW + half * 8, patch + (lane >> 2) * RPATCH_ROW + (lane & 3) * 16,
                    {a.dump, a.dump}, {false, false}, (int64_t)a.H * a.W * a.ldz, 0, 0, a.dump, make_uint4(0, 0, 0, 0), a.dump};
     bool okt[2] = {false, false};   // (h, w) of this lane's two rows of the pending tile lie inside the volume
     int dvalid = 0;                  // d-slices of the pending tile inside the volume
@@ -464,15 +481,20 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         ec.poff = (int64_t)(2 * dp) * ec.dstride + cb * 32;
         ec.dleft = dvalid - 2 * dp;
     };
-    // a phase is done: bring the next one's data to the front
+    // a phase is done: bring the next one's data to the front (zeros when nothing is left)
     auto phase_advance = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int p = 0; p + 1 < NPH; ++p)
+        if (epi_p < NPH) {
+            const int np = epi_p + 1;
 #pragma unroll
             for (int dd = 0; dd < 2; ++dd)
 #pragma unroll
-                for (int r = 0; r < 8; ++r) pend[p][dd][r] = pend[p + 1][dd][r];
-        if (epi_p < NPH) {
+                for (int r = 0; r < 8; ++r) {
+                    uint32_t v = 0u;
+                    if (np == 1) v = pend[0][dd][r];
+                    if (COB == 2 && np == 2) v = pend[NPH > 2 ? 1 : 0][dd][r];
+                    if (COB == 2 && np == 3) v = pend[NPH > 3 ? 2 : 0][dd][r];
+                    front[dd][r] = v;
+                }
             if (COB == 2 && (epi_p & 1)) {   // the channel block changes
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -530,11 +552,9 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; osum[e] = 0.f; osq[e] = 0.f; }
 #pragma unroll
-    for (int p = 0; p < NPH; ++p)
+    for (int dd = 0; dd < 2; ++dd)
 #pragma unroll
-        for (int dd = 0; dd < 2; ++dd)
-#pragma unroll
-            for (int r = 0; r < 8; ++r) pend[p][dd][r] = 0u;
+        for (int r = 0; r < 8; ++r) front[dd][r] = 0u;
 #pragma unroll
     for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
@@ -543,15 +563,18 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
             for (int r = 0; r < 16; ++r) acc[cb][d][r] = 0.f;
     phase_setup();
 
-    for (int tile = tile_lo; tile < tile_hi; ++tile) {
+    for (int tile = tile_lo; tile < tile_hi; tile += tstep) {
         for (int chunk = 0; chunk < nchunks; ++chunk) {
             const int rq1 = rq == 2 ? 0 : rq + 1, rq2 = rq == 0 ? 2 : rq - 1;
-            const char* hb = hreg + rq * RREGION + b_base;
-            const char* hbn = hreg + rq1 * RREGION + b_base;
+            const char* hr = hreg + rq * RREGION;
+            const char* hrn = hreg + rq1 * RREGION;
             // past the end of the walk the copies go on (they keep the in-flight count uniform) and
             // fetch this tile again; nothing reads what they bring
             const uint32_t hdst = hreg_a + rq2 * RREGION;
-            const HaloTile ht = halo_tile(pf_tile < tile_hi ? pf_tile : tile);
+            const int src_tile = pf_tile < tile_hi ? pf_tile : tile;
+            const HaloTile ht = halo_tile(src_tile);
+            const bool newtile = src_tile != hptr_tile;
+            hptr_tile = src_tile;
             const int choff = pf_chunk * 16;
             const int t0 = chunk * 9;
 #define RING_STEP(J)                                                                                                  \
@@ -560,16 +583,16 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         if (t8 >= spt) t8 -= spt;                                                                                     \
         const int wsl1 = wsl == RNWSLOT - 1 ? 0 : wsl + 1;                                                            \
         const uint32_t wd = wring_a + wsl * G::WBLOCK;                                                                \
-        ring_step<COB, J>(acc, acur, b0, b1, b2, hb, (J < 8 ? hb : hbn), wring + wsl1 * G::WBLOCK + a_base,            \
+        ring_step<COB, J>(acc, acur, b0, b1, b2, hr, (J < 8 ? hr : hrn), bb, wring + wsl1 * G::WBLOCK + a_base,        \
                           wd + we0 * 16, wd + we1 * 16, hdst + hoff[J], wslab0, wslab1, (size_t)t8 * G::WBLOCK_ELEMS,  \
-                          ht, hpk[J], choff, a.H, a.W, a.ldx, a.zero16, ec);                                          \
+                          ht, hpk[J], choff, a.H, a.W, a.ldx, a.zero16, hptr[J], newtile, ec);                         \
         wsl = wsl1;                                                                                                   \
     }
             RING_STEP(0) RING_STEP(1) RING_STEP(2) RING_STEP(3) RING_STEP(4) RING_STEP(5) RING_STEP(6) RING_STEP(7)
             RING_STEP(8)
 #undef RING_STEP
             phase_advance();
-            if (++pf_chunk == nchunks) { pf_chunk = 0; ++pf_tile; }
+            if (++pf_chunk == nchunks) { pf_chunk = 0; pf_tile += tstep; }
             rq = rq1;
         }
 
@@ -578,12 +601,20 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
         if (n != stat_n) { flush_stats(); stat_n = n; }
+        dvalid = min(RTD, a.D - d0);
+        // this lane's voxel of the blocks (as the MFMA result holds them): inside the volume in h and w?
+        const bool hw_in = h0 + 2 * wv + bh < a.H && w0 + bw < a.W;
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
+                const uint32_t keep = (hw_in && d < dvalid) ? 0xFFFFFFFFu : 0u;   // voxels outside the volume become zeros
 #pragma unroll
-                for (int r = 0; r < 8; ++r) pend[cb * 2 + (d >> 1)][d & 1][r] = pack_bf16(acc[cb][d][2 * r], acc[cb][d][2 * r + 1]);
+                for (int r = 0; r < 8; ++r) {
+                    const uint32_t v = pack_bf16(acc[cb][d][2 * r], acc[cb][d][2 * r + 1]) & keep;
+                    if (cb == 0 && d < 2) front[d][r] = v;
+                    else pend[cb * 2 + (d >> 1) - 1][d & 1][r] = v;
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[cb][d][r] = 0.f;
             }
@@ -596,7 +627,6 @@ __global__ __launch_bounds__(256) void conv3d_ring_kernel(RingArgs a) {
             okt[i] = gh < a.H && gw < a.W;
             ec.zp[i] = a.z + ((((int64_t)n * a.D + d0) * a.H + gh) * a.W + gw) * a.ldz + co0 + (lane & 3) * 8;
         }
-        dvalid = min(RTD, a.D - d0);
         stat_vox += dvalid * max(0, min(2, a.H - (h0 + 2 * wv))) * min(RTW, a.W - w0);
         epi_p = 0;
         phase_setup();
@@ -628,7 +658,7 @@ lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     const int td = (zd->d + RTD - 1) / RTD, th = (zd->h + RTH - 1) / RTH, tw = (zd->w + RTW - 1) / RTW;
     const int tiles_per_n = td * th * tw;
     Carver cv(ws, ws_bytes);
-    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 64);
+    bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
     // launch shape first: the statistics partials are per wave of a workgroup ([N][4 * workgroups][C][2])
     const int tiles_total = tiles_per_n * zd->n;
     const int tiles_per_xcd = (tiles_total + 7) / 8;
@@ -651,7 +681,7 @@ lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     RingArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;
-    a.dump = wp + (size_t)27 * xd->c * zd->c + 16;
+    a.dump = wp + (size_t)27 * xd->c * zd->c + xd->c + 16;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
     a.tiles_total = tiles_total; a.tiles_per_xcd = tiles_per_xcd; a.tiles_per_wg = tiles_per_wg;
