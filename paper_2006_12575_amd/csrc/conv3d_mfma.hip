@@ -43,6 +43,13 @@ template <int TDT> struct Geo {
     static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? EPI_BYTES : 0);
 };
 
+// Two floats to a pair of bf16 (round to nearest even) with the hardware conversion.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
     uint4 q = *reinterpret_cast<const uint4*>(p);
     return __builtin_bit_cast(bf16x8, q);
@@ -332,13 +339,9 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
-                    uint32_t pk[2];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t b = f2bf(acc[cb][vb][rg * 4 + e]);
-                        if (e & 1) pk[e >> 1] |= b << 16; else pk[e >> 1] = b;
-                    }
-                    *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(pk[0], pk[1]);
+                    const uint32_t p0 = pack_bf16(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1]);
+                    const uint32_t p1 = pack_bf16(acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
+                    *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
                 }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -350,7 +353,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int gh = h0 + hs * NVB * 2 + vb * 2 + rh, gw = w0 + rw;
                 const bool ok = gd < a.D && gh < a.H && gw < a.W;
                 if (ok) {
-                    *reinterpret_cast<uint4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8) = q;
+                    // streaming store: the output is not read again by this kernel and should not displace
+                    // the input lines that the next chunk passes and the neighbouring tiles still need
+                    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+                    const u32x4 sv = {q.x, q.y, q.z, q.w};
+                    __builtin_nontemporal_store(
+                        sv, reinterpret_cast<u32x4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8));
                     const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
