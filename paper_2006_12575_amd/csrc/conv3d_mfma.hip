@@ -5,13 +5,15 @@
 //
 // GEMM view per workgroup tile:  D[co][voxel] += sum_{tap, ci} Wp[tap][co][ci] * X[voxel + tap][ci]
 //   M = 32*COB output channels (A operand = weights), N = 1024 voxels (B operand = activations),
-//   K = 27 taps x Cin, walked as (Cin chunk of 16 = one MFMA k-step) x (3 kd groups) x (9 taps).
-// Tile: 8 x 8 x 16 output voxels (d,h,w); 8 waves (2 per SIMD), wave w owns d-slice w = 4 blocks
-// of 32 voxels (2 h-rows x 16 w), so a 16-lane group always reads 16 consecutive halo voxels.
+//   K = 27 taps x Cin, walked as (Cin chunk of 16 = one MFMA k-step) x (3 groups of 9 taps: one kh
+//   each for the 8-deep tile, one kd each for the 4-deep tile).
+// Tile: 8 x 8 x 16 output voxels (d,h,w); 8 waves (2 per SIMD); a wave owns 4 d-slices of one
+// (2 h-rows x 16 w) patch = 4 blocks of 32 voxels, so a 16-lane group always reads 16 consecutive
+// halo voxels and an input slice fragment serves up to three output slices (kd = 0, 1, 2).
 // LDS holds a halo chunk as two planes (channels 0-7 / 8-15 of the chunk) of 16-byte voxel
 // entries: every fragment read is a conflict-free 16-byte load at lane base + immediate offset.
 // Two halo buffers (10 x 10 x 18 voxels) let the next chunk / next tile stream in while the
-// current one is multiplied; two weight buffers hold one kd group (9 taps x 64 co x 16 ci) each.
+// current one is multiplied; two weight buffers hold one tap group (9 taps x 64 co x 16 ci) each.
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
 #include <stdlib.h>
 #include "internal.h"
@@ -57,14 +59,18 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
 
 // wp[t][oc][ic]  <-  forward: W[oc][t][ic]     dgrad: W[ic][26-t][oc]
 __global__ __launch_bounds__(256) void repack_weights_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp,
-                                                             int Cout, int Cin, int dgrad) {
+                                                             int Cout, int Cin, int dgrad, int bykh) {
     const int64_t total = (int64_t)27 * Cout * Cin;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < 8) wp[total + i] = 0;  // 16 zero bytes behind the weights: the source of the zero padding
     if (i >= total) return;
     const int ic = (int)(i % Cin);
     const int oc = (int)((i / Cin) % Cout);
-    const int t = (int)(i / ((int64_t)Cin * Cout));
+    int t = (int)(i / ((int64_t)Cin * Cout));
+    if (bykh) {   // position kh*9 + kd*3 + kw holds tap (kd, kh, kw): the 8-deep tile walks the taps kh-major
+        const int kh = t / 9, kd = (t / 3) % 3, kw = t % 3;
+        t = kd * 9 + kh * 3 + kw;
+    }
     wp[i] = dgrad ? w[((int64_t)ic * 27 + (26 - t)) * Cout + oc] : w[((int64_t)oc * 27 + t) * Cin + ic];
 }
 
@@ -154,6 +160,49 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (TDT == 8) {
+        // ---- multiply, 8-deep tile: the group is the in-plane row G = kh.  A wave owns 4 d-slices of one
+        // (2 h-rows x 16 w) patch; for a tap column kw the input slice s = d + kd serves the output slices
+        // d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6 slice fragments and 3*COB weight fragments
+        // feed 12*COB MFMAs.  The weight fragments and the first two slices of the next column are fetched
+        // while this one is multiplied.
+        bf16x8 a[2][3][COB], b[6], nb[2];
+        auto load_a = [&](int kw, int slot) __attribute__((always_inline)) {
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb) a[slot][kd][cb] = lds_frag(wb + (kd * 3 + kw) * 2 * WPLANE + cb * 32 * 16);
+        };
+        auto frag_b = [&](int kw, int sl) __attribute__((always_inline)) { return lds_frag(hb + ((sl * HH + G) * HW + kw) * 16); };
+        load_a(0, 0);
+        b[0] = frag_b(0, 0);
+        b[1] = frag_b(0, 1);
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+            for (int sl = 2; sl < 6; ++sl) b[sl] = frag_b(kw, sl);
+            if (kw < 2) {
+                load_a(kw + 1, (kw + 1) & 1);
+                nb[0] = frag_b(kw + 1, 0);
+                nb[1] = frag_b(kw + 1, 1);
+            }
+#pragma unroll
+            for (int sl = 0; sl < 6; ++sl)
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd) {
+                    const int d = sl - kd;
+                    if (d >= 0 && d < 4) {
+#pragma unroll
+                        for (int cb = 0; cb < COB; ++cb)
+                            acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kw & 1][kd][cb], b[sl], acc[cb][d], 0, 0, 0);
+                    }
+                }
+            if (kw < 2) sched_interleave<0, 12 * COB, 6 + 3 * COB>();
+            else sched_interleave<0, 12 * COB, 4>();
+            b[0] = nb[0];
+            b[1] = nb[1];
+        }
+    } else {
     // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched while
     // tap t is multiplied
     bf16x8 af[2][COB], bfr[2][NVB];
@@ -175,6 +224,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
             for (int vb = 0; vb < NVB; ++vb)
                 acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
         if (t9 < 8) sched_interleave<0, NVB * COB, COB + NVB>();
+    }
     }
     // The weight copies are older than this group's halo copies: leaving HALO_CNT copies in flight
     // still guarantees the weights have landed.  (Every wave issues all HALO_CNT copies of groups
@@ -214,8 +264,11 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15).
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
-    const int ds = wv % TDT, hs = wv / TDT;   // this wave's d-slice and h-part of the tile
-    const uint32_t b_base = (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB * 2 + bh) * HW + bw) * 16);
+    // this wave's part of the tile.  4-deep tile: d-slice ds, h-rows hs*4 .. hs*4+3 (two blocks).  8-deep
+    // tile: d-slices 4*ds .. 4*ds+3 (one block each) of the h-row pair hs.
+    const int ds = TDT == 8 ? (wv & 1) : wv % TDT, hs = TDT == 8 ? (wv >> 1) : wv / TDT;
+    const uint32_t b_base = TDT == 8 ? (uint32_t)(half * PLANE_BYTES + ((4 * ds * HH + 2 * hs + bh) * HW + bw) * 16)
+                                     : (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB * 2 + bh) * HW + bw) * 16);
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
     // ---- per-lane constants of the register-free global -> LDS copies
@@ -322,7 +375,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         // Scratch: the halo buffer of the stage just finished (free until the next prefetch).
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
-        const int gd = d0 + ds;
+        const int gd0 = TDT == 8 ? d0 + 4 * ds : d0 + ds;
         char* fbuf = GE::EPI_OWN ? lds + 2 * HALO_BYTES + 2 * WBUF_BYTES : hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
         constexpr int ROWB = WROWS * 2 + 16;          // padded row of the patch
         constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
@@ -350,7 +403,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
                 const int rg8 = row >> 3;
                 const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
-                const int gh = h0 + hs * NVB * 2 + vb * 2 + rh, gw = w0 + rw;
+                const int gd = TDT == 8 ? gd0 + vb : gd0;
+                const int gh = TDT == 8 ? h0 + 2 * hs + rh : h0 + hs * NVB * 2 + vb * 2 + rh, gw = w0 + rw;
                 const bool ok = gd < a.D && gh < a.H && gw < a.W;
                 if (ok) {
                     // streaming store: the output is not read again by this kernel and should not displace
@@ -465,8 +519,9 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                           hipStream_t s) {
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
     {
-        // Kernel choice.  The ring kernel wins where every CU gets a long run of 64-channel tiles; the tiled
-        // kernel (two waves per SIMD) copes better with short walks and 32-channel outputs.
+        // Kernel choice.  The ring kernel wins where every CU gets a long run of 64-input-channel tiles; the
+        // tiled kernel (two waves per SIMD, twice the voxels per weight byte) copes better with short walks,
+        // 32-channel outputs and more input channels.
         // LAMP_CONV_KERNEL=ring|tile forces one for experiments.
         static int forced = -1;
         if (forced < 0) {
@@ -474,7 +529,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
             forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
         }
         const int64_t tiles4 = (int64_t)zd->n * ((zd->d + 3) / 4) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
-        const bool ring = forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c >= 64 && tiles4 >= 2048);
+        const bool ring = forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
         if (ring) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     }
     const int TDT = conv_tile_depth(zd);
@@ -492,7 +547,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const int64_t wtotal = (int64_t)27 * xd->c * zd->c;
     hipLaunchKernelGGL(repack_weights_kernel, dim3(cdiv(wtotal, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
-                       dgrad ? 1 : 0);
+                       dgrad ? 1 : 0, TDT == 8 ? 1 : 0);
     LAMP_CHECK_LAUNCH();
     ConvArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
