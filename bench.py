@@ -145,6 +145,14 @@ def main():
             roof["traffic"] = float(open(traffic_file).read().split()[0])
         except Exception:
             roof["traffic"] = None
+    # The rate of the bare matrix-core instruction stream on this chip, with zero and with normally
+    # distributed operands (switching power sets the clock): context for `frac`, whose peak stays the
+    # published one.
+    try:
+        roof["mfma_rate_zero_operands_tflops"] = L.lamp_probe_mfma_rate(0, 4000)
+        roof["mfma_rate_normal_operands_tflops"] = L.lamp_probe_mfma_rate(1, 4000)
+    except Exception:
+        pass
     if args.copy_calibration:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)

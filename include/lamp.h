@@ -79,6 +79,14 @@ typedef struct {
 const char *lamp_status_string(lamp_status s);
 /* Library version and the GPU architecture its kernels were compiled for ("gfx950"). */
 const char *lamp_build_info(void);
+/* Diagnostic, not part of the method: the rate (TFLOP/s) at which this GPU executes a register-resident
+ * loop of the bf16 32x32x16 matrix-core instruction the convolution kernels use (no memory traffic),
+ * measured over `iters` x 24 instructions per wave with one wave per SIMD.  pattern selects the operand
+ * values: 0 = zeros, 1 = standard-normal (seeded).  The rate depends on the data (switching power and
+ * with it the clock), which bounds what any kernel can reach on real activations; bench.py reports it
+ * beside the published peak.  Allocates and frees a small device buffer; synchronises the stream.
+ * Errors: LAMP_ERR_NULL (tflops), LAMP_ERR_SHAPE (pattern, iters < 1), LAMP_ERR_HIP. */
+lamp_status lamp_probe_mfma_rate(int32_t pattern, int32_t iters, float *tflops, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * 3x3x3 convolution, padding 1, stride 1 (the conv of every U-Net block, Sec. 2.2 / Sec. 3).

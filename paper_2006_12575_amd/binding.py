@@ -51,6 +51,7 @@ _VP = c_void_p
 _SIGS = {
     "lamp_status_string": (c_char_p, [c_int]),
     "lamp_build_info": (c_char_p, []),
+    "lamp_probe_mfma_rate": (c_int, [c_int, c_int, POINTER(c_float), _VP]),
     "lamp_conv3d_fwd_workspace_bytes": (c_size_t, [_PD, _PD, c_int]),
     "lamp_conv3d_fwd": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_conv3d_dgrad_workspace_bytes": (c_size_t, [_PD, _PD]),
@@ -109,6 +110,13 @@ def status_string(status: int) -> str:
 
 def build_info() -> str:
     return lib().lamp_build_info().decode()
+
+
+def lamp_probe_mfma_rate(pattern: int, iters: int = 4000) -> float:
+    """TFLOP/s of a register-resident bf16 MFMA loop; pattern 0 = zero operands, 1 = standard-normal."""
+    out = c_float(0.0)
+    _check(lib().lamp_probe_mfma_rate(int(pattern), int(iters), ctypes.byref(out), _stream()), "lamp_probe_mfma_rate")
+    return float(out.value)
 
 
 def _check(status, where):
