@@ -91,8 +91,8 @@ extern "C" lamp_status lamp_probe_mfma_rate(int32_t pattern, int32_t iters, floa
         if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f) { st = LAMP_ERR_HIP; break; }
         *tflops = (float)((double)blocks * 4 * iters * 24 * 32768.0 / ms / 1e9);
     } while (0);
-    if (e0) hipEventDestroy(e0);
-    if (e1) hipEventDestroy(e1);
-    hipFree(buf);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(buf);
     return st;
 }

@@ -126,6 +126,236 @@ __global__ __launch_bounds__(256) void head_wgrad_kernel(const T* __restrict__ x
         }
 }
 
+// ---- matrix-core head (bf16, C = 16 / 32 / 48 / 64 channels, up to 16 classes) ---------------------
+// logits^T[class][voxel] = Wh[class][c] * x^T[c][voxel] with v_mfma_f32_32x32x16_bf16: the classes (padded
+// to 32) are the rows, 32 voxels the columns, so the activations enter as 16 contiguous bytes per lane
+// straight from global memory and every lane ends with 8 of its voxel's logits (classes 4*half + 0..3 and
+// 8 + 4*half + 0..3; lane pair (l, l + 32) = one voxel).  Softmax and cross entropy take two exchanges
+// inside the pair.  Backward in the same pass: dx^T[c][voxel] = Wh^T[c][class] * dlogits^T[class][voxel]
+// (dlogits rounded to bf16 for this product), and dWh[class][c] += dlogits^T * x over the voxels with
+// the fp32 instruction v_mfma_f32_32x32x2_f32, whose operands are one float per lane read from a
+// [voxel][class] / [voxel][channel] staging tile in LDS; dbh from per-lane sums.  One pass over x.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 hbf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float hf32x16;
+
+__device__ __forceinline__ uint32_t head_pack_bf16(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+
+// MODE 0: logits only.  MODE 1: + loss, dx, per-wave partials of dWh and dbh.
+template <int MODE>
+__global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
+                                                        const float* __restrict__ bh, int K, int C, int64_t Vtot,
+                                                        const int32_t* __restrict__ labels, float* __restrict__ logits,
+                                                        bf16_t* __restrict__ dx, int lddx, float* __restrict__ loss_part,
+                                                        float* __restrict__ wpart, float* __restrict__ bpart) {
+    __shared__ float dls[4][32][33];   // per wave: dlogits of 32 voxels x 32 (padded) classes
+    __shared__ float xs[4][32][65];    // per wave: activations of 32 voxels x up to 64 channels, fp32
+    __shared__ float red[256];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+    const int CK = C >> 4;                 // 16-channel k-steps
+    const int CB = (C + 31) >> 5;          // 32-channel row blocks of dx / column blocks of dWh
+    // forward A fragments: row = class l32, k = channels 16*kc + 8*half + e
+    hbf16x8 afw[4], abw[2];
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) {
+        uint4 q = make_uint4(0, 0, 0, 0);
+        if (kc < CK && l32 < K) q = *reinterpret_cast<const uint4*>(wh + (size_t)l32 * C + 16 * kc + 8 * half);
+        afw[kc] = __builtin_bit_cast(hbf16x8, q);
+    }
+    // backward A fragments: row = channel 32*cb + l32, k = classes 8*half + e
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        uint32_t r[4] = {0, 0, 0, 0};
+        const int ch = 32 * cb + l32;
+        if (cb < CB && ch < C) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = 8 * half + e;
+                const uint32_t b = k < K ? (uint32_t)wh[(size_t)k * C + ch] : 0u;
+                r[e >> 1] |= b << (16 * (e & 1));
+            }
+        }
+        abw[cb] = __builtin_bit_cast(hbf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+    }
+    // this lane's 8 classes and their biases
+    int cls[8];
+    float bias[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        cls[i] = 8 * (i >> 2) + 4 * half + (i & 3);
+        bias[i] = (bh && cls[i] < K) ? bh[cls[i]] : 0.f;
+    }
+    if (MODE == 1) {
+        for (int i = lane; i < 32 * 33; i += 64) (&dls[wv][0][0])[i] = 0.f;   // classes 16..31 stay zero
+    }
+    hf32x16 accw[2];
+    float dbsum[8];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accw[cb][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dbsum[i] = 0.f;
+    float lsum = 0.f;
+    const float invV = 1.0f / (float)Vtot;
+    const int64_t groups = (Vtot + 31) / 32;
+    for (int64_t g = (int64_t)blockIdx.x * 4 + wv; g < groups; g += (int64_t)gridDim.x * 4) {
+        const int64_t v = g * 32 + l32;
+        const bool valid = v < Vtot;
+        const bf16_t* xp = x + (valid ? v : 0) * ldx;
+        uint4 xq[4];
+        hf32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+            xq[kc] = make_uint4(0, 0, 0, 0);
+            if (kc < CK) {
+                if (valid) xq[kc] = *reinterpret_cast<const uint4*>(xp + 16 * kc + 8 * half);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afw[kc], __builtin_bit_cast(hbf16x8, xq[kc]), acc, 0, 0, 0);
+            }
+        }
+        float lg[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lg[i] = acc[i] + bias[i];
+        if (logits && valid) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (cls[i] < K) logits[v * K + cls[i]] = lg[i];
+        }
+        if (MODE == 1) {
+            float m = -3.0e38f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (cls[i] < K) m = lg[i] > m ? lg[i] : m;
+            const float mo = __shfl_xor(m, 32);
+            m = mo > m ? mo : m;
+            float se = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (cls[i] < K) se += expf(lg[i] - m);
+            se += __shfl_xor(se, 32);
+            const float lse = m + logf(se);
+            const int lab = valid ? labels[v] : -1;
+            float ll = 0.f, dl[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                dl[i] = 0.f;
+                if (cls[i] < K && valid) {
+                    if (cls[i] == lab) ll = lg[i];
+                    dl[i] = (expf(lg[i] - lse) - (cls[i] == lab ? 1.f : 0.f)) * invV;
+                }
+                dbsum[i] += dl[i];
+            }
+            ll += __shfl_xor(ll, 32);
+            if (valid && half == 0) lsum += (lse - ll) * invV;
+            // dlogits^T as the B operand of the dx product: this lane needs classes 8*half .. 8*half+7
+            float snd[4], rcv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) snd[j] = half == 0 ? dl[4 + j] : dl[j];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rcv[j] = __shfl_xor(snd[j], 32);
+            float bk[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bk[j] = half == 0 ? dl[j] : rcv[j];
+                bk[4 + j] = half == 0 ? rcv[j] : dl[4 + j];
+            }
+            const hbf16x8 bdl = __builtin_bit_cast(hbf16x8, make_uint4(head_pack_bf16(bk[0], bk[1]), head_pack_bf16(bk[2], bk[3]),
+                                                                         head_pack_bf16(bk[4], bk[5]), head_pack_bf16(bk[6], bk[7])));
+            if (dx) {
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    if (cb < CB) {
+                        hf32x16 a2;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) a2[r] = 0.f;
+                        a2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(abw[cb], bdl, a2, 0, 0, 0);
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            const int ch = 32 * cb + 8 * rg + 4 * half;
+                            if (valid && ch < C)
+                                *reinterpret_cast<uint2*>(dx + v * lddx + ch) =
+                                    make_uint2(head_pack_bf16(a2[rg * 4 + 0], a2[rg * 4 + 1]), head_pack_bf16(a2[rg * 4 + 2], a2[rg * 4 + 3]));
+                        }
+                    }
+                }
+            }
+            if (wpart) {
+                // stage dlogits [voxel][class] and x [voxel][channel] (fp32) for the voxel-reduction product
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dls[wv][l32][cls[i]] = dl[i];
+#pragma unroll
+                for (int kc = 0; kc < 4; ++kc) {
+                    if (kc < CK) {
+                        const uint32_t r4[4] = {xq[kc].x, xq[kc].y, xq[kc].z, xq[kc].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            xs[wv][l32][16 * kc + 8 * half + 2 * e] = __uint_as_float(r4[e] << 16);
+                            xs[wv][l32][16 * kc + 8 * half + 2 * e + 1] = __uint_as_float(r4[e] & 0xFFFF0000u);
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int kv = 0; kv < 16; ++kv) {
+                    const float av = dls[wv][2 * kv + half][l32];
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) {
+                        if (cb < CB) {
+                            const int ch = 32 * cb + l32;
+                            const float bv = ch < C ? xs[wv][2 * kv + half][ch] : 0.f;
+                            accw[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, accw[cb], 0, 0, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+    if (MODE == 1) {
+        red[threadIdx.x] = lsum;
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) loss_part[blockIdx.x] = red[0];
+        const int slot = blockIdx.x * 4 + wv;
+        if (wpart) {
+            // accw: row = class 8*(r/4) + 4*half + (r%4), column = channel 32*cb + l32
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int k = 8 * (r >> 2) + 4 * half + (r & 3), ch = 32 * cb + l32;
+                    if (cb < CB && k < K && ch < C) wpart[((size_t)slot * K + k) * C + ch] = accw[cb][r];
+                }
+        }
+        if (bpart) {
+            // fold the 32 voxel lanes of each half
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+#pragma unroll
+                for (int m = 1; m < 32; m <<= 1) dbsum[i] += __shfl_xor(dbsum[i], m);
+                if (l32 == 0 && cls[i] < K) bpart[(size_t)slot * K + cls[i]] = dbsum[i];
+            }
+        }
+    }
+}
+
+static bool head_mfma_ok(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh, int classes,
+                         const lamp_tensor_desc* dxd, const void* dx) {
+    const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+    if (xd->dtype != LAMP_BF16 || nm || xd->c % 16 || xd->c > 64 || xd->ldc % 8 || classes > 16) return false;
+    if (!aligned16(x) || !aligned16(wh)) return false;
+    if (dx && (dxd->ldc % 4 || (((uintptr_t)dx) & 7u))) return false;
+    return true;
+}
+static int head_mfma_blocks(int64_t V) {
+    int64_t b = ((V + 31) / 32 + 3) / 4;
+    return (int)(b > 1024 ? 1024 : (b < 1 ? 1 : b));
+}
+
 static int head_blocks(int64_t V) {
     int64_t b = (V + 255) / 256;
     return (int)(b > 2048 ? 2048 : b);
@@ -133,6 +363,13 @@ static int head_blocks(int64_t V) {
 static int head_splits(int64_t V) {
     int64_t s = (V + 511) / 512;
     return (int)(s > 4096 ? 4096 : (s < 1 ? 1 : s));
+}
+static int head_mfma_blocks(int64_t V);
+// partial slots of the weight gradient the workspace must hold: the generic path's splits or one per wave
+// of the matrix-core path
+static int head_wslots(int64_t V) {
+    const int a = head_splits(V), b = 4 * head_mfma_blocks(V);
+    return a > b ? a : b;
 }
 
 static lamp_status head_check(const lamp_tensor_desc* xd, const void* x, const void* wh, int classes) {
@@ -160,6 +397,13 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
     if (!logits) return LAMP_ERR_NULL;
     if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
+    if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr)) {
+        hipLaunchKernelGGL((head_mfma_kernel<0>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)x,
+                           xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0, nullptr, nullptr,
+                           nullptr);
+        LAMP_CHECK_LAUNCH();
+        return LAMP_OK;
+    }
     const size_t shm = (size_t)classes * xd->c * sizeof(float);
     NormIn nm = make_norm(xnorm);
     const int vec = pick_vec(xd->dtype, xd->c, {xd->ldc}, {x});
@@ -177,8 +421,9 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
 extern "C" size_t lamp_head_ce_workspace_bytes(const lamp_tensor_desc* xd, int classes) {
     if (!desc_ok(xd) || classes < 1) return 0;
     const int64_t Vt = nvox(xd);
-    return align_up((size_t)Vt * classes * sizeof(float)) + align_up((size_t)head_blocks(Vt) * sizeof(float)) +
-           align_up((size_t)head_splits(Vt) * classes * xd->c * sizeof(float)) + colsum_ws_bytes(Vt, classes);
+    return align_up((size_t)Vt * classes * sizeof(float)) + align_up((size_t)2048 * sizeof(float)) +
+           align_up((size_t)head_wslots(Vt) * classes * xd->c * sizeof(float)) + colsum_ws_bytes(Vt, classes) +
+           align_up((size_t)4096 * classes * sizeof(float));
 }
 
 extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh,
@@ -204,12 +449,25 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
     Carver cv(ws, ws_bytes);
     float* dlogits = (float*)cv.take((size_t)Vt * K * sizeof(float));
     const int nb = head_blocks(Vt);
-    float* lpart = (float*)cv.take((size_t)nb * sizeof(float));
+    float* lpart = (float*)cv.take((size_t)2048 * sizeof(float));   // one loss partial per workgroup of either path
     const int S = head_splits(Vt);
-    float* wpart = (float*)cv.take((size_t)S * K * C * sizeof(float));
+    float* wpart = (float*)cv.take((size_t)head_wslots(Vt) * K * C * sizeof(float));
     const size_t csb = colsum_ws_bytes(Vt, K);
     void* csws = cv.take(csb);
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+    if (head_mfma_ok(xd, x, xnorm, wh, K, dxd, dx)) {
+        // one pass: logits, loss, dx, per-wave partials of dWh and dbh (the dlogits buffer is not used)
+        float* bpart = (float*)cv.take((size_t)4096 * K * sizeof(float));
+        if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+        const int nbm = head_mfma_blocks(Vt);   // 4 * nbm <= 4096 partial slots
+        hipLaunchKernelGGL((head_mfma_kernel<1>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, K,
+                           C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
+        LAMP_CHECK_LAUNCH();
+        if ((st = launch_reduce_partials(lpart, nbm, 1, loss, 0.f, s)) != LAMP_OK) return st;
+        if (dwh && (st = launch_reduce_partials(wpart, nbm * 4, (int64_t)K * C, dwh, beta, s)) != LAMP_OK) return st;
+        if (dbh && (st = launch_reduce_partials(bpart, nbm * 4, K, dbh, beta, s)) != LAMP_OK) return st;
+        return LAMP_OK;
+    }
     const size_t shm = (size_t)K * C * sizeof(float);
     NormIn nm = make_norm(xnorm);
     const int vec = pick_vec(xd->dtype, C, {xd->ldc, lddx}, {x, dx});
