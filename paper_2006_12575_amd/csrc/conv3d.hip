@@ -122,6 +122,80 @@ __global__ __launch_bounds__(256) void conv3d_cin1_fwd_kernel(const bf16_t* __re
     }
 }
 
+// Forward for Cin == 1 with C_out % 32 == 0 on the matrix cores: z^T[co][voxel] = W[co][tap] * X27^T[tap][voxel],
+// taps (27, padded to 32) as the reduction dimension.  A = weights (kept in registers), B = the gathered
+// neighbours of 32 consecutive voxels (8 two-byte loads per lane and k-block, served by the caches); every
+// lane ends with 4 consecutive channels per register group of its voxel and stores them as 8 bytes.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 c1_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float c1_f32x16;
+__global__ __launch_bounds__(256, 4) void conv3d_cin1_fwd_mfma_kernel(const bf16_t* __restrict__ x, int ldx,
+                                                                      const bf16_t* __restrict__ w, bf16_t* __restrict__ z,
+                                                                      int ldz, int N, int D, int H, int W, int Cout) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
+    const int CB = Cout >> 5;
+    c1_bf16x8 a[4][2];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            uint32_t r[4] = {0, 0, 0, 0};
+            if (cb < CB) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int t = 16 * kb + 8 * half + e;
+                    const uint32_t b = t < 27 ? (uint32_t)w[(size_t)(32 * cb + l32) * 27 + t] : 0u;
+                    r[e >> 1] |= b << (16 * (e & 1));
+                }
+            }
+            a[cb][kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+        }
+    const int64_t total = (int64_t)N * D * H * W;
+    const int64_t groups = (total + 31) / 32;
+    for (int64_t g = (int64_t)blockIdx.x * 4 + wv; g < groups; g += (int64_t)gridDim.x * 4) {
+        const int64_t v = g * 32 + l32;
+        const bool valid = v < total;
+        const int64_t vc = valid ? v : 0;
+        const int wq = (int)(vc % W);
+        int64_t rr = vc / W;
+        const int h = (int)(rr % H);
+        rr /= H;
+        const int d = (int)(rr % D);
+        const int n = (int)(rr / D);
+        c1_bf16x8 b[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            uint32_t r[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int t = 16 * kb + 8 * half + e;
+                const int id = d + t / 9 - 1, ih = h + (t / 3) % 3 - 1, iw = wq + t % 3 - 1;
+                const bool in = valid && t < 27 && id >= 0 && id < D && ih >= 0 && ih < H && iw >= 0 && iw < W;
+                const uint32_t xv = in ? (uint32_t)x[((((int64_t)n * D + id) * H + ih) * W + iw) * ldx] : 0u;
+                r[e >> 1] |= xv << (16 * (e & 1));
+            }
+            b[kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+        }
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+            if (cb < CB) {
+                c1_f32x16 acc;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb][0], b[0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb][1], b[1], acc, 0, 0, 0);
+                if (valid) {
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const uint32_t p0 = (uint32_t)f2bf(acc[rg * 4 + 0]) | ((uint32_t)f2bf(acc[rg * 4 + 1]) << 16);
+                        const uint32_t p1 = (uint32_t)f2bf(acc[rg * 4 + 2]) | ((uint32_t)f2bf(acc[rg * 4 + 3]) << 16);
+                        *reinterpret_cast<uint2*>(z + v * ldz + 32 * cb + 8 * rg + 4 * half) = make_uint2(p0, p1);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Weight gradient for Cin == 1: dW[co][tap] = sum_v dz[v][co] * x[v + tap], as a matrix-core product
 // with the voxels as the reduction dimension.  Per step a wave multiplies A = dz^T (32 channels x 16
 // voxels of one W-row) by B = the gathered neighbours (16 voxels x 32 taps, taps 27..31 zero); both
@@ -256,8 +330,15 @@ extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x
     if (mfma_conv_supported(xd, zd, xnorm, bias))
         return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s);
     if (cin1_fwd_ok(xd, zd, xnorm, bias, z)) {
-        hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
-                           (const bf16_t*)w, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
+        if (zd->c % 32 == 0) {
+            const int64_t wg = (nvox(zd) + 127) / 128;
+            const dim3 grid((unsigned)(wg > 8192 ? 8192 : wg));
+            hipLaunchKernelGGL(conv3d_cin1_fwd_mfma_kernel, grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)w,
+                               (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
+        } else {
+            hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                               (const bf16_t*)w, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
+        }
         LAMP_CHECK_LAUNCH();
     } else {
         st = launch_direct<false>(xd, x, make_norm(xnorm), w, bias, zd, z, s);
