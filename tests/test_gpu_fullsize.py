@@ -138,3 +138,36 @@ def test_full_size_determinism(L, block):
     L.lamp_conv3d_wgrad(block["x"], block["dz"], dw2)
     assert torch.equal(z2, block["z"]) and torch.equal(st2, block["st"])
     assert torch.equal(dx2, block["dx"]) and torch.equal(dw2, block["dw"])
+
+
+@pytest.mark.timeout(900)
+def test_unet_train_fullsize_sampled(L):
+    """The whole-volume training workload at its full size (5 levels, base 32, 2 x 128^3 CT-like
+    volumes with organ labels, 10 classes, bf16): (a) the layer-by-layer chain, every layer checked
+    against the oracle on the GPU's own inputs of that layer -- 3x3x3 convolutions on sampled
+    outputs, every O(V) op in full; (b) the whole-network entry point, as bench.py calls it, equal
+    to that chain bit for bit (logits, loss, every gradient)."""
+    from gpu_chain import Chain
+    from test_gpu_unet import make_net
+    levels, base, K, dims = 5, 32, 10, (2, 128, 128, 128)
+    N, Dd, H, W = dims
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1004)
+    rx, rl = S.streams(1004, 3)[1:]
+    x = torch.from_numpy(S.ct_volume(rx, N, Dd, H, W)).to(BF).to(DEV).reshape(N, Dd, H, W, 1)
+    lab = torch.from_numpy(S.organ_labels(rl, N, Dd, H, W, K)).to(DEV)
+    ud = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
+    logits = torch.empty((N, Dd, H, W, K), dtype=F32, device=DEV)
+    loss = torch.empty((), dtype=F32, device=DEV)
+    grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
+    ch = Chain(L, levels, base, 1, K, False, BF, names, dev, verify="sampled")
+    lg = ch.forward(x)
+    print("forward checked:", ch.checked, flush=True)
+    assert torch.equal(lg, logits), "whole-net logits differ from the layer-by-layer chain"
+    loss_c, g_c = ch.backward(lab)
+    assert torch.equal(loss_c, loss)
+    for k, g in zip(names, grads):
+        assert torch.equal(g_c[k], g), f"whole-net grad {k} differs from the layer-by-layer chain"
+    print("checked ops:", ch.checked)
+    print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
+    assert ch.checked["conv fwd"] == 18 and ch.checked["conv dgrad"] == 17 and ch.checked["conv wgrad"] == 18
