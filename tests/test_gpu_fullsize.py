@@ -171,3 +171,133 @@ def test_unet_train_fullsize_sampled(L):
     print("checked ops:", ch.checked)
     print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
     assert ch.checked["conv fwd"] == 18 and ch.checked["conv dgrad"] == 17 and ch.checked["conv wgrad"] == 18
+
+
+@pytest.mark.timeout(900)
+def test_unet_infer_fullsize_sampled(L):
+    """Large-input inference at its full size (1 x 256 x 256 x 160 CT-like volume, 5 levels, base 32,
+    bf16): the layer-by-layer forward chain with sampled / full oracle checks of every layer, and
+    the whole-network forward entry point equal to it bit for bit."""
+    from gpu_chain import Chain
+    from test_gpu_unet import make_net
+    levels, base, K = 5, 32, 10
+    N, Dd, H, W = 1, 256, 256, 160
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1005)
+    x = torch.from_numpy(S.ct_volume(S.streams(1005, 2)[1], N, Dd, H, W)).to(BF).to(DEV)
+    ud = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
+    logits = torch.empty((N, Dd, H, W, K), dtype=F32, device=DEV)
+    L.lamp_unet_fwd(ud, dev, x, logits)
+    ch = Chain(L, levels, base, 1, K, False, BF, names, dev, verify="sampled")
+    lg = ch.forward(x)
+    assert torch.equal(lg, logits), "whole-net logits differ from the layer-by-layer chain"
+    print("checked ops:", ch.checked)
+    print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
+    assert ch.checked["conv fwd"] == 18 and ch.checked["convtr fwd"] == 4 and ch.checked["pool fwd"] == 4
+
+
+@pytest.mark.timeout(900)
+def test_sliding_window_fullsize(L):
+    """Sliding-window inference at its full size (75 windows of 64^3, overlap 0.25, over
+    256 x 256 x 160): window enumeration, extraction, Gaussian weights, blending and normalisation
+    against the oracle's sliding-window routine.  The oracle's `net` argument is the GPU patch
+    network run on the windows the ORACLE's enumeration extracts (same batch as the entry point
+    uses), so this isolates everything the sliding-window path adds to the patch network, whose
+    own parity the chain tests cover."""
+    from oracle import sliding
+    from test_gpu_unet import make_net
+    levels, base, K, P = 5, 32, 10, 64
+    Dd, H, W = 256, 256, 160
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1005)
+    vol = torch.from_numpy(S.ct_volume(S.streams(1005, 2)[1], 1, Dd, H, W)).to(BF).to(DEV)
+    cnt = L.lamp_sliding_window_count(Dd, H, W, P, 0.25)
+    starts = [sliding.window_starts(n, P) for n in (Dd, H, W)]
+    assert cnt == len(starts[0]) * len(starts[1]) * len(starts[2]) == 75
+    pd = L.unet_desc(levels, base, 1, K, cnt, P, P, P, BF)
+    out = torch.empty((1, Dd, H, W, K), dtype=F32, device=DEV)
+    L.lamp_sliding_window_fwd(pd, dev, vol, out)
+    # patch logits of the oracle-enumerated windows, one batched GPU forward
+    wins = torch.stack([vol[0, d0:d0 + P, h0:h0 + P, w0:w0 + P, :] for d0 in starts[0] for h0 in starts[1] for w0 in starts[2]])
+    plog = torch.empty((cnt, P, P, P, K), dtype=F32, device=DEV)
+    L.lamp_unet_fwd(pd, dev, wins.contiguous(), plog)
+    plog_h, wins_h = as64(plog), as64(wins)
+    k = [0]
+
+    def net(win):
+        i = k[0]
+        k[0] += 1
+        np.testing.assert_array_equal(win[0], wins_h[i])
+        return plog_h[i:i + 1]
+
+    ref = sliding.sliding_window(net, as64(vol), patch=P)
+    assert k[0] == cnt
+    e = check(as64(out), ref, F32, "full-size sliding-window logits", tol=1e-4)
+    print(f"sliding window, {cnt} windows: E_inf = {e:.2e}")
+    # cross-check with the one-pass forward: both segment the volume alike away from near-ties
+    ud = L.unet_desc(levels, base, 1, K, 1, Dd, H, W, BF)
+    whole = torch.empty_like(out)
+    L.lamp_unet_fwd(ud, dev, vol, whole)
+    agree = (whole.argmax(-1) == out.argmax(-1)).float().mean().item()
+    print(f"arg-max agreement one pass vs sliding windows: {agree:.4f}")
+
+
+@pytest.mark.timeout(900)
+def test_stage_fullsize_sampled(L):
+    """One pipeline partition (encoder blocks 1-2, base 64; Sec. 2.1 / Eq. 3) at its full size,
+    1 x 192^3 CT-like input, bf16, forward + backward as bench.py times it: the partition's
+    outputs and gradients equal, bit for bit, the layer-by-layer chain whose layers are checked
+    against the oracle (3x3x3 convolutions on sampled outputs, O(V) ops in full)."""
+    from gpu_chain import Chain
+    from test_gpu_unet import make_net
+    levels, base, K = 3, 64, 10
+    N, Dd, H, W = 1, 192, 192, 192
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1003)
+    sp = dev[:4]
+    rx, rg = S.streams(1003, 3)[1:]
+    x = torch.from_numpy(S.ct_volume(rx, N, Dd, H, W)).to(BF).to(DEV)
+    ud = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
+    ws = torch.empty(L.lamp_unet_stage_workspace_bytes(ud, 1, 2), dtype=torch.uint8, device=DEV)
+    pooled = torch.empty((N, Dd // 4, H // 4, W // 4, 2 * base), dtype=BF, device=DEV)
+    skips = [torch.empty((N, Dd, H, W, base), dtype=BF, device=DEV),
+             torch.empty((N, Dd // 2, H // 2, W // 2, 2 * base), dtype=BF, device=DEV)]
+    L.lamp_unet_stage_fwd(ud, 1, 2, sp, x, pooled, skips, ws)
+    ch = Chain(L, levels, base, 1, K, False, BF, names, dev, verify="sampled")
+    ch.nsample = 256
+    # blocks 1-2 of the chain (forward of the whole net is not needed)
+    ch.enc, ch.pooled = {}, {}
+    cur = x
+    for l in (1, 2):
+        ch.enc[l] = ch.block(f"enc{l}", cur)
+        yv = ch.enc[l][1]["y"]
+        p = torch.empty((N, yv.shape[1] // 2, yv.shape[2] // 2, yv.shape[3] // 2, yv.shape[4]), dtype=BF, device=DEV)
+        L.lamp_maxpool2_fwd(yv, p)
+        np.testing.assert_array_equal(as64(p), O.maxpool2_fwd(as64(yv)))
+        ch.pooled[l] = cur = p
+    assert torch.equal(skips[0], ch.enc[1][1]["y"]) and torch.equal(skips[1], ch.enc[2][1]["y"])
+    assert torch.equal(pooled, ch.pooled[2])
+    print("stage forward checked:", ch.checked, flush=True)
+
+    def dev_normal(shape):
+        t = torch.empty(shape, dtype=BF, device=DEV)
+        for d in range(shape[1]):
+            t[:, d] = torch.from_numpy(S.normal(rg, (shape[0],) + tuple(shape[2:]))).to(BF).to(DEV)
+        return t
+
+    gp = dev_normal(pooled.shape)
+    gs = [dev_normal(s.shape) for s in skips]
+    grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in sp]
+    L.lamp_unet_stage_bwd(ud, 1, 2, sp, x, skips, gp, gs, grads, ws)
+    cg = {}
+    g = gp
+    for l in (2, 1):
+        c1, c2 = ch.enc[l]
+        gy = torch.empty(c2["y"].shape, dtype=BF, device=DEV)
+        L.lamp_maxpool2_bwd(c2["y"], g, gy, add=gs[l - 1])
+        ref = O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(gs[l - 1])
+        check(as64(gy), ref, BF, f"pool bwd: enc{l}", tol=4e-3)
+        del ref
+        g = ch.conv_bwd(c2, gy, cg, True)
+        g = ch.conv_bwd(c1, g, cg, l > 1)
+    for kname, gr in zip(names[:4], grads):
+        assert torch.equal(gr, cg[kname]), f"stage grad {kname} differs from the chain"
+    print("checked ops:", ch.checked)
+    print("worst teacher-forced E_inf per op:", {k_: f"{v:.1e}" for k_, v in ch.worst.items()})
