@@ -26,6 +26,8 @@ struct CtArgs {
     int N, D, H, W;       // coarse (input-resolution) dims
     int Ci, Co;
     int ldb, ldo;         // channel strides of b and out
+    uint32_t mW, mH, mD;  // v / d == (v * m) >> s for v < 2^31 (round-up reciprocal, see ct_magic)
+    int sW, sH, sD;
 };
 
 // wt'[(tap*Co + co)][ci] = wt[ci][tap][co]
@@ -144,6 +146,280 @@ __global__ __launch_bounds__(256) void convtr_gemm_kernel(CtArgs a) {
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Kernels for channel counts that are multiples of 32: the fine-resolution tensor is written
+// (forward) and read (data gradient) in whole 64-byte pieces -- 32 channels of one fine voxel, four
+// lanes of 16 bytes side by side -- instead of one 8-byte piece per lane.  A per-wave LDS buffer
+// transposes between that memory order and the matrix-core fragment order; only the owning wave
+// touches its buffer, so no workgroup barrier is needed.
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float ct_f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 ct_bf16x2;
+__device__ __forceinline__ uint32_t ct_pack(float lo, float hi) {
+    ct_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ct_bf16x2));
+}
+
+static constexpr int CT_ROW = 80;  // bytes per voxel row in the transposing buffer: 64 of data, padded
+
+// fine-resolution voxel (2d,2h,2w) of coarse voxel v (v < 2^31)
+__device__ __forceinline__ uint32_t ct_div(uint32_t v, uint32_t m, int sh) { return (uint32_t)(((uint64_t)v * m) >> sh); }
+__device__ __forceinline__ int64_t ct_fine_origin(const CtArgs& a, int64_t v) {
+    const uint32_t vi = (uint32_t)v;
+    uint32_t r = ct_div(vi, a.mW, a.sW);
+    const uint32_t w = vi - r * (uint32_t)a.W;
+    uint32_t r2 = ct_div(r, a.mH, a.sH);
+    const uint32_t h = r - r2 * (uint32_t)a.H;
+    const uint32_t n = ct_div(r2, a.mD, a.sD);
+    const uint32_t d = r2 - n * (uint32_t)a.D;
+    return (((int64_t)n * 2 * a.D + 2 * d) * 2 * a.H + 2 * h) * 2 * a.W + 2 * w;
+}
+__device__ __forceinline__ int64_t ct_tap_off(const CtArgs& a, int tap) {
+    return ((int64_t)(tap >> 2) * 2 * a.H + ((tap >> 1) & 1)) * 2 * a.W + (tap & 1);
+}
+
+// Forward.  One wave = VB*32 coarse voxels x one block of RB units (a unit is (tap, 32 output
+// channels) = 32 rows of the repacked weight).  With KS > 0 (K = 16*KS input channels) the wave's x
+// operand is fetched up front in one go.  Every load of a wave is issued before its first store:
+// loads and stores complete in one queue, so a load behind a store would wait for the store; the
+// bias therefore sits in LDS.  Requires Co % 32 == 0, Co <= 256 * 4, Ci % 16 == 0, < 2^31 voxels.
+template <int RB, int VB, int KS>
+__global__ __launch_bounds__(256) void convtr_fwd32_kernel(CtArgs a) {
+    constexpr int VW = 32 * VB;  // voxels per wave
+    __shared__ __attribute__((aligned(16))) char tb[4][VW * CT_ROW];
+    __shared__ __attribute__((aligned(16))) float bsh[4][1024];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t nvox = (int64_t)a.N * a.D * a.H * a.W;
+    const int K = KS > 0 ? 16 * KS : a.K;
+    // workgroup id -> (voxel group, row block): ids are dealt round-robin to the 8 XCDs, so the row
+    // blocks of one voxel group take consecutive slots of ONE XCD and share its L2 for x
+    const int nblocks = a.rows / (32 * RB);
+    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const int yb = (int)(slot % (uint32_t)nblocks);
+    const int64_t vg = (int64_t)(slot / (uint32_t)nblocks) * 8 + xcd;
+    const int64_t v0 = (vg * 4 + wv) * VW;
+    if (v0 >= nvox) return;
+    const int r0 = yb * (32 * RB);
+
+    const bf16_t* xrow[VB];
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb) {
+        int64_t v = v0 + vb * 32 + l32;  // columns past the end repeat the last voxel and are never stored
+        if (v >= nvox) v = nvox - 1;
+        xrow[vb] = a.b + v * a.ldb + 8 * half;
+    }
+    const bf16_t* arow = a.a + (int64_t)(r0 + l32) * K + 8 * half;
+    bf16x8 ball[KS > 0 ? KS : 1][VB];
+    if (KS > 0) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb) ball[ks][vb] = *reinterpret_cast<const bf16x8*>(xrow[vb] + ks * 16);
+    }
+    // bias -> this wave's LDS copy
+    for (int c = lane * 4; c < a.Co; c += 256) {
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.bias) bv = make_float4(a.bias[c], a.bias[c + 1], a.bias[c + 2], a.bias[c + 3]);
+        *reinterpret_cast<float4*>(&bsh[wv][c]) = bv;
+    }
+    // the voxels this lane stores: 16 per pass, four lanes per voxel
+    int64_t fs[2 * VB];
+#pragma unroll
+    for (int it = 0; it < 2 * VB; ++it) {
+        const int64_t v = v0 + it * 16 + (lane >> 2);
+        fs[it] = v < nvox ? ct_fine_origin(a, v) : -1;
+    }
+
+    f32x16 acc[RB][VB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][vb][r] = 0.f;
+
+    if (KS > 0) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 af[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) af[rb] = *reinterpret_cast<const bf16x8*>(arow + rb * 32 * K + ks * 16);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int vb = 0; vb < VB; ++vb)
+                    acc[rb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb], ball[ks][vb], acc[rb][vb], 0, 0, 0);
+        }
+    } else {
+        // streaming reduction, operands fetched one step ahead
+        bf16x8 bfn[VB], afn[RB];
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb) bfn[vb] = *reinterpret_cast<const bf16x8*>(xrow[vb]);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) afn[rb] = *reinterpret_cast<const bf16x8*>(arow + (int64_t)rb * 32 * K);
+        for (int k0 = 0; k0 < K; k0 += 16) {
+            bf16x8 bf[VB], af[RB];
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb) bf[vb] = bfn[vb];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) af[rb] = afn[rb];
+            if (k0 + 16 < K) {
+#pragma unroll
+                for (int vb = 0; vb < VB; ++vb) bfn[vb] = *reinterpret_cast<const bf16x8*>(xrow[vb] + k0 + 16);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) afn[rb] = *reinterpret_cast<const bf16x8*>(arow + (int64_t)rb * 32 * K + k0 + 16);
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int vb = 0; vb < VB; ++vb)
+                    acc[rb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb], bf[vb], acc[rb][vb], 0, 0, 0);
+        }
+    }
+
+    // lane holds, for voxel l32 of block vb, rows 8*(r/4) + 4*half + (r%4) of the unit
+    char* mine = tb[wv];
+    const int cpt = a.Co >> 5;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int unit = (r0 >> 5) + rb;
+        const int tap = unit / cpt, co0 = (unit - tap * cpt) << 5;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int c = rg * 8 + half * 4;
+            const float4 bv = *reinterpret_cast<const float4*>(&bsh[wv][co0 + c]);
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb) {
+                const uint2 pk = make_uint2(ct_pack(acc[rb][vb][rg * 4 + 0] + bv.x, acc[rb][vb][rg * 4 + 1] + bv.y),
+                                            ct_pack(acc[rb][vb][rg * 4 + 2] + bv.z, acc[rb][vb][rg * 4 + 3] + bv.w));
+                *reinterpret_cast<uint2*>(mine + (vb * 32 + l32) * CT_ROW + c * 2) = pk;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const int64_t to = ct_tap_off(a, tap);
+#pragma unroll
+        for (int it = 0; it < 2 * VB; ++it) {
+            const uint4 q = *reinterpret_cast<const uint4*>(mine + (it * 16 + (lane >> 2)) * CT_ROW + (lane & 3) * 16);
+            if (fs[it] >= 0) *reinterpret_cast<uint4*>(a.out + (fs[it] + to) * a.ldo + co0 + (lane & 3) * 8) = q;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Data gradient.  One wave = 64 coarse voxels x RB blocks of 32 input channels; the reduction runs
+// over units of (tap, 32 output channels).  The 64-byte pieces of dy are gathered one unit ahead
+// into registers and handed to the matrix-core fragment order through the wave's double buffer.
+// Requires Co % 32 == 0, Ci % 32 == 0.
+template <int RB>
+__global__ __launch_bounds__(256) void convtr_dgrad32_kernel(CtArgs a) {
+    __shared__ __attribute__((aligned(16))) char tb[4][2][64 * CT_ROW];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t nvox = (int64_t)a.N * a.D * a.H * a.W;
+    const int64_t v0 = ((int64_t)blockIdx.x * 4 + wv) * 64;
+    if (v0 >= nvox) return;
+    const int r0 = blockIdx.y * (32 * RB);
+    const int nrb = min(RB, (a.rows - r0) >> 5);
+
+    int64_t fs[4], vs[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        vs[it] = v0 + it * 16 + (lane >> 2);
+        fs[it] = vs[it] < nvox ? ct_fine_origin(a, vs[it]) : -1;
+    }
+    const bf16_t* arow = a.a + (int64_t)(r0 + l32) * a.K + 8 * half;
+    const int cpt = a.Co >> 5, units = 8 * cpt;
+
+    auto gather = [&](int u, uint4 (&q)[4]) {
+        const int tap = u / cpt, c0 = (u - tap * cpt) << 5;
+        const int64_t to = ct_tap_off(a, tap);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            q[it] = make_uint4(0, 0, 0, 0);
+            if (fs[it] >= 0) q[it] = *reinterpret_cast<const uint4*>(a.b + (fs[it] + to) * a.ldb + c0 + (lane & 3) * 8);
+        }
+    };
+    auto put = [&](char* buf, const uint4 (&q)[4]) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) *reinterpret_cast<uint4*>(buf + (it * 16 + (lane >> 2)) * CT_ROW + (lane & 3) * 16) = q[it];
+    };
+
+    f32x16 acc[RB][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][vb][r] = 0.f;
+
+    uint4 q[4];
+    gather(0, q);
+    put(tb[wv][0], q);
+    __builtin_amdgcn_wave_barrier();
+    for (int u = 0; u < units; ++u) {
+        if (u + 1 < units) gather(u + 1, q);
+        const char* cur = tb[wv][u & 1];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 bf[2], af[RB];
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb)
+                bf[vb] = *reinterpret_cast<const bf16x8*>(cur + (vb * 32 + l32) * CT_ROW + ks * 32 + half * 16);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) af[rb] = gfrag(arow + (int64_t)rb * 32 * a.K + u * 32 + ks * 16, rb < nrb);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int vb = 0; vb < 2; ++vb)
+                    if (rb < nrb) acc[rb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb], bf[vb], acc[rb][vb], 0, 0, 0);
+        }
+        if (u + 1 < units) put(tb[wv][(u + 1) & 1], q);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    char* mine = tb[wv][0];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        if (rb >= nrb) break;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg)
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb) {
+                const uint2 pk = make_uint2(ct_pack(acc[rb][vb][rg * 4 + 0], acc[rb][vb][rg * 4 + 1]),
+                                            ct_pack(acc[rb][vb][rg * 4 + 2], acc[rb][vb][rg * 4 + 3]));
+                *reinterpret_cast<uint2*>(mine + (vb * 32 + l32) * CT_ROW + (rg * 8 + half * 4) * 2) = pk;
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const uint4 o = *reinterpret_cast<const uint4*>(mine + (it * 16 + (lane >> 2)) * CT_ROW + (lane & 3) * 16);
+            if (vs[it] < nvox) *reinterpret_cast<uint4*>(a.out + vs[it] * a.ldo + r0 + rb * 32 + (lane & 3) * 8) = o;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// round-up reciprocal for exact division of v < 2^31 by d: v / d == (v * m) >> s
+static void ct_magic(int d, uint32_t* m, int* s) {
+    int l = 0;
+    while ((1ll << l) < d) ++l;
+    *s = 31 + l;
+    *m = (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)d - 1) / (uint64_t)d);
+}
+static void ct_set_magic(CtArgs& a) {
+    ct_magic(a.W, &a.mW, &a.sW);
+    ct_magic(a.H, &a.mH, &a.sH);
+    ct_magic(a.D, &a.mD, &a.sD);
+}
+
+// 32 rows per wave when the volume is small (more workgroups), 128 otherwise
+static int ct_row_blocks(int64_t nv, int rows) {
+    if (nv < 65536) return 1;
+    return rows >= 128 ? 4 : (rows >= 64 ? 2 : 1);
+}
+
 bool mfma_convtr_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd, const lamp_norm_in* xnorm) {
     if (xd->dtype != LAMP_BF16) return false;
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
@@ -167,6 +443,24 @@ lamp_status mfma_convtr_fwd(const lamp_tensor_desc* xd, const void* x, const voi
     CtArgs a;
     a.a = wp; a.b = (const bf16_t*)x; a.out = (bf16_t*)y; a.bias = bias; a.rows = 8 * Co; a.K = Ci;
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = Ci; a.Co = Co; a.ldb = xd->ldc; a.ldo = yd->ldc;
+    if (Co % 32 == 0 && Co <= 1024 && yd->ldc % 8 == 0 && ((((uintptr_t)y) & 15u) == 0) && nvox(xd) < ((int64_t)1 << 31)) {
+        const int64_t nv = nvox(xd);
+        ct_set_magic(a);
+        if (nv >= 65536) {
+            // a wave = 32 voxels x 8 units: for Co = 32 it writes all eight taps of its voxels
+            const int64_t groups8 = cdiv(cdiv(nv, 128), 8) * 8;  // voxel groups, padded to whole XCD rounds
+            dim3 grid((unsigned)(groups8 * (a.rows / 256)));
+            if (Ci == 64) hipLaunchKernelGGL((convtr_fwd32_kernel<8, 1, 4>), grid, dim3(256), 0, s, a);
+            else if (Ci == 128) hipLaunchKernelGGL((convtr_fwd32_kernel<8, 1, 8>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((convtr_fwd32_kernel<8, 1, 0>), grid, dim3(256), 0, s, a);
+        } else {
+            const int64_t groups8 = cdiv(cdiv(nv, 256), 8) * 8;
+            dim3 grid((unsigned)(groups8 * (a.rows / 32)));
+            hipLaunchKernelGGL((convtr_fwd32_kernel<1, 2, 0>), grid, dim3(256), 0, s, a);
+        }
+        LAMP_CHECK_LAUNCH();
+        return LAMP_OK;
+    }
     dim3 grid(cdiv(nvox(xd), 256), cdiv(a.rows, 128));
     hipLaunchKernelGGL((convtr_gemm_kernel<0>), grid, dim3(256), 0, s, a);
     LAMP_CHECK_LAUNCH();
@@ -185,6 +479,17 @@ lamp_status mfma_convtr_dgrad(const lamp_tensor_desc* xd, const void* wt, const 
     CtArgs a;
     a.a = (const bf16_t*)wt; a.b = (const bf16_t*)dy; a.out = (bf16_t*)dx; a.bias = nullptr; a.rows = xd->c; a.K = 8 * dyd->c;
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c; a.ldb = dyd->ldc; a.ldo = dxd->ldc;
+    if (a.Co % 32 == 0 && a.Ci % 32 == 0 && dyd->ldc % 8 == 0 && dxd->ldc % 8 == 0 && ((((uintptr_t)dx) & 15u) == 0) &&
+        nvox(xd) < ((int64_t)1 << 31)) {
+        ct_set_magic(a);
+        const int rb = ct_row_blocks(nvox(xd), a.rows);
+        dim3 grid(cdiv(nvox(xd), 256), cdiv(a.rows, 32 * rb));
+        if (rb == 4) hipLaunchKernelGGL((convtr_dgrad32_kernel<4>), grid, dim3(256), 0, s, a);
+        else if (rb == 2) hipLaunchKernelGGL((convtr_dgrad32_kernel<2>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((convtr_dgrad32_kernel<1>), grid, dim3(256), 0, s, a);
+        LAMP_CHECK_LAUNCH();
+        return LAMP_OK;
+    }
     dim3 grid(cdiv(nvox(xd), 256), cdiv(a.rows, 128));
     hipLaunchKernelGGL((convtr_gemm_kernel<1>), grid, dim3(256), 0, s, a);
     LAMP_CHECK_LAUNCH();

@@ -7,9 +7,17 @@
 namespace lamp {
 
 
-static const int kRowsPerChunk = 2048;
+// Rows of one partial sum: about 2048 chunks per sample so that small volumes still fill the chip,
+// never fewer than 32 rows.
+static int rows_per_chunk(int64_t v) {
+    const int64_t r = (v + 2047) / 2048;
+    return (int)(r < 32 ? 32 : r);
+}
 
-int stats_chunks(int64_t v) { return (int)((v + kRowsPerChunk - 1) / kRowsPerChunk); }
+int stats_chunks(int64_t v) {
+    const int r = rows_per_chunk(v);
+    return (int)((v + r - 1) / r);
+}
 
 size_t stats_ws_bytes(const lamp_tensor_desc* zd) {
     int64_t V = (int64_t)zd->d * zd->h * zd->w;
@@ -37,7 +45,18 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(const T* __restrict_
     const bool active = r0 < rl && cv * VEC < C;
     if (active) {
         const T* base = z + ((int64_t)n * V) * ld + (int64_t)cv * VEC;
-        for (int64_t r = rbeg + r0; r < rend; r += rl) {
+        int64_t r = rbeg + r0;
+        // four rows in flight; the additions keep the row order
+        for (; r + 3 * (int64_t)rl < rend; r += 4 * (int64_t)rl) {
+            float v[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Vec<T, VEC>::load(base + (r + u * (int64_t)rl) * ld, v[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) { s[i] += v[u][i]; q[i] = fmaf(v[u][i], v[u][i], q[i]); }
+        }
+        for (; r < rend; r += rl) {
             float v[VEC];
             Vec<T, VEC>::load(base + r * ld, v);
 #pragma unroll
@@ -122,7 +141,7 @@ lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, f
     LAMP_DISPATCH_TV(zd->dtype, vec, {
         RowMap m = make_rowmap(zd->c, VEC);
         hipLaunchKernelGGL((stats_partial_kernel<T, VEC>), dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s,
-                           (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, kRowsPerChunk, partial, counts);
+                           (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, rows_per_chunk(V), partial, counts);
     });
     LAMP_CHECK_LAUNCH();
     return launch_stats_finalize(partial, counts, chunks, zd->n, zd->c, eps, stats, s);
@@ -188,10 +207,7 @@ __global__ __launch_bounds__(256) void inorm_bwd_partial_kernel(const T* __restr
         }
         const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
         const T* gb = dy + ((int64_t)n * V) * ldg + (int64_t)cv * VEC;
-        for (int64_t r = rbeg + r0; r < rend; r += rl) {
-            float v[VEC], g[VEC];
-            Vec<T, VEC>::load(zb + r * ldz, v);
-            Vec<T, VEC>::load(gb + r * ldg, g);
+        auto add_row = [&](const float (&v)[VEC], const float (&g)[VEC]) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 float u = norm_u(v[i], a[i], b[i]);
@@ -200,6 +216,24 @@ __global__ __launch_bounds__(256) void inorm_bwd_partial_kernel(const T* __restr
                 s[i] += gg;
                 q[i] = fmaf(gg, zh, q[i]);
             }
+        };
+        int64_t r = rbeg + r0;
+        // four rows in flight; the additions keep the row order
+        for (; r + 3 * (int64_t)rl < rend; r += 4 * (int64_t)rl) {
+            float v[4][VEC], g[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                Vec<T, VEC>::load(zb + (r + u * (int64_t)rl) * ldz, v[u]);
+                Vec<T, VEC>::load(gb + (r + u * (int64_t)rl) * ldg, g[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add_row(v[u], g[u]);
+        }
+        for (; r < rend; r += rl) {
+            float v[VEC], g[VEC];
+            Vec<T, VEC>::load(zb + r * ldz, v);
+            Vec<T, VEC>::load(gb + r * ldg, g);
+            add_row(v, g);
         }
     }
 #pragma unroll
@@ -361,7 +395,7 @@ extern "C" lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc* dyd, const vo
     LAMP_DISPATCH_TV(zd->dtype, vec, {
         RowMap m = make_rowmap(zd->c, VEC);
         hipLaunchKernelGGL((inorm_bwd_partial_kernel<T, VEC>), dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s,
-                           (const T*)dy, dyd->ldc, (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, kRowsPerChunk,
+                           (const T*)dy, dyd->ldc, (const T*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, rows_per_chunk(V),
                            stats, gamma, beta, partial);
     });
     LAMP_CHECK_LAUNCH();

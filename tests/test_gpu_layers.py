@@ -191,7 +191,8 @@ def test_maxpool2_fwd_bwd(L, dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 6, 3), (1, 4, 4, 8, 64, 32), (1, 2, 3, 9, 16, 8), (2, 2, 2, 2, 128, 64)],
+@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 6, 3), (1, 4, 4, 8, 64, 32), (1, 2, 3, 9, 16, 8), (2, 2, 2, 2, 128, 64),
+                                   (1, 5, 6, 7, 32, 64), (1, 33, 40, 50, 64, 64), (1, 33, 40, 50, 160, 32)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_convtr3d_fwd_bwd(L, dtype, shape):
     N, D, H, W, Ci, Co = shape
