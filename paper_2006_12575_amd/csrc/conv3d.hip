@@ -122,77 +122,177 @@ __global__ __launch_bounds__(256) void conv3d_cin1_fwd_kernel(const bf16_t* __re
     }
 }
 
-// Forward for Cin == 1 with C_out % 32 == 0 on the matrix cores: z^T[co][voxel] = W[co][tap] * X27^T[tap][voxel],
-// taps (27, padded to 32) as the reduction dimension.  A = weights (kept in registers), B = the gathered
-// neighbours of 32 consecutive voxels (8 two-byte loads per lane and k-block, served by the caches); every
-// lane ends with 4 consecutive channels per register group of its voxel and stores them as 8 bytes.
+// Forward for Cin == 1 with C_out = 32*CB on the matrix cores: z^T[co][voxel] = W[co][tap] * X27^T[tap][voxel],
+// taps (27, padded to 32) as the reduction dimension, weights kept in registers as the A operand.
+// A workgroup walks blocks of four output rows (one per wave) of one sample: the 3 x 6 input rows a
+// block needs are staged in LDS (zero padded), and the B operand -- the 27 neighbours of 32 voxels
+// -- is gathered from there with 16-bit LDS reads.  The weight rows are permuted so that a lane ends
+// with 16 consecutive channels of its voxel; a per-wave LDS transpose turns that into whole 64-byte
+// pieces for the store (four lanes side by side), and the per-channel sum / sum of squares of the
+// rounded outputs are accumulated on the way for the instance-norm statistics.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 c1_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float c1_f32x16;
-__global__ __launch_bounds__(256, 4) void conv3d_cin1_fwd_mfma_kernel(const bf16_t* __restrict__ x, int ldx,
-                                                                      const bf16_t* __restrict__ w, bf16_t* __restrict__ z,
-                                                                      int ldz, int N, int D, int H, int W, int Cout) {
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
-    const int CB = Cout >> 5;
-    c1_bf16x8 a[4][2];
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float c1_f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 c1_bf16x2;
+__device__ __forceinline__ uint32_t c1_pack(float lo, float hi) {
+    c1_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, c1_bf16x2));
+}
+
+struct Cin1Args {
+    const bf16_t* x; int ldx;
+    const bf16_t* w;
+    bf16_t* z; int ldz;
+    int N, D, H, W;
+    int G;           // 32-voxel groups per row
+    int WP, RS;      // staged row: WP = 32*G + 2 elements (w = -1 .. 32*G), row stride RS elements
+    uint32_t mWP; int sWP;   // e / WP == (e * mWP) >> sWP for e < 2^31
+    float* partial;  // [N][parts][C][2] per-wave (sum, sum of squares), or nullptr
+    int32_t* counts; // [N][parts] voxels behind each partial
+};
+
+static constexpr int C1_TROW = 80;  // bytes per voxel row of the transposing buffer (64 of data, padded)
+
+template <int CB, int NE>
+__global__ __launch_bounds__(256) void conv3d_cin1_fwd_tile_kernel(Cin1Args a) {
+    extern __shared__ __attribute__((aligned(16))) char c1_lds[];
+    char* tb = c1_lds + threadIdx.x / 64 * (32 * C1_TROW);          // this wave's transposing buffer
+    unsigned short* xt = reinterpret_cast<unsigned short*>(c1_lds + 4 * 32 * C1_TROW);  // [18][RS]
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, half = lane >> 5;
+    const int n = blockIdx.y;
+    const int C = 32 * CB;
+
+    // A operand: MFMA row rho of block cb carries channel 32*cb + 16*((rho>>2)&1) + 4*(rho>>3) + (rho&3), so
+    // that a lane's 16 accumulator registers are channels 32*cb + 16*half + 0..15 of its voxel
+    c1_bf16x8 wa[CB][2];
+    {
+        const int ch = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            uint32_t r[4] = {0, 0, 0, 0};
-            if (cb < CB) {
+            for (int kb = 0; kb < 2; ++kb) {
+                uint32_t r[4] = {0, 0, 0, 0};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int t = 16 * kb + 8 * half + e;
-                    const uint32_t b = t < 27 ? (uint32_t)w[(size_t)(32 * cb + l32) * 27 + t] : 0u;
+                    const uint32_t b = t < 27 ? (uint32_t)a.w[(size_t)(32 * cb + ch) * 27 + t] : 0u;
                     r[e >> 1] |= b << (16 * (e & 1));
                 }
+                wa[cb][kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
             }
-            a[cb][kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+    }
+    // B operand: element offsets of the lane's 16 taps inside the staged rows (padded taps repeat tap 26;
+    // their weights are zero)
+    int toff[2][8];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int t = 16 * kb + 8 * half + e;
+            if (t > 26) t = 26;
+            const int kd = t / 9, kh = (t / 3) % 3, kw = t % 3;
+            toff[kb][e] = (kd * 6 + kh + wv) * a.RS + kw + l32;
         }
-    const int64_t total = (int64_t)N * D * H * W;
-    const int64_t groups = (total + 31) / 32;
-    for (int64_t g = (int64_t)blockIdx.x * 4 + wv; g < groups; g += (int64_t)gridDim.x * 4) {
-        const int64_t v = g * 32 + l32;
-        const bool valid = v < total;
-        const int64_t vc = valid ? v : 0;
-        const int wq = (int)(vc % W);
-        int64_t rr = vc / W;
-        const int h = (int)(rr % H);
-        rr /= H;
-        const int d = (int)(rr % D);
-        const int n = (int)(rr / D);
-        c1_bf16x8 b[2];
+
+    float csum[CB][8], csq[CB][8];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            uint32_t r[4] = {0, 0, 0, 0};
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int t = 16 * kb + 8 * half + e;
-                const int id = d + t / 9 - 1, ih = h + (t / 3) % 3 - 1, iw = wq + t % 3 - 1;
-                const bool in = valid && t < 27 && id >= 0 && id < D && ih >= 0 && ih < H && iw >= 0 && iw < W;
-                const uint32_t xv = in ? (uint32_t)x[((((int64_t)n * D + id) * H + ih) * W + iw) * ldx] : 0u;
-                r[e >> 1] |= xv << (16 * (e & 1));
-            }
-            b[kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+        for (int e = 0; e < 8; ++e) { csum[cb][e] = 0.f; csq[cb][e] = 0.f; }
+    int32_t count = 0;
+
+    const int hblocks = (a.H + 3) >> 2;
+    const int nblk = a.D * hblocks;
+    const int total_e = 18 * a.WP;
+    const bf16_t* xs = a.x + (int64_t)n * a.D * a.H * a.W * a.ldx;
+    for (int blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const int d = blk / hblocks, h0 = (blk - d * hblocks) << 2;
+        // stage rows (kd, hh): input plane d + kd - 1, input row h0 - 1 + hh, columns w = -1 .. 32*G
+        unsigned short stg[NE];
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int e = tid + 256 * i;
+            const int r = (int)(((uint64_t)(uint32_t)e * a.mWP) >> a.sWP), j = e - r * a.WP;
+            const int kd = r / 6, hh = r - kd * 6;
+            const int id = d + kd - 1, ih = h0 - 1 + hh, iw = j - 1;
+            const bool in = e < total_e && id >= 0 && id < a.D && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            stg[i] = in ? xs[(((int64_t)id * a.H + ih) * a.W + iw) * a.ldx] : (unsigned short)0;
         }
+        __syncthreads();  // every wave is done with the previous block's rows
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-            if (cb < CB) {
-                c1_f32x16 acc;
+        for (int i = 0; i < NE; ++i) {
+            const int e = tid + 256 * i;
+            const int r = (int)(((uint64_t)(uint32_t)e * a.mWP) >> a.sWP), j = e - r * a.WP;
+            if (e < total_e) xt[r * a.RS + j] = stg[i];
+        }
+        __syncthreads();
+        const int h = h0 + wv;
+        if (h < a.H) {
+            bf16_t* zrow = a.z + ((((int64_t)n * a.D + d) * a.H + h) * a.W) * a.ldz;
+            for (int g = 0; g < a.G; ++g) {
+                c1_bf16x8 b[2];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb][0], b[0], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cb][1], b[1], acc, 0, 0, 0);
-                if (valid) {
+                for (int kb = 0; kb < 2; ++kb) {
+                    uint32_t r[4];
 #pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const uint32_t p0 = (uint32_t)f2bf(acc[rg * 4 + 0]) | ((uint32_t)f2bf(acc[rg * 4 + 1]) << 16);
-                        const uint32_t p1 = (uint32_t)f2bf(acc[rg * 4 + 2]) | ((uint32_t)f2bf(acc[rg * 4 + 3]) << 16);
-                        *reinterpret_cast<uint2*>(z + v * ldz + 32 * cb + 8 * rg + 4 * half) = make_uint2(p0, p1);
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const uint32_t lo = xt[toff[kb][2 * e2] + 32 * g], hi = xt[toff[kb][2 * e2 + 1] + 32 * g];
+                        r[e2] = lo | (hi << 16);
                     }
+                    b[kb] = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+                }
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    c1_f32x16 acc;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[cb][0], b[0], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[cb][1], b[1], acc, 0, 0, 0);
+#pragma unroll
+                    for (int q4 = 0; q4 < 2; ++q4) {
+                        const uint4 pk = make_uint4(c1_pack(acc[8 * q4 + 0], acc[8 * q4 + 1]), c1_pack(acc[8 * q4 + 2], acc[8 * q4 + 3]),
+                                                    c1_pack(acc[8 * q4 + 4], acc[8 * q4 + 5]), c1_pack(acc[8 * q4 + 6], acc[8 * q4 + 7]));
+                        *reinterpret_cast<uint4*>(tb + l32 * C1_TROW + half * 32 + q4 * 16) = pk;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) {
+                        const int vx = it * 16 + (lane >> 2), wq = 32 * g + vx;
+                        const uint4 q = *reinterpret_cast<const uint4*>(tb + vx * C1_TROW + (lane & 3) * 16);
+                        if (wq < a.W) {
+                            *reinterpret_cast<uint4*>(zrow + (int64_t)wq * a.ldz + 32 * cb + (lane & 3) * 8) = q;
+                            const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
+                                csum[cb][2 * e] += f0; csq[cb][2 * e] = fmaf(f0, f0, csq[cb][2 * e]);
+                                csum[cb][2 * e + 1] += f1; csq[cb][2 * e + 1] = fmaf(f1, f1, csq[cb][2 * e + 1]);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
                 }
             }
+            count += a.W;
         }
+    }
+    if (a.partial) {
+        // lanes with equal (lane & 3) hold the same 8 channels of different voxels
+        const int part = blockIdx.x * 4 + wv, parts = gridDim.x * 4;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float sv = csum[cb][e], qv = csq[cb][e];
+#pragma unroll
+                for (int m = 4; m < 64; m <<= 1) { sv += __shfl_xor(sv, m); qv += __shfl_xor(qv, m); }
+                if (lane < 4) {
+                    const size_t o = (((size_t)n * parts + part) * C + 32 * cb + lane * 8 + e) * 2;
+                    a.partial[o] = sv;
+                    a.partial[o + 1] = qv;
+                }
+            }
+        if (lane == 0) a.counts[(size_t)n * parts + part] = count;
     }
 }
 
@@ -259,6 +359,61 @@ static bool cin1_fwd_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, 
     return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && !bias && zd->c % 8 == 0 && zd->c <= 128 && zd->ldc % 8 == 0 &&
            aligned16(z);
 }
+// ---- tiled Cin == 1 forward: launch geometry, workspace, dispatch ----
+static int cin1_tile_groups(const lamp_tensor_desc* zd) { return (zd->w + 31) / 32; }
+static int cin1_tile_ne(const lamp_tensor_desc* zd) { return (18 * (32 * cin1_tile_groups(zd) + 2) + 255) / 256; }
+static bool cin1_tile_ok(const lamp_tensor_desc* zd) {
+    return (zd->c == 32 || zd->c == 64 || zd->c == 128) && cin1_tile_ne(zd) <= 40 && zd->n <= 65535 &&
+           (int64_t)zd->d * ((zd->h + 3) / 4) < ((int64_t)1 << 31);
+}
+static int cin1_tile_gridx(const lamp_tensor_desc* zd) {
+    const int64_t nblk = (int64_t)zd->d * ((zd->h + 3) / 4);
+    int64_t g = 2048 / zd->n;
+    if (g < 1) g = 1;
+    return (int)(nblk < g ? nblk : g);
+}
+static size_t cin1_tile_ws_bytes(const lamp_tensor_desc* zd) {
+    const size_t parts = (size_t)cin1_tile_gridx(zd) * 4;
+    return align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * parts * sizeof(int32_t));
+}
+template <int CB>
+static void cin1_tile_launch(int ne, dim3 grid, size_t lds, hipStream_t s, const Cin1Args& a) {
+    if (ne <= 12) hipLaunchKernelGGL((conv3d_cin1_fwd_tile_kernel<CB, 12>), grid, dim3(256), lds, s, a);
+    else if (ne <= 20) hipLaunchKernelGGL((conv3d_cin1_fwd_tile_kernel<CB, 20>), grid, dim3(256), lds, s, a);
+    else hipLaunchKernelGGL((conv3d_cin1_fwd_tile_kernel<CB, 40>), grid, dim3(256), lds, s, a);
+}
+static lamp_status cin1_tile_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, const lamp_tensor_desc* zd, void* z,
+                                 float* stats_out, float eps, void* ws, size_t ws_bytes, hipStream_t s) {
+    Cin1Args a;
+    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.w = (const bf16_t*)w; a.z = (bf16_t*)z; a.ldz = zd->ldc;
+    a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w;
+    a.G = cin1_tile_groups(zd);
+    a.WP = 32 * a.G + 2;
+    a.RS = a.WP;
+    {   // round-up reciprocal: e / WP == (e * m) >> sh for e < 2^31
+        int l = 0;
+        while ((1 << l) < a.WP) ++l;
+        a.sWP = 31 + l;
+        a.mWP = (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)a.WP - 1) / (uint64_t)a.WP);
+    }
+    const int gx = cin1_tile_gridx(zd);
+    const int parts = gx * 4;
+    a.partial = nullptr; a.counts = nullptr;
+    if (stats_out) {
+        if (!ws || ws_bytes < cin1_tile_ws_bytes(zd)) return LAMP_ERR_WORKSPACE;
+        a.partial = (float*)ws;
+        a.counts = (int32_t*)((char*)ws + align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)));
+    }
+    const size_t lds = 4 * 32 * C1_TROW + (size_t)18 * a.RS * sizeof(unsigned short);
+    const dim3 grid(gx, zd->n);
+    const int ne = cin1_tile_ne(zd);
+    if (zd->c == 32) cin1_tile_launch<1>(ne, grid, lds, s, a);
+    else if (zd->c == 64) cin1_tile_launch<2>(ne, grid, lds, s, a);
+    else cin1_tile_launch<4>(ne, grid, lds, s, a);
+    LAMP_CHECK_LAUNCH();
+    if (stats_out) return launch_stats_finalize(a.partial, a.counts, parts, zd->n, zd->c, eps, stats_out, s, true);
+    return LAMP_OK;
+}
 static bool cin1_wgrad_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
     return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && dzd->c % 32 == 0 && xd->w % 16 == 0;
@@ -313,6 +468,10 @@ extern "C" size_t lamp_conv3d_fwd_workspace_bytes(const lamp_tensor_desc* xd, co
     if (!desc_ok(xd) || !desc_ok(zd)) return 0;
     size_t a = want_stats ? stats_ws_bytes(zd) : 0;
     size_t b = mfma_conv_ws_bytes(xd, zd, want_stats);
+    if (want_stats && xd->c == 1 && xd->dtype == LAMP_BF16 && cin1_tile_ok(zd)) {
+        const size_t c = cin1_tile_ws_bytes(zd);
+        if (c > a) a = c;
+    }
     return a > b ? a : b;
 }
 
@@ -330,15 +489,9 @@ extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x
     if (mfma_conv_supported(xd, zd, xnorm, bias))
         return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s);
     if (cin1_fwd_ok(xd, zd, xnorm, bias, z)) {
-        if (zd->c % 32 == 0) {
-            const int64_t wg = (nvox(zd) + 127) / 128;
-            const dim3 grid((unsigned)(wg > 8192 ? 8192 : wg));
-            hipLaunchKernelGGL(conv3d_cin1_fwd_mfma_kernel, grid, dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)w,
-                               (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
-        } else {
-            hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
-                               (const bf16_t*)w, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
-        }
+        if (cin1_tile_ok(zd)) return cin1_tile_fwd(xd, x, w, zd, z, stats_out, eps, ws, ws_bytes, s);
+        hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                           (const bf16_t*)w, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, zd->c);
         LAMP_CHECK_LAUNCH();
     } else {
         st = launch_direct<false>(xd, x, make_norm(xnorm), w, bias, zd, z, s);

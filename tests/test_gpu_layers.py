@@ -81,6 +81,33 @@ def test_conv3d_fwd_dgrad_wgrad(L, dtype, shape):
     check(as64(db), 2 * db_ref, dtype, "conv dbias beta=1", tol=1e-4)
 
 
+@pytest.mark.parametrize("shape", [(2, 5, 6, 17, 32), (1, 3, 9, 70, 64), (2, 4, 8, 32, 128), (1, 6, 7, 200, 32), (1, 2, 5, 300, 32)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_first_layer_bf16(L, shape):
+    """One input channel (the network's first layer), bf16, no bias: output, fused statistics of the
+    stored output, and the same written into a channel slice of a wider buffer."""
+    N, D, H, W, Co = shape
+    r = rng(900 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, 1)), BF)
+    w = to_dev(S.kaiming_conv(r, Co, 1), BF)
+    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    stats = torch.full((N, Co, 2), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats)
+    check(as64(z), O.conv3d_fwd(as64(x), as64(w)), BF, "first-layer conv fwd")
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "first-layer stats mean", tol=1e-4)
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-4)
+    buf = torch.zeros((N, D, H, W, Co + 8), dtype=BF, device=DEV)
+    z2 = buf[..., 8:]
+    st2 = torch.empty_like(stats)
+    L.lamp_conv3d_fwd(x, w, z2, stats_out=st2)
+    assert torch.equal(z2, z) and torch.equal(st2, stats)
+    assert torch.all(buf[..., :8] == 0), "wrote outside the channel slice"
+    z3 = torch.empty_like(z)
+    L.lamp_conv3d_fwd(x, w, z3)
+    assert torch.equal(z3, z)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 def test_conv3d_on_channel_slices_and_norm_on_load(L, dtype):
     """Input read from a channel slice of a wider buffer with normalise+ReLU on load for the first
