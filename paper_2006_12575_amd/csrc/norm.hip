@@ -81,43 +81,49 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(const T* __restrict_
     if (counts && n == 0 && blockIdx.z == 0 && tid == 0) counts[chunk] = (int32_t)(rend - rbeg);
 }
 
-// One 256-thread block per (n,c): Chan/Welford merging of the parts in fp64 in a fixed order
-// (strided per thread, then a fixed tree over lanes and waves).
-struct Moments { double cnt, mean, m2; };
-__device__ __forceinline__ void merge_moments(Moments& a, double c2, double mn2, double mm2) {
-    if (c2 > 0.0) {
-        const double tot = a.cnt + c2, dlt = mn2 - a.mean;
-        a.mean += dlt * (c2 / tot);
-        a.m2 += mm2 + dlt * dlt * (a.cnt * c2 / tot);
-        a.cnt = tot;
-    }
-}
+// One 256-thread block per (n,c).  The parts carry (sum, sum of squares, count); they are added in
+// fp64 in a fixed order (strided per thread, four parts in flight, then a fixed tree over lanes and
+// waves), and mean / variance follow from the totals in fp64: with fp32 part sums as the input this
+// loses nothing against merging per-part means and second moments.
 __global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __restrict__ partial,
                                                              const int32_t* __restrict__ counts, int parts, int C,
                                                              float eps, float* __restrict__ stats, int counts_per_sample) {
     __shared__ double sh[4][3];
     const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    Moments m{0.0, 0.0, 0.0};
-    for (int p = tid; p < parts; p += 256) {
-        const double k = (double)counts[counts_per_sample ? (size_t)n * parts + p : (size_t)p];
-        if (k <= 0.0) continue;
-        const size_t o = (((size_t)n * parts + p) * C + c) * 2;
-        const double sm = (double)partial[o], sq = (double)partial[o + 1];
-        const double mp = sm / k;
-        double m2p = sq - sm * mp;
-        if (m2p < 0.0) m2p = 0.0;
-        merge_moments(m, k, mp, m2p);
+    const int32_t* cnt = counts + (counts_per_sample ? (size_t)n * parts : (size_t)0);
+    const float2* pp = reinterpret_cast<const float2*>(partial) + (size_t)n * parts * C + c;
+    double k = 0.0, sm = 0.0, sq = 0.0;
+    int p = tid;
+    for (; p + 768 < parts; p += 1024) {
+        float2 v[4];
+        int32_t kk[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { v[u] = pp[(size_t)(p + 256 * u) * C]; kk[u] = cnt[p + 256 * u]; }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (kk[u] > 0) { k += (double)kk[u]; sm += (double)v[u].x; sq += (double)v[u].y; }
+    }
+    for (; p < parts; p += 256) {
+        const float2 v = pp[(size_t)p * C];
+        const int32_t kk = cnt[p];
+        if (kk > 0) { k += (double)kk; sm += (double)v.x; sq += (double)v.y; }
     }
     for (int off = 32; off > 0; off >>= 1) {
-        const double c2 = __shfl_down(m.cnt, off), mn2 = __shfl_down(m.mean, off), mm2 = __shfl_down(m.m2, off);
-        merge_moments(m, c2, mn2, mm2);
+        k += __shfl_down(k, off);
+        sm += __shfl_down(sm, off);
+        sq += __shfl_down(sq, off);
     }
-    if (lane == 0) { sh[wv][0] = m.cnt; sh[wv][1] = m.mean; sh[wv][2] = m.m2; }
+    if (lane == 0) { sh[wv][0] = k; sh[wv][1] = sm; sh[wv][2] = sq; }
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 4; ++w) merge_moments(m, sh[w][0], sh[w][1], sh[w][2]);
-        const double var = m.cnt > 0.0 ? m.m2 / m.cnt : 0.0;
-        stats[((size_t)n * C + c) * 2 + 0] = (float)m.mean;
+        for (int w = 1; w < 4; ++w) { k += sh[w][0]; sm += sh[w][1]; sq += sh[w][2]; }
+        double mean = 0.0, var = 0.0;
+        if (k > 0.0) {
+            mean = sm / k;
+            var = sq / k - mean * mean;
+            if (var < 0.0) var = 0.0;
+        }
+        stats[((size_t)n * C + c) * 2 + 0] = (float)mean;
         stats[((size_t)n * C + c) * 2 + 1] = (float)(1.0 / sqrt(var + (double)eps));
     }
 }
