@@ -83,6 +83,8 @@ struct ConvArgs {
     const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
+    float* zpart;       // split reduction only: [splits][N*D*H*W][Cout] fp32 partial outputs
+    int cps;            // split reduction only: 16-channel input chunks per split (grid z = split)
 };
 
 // 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
@@ -237,7 +239,10 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
     asm volatile("" ::: "memory");
 }
 
-template <int COB, int TDT>
+// SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
+// writes its fp32 partial sums; a second kernel adds them in a fixed order.  For small volumes with
+// many channels, where the tiles alone cannot fill the chip.
+template <int COB, int TDT, bool SPLIT = false>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
     constexpr int TD = GE::TD, NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES,
@@ -249,6 +254,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const int l32 = lane & 31, half = lane >> 5;
     const int co0 = blockIdx.y * (32 * COB);
     const int nchunks = a.Cin >> 4;
+    const int c_lo = SPLIT ? (int)blockIdx.z * a.cps : 0;
+    const int c_hi = SPLIT ? min(c_lo + a.cps, nchunks) : nchunks;
     constexpr int WROWS = 32 * COB;
     constexpr int WPLANE = WROWS * 16;            // one (tap, plane): WROWS rows of 16 bytes
     constexpr int WINSTR = 18 * WROWS / 64;       // wave-wide copies per kd group: 18 or 9
@@ -321,12 +328,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int pk = hl.pk[j];
                 const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
                 const bool in = hd >= t0.dlo && hd <= t0.dhi && hh >= t0.hlo && hh <= t0.hhi && hw >= t0.wlo && hw <= t0.whi;
-                g2lds16(in ? t0.origin + hl.rel[j] + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
+                g2lds16(in ? t0.origin + hl.rel[j] + c_lo * 16 + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
             }
         }
 #pragma unroll
         for (int i = 0; i < 3; ++i)
-            if (wv + 8 * i < WINSTR) g2lds16(wbase + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
+            if (wv + 8 * i < WINSTR) g2lds16(wbase + c_lo * 16 + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
         wait_vmcnt<0>();
         __syncthreads();
     }
@@ -345,12 +352,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         const int next_tile = tile + wg_per_xcd;
         const HaloTile ht_cur = halo_tile(tile);
         const HaloTile ht_next = halo_tile(next_tile < tile_hi ? next_tile : tile);
-        for (int chunk = 0; chunk < nchunks; ++chunk, ++stage) {
+        for (int chunk = c_lo; chunk < c_hi; ++chunk, ++stage) {
             const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
             char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
             // what streams in during this stage: the next chunk of this tile, or chunk 0 of the next
-            const bool last_chunk = chunk + 1 == nchunks;
-            const int pf_chunk = last_chunk ? 0 : chunk + 1;
+            const bool last_chunk = chunk + 1 == c_hi;
+            const int pf_chunk = last_chunk ? c_lo : chunk + 1;
             const bool pf = !last_chunk || next_tile < tile_hi;
             const HaloTile& ht = last_chunk ? ht_next : ht_cur;
             const char* w0p = wbuf0 + wpar * WBUF_BYTES + a_base;
@@ -376,6 +383,27 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
         const int gd0 = TDT == 8 ? d0 + 4 * ds : d0 + ds;
+        if constexpr (SPLIT) {
+            // fp32 partial sums straight from the accumulators: lane = voxel (bh, bw) of block vb, four
+            // consecutive channels per register group
+            static_assert(TDT == 4, "the split reduction uses the 4-deep tile");
+            float* zp = a.zpart + (int64_t)blockIdx.z * ((int64_t)a.N * a.D * a.H * a.W) * a.Cout;
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb) {
+                const int gh = h0 + hs * NVB * 2 + vb * 2 + bh, gw = w0 + bw;
+                if (gd0 < a.D && gh < a.H && gw < a.W) {
+                    float* row = zp + ((((int64_t)n * a.D + gd0) * a.H + gh) * a.W + gw) * a.Cout + co0 + half * 4;
+#pragma unroll
+                    for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg)
+                            *reinterpret_cast<float4*>(row + cb * 32 + rg * 8) =
+                                make_float4(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1], acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
+                }
+            }
+            __syncthreads();
+            continue;
+        }
         char* fbuf = GE::EPI_OWN ? lds + 2 * HALO_BYTES + 2 * WBUF_BYTES : hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
         constexpr int ROWB = WROWS * 2 + 16;          // padded row of the patch
         constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
@@ -485,6 +513,24 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
     return tiles8 >= 512 ? 8 : 4;
 }
 
+// Number of input-channel splits for the tiled kernel (1 = none): only where the 4-deep tiling with 64
+// output channels per workgroup leaves most of the chip idle and there are chunks to share out.
+static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    static int off = -1;
+    if (off < 0) off = getenv("LAMP_CONV_NO_SPLIT") ? 1 : 0;
+    if (off || zd->c % 64 || conv_tile_depth(zd) != 4) return 1;
+    int td, th, tw;
+    tile_dims(zd, 4, td, th, tw);
+    const int64_t wgs = (int64_t)zd->n * td * th * tw * (zd->c / 64);
+    const int nchunks = xd->c / 16;
+    if (wgs > 96 || nchunks < 4) return 1;
+    int S = (int)(256 / wgs);
+    if (S > nchunks / 2) S = nchunks / 2;
+    if (S < 2) return 1;
+    const int cps = (nchunks + S - 1) / S;
+    return (nchunks + cps - 1) / cps;
+}
+
 size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return 0;
     int td, th, tw;
@@ -497,19 +543,21 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
         const size_t parts = tiles > 1024 ? tiles : 1024;
         b += align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * parts * sizeof(int32_t));
     }
+    const int S = conv_splits(xd, zd);
+    if (S > 1) b += align_up((size_t)S * nvox(zd) * zd->c * sizeof(float)) + stats_ws_bytes(zd) + 256;
     return b;
 }
 
-template <int COB, int TDT>
+template <int COB, int TDT, bool SPLIT = false>
 static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
     static bool attr_done = false;
     const int shm = Geo<TDT>::LDS_BYTES;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<COB, TDT>, hipFuncAttributeMaxDynamicSharedMemorySize, shm) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, shm) != hipSuccess)
             return LAMP_ERR_HIP;
         attr_done = true;
     }
-    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT>), grid, dim3(512), shm, s, a);
+    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT>), grid, dim3(512), shm, s, a);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
@@ -560,6 +608,19 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     int wgx = 256;  // one persistent workgroup per CU (LDS-limited), 32 per XCD
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
     dim3 grid(wgx, zd->c / (32 * cob));
+    a.zpart = nullptr; a.cps = 0;
+    const int S = conv_splits(xd, zd);
+    if (S > 1) {
+        a.zpart = (float*)cv.take((size_t)S * nvox(zd) * zd->c * sizeof(float));
+        void* sws = cv.take(stats_ws_bytes(zd));
+        if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+        a.cps = ((xd->c / 16) + S - 1) / S;
+        a.part = nullptr; a.counts = nullptr;
+        grid.z = S;
+        lamp_status st = launch_igemm<2, 4, true>(a, grid, s);
+        if (st != LAMP_OK) return st;
+        return launch_splitk_reduce(a.zpart, S, zd, z, eps, stats_out, sws, stats_ws_bytes(zd), s);
+    }
     lamp_status st;
     if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
     else st = cob == 2 ? launch_igemm<2, 4>(a, grid, s) : launch_igemm<1, 4>(a, grid, s);

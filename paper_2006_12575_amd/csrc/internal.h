@@ -9,6 +9,8 @@ namespace lamp {
 int stats_chunks(int64_t v);
 // Bytes of workspace for the stand-alone statistics pass (partials [N][chunks][C][2] fp32).
 size_t stats_ws_bytes(const lamp_tensor_desc* zd);
+lamp_status launch_splitk_reduce(const float* zpart, int S, const lamp_tensor_desc* zd, void* z, float eps, float* stats,
+                                 void* ws, size_t ws_bytes, hipStream_t s);
 // Two-kernel statistics of z: writes stats[N][C][2] = (mean, rstd).
 lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, float* stats,
                          void* ws, size_t ws_bytes, hipStream_t s);

@@ -153,6 +153,87 @@ lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, f
     return launch_stats_finalize(partial, counts, chunks, zd->n, zd->c, eps, stats, s);
 }
 
+// ---- sum of split-reduction partials -------------------------------------------------------
+// z[v][c] = bf16( sum_s zpart[s][v][c] ), splits added in order; the (sum, sum of squares) of the
+// rounded values are accumulated for the statistics like stats_partial_kernel does.  C % 8 == 0.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ zpart, int S, int64_t split_stride,
+                                                            bf16_t* __restrict__ z, int ldz, int64_t V, int C,
+                                                            int cthreads, int rl, int rows_per_chunk,
+                                                            float* __restrict__ partial, int32_t* __restrict__ counts) {
+    __shared__ float red[2][256 * 8];
+    const int tid = threadIdx.x;
+    const int cl = tid % cthreads, r0 = tid / cthreads;
+    const int cv = blockIdx.z * 256 + cl;
+    const int chunk = blockIdx.x, n = blockIdx.y, chunks = gridDim.x;
+    const int64_t rbeg = (int64_t)chunk * rows_per_chunk;
+    int64_t rend = rbeg + rows_per_chunk;
+    if (rend > V) rend = V;
+    float s[8], q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { s[i] = 0.f; q[i] = 0.f; }
+    if (r0 < rl && cv * 8 < C) {
+        for (int64_t r = rbeg + r0; r < rend; r += rl) {
+            const int64_t row = (int64_t)n * V + r;
+            const float* src = zpart + row * C + (int64_t)cv * 8;
+            float4 a0 = *reinterpret_cast<const float4*>(src), a1 = *reinterpret_cast<const float4*>(src + 4);
+            for (int sp = 1; sp < S; ++sp) {
+                const float4 b0 = *reinterpret_cast<const float4*>(src + sp * split_stride);
+                const float4 b1 = *reinterpret_cast<const float4*>(src + sp * split_stride + 4);
+                a0.x += b0.x; a0.y += b0.y; a0.z += b0.z; a0.w += b0.w;
+                a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
+            }
+            const float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            uint32_t pk[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pk[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+            *reinterpret_cast<uint4*>(z + row * ldz + (int64_t)cv * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float f0 = __uint_as_float(pk[i] << 16), f1 = __uint_as_float(pk[i] & 0xFFFF0000u);
+                s[2 * i] += f0; q[2 * i] = fmaf(f0, f0, q[2 * i]);
+                s[2 * i + 1] += f1; q[2 * i + 1] = fmaf(f1, f1, q[2 * i + 1]);
+            }
+        }
+    }
+    if (!partial) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { red[0][tid * 8 + i] = s[i]; red[1][tid * 8 + i] = q[i]; }
+    __syncthreads();
+    if (r0 == 0 && cv * 8 < C) {
+        for (int i = 0; i < 8; ++i) {
+            float ss = 0.f, qq = 0.f;
+            for (int r = 0; r < rl; ++r) {
+                ss += red[0][(r * cthreads + cl) * 8 + i];
+                qq += red[1][(r * cthreads + cl) * 8 + i];
+            }
+            size_t o = (((size_t)n * chunks + chunk) * C + (size_t)cv * 8 + i) * 2;
+            partial[o] = ss;
+            partial[o + 1] = qq;
+        }
+    }
+    if (n == 0 && blockIdx.z == 0 && tid == 0) counts[chunk] = (int32_t)(rend - rbeg);
+}
+
+lamp_status launch_splitk_reduce(const float* zpart, int S, const lamp_tensor_desc* zd, void* z, float eps, float* stats,
+                                 void* ws, size_t ws_bytes, hipStream_t s) {
+    const int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    const int chunks = stats_chunks(V);
+    float* partial = nullptr;
+    int32_t* counts = nullptr;
+    if (stats) {
+        if (!ws || ws_bytes < stats_ws_bytes(zd)) return LAMP_ERR_WORKSPACE;
+        partial = (float*)ws;
+        counts = (int32_t*)((char*)ws + align_up((size_t)zd->n * chunks * zd->c * 2 * sizeof(float)));
+    }
+    const RowMap m = make_rowmap(zd->c, 8);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s, zpart, S,
+                       (int64_t)zd->n * V * zd->c, (bf16_t*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, rows_per_chunk(V),
+                       partial, counts);
+    LAMP_CHECK_LAUNCH();
+    if (stats) return launch_stats_finalize(partial, counts, chunks, zd->n, zd->c, eps, stats, s);
+    return LAMP_OK;
+}
+
 // ---- apply ----------------------------------------------------------------------------------
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void inorm_apply_kernel(const T* __restrict__ z, int ldz, T* __restrict__ y, int ldy,

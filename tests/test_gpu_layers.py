@@ -108,6 +108,33 @@ def test_conv3d_first_layer_bf16(L, shape):
     assert torch.equal(z3, z)
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 8, 8, 128, 128), (1, 5, 9, 10, 64, 64), (2, 4, 4, 4, 256, 192), (1, 8, 8, 16, 512, 64)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_small_volume_many_channels_bf16(L, shape):
+    """Small volumes with many channels (the deep U-Net levels): the input channels of a tile are
+    shared out over several workgroups and the fp32 partial outputs added by a second kernel.
+    Forward with fused statistics, forward into a channel slice, and the data gradient."""
+    N, D, H, W, Ci, Co = shape
+    r = rng(700 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)), BF)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
+    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    stats = torch.full((N, Co, 2), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats)
+    check(as64(z), O.conv3d_fwd(as64(x), as64(w)), BF, "conv fwd (split reduction)")
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "stats mean", tol=1e-4)
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-4)
+    buf = torch.zeros((N, D, H, W, Co + 8), dtype=BF, device=DEV)
+    z2 = buf[..., 8:]
+    L.lamp_conv3d_fwd(x, w, z2)
+    assert torch.equal(z2, z) and torch.all(buf[..., :8] == 0)
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)), BF)
+    dx = torch.empty_like(x)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), BF, "conv dgrad (split reduction)")
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 def test_conv3d_on_channel_slices_and_norm_on_load(L, dtype):
     """Input read from a channel slice of a wider buffer with normalise+ReLU on load for the first
