@@ -319,29 +319,38 @@ __global__ __launch_bounds__(256) void conv3d_cin1_wgrad_kernel(const bf16_t* __
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int64_t g = g0; g < g1; ++g) {
-        const int64_t v = g * 16 + 8 * kg;  // the lane's 8 voxels v..v+7 lie in one W-row
-        const int w0 = (int)(v % W);
-        int64_t r = v / W;
-        const int h = (int)(r % H);
-        r /= H;
-        const int d = (int)(r % D);
-        const int n = (int)(r / D);
-        U16x8 a, b;
-        const bf16_t* dp = dz + v * lddz + cob + l32;
+    // four groups per round: all 64 two-byte loads of a round are in flight before its first multiply
+    // (the voxel count is below 2^31: 32-bit index arithmetic)
+    for (int64_t gb = g0; gb < g1; gb += 4) {
+        U16x8 a[4], b[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a.e[e] = dp[(int64_t)e * lddz];
-        const int id = d + kd, ih = h + kh;
-        const bool rowok = tap < 27 && id >= 0 && id < D && ih >= 0 && ih < H;
-        const int64_t base = rowok ? (((int64_t)n * D + id) * H + ih) * W : 0;
+        for (int u = 0; u < 4; ++u) {
+            const int64_t g = gb + u;
+            const bool live = g < g1;
+            const uint32_t v = (uint32_t)((live ? g : g0) * 16 + 8 * kg);  // the lane's 8 voxels v..v+7 lie in one W-row
+            const uint32_t w0 = v % (uint32_t)W;
+            uint32_t r = v / (uint32_t)W;
+            const int h = (int)(r % (uint32_t)H);
+            r /= (uint32_t)H;
+            const int d = (int)(r % (uint32_t)D);
+            const int n = (int)(r / (uint32_t)D);
+            const bf16_t* dp = dz + (int64_t)v * lddz + cob + l32;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int iw = w0 + e + kw;
-            const bool ok = rowok && iw >= 0 && iw < W;
-            b.e[e] = ok ? x[(base + iw) * ldx] : (bf16_t)0;
+            for (int e = 0; e < 8; ++e) a[u].e[e] = live ? dp[(int64_t)e * lddz] : (bf16_t)0;
+            const int id = d + kd, ih = h + kh;
+            const bool rowok = live && tap < 27 && id >= 0 && id < D && ih >= 0 && ih < H;
+            const int64_t base = rowok ? (((int64_t)n * D + id) * H + ih) * W : 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int iw = (int)w0 + e + kw;
+                const bool ok = rowok && iw >= 0 && iw < W;
+                b[u].e[e] = ok ? x[(base + iw) * ldx] : (bf16_t)0;
+            }
         }
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0,
-                                                      0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u]), __builtin_bit_cast(bf16x8, b[u]), acc, 0,
+                                                          0, 0);
     }
     if (tap < 27) {
         float* pb = part + wid * Co * 27;
@@ -416,12 +425,12 @@ static lamp_status cin1_tile_fwd(const lamp_tensor_desc* xd, const void* x, cons
 }
 static bool cin1_wgrad_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
-    return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && dzd->c % 32 == 0 && xd->w % 16 == 0;
+    return xd->dtype == LAMP_BF16 && xd->c == 1 && !nm && dzd->c % 32 == 0 && xd->w % 16 == 0 && nvox(xd) < ((int64_t)1 << 31);
 }
 // thread blocks (4 waves, one partial slab per wave) of the Cin == 1 weight gradient
 static int cin1_wgrad_blocks(int64_t V) {
     int64_t b = (V / 16 + 3) / 4;
-    return (int)(b > 512 ? 512 : (b < 1 ? 1 : b));
+    return (int)(b > 2048 ? 2048 : (b < 1 ? 1 : b));
 }
 
 static int wgrad_splits(int64_t V, int64_t O) {

@@ -896,7 +896,6 @@ size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* d
     return align_up((size_t)wgrad_slots(xd, dzd) * dzd->c * 27 * xd->c * sizeof(float)) + 256;
 }
 
-__global__ void zero16_kernel(uint32_t* p) { if (threadIdx.x < 4) p[threadIdx.x] = 0u; }
 
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz, float* dw,
                        float beta, void* ws, size_t ws_bytes, hipStream_t s) {
@@ -910,10 +909,8 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
     a.tiles_total = a.tiles_per_n * xd->n;
     const int S = wgrad_slots(xd, dzd);
     a.tiles_per_wg = (a.tiles_total + S - 1) / S;
-    uint32_t* z16 = (uint32_t*)((char*)ws + align_up((size_t)S * dzd->c * 27 * xd->c * sizeof(float)));
-    hipLaunchKernelGGL(zero16_kernel, dim3(1), dim3(64), 0, s, z16);
-    LAMP_CHECK_LAUNCH();
-    a.zero16 = (const bf16_t*)z16;
+    a.zero16 = device_zero16();
+    if (!a.zero16) return LAMP_ERR_HIP;
     const int cob = (dzd->c % 64 == 0) ? 2 : 1;
     dim3 grid(S, xd->c / 32, dzd->c / (32 * cob));
     static bool attr_done[2] = {false, false};

@@ -622,12 +622,11 @@ __global__ __launch_bounds__(256) void convtr_wgrad_mfma_kernel(CtWArgs a) {
             }
 }
 
-__global__ void zero16_ct_kernel(uint32_t* p) { if (threadIdx.x < 4) p[threadIdx.x] = 0u; }
 
 static int ctw_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* dyd) {
     const int64_t chunks = (nvox(xd) + 63) / 64;
     const int types = ((xd->c + 63) / 64) * (dyd->c / 32);
-    int64_t s = 1024 / types;
+    int64_t s = 512 / types;  // about two workgroups per CU; more only enlarges the partial sums
     if (s < 1) s = 1;
     if (s > chunks) s = chunks;
     return (int)s;
@@ -654,13 +653,11 @@ lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const l
     const int64_t O = (int64_t)xd->c * 8 * dyd->c;
     CtWArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dy = (const bf16_t*)dy; a.ldy = dyd->ldc; a.part = (float*)ws;
-    uint32_t* z16 = (uint32_t*)((char*)ws + align_up((size_t)S * O * sizeof(float)));
-    a.zero16 = (const bf16_t*)z16;
+    a.zero16 = device_zero16();
+    if (!a.zero16) return LAMP_ERR_HIP;
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c;
     const int64_t chunks = (nvox(xd) + 63) / 64;
     a.chunks_per_split = (int)((chunks + S - 1) / S);
-    hipLaunchKernelGGL(zero16_ct_kernel, dim3(1), dim3(64), 0, s, z16);
-    LAMP_CHECK_LAUNCH();
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)convtr_wgrad_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * CTW_STAGE) != hipSuccess)

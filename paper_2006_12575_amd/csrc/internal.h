@@ -22,6 +22,7 @@ lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, 
 
 // ---- reduce.hip -----------------------------------------------------------------------------
 // out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.
+const bf16_t* device_zero16();  // 16 zero bytes on the current device, nullptr on failure
 lamp_status launch_reduce_partials(const float* part, int S, int64_t O, float* out, float beta, hipStream_t s);
 // Column sums of a [rows, C] tensor with row stride ld: out[c] = beta*out[c] + sum_r t[r][c].
 size_t colsum_ws_bytes(int64_t rows, int C);

@@ -4,6 +4,29 @@
 
 namespace lamp {
 
+// 16 zero bytes in device memory: the source of the zero padding for the register-free global -> LDS
+// copies.  A statically initialised device array that no kernel writes; `used` keeps it in the device
+// code object although no kernel names it (a const array would have internal linkage and be dropped
+// there, and the lookup below would then fail).  Its address is looked up once per device and checked
+// (device memory, reads back as zeros) before any kernel gets it.
+__device__ __attribute__((used, aligned(16))) uint32_t lamp_zero16_storage[4] = {0u, 0u, 0u, 0u};
+const bf16_t* device_zero16() {
+    static const bf16_t* cache[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (!cache[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(lamp_zero16_storage)) != hipSuccess || !p) return nullptr;
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, p) != hipSuccess || at.type != hipMemoryTypeDevice) return nullptr;
+        uint32_t back[4] = {1u, 1u, 1u, 1u};
+        if (hipMemcpy(back, p, sizeof(back), hipMemcpyDeviceToHost) != hipSuccess) return nullptr;
+        if (back[0] | back[1] | back[2] | back[3]) return nullptr;
+        cache[dev] = (const bf16_t*)p;
+    }
+    return cache[dev];
+}
+
 // Block = (256/SL) outputs x SL lanes over the parts; every lane adds its strided parts in order,
 // then the lanes are added in order: a fixed summation tree, fp64.
 template <int SL>
