@@ -362,6 +362,128 @@ __global__ __launch_bounds__(256) void conv3d_cin1_wgrad_kernel(const bf16_t* __
     }
 }
 
+// Weight gradient for Cin == 1 with the operands staged in LDS (C_out = 32*CB per workgroup column):
+// dW[co][tap] = sum_v dz[v][co] * x[v + tap], voxels as the reduction dimension.  A workgroup walks
+// blocks of four output rows (one per wave) like the tiled forward kernel and stages the 3 x 6 input
+// rows the same way.  Per 16 voxels of its row a wave fetches dz with one 16-byte load per lane and
+// 32 channels (two groups ahead), passes it through a private LDS slot and reads the A operand
+// (dz^T, voxel-major per lane) with the transposing LDS load; the B operand -- 8 consecutive voxels
+// shifted by the lane's tap -- is 8 two-byte LDS reads at immediate offsets.  Every wave writes its
+// own partial [C_out][27] slab.
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short c1_s16x4;
+__device__ __forceinline__ c1_bf16x8 c1_frag_tr(const char* p) {
+    typedef __attribute__((address_space(3))) c1_s16x4 lds_s16x4;
+    c1_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    c1_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 256));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(c1_bf16x8, v);
+}
+
+struct Cin1WArgs {
+    const bf16_t* x; int ldx;
+    const bf16_t* dz; int lddz;
+    float* part;     // [waves][Co][27]
+    int N, D, H, W, Co;
+    int G;           // 16-voxel groups per row
+    int WP, RS;      // staged row: WP = 16*G + 2 elements (w = -1 .. 16*G), row stride RS elements
+    uint32_t mWP; int sWP;
+};
+
+template <int CB, int NE>
+__global__ __launch_bounds__(256) void conv3d_cin1_wgrad_tile_kernel(Cin1WArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char c1w_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, half = lane >> 5;
+    char* slot = c1w_lds + wv * (2 * CB * 1024);                                         // two dz buffers of this wave
+    unsigned short* xt = reinterpret_cast<unsigned short*>(c1w_lds + 4 * 2 * CB * 1024);  // [18][RS]
+    const int co0 = blockIdx.y * (32 * CB);
+    const int tap = l32 < 27 ? l32 : 26;   // columns 27..31 repeat tap 26 and are not written
+    const int kd = tap / 9, kh = (tap / 3) % 3, kw = tap % 3;
+    const int xoff = (kd * 6 + kh + wv) * a.RS + kw + 8 * half;
+    // lane part of a transposing fragment read: voxel row 8*(b/2) + s/4, channel bytes 32*(b%2) + 8*(s%4)
+    const int b16 = lane >> 4, s16 = lane & 15;
+    const uint32_t loff = (uint32_t)((8 * (b16 >> 1) + (s16 >> 2)) * 64 + 32 * (b16 & 1) + 8 * (s16 & 3));
+    const int vx = lane >> 2, piece = lane & 3;   // dz copy: voxel of the group, 16-byte piece of its 64 bytes
+
+    c1_f32x16 acc[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+    const int hblocks = (a.H + 3) >> 2;
+    const int per_n = a.D * hblocks;
+    const int nblk = a.N * per_n;
+    const int total_e = 18 * a.WP;
+    for (int blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const int n = blk / per_n, rblk = blk - n * per_n;
+        const int d = rblk / hblocks, h0 = (rblk - d * hblocks) << 2;
+        const bf16_t* xs = a.x + (int64_t)n * a.D * a.H * a.W * a.ldx;
+        unsigned short stg[NE];
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int e = tid + 256 * i;
+            const int r = (int)(((uint64_t)(uint32_t)e * a.mWP) >> a.sWP), j = e - r * a.WP;
+            const int skd = r / 6, hh = r - skd * 6;
+            const int id = d + skd - 1, ih = h0 - 1 + hh, iw = j - 1;
+            const bool in = e < total_e && id >= 0 && id < a.D && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            stg[i] = in ? xs[(((int64_t)id * a.H + ih) * a.W + iw) * a.ldx] : (unsigned short)0;
+        }
+        __syncthreads();  // every wave is done with the previous block's rows
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int e = tid + 256 * i;
+            const int r = (int)(((uint64_t)(uint32_t)e * a.mWP) >> a.sWP), j = e - r * a.WP;
+            if (e < total_e) xt[r * a.RS + j] = stg[i];
+        }
+        __syncthreads();
+        const int h = h0 + wv;
+        if (h < a.H) {
+            const bf16_t* dzrow = a.dz + ((((int64_t)n * a.D + d) * a.H + h) * a.W) * a.lddz + co0 + piece * 8;
+            auto fetch = [&](int g, uint4 (&q)[CB]) {
+                const int w = 16 * g + vx;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    q[cb] = make_uint4(0, 0, 0, 0);
+                    if (g < a.G && w < a.W) q[cb] = *reinterpret_cast<const uint4*>(dzrow + (int64_t)w * a.lddz + 32 * cb);
+                }
+            };
+            uint4 q0[CB], q1[CB];
+            fetch(0, q0);
+            fetch(1, q1);
+            for (int g = 0; g < a.G; ++g) {
+                char* buf = slot + (g & 1) * (CB * 1024);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<uint4*>(buf + cb * 1024 + vx * 64 + piece * 16) = q0[cb];
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) q0[cb] = q1[cb];
+                fetch(g + 2, q1);
+                __builtin_amdgcn_wave_barrier();
+                uint32_t r[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const uint32_t lo = xt[xoff + 16 * g + 2 * e2], hi = xt[xoff + 16 * g + 2 * e2 + 1];
+                    r[e2] = lo | (hi << 16);
+                }
+                const c1_bf16x8 b = __builtin_bit_cast(c1_bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1_frag_tr(buf + cb * 1024 + loff), b, acc[cb], 0, 0, 0);
+            }
+        }
+    }
+    if (l32 < 27) {
+        float* pb = a.part + ((int64_t)blockIdx.x * 4 + wv) * a.Co * 27;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + 32 * cb + 8 * (r / 4) + 4 * half + (r % 4);
+                pb[(int64_t)co * 27 + l32] = acc[cb][r];
+            }
+    }
+}
+
 static bool cin1_fwd_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm, const float* bias,
                         const void* z) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
@@ -422,6 +544,52 @@ static lamp_status cin1_tile_fwd(const lamp_tensor_desc* xd, const void* x, cons
     LAMP_CHECK_LAUNCH();
     if (stats_out) return launch_stats_finalize(a.partial, a.counts, parts, zd->n, zd->c, eps, stats_out, s, true);
     return LAMP_OK;
+}
+// ---- tiled Cin == 1 weight gradient: launch geometry, workspace, dispatch ----
+static int cin1_wtile_groups(const lamp_tensor_desc* xd) { return (xd->w + 15) / 16; }
+static int cin1_wtile_ne(const lamp_tensor_desc* xd) { return (18 * (16 * cin1_wtile_groups(xd) + 2) + 255) / 256; }
+static bool cin1_wtile_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const void* dz) {
+    return (dzd->c == 32 || dzd->c == 64 || dzd->c == 128) && dzd->ldc % 8 == 0 && aligned16(dz) && cin1_wtile_ne(xd) <= 40 &&
+           (int64_t)xd->n * xd->d * ((xd->h + 3) / 4) < ((int64_t)1 << 31);
+}
+static int cin1_wtile_gridx(const lamp_tensor_desc* xd) {
+    const int64_t nblk = (int64_t)xd->n * xd->d * ((xd->h + 3) / 4);
+    return (int)(nblk < 1024 ? nblk : 1024);
+}
+static size_t cin1_wtile_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
+    return align_up((size_t)cin1_wtile_gridx(xd) * 4 * dzd->c * 27 * sizeof(float));
+}
+template <int CB>
+static void cin1_wtile_launch(int ne, dim3 grid, size_t lds, hipStream_t s, const Cin1WArgs& a) {
+    if (ne <= 12) hipLaunchKernelGGL((conv3d_cin1_wgrad_tile_kernel<CB, 12>), grid, dim3(256), lds, s, a);
+    else if (ne <= 20) hipLaunchKernelGGL((conv3d_cin1_wgrad_tile_kernel<CB, 20>), grid, dim3(256), lds, s, a);
+    else hipLaunchKernelGGL((conv3d_cin1_wgrad_tile_kernel<CB, 40>), grid, dim3(256), lds, s, a);
+}
+static lamp_status cin1_wtile(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz, float* dw,
+                              float beta, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (!ws || ws_bytes < cin1_wtile_ws_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
+    Cin1WArgs a;
+    a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dz = (const bf16_t*)dz; a.lddz = dzd->ldc; a.part = (float*)ws;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Co = dzd->c;
+    a.G = cin1_wtile_groups(xd);
+    a.WP = 16 * a.G + 2;
+    a.RS = a.WP;
+    {
+        int l = 0;
+        while ((1 << l) < a.WP) ++l;
+        a.sWP = 31 + l;
+        a.mWP = (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)a.WP - 1) / (uint64_t)a.WP);
+    }
+    const int cb = dzd->c >= 128 ? 4 : (dzd->c >= 64 ? 2 : 1);   // channels per workgroup column: 32 * cb
+    const int gx = cin1_wtile_gridx(xd);
+    const dim3 grid(gx, dzd->c / (32 * cb));
+    const size_t lds = (size_t)4 * 2 * cb * 1024 + (size_t)18 * a.RS * sizeof(unsigned short);
+    const int ne = cin1_wtile_ne(xd);
+    if (cb == 1) cin1_wtile_launch<1>(ne, grid, lds, s, a);
+    else if (cb == 2) cin1_wtile_launch<2>(ne, grid, lds, s, a);
+    else cin1_wtile_launch<4>(ne, grid, lds, s, a);
+    LAMP_CHECK_LAUNCH();
+    return launch_reduce_partials((const float*)ws, gx * 4, (int64_t)dzd->c * 27, dw, beta, s);
 }
 static bool cin1_wgrad_ok(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
@@ -537,6 +705,10 @@ extern "C" size_t lamp_conv3d_wgrad_workspace_bytes(const lamp_tensor_desc* xd, 
         const size_t e = align_up((size_t)cin1_wgrad_blocks(nvox(xd)) * 4 * dzd->c * 27 * sizeof(float));
         if (e > a) a = e;
     }
+    if (xd->dtype == LAMP_BF16 && xd->c == 1) {
+        const size_t e = cin1_wtile_ws_bytes(xd, dzd);
+        if (e > a) a = e;
+    }
     return (a > b ? a : b) + c;
 }
 
@@ -558,6 +730,8 @@ extern "C" lamp_status lamp_conv3d_wgrad(const lamp_tensor_desc* xd, const void*
         if (st != LAMP_OK) return st;
     }
     if (mfma_wgrad_supported(xd, dzd, xnorm)) return mfma_wgrad(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
+    if (xd->dtype == LAMP_BF16 && xd->c == 1 && !(xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) && cin1_wtile_ok(xd, dzd, dz))
+        return cin1_wtile(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
     if (cin1_wgrad_ok(xd, dzd, xnorm)) {
         const int64_t groups = nvox(xd) / 16;
         const int blocks = cin1_wgrad_blocks(nvox(xd));

@@ -106,6 +106,18 @@ def test_conv3d_first_layer_bf16(L, shape):
     z3 = torch.empty_like(z)
     L.lamp_conv3d_fwd(x, w, z3)
     assert torch.equal(z3, z)
+    # weight gradient, dz contiguous and as a channel slice of a wider buffer; accumulation
+    dzb = to_dev(S.normal(r, (N, D, H, W, Co + 8)), BF)
+    dz = dzb[..., 8:].contiguous()
+    dw = torch.full((Co, 3, 3, 3, 1), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_wgrad(x, dz, dw)
+    dw_ref, _ = O.conv3d_wgrad(as64(x), as64(dz))
+    check(as64(dw), dw_ref, BF, "first-layer wgrad", tol=2e-3)
+    dw2 = torch.empty_like(dw)
+    L.lamp_conv3d_wgrad(x, dzb[..., 8:], dw2)
+    assert torch.equal(dw2, dw)
+    L.lamp_conv3d_wgrad(x, dz, dw2, beta=1.0)
+    check(as64(dw2), 2 * dw_ref, BF, "first-layer wgrad beta=1", tol=2e-3)
 
 
 @pytest.mark.parametrize("shape", [(2, 8, 8, 8, 128, 128), (1, 5, 9, 10, 64, 64), (2, 4, 4, 4, 256, 192), (1, 8, 8, 16, 512, 64)],
