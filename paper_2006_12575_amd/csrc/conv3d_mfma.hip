@@ -17,6 +17,7 @@
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
 #include <stdlib.h>
 #include "internal.h"
+#include "repack.h"
 
 namespace lamp {
 
@@ -57,21 +58,51 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
     return __builtin_bit_cast(bf16x8, q);
 }
 
-// wp[t][oc][ic]  <-  forward: W[oc][t][ic]     dgrad: W[ic][26-t][oc]
 __global__ __launch_bounds__(256) void repack_weights_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp,
                                                              int Cout, int Cin, int dgrad, int bykh) {
-    const int64_t total = (int64_t)27 * Cout * Cin;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < 8) wp[total + i] = 0;  // 16 zero bytes behind the weights: the source of the zero padding
-    if (i >= total) return;
-    const int ic = (int)(i % Cin);
-    const int oc = (int)((i / Cin) % Cout);
-    int t = (int)(i / ((int64_t)Cin * Cout));
-    if (bykh) {   // position kh*9 + kd*3 + kw holds tap (kd, kh, kw): the 8-deep tile walks the taps kh-major
-        const int kh = t / 9, kd = (t / 3) % 3, kw = t % 3;
-        t = kd * 9 + kh * 3 + kw;
+    repack_tile_gran(w, wp, (int64_t)blockIdx.x * 256 + threadIdx.x, Cout, Cin, dgrad, bykh);
+}
+
+// All the repacks of a network pass in one launch: block -> job by the jobs' first-block table.
+struct RepackBatch {
+    int n;
+    struct J { const bf16_t* w; bf16_t* wp; int Cout, Cin, dgrad, kind, blk0; } j[64];
+};
+__global__ __launch_bounds__(256) void repack_batch_kernel(RepackBatch b) {
+    int k = 0;
+    while (k + 1 < b.n && (int)blockIdx.x >= b.j[k + 1].blk0) ++k;
+    const RepackBatch::J& q = b.j[k];
+    const int64_t i = (int64_t)((int)blockIdx.x - q.blk0) * 256 + threadIdx.x;
+    if (q.kind <= 1) repack_tile_gran(q.w, q.wp, i, q.Cout, q.Cin, q.dgrad, q.kind);
+    else repack_ring_gran(q.w, q.wp, i, q.Cout, q.Cin, q.kind == 2 ? 64 : 32, q.dgrad);
+}
+
+lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s) {
+    if (n <= 0) return LAMP_OK;
+    if (n > 64) return LAMP_ERR_SHAPE;
+    RepackBatch b;
+    b.n = n;
+    int64_t blk = 0;
+    for (int k = 0; k < n; ++k) {
+        b.j[k].w = (const bf16_t*)jobs[k].w; b.j[k].wp = (bf16_t*)jobs[k].wp;
+        b.j[k].Cout = jobs[k].Cout; b.j[k].Cin = jobs[k].Cin; b.j[k].dgrad = jobs[k].dgrad; b.j[k].kind = jobs[k].kind;
+        b.j[k].blk0 = (int)blk;
+        blk += cdiv((int64_t)27 * jobs[k].Cout * jobs[k].Cin / 8, 256);
+        if (blk >= ((int64_t)1 << 31)) return LAMP_ERR_SHAPE;
     }
-    wp[i] = dgrad ? w[((int64_t)ic * 27 + (26 - t)) * Cout + oc] : w[((int64_t)oc * 27 + t) * Cin + ic];
+    hipLaunchKernelGGL(repack_batch_kernel, dim3((unsigned)blk), dim3(256), 0, s, b);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+static thread_local const RepackTable* tl_repack = nullptr;
+void set_repack_table(const RepackTable* t) { tl_repack = t; }
+const bf16_t* find_prepacked(const void* w, bool dgrad, int kind, int Cout, int Cin) {
+    const RepackTable* t = tl_repack;
+    if (!t) return nullptr;
+    for (int k = 0; k < t->n; ++k)
+        if (t->e[k].w == w && (t->e[k].dgrad != 0) == dgrad && t->e[k].kind == kind && t->e[k].Cout == Cout && t->e[k].Cin == Cin) return (const bf16_t*)t->e[k].wp;
+    return nullptr;
 }
 
 struct ConvArgs {
@@ -513,6 +544,28 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
     return tiles8 >= 512 ? 8 : 4;
 }
 
+// Kernel choice.  The ring kernel wins where every CU gets a long run of 64-input-channel tiles; the
+// tiled kernel (two waves per SIMD, twice the voxels per weight byte) copes better with short walks,
+// 32-channel outputs and more input channels.  LAMP_CONV_KERNEL=ring|tile forces one for experiments.
+static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    static int forced = -1;
+    if (forced < 0) {
+        const char* e = getenv("LAMP_CONV_KERNEL");
+        forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
+    }
+    const int64_t tiles4 = (int64_t)zd->n * ((zd->d + 3) / 4) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
+    return forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
+}
+
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return -1;
+    if (conv_use_ring(xd, zd)) return zd->c % 64 == 0 ? 2 : 3;
+    return conv_tile_depth(zd) == 8 ? 1 : 0;
+}
+size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    return align_up((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
+}
+
 // Number of input-channel splits for the tiled kernel (1 = none): only where the 4-deep tiling with 64
 // output channels per workgroup leaves most of the chip idle and there are chunks to share out.
 static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
@@ -565,21 +618,8 @@ static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
                           hipStream_t s) {
-    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
-    {
-        // Kernel choice.  The ring kernel wins where every CU gets a long run of 64-input-channel tiles; the
-        // tiled kernel (two waves per SIMD, twice the voxels per weight byte) copes better with short walks,
-        // 32-channel outputs and more input channels.
-        // LAMP_CONV_KERNEL=ring|tile forces one for experiments.
-        static int forced = -1;
-        if (forced < 0) {
-            const char* e = getenv("LAMP_CONV_KERNEL");
-            forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
-        }
-        const int64_t tiles4 = (int64_t)zd->n * ((zd->d + 3) / 4) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
-        const bool ring = forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
-        if (ring) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
-    }
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u) || (((uintptr_t)w) & 15u)) return LAMP_ERR_ALIGN;
+    if (conv_use_ring(xd, zd)) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     const int TDT = conv_tile_depth(zd);
     int td, th, tw;
     tile_dims(zd, TDT, td, th, tw);
@@ -594,9 +634,13 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     }
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const int64_t wtotal = (int64_t)27 * xd->c * zd->c;
-    hipLaunchKernelGGL(repack_weights_kernel, dim3(cdiv(wtotal, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
-                       dgrad ? 1 : 0, TDT == 8 ? 1 : 0);
-    LAMP_CHECK_LAUNCH();
+    if (const bf16_t* pre = find_prepacked(w, dgrad, TDT == 8 ? 1 : 0, zd->c, xd->c)) {
+        wp = const_cast<bf16_t*>(pre);
+    } else {
+        hipLaunchKernelGGL(repack_weights_kernel, dim3(cdiv(wtotal / 8, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
+                           dgrad ? 1 : 0, TDT == 8 ? 1 : 0);
+        LAMP_CHECK_LAUNCH();
+    }
     ConvArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;

@@ -26,6 +26,7 @@
 #include <stdlib.h>
 #include <type_traits>
 #include "internal.h"
+#include "repack.h"
 
 namespace lamp {
 namespace {
@@ -103,21 +104,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_
 // the steps of a tile follow each other in memory.
 __global__ __launch_bounds__(256) void ring_repack_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int Cout,
                                                           int Cin, int wrows, int dgrad) {
-    const int64_t total = (int64_t)27 * Cout * Cin;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < Cin + 8) wp[total + i] = 0;  // zeros behind the weights: the source of the zero padding
-    if (i >= total) return;
-    const int nchunks = Cin >> 4;
-    int64_t r = i;
-    const int e = (int)(r % 8); r /= 8;
-    const int co = (int)(r % wrows); r /= wrows;
-    const int plane = (int)(r % 2); r /= 2;
-    const int kd = (int)(r % 3); r /= 3;
-    const int j = (int)(r % 9); r /= 9;
-    const int chunk = (int)(r % nchunks);
-    const int slab = (int)(r / nchunks);
-    const int oc = slab * wrows + co, ic = chunk * 16 + plane * 8 + e, t = kd * 9 + j;
-    wp[i] = dgrad ? w[((int64_t)ic * 27 + (26 - t)) * Cout + oc] : w[((int64_t)oc * 27 + t) * Cin + ic];
+    repack_ring_gran(w, wp, (int64_t)blockIdx.x * 256 + threadIdx.x, Cout, Cin, wrows, dgrad);
 }
 
 struct HaloTile {
@@ -654,7 +641,7 @@ lamp_status launch_ring(const RingArgs& a, dim3 grid, hipStream_t s) {
 
 lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad, const lamp_tensor_desc* zd,
                           void* z, float* stats_out, float eps, void* ws, size_t ws_bytes, hipStream_t s) {
-    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u) || (((uintptr_t)w) & 15u)) return LAMP_ERR_ALIGN;
     const int td = (zd->d + RTD - 1) / RTD, th = (zd->h + RTH - 1) / RTH, tw = (zd->w + RTW - 1) / RTW;
     const int tiles_per_n = td * th * tw;
     Carver cv(ws, ws_bytes);
@@ -675,9 +662,13 @@ lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
     const int64_t wtotal = (int64_t)27 * xd->c * zd->c;
-    hipLaunchKernelGGL(ring_repack_kernel, dim3(cdiv(wtotal, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
-                       32 * cob, dgrad ? 1 : 0);
-    LAMP_CHECK_LAUNCH();
+    if (const bf16_t* pre = find_prepacked(w, dgrad, cob == 2 ? 2 : 3, zd->c, xd->c)) {
+        wp = const_cast<bf16_t*>(pre);
+    } else {
+        hipLaunchKernelGGL(ring_repack_kernel, dim3(cdiv(wtotal / 8, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
+                           32 * cob, dgrad ? 1 : 0);
+        LAMP_CHECK_LAUNCH();
+    }
     RingArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;

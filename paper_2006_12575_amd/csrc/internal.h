@@ -22,6 +22,18 @@ lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, 
 
 // ---- reduce.hip -----------------------------------------------------------------------------
 // out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.
+// ---- repacked conv weights prepared ahead of the calls that use them (network entry points) ----
+// kind: 0 tiled kernel (4-deep tile), 1 tiled kernel (8-deep tile, kh-major taps), 2 ring kernel with
+// 64 output channels per workgroup, 3 ring kernel with 32; -1: the shape does not take a matrix-core path.
+struct RepackJob { const void* w; void* wp; int Cout, Cin, dgrad, kind; };
+struct RepackTable { int n; RepackJob e[64]; };
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
+size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
+lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s);
+// The table the calling thread's conv calls consult (weight pointer + direction + kind must match);
+// nullptr outside a network entry point.
+void set_repack_table(const RepackTable* t);
+const bf16_t* find_prepacked(const void* w, bool dgrad, int kind, int Cout, int Cin);
 const bf16_t* device_zero16();  // 16 zero bytes on the current device, nullptr on failure
 lamp_status launch_reduce_partials(const float* part, int S, int64_t O, float* out, float beta, hipStream_t s);
 // Column sums of a [rows, C] tensor with row stride ld: out[c] = beta*out[c] + sum_r t[r][c].

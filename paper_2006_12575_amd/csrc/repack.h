@@ -1,0 +1,67 @@
+// Weight repacking for the matrix-core 3x3x3 convolution kernels, one element per thread: shared by
+// the per-call repack kernels and the batched one the network entry points use.
+#pragma once
+#include "internal.h"
+
+namespace lamp {
+
+// One thread moves one granule of 8 consecutive input channels (16 bytes) of the repacked layout.
+// Forward: the granule is contiguous in W as well (one 16-byte load).  Data gradient: its 8 elements
+// come from 8 rows of W; the threads are numbered with the output channel fastest, which is the
+// contiguous dimension of W in that direction, so each of the 8 loads is coalesced across the wave.
+__device__ __forceinline__ uint4 repack_gather8(const bf16_t* __restrict__ p, int64_t stride) {
+    uint32_t r[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = (uint32_t)p[(2 * e) * stride] | ((uint32_t)p[(2 * e + 1) * stride] << 16);
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+// Tiled kernel: wp[t][oc][ic]  <-  forward: W[oc][t][ic]     dgrad: W[ic][26-t][oc];
+// bykh: position kh*9 + kd*3 + kw holds tap (kd, kh, kw) (the 8-deep tile walks the taps kh-major).
+// 16 zero bytes behind the weights are the source of the zero padding.  g: granule index, Cin % 8 == 0.
+__device__ __forceinline__ void repack_tile_gran(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int64_t g, int Cout,
+                                                 int Cin, int dgrad, int bykh) {
+    const int64_t total = (int64_t)27 * Cout * Cin;
+    if (g == 0) *reinterpret_cast<uint4*>(wp + total) = make_uint4(0, 0, 0, 0);
+    if (g >= total / 8) return;
+    const int cg = Cin >> 3;
+    int ic8, oc, t;
+    if (!dgrad) {
+        ic8 = (int)(g % cg); oc = (int)((g / cg) % Cout); t = (int)(g / ((int64_t)cg * Cout));
+    } else {
+        oc = (int)(g % Cout); ic8 = (int)((g / Cout) % cg); t = (int)(g / ((int64_t)cg * Cout));
+    }
+    int ts = t;
+    if (bykh) {
+        const int kh = t / 9, kd = (t / 3) % 3, kw = t % 3;
+        ts = kd * 9 + kh * 3 + kw;
+    }
+    uint4 v;
+    if (!dgrad) v = *reinterpret_cast<const uint4*>(w + ((int64_t)oc * 27 + ts) * Cin + ic8 * 8);
+    else v = repack_gather8(w + ((int64_t)(ic8 * 8) * 27 + (26 - ts)) * Cout + oc, (int64_t)27 * Cout);
+    *reinterpret_cast<uint4*>(wp + ((int64_t)t * Cout + oc) * Cin + ic8 * 8) = v;
+}
+
+// Ring kernel: wp[slab][chunk][j = kh*3+kw][kd][plane][co][8] with oc = slab*wrows + co,
+// ic = chunk*16 + plane*8 + e, t = kd*9 + j; Cin + 8 zero elements behind the weights.
+__device__ __forceinline__ void repack_ring_gran(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int64_t g, int Cout,
+                                                 int Cin, int wrows, int dgrad) {
+    const int64_t total = (int64_t)27 * Cout * Cin;
+    if (g * 8 < Cin + 8) *reinterpret_cast<uint4*>(wp + total + g * 8) = make_uint4(0, 0, 0, 0);
+    if (g >= total / 8) return;
+    const int nchunks = Cin >> 4;
+    int64_t r = g;
+    const int co = (int)(r % wrows); r /= wrows;
+    const int plane = (int)(r % 2); r /= 2;
+    const int kd = (int)(r % 3); r /= 3;
+    const int j = (int)(r % 9); r /= 9;
+    const int chunk = (int)(r % nchunks);
+    const int slab = (int)(r / nchunks);
+    const int oc = slab * wrows + co, ic0 = chunk * 16 + plane * 8, t = kd * 9 + j;
+    uint4 v;
+    if (!dgrad) v = *reinterpret_cast<const uint4*>(w + ((int64_t)oc * 27 + t) * Cin + ic0);
+    else v = repack_gather8(w + ((int64_t)ic0 * 27 + (26 - t)) * Cout + oc, (int64_t)27 * Cout);
+    *reinterpret_cast<uint4*>(wp + g * 8) = v;
+}
+
+}  // namespace lamp

@@ -117,8 +117,11 @@ struct Layout {
     std::vector<void*> cat, pooled, gcat;
     void *g0, *g1;
     void* scratch; size_t scratch_bytes;
+    void* repack; size_t repack_bytes;   // repacked conv weights of the whole pass (one launch)
     size_t total;
 };
+
+static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole, bool bwd);
 
 // Lays out every buffer of levels [first, last] of the encoder and (whole == true) the decoder.
 static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void* base, Layout& lay,
@@ -186,6 +189,8 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
     if (bwd) { lay.g0 = take(gmax); lay.g1 = take(gmax); }
     lay.scratch_bytes = align_up(scratch);
     lay.scratch = take(lay.scratch_bytes);
+    lay.repack_bytes = align_up(repack_region_bytes(nt, first, last, whole, bwd));
+    lay.repack = lay.repack_bytes ? take(lay.repack_bytes) : nullptr;
     lay.total = align_up(cv.off) + 256;
 }
 
@@ -194,6 +199,66 @@ static int dec_pi(const lamp_unet_desc* u, int l) {  // index of "up Wt" of deco
     return u->levels * 2 * per_conv(u) + (u->levels - 1 - l) * (2 + 2 * per_conv(u));
 }
 static int head_pi(const lamp_unet_desc* u) { return u->levels * 2 * per_conv(u) + (u->levels - 1) * (2 + 2 * per_conv(u)); }
+
+// ---- conv weights repacked ahead of the pass, all in one launch ---------------------------------
+// The 3x3x3 convs of levels [first, last] (and of the decoder when `whole`): parameter index, shapes.
+struct ConvSpec { int pi, l, Cin, Cout; bool dgrad; };
+static void list_convs(const Net& nt, int first, int last, bool whole, int pbase, bool first_dgrad, std::vector<ConvSpec>& v) {
+    const lamp_unet_desc* u = nt.u;
+    const int pc = per_conv(u);
+    for (int l = first; l <= last; ++l) {
+        const int C = nt.chan(l), Cin = l == 1 ? u->in_ch : nt.chan(l - 1), pi = enc_pi(u, l) - pbase;
+        v.push_back(ConvSpec{pi, l, Cin, C, l > first || first_dgrad});
+        v.push_back(ConvSpec{pi + pc, l, C, C, true});
+    }
+    if (whole)
+        for (int l = nt.L - 1; l >= 1; --l) {
+            const int C = nt.chan(l), pi = dec_pi(u, l) + 2;
+            v.push_back(ConvSpec{pi, l, 2 * C, C, true});
+            v.push_back(ConvSpec{pi + pc, l, C, C, true});
+        }
+}
+static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole, bool bwd) {
+    std::vector<ConvSpec> v;
+    list_convs(nt, first, last, whole, 0, true, v);
+    size_t b = 0;
+    for (const ConvSpec& c : v) {
+        lamp_tensor_desc xi = nt.td(c.l, c.Cin, c.Cin), xo = nt.td(c.l, c.Cout, c.Cout);
+        if (conv_repack_kind(&xi, &xo) >= 0) b += conv_repack_bytes(&xi, &xo);
+        if (bwd && conv_repack_kind(&xo, &xi) >= 0) b += conv_repack_bytes(&xo, &xi);
+    }
+    return b;
+}
+// Fills the table and launches the repack of every conv weight the pass will use (fwd: forward
+// layouts; dgrad: data-gradient layouts) into lay.repack.
+static lamp_status prepare_repack(const Net& nt, const Layout& lay, int first, int last, bool whole, int pbase,
+                                  const void* const* P, bool fwd, bool dgrad, bool first_dgrad, RepackTable& tab) {
+    tab.n = 0;
+    if (!lay.repack) return LAMP_OK;
+    std::vector<ConvSpec> v;
+    list_convs(nt, first, last, whole, pbase, first_dgrad, v);
+    char* base = (char*)lay.repack;
+    size_t off = 0;
+    for (const ConvSpec& c : v) {
+        lamp_tensor_desc xi = nt.td(c.l, c.Cin, c.Cin), xo = nt.td(c.l, c.Cout, c.Cout);
+        for (int dir = 0; dir < 2; ++dir) {
+            if (dir == 0 ? !fwd : !(dgrad && c.dgrad)) continue;
+            const lamp_tensor_desc* xd = dir == 0 ? &xi : &xo;   // the conv's input / output in this direction
+            const lamp_tensor_desc* zd = dir == 0 ? &xo : &xi;
+            const int kind = conv_repack_kind(xd, zd);
+            if (kind < 0 || tab.n >= 64 || !aligned16(P[c.pi])) continue;
+            const size_t b = conv_repack_bytes(xd, zd);
+            if (off + b > lay.repack_bytes) continue;
+            tab.e[tab.n++] = RepackJob{P[c.pi], base + off, zd->c, xd->c, dir, kind};
+            off += b;
+        }
+    }
+    return launch_repack_batch(tab.e, tab.n, nt.s);
+}
+struct RepackScope {   // the calling thread's conv calls see the table for the duration of the pass
+    explicit RepackScope(const RepackTable* t) { set_repack_table(t); }
+    ~RepackScope() { set_repack_table(nullptr); }
+};
 
 static lamp_status encoder_fwd(Net& nt, Layout& lay, int first, int last, const void* const* P, int pbase, const void* x) {
     const lamp_unet_desc* u = nt.u;
@@ -314,6 +379,9 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     Layout lay;
     make_layout(nt, 1, L, true, bwd, ws, lay, nullptr, nullptr);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    RepackTable tab;
+    if ((st = prepare_repack(nt, lay, 1, L, true, 0, P, true, bwd, false, tab)) != LAMP_OK) return st;
+    RepackScope scope(&tab);
 
     if ((st = encoder_fwd(nt, lay, 1, L, P, 0, x)) != LAMP_OK) return st;
     const void* cur = lay.e2[L - 1].y;
@@ -416,6 +484,9 @@ extern "C" lamp_status lamp_unet_stage_fwd(const lamp_unet_desc* u, int first, i
     Layout lay;
     make_layout(nt, first, last, false, true, ws, lay, skips, pooled);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    RepackTable tab;
+    if ((st = prepare_repack(nt, lay, first, last, false, enc_pi(&v, first), params, true, false, false, tab)) != LAMP_OK) return st;
+    RepackScope scope(&tab);
     return encoder_fwd(nt, lay, first, last, params, enc_pi(&v, first), x);
 }
 
@@ -441,6 +512,10 @@ extern "C" lamp_status lamp_unet_stage_bwd(const lamp_unet_desc* u, int first, i
     Layout lay;
     make_layout(nt, first, last, false, true, ws, lay, (void* const*)skips, nullptr);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    RepackTable tab;
+    if ((st = prepare_repack(nt, lay, first, last, false, enc_pi(&v, first), params, false, true, dx != nullptr, tab)) != LAMP_OK)
+        return st;
+    RepackScope scope(&tab);
     std::vector<const void*> sg(v.levels, nullptr);
     std::vector<int> ld(v.levels, 0);
     for (int l = first; l <= last; ++l) { sg[l - 1] = d_skips[l - first]; ld[l - 1] = nt.chan(l); }
