@@ -148,6 +148,35 @@ def test_conv3d_small_volume_many_channels_bf16(L, shape):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 32, 32), (1, 2, 2, 2, 64, 64), (3, 1, 1, 17, 16, 32), (2, 1, 3, 1, 1, 32), (1, 2, 1, 1, 128, 64)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_degenerate_volumes(L, dtype, shape):
+    """Volumes thinner than the kernel or the tiles (single voxels, single rows): only the taps that
+    fall inside the volume contribute; statistics of one-voxel samples have zero variance."""
+    N, D, H, W, Ci, Co = shape
+    r = rng(1300 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)), dtype)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), dtype)
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)), dtype)
+    z = torch.empty((N, D, H, W, Co), dtype=dtype, device=DEV)
+    stats = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats)
+    check(as64(z), O.conv3d_fwd(as64(x), as64(w)), dtype, "conv fwd")
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "stats mean", tol=1e-4)
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-3 if D * H * W == 1 else 2e-4)
+    dx = torch.empty_like(x)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), dtype, "conv dgrad")
+    dw = torch.empty((Co, 3, 3, 3, Ci), dtype=F32, device=DEV)
+    L.lamp_conv3d_wgrad(x, dz, dw)
+    check(as64(dw), O.conv3d_wgrad(as64(x), as64(dz))[0], dtype, "conv wgrad", tol=1e-4 if dtype == F32 else 2e-3)
+    y = torch.empty_like(z)
+    L.lamp_inorm_relu(z, y, stats, stats_given=True)
+    check(as64(y), O.inorm_relu(as64(z))[0], dtype, "inorm+relu", tol=None if D * H * W > 1 else 2e-2)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 def test_conv3d_on_channel_slices_and_norm_on_load(L, dtype):
     """Input read from a channel slice of a wider buffer with normalise+ReLU on load for the first
     c_norm channels (the concat case), output written into a channel slice."""
