@@ -116,6 +116,11 @@ struct ConvArgs {
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
     float* zpart;       // split reduction only: [splits][N*D*H*W][Cout] fp32 partial outputs
     int cps;            // split reduction only: 16-channel input chunks per split (grid z = split)
+    // Two-part tensors (a concat that is never materialised).  Input: the 16-channel chunks from xsplit on
+    // are read from x + xdelta (an element offset to the second tensor, same channel stride).  Output:
+    // channels from zsplit on go to z2 (channel stride ldz2), counted from its channel 0.
+    int64_t xdelta; int xsplit;
+    bf16_t* z2; int ldz2, zsplit;
 };
 
 // 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
@@ -162,7 +167,7 @@ struct HaloTile {
 template <int COB, int TDT, int G, int HALO_FIRST, int HALO_CNT>
 __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], const char* __restrict__ hb, const char* __restrict__ wb,
                                            char* __restrict__ hb_next, char* __restrict__ wb_next, bool pf_halo,
-                                           bool pf_w, const HaloLane& hl, const HaloTile& ht, int pf_choff,
+                                           bool pf_w, const HaloLane& hl, const HaloTile& ht, int64_t pf_choff,
                                            const bf16_t* zero16, const bf16_t* wsrc, const int (&wrel)[3], int wv,
                                            int lane) {
     typedef Geo<TDT> GE;
@@ -287,6 +292,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const int nchunks = a.Cin >> 4;
     const int c_lo = SPLIT ? (int)blockIdx.z * a.cps : 0;
     const int c_hi = SPLIT ? min(c_lo + a.cps, nchunks) : nchunks;
+    // element offset of a 16-channel chunk from channel 0 of the (first) input tensor
+    auto choff = [&](int chunk) -> int64_t {
+        return chunk < a.xsplit ? (int64_t)chunk * 16 : a.xdelta + (int64_t)(chunk - a.xsplit) * 16;
+    };
     constexpr int WROWS = 32 * COB;
     constexpr int WPLANE = WROWS * 16;            // one (tap, plane): WROWS rows of 16 bytes
     constexpr int WINSTR = 18 * WROWS / 64;       // wave-wide copies per kd group: 18 or 9
@@ -359,7 +368,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int pk = hl.pk[j];
                 const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
                 const bool in = hd >= t0.dlo && hd <= t0.dhi && hh >= t0.hlo && hh <= t0.hhi && hw >= t0.wlo && hw <= t0.whi;
-                g2lds16(in ? t0.origin + hl.rel[j] + c_lo * 16 + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
+                g2lds16(in ? t0.origin + hl.rel[j] + choff(c_lo) + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
             }
         }
 #pragma unroll
@@ -398,11 +407,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             const bf16_t* wc = wbase + chunk * 16;
             // halo copy slots per group (slot = block j * 2 + plane): 4 + 2 + 2 of 8, or 2 + 2 + 2 of 6
             constexpr int S0 = 2 * HJ - 4;
-            conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+            const int64_t pf_off = choff(pf_chunk);
+            conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
                                            wc + wgstride, wrel, wv, lane);
-            conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_chunk * 16, a.zero16,
+            conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16,
                                            wc + 2 * wgstride, wrel, wv, lane);
-            conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_chunk * 16, a.zero16,
+            conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16,
                                                wbase + pf_chunk * 16, wrel, wv, lane);
             wpar ^= 1;
         }
@@ -470,8 +480,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     // the input lines that the next chunk passes and the neighbouring tiles still need
                     typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
                     const u32x4 sv = {q.x, q.y, q.z, q.w};
-                    __builtin_nontemporal_store(
-                        sv, reinterpret_cast<u32x4*>(a.z + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.ldz + co0 + part * 8));
+                    const int64_t vlin = (((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw;
+                    const int ch = co0 + part * 8;
+                    bf16_t* dst = ch < a.zsplit ? a.z + vlin * a.ldz + ch : a.z2 + vlin * a.ldz2 + (ch - a.zsplit);
+                    __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(dst));
                     const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -557,9 +569,9 @@ static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     return forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
 }
 
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return -1;
-    if (conv_use_ring(xd, zd)) return zd->c % 64 == 0 ? 2 : 3;
+    if (!tiled_only && conv_use_ring(xd, zd)) return zd->c % 64 == 0 ? 2 : 3;
     return conv_tile_depth(zd) == 8 ? 1 : 0;
 }
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
@@ -617,9 +629,13 @@ static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
 
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
-                          hipStream_t s) {
+                          hipStream_t s, const ConvParts* parts) {
+    const bool two_in = parts && parts->x2, two_out = parts && parts->z2;
+    if (two_in && ((((uintptr_t)parts->x2) & 15u) || parts->x_c1 % 16 || parts->x_c1 <= 0 || parts->x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
+    if (two_out && ((((uintptr_t)parts->z2) & 15u) || parts->z_c1 % 32 || parts->z_c1 <= 0 || parts->z_c1 >= zd->c || parts->ldz2 % 8))
+        return LAMP_ERR_ALIGN;
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u) || (((uintptr_t)w) & 15u)) return LAMP_ERR_ALIGN;
-    if (conv_use_ring(xd, zd)) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
+    if (!two_in && !two_out && conv_use_ring(xd, zd)) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     const int TDT = conv_tile_depth(zd);
     int td, th, tw;
     tile_dims(zd, TDT, td, th, tw);
@@ -653,6 +669,11 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
     dim3 grid(wgx, zd->c / (32 * cob));
     a.zpart = nullptr; a.cps = 0;
+    a.xdelta = two_in ? (int64_t)((const bf16_t*)parts->x2 - (const bf16_t*)x) : 0;
+    a.xsplit = two_in ? parts->x_c1 / 16 : 0x7fffffff;
+    a.z2 = two_out ? (bf16_t*)parts->z2 : nullptr;
+    a.ldz2 = two_out ? parts->ldz2 : 0;
+    a.zsplit = two_out ? parts->z_c1 : 0x7fffffff;
     const int S = conv_splits(xd, zd);
     if (S > 1) {
         a.zpart = (float*)cv.take((size_t)S * nvox(zd) * zd->c * sizeof(float));
@@ -663,7 +684,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         grid.z = S;
         lamp_status st = launch_igemm<2, 4, true>(a, grid, s);
         if (st != LAMP_OK) return st;
-        return launch_splitk_reduce(a.zpart, S, zd, z, eps, stats_out, sws, stats_ws_bytes(zd), s);
+        return launch_splitk_reduce(a.zpart, S, zd, z, eps, stats_out, sws, stats_ws_bytes(zd), s, a.z2, a.ldz2, a.zsplit);
     }
     lamp_status st;
     if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
@@ -703,6 +724,7 @@ struct WgradArgs {
     const bf16_t* zero16;  // 16 zero bytes in global memory
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_wg;
+    const bf16_t* x2; int xsplit;   // two-part x: input channels from xsplit on live in x2 (same channel stride)
 };
 
 __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
@@ -792,6 +814,7 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int ci0 = blockIdx.y * 32, co0 = blockIdx.z * (32 * COB);
+    const bf16_t* xpart = ci0 < a.xsplit ? a.x + ci0 : a.x2 + (ci0 - a.xsplit);   // this workgroup's 32 input channels
     const int tile_lo = blockIdx.x * a.tiles_per_wg;
     const int tile_hi = min(tile_lo + a.tiles_per_wg, a.tiles_total);
 
@@ -849,7 +872,7 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     auto run_tile = [&](int tile_to_fetch, bool pf, const char* st, char* st_next) {
         int n, d0, h0, w0;
         tile_coords(tile_to_fetch, n, d0, h0, w0);
-        const bf16_t* xorg = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx + ci0;
+        const bf16_t* xorg = xpart + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
         const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
         if (has4)
             wgrad_tile<COB, 4>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
@@ -864,7 +887,7 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         // only the copies are wanted here, so issue them directly)
         int n, d0, h0, w0;
         tile_coords(tile_lo, n, d0, h0, w0);
-        const bf16_t* xorg = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx + ci0;
+        const bf16_t* xorg = xpart + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
         const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
@@ -942,11 +965,13 @@ size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* d
 
 
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz, float* dw,
-                       float beta, void* ws, size_t ws_bytes, hipStream_t s) {
+                       float beta, void* ws, size_t ws_bytes, hipStream_t s, const void* x2, int x_c1) {
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)dz) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
+    if (x2 && ((((uintptr_t)x2) & 15u) || x_c1 % 32 || x_c1 <= 0 || x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
     if (ws_bytes < mfma_wgrad_ws_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
     WgradArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dz = (const bf16_t*)dz; a.lddz = dzd->ldc; a.part = (float*)ws;
+    a.x2 = (const bf16_t*)x2; a.xsplit = x2 ? x_c1 : 0x7fffffff;
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Cin = xd->c; a.Cout = dzd->c;
     wtile_dims(xd, a.tiles_d, a.tiles_h, a.tiles_w);
     a.tiles_per_n = a.tiles_d * a.tiles_h * a.tiles_w;

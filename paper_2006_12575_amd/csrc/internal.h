@@ -10,7 +10,7 @@ int stats_chunks(int64_t v);
 // Bytes of workspace for the stand-alone statistics pass (partials [N][chunks][C][2] fp32).
 size_t stats_ws_bytes(const lamp_tensor_desc* zd);
 lamp_status launch_splitk_reduce(const float* zpart, int S, const lamp_tensor_desc* zd, void* z, float eps, float* stats,
-                                 void* ws, size_t ws_bytes, hipStream_t s);
+                                 void* ws, size_t ws_bytes, hipStream_t s, void* z2 = nullptr, int ldz2 = 0, int zsplit = 0);
 // Two-kernel statistics of z: writes stats[N][C][2] = (mean, rstd).
 lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, float* stats,
                          void* ws, size_t ws_bytes, hipStream_t s);
@@ -27,7 +27,7 @@ lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, 
 // 64 output channels per workgroup, 3 ring kernel with 32; -1: the shape does not take a matrix-core path.
 struct RepackJob { const void* w; void* wp; int Cout, Cin, dgrad, kind; };
 struct RepackTable { int n; RepackJob e[64]; };
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only = false);
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
 lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s);
 // The table the calling thread's conv calls consult (weight pointer + direction + kind must match);
@@ -47,13 +47,19 @@ lamp_status launch_colsum(const void* t, int dtype, int64_t rows, int C, int ld,
 bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm,
                          const float* bias);
 size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats);
+// Two-part tensors: a channel concat that is never materialised.  x2: second input tensor holding the
+// input channels from x_c1 on (same channel stride as x, x_c1 % 16 == 0); z2: second output tensor
+// receiving the output channels from z_c1 on (channel stride ldz2, z_c1 % 32 == 0).  With parts the
+// tiled kernel is used whatever the shape.
+struct ConvParts { const void* x2; int x_c1; void* z2; int z_c1, ldz2; };
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
-                          void* ws, size_t ws_bytes, hipStream_t s);
+                          void* ws, size_t ws_bytes, hipStream_t s, const ConvParts* parts = nullptr);
 bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm);
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd);
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,
-                       float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s);
+                       float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s, const void* x2 = nullptr,
+                       int x_c1 = 0);
 
 // ---- conv3d_mfma_ring.hip -------------------------------------------------------------------
 // Ring variant of the matrix-core convolution (same contract and workspace as mfma_conv_fwd).

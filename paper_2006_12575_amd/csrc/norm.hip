@@ -157,7 +157,8 @@ lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, f
 // z[v][c] = bf16( sum_s zpart[s][v][c] ), splits added in order; the (sum, sum of squares) of the
 // rounded values are accumulated for the statistics like stats_partial_kernel does.  C % 8 == 0.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ zpart, int S, int64_t split_stride,
-                                                            bf16_t* __restrict__ z, int ldz, int64_t V, int C,
+                                                            bf16_t* __restrict__ z, int ldz, bf16_t* __restrict__ z2, int ldz2,
+                                                            int zsplit, int64_t V, int C,
                                                             int cthreads, int rl, int rows_per_chunk,
                                                             float* __restrict__ partial, int32_t* __restrict__ counts) {
     __shared__ float red[2][256 * 8];
@@ -186,7 +187,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
             uint32_t pk[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) pk[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
-            *reinterpret_cast<uint4*>(z + row * ldz + (int64_t)cv * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            // channels from zsplit on belong to the second output tensor (two-part output)
+            bf16_t* dst = cv * 8 < zsplit ? z + row * ldz + (int64_t)cv * 8 : z2 + row * ldz2 + ((int64_t)cv * 8 - zsplit);
+            *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float f0 = __uint_as_float(pk[i] << 16), f1 = __uint_as_float(pk[i] & 0xFFFF0000u);
@@ -215,7 +218,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 }
 
 lamp_status launch_splitk_reduce(const float* zpart, int S, const lamp_tensor_desc* zd, void* z, float eps, float* stats,
-                                 void* ws, size_t ws_bytes, hipStream_t s) {
+                                 void* ws, size_t ws_bytes, hipStream_t s, void* z2, int ldz2, int zsplit) {
     const int64_t V = (int64_t)zd->d * zd->h * zd->w;
     const int chunks = stats_chunks(V);
     float* partial = nullptr;
@@ -227,7 +230,8 @@ lamp_status launch_splitk_reduce(const float* zpart, int S, const lamp_tensor_de
     }
     const RowMap m = make_rowmap(zd->c, 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(chunks, zd->n, m.ctiles), dim3(256), 0, s, zpart, S,
-                       (int64_t)zd->n * V * zd->c, (bf16_t*)z, zd->ldc, V, zd->c, m.cthreads, m.rl, rows_per_chunk(V),
+                       (int64_t)zd->n * V * zd->c, (bf16_t*)z, zd->ldc, (bf16_t*)z2, ldz2, z2 ? zsplit : 0x7fffffff, V, zd->c,
+                       m.cthreads, m.rl, rows_per_chunk(V),
                        partial, counts);
     LAMP_CHECK_LAUNCH();
     if (stats) return launch_stats_finalize(partial, counts, chunks, zd->n, zd->c, eps, stats, s);

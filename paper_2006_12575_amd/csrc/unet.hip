@@ -3,9 +3,13 @@
 //
 // Data flow of a block  [conv -> InstanceNorm -> ReLU] x 2 : every conv writes its raw output z
 // and the InstanceNorm statistics (conv epilogue); the activated tensor y is written once by the
-// apply kernel -- for an encoder block's second conv straight into channels [0,C) of that level's
-// concat buffer (zero-copy skip), where the transposed conv later writes channels [C,2C).
-// The backward recomputes the ReLU mask from z and the statistics.
+// apply kernel.  The skip concat is never copied.  Where the matrix-core kernels apply (bf16, channel
+// counts that are multiples of 32) it is not even materialised: the encoder output e_l and the
+// up-sampled tensor are two contiguous tensors and the decoder's first conv reads its input
+// channels from both (its data gradient writes to both), so that pooling, the transposed conv and
+// their gradients never touch 64 of every 128 bytes.  Otherwise an encoder block's second conv
+// writes straight into channels [0,C) of that level's concat buffer, where the transposed conv
+// later writes channels [C,2C).  The backward recomputes the ReLU mask from z and the statistics.
 #include <math.h>
 #include <vector>
 #include "internal.h"
@@ -60,12 +64,17 @@ static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
 }
 
 static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, int Cout, const void* const* P, int pi,
-                             ConvBuf& c1, ConvBuf& c2) {
+                             ConvBuf& c1, ConvBuf& c2, const void* x2 = nullptr) {
     const lamp_unet_desc* u = nt.u;
     const int pc = per_conv(u);
     lamp_tensor_desc xd = nt.td(l, Cin, ldx), zd = nt.td(l, Cout, Cout);
-    lamp_status st = lamp_conv3d_fwd(&xd, x, nullptr, P[pi], nullptr, &zd, c1.z, c1.stats, u->eps, nt.scratch,
-                                     nt.scratch_bytes, nt.s);
+    lamp_status st;
+    if (x2) {   // input channels [0, Cin/2) in x, the rest in x2
+        ConvParts parts{x2, Cin / 2, nullptr, 0, 0};
+        st = mfma_conv_fwd(&xd, x, P[pi], false, &zd, c1.z, c1.stats, u->eps, nt.scratch, nt.scratch_bytes, nt.s, &parts);
+    } else {
+        st = lamp_conv3d_fwd(&xd, x, nullptr, P[pi], nullptr, &zd, c1.z, c1.stats, u->eps, nt.scratch, nt.scratch_bytes, nt.s);
+    }
     if (st != LAMP_OK) return st;
     lamp_tensor_desc y1 = nt.td(l, Cout, c1.ldy);
     st = lamp_inorm_relu(&zd, c1.z, u->affine ? (const float*)P[pi + 1] : nullptr,
@@ -84,7 +93,7 @@ static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, in
 // gx (nullable): receives the gradient w.r.t. the block input, channel stride ldgx.
 static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, int Cout, const void* const* P,
                              float* const* G, int pi, ConvBuf& c1, ConvBuf& c2, void* g, void* gtmp, void* gx, int ldgx,
-                             float beta) {
+                             float beta, const void* x2 = nullptr, void* gx2 = nullptr) {
     const lamp_unet_desc* u = nt.u;
     const int pc = per_conv(u);
     const bool af = u->affine != 0;
@@ -101,11 +110,19 @@ static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, in
                              af ? (const float*)P[pi + 2] : nullptr, &zd, gtmp, af ? G[pi + 1] : nullptr,
                              af ? G[pi + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
     if (st != LAMP_OK) return st;
-    st = lamp_conv3d_wgrad(&xd, x, nullptr, &zd, gtmp, G[pi], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+    if (x2)   // two-part input (see block_fwd); the partial sums take the head of the scratch buffer
+        st = mfma_wgrad(&xd, x, &zd, gtmp, G[pi], beta, nt.scratch, mfma_wgrad_ws_bytes(&xd, &zd), nt.s, x2, Cin / 2);
+    else
+        st = lamp_conv3d_wgrad(&xd, x, nullptr, &zd, gtmp, G[pi], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
     if (st != LAMP_OK) return st;
     if (gx) {
         lamp_tensor_desc gxd = nt.td(l, Cin, ldgx);
-        st = lamp_conv3d_dgrad(&zd, gtmp, P[pi], &gxd, gx, nt.scratch, nt.scratch_bytes, nt.s);
+        if (gx2) {
+            ConvParts parts{nullptr, 0, gx2, Cin / 2, ldgx};
+            st = mfma_conv_fwd(&zd, gtmp, P[pi], true, &gxd, gx, nullptr, 0.f, nt.scratch, nt.scratch_bytes, nt.s, &parts);
+        } else {
+            st = lamp_conv3d_dgrad(&zd, gtmp, P[pi], &gxd, gx, nt.scratch, nt.scratch_bytes, nt.s);
+        }
     }
     return st;
 }
@@ -114,7 +131,11 @@ static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, in
 struct Layout {
     // encoder level l (1-based index l-1), decoder level l (index l-1, l < L)
     std::vector<ConvBuf> e1, e2, d1, d2;
-    std::vector<void*> cat, pooled, gcat;
+    // skip[l] = e_l's activated output, up[l] = the transposed conv's output, channel stride ldcat[l] (C when the
+    // two are separate tensors, 2C when they are the halves of one concat buffer); gskip / gup: their gradients
+    std::vector<void*> skip, up, gskip, gup, pooled;
+    std::vector<int> ldcat;
+    bool vcat;
     void *g0, *g1;
     void* scratch; size_t scratch_bytes;
     void* repack; size_t repack_bytes;   // repacked conv weights of the whole pass (one launch)
@@ -122,6 +143,22 @@ struct Layout {
 };
 
 static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole, bool bwd);
+
+// The concat stays virtual when every decoder block's first conv (2C -> C) takes the matrix-core
+// kernels in all three directions.
+static bool vcat_ok(const Net& nt) {
+    static int off = -1;
+    if (off < 0) off = getenv("LAMP_MATERIALISE_CONCAT") ? 1 : 0;
+    if (off || nt.dt != LAMP_BF16 || nt.L < 2) return false;
+    for (int l = 1; l < nt.L; ++l) {
+        const int C = nt.chan(l);
+        lamp_tensor_desc x2 = nt.td(l, 2 * C, C), z = nt.td(l, C, C);
+        if (C % 32 || !mfma_conv_supported(&x2, &z, nullptr, nullptr) || !mfma_conv_supported(&z, &x2, nullptr, nullptr) ||
+            !mfma_wgrad_supported(&x2, &z, nullptr))
+            return false;
+    }
+    return true;
+}
 
 // Lays out every buffer of levels [first, last] of the encoder and (whole == true) the decoder.
 static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void* base, Layout& lay,
@@ -131,7 +168,9 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
     Carver cv(base ? base : (void*)256, (size_t)1 << 62);
     auto take = [&](size_t b) -> void* { void* p = cv.take(b); return base ? p : nullptr; };
     lay.e1.assign(L, ConvBuf{}); lay.e2.assign(L, ConvBuf{}); lay.d1.assign(L, ConvBuf{}); lay.d2.assign(L, ConvBuf{});
-    lay.cat.assign(L, nullptr); lay.pooled.assign(L, nullptr); lay.gcat.assign(L, nullptr);
+    lay.skip.assign(L, nullptr); lay.up.assign(L, nullptr); lay.gskip.assign(L, nullptr); lay.gup.assign(L, nullptr);
+    lay.pooled.assign(L, nullptr); lay.ldcat.assign(L, 0);
+    lay.vcat = whole && vcat_ok(nt);
     const size_t es = nt.es;
     size_t scratch = 0, gmax = 0;
     for (int l = first; l <= last; ++l) {
@@ -143,9 +182,18 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
         a.y = bwd ? take(tb) : a.z; a.ldy = C;
         b.z = take(tb); b.stats = (float*)take(sb);
         if (whole && l < L) {
-            lay.cat[l - 1] = take(2 * tb);
-            b.y = lay.cat[l - 1]; b.ldy = 2 * C;
-            if (bwd) lay.gcat[l - 1] = take(2 * tb);
+            if (lay.vcat) {
+                lay.skip[l - 1] = take(tb); lay.up[l - 1] = take(tb); lay.ldcat[l - 1] = C;
+                if (bwd) { lay.gskip[l - 1] = take(tb); lay.gup[l - 1] = take(tb); }
+            } else {
+                char* cat = (char*)take(2 * tb);
+                lay.skip[l - 1] = cat; lay.up[l - 1] = base ? cat + (size_t)C * es : nullptr; lay.ldcat[l - 1] = 2 * C;
+                if (bwd) {
+                    char* gcat = (char*)take(2 * tb);
+                    lay.gskip[l - 1] = gcat; lay.gup[l - 1] = base ? gcat + (size_t)C * es : nullptr;
+                }
+            }
+            b.y = lay.skip[l - 1]; b.ldy = lay.ldcat[l - 1];
         } else if (!whole) {
             b.y = ext_skips ? ext_skips[l - first] : nullptr; b.ldy = C;
         } else {
@@ -202,20 +250,20 @@ static int head_pi(const lamp_unet_desc* u) { return u->levels * 2 * per_conv(u)
 
 // ---- conv weights repacked ahead of the pass, all in one launch ---------------------------------
 // The 3x3x3 convs of levels [first, last] (and of the decoder when `whole`): parameter index, shapes.
-struct ConvSpec { int pi, l, Cin, Cout; bool dgrad; };
+struct ConvSpec { int pi, l, Cin, Cout; bool dgrad, parts; };
 static void list_convs(const Net& nt, int first, int last, bool whole, int pbase, bool first_dgrad, std::vector<ConvSpec>& v) {
     const lamp_unet_desc* u = nt.u;
     const int pc = per_conv(u);
     for (int l = first; l <= last; ++l) {
         const int C = nt.chan(l), Cin = l == 1 ? u->in_ch : nt.chan(l - 1), pi = enc_pi(u, l) - pbase;
-        v.push_back(ConvSpec{pi, l, Cin, C, l > first || first_dgrad});
-        v.push_back(ConvSpec{pi + pc, l, C, C, true});
+        v.push_back(ConvSpec{pi, l, Cin, C, l > first || first_dgrad, false});
+        v.push_back(ConvSpec{pi + pc, l, C, C, true, false});
     }
     if (whole)
         for (int l = nt.L - 1; l >= 1; --l) {
             const int C = nt.chan(l), pi = dec_pi(u, l) + 2;
-            v.push_back(ConvSpec{pi, l, 2 * C, C, true});
-            v.push_back(ConvSpec{pi + pc, l, C, C, true});
+            v.push_back(ConvSpec{pi, l, 2 * C, C, true, vcat_ok(nt)});
+            v.push_back(ConvSpec{pi + pc, l, C, C, true, false});
         }
 }
 static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole, bool bwd) {
@@ -224,8 +272,8 @@ static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole
     size_t b = 0;
     for (const ConvSpec& c : v) {
         lamp_tensor_desc xi = nt.td(c.l, c.Cin, c.Cin), xo = nt.td(c.l, c.Cout, c.Cout);
-        if (conv_repack_kind(&xi, &xo) >= 0) b += conv_repack_bytes(&xi, &xo);
-        if (bwd && conv_repack_kind(&xo, &xi) >= 0) b += conv_repack_bytes(&xo, &xi);
+        if (conv_repack_kind(&xi, &xo, c.parts) >= 0) b += conv_repack_bytes(&xi, &xo);
+        if (bwd && conv_repack_kind(&xo, &xi, c.parts) >= 0) b += conv_repack_bytes(&xo, &xi);
     }
     return b;
 }
@@ -245,7 +293,7 @@ static lamp_status prepare_repack(const Net& nt, const Layout& lay, int first, i
             if (dir == 0 ? !fwd : !(dgrad && c.dgrad)) continue;
             const lamp_tensor_desc* xd = dir == 0 ? &xi : &xo;   // the conv's input / output in this direction
             const lamp_tensor_desc* zd = dir == 0 ? &xo : &xi;
-            const int kind = conv_repack_kind(xd, zd);
+            const int kind = conv_repack_kind(xd, zd, c.parts);
             if (kind < 0 || tab.n >= 64 || !aligned16(P[c.pi])) continue;
             const size_t b = conv_repack_bytes(xd, zd);
             if (off + b > lay.repack_bytes) continue;
@@ -387,11 +435,13 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     const void* cur = lay.e2[L - 1].y;
     for (int l = L - 1; l >= 1; --l) {
         const int C = nt.chan(l), pi = dec_pi(u, l);
-        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
-        st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, (char*)lay.cat[l - 1] + (size_t)C * nt.es,
-                           nt.scratch, nt.scratch_bytes, nt.s);
+        const int ldc = lay.ldcat[l - 1];
+        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, ldc);
+        st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, lay.up[l - 1], nt.scratch, nt.scratch_bytes,
+                           nt.s);
         if (st != LAMP_OK) return st;
-        st = block_fwd(nt, l, 2 * C, 2 * C, lay.cat[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1]);
+        st = block_fwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1],
+                       lay.vcat ? lay.up[l - 1] : nullptr);
         if (st != LAMP_OK) return st;
         cur = lay.d2[l - 1].y;
     }
@@ -411,16 +461,17 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     std::vector<int> ldsg(L, 0);
     for (int l = 1; l <= L - 1; ++l) {
         const int C = nt.chan(l), pi = dec_pi(u, l);
-        st = block_bwd(nt, l, 2 * C, 2 * C, lay.cat[l - 1], C, P, G, pi + 2, lay.d1[l - 1], lay.d2[l - 1], lay.g0, lay.g1,
-                       lay.gcat[l - 1], 2 * C, beta);
+        const int ldc = lay.ldcat[l - 1];
+        st = block_bwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, G, pi + 2, lay.d1[l - 1], lay.d2[l - 1], lay.g0, lay.g1,
+                       lay.gskip[l - 1], ldc, beta, lay.vcat ? lay.up[l - 1] : nullptr, lay.vcat ? lay.gup[l - 1] : nullptr);
         if (st != LAMP_OK) return st;
-        skip_g[l - 1] = lay.gcat[l - 1];
-        ldsg[l - 1] = 2 * C;
-        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), dyd = nt.td(l, C, 2 * C), dxd = nt.td(l + 1, 2 * C, 2 * C);
+        skip_g[l - 1] = lay.gskip[l - 1];
+        ldsg[l - 1] = ldc;
+        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), dyd = nt.td(l, C, ldc), dxd = nt.td(l + 1, 2 * C, 2 * C);
         const void* xin = l + 1 == L ? lay.e2[L - 1].y : lay.d2[l].y;
         xd.ldc = l + 1 == L ? lay.e2[L - 1].ldy : lay.d2[l].ldy;
-        st = lamp_convtr3d_bwd(&xd, xin, nullptr, P[pi], &dyd, (char*)lay.gcat[l - 1] + (size_t)C * nt.es, &dxd, lay.g0,
-                               G[pi], G[pi + 1], beta, nt.scratch, nt.scratch_bytes, nt.s);
+        st = lamp_convtr3d_bwd(&xd, xin, nullptr, P[pi], &dyd, lay.gup[l - 1], &dxd, lay.g0, G[pi], G[pi + 1], beta, nt.scratch,
+                               nt.scratch_bytes, nt.s);
         if (st != LAMP_OK) return st;
     }
     return encoder_bwd(nt, lay, 1, L, P, G, 0, x, lay.g0, skip_g.data(), ldsg.data(), nullptr, beta);
