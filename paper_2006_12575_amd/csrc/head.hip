@@ -217,10 +217,25 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
         float lg[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) lg[i] = acc[i] + bias[i];
-        if (logits && valid) {
+        if (logits) {
+            // the group's logits are 32*K consecutive floats: pack them in LDS ([voxel][class]) and store 16 bytes
+            // per lane instead of eight 4-byte pieces per lane
+            float* pk = &xs[wv][0][0];
+            const int64_t left = Vtot - g * 32;   // valid voxels of the group (wave-uniform)
+            if (left >= 32) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (cls[i] < K) logits[v * K + cls[i]] = lg[i];
+                for (int i = 0; i < 8; ++i)
+                    if (cls[i] < K) pk[l32 * K + cls[i]] = lg[i];
+                __builtin_amdgcn_wave_barrier();
+                float* dst = logits + g * 32 * K;
+                for (int q4 = lane; q4 < 8 * K; q4 += 64)
+                    *reinterpret_cast<float4*>(dst + 4 * q4) = *reinterpret_cast<const float4*>(pk + 4 * q4);
+                __builtin_amdgcn_wave_barrier();
+            } else if (valid) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (cls[i] < K) logits[v * K + cls[i]] = lg[i];
+            }
         }
         if (MODE == 1) {
             float m = -3.0e38f;
@@ -270,13 +285,22 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
 #pragma unroll
                         for (int r = 0; r < 16; ++r) a2[r] = 0.f;
                         a2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(abw[cb], bdl, a2, 0, 0, 0);
+                        // 32 voxels x 32 channels: through LDS (80-byte rows) so that four lanes store the 64 bytes of
+                        // a voxel side by side
+                        char* tp = reinterpret_cast<char*>(&xs[wv][0][0]);
 #pragma unroll
-                        for (int rg = 0; rg < 4; ++rg) {
-                            const int ch = 32 * cb + 8 * rg + 4 * half;
-                            if (valid && ch < C)
-                                *reinterpret_cast<uint2*>(dx + v * lddx + ch) =
-                                    make_uint2(head_pack_bf16(a2[rg * 4 + 0], a2[rg * 4 + 1]), head_pack_bf16(a2[rg * 4 + 2], a2[rg * 4 + 3]));
+                        for (int rg = 0; rg < 4; ++rg)
+                            *reinterpret_cast<uint2*>(tp + l32 * 80 + (8 * rg + 4 * half) * 2) =
+                                make_uint2(head_pack_bf16(a2[rg * 4 + 0], a2[rg * 4 + 1]), head_pack_bf16(a2[rg * 4 + 2], a2[rg * 4 + 3]));
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int it = 0; it < 2; ++it) {
+                            const int vx = it * 16 + (lane >> 2), ch = 32 * cb + (lane & 3) * 8;
+                            const uint4 q = *reinterpret_cast<const uint4*>(tp + vx * 80 + (lane & 3) * 16);
+                            const int64_t vv = g * 32 + vx;
+                            if (vv < Vtot && ch < C) *reinterpret_cast<uint4*>(dx + vv * lddx + ch) = q;
                         }
+                        __builtin_amdgcn_wave_barrier();
                     }
                 }
             }
@@ -344,11 +368,12 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
 }
 
 static bool head_mfma_ok(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh, int classes,
-                         const lamp_tensor_desc* dxd, const void* dx) {
+                         const lamp_tensor_desc* dxd, const void* dx, const void* logits) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
     if (xd->dtype != LAMP_BF16 || nm || xd->c % 16 || xd->c > 64 || xd->ldc % 8 || classes > 16) return false;
     if (!aligned16(x) || !aligned16(wh)) return false;
-    if (dx && (dxd->ldc % 4 || (((uintptr_t)dx) & 7u))) return false;
+    if (dx && (dxd->ldc % 8 || !aligned16(dx))) return false;
+    if (logits && !aligned16(logits)) return false;
     return true;
 }
 static int head_mfma_blocks(int64_t V) {
@@ -397,7 +422,7 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
     if (!logits) return LAMP_ERR_NULL;
     if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
-    if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr)) {
+    if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr, logits)) {
         hipLaunchKernelGGL((head_mfma_kernel<0>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)x,
                            xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0, nullptr, nullptr,
                            nullptr);
@@ -455,7 +480,7 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
     const size_t csb = colsum_ws_bytes(Vt, K);
     void* csws = cv.take(csb);
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
-    if (head_mfma_ok(xd, x, xnorm, wh, K, dxd, dx)) {
+    if (head_mfma_ok(xd, x, xnorm, wh, K, dxd, dx, logits)) {
         // one pass: logits, loss, dx, per-wave partials of dWh and dbh (the dlogits buffer is not used)
         float* bpart = (float*)cv.take((size_t)4096 * K * sizeof(float));
         if (!cv.ok()) return LAMP_ERR_WORKSPACE;
