@@ -344,21 +344,35 @@ __global__ __launch_bounds__(256) void inorm_bwd_partial_kernel(const T* __restr
     }
 }
 
-// sums[n][c][2] = (sum g, sum g*zh) over all parts, fp64, fixed order.
-__global__ __launch_bounds__(64) void inorm_bwd_finalize_kernel(const float* __restrict__ partial, int parts, int C,
-                                                                float* __restrict__ sums) {
-    const int c = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
+// sums[n][c][2] = (sum g, sum g*zh) over all parts, fp64, fixed order (strided per thread with four
+// parts in flight, then a fixed tree over lanes and waves).
+__global__ __launch_bounds__(256) void inorm_bwd_finalize_kernel(const float* __restrict__ partial, int parts, int C,
+                                                                 float* __restrict__ sums) {
+    __shared__ double sh[4][2];
+    const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float2* pp = reinterpret_cast<const float2*>(partial) + (size_t)n * parts * C + c;
     double s = 0.0, q = 0.0;
-    for (int p = lane; p < parts; p += 64) {
-        size_t o = (((size_t)n * parts + p) * C + c) * 2;
-        s += (double)partial[o];
-        q += (double)partial[o + 1];
+    int p = tid;
+    for (; p + 768 < parts; p += 1024) {
+        float2 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = pp[(size_t)(p + 256 * u) * C];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s += (double)v[u].x; q += (double)v[u].y; }
+    }
+    for (; p < parts; p += 256) {
+        const float2 v = pp[(size_t)p * C];
+        s += (double)v.x;
+        q += (double)v.y;
     }
     for (int off = 32; off > 0; off >>= 1) {
         s += __shfl_down(s, off);
         q += __shfl_down(q, off);
     }
-    if (lane == 0) {
+    if (lane == 0) { sh[wv][0] = s; sh[wv][1] = q; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) { s += sh[w][0]; q += sh[w][1]; }
         sums[((size_t)n * C + c) * 2 + 0] = (float)s;
         sums[((size_t)n * C + c) * 2 + 1] = (float)q;
     }
@@ -490,7 +504,7 @@ extern "C" lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc* dyd, const vo
                            stats, gamma, beta, partial);
     });
     LAMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(zd->c, zd->n), dim3(64), 0, s, partial, chunks, zd->c, sums);
+    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(zd->c, zd->n), dim3(256), 0, s, partial, chunks, zd->c, sums);
     LAMP_CHECK_LAUNCH();
     if (dgamma || dbeta) {
         hipLaunchKernelGGL(inorm_dgb_kernel, dim3(cdiv(zd->c, 64)), dim3(64), 0, s, sums, zd->n, zd->c, dgamma, dbeta,
