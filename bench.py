@@ -49,7 +49,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
-              "(the path has no collectives; see DESIGN.md for how it would shard).", file=sys.stderr)
+              "(the path has no collectives; it would shard data-parallel over samples, as pipeline stages "
+              "after any block, or as spatial slabs with a one-voxel halo exchange).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
