@@ -60,7 +60,9 @@ def test_config1_tiny_unet_forward_fp32(L):
     dict(levels=2, base=8, in_ch=2, classes=5, affine=True, dtype=F32, dims=(1, 8, 12, 16)),
     dict(levels=3, base=32, in_ch=1, classes=4, affine=True, dtype=BF, dims=(1, 16, 24, 16)),
     dict(levels=1, base=32, in_ch=1, classes=3, affine=False, dtype=BF, dims=(1, 8, 8, 16)),
-], ids=["bf16-3lvl", "f32-affine", "bf16-affine", "bf16-1lvl"])
+    # 16 channels at level 1: generic kernels and a materialised concat buffer in bf16
+    dict(levels=2, base=16, in_ch=1, classes=3, affine=False, dtype=BF, dims=(2, 8, 8, 16)),
+], ids=["bf16-3lvl", "f32-affine", "bf16-affine", "bf16-1lvl", "bf16-base16"])
 def test_unet_fwd_bwd(L, cfg):
     """(a) every layer of the replayed chain matches the oracle given the GPU's own inputs,
     (b) lamp_unet_fwd_bwd reproduces the chain bit for bit, (c) end to end, logits and loss match the
