@@ -152,6 +152,7 @@ def main():
     try:
         roof["mfma_rate_zero_operands_tflops"] = L.lamp_probe_mfma_rate(0, 4000)
         roof["mfma_rate_normal_operands_tflops"] = L.lamp_probe_mfma_rate(1, 4000)
+        roof["mfma_rate_lds_fed_kernel_mix_tflops"] = L.lamp_probe_mfma_rate(2, 4000)
     except Exception:
         pass
     if args.copy_calibration:

@@ -84,7 +84,11 @@ const char *lamp_build_info(void);
  * measured over `iters` x 24 instructions per wave with one wave per SIMD.  pattern selects the operand
  * values: 0 = zeros, 1 = standard-normal (seeded).  The rate depends on the data (switching power and
  * with it the clock), which bounds what any kernel can reach on real activations; bench.py reports it
- * beside the published peak.  Allocates and frees a small device buffer; synchronises the stream.
+ * beside the published peak.  pattern 2 = the same loop at the convolution kernel's design point:
+ * standard-normal operands fetched fresh from LDS (12 fragment reads per 24 instructions), that kernel's
+ * measured ratio of other vector / scalar instructions and 3 register-free global->LDS copies beside
+ * them, no barriers and no exposed memory latency: what perfect scheduling of that instruction mix
+ * reaches.  Allocates and frees a small device buffer; synchronises the stream.
  * Errors: LAMP_ERR_NULL (tflops), LAMP_ERR_SHAPE (pattern, iters < 1), LAMP_ERR_HIP. */
 lamp_status lamp_probe_mfma_rate(int32_t pattern, int32_t iters, float *tflops, void *stream);
 

@@ -113,7 +113,8 @@ def build_info() -> str:
 
 
 def lamp_probe_mfma_rate(pattern: int, iters: int = 4000) -> float:
-    """TFLOP/s of a register-resident bf16 MFMA loop; pattern 0 = zero operands, 1 = standard-normal."""
+    """TFLOP/s of a bf16 MFMA loop, one wave per SIMD; pattern 0 = zero operands in registers, 1 = standard-normal
+    operands in registers, 2 = standard-normal operands fresh from LDS beside the conv kernel's instruction mix."""
     out = c_float(0.0)
     _check(lib().lamp_probe_mfma_rate(int(pattern), int(iters), ctypes.byref(out), _stream()), "lamp_probe_mfma_rate")
     return float(out.value)

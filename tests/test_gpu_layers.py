@@ -363,3 +363,11 @@ def test_determinism_bitwise(L):
         outs.append((z, st, dx, dw))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_probe_mfma_rate(L):
+    """The diagnostic entry point runs for every operand pattern and rejects an unknown one."""
+    rates = [L.lamp_probe_mfma_rate(p, 200) for p in (0, 1, 2)]
+    assert all(r > 10.0 for r in rates), rates
+    with pytest.raises(Exception):
+        L.lamp_probe_mfma_rate(3, 200)
