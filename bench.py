@@ -40,7 +40,8 @@ def main():
     ap.add_argument("--size", type=int, default=128, help="cubic volume side (default: the benchmark's 128)")
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny"],
+    ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny", "unet_train_b64", "unet_train_b128",
+                             "unet_infer_whole"],
                     help="block (default): the headline conv block (config 2). The others time the network-level "
                          "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -225,6 +226,11 @@ def net_bench(args, torch, np, S, L):
         "unet_train": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
         "unet_infer": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
         "sliding": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
+        # the wider nets of the paper's Sec. 3 (base 64 / 128: up to 1024 / 2048 channels) and a whole
+        # head-and-neck sized volume with unequal axes
+        "unet_train_b64": dict(levels=5, base=64, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1006),
+        "unet_train_b128": dict(levels=5, base=128, in_ch=1, classes=10, dims=(1, 128, 128, 128), dtype=bf, seed=1007),
+        "unet_infer_whole": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 352, 256, 288), dtype=bf, seed=1008),
     }[wl]
     levels, base, K, dt = cfg["levels"], cfg["base"], cfg["classes"], cfg["dtype"]
     N, D, H, W = cfg["dims"]
@@ -235,14 +241,14 @@ def net_bench(args, torch, np, S, L):
     x = torch.from_numpy(S.ct_volume(rx, N, D, H, W) if wl != "tiny" else S.normal(rx, (N, D, H, W, 1))).to(dt).to(dev)
     V = N * D * H * W
     steps, warm = max(1, args.steps), max(1, args.warmup)
-    if wl in ("tiny", "unet_infer"):
+    if wl in ("tiny", "unet_infer", "unet_infer_whole"):
         ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
         logits = torch.empty((N, D, H, W, K), dtype=f32, device=dev)
         ws = torch.empty(L.lamp_unet_workspace_bytes(ud, False), dtype=torch.uint8, device=dev)
         run = lambda: L.lamp_unet_fwd(ud, params, x, logits, ws=ws)
         flops = unet_flops(levels, base, 1, K, N, D, H, W)
         what = f"{levels}-level base-{base} U-Net forward, {N}x{D}x{H}x{W}"
-    elif wl == "unet_train":
+    elif wl.startswith("unet_train"):
         ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
         lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(dev)
         grads = [torch.empty(t.shape, dtype=f32, device=dev) for t in params]

@@ -60,7 +60,7 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
 
 __global__ __launch_bounds__(256) void repack_weights_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp,
                                                              int Cout, int Cin, int dgrad, int bykh) {
-    repack_tile_gran(w, wp, (int64_t)blockIdx.x * 256 + threadIdx.x, Cout, Cin, dgrad, bykh);
+    repack_tile_gran(w, wp, (int64_t)blockIdx.x * 256 + threadIdx.x, Cout, Cin, Cout % 64 == 0 ? 64 : 32, dgrad, bykh);
 }
 
 // All the repacks of a network pass in one launch: block -> job by the jobs' first-block table.
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void repack_batch_kernel(RepackBatch b) {
     while (k + 1 < b.n && (int)blockIdx.x >= b.j[k + 1].blk0) ++k;
     const RepackBatch::J& q = b.j[k];
     const int64_t i = (int64_t)((int)blockIdx.x - q.blk0) * 256 + threadIdx.x;
-    if (q.kind <= 1) repack_tile_gran(q.w, q.wp, i, q.Cout, q.Cin, q.dgrad, q.kind);
+    if (q.kind <= 1) repack_tile_gran(q.w, q.wp, i, q.Cout, q.Cin, q.Cout % 64 == 0 ? 64 : 32, q.dgrad, q.kind);
     else repack_ring_gran(q.w, q.wp, i, q.Cout, q.Cin, q.kind == 2 ? 64 : 32, q.dgrad);
 }
 
@@ -328,14 +328,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         hl.rel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx;
         hl.pk[j] = hd | (hh << 8) | (hw << 16);
     }
-    // weight copy q = wv + 8*i of a kd group: 64 consecutive (entry,row) pairs, entry = tap9*2 + plane
+    // weight copy q = wv + 8*i of a group: 64 consecutive (entry,row) pairs, entry = tap9*2 + plane.  The
+    // repacked weights are the LDS image itself, [co block][chunk][group][entry][row][8]: every copy reads 1 KB
+    // of consecutive memory
     int wrel[3];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const int er = (wv + 8 * i) * 64 + lane;
-        const int entry = er / WROWS, row = er - entry * WROWS;
-        wrel[i] = ((entry >> 1) * a.Cout + row) * a.Cin + (entry & 1) * 8;
-    }
+    for (int i = 0; i < 3; ++i) wrel[i] = ((wv + 8 * i) * 64 + lane) * 8;
     auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
@@ -352,8 +350,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         t.dlo = 1 - d0; t.dhi = a.D - d0; t.hlo = 1 - h0; t.hhi = a.H - h0; t.wlo = 1 - w0; t.whi = a.W - w0;
         return t;
     };
-    const bf16_t* wbase = a.wp + (int64_t)co0 * a.Cin;   // + (9*g*Cout)*Cin + chunk*16 per group
-    const int wgstride = 9 * a.Cout * a.Cin;
+    constexpr int wgstride = 18 * WROWS * 8;                                       // elements of one group
+    const bf16_t* wbase = a.wp + (int64_t)blockIdx.y * nchunks * (3 * wgstride);    // + (chunk*3 + g) * wgstride
 
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
@@ -373,7 +371,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         }
 #pragma unroll
         for (int i = 0; i < 3; ++i)
-            if (wv + 8 * i < WINSTR) g2lds16(wbase + c_lo * 16 + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
+            if (wv + 8 * i < WINSTR) g2lds16(wbase + (int64_t)c_lo * (3 * wgstride) + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
         wait_vmcnt<0>();
         __syncthreads();
     }
@@ -404,7 +402,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             const char* w1p = wbuf0 + (wpar ^ 1) * WBUF_BYTES + a_base;
             char* w0n = wbuf0 + wpar * WBUF_BYTES;
             char* w1n = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
-            const bf16_t* wc = wbase + chunk * 16;
+            const bf16_t* wc = wbase + (int64_t)chunk * (3 * wgstride);
             // halo copy slots per group (slot = block j * 2 + plane): 4 + 2 + 2 of 8, or 2 + 2 + 2 of 6
             constexpr int S0 = 2 * HJ - 4;
             const int64_t pf_off = choff(pf_chunk);
@@ -413,7 +411,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16,
                                            wc + 2 * wgstride, wrel, wv, lane);
             conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16,
-                                               wbase + pf_chunk * 16, wrel, wv, lane);
+                                               wbase + (int64_t)pf_chunk * (3 * wgstride), wrel, wv, lane);
             wpar ^= 1;
         }
 
