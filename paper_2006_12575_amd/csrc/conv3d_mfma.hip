@@ -121,6 +121,10 @@ struct ConvArgs {
     // channels from zsplit on go to z2 (channel stride ldz2), counted from its channel 0.
     int64_t xdelta; int xsplit;
     bf16_t* z2; int ldz2, zsplit;
+    // With very few tiles only the first XCD ranges hold work, and a workgroup's XCD is its flattened id
+    // modulo 8 = blockIdx.x & 7: rotating the range a workgroup serves by its channel-block / split index
+    // spreads the channel blocks of those few tiles over all eight XCDs.
+    int xcd_rot;
 };
 
 // 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
@@ -301,7 +305,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     constexpr int WINSTR = 18 * WROWS / 64;       // wave-wide copies per kd group: 18 or 9
 
     // persistent walk over an XCD-contiguous range of tiles
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+    const int xcd = (blockIdx.x + (a.xcd_rot ? blockIdx.y + blockIdx.z : 0u)) & 7, local = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
     const int tile_lo = xcd * a.tiles_per_xcd;
     const int tile_hi = min(tile_lo + a.tiles_per_xcd, a.tiles_total);
 
@@ -667,6 +671,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
     dim3 grid(wgx, zd->c / (32 * cob));
     a.zpart = nullptr; a.cps = 0;
+    a.xcd_rot = a.tiles_total < 32 ? 1 : 0;
     a.xdelta = two_in ? (int64_t)((const bf16_t*)parts->x2 - (const bf16_t*)x) : 0;
     a.xsplit = two_in ? parts->x_c1 / 16 : 0x7fffffff;
     a.z2 = two_out ? (bf16_t*)parts->z2 : nullptr;
