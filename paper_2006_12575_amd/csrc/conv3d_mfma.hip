@@ -581,7 +581,7 @@ size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd)
 }
 
 // Number of input-channel splits for the tiled kernel (1 = none): only where the 4-deep tiling with 64
-// output channels per workgroup leaves most of the chip idle and there are chunks to share out.
+// output channels per workgroup leaves at least half of the chip idle and there are chunks to share out.
 static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
     static int off = -1;
     if (off < 0) off = getenv("LAMP_CONV_NO_SPLIT") ? 1 : 0;
@@ -590,7 +590,7 @@ static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
     tile_dims(zd, 4, td, th, tw);
     const int64_t wgs = (int64_t)zd->n * td * th * tw * (zd->c / 64);
     const int nchunks = xd->c / 16;
-    if (wgs > 96 || nchunks < 4) return 1;
+    if (wgs > 128 || nchunks < 4) return 1;
     int S = (int)(256 / wgs);
     if (S > nchunks / 2) S = nchunks / 2;
     if (S < 2) return 1;
