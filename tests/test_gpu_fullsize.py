@@ -301,3 +301,44 @@ def test_stage_fullsize_sampled(L):
         assert torch.equal(gr, cg[kname]), f"stage grad {kname} differs from the chain"
     print("checked ops:", ch.checked)
     print("worst teacher-forced E_inf per op:", {k_: f"{v:.1e}" for k_, v in ch.worst.items()})
+
+
+# bench.py times the wide nets on 2 x 128^3 (base 64) and 1 x 128^3 (base 128); the routine suite checks them
+# on half / an eighth of that (same kernels: the ring kernel at level 1 of base 64, every 1024- and
+# 2048-channel layer); LAMP_TEST_WIDE_FULL=1 runs the bench sizes (4 minutes: passed when this was written).
+import os
+_WIDE = ([(64, (2, 128, 128, 128), 1006), (128, (1, 128, 128, 128), 1007)] if os.environ.get("LAMP_TEST_WIDE_FULL")
+         else [(64, (1, 128, 128, 128), 1006), (128, (1, 64, 64, 64), 1007)])
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("base,dims,seed", _WIDE, ids=["base64", "base128"])
+def test_wide_unet_train_sampled(L, base, dims, seed):
+    """The paper's wider nets (Sec. 3: 64 and 128 base filters, up to 1024 / 2048 channels):
+    layer-by-layer chain with sampled oracle checks of the 3x3x3 convolutions and full checks of
+    the O(V) ops, whole-network entry point equal to it bit for bit."""
+    from gpu_chain import Chain
+    from test_gpu_unet import make_net
+    levels, K = 5, 10
+    N, Dd, H, W = dims
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, seed)
+    rx, rl = S.streams(seed, 3)[1:]
+    x = torch.from_numpy(S.ct_volume(rx, N, Dd, H, W)).to(BF).to(DEV)
+    lab = torch.from_numpy(S.organ_labels(rl, N, Dd, H, W, K)).to(DEV)
+    ud = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
+    logits = torch.empty((N, Dd, H, W, K), dtype=F32, device=DEV)
+    loss = torch.empty((), dtype=F32, device=DEV)
+    grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
+    ch = Chain(L, levels, base, 1, K, False, BF, names, dev, verify="sampled")
+    ch.nsample = 256
+    lg = ch.forward(x)
+    print("forward checked:", ch.checked, flush=True)
+    assert torch.equal(lg, logits), "whole-net logits differ from the layer-by-layer chain"
+    loss_c, g_c = ch.backward(lab)
+    assert torch.equal(loss_c, loss)
+    for k, g in zip(names, grads):
+        assert torch.equal(g_c[k], g), f"whole-net grad {k} differs from the layer-by-layer chain"
+    print("checked ops:", ch.checked)
+    print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
+    assert ch.checked["conv fwd"] == 18 and ch.checked["conv dgrad"] == 17 and ch.checked["conv wgrad"] == 18
