@@ -141,29 +141,30 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float hf32x16;
 __device__ __forceinline__ uint32_t head_pack_bf16(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 
 // MODE 0: logits only.  MODE 1: + loss, dx, per-wave partials of dWh and dbh.
-template <int MODE>
-__global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
+// NCB: 32-channel blocks the instantiation holds (C <= 32 * NCB).
+template <int MODE, int NCB>
+__global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
                                                         const float* __restrict__ bh, int K, int C, int64_t Vtot,
                                                         const int32_t* __restrict__ labels, float* __restrict__ logits,
                                                         bf16_t* __restrict__ dx, int lddx, float* __restrict__ loss_part,
                                                         float* __restrict__ wpart, float* __restrict__ bpart) {
     __shared__ float dls[4][32][33];   // per wave: dlogits of 32 voxels x 32 (padded) classes
-    __shared__ float xs[4][32][65];    // per wave: activations of 32 voxels x up to 64 channels, fp32
+    __shared__ float xs[4][32][32 * NCB + 1];   // per wave: activations of 32 voxels x up to 32*NCB channels, fp32
     __shared__ float red[256];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l32 = lane & 31, half = lane >> 5;
     const int CK = C >> 4;                 // 16-channel k-steps
     const int CB = (C + 31) >> 5;          // 32-channel row blocks of dx / column blocks of dWh
     // forward A fragments: row = class l32, k = channels 16*kc + 8*half + e
-    hbf16x8 afw[4], abw[2];
+    hbf16x8 afw[2 * NCB], abw[NCB];
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
+    for (int kc = 0; kc < 2 * NCB; ++kc) {
         uint4 q = make_uint4(0, 0, 0, 0);
         if (kc < CK && l32 < K) q = *reinterpret_cast<const uint4*>(wh + (size_t)l32 * C + 16 * kc + 8 * half);
         afw[kc] = __builtin_bit_cast(hbf16x8, q);
     }
     // backward A fragments: row = channel 32*cb + l32, k = classes 8*half + e
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < NCB; ++cb) {
         uint32_t r[4] = {0, 0, 0, 0};
         const int ch = 32 * cb + l32;
         if (cb < CB && ch < C) {
@@ -187,10 +188,10 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
     if (MODE == 1) {
         for (int i = lane; i < 32 * 33; i += 64) (&dls[wv][0][0])[i] = 0.f;   // classes 16..31 stay zero
     }
-    hf32x16 accw[2];
+    hf32x16 accw[NCB];
     float dbsum[8];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) accw[cb][r] = 0.f;
 #pragma unroll
@@ -202,12 +203,12 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
         const int64_t v = g * 32 + l32;
         const bool valid = v < Vtot;
         const bf16_t* xp = x + (valid ? v : 0) * ldx;
-        uint4 xq[4];
+        uint4 xq[2 * NCB];
         hf32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-        for (int kc = 0; kc < 4; ++kc) {
+        for (int kc = 0; kc < 2 * NCB; ++kc) {
             xq[kc] = make_uint4(0, 0, 0, 0);
             if (kc < CK) {
                 if (valid) xq[kc] = *reinterpret_cast<const uint4*>(xp + 16 * kc + 8 * half);
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
                                                                          head_pack_bf16(bk[4], bk[5]), head_pack_bf16(bk[6], bk[7])));
             if (dx) {
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb) {
+                for (int cb = 0; cb < NCB; ++cb) {
                     if (cb < CB) {
                         hf32x16 a2;
 #pragma unroll
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
 #pragma unroll
                 for (int i = 0; i < 8; ++i) dls[wv][l32][cls[i]] = dl[i];
 #pragma unroll
-                for (int kc = 0; kc < 4; ++kc) {
+                for (int kc = 0; kc < 2 * NCB; ++kc) {
                     if (kc < CK) {
                         const uint32_t r4[4] = {xq[kc].x, xq[kc].y, xq[kc].z, xq[kc].w};
 #pragma unroll
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
                 for (int kv = 0; kv < 16; ++kv) {
                     const float av = dls[wv][2 * kv + half][l32];
 #pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) {
+                    for (int cb = 0; cb < NCB; ++cb) {
                         if (cb < CB) {
                             const int ch = 32 * cb + l32;
                             const float bv = ch < C ? xs[wv][2 * kv + half][ch] : 0.f;
@@ -348,7 +349,7 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
         if (wpart) {
             // accw: row = class 8*(r/4) + 4*half + (r%4), column = channel 32*cb + l32
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
+            for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int k = 8 * (r >> 2) + 4 * half + (r & 3), ch = 32 * cb + l32;
@@ -370,7 +371,7 @@ __global__ __launch_bounds__(256, 3) void head_mfma_kernel(const bf16_t* __restr
 static bool head_mfma_ok(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh, int classes,
                          const lamp_tensor_desc* dxd, const void* dx, const void* logits) {
     const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
-    if (xd->dtype != LAMP_BF16 || nm || xd->c % 16 || xd->c > 64 || xd->ldc % 8 || classes > 16) return false;
+    if (xd->dtype != LAMP_BF16 || nm || xd->c % 16 || xd->c > 128 || xd->ldc % 8 || classes > 16) return false;
     if (!aligned16(x) || !aligned16(wh)) return false;
     if (dx && (dxd->ldc % 8 || !aligned16(dx))) return false;
     if (logits && !aligned16(logits)) return false;
@@ -423,9 +424,14 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
     if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
     if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr, logits)) {
-        hipLaunchKernelGGL((head_mfma_kernel<0>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)x,
-                           xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0, nullptr, nullptr,
-                           nullptr);
+        if (xd->c <= 64)
+            hipLaunchKernelGGL((head_mfma_kernel<0, 2>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
+                               (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0,
+                               nullptr, nullptr, nullptr);
+        else
+            hipLaunchKernelGGL((head_mfma_kernel<0, 4>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
+                               (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0,
+                               nullptr, nullptr, nullptr);
         LAMP_CHECK_LAUNCH();
         return LAMP_OK;
     }
@@ -485,8 +491,12 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
         float* bpart = (float*)cv.take((size_t)4096 * K * sizeof(float));
         if (!cv.ok()) return LAMP_ERR_WORKSPACE;
         const int nbm = head_mfma_blocks(Vt);   // 4 * nbm <= 4096 partial slots
-        hipLaunchKernelGGL((head_mfma_kernel<1>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, K,
-                           C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
+        if (C <= 64)
+            hipLaunchKernelGGL((head_mfma_kernel<1, 2>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
+                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
+        else
+            hipLaunchKernelGGL((head_mfma_kernel<1, 4>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
+                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
         LAMP_CHECK_LAUNCH();
         if ((st = launch_reduce_partials(lpart, nbm, 1, loss, 0.f, s)) != LAMP_OK) return st;
         if (dwh && (st = launch_reduce_partials(wpart, nbm * 4, (int64_t)K * C, dwh, beta, s)) != LAMP_OK) return st;

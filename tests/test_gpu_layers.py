@@ -315,7 +315,8 @@ def test_convtr3d_fwd_bwd(L, dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 8, 5), (1, 8, 8, 8, 32, 10), (1, 5, 7, 9, 6, 1), (1, 4, 4, 4, 64, 16)],
+@pytest.mark.parametrize("shape", [(2, 3, 4, 5, 8, 5), (1, 8, 8, 8, 32, 10), (1, 5, 7, 9, 6, 1), (1, 4, 4, 4, 64, 16),
+                                   (2, 5, 6, 7, 128, 10), (1, 3, 5, 11, 96, 3)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_head_softmax_ce(L, dtype, shape):
     N, D, H, W, C, K = shape
