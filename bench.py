@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny", "unet_train_b64", "unet_train_b128",
-                             "unet_infer_whole"],
+                             "unet_infer_whole", "unet_train_step"],
                     help="block (default): the headline conv block (config 2). The others time the network-level "
                          "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -228,6 +228,8 @@ def net_bench(args, torch, np, S, L):
         "sliding": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
         # the wider nets of the paper's Sec. 3 (base 64 / 128: up to 1024 / 2048 channels) and a whole
         # head-and-neck sized volume with unequal axes
+        # forward + backward + RMSProp update of the fp32 masters and the bf16 working copies: one optimiser step
+        "unet_train_step": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
         "unet_train_b64": dict(levels=5, base=64, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1006),
         "unet_train_b128": dict(levels=5, base=128, in_ch=1, classes=10, dims=(1, 128, 128, 128), dtype=bf, seed=1007),
         "unet_infer_whole": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 352, 256, 288), dtype=bf, seed=1008),
@@ -254,9 +256,18 @@ def net_bench(args, torch, np, S, L):
         grads = [torch.empty(t.shape, dtype=f32, device=dev) for t in params]
         loss = torch.empty((), dtype=f32, device=dev)
         ws = torch.empty(L.lamp_unet_workspace_bytes(ud, True), dtype=torch.uint8, device=dev)
-        run = lambda: L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
         flops = 3.0 * unet_flops(levels, base, 1, K, N, D, H, W)
         what = f"{levels}-level base-{base} U-Net forward+backward (softmax CE), {N}x{D}x{H}x{W}"
+        if wl == "unet_train_step":
+            masters = [t.to(f32).clone() for t in params]
+            msq = [torch.zeros_like(t) for t in masters]
+
+            def run():
+                L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
+                L.lamp_rmsprop_step(masters, msq, grads, params, lr=1e-3, alpha=0.99, eps=1e-8)
+            what += " + RMSProp update (lr 1e-3)"
+        else:
+            run = lambda: L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
     elif wl == "sliding":
         P = 64
         cnt = L.lamp_sliding_window_count(D, H, W, P, 0.25)
@@ -299,6 +310,11 @@ def net_bench(args, torch, np, S, L):
            "dtype": "bf16" if dt == bf else "f32", "data": "synthetic",
            "config": {"workload": what, "voxels": V, "flop_per_step": flops},
            "tflops": flops / dtm / 1e12, "pct_mfma_peak": 100.0 * flops / dtm / 1e12 / PEAK_BF16_TFLOPS}
+    if wl.startswith("unet_train"):
+        out["final_loss"] = float(loss.item())   # the timed steps ran on finite data (the optimiser workload moves the weights)
+        if not np.isfinite(out["final_loss"]):
+            print("bench.py: the loss is not finite after the timed steps", file=sys.stderr)
+            sys.exit(1)
     print(json.dumps(out))
 
 

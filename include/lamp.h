@@ -79,6 +79,19 @@ typedef struct {
 const char *lamp_status_string(lamp_status s);
 /* Library version and the GPU architecture its kernels were compiled for ("gfx950"). */
 const char *lamp_build_info(void);
+/* RMSProp update of a set of parameter tensors in one pass (training recipe of Sec. 3: RMSProp, learning
+ * rate 1e-3; the update rule is the usual one, v <- alpha v + (1 - alpha) g^2, w <- w - lr g / (sqrt(v) + eps),
+ * no momentum, not centred).  For tensor i < count (numel[i] elements, all device pointers): w[i] fp32 master
+ * weights and v[i] fp32 running mean squares are updated in place from the fp32 gradient g[i] (as written by
+ * the backward entry points); w_out[i], if w_out and w_out[i] are non-null, receives the new weights in
+ * out_dtype[i] (LAMP_BF16: rounded to nearest even; LAMP_F32: copied unless it is w[i] itself): the working
+ * copy the forward pass reads.  The pointer tables and numel are host arrays, read during the call.  Nothing
+ * is allocated; the launches are enqueued on `stream`.
+ * Errors: LAMP_ERR_NULL, LAMP_ERR_SHAPE (count or numel negative, lr / alpha / eps out of range),
+ * LAMP_ERR_DTYPE (out_dtype), LAMP_ERR_HIP. */
+lamp_status lamp_rmsprop_step(int32_t count, const int64_t *numel, float *const *w, float *const *v, const float *const *g,
+                              void *const *w_out, const int32_t *out_dtype, float lr, float alpha, float eps, void *stream);
+
 /* Diagnostic, not part of the method: the rate (TFLOP/s) at which this GPU executes a register-resident
  * loop of the bf16 32x32x16 matrix-core instruction the convolution kernels use (no memory traffic),
  * measured over `iters` x 24 instructions per wave with one wave per SIMD.  pattern selects the operand

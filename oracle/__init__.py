@@ -270,3 +270,15 @@ def conv3d_wgrad_at(x, dz, entries):
         xx = x[:, od0 + kd - 1:od1 + kd - 1, oh0 + kh - 1:oh1 + kh - 1, ow0 + kw - 1:ow1 + kw - 1, ci].astype(np.float64)
         out[s] = float(np.sum(g * xx))
     return out
+
+
+# ---- optimiser (Sec. 3: RMSProp, learning rate 1e-3) -----------------------------------------------
+
+def rmsprop_step(w, v, g, lr=1e-3, alpha=0.99, eps=1e-8):
+    """One RMSProp update in fp64 (no momentum, not centred):
+    v' = alpha v + (1 - alpha) g^2,  w' = w - lr g / (sqrt(v') + eps).  Returns (w', v')."""
+    w = np.asarray(w, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    v2 = alpha * v + (1.0 - alpha) * g * g
+    return w - lr * g / (np.sqrt(v2) + eps), v2

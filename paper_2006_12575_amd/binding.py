@@ -52,6 +52,8 @@ _SIGS = {
     "lamp_status_string": (c_char_p, [c_int]),
     "lamp_build_info": (c_char_p, []),
     "lamp_probe_mfma_rate": (c_int, [c_int, c_int, POINTER(c_float), _VP]),
+    "lamp_rmsprop_step": (c_int, [c_int, POINTER(ctypes.c_int64), _VP, _VP, _VP, _VP, POINTER(c_int32), c_float, c_float,
+                                  c_float, _VP]),
     "lamp_conv3d_fwd_workspace_bytes": (c_size_t, [_PD, _PD, c_int]),
     "lamp_conv3d_fwd": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_conv3d_dgrad_workspace_bytes": (c_size_t, [_PD, _PD]),
@@ -176,6 +178,20 @@ def _ptr_table(tensors):
     for i, t in enumerate(tensors):
         arr[i] = t.data_ptr()
     return arr
+
+
+def lamp_rmsprop_step(w, v, g, w_out=None, lr=1e-3, alpha=0.99, eps=1e-8):
+    """RMSProp update of the fp32 master tensors `w` (lists of tensors; running mean squares `v`, fp32
+    gradients `g`), writing the working copies `w_out` (fp32 or bf16 tensors, entries may be None)."""
+    n = len(w)
+    numel = (ctypes.c_int64 * n)(*[int(t.numel()) for t in w])
+    outs = list(w_out) if w_out is not None else [None] * n
+    codes = (c_int32 * n)(*[_dtype_code(t) if t is not None else F32 for t in outs])
+    out_tab = (c_void_p * n)()
+    for i, t in enumerate(outs):
+        out_tab[i] = t.data_ptr() if t is not None else None
+    _check(lib().lamp_rmsprop_step(n, numel, _ptr_table(w), _ptr_table(v), _ptr_table(g), out_tab, codes, lr, alpha, eps,
+                                   _stream()), "lamp_rmsprop_step")
 
 
 # ---- layer calls ----------------------------------------------------------------------------------

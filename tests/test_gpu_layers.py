@@ -372,3 +372,28 @@ def test_probe_mfma_rate(L):
     assert all(r > 10.0 for r in rates), rates
     with pytest.raises(Exception):
         L.lamp_probe_mfma_rate(3, 200)
+
+
+def test_rmsprop_step(L):
+    """RMSProp update of several tensors in one call (odd sizes, a zero-sized one, fp32 and bf16 working
+    copies) against the fp64 oracle; the bf16 copy is the new master rounded to nearest even."""
+    r = rng(2100)
+    sizes = [1, 5, 1000, 27 * 32 * 32, 0, 4099]
+    w = [to_dev(S.normal(r, (n,)), F32) for n in sizes]
+    v = [to_dev(np.abs(S.normal(r, (n,))) * 0.1, F32) for n in sizes]
+    g = [to_dev(S.normal(r, (n,)) * 10.0 ** (i - 2), F32) for i, n in enumerate(sizes)]
+    outs = [torch.empty(n, dtype=BF if i % 2 == 0 else F32, device=DEV) for i, n in enumerate(sizes)]
+    outs[3] = None
+    w0, v0 = [as64(t) for t in w], [as64(t) for t in v]
+    for step in range(2):
+        L.lamp_rmsprop_step(w, v, g, outs, lr=1e-3, alpha=0.99, eps=1e-8)
+        for i in range(len(sizes)):
+            w0[i], v0[i] = O.rmsprop_step(w0[i], v0[i], as64(g[i]), 1e-3, 0.99, 1e-8)
+    for i, n in enumerate(sizes):
+        if n == 0:
+            continue
+        np.testing.assert_allclose(as64(w[i]), w0[i], rtol=2e-6, atol=1e-7)
+        np.testing.assert_allclose(as64(v[i]), v0[i], rtol=2e-6, atol=1e-12)
+        if outs[i] is not None:
+            ref = O.round_bf16(as64(w[i])) if outs[i].dtype == BF else as64(w[i])
+            np.testing.assert_array_equal(as64(outs[i]), ref)

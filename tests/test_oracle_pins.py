@@ -397,3 +397,27 @@ def test_round_bf16_known_values():
 
     t = torch.randn(1000, dtype=torch.float64, generator=torch.Generator().manual_seed(0))
     np.testing.assert_array_equal(O.round_bf16(t.numpy()), t.float().to(torch.bfloat16).double().numpy())
+
+
+def test_rmsprop_matches_an_independent_implementation():
+    """The oracle's RMSProp step against torch.optim.RMSprop (CPU, fp64) over several steps, and a
+    closed form: with a constant gradient c and v0 = 0, v_t = (1 - alpha^t) c^2."""
+    import torch
+    r = np.random.Generator(np.random.PCG64(5))
+    w0 = r.standard_normal((7, 5))
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.RMSprop([p], lr=1e-3, alpha=0.99, eps=1e-8)
+    w, v = w0.copy(), np.zeros_like(w0)
+    for step in range(5):
+        g = r.standard_normal(w0.shape) * (10.0 ** (step - 2))
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, v = O.rmsprop_step(w, v, g, lr=1e-3, alpha=0.99, eps=1e-8)
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=1e-13, atol=1e-15)
+    c, a = 0.3, 0.9
+    w, v = np.zeros(3), np.zeros(3)
+    for t in range(1, 6):
+        w_prev = w
+        w, v = O.rmsprop_step(w, v, np.full(3, c), lr=0.1, alpha=a, eps=0.0)
+        np.testing.assert_allclose(v, (1 - a ** t) * c * c, rtol=1e-13)
+        np.testing.assert_allclose(w_prev - w, 0.1 / np.sqrt(1 - a ** t), rtol=1e-13)
