@@ -127,3 +127,71 @@ def stage_backward(params, cache, g_pool, g_skips, first_level, last_level, leve
         g = store(g)
         g = _block_bwd(params, f"enc{l}", g, eps, store, cache, grads, need_dx=(l > first_level or first_level > 1))
     return grads, g
+
+
+# ---- the sequential form of Eq. 3: the net cut after encoder block `cut` -------------------------
+# Partition 0 = encoder blocks 1..cut (forward(..., first_level=1, last_level=cut) / stage_backward);
+# partition 1 ("tail") = encoder blocks cut+1..L, the decoder and the softmax head.  The skip copies
+# e_{l,1}, l <= cut, cross the cut next to the pooled tensor and come back as gradients.
+
+def tail_forward(params, pooled, skips, first_level, levels, eps=1e-5, store=_ident):
+    """pooled = pool(e_{first_level-1}); skips[l-1] = e_l for l < first_level.  -> (logits, cache)."""
+    cache = {}
+    a = np.asarray(pooled, dtype=np.float64)
+    sk = {l: np.asarray(skips[l - 1], dtype=np.float64) for l in range(1, first_level)}
+    for l in range(first_level, levels + 1):
+        a = _block_fwd(params, f"enc{l}", a, eps, store, cache)
+        if l < levels:
+            sk[l] = a
+            p = store(O.maxpool2_fwd(a))
+            cache[f"pool{l}"] = dict(x=a)
+            a = p
+    for l in range(levels - 1, 0, -1):
+        up = store(O.convtr3d_fwd(a, params[f"dec{l}.up.w"], params[f"dec{l}.up.b"]))
+        cache[f"dec{l}.up"] = dict(x=a)
+        a = _block_fwd(params, f"dec{l}", np.concatenate([sk[l], up], axis=-1), eps, store, cache)
+    cache["head"] = dict(x=a)
+    return O.head_fwd(a, params["head.w"], params["head.b"]), cache
+
+
+def tail_backward(params, cache, dlogits, first_level, levels, eps=1e-5, store=_ident):
+    """-> (grads of the tail's parameters, gradient of `pooled`, [gradient of e_l for l < first_level])."""
+    grads = {}
+    g, grads["head.w"], grads["head.b"] = O.head_bwd(cache["head"]["x"], params["head.w"], dlogits)
+    g = store(g)
+    skip_g = {}
+    for l in range(1, levels):
+        g = _block_bwd(params, f"dec{l}", g, eps, store, cache, grads)
+        C = g.shape[-1] // 2
+        skip_g[l] = np.ascontiguousarray(g[..., :C])
+        c = cache[f"dec{l}.up"]
+        g, grads[f"dec{l}.up.w"], grads[f"dec{l}.up.b"] = O.convtr3d_bwd(c["x"], params[f"dec{l}.up.w"],
+                                                                        np.ascontiguousarray(g[..., C:]))
+        g = store(g)
+    for l in range(levels, first_level - 1, -1):
+        if l < levels:
+            g = store(O.maxpool2_bwd(cache[f"pool{l}"]["x"], g) + skip_g[l])
+        g = _block_bwd(params, f"enc{l}", g, eps, store, cache, grads, need_dx=True)
+    return grads, g, [skip_g[l] for l in range(1, first_level)]
+
+
+def pipeline_loss_and_grads(params, x, labels, levels, cut, micro_batches, eps=1e-5, store=_ident):
+    """The mini-batch x (leading axis = micro_batches * n samples) run as the paper's pipeline does
+    (Sec. 2.1): split into micro-batches, each taken through partition 0 and the tail and back, the
+    weight gradients accumulated over the micro-batches.  Loss and gradients are those of the mean
+    cross entropy over the whole mini-batch, so each micro-batch's dlogits carry 1/(M n V)."""
+    M = micro_batches
+    n = x.shape[0] // M
+    assert n * M == x.shape[0]
+    total, loss = {}, 0.0
+    for m in range(M):
+        xm, lm = x[m * n:(m + 1) * n], labels[m * n:(m + 1) * n]
+        (pooled, skips), c0 = forward(params, xm, levels, eps, store, first_level=1, last_level=cut)
+        logits, c1 = tail_forward(params, pooled, skips, cut + 1, levels, eps, store)
+        l_m, dlogits = O.cross_entropy(logits, lm)
+        loss += l_m / M
+        g1, g_pooled, g_skips = tail_backward(params, c1, dlogits / M, cut + 1, levels, eps, store)
+        g0, _ = stage_backward(params, c0, g_pooled, g_skips, 1, cut, levels, eps, store)
+        for k, v in {**g0, **g1}.items():
+            total[k] = total[k] + v if k in total else v
+    return loss, total

@@ -113,6 +113,63 @@ def test_stage_composition_equals_whole_net():
         np.testing.assert_allclose(sg[k], grads[k], rtol=1e-10, atol=1e-14)
 
 
+@pytest.mark.parametrize("cut", [1, 2])
+def test_tail_after_stage_equals_whole_net(cut):
+    # Eq. 3 == Eq. 2 for the other side of the cut: partition 0 followed by the tail is the whole net,
+    # forward and backward, whose gradients the finite-difference pin above fixes
+    levels = 3
+    p, x, lab = make(levels, 2, 1, 3, (2, 8, 8, 8), 6)
+    loss, grads, logits, _ = unet.loss_and_grads(p, x, lab, levels)
+    (pooled, skips), c0 = unet.forward(p, x, levels, first_level=1, last_level=cut)
+    tl, c1 = unet.tail_forward(p, pooled, skips, cut + 1, levels)
+    np.testing.assert_array_equal(tl, logits)
+    _, dl = O.cross_entropy(tl, lab)
+    g1, g_pooled, g_skips = unet.tail_backward(p, c1, dl, cut + 1, levels)
+    g0, _ = unet.stage_backward(p, c0, g_pooled, g_skips, 1, cut, levels)
+    assert set(g0) | set(g1) == set(grads) and not set(g0) & set(g1)
+    assert all(k.startswith(tuple(f"enc{l}." for l in range(1, cut + 1))) for k in g0)
+    for k, v in {**g0, **g1}.items():
+        np.testing.assert_allclose(v, grads[k], rtol=1e-10, atol=1e-14, err_msg=k)
+
+
+def test_tail_input_gradients_by_finite_differences():
+    # the gradients that cross the cut backwards (of the pooled tensor and of each skip copy e_{l,1})
+    levels, cut = 3, 2
+    p, x, lab = make(levels, 2, 1, 3, (1, 8, 8, 8), 8)
+    (pooled, skips), _ = unet.forward(p, x, levels, first_level=1, last_level=cut)
+    logits, c1 = unet.tail_forward(p, pooled, skips, cut + 1, levels)
+    _, dl = O.cross_entropy(logits, lab)
+    _, g_pooled, g_skips = unet.tail_backward(p, c1, dl, cut + 1, levels)
+    r = np.random.Generator(np.random.PCG64(9))
+    hh = 1e-6
+    for t, g in [(pooled, g_pooled), (skips[0], g_skips[0]), (skips[1], g_skips[1])]:
+        assert g.shape == t.shape
+        flat, gflat = t.reshape(-1), g.reshape(-1)
+        for idx in r.choice(flat.size, size=3, replace=False):
+            old = flat[idx]
+            flat[idx] = old + hh
+            lp = O.cross_entropy(unet.tail_forward(p, pooled, skips, cut + 1, levels)[0], lab)[0]
+            flat[idx] = old - hh
+            lm = O.cross_entropy(unet.tail_forward(p, pooled, skips, cut + 1, levels)[0], lab)[0]
+            flat[idx] = old
+            fd = (lp - lm) / (2 * hh)
+            assert abs(fd - gflat[idx]) <= 2e-4 * max(1e-4, abs(fd)), (idx, fd, gflat[idx])
+
+
+@pytest.mark.parametrize("M", [2, 4])
+def test_micro_batches_add_up_to_the_mini_batch(M):
+    # Sec. 2.1: splitting the mini-batch into micro-batches changes nothing here because the
+    # normalisation is per sample: loss and accumulated gradients equal the whole mini-batch's
+    levels = 3
+    p, x, lab = make(levels, 2, 1, 3, (4, 8, 8, 8), 7)
+    loss, grads, _, _ = unet.loss_and_grads(p, x, lab, levels)
+    pl, pg = unet.pipeline_loss_and_grads(p, x, lab, levels, cut=1, micro_batches=M)
+    assert abs(pl - loss) <= 1e-12 * abs(loss)
+    assert set(pg) == set(grads)
+    for k in grads:
+        np.testing.assert_allclose(pg[k], grads[k], rtol=1e-9, atol=1e-14, err_msg=k)
+
+
 def test_bias_free_blocks_are_exact():
     # InstanceNorm removes a per-channel constant: adding a conv bias would change nothing
     levels = 2
