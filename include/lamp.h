@@ -283,6 +283,50 @@ lamp_status lamp_unet_stage_bwd(const lamp_unet_desc *desc, int first_level, int
                                 float *const *grads, float beta, void *dx,
                                 void *ws, size_t ws_bytes, void *stream);
 
+/* The net's tail as the last pipeline partition (Sec. 2.2 Eq. 3: the sequential form of the U-Net,
+ * in which the skip copies e_{l,1} of the blocks before the cut travel on to the decoder): encoder
+ * blocks first_level..levels, every decoder block and the head.  2 <= first_level <= levels.
+ * desc is the WHOLE net's descriptor (d,h,w = the network input's dims).
+ *   params / grads : the whole net's tables from entry lamp_unet_tail_param_offset(desc, first_level) on.
+ *   x              : pool(e_{first_level-1}), dense [N, D/2^(first_level-1).., C_{first_level-1}].
+ *   skips[l-1]     : e_l (activated, dense [N, D/2^(l-1).., C_l]) for l = 1..first_level-1, i.e. what
+ *                    lamp_unet_stage_fwd(desc, 1, first_level-1, ...) returns.
+ *   d_x, d_skips   : outputs of the backward, the gradients of x (nullable) and of every skip — the
+ *                    d_pooled / d_skips that lamp_unet_stage_bwd takes.
+ * Only where the decoder reads its concat input from two tensors (bf16, base a multiple of 32, the
+ * shapes the matrix-core kernels serve); otherwise LAMP_ERR_UNSUPPORTED and a workspace size of 0. */
+int32_t lamp_unet_tail_param_offset(const lamp_unet_desc *desc, int32_t first_level);
+size_t lamp_unet_tail_workspace_bytes(const lamp_unet_desc *desc, int first_level, int with_backward);
+lamp_status lamp_unet_tail_fwd(const lamp_unet_desc *desc, int first_level, const void *const *params,
+                               const void *x, const void *const *skips, float *logits,
+                               void *ws, size_t ws_bytes, void *stream);
+lamp_status lamp_unet_tail_fwd_bwd(const lamp_unet_desc *desc, int first_level, const void *const *params,
+                                   const void *x, const void *const *skips, const int32_t *labels,
+                                   float *logits, float *loss, float *const *grads, float beta,
+                                   void *d_x, void *const *d_skips,
+                                   void *ws, size_t ws_bytes, void *stream);
+
+/* Two partitions, M micro-batches, in the order of the micro-batch pipeline schedule (Sec. 2.1,
+ * Fig. 2c), on ONE device: partition 0 = encoder blocks 1..cut on `stream`, partition 1 = the tail
+ * on `aux_stream` (a different stream, same device, default priority).  Forward: at clock t
+ * partition 0 runs micro-batch t while partition 1 runs micro-batch t-1; backward: micro-batches in
+ * reverse, partition 1 one clock ahead of partition 0.  Every micro-batch keeps its activations
+ * (no recomputation).  desc describes ONE micro-batch (desc->n samples); x [M*n,D,H,W,in_ch],
+ * labels [M*n,D,H,W], logits (nullable) [M*n,D,H,W,classes].
+ * Results: loss = mean cross entropy over all M*n samples; grads = beta*grads + its gradient —
+ * the same function as lamp_unet_fwd_bwd on the whole mini-batch (InstanceNorm statistics are per
+ * sample, so micro-batching changes no activation); only the order of the fp32 sums over samples
+ * differs.  Deterministic: the order of accumulation is fixed by the schedule.
+ * Stream contract: the call waits (on the device) for the work already enqueued on `stream`, and
+ * `stream` waits for everything the call enqueued on `aux_stream`: synchronising `stream` is enough.
+ * The call creates and destroys 2M+2 HIP events (no device memory).  1 <= cut < levels, M <= 64.
+ * Restrictions of lamp_unet_tail_fwd_bwd apply. */
+size_t lamp_unet_pipeline_workspace_bytes(const lamp_unet_desc *desc, int cut, int micro_batches);
+lamp_status lamp_unet_pipeline_fwd_bwd(const lamp_unet_desc *desc, int cut, int micro_batches,
+                                       const void *const *params, const void *x, const int32_t *labels,
+                                       float *logits, float *loss, float *const *grads, float beta,
+                                       void *ws, size_t ws_bytes, void *stream, void *aux_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Sliding-window inference (Sec. 3, Tables 3/5: windows versus one whole-image pass).
  * The volume [1,D,H,W,in_ch] is covered by cubic windows of side `patch` with stride

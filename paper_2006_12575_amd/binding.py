@@ -82,6 +82,14 @@ _SIGS = {
     "lamp_unet_stage_fwd": (c_int, [_PU, c_int, c_int, POINTER(c_void_p), _VP, _VP, POINTER(c_void_p), _VP, c_size_t, _VP]),
     "lamp_unet_stage_bwd": (c_int, [_PU, c_int, c_int, POINTER(c_void_p), _VP, POINTER(c_void_p), _VP, POINTER(c_void_p),
                                     POINTER(c_void_p), c_float, _VP, _VP, c_size_t, _VP]),
+    "lamp_unet_tail_param_offset": (c_int32, [_PU, c_int32]),
+    "lamp_unet_tail_workspace_bytes": (c_size_t, [_PU, c_int, c_int]),
+    "lamp_unet_tail_fwd": (c_int, [_PU, c_int, POINTER(c_void_p), _VP, POINTER(c_void_p), _VP, _VP, c_size_t, _VP]),
+    "lamp_unet_tail_fwd_bwd": (c_int, [_PU, c_int, POINTER(c_void_p), _VP, POINTER(c_void_p), _VP, _VP, _VP,
+                                       POINTER(c_void_p), c_float, _VP, POINTER(c_void_p), _VP, c_size_t, _VP]),
+    "lamp_unet_pipeline_workspace_bytes": (c_size_t, [_PU, c_int, c_int]),
+    "lamp_unet_pipeline_fwd_bwd": (c_int, [_PU, c_int, c_int, POINTER(c_void_p), _VP, _VP, _VP, _VP, POINTER(c_void_p),
+                                           c_float, _VP, c_size_t, _VP, _VP]),
     "lamp_sliding_window_count": (c_int32, [c_int32, c_int32, c_int32, c_int32, c_float]),
     "lamp_sliding_window_workspace_bytes": (c_size_t, [_PU, c_int32, c_int32, c_int32]),
     "lamp_sliding_window_fwd": (c_int, [_PU, POINTER(c_void_p), _VP, c_int32, c_int32, c_int32, c_float, c_float, _VP, _VP,
@@ -342,6 +350,46 @@ def lamp_unet_stage_bwd(ud, first, last, params, x, skips, d_pooled, d_skips, gr
     _check(lib().lamp_unet_stage_bwd(ctypes.byref(ud), first, last, _ptr_table(params), _ptr(x), _ptr_table(skips),
                                      _ptr(d_pooled), _ptr_table(d_skips), _ptr_table(grads), beta, _ptr(dx), _ptr(ws),
                                      ws.numel(), _stream()), "lamp_unet_stage_bwd")
+
+
+def lamp_unet_tail_param_offset(ud, first):
+    return int(lib().lamp_unet_tail_param_offset(ctypes.byref(ud), first))
+
+
+def lamp_unet_tail_workspace_bytes(ud, first, with_backward=True):
+    return int(lib().lamp_unet_tail_workspace_bytes(ctypes.byref(ud), first, 1 if with_backward else 0))
+
+
+def lamp_unet_tail_fwd(ud, first, params, x, skips, logits, ws=None):
+    """params: the whole net's table from lamp_unet_tail_param_offset(ud, first) on."""
+    ws = ws if ws is not None else _ws(lamp_unet_tail_workspace_bytes(ud, first, False), x.device)
+    _check(lib().lamp_unet_tail_fwd(ctypes.byref(ud), first, _ptr_table(params), _ptr(x), _ptr_table(skips), _ptr(logits),
+                                    _ptr(ws), ws.numel(), _stream()), "lamp_unet_tail_fwd")
+    return logits
+
+
+def lamp_unet_tail_fwd_bwd(ud, first, params, x, skips, labels, loss, grads, d_skips, d_x=None, logits=None, beta=0.0,
+                           ws=None):
+    ws = ws if ws is not None else _ws(lamp_unet_tail_workspace_bytes(ud, first, True), x.device)
+    _check(lib().lamp_unet_tail_fwd_bwd(ctypes.byref(ud), first, _ptr_table(params), _ptr(x), _ptr_table(skips), _ptr(labels),
+                                        _ptr(logits), _ptr(loss), _ptr_table(grads), beta, _ptr(d_x), _ptr_table(d_skips),
+                                        _ptr(ws), ws.numel(), _stream()), "lamp_unet_tail_fwd_bwd")
+    return loss
+
+
+def lamp_unet_pipeline_workspace_bytes(ud, cut, micro_batches):
+    return int(lib().lamp_unet_pipeline_workspace_bytes(ctypes.byref(ud), cut, micro_batches))
+
+
+def lamp_unet_pipeline_fwd_bwd(ud, cut, micro_batches, params, x, labels, loss, grads, aux_stream, logits=None, beta=0.0,
+                               ws=None):
+    """ud describes one micro-batch; x and labels hold micro_batches of them.  aux_stream: a
+    torch.cuda.Stream (default priority) other than the current one."""
+    ws = ws if ws is not None else _ws(lamp_unet_pipeline_workspace_bytes(ud, cut, micro_batches), x.device)
+    _check(lib().lamp_unet_pipeline_fwd_bwd(ctypes.byref(ud), cut, micro_batches, _ptr_table(params), _ptr(x), _ptr(labels),
+                                            _ptr(logits), _ptr(loss), _ptr_table(grads), beta, _ptr(ws), ws.numel(),
+                                            _stream(), c_void_p(aux_stream.cuda_stream)), "lamp_unet_pipeline_fwd_bwd")
+    return loss
 
 
 def lamp_sliding_window_count(D, H, W, patch, overlap=0.25):

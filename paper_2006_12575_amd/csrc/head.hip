@@ -14,13 +14,12 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, int 
                                                    const float* __restrict__ bh, int K, int C, int64_t Vs, int64_t Vtot,
                                                    const int32_t* __restrict__ labels, float* __restrict__ logits,
                                                    float* __restrict__ dlogits, T* __restrict__ dx, int lddx,
-                                                   float* __restrict__ loss_part) {
+                                                   float* __restrict__ loss_part, float invV) {
     extern __shared__ float wsh[];  // [K][C]
     __shared__ float red[256];
     for (int i = threadIdx.x; i < K * C; i += 256) wsh[i] = io<T>::ld(wh + i);
     __syncthreads();
     float lsum = 0.f;
-    const float invV = 1.0f / (float)Vtot;
     for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < Vtot; v += (int64_t)gridDim.x * 256) {
         const int n = (int)(v / Vs);
         float acc[KM];
@@ -147,7 +146,7 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
                                                         const float* __restrict__ bh, int K, int C, int64_t Vtot,
                                                         const int32_t* __restrict__ labels, float* __restrict__ logits,
                                                         bf16_t* __restrict__ dx, int lddx, float* __restrict__ loss_part,
-                                                        float* __restrict__ wpart, float* __restrict__ bpart) {
+                                                        float* __restrict__ wpart, float* __restrict__ bpart, float invV) {
     __shared__ float dls[4][32][33];   // per wave: dlogits of 32 voxels x 32 (padded) classes
     __shared__ float xs[4][32][32 * NCB + 1];   // per wave: activations of 32 voxels x up to 32*NCB channels, fp32
     __shared__ float red[256];
@@ -197,7 +196,6 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
 #pragma unroll
     for (int i = 0; i < 8; ++i) dbsum[i] = 0.f;
     float lsum = 0.f;
-    const float invV = 1.0f / (float)Vtot;
     const int64_t groups = (Vtot + 31) / 32;
     for (int64_t g = (int64_t)blockIdx.x * 4 + wv; g < groups; g += (int64_t)gridDim.x * 4) {
         const int64_t v = g * 32 + l32;
@@ -427,11 +425,11 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
         if (xd->c <= 64)
             hipLaunchKernelGGL((head_mfma_kernel<0, 2>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
                                (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0,
-                               nullptr, nullptr, nullptr);
+                               nullptr, nullptr, nullptr, 0.f);
         else
             hipLaunchKernelGGL((head_mfma_kernel<0, 4>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
                                (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0,
-                               nullptr, nullptr, nullptr);
+                               nullptr, nullptr, nullptr, 0.f);
         LAMP_CHECK_LAUNCH();
         return LAMP_OK;
     }
@@ -442,7 +440,7 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
         LAMP_DISPATCH_KM(classes, {
             hipLaunchKernelGGL((head_kernel<T, VEC, 0, KM>), dim3(head_blocks(Vt)), dim3(256), shm, (hipStream_t)stream,
                                (const T*)x, xd->ldc, nm, (const T*)wh, bh, classes, xd->c, Vs, Vt, nullptr, logits,
-                               nullptr, (T*)nullptr, 0, nullptr);
+                               nullptr, (T*)nullptr, 0, nullptr, 0.f);
         });
     });
     LAMP_CHECK_LAUNCH();
@@ -461,6 +459,17 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
                                     const float* bh, int classes, const int32_t* labels, float* logits, float* loss,
                                     const lamp_tensor_desc* dxd, void* dx, float* dwh, float* dbh, float beta, void* ws,
                                     size_t ws_bytes, void* stream) {
+    return lamp::head_ce_run(xd, x, xnorm, wh, bh, classes, labels, logits, loss, dxd, dx, dwh, dbh, beta, 0, 0.f, ws, ws_bytes,
+                             stream);
+}
+
+// norm_count: the voxel count the mean is taken over (0: this call's own voxels); a micro-batch of a
+// larger mini-batch passes the mini-batch's count, so that losses and gradients of the micro-batches
+// add up to the mini-batch's.  loss_beta: 1 adds this call's loss to *loss instead of overwriting it.
+lamp_status lamp::head_ce_run(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh,
+                              const float* bh, int classes, const int32_t* labels, float* logits, float* loss,
+                              const lamp_tensor_desc* dxd, void* dx, float* dwh, float* dbh, float beta, int64_t norm_count,
+                              float loss_beta, void* ws, size_t ws_bytes, void* stream) {
     lamp_status st = head_check(xd, x, wh, classes);
     if (st != LAMP_OK) return st;
     if (!labels || !loss) return LAMP_ERR_NULL;
@@ -476,6 +485,7 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
     if (!ws || ws_bytes < lamp_head_ce_workspace_bytes(xd, classes)) return LAMP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
+    const float invV = 1.0f / (float)(norm_count > 0 ? norm_count : Vt);
     const int K = classes, C = xd->c;
     Carver cv(ws, ws_bytes);
     float* dlogits = (float*)cv.take((size_t)Vt * K * sizeof(float));
@@ -493,12 +503,12 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
         const int nbm = head_mfma_blocks(Vt);   // 4 * nbm <= 4096 partial slots
         if (C <= 64)
             hipLaunchKernelGGL((head_mfma_kernel<1, 2>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
-                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
+                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
         else
             hipLaunchKernelGGL((head_mfma_kernel<1, 4>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
-                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr);
+                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
         LAMP_CHECK_LAUNCH();
-        if ((st = launch_reduce_partials(lpart, nbm, 1, loss, 0.f, s)) != LAMP_OK) return st;
+        if ((st = launch_reduce_partials(lpart, nbm, 1, loss, loss_beta, s)) != LAMP_OK) return st;
         if (dwh && (st = launch_reduce_partials(wpart, nbm * 4, (int64_t)K * C, dwh, beta, s)) != LAMP_OK) return st;
         if (dbh && (st = launch_reduce_partials(bpart, nbm * 4, K, dbh, beta, s)) != LAMP_OK) return st;
         return LAMP_OK;
@@ -509,11 +519,11 @@ extern "C" lamp_status lamp_head_ce(const lamp_tensor_desc* xd, const void* x, c
     LAMP_DISPATCH_TV(xd->dtype, vec, {
         LAMP_DISPATCH_KM(K, {
             hipLaunchKernelGGL((head_kernel<T, VEC, 1, KM>), dim3(nb), dim3(256), shm, s, (const T*)x, xd->ldc, nm,
-                               (const T*)wh, bh, K, C, Vs, Vt, labels, logits, dlogits, (T*)dx, lddx, lpart);
+                               (const T*)wh, bh, K, C, Vs, Vt, labels, logits, dlogits, (T*)dx, lddx, lpart, invV);
         });
     });
     LAMP_CHECK_LAUNCH();
-    if ((st = launch_reduce_partials(lpart, nb, 1, loss, 0.f, s)) != LAMP_OK) return st;
+    if ((st = launch_reduce_partials(lpart, nb, 1, loss, loss_beta, s)) != LAMP_OK) return st;
     if (dwh) {
         const int64_t vps = (Vt + S - 1) / S;
         dim3 grid(S, cdiv(C, 256));

@@ -41,6 +41,14 @@ size_t colsum_ws_bytes(int64_t rows, int C);
 lamp_status launch_colsum(const void* t, int dtype, int64_t rows, int C, int ld, float* out, float beta,
                           void* ws, size_t ws_bytes, hipStream_t s);
 
+// ---- head.hip -------------------------------------------------------------------------------
+// lamp_head_ce with the mean taken over norm_count voxels (0: the call's own) and the loss added to
+// *loss when loss_beta == 1.
+lamp_status head_ce_run(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh,
+                        const float* bh, int classes, const int32_t* labels, float* logits, float* loss,
+                        const lamp_tensor_desc* dxd, void* dx, float* dwh, float* dbh, float beta, int64_t norm_count,
+                        float loss_beta, void* ws, size_t ws_bytes, void* stream);
+
 // ---- conv3d_mfma.hip ------------------------------------------------------------------------
 // Matrix-core implicit-GEMM paths; each returns LAMP_ERR_UNSUPPORTED when the shape is not one
 // they serve, and the caller falls back to the generic kernels.

@@ -161,8 +161,10 @@ static bool vcat_ok(const Net& nt) {
 }
 
 // Lays out every buffer of levels [first, last] of the encoder and (whole == true) the decoder.
+// whole && first > 1 (the net's tail): the skips of levels below `first` and their gradients are the
+// caller's tensors ext_skips[l-1] / ext_gskips[l-1]; this needs the virtual concat.
 static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void* base, Layout& lay,
-                        void* const* ext_skips, void* ext_pooled) {
+                        void* const* ext_skips, void* ext_pooled, void* const* ext_gskips = nullptr) {
     const lamp_unet_desc* u = nt.u;
     const int L = nt.L;
     Carver cv(base ? base : (void*)256, (size_t)1 << 62);
@@ -173,6 +175,15 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
     lay.vcat = whole && vcat_ok(nt);
     const size_t es = nt.es;
     size_t scratch = 0, gmax = 0;
+    if (whole)
+        for (int l = 1; l < first; ++l) {
+            const size_t tb = (size_t)nt.vox(l) * nt.chan(l) * es;
+            lay.skip[l - 1] = ext_skips ? ext_skips[l - 1] : nullptr;
+            lay.gskip[l - 1] = ext_gskips ? ext_gskips[l - 1] : nullptr;
+            lay.up[l - 1] = take(tb);
+            if (bwd) lay.gup[l - 1] = take(tb);
+            lay.ldcat[l - 1] = nt.chan(l);
+        }
     for (int l = first; l <= last; ++l) {
         const int C = nt.chan(l);
         const int Cin = l == 1 ? u->in_ch : nt.chan(l - 1);
@@ -217,6 +228,7 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
             b.z = take(tb); b.stats = (float*)take(sb); b.y = bwd ? take(tb) : b.z; b.ldy = C;
             size_t sc = block_scratch(nt, l, 2 * C, C, bwd);
             scratch = sc > scratch ? sc : scratch;
+            gmax = tb > gmax ? tb : gmax;
             {
                 lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, 2 * C);
                 size_t t = lamp_convtr3d_workspace_bytes(&xd, &yd);
@@ -261,7 +273,7 @@ static void list_convs(const Net& nt, int first, int last, bool whole, int pbase
     }
     if (whole)
         for (int l = nt.L - 1; l >= 1; --l) {
-            const int C = nt.chan(l), pi = dec_pi(u, l) + 2;
+            const int C = nt.chan(l), pi = dec_pi(u, l) + 2 - pbase;
             v.push_back(ConvSpec{pi, l, 2 * C, C, true, vcat_ok(nt)});
             v.push_back(ConvSpec{pi + pc, l, C, C, true, false});
         }
@@ -405,13 +417,30 @@ extern "C" size_t lamp_unet_workspace_bytes(const lamp_unet_desc* u, int with_ba
     return lay.total;
 }
 
+// The net's tail: encoder blocks first..L, the whole decoder and the head, fed with the pooled output
+// of block first-1 and the skips e_1..e_{first-1} (Eq. 3: the copies e_{l,1} that travel past the cut).
+// phase 0: the whole pass; 1: the forward up to the head's input, laid out for a backward;
+// 2: head, loss and the backward over what phase 1 left in the workspace.
+struct TailIO {
+    int first;
+    const void* const* skips;   // [first-1]
+    void* const* d_skips;       // [first-1], written (backward)
+    void* d_x;                  // gradient w.r.t. the tail's input (backward), nullable
+    int phase;
+    int64_t norm_count;         // voxel count of the loss mean (0: this call's own)
+    float loss_beta;
+};
+
 static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const void* x, const int32_t* labels,
                             float* logits, float* loss, float* const* G, float beta, bool bwd, void* ws, size_t ws_bytes,
-                            void* stream) {
+                            void* stream, const TailIO* tail = nullptr) {
     lamp_status st = unet_desc_ok(u);
     if (st != LAMP_OK) return st;
     if (!P || !x) return LAMP_ERR_NULL;
-    const int np = lamp_unet_param_count(u);
+    const int first = tail ? tail->first : 1, phase = tail ? tail->phase : 0;
+    if (first < 1 || first > u->levels) return LAMP_ERR_SHAPE;
+    const int pbase = enc_pi(u, first);
+    const int np = lamp_unet_param_count(u) - pbase;
     for (int i = 0; i < np; ++i)
         if (!P[i]) return LAMP_ERR_NULL;
     if (bwd) {
@@ -420,47 +449,63 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
             if (!G[i]) return LAMP_ERR_NULL;
         if (beta != 0.f && beta != 1.f) return LAMP_ERR_SHAPE;
     } else if (!logits) return LAMP_ERR_NULL;
+    if (first > 1) {
+        if (!tail->skips || (bwd && !tail->d_skips)) return LAMP_ERR_NULL;
+        for (int l = 1; l < first; ++l) {
+            if (!tail->skips[l - 1] || (bwd && !tail->d_skips[l - 1])) return LAMP_ERR_NULL;
+            if (!aligned16(tail->skips[l - 1]) || (bwd && !aligned16(tail->d_skips[l - 1]))) return LAMP_ERR_ALIGN;
+        }
+        if (tail->d_x && !aligned16(tail->d_x)) return LAMP_ERR_ALIGN;
+    }
     if (!aligned16(x) || !aligned16(ws)) return LAMP_ERR_ALIGN;
-    if (!ws || ws_bytes < lamp_unet_workspace_bytes(u, bwd)) return LAMP_ERR_WORKSPACE;
     Net nt{u, u->levels, u->dtype, esize(u->dtype), (hipStream_t)stream, nullptr, 0};
     const int L = nt.L;
+    if (first > 1 && !vcat_ok(nt)) return LAMP_ERR_UNSUPPORTED;   // external skips need the two-tensor concat
     Layout lay;
-    make_layout(nt, 1, L, true, bwd, ws, lay, nullptr, nullptr);
+    make_layout(nt, first, L, true, bwd, nullptr, lay, nullptr, nullptr);
+    if (!ws || ws_bytes < lay.total) return LAMP_ERR_WORKSPACE;
+    make_layout(nt, first, L, true, bwd, ws, lay, tail ? (void* const*)tail->skips : nullptr, nullptr,
+                tail && bwd ? tail->d_skips : nullptr);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    const bool first_dgrad = tail && tail->d_x;
     RepackTable tab;
-    if ((st = prepare_repack(nt, lay, 1, L, true, 0, P, true, bwd, false, tab)) != LAMP_OK) return st;
+    if ((st = prepare_repack(nt, lay, first, L, true, pbase, P, phase != 2, bwd && phase != 1, first_dgrad, tab)) != LAMP_OK)
+        return st;
     RepackScope scope(&tab);
 
-    if ((st = encoder_fwd(nt, lay, 1, L, P, 0, x)) != LAMP_OK) return st;
-    const void* cur = lay.e2[L - 1].y;
-    for (int l = L - 1; l >= 1; --l) {
-        const int C = nt.chan(l), pi = dec_pi(u, l);
-        const int ldc = lay.ldcat[l - 1];
-        lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, ldc);
-        st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, lay.up[l - 1], nt.scratch, nt.scratch_bytes,
-                           nt.s);
-        if (st != LAMP_OK) return st;
-        st = block_fwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1],
-                       lay.vcat ? lay.up[l - 1] : nullptr);
-        if (st != LAMP_OK) return st;
-        cur = lay.d2[l - 1].y;
-    }
-    const int C1 = nt.chan(1), hp = head_pi(u);
+    const int C1 = nt.chan(1), hp = head_pi(u) - pbase;
     lamp_tensor_desc hd = nt.td(1, C1, C1);
     const void* top = L > 1 ? lay.d2[0].y : lay.e2[0].y;
-    const int ldtop = L > 1 ? lay.d2[0].ldy : lay.e2[0].ldy;
-    hd.ldc = ldtop;
-    if (!bwd) return lamp_head_fwd(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, logits, nt.s);
+    hd.ldc = L > 1 ? lay.d2[0].ldy : lay.e2[0].ldy;
+    if (phase != 2) {
+        if ((st = encoder_fwd(nt, lay, first, L, P, pbase, x)) != LAMP_OK) return st;
+        const void* cur = lay.e2[L - 1].y;
+        for (int l = L - 1; l >= 1; --l) {
+            const int C = nt.chan(l), pi = dec_pi(u, l) - pbase;
+            const int ldc = lay.ldcat[l - 1];
+            lamp_tensor_desc xd = nt.td(l + 1, 2 * C, 2 * C), yd = nt.td(l, C, ldc);
+            st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, lay.up[l - 1], nt.scratch,
+                               nt.scratch_bytes, nt.s);
+            if (st != LAMP_OK) return st;
+            st = block_fwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1],
+                           lay.vcat ? lay.up[l - 1] : nullptr);
+            if (st != LAMP_OK) return st;
+            cur = lay.d2[l - 1].y;
+        }
+        if (!bwd) return lamp_head_fwd(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, logits, nt.s);
+        if (phase == 1) return LAMP_OK;
+    }
 
     // ---- backward ----
     lamp_tensor_desc gd = nt.td(1, C1, C1);
-    st = lamp_head_ce(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, labels, logits, loss, &gd, lay.g0,
-                      G[hp], G[hp + 1], beta, nt.scratch, nt.scratch_bytes, nt.s);
+    st = head_ce_run(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, labels, logits, loss, &gd, lay.g0, G[hp],
+                     G[hp + 1], beta, tail ? tail->norm_count : 0, tail ? tail->loss_beta : 0.f, nt.scratch, nt.scratch_bytes,
+                     nt.s);
     if (st != LAMP_OK) return st;
     std::vector<const void*> skip_g(L, nullptr);
     std::vector<int> ldsg(L, 0);
     for (int l = 1; l <= L - 1; ++l) {
-        const int C = nt.chan(l), pi = dec_pi(u, l);
+        const int C = nt.chan(l), pi = dec_pi(u, l) - pbase;
         const int ldc = lay.ldcat[l - 1];
         st = block_bwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, G, pi + 2, lay.d1[l - 1], lay.d2[l - 1], lay.g0, lay.g1,
                        lay.gskip[l - 1], ldc, beta, lay.vcat ? lay.up[l - 1] : nullptr, lay.vcat ? lay.gup[l - 1] : nullptr);
@@ -474,7 +519,7 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
                                nt.scratch_bytes, nt.s);
         if (st != LAMP_OK) return st;
     }
-    return encoder_bwd(nt, lay, 1, L, P, G, 0, x, lay.g0, skip_g.data(), ldsg.data(), nullptr, beta);
+    return encoder_bwd(nt, lay, first, L, P, G, pbase, x, lay.g0, skip_g.data(), ldsg.data(), tail ? tail->d_x : nullptr, beta);
 }
 
 extern "C" lamp_status lamp_unet_fwd(const lamp_unet_desc* u, const void* const* params, const void* x, float* logits,
@@ -571,6 +616,182 @@ extern "C" lamp_status lamp_unet_stage_bwd(const lamp_unet_desc* u, int first, i
     std::vector<int> ld(v.levels, 0);
     for (int l = first; l <= last; ++l) { sg[l - 1] = d_skips[l - first]; ld[l - 1] = nt.chan(l); }
     return encoder_bwd(nt, lay, first, last, params, grads, enc_pi(&v, first), x, d_pooled, sg.data(), ld.data(), dx, beta);
+}
+
+// ---- the net's tail (second pipeline partition) and the two-partition micro-batch schedule -----------
+static lamp_status tail_ok(const lamp_unet_desc* u, int first) {
+    lamp_status st = unet_desc_ok(u);
+    if (st != LAMP_OK) return st;
+    if (first < 2 || first > u->levels) return LAMP_ERR_SHAPE;
+    return LAMP_OK;
+}
+
+extern "C" int32_t lamp_unet_tail_param_offset(const lamp_unet_desc* u, int32_t first) {
+    if (tail_ok(u, first) != LAMP_OK) return -1;
+    return enc_pi(u, first);
+}
+
+extern "C" size_t lamp_unet_tail_workspace_bytes(const lamp_unet_desc* u, int first, int with_backward) {
+    if (tail_ok(u, first) != LAMP_OK) return 0;
+    Net nt{u, u->levels, u->dtype, esize(u->dtype), nullptr, nullptr, 0};
+    if (!vcat_ok(nt)) return 0;
+    Layout lay;
+    make_layout(nt, first, u->levels, true, with_backward != 0, nullptr, lay, nullptr, nullptr);
+    return lay.total;
+}
+
+extern "C" lamp_status lamp_unet_tail_fwd(const lamp_unet_desc* u, int first, const void* const* params, const void* x,
+                                          const void* const* skips, float* logits, void* ws, size_t ws_bytes, void* stream) {
+    lamp_status st = tail_ok(u, first);
+    if (st != LAMP_OK) return st;
+    TailIO io{first, skips, nullptr, nullptr, 0, 0, 0.f};
+    return unet_run(u, params, x, nullptr, logits, nullptr, nullptr, 0.f, false, ws, ws_bytes, stream, &io);
+}
+
+extern "C" lamp_status lamp_unet_tail_fwd_bwd(const lamp_unet_desc* u, int first, const void* const* params, const void* x,
+                                              const void* const* skips, const int32_t* labels, float* logits, float* loss,
+                                              float* const* grads, float beta, void* d_x, void* const* d_skips, void* ws,
+                                              size_t ws_bytes, void* stream) {
+    lamp_status st = tail_ok(u, first);
+    if (st != LAMP_OK) return st;
+    TailIO io{first, skips, d_skips, d_x, 0, 0, 0.f};
+    return unet_run(u, params, x, labels, logits, loss, grads, beta, true, ws, ws_bytes, stream, &io);
+}
+
+namespace lamp {
+
+// Per-micro-batch buffers of the two-partition schedule, carved from the caller's workspace.
+struct PipeSlot {
+    void* stage_ws; void* tail_ws;
+    void* pooled; void* d_pooled;
+    void* skips[8]; void* d_skips[8];
+};
+struct PipeLayout {
+    size_t stage_bytes, tail_bytes, total;
+    std::vector<PipeSlot> slot;
+};
+
+static bool pipe_layout(const lamp_unet_desc* u, int cut, int M, void* base, PipeLayout& pl) {
+    Net nt{u, u->levels, u->dtype, esize(u->dtype), nullptr, nullptr, 0};
+    pl.stage_bytes = lamp_unet_stage_workspace_bytes(u, 1, cut, 1);
+    pl.tail_bytes = lamp_unet_tail_workspace_bytes(u, cut + 1, 1);
+    if (!pl.stage_bytes || !pl.tail_bytes) return false;
+    Carver cv(base ? base : (void*)256, (size_t)1 << 62);
+    auto take = [&](size_t b) -> void* { void* p = cv.take(b); return base ? p : nullptr; };
+    pl.slot.assign(M, PipeSlot{});
+    for (int m = 0; m < M; ++m) {
+        PipeSlot& sl = pl.slot[m];
+        sl.stage_ws = take(pl.stage_bytes);
+        sl.tail_ws = take(pl.tail_bytes);
+        const size_t pb = (size_t)nt.vox(cut + 1) * nt.chan(cut) * nt.es;
+        sl.pooled = take(pb); sl.d_pooled = take(pb);
+        for (int l = 1; l <= cut; ++l) {
+            const size_t tb = (size_t)nt.vox(l) * nt.chan(l) * nt.es;
+            sl.skips[l - 1] = take(tb); sl.d_skips[l - 1] = take(tb);
+        }
+    }
+    pl.total = align_up(cv.off) + 256;
+    return true;
+}
+
+}  // namespace lamp
+
+static lamp_status pipe_ok(const lamp_unet_desc* u, int cut, int M) {
+    lamp_status st = unet_desc_ok(u);
+    if (st != LAMP_OK) return st;
+    if (cut < 1 || cut >= u->levels || M < 1 || M > 64) return LAMP_ERR_SHAPE;
+    return LAMP_OK;
+}
+
+extern "C" size_t lamp_unet_pipeline_workspace_bytes(const lamp_unet_desc* u, int cut, int micro_batches) {
+    if (pipe_ok(u, cut, micro_batches) != LAMP_OK) return 0;
+    PipeLayout pl;
+    return pipe_layout(u, cut, micro_batches, nullptr, pl) ? pl.total : 0;
+}
+
+#define LAMP_PIPE_HIP(call)                         \
+    do {                                            \
+        if (st == LAMP_OK && (call) != hipSuccess) st = LAMP_ERR_HIP; \
+    } while (0)
+
+extern "C" lamp_status lamp_unet_pipeline_fwd_bwd(const lamp_unet_desc* u, int cut, int micro_batches,
+                                                  const void* const* params, const void* x, const int32_t* labels,
+                                                  float* logits, float* loss, float* const* grads, float beta, void* ws,
+                                                  size_t ws_bytes, void* stream, void* aux_stream) {
+    lamp_status st = pipe_ok(u, cut, micro_batches);
+    if (st != LAMP_OK) return st;
+    const int M = micro_batches, L = u->levels;
+    if (!params || !x || !labels || !loss || !grads) return LAMP_ERR_NULL;
+    const int np = lamp_unet_param_count(u);
+    for (int i = 0; i < np; ++i)
+        if (!params[i] || !grads[i]) return LAMP_ERR_NULL;
+    if (beta != 0.f && beta != 1.f) return LAMP_ERR_SHAPE;
+    if (stream == aux_stream) return LAMP_ERR_SHAPE;   // the two partitions run on two different streams
+    if (!aligned16(x) || !aligned16(ws)) return LAMP_ERR_ALIGN;
+    PipeLayout pl;
+    if (!pipe_layout(u, cut, M, nullptr, pl)) return LAMP_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < pl.total) return LAMP_ERR_WORKSPACE;
+    pipe_layout(u, cut, M, ws, pl);
+    Net nt{u, L, u->dtype, esize(u->dtype), nullptr, nullptr, 0};
+    const size_t x_mb = (size_t)nt.vox(1) * u->in_ch * nt.es;   // bytes of one micro-batch of x
+    if (x_mb % 16) return LAMP_ERR_ALIGN;
+    const int64_t v_mb = nt.vox(1);
+    const int toff = enc_pi(u, cut + 1);
+    hipStream_t s0 = (hipStream_t)stream, s1 = (hipStream_t)aux_stream;
+
+    // events: [0, M) forward of partition 0 done, [M, 2M) backward of partition 1 done, 2M fork, 2M+1 join
+    std::vector<hipEvent_t> ev(2 * M + 2, nullptr);
+    for (size_t i = 0; i < ev.size(); ++i)
+        if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+            return LAMP_ERR_HIP;
+        }
+    LAMP_PIPE_HIP(hipEventRecord(ev[2 * M], s0));
+    LAMP_PIPE_HIP(hipStreamWaitEvent(s1, ev[2 * M], 0));
+    auto xm = [&](int m) { return (const char*)x + (size_t)m * x_mb; };
+    auto tail_io = [&](int m, int phase, bool first_bwd) {
+        const PipeSlot& sl = pl.slot[m];
+        return TailIO{cut + 1, (const void* const*)sl.skips, (void* const*)sl.d_skips, sl.d_pooled, phase,
+                      (int64_t)M * v_mb, first_bwd ? 0.f : 1.f};
+    };
+    // forward: at clock t partition 0 runs micro-batch t and partition 1 micro-batch t-1
+    for (int t = 0; t <= M && st == LAMP_OK; ++t) {
+        if (t < M) {
+            const PipeSlot& sl = pl.slot[t];
+            st = lamp_unet_stage_fwd(u, 1, cut, params, xm(t), sl.pooled, (void* const*)sl.skips, sl.stage_ws, pl.stage_bytes,
+                                     s0);
+            LAMP_PIPE_HIP(hipEventRecord(ev[t], s0));
+        }
+        if (t >= 1 && st == LAMP_OK) {
+            const int m = t - 1;
+            const PipeSlot& sl = pl.slot[m];
+            LAMP_PIPE_HIP(hipStreamWaitEvent(s1, ev[m], 0));
+            TailIO io = tail_io(m, 1, false);
+            if (st == LAMP_OK)
+                st = unet_run(u, params + toff, sl.pooled, labels + (size_t)m * v_mb, nullptr, loss, grads + toff, beta, true,
+                              sl.tail_ws, pl.tail_bytes, s1, &io);
+        }
+    }
+    // backward, micro-batches in reverse: partition 1 first, partition 0 one clock behind it
+    for (int t = 0; t < M && st == LAMP_OK; ++t) {
+        const int m = M - 1 - t;
+        const PipeSlot& sl = pl.slot[m];
+        const float b = t == 0 ? beta : 1.f;
+        TailIO io = tail_io(m, 2, t == 0);
+        st = unet_run(u, params + toff, sl.pooled, labels + (size_t)m * v_mb,
+                      logits ? logits + (size_t)m * v_mb * u->classes : nullptr, loss, grads + toff, b, true, sl.tail_ws,
+                      pl.tail_bytes, s1, &io);
+        LAMP_PIPE_HIP(hipEventRecord(ev[M + m], s1));
+        LAMP_PIPE_HIP(hipStreamWaitEvent(s0, ev[M + m], 0));
+        if (st == LAMP_OK)
+            st = lamp_unet_stage_bwd(u, 1, cut, params, xm(m), (const void* const*)sl.skips, sl.d_pooled,
+                                     (const void* const*)sl.d_skips, grads, b, nullptr, sl.stage_ws, pl.stage_bytes, s0);
+    }
+    // join: whatever was enqueued on the second stream completes before later work on `stream`
+    if (hipEventRecord(ev[2 * M + 1], s1) != hipSuccess || hipStreamWaitEvent(s0, ev[2 * M + 1], 0) != hipSuccess)
+        if (st == LAMP_OK) st = LAMP_ERR_HIP;
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    return st;
 }
 
 // ---- sliding-window inference -------------------------------------------------------------------

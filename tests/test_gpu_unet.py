@@ -159,6 +159,132 @@ def test_stage_partition_fwd_bwd(L):
         assert cos > 0.95, f"stage grad {k}: cosine {cos:.3f}"
 
 
+def _stage_shapes(N, D, H, W, base, cut):
+    sk = [(N, D >> (l - 1), H >> (l - 1), W >> (l - 1), base << (l - 1)) for l in range(1, cut + 1)]
+    return (N, D >> cut, H >> cut, W >> cut, base << (cut - 1)), sk
+
+
+@pytest.mark.parametrize("cut", [1, 2])
+def test_tail_partition_fwd_bwd(L, cut):
+    """The net cut after encoder block `cut` (Sec. 2.2 Eq. 3): partition 0 forward, the tail forward
+    and backward, partition 0 backward.  Every result must equal the whole net's bit for bit (the
+    whole net is itself verified layer by layer against the oracle); the gradients that cross the cut
+    are compared with the oracle's, computed from the GPU's own partition-0 outputs."""
+    levels, base, K, dtype = 3, 32, 5, BF
+    N, D, H, W = 2, 16, 16, 32
+    names, dev, ora = make_net(levels, base, 1, K, False, dtype, 21)
+    rx, rl = S.streams(22, 2)
+    x = to_dev(S.ct_volume(rx, N, D, H, W), dtype)
+    lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(DEV)
+    ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype)
+    grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    loss = torch.empty((), dtype=F32, device=DEV)
+    logits = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
+
+    toff = L.lamp_unet_tail_param_offset(ud, cut + 1)
+    assert toff == 2 * cut
+    pshape, sshapes = _stage_shapes(N, D, H, W, base, cut)
+    pooled = torch.empty(pshape, dtype=dtype, device=DEV)
+    skips = [torch.empty(sh, dtype=dtype, device=DEV) for sh in sshapes]
+    ws0 = torch.empty(L.lamp_unet_stage_workspace_bytes(ud, 1, cut), dtype=torch.uint8, device=DEV)
+    L.lamp_unet_stage_fwd(ud, 1, cut, dev[:toff], x, pooled, skips, ws0)
+    # forward only
+    lt = torch.empty_like(logits)
+    L.lamp_unet_tail_fwd(ud, cut + 1, dev[toff:], pooled, skips, lt)
+    assert torch.equal(lt, logits), "tail logits differ from the whole net's"
+    # forward + backward
+    gt = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev[toff:]]
+    d_x = torch.full(pshape, float("nan"), dtype=dtype, device=DEV)
+    d_skips = [torch.full(sh, float("nan"), dtype=dtype, device=DEV) for sh in sshapes]
+    loss_t = torch.empty((), dtype=F32, device=DEV)
+    lt.zero_()
+    L.lamp_unet_tail_fwd_bwd(ud, cut + 1, dev[toff:], pooled, skips, lab, loss_t, gt, d_skips, d_x=d_x, logits=lt)
+    assert torch.equal(lt, logits) and torch.equal(loss_t, loss)
+    for k, a, b in zip(names[toff:], gt, grads[toff:]):
+        assert torch.equal(a, b), f"tail grad {k} differs from the whole net's"
+    gs = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev[:toff]]
+    L.lamp_unet_stage_bwd(ud, 1, cut, dev[:toff], x, skips, d_x, d_skips, gs, ws0)
+    for k, a, b in zip(names[:toff], gs, grads[:toff]):
+        assert torch.equal(a, b), f"partition-0 grad {k} (from the tail's cut gradients) differs from the whole net's"
+    # the cut-crossing gradients against the oracle's tail, fed with the GPU's partition-0 outputs
+    lg_ref, c1 = unet.tail_forward(ora, as64(pooled), [as64(t) for t in skips], cut + 1, levels, store=O.round_bf16)
+    check(as64(lt), lg_ref, dtype, "tail logits")
+    _, dl = O.cross_entropy(lg_ref, lab.cpu().numpy())
+    _, gp_ref, gsk_ref = unet.tail_backward(ora, c1, dl, cut + 1, levels, store=O.round_bf16)
+    for nm, a, b in [("d_x", d_x, gp_ref)] + [(f"d_skip{i + 1}", t, r) for i, (t, r) in enumerate(zip(d_skips, gsk_ref))]:
+        a, b = as64(a).ravel(), b.ravel()
+        assert np.isfinite(a).all()
+        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
+        assert cos > 0.98, f"{nm}: cosine {cos:.4f} to the storage-emulating oracle"
+    # argument errors are found on the host
+    with pytest.raises(RuntimeError):
+        L.lamp_unet_tail_fwd(ud, 1, dev, pooled, skips, lt)          # first_level 1 is the whole net
+    assert L.lamp_unet_tail_workspace_bytes(L.unet_desc(levels, 16, 1, K, N, D, H, W, dtype), cut + 1) == 0
+    assert L.lamp_unet_tail_workspace_bytes(L.unet_desc(levels, base, 1, K, N, D, H, W, F32), cut + 1) == 0
+
+
+@pytest.mark.parametrize("cut,n,M", [(1, 1, 2), (2, 2, 3), (1, 2, 1)], ids=["cut1-1x2", "cut2-2x3", "cut1-2x1"])
+def test_pipeline_two_partitions_micro_batches(L, cut, n, M):
+    """Partition 0 and the tail on two streams, M micro-batches of n samples in the pipeline order
+    (Sec. 2.1).  The result is the mini-batch's loss and gradients: compared with lamp_unet_fwd_bwd
+    on the whole mini-batch (bit for bit when M == 1: same kernels on the same shapes; to the bf16
+    bound otherwise, since tile counts, hence the split of the reductions, depend on the batch) and
+    with the oracle's micro-batch pipeline."""
+    levels, base, K, dtype = 3, 32, 4, BF
+    D, H, W = 16, 16, 16
+    N = n * M
+    names, dev, ora = make_net(levels, base, 1, K, False, dtype, 31)
+    rx, rl = S.streams(32 + cut, 2)
+    x = to_dev(S.ct_volume(rx, N, D, H, W), dtype)
+    lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(DEV)
+    full = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype)
+    g_full = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    loss_full = torch.empty((), dtype=F32, device=DEV)
+    lg_full = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
+    L.lamp_unet_fwd_bwd(full, dev, x, lab, loss_full, g_full, logits=lg_full)
+
+    mb = L.unet_desc(levels, base, 1, K, n, D, H, W, dtype)
+    aux = torch.cuda.Stream()
+    ws = torch.empty(L.lamp_unet_pipeline_workspace_bytes(mb, cut, M), dtype=torch.uint8, device=DEV)
+    runs = []
+    for rep in range(2):
+        ws.fill_(0xFF)   # NaN patterns: nothing may be read before it is written
+        g = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev]
+        loss = torch.full((), float("nan"), dtype=F32, device=DEV)
+        lg = torch.full((N, D, H, W, K), float("nan"), dtype=F32, device=DEV)
+        L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, dev, x, lab, loss, g, aux, logits=lg, ws=ws)
+        torch.cuda.current_stream().synchronize()   # the contract: the caller's stream alone
+        runs.append((loss.clone(), [t.clone() for t in g], lg.clone()))
+    loss, g, lg = runs[0]
+    assert torch.equal(loss, runs[1][0]) and torch.equal(lg, runs[1][2])
+    for a, b in zip(g, runs[1][1]):
+        assert torch.equal(a, b), "pipeline results differ from run to run"
+    if M == 1:
+        assert torch.equal(loss, loss_full) and torch.equal(lg, lg_full)
+        for k, a, b in zip(names, g, g_full):
+            assert torch.equal(a, b), f"pipeline grad {k} differs from the whole net's"
+    else:
+        check(as64(lg), as64(lg_full), dtype, "pipeline logits vs mini-batch run")
+        assert abs(loss.item() - loss_full.item()) <= 1e-3 * abs(loss_full.item())
+        for k, a, b in zip(names, g, g_full):
+            check(as64(a), as64(b), dtype, f"pipeline grad {k} vs mini-batch run")
+    loss_ref, g_ref = unet.pipeline_loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, cut, M, store=O.round_bf16)
+    assert abs(loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
+    for k, a in zip(names, g):
+        a, b = as64(a).ravel(), g_ref[k].ravel()
+        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
+        assert cos > 0.9, f"pipeline grad {k}: cosine {cos:.3f} to the oracle's pipeline"
+    # beta = 1 accumulates onto what is there
+    g2 = [t.clone() for t in g]
+    L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, dev, x, lab, loss, g2, aux, beta=1.0, ws=ws)
+    torch.cuda.current_stream().synchronize()
+    for a, b in zip(g, g2):   # fp32 sums taken in another order: bound relative to the tensor's scale
+        assert (b - 2 * a).abs().max().item() <= 1e-5 * a.abs().max().item()
+    with pytest.raises(RuntimeError):   # the two partitions need two different streams
+        L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, dev, x, lab, loss, g2, torch.cuda.current_stream(), ws=ws)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 def test_sliding_window_vs_oracle(L, dtype):
     levels, base, K, P = 2, 8 if dtype == F32 else 32, 3, 8
