@@ -41,9 +41,11 @@ def main():
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny", "unet_train_b64", "unet_train_b128",
-                             "unet_infer_whole", "unet_train_step"],
+                             "unet_infer_whole", "unet_train_step", "unet_train_pipeline"],
                     help="block (default): the headline conv block (config 2). The others time the network-level "
                          "entry points on the remaining configurations and report voxels/s.")
+    ap.add_argument("--micro-batches", type=int, default=2, help="unet_train_pipeline: micro-batches the 2 samples are split into")
+    ap.add_argument("--cut", type=int, default=2, help="unet_train_pipeline: last encoder block of partition 0")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic) so that a counter "
                          "profile of this run can scale FETCH_SIZE / WRITE_SIZE")
@@ -230,6 +232,8 @@ def net_bench(args, torch, np, S, L):
         # head-and-neck sized volume with unequal axes
         # forward + backward + RMSProp update of the fp32 masters and the bf16 working copies: one optimiser step
         "unet_train_step": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
+        # the same mini-batch as two partitions on two streams, one sample per micro-batch, in the pipeline order
+        "unet_train_pipeline": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
         "unet_train_b64": dict(levels=5, base=64, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1006),
         "unet_train_b128": dict(levels=5, base=128, in_ch=1, classes=10, dims=(1, 128, 128, 128), dtype=bf, seed=1007),
         "unet_infer_whole": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 352, 256, 288), dtype=bf, seed=1008),
@@ -266,6 +270,16 @@ def net_bench(args, torch, np, S, L):
                 L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
                 L.lamp_rmsprop_step(masters, msq, grads, params, lr=1e-3, alpha=0.99, eps=1e-8)
             what += " + RMSProp update (lr 1e-3)"
+        elif wl == "unet_train_pipeline":
+            M, cut = args.micro_batches, args.cut
+            if N % M:
+                print("bench.py: --micro-batches must divide the mini-batch of 2", file=sys.stderr)
+                sys.exit(2)
+            mb = L.unet_desc(levels, base, 1, K, N // M, D, H, W, dt)
+            aux = torch.cuda.Stream()
+            ws = torch.empty(L.lamp_unet_pipeline_workspace_bytes(mb, cut, M), dtype=torch.uint8, device=dev)
+            run = lambda: L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, params, x, lab, loss, grads, aux, ws=ws)
+            what += f" as 2 partitions (cut after encoder block {cut}) x {M} micro-batches on two streams"
         else:
             run = lambda: L.lamp_unet_fwd_bwd(ud, params, x, lab, loss, grads, ws=ws)
     elif wl == "sliding":

@@ -173,6 +173,52 @@ def test_unet_train_fullsize_sampled(L):
     assert ch.checked["conv fwd"] == 18 and ch.checked["conv dgrad"] == 17 and ch.checked["conv wgrad"] == 18
 
 
+@pytest.mark.timeout(600)
+def test_pipeline_fullsize_vs_whole_net(L):
+    """The training mini-batch (2 x 128^3, 5 levels, base 32) as bench.py's pipeline workload runs it:
+    two partitions (cut after encoder block 2) on two streams, one sample per micro-batch.
+    (a) Exact: with two micro-batches every gradient is half the sum of the two samples' own
+    whole-net gradients, accumulated in the schedule's order (halving is exact in binary floating
+    point, so the comparison is bit for bit).  (b) Against the whole-net call on the mini-batch of
+    two, the call the sampled chain test verifies: logits to the bf16 bound, gradients by direction
+    (the end-to-end gradients of two bf16 realisations drift apart through near-tie flips)."""
+    from test_gpu_unet import make_net
+    levels, base, K, cut, M = 5, 32, 10, 2, 2
+    N, Dd, H, W = 2, 128, 128, 128
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1004)
+    rx, rl = S.streams(1004, 3)[1:]
+    x = torch.from_numpy(S.ct_volume(rx, N, Dd, H, W)).to(BF).to(DEV).reshape(N, Dd, H, W, 1)
+    lab = torch.from_numpy(S.organ_labels(rl, N, Dd, H, W, K)).to(DEV)
+    mb = L.unet_desc(levels, base, 1, K, 1, Dd, H, W, BF)
+    aux = torch.cuda.Stream()
+    g = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev]
+    loss = torch.full((), float("nan"), dtype=F32, device=DEV)
+    lg = torch.empty((N, Dd, H, W, K), dtype=F32, device=DEV)
+    L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, dev, x, lab, loss, g, aux, logits=lg)
+    torch.cuda.current_stream().synchronize()
+    # (a) the samples one at a time through the whole-net entry point, last micro-batch first
+    g1 = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    l1 = [torch.empty((), dtype=F32, device=DEV) for _ in range(M)]
+    lg1 = torch.empty_like(lg)
+    for i, m in enumerate(reversed(range(M))):
+        L.lamp_unet_fwd_bwd(mb, dev, x[m:m + 1], lab[m:m + 1], l1[m], g1, logits=lg1[m:m + 1], beta=0.0 if i == 0 else 1.0)
+    assert torch.equal(lg, lg1), "pipeline logits differ from the per-sample whole-net runs"
+    assert abs(loss.item() - 0.5 * (l1[0].item() + l1[1].item())) <= 1e-6 * loss.item()
+    for k, a, b in zip(names, g, g1):
+        assert torch.equal(a, 0.5 * b), f"pipeline grad {k} is not half the sum of the per-sample gradients"
+    # (b) the mini-batch in one whole-net call
+    full = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
+    gf = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
+    lf = torch.empty((), dtype=F32, device=DEV)
+    L.lamp_unet_fwd_bwd(full, dev, x, lab, lf, gf, logits=lg1)
+    check(as64(lg[:, ::4, ::4, ::4]), as64(lg1[:, ::4, ::4, ::4]), BF, "pipeline logits vs mini-batch run")
+    assert abs(loss.item() - lf.item()) <= 1e-3 * lf.item()
+    for k, a, b in zip(names, g, gf):   # two bf16 realisations of a deep net (the kernels' tiling follows the batch)
+        a, b = as64(a).ravel(), as64(b).ravel()
+        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
+        assert cos > 0.95, f"pipeline grad {k} vs mini-batch run: cosine {cos:.4f}"
+
+
 @pytest.mark.timeout(900)
 def test_unet_infer_fullsize_sampled(L):
     """Large-input inference at its full size (1 x 256 x 256 x 160 CT-like volume, 5 levels, base 32,
