@@ -282,3 +282,52 @@ def rmsprop_step(w, v, g, lr=1e-3, alpha=0.99, eps=1e-8):
     g = np.asarray(g, dtype=np.float64)
     v2 = alpha * v + (1.0 - alpha) * g * g
     return w - lr * g / (np.sqrt(v2) + eps), v2
+
+
+# ---- squeeze-and-excitation on top of InstanceNorm + ReLU (the SEU-Net variant named in Sec. 1) -----
+# The paper names the block only through its citations; this is the published squeeze-and-excitation
+# gate written out: squeeze = per-sample, per-channel mean of the activated feature map over the
+# volume, excitation = two small fully connected layers (ReLU between them, logistic sigmoid after),
+# the feature map scaled channel-wise by the gate, and an optional residual tensor added.
+
+def se_gate(m, w1, b1, w2, b2):
+    """m [N,C] -> (e [N,C] in (0,1), h [N,Cr]):  h = max(0, W1 m + b1),  e = sigmoid(W2 h + b2)."""
+    m, w1, b1, w2, b2 = (np.asarray(t, dtype=np.float64) for t in (m, w1, b1, w2, b2))
+    h = np.maximum(m @ w1.T + b1, 0.0)
+    e = 1.0 / (1.0 + np.exp(-(h @ w2.T + b2)))
+    return e, h
+
+
+def inorm_relu_se(z, gamma, beta, w1, b1, w2, b2, residual=None, eps=1e-5):
+    """a = max(0, gamma zhat + beta) (O4);  m = mean_v a;  e = gate(m);  y = a * e (+ residual).
+    Returns (y, dict(a, m, e, h, stats))."""
+    a, stats = inorm_relu(z, gamma, beta, eps)
+    N, C = a.shape[0], a.shape[-1]
+    m = a.reshape(N, -1, C).mean(axis=1)
+    e, h = se_gate(m, w1, b1, w2, b2)
+    y = a * e.reshape((N,) + (1,) * (a.ndim - 2) + (C,))
+    if residual is not None:
+        y = y + np.asarray(residual, dtype=np.float64)
+    return y, dict(a=a, m=m, e=e, h=h, stats=stats)
+
+
+def inorm_relu_se_bwd(dy, z, gamma, beta, w1, b1, w2, b2, eps=1e-5):
+    """Adjoint of inorm_relu_se for upstream dy (the residual's gradient is dy itself).
+    Returns (dz, dgamma, dbeta, dw1, db1, dw2, db2)."""
+    dy = np.asarray(dy, dtype=np.float64)
+    w1 = np.asarray(w1, dtype=np.float64)
+    w2 = np.asarray(w2, dtype=np.float64)
+    _, c = inorm_relu_se(z, gamma, beta, w1, b1, w2, b2, None, eps)
+    a, m, e, h = c["a"], c["m"], c["e"], c["h"]
+    N, C = a.shape[0], a.shape[-1]
+    V = a.size // (N * C)
+    bshape = (N,) + (1,) * (a.ndim - 2) + (C,)
+    de = (dy * a).reshape(N, V, C).sum(axis=1)          # gradient of the gate
+    dp2 = de * e * (1.0 - e)                            # through the sigmoid
+    dw2, db2 = dp2.T @ h, dp2.sum(axis=0)
+    dp1 = (dp2 @ w2) * (h > 0)                          # through the hidden ReLU
+    dw1, db1 = dp1.T @ m, dp1.sum(axis=0)
+    dm = dp1 @ w1                                       # gradient of the squeezed means
+    da = dy * e.reshape(bshape) + dm.reshape(bshape) / V
+    dz, dgamma, dbeta = inorm_relu_bwd(da, z, gamma, beta, eps)
+    return dz, dgamma, dbeta, dw1, db1, dw2, db2

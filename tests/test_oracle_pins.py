@@ -421,3 +421,84 @@ def test_rmsprop_matches_an_independent_implementation():
         w, v = O.rmsprop_step(w, v, np.full(3, c), lr=0.1, alpha=a, eps=0.0)
         np.testing.assert_allclose(v, (1 - a ** t) * c * c, rtol=1e-13)
         np.testing.assert_allclose(w_prev - w, 0.1 / np.sqrt(1 - a ** t), rtol=1e-13)
+
+
+# ------------------------------------------------- squeeze-and-excitation on InstanceNorm + ReLU
+
+def _se_case(seed, N=2, shape=(3, 4, 5), C=6, Cr=3):
+    r = rng(seed)
+    z = r.standard_normal((N,) + shape + (C,))
+    gamma, beta = r.uniform(0.5, 1.5, C), r.uniform(-0.5, 0.5, C)
+    w1, b1 = r.standard_normal((Cr, C)), r.uniform(0.1, 0.5, Cr)   # positive biases keep the hidden units off their kink
+    w2, b2 = r.standard_normal((C, Cr)), r.standard_normal(C) * 0.3
+    return r, z, gamma, beta, w1, b1, w2, b2
+
+
+def test_se_gate_and_squeeze_by_explicit_loops():
+    r, z, gamma, beta, w1, b1, w2, b2 = _se_case(61)
+    res = r.standard_normal(z.shape)
+    y, c = O.inorm_relu_se(z, gamma, beta, w1, b1, w2, b2, residual=res)
+    a, _ = O.inorm_relu(z, gamma, beta)
+    N, C, Cr = z.shape[0], z.shape[-1], w1.shape[0]
+    V = z.size // (N * C)
+    for n in range(N):
+        m = [sum(a[n].reshape(V, C)[v, ch] for v in range(V)) / V for ch in range(C)]
+        h = [max(0.0, sum(w1[j, ch] * m[ch] for ch in range(C)) + b1[j]) for j in range(Cr)]
+        e = [1.0 / (1.0 + np.exp(-(sum(w2[ch, j] * h[j] for j in range(Cr)) + b2[ch]))) for ch in range(C)]
+        assert all(0.0 < v < 1.0 for v in e)
+        np.testing.assert_allclose(c["m"][n], m, rtol=1e-12)
+        np.testing.assert_allclose(c["e"][n], e, rtol=1e-12)
+        for ch in range(C):
+            np.testing.assert_allclose(y[n, ..., ch], a[n, ..., ch] * e[ch] + res[n, ..., ch], rtol=1e-12, atol=1e-15)
+
+
+def test_se_special_cases_reduce_to_plain_inorm_relu():
+    r, z, gamma, beta, w1, b1, w2, b2 = _se_case(62)
+    a, _ = O.inorm_relu(z, gamma, beta)
+    # second layer switched off: the gate is sigmoid(0) = 1/2 everywhere
+    y, _ = O.inorm_relu_se(z, gamma, beta, w1, b1, np.zeros_like(w2), np.zeros_like(b2))
+    np.testing.assert_allclose(y, 0.5 * a, rtol=1e-14)
+    # saturated gate: the block is InstanceNorm + ReLU itself, forward and backward
+    big = np.full_like(b2, 40.0)
+    y, _ = O.inorm_relu_se(z, gamma, beta, w1, b1, w2, big)
+    np.testing.assert_allclose(y, a, rtol=1e-12)
+    dy = r.standard_normal(z.shape)
+    dz, dg, db, dw1, db1, dw2, db2 = O.inorm_relu_se_bwd(dy, z, gamma, beta, w1, b1, w2, big)
+    dz0, dg0, db0 = O.inorm_relu_bwd(dy, z, gamma, beta)
+    np.testing.assert_allclose(dz, dz0, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(dg, dg0, rtol=1e-9)
+    assert np.abs(dw1).max() < 1e-12 and np.abs(dw2).max() < 1e-12   # a saturated gate passes no gradient
+
+
+def test_se_backward_by_finite_differences():
+    r, z, gamma, beta, w1, b1, w2, b2 = _se_case(63)
+    res = r.standard_normal(z.shape)
+    R = r.standard_normal(z.shape)          # L = <y, R>: upstream gradient dy = R
+    grads = O.inorm_relu_se_bwd(R, z, gamma, beta, w1, b1, w2, b2)
+    params = [z, gamma, beta, w1, b1, w2, b2]
+    names = ["z", "gamma", "beta", "w1", "b1", "w2", "b2"]
+
+    def loss():
+        return float(np.sum(O.inorm_relu_se(z, gamma, beta, w1, b1, w2, b2, residual=res)[0] * R))
+
+    hh = 1e-6
+    for name, p, g in zip(names, params, grads):
+        flat, gflat = p.reshape(-1), g.reshape(-1)
+        for idx in r.choice(flat.size, size=min(6, flat.size), replace=False):
+            old = flat[idx]
+            flat[idx] = old + hh
+            lp = loss()
+            flat[idx] = old - hh
+            lm = loss()
+            flat[idx] = old
+            fd = (lp - lm) / (2 * hh)
+            assert abs(fd - gflat[idx]) <= 1e-5 * max(1.0, abs(fd)), (name, idx, fd, gflat[idx])
+    # the residual enters by plain addition: its gradient is the upstream gradient
+    flat = res.reshape(-1)
+    old = flat[7]
+    flat[7] = old + hh
+    lp = loss()
+    flat[7] = old - hh
+    lm = loss()
+    flat[7] = old
+    assert abs((lp - lm) / (2 * hh) - R.reshape(-1)[7]) < 1e-6
