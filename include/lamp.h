@@ -171,6 +171,38 @@ lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc *dyd, const void *dy,
                                 void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * InstanceNorm + ReLU followed by a squeeze-and-excitation gate (the SEU-Net variant that Sec. 1
+ * names through its citations; the gate is the cited squeeze-and-excitation block written out):
+ *   a = max(0, gamma*zh + beta)                       (not stored)
+ *   m[n,c] = mean_v a                                 squeeze
+ *   h = max(0, W1 m + b1),  e = sigmoid(W2 h + b2)    excitation; W1 fp32 [cr][C], W2 fp32 [C][cr],
+ *                                                     b1 [cr], b2 [C] nullable (= 0)
+ *   y = a * e[n,c] (+ residual)                       residual nullable, same shape/dtype as z
+ *   stats     : fp32 [N][C][2] (mean, rstd), an INPUT (from lamp_conv3d_fwd or lamp_inorm_relu).
+ *   gate_save : fp32 [N][2*C + cr] output = (m, e, h) per sample; the backward reads it.
+ * Backward, for upstream dy (the residual's gradient is dy itself, nothing to compute):
+ *   de = sum_v dy*a;  through sigmoid, W2, the hidden ReLU and W1 to dm[n,c];
+ *   g = [u>0] * (dy*e + dm/V);  dz = gamma*rstd*( g - mean_v(g) - zh*mean_v(g*zh) );
+ *   dgamma, dbeta as in lamp_inorm_relu_bwd with this g; dw1, db1, dw2, db2 fp32, all nullable,
+ *   all accumulated with beta_acc in {0,1}.  dz may alias dy.
+ * 1 <= cr <= 1024, C <= 4096.  One workspace size serves both calls. */
+size_t lamp_inorm_relu_se_workspace_bytes(const lamp_tensor_desc *zd, int cr);
+lamp_status lamp_inorm_relu_se(const lamp_tensor_desc *zd, const void *z, const float *stats,
+                               const float *gamma, const float *beta,
+                               int cr, const float *w1, const float *b1, const float *w2, const float *b2,
+                               const lamp_tensor_desc *rd, const void *residual,
+                               const lamp_tensor_desc *yd, void *y, float *gate_save,
+                               void *ws, size_t ws_bytes, void *stream);
+lamp_status lamp_inorm_relu_se_bwd(const lamp_tensor_desc *dyd, const void *dy,
+                                   const lamp_tensor_desc *zd, const void *z, const float *stats,
+                                   const float *gamma, const float *beta,
+                                   int cr, const float *w1, const float *w2, const float *gate_save,
+                                   const lamp_tensor_desc *dzd, void *dz,
+                                   float *dgamma, float *dbeta,
+                                   float *dw1, float *db1, float *dw2, float *db2, float beta_acc,
+                                   void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * 2x2x2 max pooling, stride 2 (between encoder blocks).  d,h,w of x must be even.
  *   y[n,d,h,w,c] = max_{i,j,k in {0,1}} X[n,2d+i,2h+j,2w+k,c]
  * Backward: dx = dy at the arg-max (first in (i,j,k) raster order under strict '>'), 0 elsewhere,

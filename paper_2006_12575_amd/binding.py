@@ -70,6 +70,10 @@ _SIGS = {
     "lamp_convtr3d": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP, c_size_t, _VP]),
     "lamp_convtr3d_bwd_workspace_bytes": (c_size_t, [_PD, _PD]),
     "lamp_convtr3d_bwd": (c_int, [_PD, _VP, _PN, _VP, _PD, _VP, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
+    "lamp_inorm_relu_se_workspace_bytes": (c_size_t, [_PD, c_int]),
+    "lamp_inorm_relu_se": (c_int, [_PD, _VP, _VP, _VP, _VP, c_int, _VP, _VP, _VP, _VP, _PD, _VP, _PD, _VP, _VP, _VP, c_size_t, _VP]),
+    "lamp_inorm_relu_se_bwd": (c_int, [_PD, _VP, _PD, _VP, _VP, _VP, _VP, c_int, _VP, _VP, _VP, _PD, _VP, _VP, _VP, _VP, _VP, _VP,
+                                       _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_head_ce_workspace_bytes": (c_size_t, [_PD, c_int]),
     "lamp_head_fwd": (c_int, [_PD, _VP, _PN, _VP, _VP, c_int, _VP, _VP]),
     "lamp_head_ce": (c_int, [_PD, _VP, _PN, _VP, _VP, c_int, _VP, _VP, _VP, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
@@ -247,6 +251,32 @@ def lamp_inorm_relu_bwd(dy, z, stats, dz, gamma=None, beta=None, dgamma=None, db
     _check(lib().lamp_inorm_relu_bwd(ctypes.byref(dyd), _ptr(dy), ctypes.byref(zd), _ptr(z), _ptr(stats), _ptr(gamma),
                                      _ptr(beta), ctypes.byref(dzd), _ptr(dz), _ptr(dgamma), _ptr(dbeta), beta_acc,
                                      _ptr(ws), ws.numel(), _stream()), "lamp_inorm_relu_bwd")
+    return dz
+
+
+def lamp_inorm_relu_se(z, stats, w1, w2, y, gate_save, b1=None, b2=None, gamma=None, beta=None, residual=None, ws=None):
+    """y = max(0, gamma*zhat + beta) * e[n,c] (+ residual), e the squeeze-and-excitation gate; w1 [cr, C], w2 [C, cr]
+    fp32; gate_save fp32 [N, 2C + cr] receives (means, gate, hidden) for the backward."""
+    zd, yd = desc(z), desc(y)
+    rd = desc(residual) if residual is not None else None
+    cr = int(w1.shape[0])
+    ws = ws if ws is not None else _ws(lib().lamp_inorm_relu_se_workspace_bytes(ctypes.byref(zd), cr), z.device)
+    _check(lib().lamp_inorm_relu_se(ctypes.byref(zd), _ptr(z), _ptr(stats), _ptr(gamma), _ptr(beta), cr, _ptr(w1), _ptr(b1),
+                                    _ptr(w2), _ptr(b2), ctypes.byref(rd) if rd is not None else None, _ptr(residual),
+                                    ctypes.byref(yd), _ptr(y), _ptr(gate_save), _ptr(ws), ws.numel(), _stream()),
+           "lamp_inorm_relu_se")
+    return y
+
+
+def lamp_inorm_relu_se_bwd(dy, z, stats, w1, w2, gate_save, dz, gamma=None, beta=None, dgamma=None, dbeta=None, dw1=None,
+                           db1=None, dw2=None, db2=None, beta_acc=0.0, ws=None):
+    dyd, zd, dzd = desc(dy), desc(z), desc(dz)
+    cr = int(w1.shape[0])
+    ws = ws if ws is not None else _ws(lib().lamp_inorm_relu_se_workspace_bytes(ctypes.byref(zd), cr), z.device)
+    _check(lib().lamp_inorm_relu_se_bwd(ctypes.byref(dyd), _ptr(dy), ctypes.byref(zd), _ptr(z), _ptr(stats), _ptr(gamma),
+                                        _ptr(beta), cr, _ptr(w1), _ptr(w2), _ptr(gate_save), ctypes.byref(dzd), _ptr(dz),
+                                        _ptr(dgamma), _ptr(dbeta), _ptr(dw1), _ptr(db1), _ptr(dw2), _ptr(db2), beta_acc,
+                                        _ptr(ws), ws.numel(), _stream()), "lamp_inorm_relu_se_bwd")
     return dz
 
 

@@ -259,6 +259,78 @@ def test_inorm_relu_fwd_bwd(L, dtype, shape, affine):
     assert torch.equal(dz2, dz)
 
 
+SE_CASES = [((2, 3, 5, 7, 5), 2), ((2, 16, 20, 24, 64), 16), ((1, 17, 9, 33, 32), 8), ((1, 4, 4, 4, 512), 32), ((3, 6, 6, 6, 24), 6)]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", SE_CASES, ids=lambda c: "x".join(map(str, c[0])) + f"-r{c[1]}")
+@pytest.mark.parametrize("variant", ["plain", "affine+residual"])
+def test_inorm_relu_se_fwd_bwd(L, dtype, case, variant):
+    """InstanceNorm + ReLU + squeeze-and-excitation gate (+ residual), forward and backward, against
+    the oracle on the GPU's own z (the statistics come from the library, as a conv epilogue would
+    hand them over)."""
+    shape, Cr = case
+    N, D, H, W, C = shape
+    V = D * H * W
+    full = variant != "plain"
+    r = rng(900 + sum(shape) + Cr)
+    z = to_dev(S.normal(r, shape, 1.7) + 0.4, dtype)
+    dy = to_dev(S.normal(r, shape), dtype)
+    res = to_dev(S.normal(r, shape), dtype) if full else None
+    g = to_dev(r.uniform(0.5, 1.5, C), F32) if full else None
+    b = to_dev(r.uniform(-0.5, 0.5, C), F32) if full else None
+    w1 = to_dev(r.standard_normal((Cr, C)) / np.sqrt(C), F32)
+    b1 = to_dev(r.uniform(0.2, 0.6, Cr), F32)
+    w2 = to_dev(r.standard_normal((C, Cr)) / np.sqrt(Cr), F32)
+    b2 = to_dev(r.standard_normal(C) * 0.3, F32) if full else None
+    stats = torch.empty((N, C, 2), dtype=F32, device=DEV)
+    L.lamp_inorm_relu(z, torch.empty_like(z), stats, gamma=g, beta=b)
+    y = torch.empty_like(z)
+    save = torch.full((N, 2 * C + Cr), float("nan"), dtype=F32, device=DEV)
+    L.lamp_inorm_relu_se(z, stats, w1, w2, y, save, b1=b1, b2=b2, gamma=g, beta=b, residual=res)
+    g64, b64 = (as64(g), as64(b)) if full else (None, None)
+    b2_64 = as64(b2) if full else np.zeros(C)
+    y_ref, c = O.inorm_relu_se(as64(z), g64, b64, as64(w1), as64(b1), as64(w2), b2_64, residual=as64(res) if full else None)
+    check(as64(y), y_ref, dtype, "inorm+relu+se")
+    sv = as64(save)
+    np.testing.assert_allclose(sv[:, :C], c["m"], rtol=2e-4, atol=1e-6)
+    np.testing.assert_allclose(sv[:, C:2 * C], c["e"], rtol=2e-4)
+    np.testing.assert_allclose(sv[:, 2 * C:], c["h"], rtol=2e-4, atol=1e-6)
+    assert np.abs(c["m"] @ as64(w1).T + as64(b1)).min() > 1e-3, "a hidden unit sits on its kink: pick another seed"
+    # backward
+    u_ref, _ = O.inorm_relu(as64(z), g64, b64, relu=False)
+    near = np.abs(u_ref) <= 1e-3
+    dz = torch.empty_like(z)
+    outs = dict(dw1=torch.full((Cr, C), float("nan"), dtype=F32, device=DEV), db1=torch.empty(Cr, dtype=F32, device=DEV),
+                dw2=torch.full((C, Cr), float("nan"), dtype=F32, device=DEV), db2=torch.empty(C, dtype=F32, device=DEV))
+    if full:
+        outs.update(dgamma=torch.empty(C, dtype=F32, device=DEV), dbeta=torch.empty(C, dtype=F32, device=DEV))
+    L.lamp_inorm_relu_se_bwd(dy, z, stats, w1, w2, save, dz, gamma=g, beta=b, **outs)
+    ref = O.inorm_relu_se_bwd(as64(dy), as64(z), g64, b64, as64(w1), as64(b1), as64(w2), b2_64)
+    dz_ref, dg_ref, dbt_ref, dw1_ref, db1_ref, dw2_ref, db2_ref = ref
+    check(as64(dz), dz_ref, dtype, "se bwd dz", ignore=near)
+    assert near.mean() < 0.01
+    for name, rf in [("dw1", dw1_ref), ("db1", db1_ref), ("dw2", dw2_ref), ("db2", db2_ref)]:
+        # fp32 sums over the volume; masks at the kink carry a ~ 0, so they move these sums by nothing
+        check(as64(outs[name]), rf, F32, f"se bwd {name}", tol=2e-4 if dtype == F32 else 2e-3)
+    if full:
+        slack = (np.abs(as64(dy)) * near).reshape(-1, C).sum(0) + 1e-3 * np.sqrt(N * V) * (dtype == BF)
+        assert np.all(np.abs(as64(outs["dbeta"]) - dbt_ref) <= 1e-4 * np.abs(dbt_ref).max() + slack)
+        assert np.all(np.abs(as64(outs["dgamma"]) - dg_ref) <= 1e-4 * np.abs(dg_ref).max() + 3 * slack)
+    # in place, run-to-run, accumulation
+    dz2 = dy.clone()
+    acc = {k: v.clone() for k, v in outs.items()}
+    L.lamp_inorm_relu_se_bwd(dz2, z, stats, w1, w2, save, dz2, gamma=g, beta=b, beta_acc=1.0, **acc)
+    assert torch.equal(dz2, dz)
+    for k in outs:
+        assert torch.equal(acc[k], 2 * outs[k]), k
+    y2 = torch.empty_like(y)
+    L.lamp_inorm_relu_se(z, stats, w1, w2, y2, save, b1=b1, b2=b2, gamma=g, beta=b, residual=res)
+    assert torch.equal(y2, y)
+    with pytest.raises(RuntimeError):
+        L.lamp_inorm_relu_se(z, stats, torch.empty((0, C), dtype=F32, device=DEV), w2, y2, save)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(2, 4, 6, 10, 5), (1, 8, 8, 8, 32), (2, 6, 10, 14, 64), (1, 2, 2, 2, 1)],
                          ids=lambda s: "x".join(map(str, s)))
