@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny", "unet_train_b64", "unet_train_b128",
-                             "unet_infer_whole", "unet_train_step", "unet_train_pipeline"],
+                             "unet_infer_whole", "unet_train_step", "unet_train_pipeline", "se_block"],
                     help="block (default): the headline conv block (config 2). The others time the network-level "
                          "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--micro-batches", type=int, default=2, help="unet_train_pipeline: micro-batches the 2 samples are split into")
@@ -218,10 +218,60 @@ def unet_flops(levels, base, in_ch, classes, n, d, h, w):
     return fl
 
 
+def se_bench(args, torch, np, S, L):
+    """InstanceNorm + ReLU + squeeze-and-excitation gate + residual, forward and backward, on the headline
+    tensor (1 x size^3 x C, bf16).  Bandwidth-bound: the line carries an HBM roofline object."""
+    dev, bf, f32 = "cuda:0", torch.bfloat16, torch.float32
+    D, C = args.size, args.channels
+    Cr = max(1, C // 16)
+    gen = torch.Generator(dev).manual_seed(1009)
+    shape = (1, D, D, D, C)
+    z = (torch.randn(shape, device=dev, generator=gen) * 1.7 + 0.4).to(bf)
+    dy = torch.randn(shape, device=dev, generator=gen).to(bf)
+    res = torch.randn(shape, device=dev, generator=gen).to(bf)
+    w1 = torch.randn((Cr, C), device=dev, generator=gen) / C ** 0.5
+    b1 = torch.full((Cr,), 0.3, device=dev)
+    w2 = torch.randn((C, Cr), device=dev, generator=gen) / Cr ** 0.5
+    b2 = torch.zeros(C, device=dev)
+    stats = torch.empty((1, C, 2), dtype=f32, device=dev)
+    y, dz = torch.empty_like(z), torch.empty_like(z)
+    L.lamp_inorm_relu(z, y, stats)
+    save = torch.empty((1, 4 * C + Cr), dtype=f32, device=dev)
+    g = dict(dw1=torch.empty_like(w1), db1=torch.empty_like(b1), dw2=torch.empty_like(w2), db2=torch.empty_like(b2))
+    import ctypes
+    ws = torch.empty(int(L.lib().lamp_inorm_relu_se_workspace_bytes(ctypes.byref(L.desc(z)), Cr)), dtype=torch.uint8, device=dev)
+
+    def run():
+        L.lamp_inorm_relu_se(z, stats, w1, w2, y, save, b1=b1, b2=b2, residual=res, ws=ws)
+        L.lamp_inorm_relu_se_bwd(dy, z, stats, w1, w2, save, dz, ws=ws, **g)
+    steps, warm = max(1, args.steps), max(1, args.warmup)
+    for _ in range(warm):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dtm = (time.perf_counter() - t0) / steps
+    tb = z.numel() * 2
+    alg = 9 * tb   # forward: z twice, residual, y; backward: dy and z twice, dz
+    V = D ** 3
+    print(json.dumps({
+        "metric": "Conv3d fwd+bwd TFLOP/s (% MFMA peak); whole-U-Net voxels/sec at 1 GPU", "value": V / dtm, "unit": "voxels/s",
+        "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": dtm * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"InstanceNorm+ReLU+squeeze-and-excitation (ratio 16)+residual, forward+backward, 1x{D}^3x{C}",
+                   "voxels": V, "algorithmic_bytes_per_step": alg},
+        "roofline": {"bound": "hbm", "achieved": alg / dtm / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": alg / dtm / 1e9 / PEAK_HBM_GBS, "traffic": None}}))
+
+
 def net_bench(args, torch, np, S, L):
     dev = "cuda:0"
     bf, f32 = torch.bfloat16, torch.float32
     wl = args.workload
+    if wl == "se_block":
+        return se_bench(args, torch, np, S, L)
     cfg = {
         "tiny": dict(levels=3, base=8, in_ch=1, classes=5, dims=(1, 32, 32, 32), dtype=f32, seed=1001),
         "stage": dict(levels=3, base=64, in_ch=1, classes=10, dims=(1, 192, 192, 192), dtype=bf, seed=1003),

@@ -179,7 +179,8 @@ lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc *dyd, const void *dy,
  *                                                     b1 [cr], b2 [C] nullable (= 0)
  *   y = a * e[n,c] (+ residual)                       residual nullable, same shape/dtype as z
  *   stats     : fp32 [N][C][2] (mean, rstd), an INPUT (from lamp_conv3d_fwd or lamp_inorm_relu).
- *   gate_save : fp32 [N][2*C + cr] output = (m, e, h) per sample; the backward reads it.
+ *   gate_save : fp32 [N][4*C + cr] output = (m [C], e [C], h [cr], sum_v [u>0] [C], sum_v [u>0]*zh [C])
+ *               per sample; the backward reads it.
  * Backward, for upstream dy (the residual's gradient is dy itself, nothing to compute):
  *   de = sum_v dy*a;  through sigmoid, W2, the hidden ReLU and W1 to dm[n,c];
  *   g = [u>0] * (dy*e + dm/V);  dz = gamma*rstd*( g - mean_v(g) - zh*mean_v(g*zh) );

@@ -256,7 +256,7 @@ def lamp_inorm_relu_bwd(dy, z, stats, dz, gamma=None, beta=None, dgamma=None, db
 
 def lamp_inorm_relu_se(z, stats, w1, w2, y, gate_save, b1=None, b2=None, gamma=None, beta=None, residual=None, ws=None):
     """y = max(0, gamma*zhat + beta) * e[n,c] (+ residual), e the squeeze-and-excitation gate; w1 [cr, C], w2 [C, cr]
-    fp32; gate_save fp32 [N, 2C + cr] receives (means, gate, hidden) for the backward."""
+    fp32; gate_save fp32 [N, 4C + cr] receives (means, gate, hidden, two mask sums) for the backward."""
     zd, yd = desc(z), desc(y)
     rd = desc(residual) if residual is not None else None
     cr = int(w1.shape[0])

@@ -5,24 +5,25 @@
 //   h = max(0, W1 m + b1), e = sigmoid(W2 h + b2)   excitation, W1 [Cr,C], W2 [C,Cr], fp32
 //   y = a * e[n,c] (+ residual)
 // Everything here is bandwidth-bound: forward = one read of z for the squeeze, one read of z (and of the
-// residual) + one write of y for the scale; backward = one read of (dy, z) for five per-(n,c) sums from
-// which both the gate's gradient and the two InstanceNorm-backward sums follow, one read of (dy, z) + one
-// write of dz for the apply.  All reductions are two-stage in a fixed order (fp32 partials per row
-// chunk, fp64 across chunks).
+// residual) + one write of y for the scale; backward = one read of (dy, z) for three per-(n,c) sums from
+// which, with two sums the forward keeps, both the gate's gradient and the two InstanceNorm-backward
+// sums follow, then one read of (dy, z) + one write of dz for the apply.  All reductions are two-stage
+// in a fixed order (fp32 partials per row chunk, fp64 across chunks).
 #include "internal.h"
 #include "vec.h"
 
 namespace lamp {
 
-// MODE 0: 1 sum per (n,c): sum_v a.
-// MODE 1: 5 sums: sum dy*a, sum dy*mask, sum dy*mask*zhat, sum mask, sum mask*zhat.
-// partial[((n*chunks + chunk)*C + c)*K + k]
+// Three sums per (n,c) over a chunk of rows (mask = [u > 0]):
+// MODE 0 (forward):  sum a, sum mask, sum mask*zhat        (the last two are kept for the backward)
+// MODE 1 (backward): sum dy*a, sum dy*mask, sum dy*mask*zhat
+// partial[((n*chunks + chunk)*C + c)*3 + k]
 template <typename T, int VEC, int MODE>
 __global__ __launch_bounds__(256) void se_partial_kernel(const T* __restrict__ dy, int ldg, const T* __restrict__ z, int ldz,
                                                          int64_t V, int C, int cthreads, int rl, int rows_per_chunk,
                                                          const float* __restrict__ stats, const float* __restrict__ gamma,
                                                          const float* __restrict__ beta, float* __restrict__ partial) {
-    constexpr int K = MODE == 0 ? 1 : 5;
+    constexpr int K = 3;
     __shared__ float red[K][256 * VEC];
     const int tid = threadIdx.x;
     const int cl = tid % cthreads, r0 = tid / cthreads;
@@ -52,16 +53,16 @@ __global__ __launch_bounds__(256) void se_partial_kernel(const T* __restrict__ d
             for (int i = 0; i < VEC; ++i) {
                 const float u = norm_u(v[i], a[i], b[i]);
                 const bool on = u > 0.f;
+                const float zh = (v[i] - mean[i]) * rstd[i];
                 if (MODE == 0) {
                     s[0][i] += on ? u : 0.f;
+                    s[1][i] += on ? 1.f : 0.f;
+                    s[2][i] += on ? zh : 0.f;
                 } else {
                     const float gg = on ? g[i] : 0.f;
-                    const float zh = (v[i] - mean[i]) * rstd[i];
                     s[0][i] = fmaf(gg, u, s[0][i]);
-                    s[1 % K][i] += gg;
-                    s[2 % K][i] = fmaf(gg, zh, s[2 % K][i]);
-                    s[3 % K][i] += on ? 1.f : 0.f;
-                    s[4 % K][i] += on ? zh : 0.f;
+                    s[1][i] += gg;
+                    s[2][i] = fmaf(gg, zh, s[2][i]);
                 }
             }
         };
@@ -126,8 +127,9 @@ __global__ __launch_bounds__(256) void se_finalize_kernel(const float* __restric
         for (int k = 0; k < K; ++k) sums[((size_t)n * C + c) * K + k] = (float)(sh[0][k] + sh[1][k] + sh[2][k] + sh[3][k]);
 }
 
-// One workgroup per sample.  save[n] = { m[C], e[C], h[Cr] }.
-__global__ __launch_bounds__(256) void se_gate_kernel(const float* __restrict__ asum, float invV, int C, int Cr,
+// One workgroup per sample.  save[n] = { m[C], e[C], h[Cr], sum mask [C], sum mask*zhat [C] }; a3[n][c][3] as
+// written by the MODE 0 sums.
+__global__ __launch_bounds__(256) void se_gate_kernel(const float* __restrict__ a3, float invV, int C, int Cr,
                                                       const float* __restrict__ w1, const float* __restrict__ b1,
                                                       const float* __restrict__ w2, const float* __restrict__ b2,
                                                       float* __restrict__ save) {
@@ -135,11 +137,14 @@ __global__ __launch_bounds__(256) void se_gate_kernel(const float* __restrict__ 
     float* m = sm;
     float* h = sm + C;
     const int n = blockIdx.x, tid = threadIdx.x;
-    float* sv = save + (size_t)n * (2 * C + Cr);
+    float* sv = save + (size_t)n * (4 * C + Cr);
     for (int c = tid; c < C; c += 256) {
-        const float v = asum[(size_t)n * C + c] * invV;
+        const float* q = a3 + ((size_t)n * C + c) * 3;
+        const float v = q[0] * invV;
         m[c] = v;
         sv[c] = v;
+        sv[2 * C + Cr + c] = q[1];
+        sv[3 * C + Cr + c] = q[2];
     }
     __syncthreads();
     for (int j = tid; j < Cr; j += 256) {
@@ -173,7 +178,7 @@ __global__ __launch_bounds__(256) void se_apply_kernel(const T* __restrict__ z, 
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         norm_coeffs(nm, n, cv * VEC + i, a[i], b[i]);
-        e[i] = save[(size_t)n * (2 * C + Cr) + C + cv * VEC + i];
+        e[i] = save[(size_t)n * (4 * C + Cr) + C + cv * VEC + i];
     }
     const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
     const T* rb = RES ? res + ((int64_t)n * V) * ldr + (int64_t)cv * VEC : nullptr;
@@ -192,10 +197,10 @@ __global__ __launch_bounds__(256) void se_apply_kernel(const T* __restrict__ z, 
     }
 }
 
-// Backward of the gate, one workgroup per sample.  s5[n][c][5] as written by the MODE 1 sums.
+// Backward of the gate, one workgroup per sample.  s3[n][c][3] as written by the MODE 1 sums.
 // Writes dp2[n][C], dp1[n][Cr], dmv[n][C] = dm/V and the InstanceNorm-backward sums
 // sums2[n][c] = (sum_v g*mask, sum_v g*mask*zhat) for g = dy*e + dm/V.
-__global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restrict__ s5, float invV, int C, int Cr,
+__global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restrict__ s3, float invV, int C, int Cr,
                                                           const float* __restrict__ w1, const float* __restrict__ w2,
                                                           const float* __restrict__ save, float* __restrict__ dp2,
                                                           float* __restrict__ dp1, float* __restrict__ dmv,
@@ -204,10 +209,10 @@ __global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restric
     float* p2 = sm;
     float* p1 = sm + C;
     const int n = blockIdx.x, tid = threadIdx.x;
-    const float* sv = save + (size_t)n * (2 * C + Cr);
+    const float* sv = save + (size_t)n * (4 * C + Cr);
     for (int c = tid; c < C; c += 256) {
         const float e = sv[C + c];
-        const float t = s5[((size_t)n * C + c) * 5] * e * (1.0f - e);
+        const float t = s3[((size_t)n * C + c) * 3] * e * (1.0f - e);
         p2[c] = t;
         dp2[(size_t)n * C + c] = t;
     }
@@ -225,10 +230,10 @@ __global__ __launch_bounds__(256) void se_gate_bwd_kernel(const float* __restric
         for (int j = 0; j < Cr; ++j) dm = fmaf(p1[j], w1[(size_t)j * C + c], dm);
         dm *= invV;
         const float e = sv[C + c];
-        const float* q = s5 + ((size_t)n * C + c) * 5;
+        const float* q = s3 + ((size_t)n * C + c) * 3;
         dmv[(size_t)n * C + c] = dm;
-        sums2[((size_t)n * C + c) * 2 + 0] = fmaf(e, q[1], dm * q[3]);
-        sums2[((size_t)n * C + c) * 2 + 1] = fmaf(e, q[2], dm * q[4]);
+        sums2[((size_t)n * C + c) * 2 + 0] = fmaf(e, q[1], dm * sv[2 * C + Cr + c]);
+        sums2[((size_t)n * C + c) * 2 + 1] = fmaf(e, q[2], dm * sv[3 * C + Cr + c]);
     }
 }
 
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(256) void se_param_grad_kernel(const float* __restr
                                                             float* __restrict__ dw1, float* __restrict__ db1,
                                                             float* __restrict__ dw2, float* __restrict__ db2, float acc) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
-    const int S = 2 * C + Cr;
+    const int S = 4 * C + Cr;
     if (idx < C * Cr) {
         const int c = idx / Cr, j = idx % Cr;
         float t2 = 0.f, t1 = 0.f;
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(256) void se_bwd_apply_kernel(const T* __restrict__
         rstd[i] = stats[nc * 2 + 1];
         c1[i] = sums2[nc * 2] * invV;
         c2[i] = sums2[nc * 2 + 1] * invV;
-        e[i] = save[(size_t)n * (2 * C + Cr) + C + cv * VEC + i];
+        e[i] = save[(size_t)n * (4 * C + Cr) + C + cv * VEC + i];
         dm[i] = dmv[nc];
     }
     const T* zb = z + ((int64_t)n * V) * ldz + (int64_t)cv * VEC;
@@ -339,7 +344,7 @@ extern "C" size_t lamp_inorm_relu_se_workspace_bytes(const lamp_tensor_desc* zd,
     if (!zd || se_check(zd, cr) != LAMP_OK) return 0;
     const int64_t V = (int64_t)zd->d * zd->h * zd->w;
     const size_t nc = (size_t)zd->n * zd->c;
-    return align_up(nc * stats_chunks(V) * 5 * sizeof(float)) + align_up(nc * 5 * sizeof(float)) +
+    return align_up(nc * stats_chunks(V) * 3 * sizeof(float)) + align_up(nc * 3 * sizeof(float)) +
            align_up(nc * 2 * sizeof(float)) + 2 * align_up(nc * sizeof(float)) +
            align_up((size_t)zd->n * cr * sizeof(float)) + 256;
 }
@@ -365,8 +370,8 @@ extern "C" lamp_status lamp_inorm_relu_se(const lamp_tensor_desc* zd, const void
     const int C = zd->c, chunks = stats_chunks(V);
     const int rpc = (int)((V + chunks - 1) / chunks);
     Carver cv(ws, ws_bytes);
-    float* partial = (float*)cv.take((size_t)zd->n * C * chunks * sizeof(float));
-    float* asum = (float*)cv.take((size_t)zd->n * C * sizeof(float));
+    float* partial = (float*)cv.take((size_t)zd->n * C * chunks * 3 * sizeof(float));
+    float* asum = (float*)cv.take((size_t)zd->n * C * 3 * sizeof(float));
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
     const int vec = pick_vec(zd->dtype, C, {zd->ldc, yd->ldc, residual ? rd->ldc : 0}, {z, y, residual});
     LAMP_DISPATCH_TV(zd->dtype, vec, {
@@ -375,7 +380,7 @@ extern "C" lamp_status lamp_inorm_relu_se(const lamp_tensor_desc* zd, const void
                            (const T*)z, zd->ldc, V, C, m.cthreads, m.rl, rpc, stats, gamma, beta, partial);
     });
     LAMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(se_finalize_kernel<1>, dim3(C, zd->n), dim3(256), 0, s, partial, chunks, C, asum);
+    hipLaunchKernelGGL(se_finalize_kernel<3>, dim3(C, zd->n), dim3(256), 0, s, partial, chunks, C, asum);
     LAMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(se_gate_kernel, dim3(zd->n), dim3(256), (size_t)(C + cr) * sizeof(float), s, asum, 1.0f / (float)V, C, cr,
                        w1, b1, w2, b2, gate_save);
@@ -414,8 +419,8 @@ extern "C" lamp_status lamp_inorm_relu_se_bwd(const lamp_tensor_desc* dyd, const
     const int rpc = (int)((V + chunks - 1) / chunks);
     const size_t nc = (size_t)N * C;
     Carver cv(ws, ws_bytes);
-    float* partial = (float*)cv.take(nc * chunks * 5 * sizeof(float));
-    float* s5 = (float*)cv.take(nc * 5 * sizeof(float));
+    float* partial = (float*)cv.take(nc * chunks * 3 * sizeof(float));
+    float* s3 = (float*)cv.take(nc * 3 * sizeof(float));
     float* sums2 = (float*)cv.take(nc * 2 * sizeof(float));
     float* dmv = (float*)cv.take(nc * sizeof(float));
     float* dp2 = (float*)cv.take(nc * sizeof(float));
@@ -428,9 +433,9 @@ extern "C" lamp_status lamp_inorm_relu_se_bwd(const lamp_tensor_desc* dyd, const
                            (const T*)z, zd->ldc, V, C, m.cthreads, m.rl, rpc, stats, gamma, beta, partial);
     });
     LAMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(se_finalize_kernel<5>, dim3(C, N), dim3(256), 0, s, partial, chunks, C, s5);
+    hipLaunchKernelGGL(se_finalize_kernel<3>, dim3(C, N), dim3(256), 0, s, partial, chunks, C, s3);
     LAMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(se_gate_bwd_kernel, dim3(N), dim3(256), (size_t)(C + cr) * sizeof(float), s, s5, 1.0f / (float)V, C, cr,
+    hipLaunchKernelGGL(se_gate_bwd_kernel, dim3(N), dim3(256), (size_t)(C + cr) * sizeof(float), s, s3, 1.0f / (float)V, C, cr,
                        w1, w2, gate_save, dp2, dp1, dmv, sums2);
     LAMP_CHECK_LAUNCH();
     if (dw1 || db1 || dw2 || db2) {

@@ -286,7 +286,7 @@ def test_inorm_relu_se_fwd_bwd(L, dtype, case, variant):
     stats = torch.empty((N, C, 2), dtype=F32, device=DEV)
     L.lamp_inorm_relu(z, torch.empty_like(z), stats, gamma=g, beta=b)
     y = torch.empty_like(z)
-    save = torch.full((N, 2 * C + Cr), float("nan"), dtype=F32, device=DEV)
+    save = torch.full((N, 4 * C + Cr), float("nan"), dtype=F32, device=DEV)
     L.lamp_inorm_relu_se(z, stats, w1, w2, y, save, b1=b1, b2=b2, gamma=g, beta=b, residual=res)
     g64, b64 = (as64(g), as64(b)) if full else (None, None)
     b2_64 = as64(b2) if full else np.zeros(C)
@@ -295,11 +295,17 @@ def test_inorm_relu_se_fwd_bwd(L, dtype, case, variant):
     sv = as64(save)
     np.testing.assert_allclose(sv[:, :C], c["m"], rtol=2e-4, atol=1e-6)
     np.testing.assert_allclose(sv[:, C:2 * C], c["e"], rtol=2e-4)
-    np.testing.assert_allclose(sv[:, 2 * C:], c["h"], rtol=2e-4, atol=1e-6)
+    np.testing.assert_allclose(sv[:, 2 * C:2 * C + Cr], c["h"], rtol=2e-4, atol=1e-6)
     assert np.abs(c["m"] @ as64(w1).T + as64(b1)).min() > 1e-3, "a hidden unit sits on its kink: pick another seed"
     # backward
     u_ref, _ = O.inorm_relu(as64(z), g64, b64, relu=False)
     near = np.abs(u_ref) <= 1e-3
+    # the two mask sums the forward keeps for the backward: sum [u>0] and sum [u>0]*zhat
+    zh_ref = (as64(z) - c["stats"][:, None, None, None, :, 0]) * c["stats"][:, None, None, None, :, 1]
+    on = u_ref > 0
+    flips = near.reshape(N, V, C).sum(1)
+    assert np.all(np.abs(sv[:, 2 * C + Cr:3 * C + Cr] - on.reshape(N, V, C).sum(1)) <= flips + 1e-6 * V)
+    assert np.all(np.abs(sv[:, 3 * C + Cr:] - (on * zh_ref).reshape(N, V, C).sum(1)) <= 3 * flips + 1e-4 * V)
     dz = torch.empty_like(z)
     outs = dict(dw1=torch.full((Cr, C), float("nan"), dtype=F32, device=DEV), db1=torch.empty(Cr, dtype=F32, device=DEV),
                 dw2=torch.full((C, Cr), float("nan"), dtype=F32, device=DEV), db2=torch.empty(C, dtype=F32, device=DEV))
