@@ -140,6 +140,39 @@ def test_full_size_determinism(L, block):
     assert torch.equal(dx2, block["dx"]) and torch.equal(dw2, block["dw"])
 
 
+def test_se_block_fullsize(L, block):
+    """The squeeze-and-excitation block at the size bench.py's se_block workload runs it (1 x 128^3 x
+    64, bf16, reduction ratio 16, with residual): z and its statistics are the conv block's own, the
+    block input serves as the residual.  O(V) work, so every output is checked in full."""
+    z, st, dy, res = block["z"], block["st"], block["dy"], block["x"]
+    Cr = C // 16
+    r = np.random.Generator(np.random.PCG64(41))
+    w1 = torch.from_numpy(r.standard_normal((Cr, C)) / np.sqrt(C)).to(F32).to(DEV)
+    b1 = torch.from_numpy(r.uniform(0.2, 0.6, Cr)).to(F32).to(DEV)
+    w2 = torch.from_numpy(r.standard_normal((C, Cr)) / np.sqrt(Cr)).to(F32).to(DEV)
+    b2 = torch.from_numpy(r.standard_normal(C) * 0.3).to(F32).to(DEV)
+    y, dz = torch.empty_like(z), torch.empty_like(z)
+    save = torch.empty((1, 4 * C + Cr), dtype=F32, device=DEV)
+    g = dict(dw1=torch.empty_like(w1), db1=torch.empty_like(b1), dw2=torch.empty_like(w2), db2=torch.empty_like(b2))
+    L.lamp_inorm_relu_se(z, st, w1, w2, y, save, b1=b1, b2=b2, residual=res)
+    L.lamp_inorm_relu_se_bwd(dy, z, st, w1, w2, save, dz, **g)
+    z64 = z.cpu().float().numpy().astype(np.float64)
+    res64 = res.cpu().float().numpy().astype(np.float64)
+    y_ref, c = O.inorm_relu_se(z64, None, None, as64(w1), as64(b1), as64(w2), as64(b2), residual=res64)
+    check(y.cpu().float().numpy(), y_ref, BF, "full-size se forward")
+    del y_ref, res64
+    np.testing.assert_allclose(as64(save)[0, :C], c["m"][0], rtol=1e-4)
+    np.testing.assert_allclose(as64(save)[0, C:2 * C], c["e"][0], rtol=1e-4)
+    dy64 = dy.cpu().float().numpy().astype(np.float64)
+    ref = O.inorm_relu_se_bwd(dy64, z64, None, None, as64(w1), as64(b1), as64(w2), as64(b2))
+    u_ref, _ = O.inorm_relu(z64, relu=False)
+    near = np.abs(u_ref) <= 1e-3
+    del u_ref
+    check(dz.cpu().float().numpy(), ref[0], BF, "full-size se backward dz", ignore=near)
+    for name, rf in zip(["dw1", "db1", "dw2", "db2"], ref[3:]):
+        check(as64(g[name]), rf, F32, f"full-size se {name}", tol=2e-3)
+
+
 @pytest.mark.timeout(900)
 def test_unet_train_fullsize_sampled(L):
     """The whole-volume training workload at its full size (5 levels, base 32, 2 x 128^3 CT-like
