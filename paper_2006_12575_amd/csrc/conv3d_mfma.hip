@@ -571,8 +571,113 @@ static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     return forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
 }
 
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only) {
+// ---- many small volumes: one packed volume ---------------------------------------------------------
+// A batch of tiny volumes (the deep levels of a batch of sliding windows) fills a 4 x 8 x 16 tile
+// badly: a 4^3 sample uses 64 of its 512 voxel slots.  Such a batch is laid out as ONE volume
+// [1][D][gh*(H+1)][gw*(W+1)]: sample n = a*gw + b sits at rows a*(H+1).. and columns b*(W+1)..,
+// followed by one row / column of zeros, which is the zero padding of both neighbours.  The conv of
+// the packed volume equals the per-sample conv at every real voxel; the voxels in the gaps are
+// dropped when the result is copied back.
+struct PackPlan { int gh, gw, hp, wp; };
+static int64_t pack_slots(int d, int h, int w) { return (int64_t)((d + 3) / 4) * ((h + TH - 1) / TH) * ((w + TW - 1) / TW); }
+static bool conv_pack_plan(const lamp_tensor_desc* zd, PackPlan& best) {
+    static int off = -1;
+    if (off < 0) off = getenv("LAMP_CONV_NO_PACK") ? 1 : 0;
+    if (off || zd->n < 4 || zd->w > 8 || zd->h > 16 || zd->d > 64 || zd->c > 4096) return false;
+    const int64_t plain = (int64_t)zd->n * pack_slots(zd->d, zd->h, zd->w);
+    int64_t bs = plain;
+    bool found = false;
+    for (int gh = 1; gh <= 8 && gh <= zd->n; ++gh) {
+        const int gw = (zd->n + gh - 1) / gh;
+        const int hp = gh * (zd->h + 1), wp = gw * (zd->w + 1);
+        const int64_t sl = pack_slots(zd->d, hp, wp);
+        if ((int64_t)zd->d * hp * wp * 4096 >= ((int64_t)1 << 31)) continue;   // 32-bit element offsets, up to 4096 channels
+        if (sl * 5 <= plain * 4 && sl < bs) { bs = sl; best = PackPlan{gh, gw, hp, wp}; found = true; }   // at least a fifth fewer tiles
+    }
+    return found;
+}
+static void pack_descs(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const PackPlan& p, lamp_tensor_desc& xp,
+                       lamp_tensor_desc& zp) {
+    xp = *xd; xp.n = 1; xp.h = p.hp; xp.w = p.wp; xp.ldc = xd->c;
+    zp = *zd; zp.n = 1; zp.h = p.hp; zp.w = p.wp; zp.ldc = zd->c;
+}
+
+// One thread per (packed voxel, 16-byte granule of 8 channels).  Channels from csplit on come from x2.
+__global__ __launch_bounds__(256) void conv_pack_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ x2,
+                                                        int csplit, bf16_t* __restrict__ xp, int N, int D, int H, int W, int C,
+                                                        int gw, int hp, int wp) {
+    const int gpv = C / 8;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)D * hp * wp * gpv) return;
+    const int g = (int)(i % gpv);
+    int64_t v = i / gpv;
+    const int wq = (int)(v % wp); v /= wp;
+    const int hq = (int)(v % hp);
+    const int d = (int)(v / hp);
+    const int a = hq / (H + 1), h = hq % (H + 1), b = wq / (W + 1), w = wq % (W + 1);
+    const int n = a * gw + b;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (h < H && w < W && n < N) {
+        const int c = g * 8;
+        const bf16_t* src = c < csplit ? x + c : x2 + (c - csplit);
+        q = *reinterpret_cast<const uint4*>(src + ((((int64_t)n * D + d) * H + h) * W + w) * ldx);
+    }
+    *reinterpret_cast<uint4*>(xp + i * 8) = q;
+}
+
+// One workgroup per (sample, 64 output channels): copies the sample's voxels out of the packed result
+// and, when stats != nullptr, takes mean and rstd of the stored values per channel (fixed order).
+__global__ __launch_bounds__(256) void conv_unpack_kernel(const bf16_t* __restrict__ zp, bf16_t* __restrict__ z, int ldz, int N,
+                                                          int D, int H, int W, int C, int gw, int hp, int wp, float eps,
+                                                          float* __restrict__ stats) {
+    __shared__ float red[2][32][64];
+    const int n = blockIdx.x, c0 = blockIdx.y * 64;
+    const int g = threadIdx.x & 7, vl = threadIdx.x >> 3;
+    const int a = n / gw, b = n % gw;
+    const int V = D * H * W;
+    float s[8], q[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s[e] = 0.f; q[e] = 0.f; }
+    const int c = c0 + g * 8;
+    if (c < C) {
+        for (int v = vl; v < V; v += 32) {
+            const int w = v % W, h = (v / W) % H, d = v / (W * H);
+            const int64_t pv = ((int64_t)d * hp + a * (H + 1) + h) * wp + b * (W + 1) + w;
+            const uint4 t = *reinterpret_cast<const uint4*>(zp + pv * C + c);
+            *reinterpret_cast<uint4*>(z + ((((int64_t)n * D + d) * H + h) * W + w) * ldz + c) = t;
+            const uint32_t r[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float f0 = __uint_as_float(r[e] << 16), f1 = __uint_as_float(r[e] & 0xFFFF0000u);
+                s[2 * e] += f0; q[2 * e] = fmaf(f0, f0, q[2 * e]);
+                s[2 * e + 1] += f1; q[2 * e + 1] = fmaf(f1, f1, q[2 * e + 1]);
+            }
+        }
+    }
+    if (!stats) return;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { red[0][vl][g * 8 + e] = s[e]; red[1][vl][g * 8 + e] = q[e]; }
+    __syncthreads();
+    if (threadIdx.x < 64 && c0 + (int)threadIdx.x < C) {
+        double ss = 0.0, qq = 0.0;
+        for (int r = 0; r < 32; ++r) { ss += (double)red[0][r][threadIdx.x]; qq += (double)red[1][r][threadIdx.x]; }
+        const double mean = ss / V;
+        double var = qq / V - mean * mean;
+        if (var < 0.0) var = 0.0;
+        float* o = stats + ((size_t)n * C + c0 + threadIdx.x) * 2;
+        o[0] = (float)mean;
+        o[1] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+}
+
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only, bool two_out) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return -1;
+    PackPlan pp;
+    if (!two_out && conv_pack_plan(zd, pp)) {   // the conv runs on the packed volume, as one contiguous tensor
+        lamp_tensor_desc xp, zp;
+        pack_descs(xd, zd, pp, xp, zp);
+        return conv_repack_kind(&xp, &zp, false, false);
+    }
     if (!tiled_only && conv_use_ring(xd, zd)) return zd->c % 64 == 0 ? 2 : 3;
     return conv_tile_depth(zd) == 8 ? 1 : 0;
 }
@@ -612,6 +717,14 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     }
     const int S = conv_splits(xd, zd);
     if (S > 1) b += align_up((size_t)S * nvox(zd) * zd->c * sizeof(float)) + stats_ws_bytes(zd) + 256;
+    PackPlan pp;
+    if (conv_pack_plan(zd, pp)) {   // packed input and output + the inner conv's own workspace
+        lamp_tensor_desc xp, zp;
+        pack_descs(xd, zd, pp, xp, zp);
+        const size_t pb = align_up((size_t)nvox(&xp) * xp.c * 2) + align_up((size_t)nvox(&zp) * zp.c * 2) +
+                          mfma_conv_ws_bytes(&xp, &zp, 0) + 512;
+        if (pb > b) b = pb;
+    }
     return b;
 }
 
@@ -637,6 +750,28 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     if (two_out && ((((uintptr_t)parts->z2) & 15u) || parts->z_c1 % 32 || parts->z_c1 <= 0 || parts->z_c1 >= zd->c || parts->ldz2 % 8))
         return LAMP_ERR_ALIGN;
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)z) & 15u) || (((uintptr_t)ws) & 15u) || (((uintptr_t)w) & 15u)) return LAMP_ERR_ALIGN;
+    PackPlan pp;
+    if (!two_out && conv_pack_plan(zd, pp)) {
+        lamp_tensor_desc xp, zp;
+        pack_descs(xd, zd, pp, xp, zp);
+        Carver pc(ws, ws_bytes);
+        bf16_t* xpk = (bf16_t*)pc.take((size_t)nvox(&xp) * xp.c * 2);
+        bf16_t* zpk = (bf16_t*)pc.take((size_t)nvox(&zp) * zp.c * 2);
+        const size_t inner = mfma_conv_ws_bytes(&xp, &zp, 0);
+        void* iws = pc.take(inner);
+        if (!pc.ok()) return LAMP_ERR_WORKSPACE;
+        const int64_t granules = nvox(&xp) * (xp.c / 8);
+        hipLaunchKernelGGL(conv_pack_kernel, dim3(cdiv(granules, 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                           two_in ? (const bf16_t*)parts->x2 : (const bf16_t*)x, two_in ? parts->x_c1 : xd->c, xpk, xd->n, xd->d,
+                           xd->h, xd->w, xd->c, pp.gw, pp.hp, pp.wp);
+        LAMP_CHECK_LAUNCH();
+        lamp_status st = mfma_conv_fwd(&xp, xpk, w, dgrad, &zp, zpk, nullptr, 0.f, iws, inner, s, nullptr);
+        if (st != LAMP_OK) return st;
+        hipLaunchKernelGGL(conv_unpack_kernel, dim3(zd->n, cdiv(zd->c, 64)), dim3(256), 0, s, zpk, (bf16_t*)z, zd->ldc, zd->n,
+                           zd->d, zd->h, zd->w, zd->c, pp.gw, pp.hp, pp.wp, eps, stats_out);
+        LAMP_CHECK_LAUNCH();
+        return LAMP_OK;
+    }
     if (!two_in && !two_out && conv_use_ring(xd, zd)) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     const int TDT = conv_tile_depth(zd);
     int td, th, tw;

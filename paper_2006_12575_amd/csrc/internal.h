@@ -27,7 +27,9 @@ lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, 
 // 64 output channels per workgroup, 3 ring kernel with 32; -1: the shape does not take a matrix-core path.
 struct RepackJob { const void* w; void* wp; int Cout, Cin, dgrad, kind; };
 struct RepackTable { int n; RepackJob e[64]; };
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only = false);
+// tiled_only: the conv reads or writes a two-part tensor; two_out: it writes one (then the batch of small
+// volumes is not packed into one volume).
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only = false, bool two_out = false);
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
 lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s);
 // The table the calling thread's conv calls consult (weight pointer + direction + kind must match);

@@ -305,7 +305,7 @@ static lamp_status prepare_repack(const Net& nt, const Layout& lay, int first, i
             if (dir == 0 ? !fwd : !(dgrad && c.dgrad)) continue;
             const lamp_tensor_desc* xd = dir == 0 ? &xi : &xo;   // the conv's input / output in this direction
             const lamp_tensor_desc* zd = dir == 0 ? &xo : &xi;
-            const int kind = conv_repack_kind(xd, zd, c.parts);
+            const int kind = conv_repack_kind(xd, zd, c.parts, c.parts && dir == 1);
             if (kind < 0 || tab.n >= 64 || !aligned16(P[c.pi])) continue;
             const size_t b = conv_repack_bytes(xd, zd);
             if (off + b > lay.repack_bytes) continue;

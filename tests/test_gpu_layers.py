@@ -147,6 +147,41 @@ def test_conv3d_small_volume_many_channels_bf16(L, shape):
     check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), BF, "conv dgrad (split reduction)")
 
 
+@pytest.mark.parametrize("shape", [(12, 4, 4, 4, 64, 64), (75, 4, 4, 4, 128, 128), (60, 8, 8, 8, 32, 64), (5, 2, 3, 4, 32, 32),
+                                   (16, 8, 16, 8, 64, 32), (9, 1, 1, 1, 32, 32), (7, 4, 4, 4, 48, 96)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_many_small_volumes_bf16(L, shape):
+    """A batch of tiny volumes (the deep levels of a batch of sliding windows): the library lays the
+    samples out as one volume with zero gaps between them, so that tiles are filled; every sample must
+    still see its own zero padding and its own statistics.  Forward with statistics, forward into a
+    channel slice, data gradient."""
+    N, D, H, W, Ci, Co = shape
+    r = rng(1500 + sum(shape))
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)) + 0.5, BF)   # non-zero mean: a neighbour leaking in would show
+    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
+    z = torch.full((N, D, H, W, Co), float("nan"), dtype=BF, device=DEV)
+    stats = torch.full((N, Co, 2), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats)
+    check(as64(z), O.conv3d_fwd(as64(x), as64(w)), BF, "conv fwd (packed batch)")
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "stats mean", tol=1e-4)
+    if D * H * W > 1:
+        np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-4)
+    buf = torch.zeros((N, D, H, W, Co + 8), dtype=BF, device=DEV)
+    z2 = buf[..., 8:]
+    L.lamp_conv3d_fwd(x, w, z2)
+    assert torch.equal(z2, z) and torch.all(buf[..., :8] == 0)
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)) + 0.5, BF)
+    dx = torch.full(x.shape, float("nan"), dtype=BF, device=DEV)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), BF, "conv dgrad (packed batch)")
+    # each sample alone gives the same bits as the batch: nothing crosses the gaps
+    z1 = torch.empty((1, D, H, W, Co), dtype=BF, device=DEV)
+    for n in (0, N - 1):
+        L.lamp_conv3d_fwd(x[n:n + 1], w, z1)
+        assert torch.equal(z1[0], z[n]), f"sample {n} differs between the packed batch and a call of its own"
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1, 32, 32), (1, 2, 2, 2, 64, 64), (3, 1, 1, 17, 16, 32), (2, 1, 3, 1, 1, 32), (1, 2, 1, 1, 128, 64)],
                          ids=lambda s: "x".join(map(str, s)))

@@ -62,7 +62,9 @@ def test_config1_tiny_unet_forward_fp32(L):
     dict(levels=1, base=32, in_ch=1, classes=3, affine=False, dtype=BF, dims=(1, 8, 8, 16)),
     # 16 channels at level 1: generic kernels and a materialised concat buffer in bf16
     dict(levels=2, base=16, in_ch=1, classes=3, affine=False, dtype=BF, dims=(2, 8, 8, 16)),
-], ids=["bf16-3lvl", "f32-affine", "bf16-affine", "bf16-1lvl", "bf16-base16"])
+    # many tiny samples: the convs run on one packed volume (also the decoder conv that reads its concat from two tensors)
+    dict(levels=2, base=32, in_ch=1, classes=3, affine=False, dtype=BF, dims=(8, 4, 4, 4)),
+], ids=["bf16-3lvl", "f32-affine", "bf16-affine", "bf16-1lvl", "bf16-base16", "bf16-8x4cubed"])
 def test_unet_fwd_bwd(L, cfg):
     """(a) every layer of the replayed chain matches the oracle given the GPU's own inputs,
     (b) lamp_unet_fwd_bwd reproduces the chain bit for bit, (c) end to end, logits and loss match the
