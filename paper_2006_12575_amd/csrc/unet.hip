@@ -827,6 +827,7 @@ __global__ __launch_bounds__(256) void sw_blend_kernel(const float* __restrict__
     if (v >= (int64_t)D * H * W) return;
     const int w = (int)(v % W), h = (int)((v / W) % H), d = (int)(v / ((int64_t)W * H));
     const float m = 0.5f * (P - 1);
+    const bool even = (K & 1) == 0;
     float acc[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) acc[k] = 0.f;
@@ -846,16 +847,34 @@ __global__ __launch_bounds__(256) void sw_blend_kernel(const float* __restrict__
                 const float g = expf(-(fd * fd + fh * fh + fw * fw) * inv2s2);
                 const int wi = (id * ch + ih) * cw + iw;
                 const float* p = wl + ((((int64_t)wi * P + (d - d0)) * P + (h - h0)) * P + (w - w0)) * K;
+                if (even) {   // a voxel's K floats start on an 8-byte boundary: half as many load instructions
+                    const float2* p2 = reinterpret_cast<const float2*>(p);
 #pragma unroll
-                for (int k = 0; k < 16; ++k)
-                    if (k < K) acc[k] = fmaf(g, p[k], acc[k]);
+                    for (int k = 0; k < 8; ++k)
+                        if (2 * k < K) {
+                            const float2 t = p2[k];
+                            acc[2 * k] = fmaf(g, t.x, acc[2 * k]);
+                            acc[2 * k + 1] = fmaf(g, t.y, acc[2 * k + 1]);
+                        }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k)
+                        if (k < K) acc[k] = fmaf(g, p[k], acc[k]);
+                }
                 wsum += g;
             }
         }
     }
+    if (even) {
+        float2* o2 = reinterpret_cast<float2*>(out + v * K);
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-        if (k < K) out[v * K + k] = acc[k] / wsum;
+        for (int k = 0; k < 8; ++k)
+            if (2 * k < K) o2[k] = make_float2(acc[2 * k] / wsum, acc[2 * k + 1] / wsum);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < K) out[v * K + k] = acc[k] / wsum;
+    }
 }
 
 }  // namespace lamp
