@@ -141,12 +141,15 @@ __device__ __forceinline__ uint32_t head_pack_bf16(float lo, float hi) { return 
 
 // MODE 0: logits only.  MODE 1: + loss, dx, per-wave partials of dWh and dbh.
 // NCB: 32-channel blocks the instantiation holds (C <= 32 * NCB).
-template <int MODE, int NCB>
+// NORM: x is a raw conv output; InstanceNorm (+ ReLU) is applied while it is loaded, rounded to bf16 as the
+// stored activation would be (every 32-voxel group lies inside one sample: Vs % 32 == 0).
+template <int MODE, int NCB, bool NORM = false>
 __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
                                                         const float* __restrict__ bh, int K, int C, int64_t Vtot,
                                                         const int32_t* __restrict__ labels, float* __restrict__ logits,
                                                         bf16_t* __restrict__ dx, int lddx, float* __restrict__ loss_part,
-                                                        float* __restrict__ wpart, float* __restrict__ bpart, float invV) {
+                                                        float* __restrict__ wpart, float* __restrict__ bpart, float invV,
+                                                        NormIn nm = NormIn{nullptr, nullptr, nullptr, 0, 0}, int64_t Vs = 1) {
     __shared__ float dls[4][32][33];   // per wave: dlogits of 32 voxels x 32 (padded) classes
     __shared__ float xs[4][32][32 * NCB + 1];   // per wave: activations of 32 voxels x up to 32*NCB channels, fp32
     __shared__ float red[256];
@@ -196,10 +199,27 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
 #pragma unroll
     for (int i = 0; i < 8; ++i) dbsum[i] = 0.f;
     float lsum = 0.f;
+    __shared__ __attribute__((aligned(16))) float nco[NORM ? 4 : 1][2][NORM ? 32 * NCB : 4];   // per wave: a[c], b[c] of its current sample
+    int cur_n = -1;
     const int64_t groups = (Vtot + 31) / 32;
-    for (int64_t g = (int64_t)blockIdx.x * 4 + wv; g < groups; g += (int64_t)gridDim.x * 4) {
+    // With normalise-on-load every wave walks a contiguous run of groups, so that the sample (and with it the
+    // coefficients) changes at most a few times per wave; otherwise the groups are dealt round robin.
+    const int64_t nwaves = (int64_t)gridDim.x * 4, wid = (int64_t)blockIdx.x * 4 + wv;
+    const int64_t gpw = (groups + nwaves - 1) / nwaves;
+    const int64_t g_lo = NORM ? wid * gpw : wid, g_hi = NORM ? (g_lo + gpw < groups ? g_lo + gpw : groups) : groups;
+    const int64_t g_step = NORM ? 1 : nwaves;
+    for (int64_t g = g_lo; g < g_hi; g += g_step) {
         const int64_t v = g * 32 + l32;
         const bool valid = v < Vtot;
+        if (NORM) {
+            const int n = (int)((g * 32) / Vs);
+            if (n != cur_n) {   // wave-uniform
+                cur_n = n;
+                __builtin_amdgcn_wave_barrier();
+                for (int c = lane; c < C; c += 64) norm_coeffs(nm, n, c, nco[wv][0][c], nco[wv][1][c]);
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
         const bf16_t* xp = x + (valid ? v : 0) * ldx;
         uint4 xq[2 * NCB];
         hf32x16 acc;
@@ -210,6 +230,25 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
             xq[kc] = make_uint4(0, 0, 0, 0);
             if (kc < CK) {
                 if (valid) xq[kc] = *reinterpret_cast<const uint4*>(xp + 16 * kc + 8 * half);
+                if (NORM) {
+                    uint32_t r4[4] = {xq[kc].x, xq[kc].y, xq[kc].z, xq[kc].w};
+                    float na[8], nb[8];
+                    *reinterpret_cast<float4*>(na) = *reinterpret_cast<const float4*>(&nco[wv][0][16 * kc + 8 * half]);
+                    *reinterpret_cast<float4*>(na + 4) = *reinterpret_cast<const float4*>(&nco[wv][0][16 * kc + 8 * half + 4]);
+                    *reinterpret_cast<float4*>(nb) = *reinterpret_cast<const float4*>(&nco[wv][1][16 * kc + 8 * half]);
+                    *reinterpret_cast<float4*>(nb + 4) = *reinterpret_cast<const float4*>(&nco[wv][1][16 * kc + 8 * half + 4]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float u0 = norm_u(__uint_as_float(r4[e] << 16), na[2 * e], nb[2 * e]);
+                        float u1 = norm_u(__uint_as_float(r4[e] & 0xFFFF0000u), na[2 * e + 1], nb[2 * e + 1]);
+                        if (nm.relu) { u0 = u0 > 0.f ? u0 : 0.f; u1 = u1 > 0.f ? u1 : 0.f; }
+                        typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+                        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+                        const f32x2 uu = {u0, u1};
+                        r4[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(uu, bf16x2));   // round to nearest even
+                    }
+                    xq[kc] = valid ? make_uint4(r4[0], r4[1], r4[2], r4[3]) : make_uint4(0, 0, 0, 0);
+                }
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afw[kc], __builtin_bit_cast(hbf16x8, xq[kc]), acc, 0, 0, 0);
             }
         }
@@ -367,8 +406,10 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
 }
 
 static bool head_mfma_ok(const lamp_tensor_desc* xd, const void* x, const lamp_norm_in* xnorm, const void* wh, int classes,
-                         const lamp_tensor_desc* dxd, const void* dx, const void* logits) {
-    const bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+                         const lamp_tensor_desc* dxd, const void* dx, const void* logits, bool allow_norm = false) {
+    bool nm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+    // normalise-on-load: forward only, all channels, voxel groups that do not straddle samples
+    if (nm && allow_norm && xnorm->c_norm == xd->c && ((int64_t)xd->d * xd->h * xd->w) % 32 == 0) nm = false;
     if (xd->dtype != LAMP_BF16 || nm || xd->c % 16 || xd->c > 128 || xd->ldc % 8 || classes > 16) return false;
     if (!aligned16(x) || !aligned16(wh)) return false;
     if (dx && (dxd->ldc % 8 || !aligned16(dx))) return false;
@@ -421,7 +462,20 @@ extern "C" lamp_status lamp_head_fwd(const lamp_tensor_desc* xd, const void* x, 
     if (!logits) return LAMP_ERR_NULL;
     if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
     const int64_t Vs = (int64_t)xd->d * xd->h * xd->w, Vt = nvox(xd);
-    if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr, logits)) {
+    if (head_mfma_ok(xd, x, xnorm, wh, classes, nullptr, nullptr, logits, true)) {
+        if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) {
+            const NormIn nm = make_norm(xnorm);
+            if (xd->c <= 64)
+                hipLaunchKernelGGL((head_mfma_kernel<0, 2, true>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
+                                   (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr,
+                                   0, nullptr, nullptr, nullptr, 0.f, nm, Vs);
+            else
+                hipLaunchKernelGGL((head_mfma_kernel<0, 4, true>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
+                                   (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr,
+                                   0, nullptr, nullptr, nullptr, 0.f, nm, Vs);
+            LAMP_CHECK_LAUNCH();
+            return LAMP_OK;
+        }
         if (xd->c <= 64)
             hipLaunchKernelGGL((head_mfma_kernel<0, 2>), dim3(head_mfma_blocks(Vt)), dim3(256), 0, (hipStream_t)stream,
                                (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, bh, classes, xd->c, Vt, nullptr, logits, nullptr, 0,

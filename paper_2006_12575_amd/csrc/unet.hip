@@ -63,8 +63,10 @@ static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
     return m;
 }
 
+// last_apply == false leaves the second conv's output raw (z and its statistics): the consumer normalises
+// while it loads.
 static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, int Cout, const void* const* P, int pi,
-                             ConvBuf& c1, ConvBuf& c2, const void* x2 = nullptr) {
+                             ConvBuf& c1, ConvBuf& c2, const void* x2 = nullptr, bool last_apply = true) {
     const lamp_unet_desc* u = nt.u;
     const int pc = per_conv(u);
     lamp_tensor_desc xd = nt.td(l, Cin, ldx), zd = nt.td(l, Cout, Cout);
@@ -82,7 +84,7 @@ static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, in
     if (st != LAMP_OK) return st;
     st = lamp_conv3d_fwd(&y1, c1.y, nullptr, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch,
                          nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK) return st;
+    if (st != LAMP_OK || !last_apply) return st;
     lamp_tensor_desc y2 = nt.td(l, Cout, c2.ldy);
     return lamp_inorm_relu(&zd, c2.z, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
                            u->affine ? (const float*)P[pi + pc + 2] : nullptr, u->eps, &y2, c2.y, c2.stats, 1, nullptr, 0,
@@ -487,10 +489,18 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
             st = lamp_convtr3d(&xd, cur, nullptr, P[pi], (const float*)P[pi + 1], &yd, lay.up[l - 1], nt.scratch,
                                nt.scratch_bytes, nt.s);
             if (st != LAMP_OK) return st;
+            // inference: the last block's output feeds only the head, which normalises while it loads
             st = block_fwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1],
-                           lay.vcat ? lay.up[l - 1] : nullptr);
+                           lay.vcat ? lay.up[l - 1] : nullptr, bwd || l > 1);
             if (st != LAMP_OK) return st;
             cur = lay.d2[l - 1].y;
+        }
+        if (!bwd && L > 1) {
+            const int pc = per_conv(u), pi2 = dec_pi(u, 1) - pbase + 2 + pc;   // the last block's second conv
+            lamp_norm_in hn{lay.d2[0].stats, u->affine ? (const float*)P[pi2 + 1] : nullptr,
+                            u->affine ? (const float*)P[pi2 + 2] : nullptr, C1, 1};
+            lamp_tensor_desc zd = nt.td(1, C1, C1);
+            return lamp_head_fwd(&zd, lay.d2[0].z, &hn, P[hp], (const float*)P[hp + 1], u->classes, logits, nt.s);
         }
         if (!bwd) return lamp_head_fwd(&hd, top, nullptr, P[hp], (const float*)P[hp + 1], u->classes, logits, nt.s);
         if (phase == 1) return LAMP_OK;

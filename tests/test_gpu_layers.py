@@ -460,6 +460,36 @@ def test_head_softmax_ce(L, dtype, shape):
     assert abs(loss.item() - np.log(K)) < 1e-5
 
 
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 4, 4, 4, 32, 10), (3, 2, 4, 8, 64, 5), (1, 8, 8, 8, 128, 3), (2, 3, 3, 5, 32, 4), (1, 4, 8, 8, 16, 2)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("affine", [False, True], ids=["plain", "affine"])
+def test_head_normalise_on_load(L, dtype, shape, affine):
+    """The head fed with a raw conv output and its statistics (inference skips the last apply pass):
+    the logits must equal, bit for bit, those computed from the materialised activation."""
+    N, D, H, W, C, K = shape
+    r = rng(1700 + sum(shape))
+    z = to_dev(S.normal(r, (N, D, H, W, C), 1.3) + 0.2, dtype)
+    g = to_dev(r.uniform(0.5, 1.5, C), F32) if affine else None
+    b = to_dev(r.uniform(-0.5, 0.5, C), F32) if affine else None
+    wh = to_dev(S.normal(r, (K, C), np.sqrt(2.0 / C)), dtype)
+    bh = to_dev(S.normal(r, (K,), 0.1), F32)
+    y = torch.empty_like(z)
+    stats = torch.empty((N, C, 2), dtype=F32, device=DEV)
+    L.lamp_inorm_relu(z, y, stats, gamma=g, beta=b)
+    ref = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
+    L.lamp_head_fwd(y, wh, bh, ref)
+    got = torch.full_like(ref, float("nan"))
+    L.lamp_head_fwd(z, wh, bh, got, xnorm=dict(mean_rstd=stats, gamma=g, beta=b, c_norm=C, relu=1))
+    if dtype == F32 or (D * H * W) % 32 == 0:   # the same kernel serves both calls
+        assert torch.equal(got, ref)
+    else:   # matrix-core kernel on the stored activation, generic kernel when a voxel group would straddle samples
+        check(as64(got), as64(ref), F32, "head logits, generic vs matrix-core kernel", tol=1e-5)
+    y_ref, _ = O.inorm_relu(as64(z), as64(g) if affine else None, as64(b) if affine else None)
+    y_st = O.round_bf16(y_ref) if dtype == BF else y_ref
+    check(as64(got), O.head_fwd(y_st, as64(wh), as64(bh)), dtype, "head logits (normalise on load)")
+
+
 def test_determinism_bitwise(L):
     r = rng(9)
     x = to_dev(S.normal(r, (1, 12, 20, 36, 64)), BF)
