@@ -166,26 +166,26 @@ def _stage_shapes(N, D, H, W, base, cut):
     return (N, D >> cut, H >> cut, W >> cut, base << (cut - 1)), sk
 
 
-@pytest.mark.parametrize("cut", [1, 2])
-def test_tail_partition_fwd_bwd(L, cut):
+@pytest.mark.parametrize("cut,affine", [(1, False), (2, False), (1, True)], ids=["cut1", "cut2", "cut1-affine"])
+def test_tail_partition_fwd_bwd(L, cut, affine):
     """The net cut after encoder block `cut` (Sec. 2.2 Eq. 3): partition 0 forward, the tail forward
     and backward, partition 0 backward.  Every result must equal the whole net's bit for bit (the
     whole net is itself verified layer by layer against the oracle); the gradients that cross the cut
     are compared with the oracle's, computed from the GPU's own partition-0 outputs."""
     levels, base, K, dtype = 3, 32, 5, BF
     N, D, H, W = 2, 16, 16, 32
-    names, dev, ora = make_net(levels, base, 1, K, False, dtype, 21)
+    names, dev, ora = make_net(levels, base, 1, K, affine, dtype, 21)
     rx, rl = S.streams(22, 2)
     x = to_dev(S.ct_volume(rx, N, D, H, W), dtype)
     lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(DEV)
-    ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype)
+    ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype, affine=affine)
     grads = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
     loss = torch.empty((), dtype=F32, device=DEV)
     logits = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
     L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
 
     toff = L.lamp_unet_tail_param_offset(ud, cut + 1)
-    assert toff == 2 * cut
+    assert toff == 2 * cut * (3 if affine else 1)
     pshape, sshapes = _stage_shapes(N, D, H, W, base, cut)
     pooled = torch.empty(pshape, dtype=dtype, device=DEV)
     skips = [torch.empty(sh, dtype=dtype, device=DEV) for sh in sshapes]
@@ -226,8 +226,9 @@ def test_tail_partition_fwd_bwd(L, cut):
     assert L.lamp_unet_tail_workspace_bytes(L.unet_desc(levels, base, 1, K, N, D, H, W, F32), cut + 1) == 0
 
 
-@pytest.mark.parametrize("cut,n,M", [(1, 1, 2), (2, 2, 3), (1, 2, 1)], ids=["cut1-1x2", "cut2-2x3", "cut1-2x1"])
-def test_pipeline_two_partitions_micro_batches(L, cut, n, M):
+@pytest.mark.parametrize("cut,n,M,affine", [(1, 1, 2, False), (2, 2, 3, False), (1, 2, 1, False), (2, 1, 2, True)],
+                         ids=["cut1-1x2", "cut2-2x3", "cut1-2x1", "cut2-1x2-affine"])
+def test_pipeline_two_partitions_micro_batches(L, cut, n, M, affine):
     """Partition 0 and the tail on two streams, M micro-batches of n samples in the pipeline order
     (Sec. 2.1).  The result is the mini-batch's loss and gradients: compared with lamp_unet_fwd_bwd
     on the whole mini-batch (bit for bit when M == 1: same kernels on the same shapes; to the bf16
@@ -236,17 +237,17 @@ def test_pipeline_two_partitions_micro_batches(L, cut, n, M):
     levels, base, K, dtype = 3, 32, 4, BF
     D, H, W = 16, 16, 16
     N = n * M
-    names, dev, ora = make_net(levels, base, 1, K, False, dtype, 31)
+    names, dev, ora = make_net(levels, base, 1, K, affine, dtype, 31)
     rx, rl = S.streams(32 + cut, 2)
     x = to_dev(S.ct_volume(rx, N, D, H, W), dtype)
     lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(DEV)
-    full = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype)
+    full = L.unet_desc(levels, base, 1, K, N, D, H, W, dtype, affine=affine)
     g_full = [torch.empty(t.shape, dtype=F32, device=DEV) for t in dev]
     loss_full = torch.empty((), dtype=F32, device=DEV)
     lg_full = torch.empty((N, D, H, W, K), dtype=F32, device=DEV)
     L.lamp_unet_fwd_bwd(full, dev, x, lab, loss_full, g_full, logits=lg_full)
 
-    mb = L.unet_desc(levels, base, 1, K, n, D, H, W, dtype)
+    mb = L.unet_desc(levels, base, 1, K, n, D, H, W, dtype, affine=affine)
     aux = torch.cuda.Stream()
     ws = torch.empty(L.lamp_unet_pipeline_workspace_bytes(mb, cut, M), dtype=torch.uint8, device=DEV)
     runs = []
