@@ -46,6 +46,9 @@ def main():
                          "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--micro-batches", type=int, default=2, help="unet_train_pipeline: micro-batches the 2 samples are split into")
     ap.add_argument("--cut", type=int, default=2, help="unet_train_pipeline: last encoder block of partition 0")
+    ap.add_argument("--graph", action="store_true",
+                    help="tiny: replay the ~60 small kernels as one captured HIP graph (measured: no faster than launching "
+                         "them one by one, the step is bound by the chain of small kernels on the GPU, not by the launches)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic) so that a counter "
                          "profile of this run can scale FETCH_SIZE / WRITE_SIZE")
@@ -363,6 +366,23 @@ def net_bench(args, torch, np, S, L):
     for _ in range(warm):
         run()
     torch.cuda.synchronize()
+    if wl == "tiny" and args.graph:
+        # about 60 kernels of a few microseconds: the forward is captured once as a HIP graph on a side stream
+        # (the library only enqueues kernels, so the call is capturable as it stands) and a step replays it
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        eager = logits.clone()
+        graph.replay()
+        torch.cuda.synchronize()
+        if not torch.equal(logits, eager):
+            print("bench.py: the captured graph does not reproduce the eager logits", file=sys.stderr)
+            sys.exit(1)
+        run = graph.replay
+        what += " (one captured HIP graph per step)"
+        for _ in range(warm):
+            run()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         run()

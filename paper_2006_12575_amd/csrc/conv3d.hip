@@ -2,6 +2,7 @@
 // direct kernels (any dtype / channel count) that serve the fp32 path and odd channel counts.
 // Shapes with channel counts in multiples of 32 in bf16 go to the matrix-core kernels.
 #include "internal.h"
+#include "vec.h"
 
 namespace lamp {
 
@@ -619,10 +620,166 @@ static lamp_status check_conv_pair(const lamp_tensor_desc* a, const void* pa, co
     return LAMP_OK;
 }
 
+// The same sum with register tiling, for channel counts that are small multiples of 8 (the fp32 path of small
+// nets): a thread owns OCG output channels of one voxel; the weights of a chunk of 8 input channels sit in
+// LDS as [tap][ic][oc] (every lane of a wave reads the same few addresses), the input voxel is read once per
+// (tap, ic) and used OCG times.  Input-channel chunks are taken in order, taps inside a chunk: a fixed order.
+template <typename T, bool DGRAD, int OCG>
+__global__ __launch_bounds__(256) void conv3d_regtile_kernel(const T* __restrict__ x, int ldx, const T* __restrict__ w,
+                                                             const float* __restrict__ bias, T* __restrict__ z, int ldz, int N,
+                                                             int D, int H, int W, int Cin, int Cout, int xvec, int wvec) {
+    extern __shared__ float wsm[];   // [27][ICH][Cout]
+    constexpr int ICH = 8;
+    const int G = Cout / OCG, vpb = 256 / G;
+    const int og = threadIdx.x % G, vl = threadIdx.x / G;
+    const int64_t total = (int64_t)N * D * H * W;
+    const int64_t v = (int64_t)blockIdx.x * vpb + vl;
+    const bool active = vl < vpb && v < total;
+    int wv = 0, h = 0, d = 0, n = 0;
+    if (active) {
+        wv = (int)(v % W);
+        int64_t r = v / W;
+        h = (int)(r % H);
+        r /= H;
+        d = (int)(r % D);
+        n = (int)(r / D);
+    }
+    float acc[OCG];
+#pragma unroll
+    for (int o = 0; o < OCG; ++o) acc[o] = bias ? bias[og * OCG + o] : 0.f;
+    for (int ic0 = 0; ic0 < Cin; ic0 += ICH) {
+        const int nic = Cin - ic0 < ICH ? Cin - ic0 : ICH;
+        __syncthreads();
+        // weights of the chunk -> LDS [tap][ic][oc].  16-byte granules where the layout allows (forward: along ic,
+        // the contiguous index of W[oc][t][ic]; data gradient: along oc of W[ic][26-t][oc]); four granules in flight.
+        constexpr int VW = sizeof(T) == 2 ? 8 : 4;
+        if (wvec && nic == ICH) {
+            const int gtot = 27 * ICH * Cout / VW;
+            for (int i0 = threadIdx.x; i0 < gtot; i0 += 1024) {
+                float val[4][VW];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + 256 * u;
+                    dst[u] = -1;
+                    if (i < gtot) {
+                        if (DGRAD) {
+                            const int ocv = i % (Cout / VW), r = i / (Cout / VW), ic = r % ICH, t = r / ICH;
+                            Vec<T, VW>::load(w + ((int64_t)(ic0 + ic) * 27 + (26 - t)) * Cout + ocv * VW, val[u]);
+                            dst[u] = (t * ICH + ic) * Cout + ocv * VW;
+                        } else {
+                            const int icv = i % (ICH / VW), r = i / (ICH / VW), t = r % 27, oc = r / 27;
+                            Vec<T, VW>::load(w + ((int64_t)oc * 27 + t) * Cin + ic0 + icv * VW, val[u]);
+                            dst[u] = (t * ICH + icv * VW) * Cout + oc;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) {
+#pragma unroll
+                        for (int e = 0; e < VW; ++e) wsm[dst[u] + (DGRAD ? e : e * Cout)] = val[u][e];
+                    }
+            }
+        } else {
+            const int wtot = 27 * nic * Cout;
+            for (int i = threadIdx.x; i < wtot; i += 256) {
+                const int ic = i % nic, r = i / nic;
+                int t, oc;
+                const T* src;
+                if (DGRAD) {
+                    oc = r % Cout; t = r / Cout;
+                    src = w + ((int64_t)(ic0 + ic) * 27 + (26 - t)) * Cout + oc;
+                } else {
+                    t = r % 27; oc = r / 27;
+                    src = w + ((int64_t)oc * 27 + t) * Cin + ic0 + ic;
+                }
+                wsm[(t * ICH + ic) * Cout + oc] = io<T>::ld(src);
+            }
+        }
+        __syncthreads();
+        if (!active) continue;
+        // the three taps of a w-row are loaded together, one row ahead of the multiply-adds
+        auto load_row = [&](int kdh, float (&xr)[3][ICH]) __attribute__((always_inline)) {
+            const int id = d + kdh / 3 - 1, ih = h + kdh % 3 - 1;
+            const bool rin = id >= 0 && id < D && ih >= 0 && ih < H;
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int iw = wv + kw - 1;
+                const bool in = rin && iw >= 0 && iw < W;
+                const T* xp = x + ((((int64_t)n * D + (rin ? id : d)) * H + (rin ? ih : h)) * W + (in ? iw : wv)) * ldx + ic0;
+                if (xvec && nic == ICH) {   // one or two 16-byte loads instead of eight narrow ones
+                    constexpr int VW = sizeof(T) == 2 ? 8 : 4;
+                    if (in) {
+                        Vec<T, VW>::load(xp, *reinterpret_cast<float(*)[VW]>(&xr[kw][0]));
+                        if (VW == 4) Vec<T, VW>::load(xp + 4, *reinterpret_cast<float(*)[VW]>(&xr[kw][ICH - VW]));
+                    } else {
+#pragma unroll
+                        for (int ic = 0; ic < ICH; ++ic) xr[kw][ic] = 0.f;
+                    }
+                } else {
+#pragma unroll
+                    for (int ic = 0; ic < ICH; ++ic) xr[kw][ic] = (in && ic < nic) ? io<T>::ld(xp + ic) : 0.f;
+                }
+            }
+        };
+        auto mul_row = [&](int kdh, const float (&xr)[3][ICH]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const float* wt = wsm + ((kdh * 3 + kw) * ICH) * Cout + og * OCG;
+                if (nic == ICH) {   // branch-free: the eight weight rows are read ahead of the multiply-adds
+                    float wr[ICH][OCG];
+#pragma unroll
+                    for (int ic = 0; ic < ICH; ++ic)
+#pragma unroll
+                        for (int o = 0; o < OCG; ++o) wr[ic][o] = wt[ic * Cout + o];
+#pragma unroll
+                    for (int ic = 0; ic < ICH; ++ic)
+#pragma unroll
+                        for (int o = 0; o < OCG; ++o) acc[o] = fmaf(xr[kw][ic], wr[ic][o], acc[o]);
+                } else {
+                    for (int ic = 0; ic < nic; ++ic)
+#pragma unroll
+                        for (int o = 0; o < OCG; ++o) acc[o] = fmaf(xr[kw][ic], wt[ic * Cout + o], acc[o]);
+                }
+            }
+        };
+        float xa[3][ICH], xb[3][ICH];
+        load_row(0, xa);
+#pragma unroll
+        for (int kdh = 0; kdh < 9; kdh += 2) {
+            if (kdh + 1 < 9) load_row(kdh + 1, xb);
+            mul_row(kdh, xa);
+            if (kdh + 2 < 9) load_row(kdh + 2, xa);
+            if (kdh + 1 < 9) mul_row(kdh + 1, xb);
+        }
+    }
+    if (active) {
+#pragma unroll
+        for (int o = 0; o < OCG; ++o) io<T>::st(z + v * ldz + og * OCG + o, acc[o]);
+    }
+}
+
 template <bool DGRAD>
 static lamp_status launch_direct(const lamp_tensor_desc* xd, const void* x, NormIn nm, const void* w, const float* bias,
                                  const lamp_tensor_desc* zd, void* z, hipStream_t s) {
     const int Cout = zd->c, Cin = xd->c;
+    if (!nm.mean_rstd && Cout % 8 == 0 && Cout <= 64) {
+        const int G = Cout / 8, vpb = 256 / G;
+        const size_t shm = (size_t)27 * 8 * Cout * sizeof(float);   // at most 55 KB
+        const dim3 grid(cdiv(nvox(zd), vpb));
+        // 16-byte loads of a voxel's 8-channel chunk need aligned rows
+        const int xvec = aligned16(x) && (xd->ldc * esize(xd->dtype)) % 16 == 0 ? 1 : 0;
+        const int wvec = aligned16(w) && ((DGRAD ? Cout : Cin) * esize(xd->dtype)) % 16 == 0 ? 1 : 0;
+        if (xd->dtype == LAMP_BF16)
+            hipLaunchKernelGGL((conv3d_regtile_kernel<bf16_t, DGRAD, 8>), grid, dim3(256), shm, s, (const bf16_t*)x, xd->ldc,
+                               (const bf16_t*)w, bias, (bf16_t*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, Cin, Cout, xvec, wvec);
+        else
+            hipLaunchKernelGGL((conv3d_regtile_kernel<float, DGRAD, 8>), grid, dim3(256), shm, s, (const float*)x, xd->ldc,
+                               (const float*)w, bias, (float*)z, zd->ldc, zd->n, zd->d, zd->h, zd->w, Cin, Cout, xvec, wvec);
+        LAMP_CHECK_LAUNCH();
+        return LAMP_OK;
+    }
     const int ocT = Cout < 256 ? Cout : 256;
     const int vpb = 256 / ocT;
     const int64_t total = nvox(zd);

@@ -302,3 +302,31 @@ def test_sliding_window_vs_oracle(L, dtype):
     store = O.round_bf16 if dtype == BF else (lambda a: a)
     ref = sliding.sliding_window(lambda win: unet.forward(ora, win, levels, store=store)[0], as64(vol), patch=P)
     check(as64(out), ref, dtype, "sliding-window logits")
+
+
+def test_unet_forward_as_captured_graph(L):
+    """The whole-network forward only enqueues kernels (no allocation, no memset, no synchronisation), so
+    it can be captured as one HIP graph.  Every replay -- with eager work, new inputs and synchronisations
+    between the replays -- must reproduce the eager result bit for bit."""
+    names, dev, _ = make_net(3, 8, 1, 5, False, F32, 1001)
+    ud = L.unet_desc(3, 8, 1, 5, 1, 32, 32, 32, F32)
+    x = torch.empty((1, 32, 32, 32, 1), dtype=F32, device=DEV)
+    logits = torch.empty((1, 32, 32, 32, 5), dtype=F32, device=DEV)
+    ws = torch.empty(L.lamp_unet_workspace_bytes(ud, False), dtype=torch.uint8, device=DEV)
+    eager_out = torch.empty_like(logits)
+    rx = S.streams(1001, 4)
+    x.copy_(to_dev(S.normal(rx[0], x.shape), F32))
+    L.lamp_unet_fwd(ud, dev, x, eager_out, ws=ws)       # also takes the one-time set-up out of the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.lamp_unet_fwd(ud, dev, x, logits, ws=ws)
+    for i in range(4):
+        x.copy_(to_dev(S.normal(rx[i], x.shape), F32))  # new input in place, eager work between the replays
+        L.lamp_unet_fwd(ud, dev, x, eager_out, ws=ws)
+        torch.cuda.synchronize()
+        logits.fill_(float("nan"))
+        ws.fill_(0xFF)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(logits, eager_out), f"replay {i} differs from the eager forward"
