@@ -103,3 +103,45 @@ def test_argument_errors_are_caught_on_the_host(L):
     # sliding window: batch of the patch descriptor must equal the window count
     pd = L.unet_desc(3, 8, 1, 5, 7, 64, 64, 64, torch.float32)
     assert lib.lamp_sliding_window_fwd(by(pd), tbl, fake, 256, 256, 160, 0.25, 0.125, fake, fake, 1 << 40, None) == -2
+
+
+def test_tail_pipeline_and_gate_queries_on_the_host(L):
+    """Workspace queries and argument checks of the partition / pipeline / squeeze-and-excitation entry
+    points: pure host logic, nothing is launched."""
+    lib = L.lib()
+    by = ctypes.byref
+    fake = ctypes.c_void_p(4096)
+    tbl = (ctypes.c_void_p * 64)(*([4096] * 64))
+    ud = L.unet_desc(5, 32, 1, 10, 1, 128, 128, 128, torch.bfloat16)
+    np_all = L.lamp_unet_param_count(ud)
+    # the tail's parameters are the whole net's from the first block after the cut on
+    assert [L.lamp_unet_tail_param_offset(ud, f) for f in (2, 3, 5)] == [2, 4, 8]
+    assert L.lamp_unet_tail_param_offset(ud, 1) == -1 and L.lamp_unet_tail_param_offset(ud, 6) == -1
+    affine = L.unet_desc(5, 32, 1, 10, 1, 128, 128, 128, torch.bfloat16, affine=True)
+    assert L.lamp_unet_tail_param_offset(affine, 3) == 12 and np_all == 28
+    # workspaces: a later cut leaves less to the tail; the pipeline holds every micro-batch's share
+    t2, t4 = L.lamp_unet_tail_workspace_bytes(ud, 2), L.lamp_unet_tail_workspace_bytes(ud, 4)
+    assert 0 < t4 < t2 < L.lamp_unet_workspace_bytes(ud, True)
+    p1, p2 = L.lamp_unet_pipeline_workspace_bytes(ud, 2, 1), L.lamp_unet_pipeline_workspace_bytes(ud, 2, 2)
+    assert p1 > t2 and abs(p2 - 2 * p1) <= 1024
+    # the tail needs the concat read from two tensors: bf16 and a base that is a multiple of 32
+    assert L.lamp_unet_tail_workspace_bytes(L.unet_desc(5, 32, 1, 10, 1, 128, 128, 128, torch.float32), 2) == 0
+    assert L.lamp_unet_tail_workspace_bytes(L.unet_desc(5, 16, 1, 10, 1, 128, 128, 128, torch.bfloat16), 2) == 0
+    assert L.lamp_unet_pipeline_workspace_bytes(ud, 5, 2) == 0 and L.lamp_unet_pipeline_workspace_bytes(ud, 2, 0) == 0
+    # argument errors before any launch
+    assert lib.lamp_unet_tail_fwd(by(ud), 1, tbl, fake, tbl, fake, fake, 1 << 40, None) == -2            # first_level 1
+    assert lib.lamp_unet_tail_fwd(by(ud), 3, tbl, fake, None, fake, fake, 1 << 40, None) == -1           # no skips
+    assert lib.lamp_unet_tail_fwd(by(ud), 3, tbl, fake, tbl, fake, fake, 16, None) == -5                 # workspace
+    assert lib.lamp_unet_pipeline_fwd_bwd(by(ud), 2, 2, tbl, fake, fake, None, fake, tbl, 0.0, fake, 1 << 40, fake, fake) == -2  # one stream twice
+    assert lib.lamp_unet_pipeline_fwd_bwd(by(ud), 2, 2, tbl, fake, fake, None, fake, tbl, 0.5, fake, 1 << 40, None, fake) == -2  # beta
+    assert lib.lamp_unet_pipeline_fwd_bwd(by(ud), 2, 2, tbl, fake, fake, None, fake, tbl, 0.0, fake, 16, None, fake) == -5
+    # squeeze-and-excitation gate
+    TD = L.binding.TensorDesc
+    d = TD(2, 8, 8, 8, 64, 64, L.binding.BF16)
+    assert lib.lamp_inorm_relu_se_workspace_bytes(by(d), 4) > 0
+    assert lib.lamp_inorm_relu_se_workspace_bytes(by(d), 0) == 0
+    args = (by(d), fake, fake, None, None)
+    assert lib.lamp_inorm_relu_se(*args, 0, fake, None, fake, None, None, None, by(d), fake, fake, fake, 1 << 30, None) == -2   # cr
+    assert lib.lamp_inorm_relu_se(*args, 4, None, None, fake, None, None, None, by(d), fake, fake, fake, 1 << 30, None) == -1   # w1
+    assert lib.lamp_inorm_relu_se(*args, 4, fake, None, fake, None, None, fake, by(d), fake, fake, fake, 1 << 30, None) == -1   # residual without descriptor
+    assert lib.lamp_inorm_relu_se(*args, 4, fake, None, fake, None, None, None, by(d), fake, fake, fake, 16, None) == -5
