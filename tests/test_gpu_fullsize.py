@@ -6,6 +6,8 @@ The O(V * 27 * C^2) results are checked on sampled outputs the oracle computes o
 voxels x all channels, forcing the 8 corners, edges, faces and coordinates on both sides of every
 kind of tile boundary); the O(V) results (statistics, normalise+ReLU, its backward) in full.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -253,16 +255,18 @@ def test_pipeline_fullsize_vs_whole_net(L):
 
 
 @pytest.mark.timeout(900)
-def test_unet_infer_fullsize_sampled(L):
+@pytest.mark.parametrize("dims,seed", [((256, 256, 160), 1005), ((352, 256, 288), 1008)], ids=["256x256x160", "352x256x288"])
+def test_unet_infer_fullsize_sampled(L, dims, seed):
     """Large-input inference at its full size (1 x 256 x 256 x 160 CT-like volume, 5 levels, base 32,
     bf16): the layer-by-layer forward chain with sampled / full oracle checks of every layer, and
-    the whole-network forward entry point equal to it bit for bit."""
+    the whole-network forward entry point equal to it bit for bit.  The whole head-and-neck sized
+    volume with unequal axes (352 x 256 x 288, Sec. 3) is the second case."""
     from gpu_chain import Chain
     from test_gpu_unet import make_net
     levels, base, K = 5, 32, 10
-    N, Dd, H, W = 1, 256, 256, 160
-    names, dev, _ = make_net(levels, base, 1, K, False, BF, 1005)
-    x = torch.from_numpy(S.ct_volume(S.streams(1005, 2)[1], N, Dd, H, W)).to(BF).to(DEV)
+    N, (Dd, H, W) = 1, dims
+    names, dev, _ = make_net(levels, base, 1, K, False, BF, seed)
+    x = torch.from_numpy(S.ct_volume(S.streams(seed, 2)[1], N, Dd, H, W)).to(BF).to(DEV)
     ud = L.unet_desc(levels, base, 1, K, N, Dd, H, W, BF)
     logits = torch.empty((N, Dd, H, W, K), dtype=F32, device=DEV)
     L.lamp_unet_fwd(ud, dev, x, logits)
