@@ -289,6 +289,8 @@ def rmsprop_step(w, v, g, lr=1e-3, alpha=0.99, eps=1e-8):
 # gate written out: squeeze = per-sample, per-channel mean of the activated feature map over the
 # volume, excitation = two small fully connected layers (ReLU between them, logistic sigmoid after),
 # the feature map scaled channel-wise by the gate, and an optional residual tensor added.
+# Relative to the paper itself this block is "parity unpinned" (the paper prints neither its definition nor
+# any value of it); the functions are pinned by the mathematics of this definition (tests/test_oracle_pins.py).
 
 def se_gate(m, w1, b1, w2, b2):
     """m [N,C] -> (e [N,C] in (0,1), h [N,Cr]):  h = max(0, W1 m + b1),  e = sigmoid(W2 h + b2)."""
