@@ -479,6 +479,8 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     lamp_tensor_desc hd = nt.td(1, C1, C1);
     const void* top = L > 1 ? lay.d2[0].y : lay.e2[0].y;
     hd.ldc = L > 1 ? lay.d2[0].ldy : lay.e2[0].ldy;
+    // the matrix-core head normalises on load only where its 32-voxel groups stay inside one sample
+    const bool head_norm = ((int64_t)u->d * u->h * u->w) % 32 == 0;
     if (phase != 2) {
         if ((st = encoder_fwd(nt, lay, first, L, P, pbase, x)) != LAMP_OK) return st;
         const void* cur = lay.e2[L - 1].y;
@@ -491,11 +493,11 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
             if (st != LAMP_OK) return st;
             // inference: the last block's output feeds only the head, which normalises while it loads
             st = block_fwd(nt, l, 2 * C, ldc, lay.skip[l - 1], C, P, pi + 2, lay.d1[l - 1], lay.d2[l - 1],
-                           lay.vcat ? lay.up[l - 1] : nullptr, bwd || l > 1);
+                           lay.vcat ? lay.up[l - 1] : nullptr, bwd || l > 1 || !head_norm);
             if (st != LAMP_OK) return st;
             cur = lay.d2[l - 1].y;
         }
-        if (!bwd && L > 1) {
+        if (!bwd && L > 1 && head_norm) {
             const int pc = per_conv(u), pi2 = dec_pi(u, 1) - pbase + 2 + pc;   // the last block's second conv
             lamp_norm_in hn{lay.d2[0].stats, u->affine ? (const float*)P[pi2 + 1] : nullptr,
                             u->affine ? (const float*)P[pi2 + 2] : nullptr, C1, 1};
