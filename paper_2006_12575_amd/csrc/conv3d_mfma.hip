@@ -1116,6 +1116,10 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
     a.tiles_total = a.tiles_per_n * xd->n;
     const int S = wgrad_slots(xd, dzd);
     a.tiles_per_wg = (a.tiles_total + S - 1) / S;
+    // one slot and nothing to accumulate onto: the only partial IS the result (wide layers on small volumes,
+    // whose dW runs to hundreds of megabytes), so the kernel writes it in place and no second pass is needed
+    const bool direct = S == 1 && beta == 0.f;
+    if (direct) a.part = dw;
     a.zero16 = device_zero16();
     if (!a.zero16) return LAMP_ERR_HIP;
     const int cob = (dzd->c % 64 == 0) ? 2 : 1;
@@ -1137,6 +1141,7 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
         hipLaunchKernelGGL((conv3d_wgrad_kernel<1>), grid, dim3(512), WG_LDS_BYTES, s, a);
     }
     LAMP_CHECK_LAUNCH();
+    if (direct) return LAMP_OK;
     return launch_reduce_partials((const float*)ws, S, (int64_t)dzd->c * 27 * xd->c, dw, beta, s);
 }
 
