@@ -660,6 +660,8 @@ lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const l
     const int64_t O = (int64_t)xd->c * 8 * dyd->c;
     CtWArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dy = (const bf16_t*)dy; a.ldy = dyd->ldc; a.part = (float*)ws;
+    const bool direct = S == 1 && beta == 0.f;   // the only partial is the result: written in place
+    if (direct) a.part = dwt;
     a.zero16 = device_zero16();
     if (!a.zero16) return LAMP_ERR_HIP;
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c;
@@ -674,6 +676,7 @@ lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const l
     dim3 grid(S, (xd->c + 63) / 64, dyd->c / 32);
     hipLaunchKernelGGL(convtr_wgrad_mfma_kernel, grid, dim3(256), 2 * CTW_STAGE, s, a);
     LAMP_CHECK_LAUNCH();
+    if (direct) return LAMP_OK;
     return launch_reduce_partials((const float*)ws, S, O, dwt, beta, s);
 }
 
