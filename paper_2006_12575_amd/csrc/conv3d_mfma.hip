@@ -558,17 +558,19 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
     return tiles8 >= 512 ? 8 : 4;
 }
 
-// Kernel choice.  The ring kernel wins where every CU gets a long run of 64-input-channel tiles; the
-// tiled kernel (two waves per SIMD, twice the voxels per weight byte) copes better with short walks,
-// 32-channel outputs and more input channels.  LAMP_CONV_KERNEL=ring|tile forces one for experiments.
+// Kernel choice.  The tiled kernel (two waves per SIMD, twice the voxels per weight byte) serves every
+// shape.  The ring kernel was the faster one on long runs of 64-input-channel tiles until the tiled
+// kernel got its weights as a ready LDS image and the XCD-aware walk; it now trails it by 2-6 % there
+// (and by more elsewhere) and is kept for comparison: LAMP_CONV_KERNEL=ring selects it wherever its
+// shape constraints hold.
 static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
     static int forced = -1;
     if (forced < 0) {
         const char* e = getenv("LAMP_CONV_KERNEL");
         forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
     }
-    const int64_t tiles4 = (int64_t)zd->n * ((zd->d + 3) / 4) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
-    return forced == 1 || (forced == 0 && zd->c % 64 == 0 && xd->c == 64 && tiles4 >= 2048);
+    (void)xd; (void)zd;
+    return forced == 1;
 }
 
 // ---- many small volumes: one packed volume ---------------------------------------------------------
