@@ -697,7 +697,7 @@ static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
     tile_dims(zd, 4, td, th, tw);
     const int64_t wgs = (int64_t)zd->n * td * th * tw * (zd->c / 64);
     const int nchunks = xd->c / 16;
-    if (wgs > 128 || nchunks < 4) return 1;
+    if (wgs > 128 || nchunks < 8) return 1;   // measured: with 64 input channels the split costs more than it brings
     int S = (int)(256 / wgs);
     if (S > nchunks / 2) S = nchunks / 2;
     if (S < 2) return 1;
