@@ -999,13 +999,15 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         wl.zrel[i] = ((d * a.H + h) * a.W + w) * a.lddz + hf * 32 + cp * 8;
         wl.zpk[i] = d | (h << 8) | (w << 16);
     }
+    // tiles are numbered d-fastest: consecutive tiles of a workgroup's walk share two of their four halo
+    // d-slices, which the second one then finds in the XCD's L2
     auto tile_coords = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
+        d0 = (r % a.tiles_d) * WTD;
+        r /= a.tiles_d;
         w0 = (r % a.tiles_w) * WTW;
-        r /= a.tiles_w;
-        h0 = (r % a.tiles_h) * WTH;
-        d0 = (r / a.tiles_h) * WTD;
+        h0 = (r / a.tiles_w) * WTH;
     };
 
     // one tile's copies + multiply; `cur` selects the LDS stage holding `tile`
