@@ -204,7 +204,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (TDT == 8) {
         // ---- multiply, 8-deep tile: the group is the in-plane row G = kh.  A wave owns 4 d-slices of one
-        // (2 h-rows x 16 w) patch; for a tap column kw the input slice s = d + kd serves the output slices
+        // (2 h-rows x 16 w) block; for a tap column kw the input slice s = d + kd serves the output slices
         // d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6 slice fragments and 3*COB weight fragments
         // feed 12*COB MFMAs.  The weight fragments and the first two slices of the next column are fetched
         // while this one is multiplied.
@@ -254,7 +254,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * 2 * HW * 16);
+        for (int vb = 0; vb < NVB; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * HW * 16);
     };
     load_frags(0, 0);
 #pragma unroll
@@ -309,17 +309,19 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const int tile_lo = xcd * a.tiles_per_xcd;
     const int tile_hi = min(tile_lo + a.tiles_per_xcd, a.tiles_total);
 
-    // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read is serviced
-    // for lanes {0-7,24-31}, {8-15,16-23} (and the same in the upper half) together, so those
-    // pairs must fall into opposite 128-byte halves of the bank space: groups of 8 lanes take
-    // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15).
+    // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read runs at full rate
+    // (measured: 4 cycles per wave instead of 8) when the 8-lane groups {0-7,24-31} and {8-15,16-23}
+    // (and the same in the upper half) fall into opposite 128-byte halves of the bank space AND all
+    // four groups start at the same offset modulo 128 bytes.  Groups of 8 lanes take (row0,w0-7)
+    // (row1,w0-7) (row1,w8-15) (row0,w8-15), and the two rows of a block are h and h+4: their distance,
+    // 4 halo rows of 288 bytes, is 128 modulo 256, where adjacent rows would differ by 32 modulo 128.
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
-    // this wave's part of the tile.  4-deep tile: d-slice ds, h-rows hs*4 .. hs*4+3 (two blocks).  8-deep
-    // tile: d-slices 4*ds .. 4*ds+3 (one block each) of the h-row pair hs.
+    // this wave's part of the tile.  4-deep tile: d-slice ds, h-row pairs (2*hs + vb, 2*hs + vb + 4) for the
+    // two blocks vb.  8-deep tile: d-slices 4*ds .. 4*ds+3 (one block each) of the h-row pair (hs, hs + 4).
     const int ds = TDT == 8 ? (wv & 1) : wv % TDT, hs = TDT == 8 ? (wv >> 1) : wv / TDT;
-    const uint32_t b_base = TDT == 8 ? (uint32_t)(half * PLANE_BYTES + ((4 * ds * HH + 2 * hs + bh) * HW + bw) * 16)
-                                     : (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB * 2 + bh) * HW + bw) * 16);
+    const uint32_t b_base = TDT == 8 ? (uint32_t)(half * PLANE_BYTES + ((4 * ds * HH + hs + 4 * bh) * HW + bw) * 16)
+                                     : (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB + 4 * bh) * HW + bw) * 16);
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
     // ---- per-lane constants of the register-free global -> LDS copies
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             float* zp = a.zpart + (int64_t)blockIdx.z * ((int64_t)a.N * a.D * a.H * a.W) * a.Cout;
 #pragma unroll
             for (int vb = 0; vb < NVB; ++vb) {
-                const int gh = h0 + hs * NVB * 2 + vb * 2 + bh, gw = w0 + bw;
+                const int gh = h0 + hs * NVB + vb + 4 * bh, gw = w0 + bw;
                 if (gd0 < a.D && gh < a.H && gw < a.W) {
                     float* row = zp + ((((int64_t)n * a.D + gd0) * a.H + gh) * a.W + gw) * a.Cout + co0 + half * 4;
 #pragma unroll
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int rg8 = row >> 3;
                 const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
                 const int gd = TDT == 8 ? gd0 + vb : gd0;
-                const int gh = TDT == 8 ? h0 + 2 * hs + rh : h0 + hs * NVB * 2 + vb * 2 + rh, gw = w0 + rw;
+                const int gh = TDT == 8 ? h0 + hs + 4 * rh : h0 + hs * NVB + vb + 4 * rh, gw = w0 + rw;
                 const bool ok = gd < a.D && gh < a.H && gw < a.W;
                 if (ok) {
                     // streaming store: the output is not read again by this kernel and should not displace
