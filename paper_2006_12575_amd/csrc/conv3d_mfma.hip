@@ -17,6 +17,7 @@
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
 #include <stdlib.h>
 #include "internal.h"
+#include <type_traits>
 #include "repack.h"
 
 namespace lamp {
@@ -125,6 +126,11 @@ struct ConvArgs {
     // modulo 8 = blockIdx.x & 7: rotating the range a workgroup serves by its channel-block / split index
     // spreads the channel blocks of those few tiles over all eight XCDs.
     int xcd_rot;
+    // Output-channel blocks inside a one-dimensional grid: workgroup id = (walker * cb_inner + channel block) * 8 + XCD,
+    // so the workgroups that read the same tiles for different output channels are resident on the same XCD at
+    // the same time and share the input through its L2.  0: the channel block is blockIdx.y (they run one after
+    // the other when the grid exceeds the chip).
+    int cb_inner;
 };
 
 // 16-byte global -> LDS copy that bypasses registers: lane l's 16 bytes land at lds_base + 16*l
@@ -292,7 +298,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     char* wbuf0 = lds + 2 * HALO_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int co0 = blockIdx.y * (32 * COB);
+    const int cbi = a.cb_inner ? (int)(blockIdx.x >> 3) % a.cb_inner : (int)blockIdx.y;   // output-channel block
+    const int co0 = cbi * (32 * COB);
     const int nchunks = a.Cin >> 4;
     const int c_lo = SPLIT ? (int)blockIdx.z * a.cps : 0;
     const int c_hi = SPLIT ? min(c_lo + a.cps, nchunks) : nchunks;
@@ -305,7 +312,9 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     constexpr int WINSTR = 18 * WROWS / 64;       // wave-wide copies per kd group: 18 or 9
 
     // persistent walk over an XCD-contiguous range of tiles
-    const int xcd = (blockIdx.x + (a.xcd_rot ? blockIdx.y + blockIdx.z : 0u)) & 7, local = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+    const int xcd = (blockIdx.x + (a.xcd_rot ? blockIdx.y + blockIdx.z : 0u)) & 7;
+    const int local = a.cb_inner ? (int)(blockIdx.x >> 3) / a.cb_inner : (int)(blockIdx.x >> 3);
+    const int wg_per_xcd = a.cb_inner ? (int)(gridDim.x >> 3) / a.cb_inner : (int)(gridDim.x >> 3);
     const int tile_lo = xcd * a.tiles_per_xcd;
     const int tile_hi = min(tile_lo + a.tiles_per_xcd, a.tiles_total);
 
@@ -357,7 +366,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         return t;
     };
     constexpr int wgstride = 18 * WROWS * 8;                                       // elements of one group
-    const bf16_t* wbase = a.wp + (int64_t)blockIdx.y * nchunks * (3 * wgstride);    // + (chunk*3 + g) * wgstride
+    const bf16_t* wbase = a.wp + (int64_t)cbi * nchunks * (3 * wgstride);    // + (chunk*3 + g) * wgstride
 
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
@@ -455,10 +464,26 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
         char* patch = fbuf + wv * (32 * ROWB);
         float* sred = reinterpret_cast<float*>(fbuf + 8 * 32 * (64 * 2 + 16));
-        const int part = lane % PARTS, prow = lane / PARTS;
+        // The lane id enters the epilogue through an opaque copy: what is derived from it below would otherwise
+        // be hoisted out of the tile loop and stay in registers across the multiply loop, which has none to spare.
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int part = lane_e % PARTS, prow = lane_e / PARTS;
         float csum[8], csq[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; }
+        // Where this lane's 16-byte pieces go.  Its 8 channels, and with them the tensor and the channel
+        // stride, are fixed; the tile origin is wave-uniform; what is left per store is a small offset
+        // inside the tile.  Tiles that lie inside the volume (all but the ragged rim) skip the bounds tests.
+        const int ch = co0 + part * 8;
+        const bool second = ch >= a.zsplit;
+        const int ldo = second ? a.ldz2 : a.ldz;
+        const int hb0 = TDT == 8 ? h0 + hs : h0 + hs * NVB;
+        bf16_t* const tbase = (second ? a.z2 + (ch - a.zsplit) : a.z + ch) +
+                              ((((int64_t)n * a.D + gd0) * a.H + hb0) * a.W + w0) * ldo;
+        const int vbvox = TDT == 8 ? a.H * a.W : a.W;   // voxels from block vb to vb + 1 (offsets inside a tile fit 32 bits)
+        const bool full = gd0 + (TDT == 8 ? NVB : 1) <= a.D && h0 + TH <= a.H && w0 + TW <= a.W;
+        const bool want_stats = a.part != nullptr;
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
@@ -475,25 +500,28 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
                 const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
                 const int rg8 = row >> 3;
-                const int rw = (row & 7) + 8 * (rg8 >> 1), rh = (rg8 ^ (rg8 >> 1)) & 1;
-                const int gd = TDT == 8 ? gd0 + vb : gd0;
-                const int gh = TDT == 8 ? h0 + hs + 4 * rh : h0 + hs * NVB + vb + 4 * rh, gw = w0 + rw;
-                const bool ok = gd < a.D && gh < a.H && gw < a.W;
+                const int rw = (row & 7) + 8 * (rg8 >> 1), rh = 4 * ((rg8 ^ (rg8 >> 1)) & 1);
+                bool ok = true;
+                if (!full) {
+                    const int gd = TDT == 8 ? gd0 + vb : gd0;
+                    const int gh = TDT == 8 ? hb0 + rh : hb0 + vb + rh, gw = w0 + rw;
+                    ok = gd < a.D && gh < a.H && gw < a.W;
+                }
                 if (ok) {
                     // streaming store: the output is not read again by this kernel and should not displace
                     // the input lines that the next chunk passes and the neighbouring tiles still need
                     typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
                     const u32x4 sv = {q.x, q.y, q.z, q.w};
-                    const int64_t vlin = (((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw;
-                    const int ch = co0 + part * 8;
-                    bf16_t* dst = ch < a.zsplit ? a.z + vlin * a.ldz + ch : a.z2 + vlin * a.ldz2 + (ch - a.zsplit);
+                    bf16_t* dst = tbase + (vb * vbvox + rh * a.W + rw) * ldo;
                     __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(dst));
-                    const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+                    if (want_stats) {
+                        const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
-                        csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
-                        csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
+                        for (int e = 0; e < 4; ++e) {
+                            const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
+                            csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
+                            csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
+                        }
                     }
                 }
             }
@@ -524,7 +552,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 for (int w8 = 0; w8 < 8; ++w8) v += sred[(w8 * 64 + c) * 2 + k];
                 a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
             }
-            if (a.counts && tid == 0 && n == 0 && blockIdx.y == 0)
+            if (a.counts && tid == 0 && n == 0 && cbi == 0)
                 a.counts[tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
         }
         __syncthreads();  // the patch buffer is the next stage's prefetch target
@@ -541,6 +569,9 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
     if (bias) return false;
     if (xd->c % 16 || zd->c % 32 || xd->ldc % 8 || zd->ldc % 8) return false;
+    // element offsets inside a tile's halo (10 slices of H x W voxels) are kept in 32 bits
+    const int64_t ldmax = xd->ldc > zd->ldc ? xd->ldc : zd->ldc;
+    if ((int64_t)10 * zd->h * zd->w * ldmax >= ((int64_t)1 << 31)) return false;
     return true;
 }
 
@@ -811,6 +842,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     dim3 grid(wgx, zd->c / (32 * cob));
     a.zpart = nullptr; a.cps = 0;
     a.xcd_rot = a.tiles_total < 32 ? 1 : 0;
+    a.cb_inner = 0;
     a.xdelta = two_in ? (int64_t)((const bf16_t*)parts->x2 - (const bf16_t*)x) : 0;
     a.xsplit = two_in ? parts->x_c1 / 16 : 0x7fffffff;
     a.z2 = two_out ? (bf16_t*)parts->z2 : nullptr;
@@ -827,6 +859,12 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         lamp_status st = launch_igemm<2, 4, true>(a, grid, s);
         if (st != LAMP_OK) return st;
         return launch_splitk_reduce(a.zpart, S, zd, z, eps, stats_out, sws, stats_ws_bytes(zd), s, a.z2, a.ldz2, a.zsplit);
+    }
+    static const bool cb_outer = getenv("LAMP_CONV_CB_OUTER") != nullptr;
+    if (!a.xcd_rot && grid.y > 1 && !cb_outer) {
+        a.cb_inner = (int)grid.y;
+        grid.x *= grid.y;
+        grid.y = 1;
     }
     lamp_status st;
     if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
