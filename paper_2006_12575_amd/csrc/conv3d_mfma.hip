@@ -1137,6 +1137,9 @@ bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dz
     if (xd->dtype != LAMP_BF16) return false;
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
     if (xd->c % 32 || dzd->c % 32 || xd->ldc % 8 || dzd->ldc % 8) return false;
+    // element offsets inside a tile's halo (4 slices of H x W voxels) are kept in 32 bits
+    const int64_t ldmax = xd->ldc > dzd->ldc ? xd->ldc : dzd->ldc;
+    if ((int64_t)4 * xd->h * xd->w * ldmax + 4096 >= ((int64_t)1 << 31)) return false;
     return true;
 }
 

@@ -144,7 +144,7 @@ __device__ __forceinline__ uint32_t head_pack_bf16(float lo, float hi) { return 
 // NORM: x is a raw conv output; InstanceNorm (+ ReLU) is applied while it is loaded, rounded to bf16 as the
 // stored activation would be (every 32-voxel group lies inside one sample: Vs % 32 == 0).
 template <int MODE, int NCB, bool NORM = false>
-__global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
+__global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
                                                         const float* __restrict__ bh, int K, int C, int64_t Vtot,
                                                         const int32_t* __restrict__ labels, float* __restrict__ logits,
                                                         bf16_t* __restrict__ dx, int lddx, float* __restrict__ loss_part,
@@ -208,6 +208,21 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
     const int64_t gpw = (groups + nwaves - 1) / nwaves;
     const int64_t g_lo = NORM ? wid * gpw : wid, g_hi = NORM ? (g_lo + gpw < groups ? g_lo + gpw : groups) : groups;
     const int64_t g_step = NORM ? 1 : nwaves;
+    // the activations of a group are fetched one group ahead (not where that would spill: the backward
+    // instantiation for 64 channels is at its register limit for three workgroups per CU)
+    constexpr bool AHEAD = !(MODE == 1 && NCB == 2);
+    uint4 xnext[AHEAD ? 2 * NCB : 1];
+    auto fetch_x = [&](int64_t g, auto& q) __attribute__((always_inline)) {
+        const int64_t v = g * 32 + l32;
+        const bool ok = g < g_hi && v < Vtot;
+        const bf16_t* xp = x + (ok ? v : 0) * ldx;
+#pragma unroll
+        for (int kc = 0; kc < 2 * NCB; ++kc) {
+            q[kc] = make_uint4(0, 0, 0, 0);
+            if (kc < CK && ok) q[kc] = *reinterpret_cast<const uint4*>(xp + 16 * kc + 8 * half);
+        }
+    };
+    if constexpr (AHEAD) fetch_x(g_lo, xnext);
     for (int64_t g = g_lo; g < g_hi; g += g_step) {
         const int64_t v = g * 32 + l32;
         const bool valid = v < Vtot;
@@ -220,16 +235,20 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
                 __builtin_amdgcn_wave_barrier();
             }
         }
-        const bf16_t* xp = x + (valid ? v : 0) * ldx;
         uint4 xq[2 * NCB];
+        if constexpr (AHEAD) {
+#pragma unroll
+            for (int kc = 0; kc < 2 * NCB; ++kc) xq[kc] = xnext[kc];
+            fetch_x(g + g_step, xnext);
+        } else {
+            fetch_x(g, xq);
+        }
         hf32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < 2 * NCB; ++kc) {
-            xq[kc] = make_uint4(0, 0, 0, 0);
             if (kc < CK) {
-                if (valid) xq[kc] = *reinterpret_cast<const uint4*>(xp + 16 * kc + 8 * half);
                 if (NORM) {
                     uint32_t r4[4] = {xq[kc].x, xq[kc].y, xq[kc].z, xq[kc].w};
                     float na[8], nb[8];
@@ -282,12 +301,14 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
                 if (cls[i] < K) m = lg[i] > m ? lg[i] : m;
             const float mo = __shfl_xor(m, 32);
             m = mo > m ? mo : m;
-            float se = 0.f;
+            float se = 0.f, ex[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (cls[i] < K) se += expf(lg[i] - m);
+            for (int i = 0; i < 8; ++i) {
+                ex[i] = cls[i] < K ? expf(lg[i] - m) : 0.f;
+                se += ex[i];
+            }
             se += __shfl_xor(se, 32);
-            const float lse = m + logf(se);
+            const float lse = m + logf(se), rse = 1.0f / se;
             const int lab = valid ? labels[v] : -1;
             float ll = 0.f, dl[8];
 #pragma unroll
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(256, NCB <= 2 ? 3 : 1) void head_mfma_kernel(const 
                 dl[i] = 0.f;
                 if (cls[i] < K && valid) {
                     if (cls[i] == lab) ll = lg[i];
-                    dl[i] = (expf(lg[i] - lse) - (cls[i] == lab ? 1.f : 0.f)) * invV;
+                    dl[i] = (ex[i] * rse - (cls[i] == lab ? 1.f : 0.f)) * invV;
                 }
                 dbsum[i] += dl[i];
             }
@@ -416,9 +437,13 @@ static bool head_mfma_ok(const lamp_tensor_desc* xd, const void* x, const lamp_n
     if (logits && !aligned16(logits)) return false;
     return true;
 }
-static int head_mfma_blocks(int64_t V) {
+// Workgroups of the matrix-core head: every one walks the same number of voxel groups, so the grid is at most
+// what is resident at once (`per_cu` workgroups on each of the 256 CUs); a partial second round would leave
+// most of the chip idle for half of the run.  4 * blocks <= 4096 partial slots.
+static int head_mfma_blocks(int64_t V, int per_cu = 4) {
     int64_t b = ((V + 31) / 32 + 3) / 4;
-    return (int)(b > 1024 ? 1024 : (b < 1 ? 1 : b));
+    const int64_t cap = 256 * (int64_t)per_cu;
+    return (int)(b > cap ? cap : (b < 1 ? 1 : b));
 }
 
 static int head_blocks(int64_t V) {
@@ -429,7 +454,7 @@ static int head_splits(int64_t V) {
     int64_t s = (V + 511) / 512;
     return (int)(s > 4096 ? 4096 : (s < 1 ? 1 : s));
 }
-static int head_mfma_blocks(int64_t V);
+static int head_mfma_blocks(int64_t V, int per_cu);
 // partial slots of the weight gradient the workspace must hold: the generic path's splits or one per wave
 // of the matrix-core path
 static int head_wslots(int64_t V) {
@@ -554,8 +579,11 @@ lamp_status lamp::head_ce_run(const lamp_tensor_desc* xd, const void* x, const l
         // one pass: logits, loss, dx, per-wave partials of dWh and dbh (the dlogits buffer is not used)
         float* bpart = (float*)cv.take((size_t)4096 * K * sizeof(float));
         if (!cv.ok()) return LAMP_ERR_WORKSPACE;
-        const int nbm = head_mfma_blocks(Vt);   // 4 * nbm <= 4096 partial slots
-        if (C <= 64)
+        const int nbm = head_mfma_blocks(Vt, C <= 32 ? 4 : C <= 64 ? 3 : 4);   // 4 * nbm <= 4096 partial slots
+        if (C <= 32)
+            hipLaunchKernelGGL((head_mfma_kernel<1, 1>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
+                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
+        else if (C <= 64)
             hipLaunchKernelGGL((head_mfma_kernel<1, 2>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
                                bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
         else
