@@ -39,6 +39,8 @@ CONV_SHAPES = [
     (1, 3, 5, 33, 64, 128),
     (1, 12, 20, 36, 64, 64),
     (1, 4, 8, 16, 96, 96),    # multiple of 32 but not of 64
+    (1, 16, 32, 32, 128, 128),  # 32 tiles x 2 output-channel blocks: the blocks of a tile side by side in the grid
+    (1, 16, 32, 48, 96, 96),    # 48 tiles x 3 blocks of 32
 ]
 
 
