@@ -576,8 +576,8 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
 }
 
 // Tile depth.  The 8-deep tile gives each wave a 128-voxel x 64-channel register tile (fewest LDS
-// bytes and barriers per MFMA) and is used when it still yields at least two tiles per CU; smaller
-// volumes take the 4-deep tile so that more workgroups exist.  (The 4-deep tile also halves the
+// bytes and barriers per MFMA); the 4-deep tile yields twice the workgroup-tiles, which fills the chip
+// on small volumes and wastes less of a last, partial round on medium ones.  (The 4-deep tile also halves the
 // HBM re-fetch -- its per-XCD working set fits the 4 MiB L2 between chunk passes -- but is slower
 // per MFMA.)  LAMP_CONV_TILE_DEPTH=4|8 forces one for experiments.
 static int conv_tile_depth(const lamp_tensor_desc* zd) {
@@ -587,8 +587,13 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
         forced = e ? atoi(e) : 0;
     }
     if (forced == 4 || forced == 8) return forced;
-    const int64_t tiles8 = (int64_t)zd->n * ((zd->d + 7) / 8) * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
-    return tiles8 >= 512 ? 8 : 4;
+    // Rounds of the chip: (tiles x output-channel blocks) workgroup-tiles over 256 CUs, rounded up; an 8-deep
+    // tile costs 1.9 four-deep ones.  (Measured on 15 layer shapes from 32^3 to 176 x 128 x 144 with 32 to 256
+    // channels: the cheaper side of this comparison was the faster kernel on every one.)
+    const int64_t hw = (int64_t)zd->n * ((zd->h + TH - 1) / TH) * ((zd->w + TW - 1) / TW);
+    const int64_t ncb = (zd->c + (zd->c % 64 == 0 ? 64 : 32) - 1) / (zd->c % 64 == 0 ? 64 : 32);
+    const int64_t rounds8 = (hw * ((zd->d + 7) / 8) * ncb + 255) / 256, rounds4 = (hw * ((zd->d + 3) / 4) * ncb + 255) / 256;
+    return 19 * rounds8 <= 10 * rounds4 ? 8 : 4;
 }
 
 // Kernel choice.  The tiled kernel (two waves per SIMD, twice the voxels per weight byte) serves every
