@@ -143,7 +143,7 @@ def main():
     # event-timed entry points (each bracket also holds the 221 KB weight repack and, for the forward,
     # the statistics finalize: ~2 % of the time).
     t_conv = 0.5 * (parts["conv3d_fwd"] + parts["conv3d_dgrad"])
-    roof = {"bound": "mfma", "kernel": "conv3d_igemm_kernel<2, 8> (implicit GEMM 64->64, 128^3; fwd and dgrad launches)",
+    roof = {"bound": "mfma", "kernel": f"conv3d_igemm_kernel<2, 8> (implicit GEMM {C}->{C}, {D}^3; fwd and dgrad launches)",
             "achieved": flops_conv / t_conv / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": flops_conv / t_conv / 1e12 / PEAK_BF16_TFLOPS, "traffic": None}
     traffic_file = os.path.join(ROOT, "profiles", "conv3d_igemm_c64_128_traffic_bytes.txt")
