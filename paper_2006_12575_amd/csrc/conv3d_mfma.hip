@@ -40,9 +40,9 @@ template <int TDT> struct Geo {
     static constexpr int HALO_BYTES = 2 * PLANE_BYTES;       // one 16-channel chunk
     static constexpr int HBLK = (HALO_VOX + 63) / 64;        // wave-wide copies per halo plane: 29 / 17
     static constexpr int HJ = (HBLK + 7) / 8;                // halo blocks per wave: 4 / 3
-    // epilogue scratch (8 wave patches of 32 rows x 144 bytes + channel sums): the 8-deep tile reuses
+    // epilogue scratch (8 wave patches of 32 rows x 144 bytes + channel sums of the 4 lane rows of each wave): the 8-deep tile reuses
     // the halo buffer of the finished stage, the 4-deep one is too small for that and gets its own
-    static constexpr int EPI_BYTES = 8 * 32 * 144 + 8 * 64 * 2 * 4;
+    static constexpr int EPI_BYTES = 8 * 32 * 144 + 8 * 4 * 64 * 2 * 4;
     static constexpr bool EPI_OWN = HALO_BYTES < EPI_BYTES;
     static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? EPI_BYTES : 0);
 };
@@ -53,6 +53,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+// v of the lane N places further round in its row of 16 lanes (a DPP row rotation).
+template <int N> __device__ __forceinline__ float row_ror(float v) {
+    const int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xF, 0xF, false);
+    return __builtin_bit_cast(float, r);
 }
 __device__ __forceinline__ bf16x8 lds_frag(const char* p) {
     uint4 q = *reinterpret_cast<const uint4*>(p);
@@ -528,20 +533,25 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             __builtin_amdgcn_wave_barrier();
         }
         if (a.part) {
-            // lanes with equal `part` hold the same 8 channels: fold them (lane bits above log2(PARTS))
+            // Lanes with equal `part` hold the same 8 channels.  Inside a row of 16 lanes they are folded by
+            // rotations of the row (data-parallel primitives: no LDS traffic, where lane exchanges through the
+            // LDS cost more than the tile's whole transpose); the 4 rows of a wave and the 8 waves are added by
+            // the threads that write the tile's partial.
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-#pragma unroll
-                for (int m = PARTS; m < 64; m <<= 1) {
-                    csum[e] += __shfl_xor(csum[e], m);
-                    csq[e] += __shfl_xor(csq[e], m);
+                csum[e] += row_ror<8>(csum[e]);
+                csq[e] += row_ror<8>(csq[e]);
+                if constexpr (PARTS == 4) {
+                    csum[e] += row_ror<4>(csum[e]);
+                    csq[e] += row_ror<4>(csq[e]);
                 }
             }
-            if (lane < PARTS) {
+            if ((lane_e & 15) < PARTS) {   // then part == lane & 15
+                float* dst = sred + ((wv * 4 + (lane_e >> 4)) * 64 + part * 8) * 2;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    sred[(wv * 64 + part * 8 + e) * 2 + 0] = csum[e];
-                    sred[(wv * 64 + part * 8 + e) * 2 + 1] = csq[e];
+                    dst[2 * e + 0] = csum[e];
+                    dst[2 * e + 1] = csq[e];
                 }
             }
             __syncthreads();
@@ -549,7 +559,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int c = tid >> 1, k = tid & 1;
                 float v = 0.f;
 #pragma unroll
-                for (int w8 = 0; w8 < 8; ++w8) v += sred[(w8 * 64 + c) * 2 + k];
+                for (int q = 0; q < 32; ++q) v += sred[(q * 64 + c) * 2 + k];
                 a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
             }
             if (a.counts && tid == 0 && n == 0 && cbi == 0)
