@@ -54,6 +54,10 @@ lamp_status head_ce_run(const lamp_tensor_desc* xd, const void* x, const lamp_no
 // ---- conv3d_mfma.hip ------------------------------------------------------------------------
 // Matrix-core implicit-GEMM paths; each returns LAMP_ERR_UNSUPPORTED when the shape is not one
 // they serve, and the caller falls back to the generic kernels.
+// InstanceNorm + ReLU of a raw conv output z (statistics and affine parameters in xnorm, all channels) fused with
+// the 2x2x2 max-pool of the result: writes the activated tensor to yfull (channel stride ldyf) and the pooled one to y.
+lamp_status inorm_relu_maxpool2(const lamp_tensor_desc* xd, const void* z, const lamp_norm_in* xnorm, void* yfull, int ldyf,
+                                const lamp_tensor_desc* yd, void* y, hipStream_t s);
 bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm,
                          const float* bias);
 size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats);

@@ -8,7 +8,8 @@ namespace lamp {
 
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void maxpool2_fwd_kernel(const T* __restrict__ x, int ldx, NormIn nm, T* __restrict__ y,
-                                                           int ldy, int N, int Do, int Ho, int Wo, int C) {
+                                                           int ldy, int N, int Do, int Ho, int Wo, int C,
+                                                           T* __restrict__ yfull = nullptr, int ldyf = 0) {
     const int CV = C / VEC;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t total = (int64_t)N * Do * Ho * Wo * CV;
@@ -25,6 +26,33 @@ __global__ __launch_bounds__(256) void maxpool2_fwd_kernel(const T* __restrict__
     float m[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) m[i] = -INFINITY;
+    if (yfull) {
+        // also write the activated input: all channels normalised, the coefficients of this thread's channels
+        // fetched once, the two voxels of a w pair stored back to back
+        float a[VEC], b[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) norm_coeffs(nm, n, cv * VEC + e, a[e], b[e]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i = t >> 1, j = t & 1;
+            const int64_t iv = (((int64_t)n * D + 2 * d + i) * H + 2 * h + j) * W + 2 * w;
+            float v0[VEC], v1[VEC];
+            Vec<T, VEC>::load(x + iv * ldx + cv * VEC, v0);
+            Vec<T, VEC>::load(x + (iv + 1) * ldx + cv * VEC, v1);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                float u0 = norm_u(v0[e], a[e], b[e]), u1 = norm_u(v1[e], a[e], b[e]);
+                if (nm.relu) { u0 = u0 > 0.f ? u0 : 0.f; u1 = u1 > 0.f ? u1 : 0.f; }
+                v0[e] = io<T>::rnd(u0); v1[e] = io<T>::rnd(u1);
+                const float mm = v0[e] > v1[e] ? v0[e] : v1[e];
+                m[e] = mm > m[e] ? mm : m[e];
+            }
+            Vec<T, VEC>::store(yfull + iv * ldyf + cv * VEC, v0);
+            Vec<T, VEC>::store(yfull + (iv + 1) * ldyf + cv * VEC, v1);
+        }
+        Vec<T, VEC>::store(y + ov * ldy + cv * VEC, m);
+        return;
+    }
     for (int t = 0; t < 8; ++t) {
         int i = t >> 2, j = (t >> 1) & 1, k = t & 1;
         const T* p = x + ((((int64_t)n * D + 2 * d + i) * H + 2 * h + j) * W + 2 * w + k) * ldx + cv * VEC;
@@ -95,6 +123,27 @@ static lamp_status pool_shapes(const lamp_tensor_desc* xd, const lamp_tensor_des
     if (yd->n != xd->n || yd->d * 2 != xd->d || yd->h * 2 != xd->h || yd->w * 2 != xd->w || yd->c != xd->c)
         return LAMP_ERR_SHAPE;
     if (xd->dtype != yd->dtype) return LAMP_ERR_DTYPE;
+    return LAMP_OK;
+}
+
+// InstanceNorm + ReLU of a raw conv output and the max-pool of the result in one pass: writes the activated
+// tensor (yfull, channel stride ldyf) and its pooled version.  Same arithmetic and rounding as the two
+// separate passes; one read of the full-resolution tensor less.
+lamp_status lamp::inorm_relu_maxpool2(const lamp_tensor_desc* xd, const void* z, const lamp_norm_in* xnorm, void* yfull, int ldyf,
+                                      const lamp_tensor_desc* yd, void* y, hipStream_t s) {
+    if (!xd || !yd || !z || !y || !yfull || !xnorm || !xnorm->mean_rstd) return LAMP_ERR_NULL;
+    lamp_status st = pool_shapes(xd, yd);
+    if (st != LAMP_OK) return st;
+    if ((st = norm_ok(xnorm, xd)) != LAMP_OK) return st;
+    if (xnorm->c_norm != xd->c) return LAMP_ERR_SHAPE;
+    const int vec = pick_vec(xd->dtype, xd->c, {xd->ldc, yd->ldc, ldyf}, {z, y, yfull});
+    NormIn nm = make_norm(xnorm);
+    LAMP_DISPATCH_TV(xd->dtype, vec, {
+        int64_t total = nvox(yd) * (xd->c / VEC);
+        hipLaunchKernelGGL((maxpool2_fwd_kernel<T, VEC>), dim3(cdiv(total, 256)), dim3(256), 0, s, (const T*)z, xd->ldc, nm,
+                           (T*)y, yd->ldc, yd->n, yd->d, yd->h, yd->w, xd->c, (T*)yfull, ldyf);
+    });
+    LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
 

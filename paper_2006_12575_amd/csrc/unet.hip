@@ -328,11 +328,18 @@ static lamp_status encoder_fwd(Net& nt, Layout& lay, int first, int last, const 
     int cur_c = first == 1 ? u->in_ch : nt.chan(first - 1);
     for (int l = first; l <= last; ++l) {
         const int C = nt.chan(l);
-        lamp_status st = block_fwd(nt, l, cur_c, cur_c, cur, C, P, enc_pi(u, l) - pbase, lay.e1[l - 1], lay.e2[l - 1]);
+        // Above the bottom level the block's second InstanceNorm + ReLU is applied by the pooling pass, which
+        // writes the activated tensor (the skip) and its pooled version from one read of the raw conv output.
+        const bool pooled = l < nt.L;
+        const int pi = enc_pi(u, l) - pbase;
+        lamp_status st = block_fwd(nt, l, cur_c, cur_c, cur, C, P, pi, lay.e1[l - 1], lay.e2[l - 1], nullptr, !pooled);
         if (st != LAMP_OK) return st;
-        if (l < nt.L) {
-            lamp_tensor_desc xd = nt.td(l, C, lay.e2[l - 1].ldy), yd = nt.td(l + 1, C, C);
-            st = lamp_maxpool2_fwd(&xd, lay.e2[l - 1].y, nullptr, &yd, lay.pooled[l - 1], nt.s);
+        if (pooled) {
+            const int pc = per_conv(u);
+            lamp_norm_in zn{lay.e2[l - 1].stats, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
+                            u->affine ? (const float*)P[pi + pc + 2] : nullptr, C, 1};
+            lamp_tensor_desc zd = nt.td(l, C, C), yd = nt.td(l + 1, C, C);
+            st = inorm_relu_maxpool2(&zd, lay.e2[l - 1].z, &zn, lay.e2[l - 1].y, lay.e2[l - 1].ldy, &yd, lay.pooled[l - 1], nt.s);
             if (st != LAMP_OK) return st;
             cur = lay.pooled[l - 1];
         }
