@@ -143,7 +143,8 @@ __device__ __forceinline__ uint32_t head_pack_bf16(float lo, float hi) { return 
 // NCB: 32-channel blocks the instantiation holds (C <= 32 * NCB).
 // NORM: x is a raw conv output; InstanceNorm (+ ReLU) is applied while it is loaded, rounded to bf16 as the
 // stored activation would be (every 32-voxel group lies inside one sample: Vs % 32 == 0).
-template <int MODE, int NCB, bool NORM = false>
+// NI: classes a lane works on (4 serves up to 8 classes: 4*half + i; 8 serves 16).
+template <int MODE, int NCB, bool NORM = false, int NI = 8>
 __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfma_kernel(const bf16_t* __restrict__ x, int ldx, const bf16_t* __restrict__ wh,
                                                         const float* __restrict__ bh, int K, int C, int64_t Vtot,
                                                         const int32_t* __restrict__ labels, float* __restrict__ logits,
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
     int cls[8];
     float bias[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NI; ++i) {
         cls[i] = 8 * (i >> 2) + 4 * half + (i & 3);
         bias[i] = (bh && cls[i] < K) ? bh[cls[i]] : 0.f;
     }
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
 #pragma unroll
         for (int r = 0; r < 16; ++r) accw[cb][r] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dbsum[i] = 0.f;
+    for (int i = 0; i < NI; ++i) dbsum[i] = 0.f;
     float lsum = 0.f;
     __shared__ __attribute__((aligned(16))) float nco[NORM ? 4 : 1][2][NORM ? 32 * NCB : 4];   // per wave: a[c], b[c] of its current sample
     int cur_n = -1;
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
         }
         float lg[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lg[i] = acc[i] + bias[i];
+        for (int i = 0; i < NI; ++i) lg[i] = acc[i] + bias[i];
         if (logits) {
             // the group's logits are 32*K consecutive floats: pack them in LDS ([voxel][class]) and store 16 bytes
             // per lane instead of eight 4-byte pieces per lane
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
             const int64_t left = Vtot - g * 32;   // valid voxels of the group (wave-uniform)
             if (left >= 32) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
+                for (int i = 0; i < NI; ++i)
                     if (cls[i] < K) pk[l32 * K + cls[i]] = lg[i];
                 __builtin_amdgcn_wave_barrier();
                 float* dst = logits + g * 32 * K;
@@ -290,29 +291,29 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
                 __builtin_amdgcn_wave_barrier();
             } else if (valid) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
+                for (int i = 0; i < NI; ++i)
                     if (cls[i] < K) logits[v * K + cls[i]] = lg[i];
             }
         }
         if (MODE == 1) {
             float m = -3.0e38f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < NI; ++i)
                 if (cls[i] < K) m = lg[i] > m ? lg[i] : m;
             const float mo = __shfl_xor(m, 32);
             m = mo > m ? mo : m;
             float se = 0.f, ex[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < NI; ++i) {
                 ex[i] = cls[i] < K ? expf(lg[i] - m) : 0.f;
                 se += ex[i];
             }
             se += __shfl_xor(se, 32);
             const float lse = m + logf(se), rse = 1.0f / se;
             const int lab = valid ? labels[v] : -1;
-            float ll = 0.f, dl[8];
+            float ll = 0.f, dl[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < NI; ++i) {
                 dl[i] = 0.f;
                 if (cls[i] < K && valid) {
                     if (cls[i] == lab) ll = lg[i];
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
             if (wpart) {
                 // stage dlogits [voxel][class] and x [voxel][channel] (fp32) for the voxel-reduction product
 #pragma unroll
-                for (int i = 0; i < 8; ++i) dls[wv][l32][cls[i]] = dl[i];
+                for (int i = 0; i < NI; ++i) dls[wv][l32][cls[i]] = dl[i];
 #pragma unroll
                 for (int kc = 0; kc < 2 * NCB; ++kc) {
                     if (kc < CK) {
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(256, NCB == 1 ? 4 : NCB == 2 ? 3 : 1) void head_mfm
         if (bpart) {
             // fold the 32 voxel lanes of each half
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < NI; ++i) {
 #pragma unroll
                 for (int m = 1; m < 32; m <<= 1) dbsum[i] += __shfl_xor(dbsum[i], m);
                 if (l32 == 0 && cls[i] < K) bpart[(size_t)slot * K + cls[i]] = dbsum[i];
@@ -580,15 +581,19 @@ lamp_status lamp::head_ce_run(const lamp_tensor_desc* xd, const void* x, const l
         float* bpart = (float*)cv.take((size_t)4096 * K * sizeof(float));
         if (!cv.ok()) return LAMP_ERR_WORKSPACE;
         const int nbm = head_mfma_blocks(Vt, C <= 32 ? 4 : C <= 64 ? 3 : 4);   // 4 * nbm <= 4096 partial slots
-        if (C <= 32)
-            hipLaunchKernelGGL((head_mfma_kernel<1, 1>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
-                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
-        else if (C <= 64)
-            hipLaunchKernelGGL((head_mfma_kernel<1, 2>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
-                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
-        else
-            hipLaunchKernelGGL((head_mfma_kernel<1, 4>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh,
-                               bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV);
+#define LAMP_HEAD_BWD(NCB_, NI_)                                                                                                   \
+    hipLaunchKernelGGL((head_mfma_kernel<1, NCB_, false, NI_>), dim3(nbm), dim3(256), 0, s, (const bf16_t*)x, xd->ldc, (const bf16_t*)wh, \
+                       bh, K, C, Vt, labels, logits, (bf16_t*)dx, lddx, lpart, dwh ? wpart : nullptr, dbh ? bpart : nullptr, invV)
+        if (K <= 8) {   // the usual few classes: half the per-class work of a lane
+            if (C <= 32) LAMP_HEAD_BWD(1, 4);
+            else if (C <= 64) LAMP_HEAD_BWD(2, 4);
+            else LAMP_HEAD_BWD(4, 4);
+        } else {
+            if (C <= 32) LAMP_HEAD_BWD(1, 8);
+            else if (C <= 64) LAMP_HEAD_BWD(2, 8);
+            else LAMP_HEAD_BWD(4, 8);
+        }
+#undef LAMP_HEAD_BWD
         LAMP_CHECK_LAUNCH();
         if ((st = launch_reduce_partials(lpart, nbm, 1, loss, loss_beta, s)) != LAMP_OK) return st;
         if (dwh && (st = launch_reduce_partials(wpart, nbm * 4, (int64_t)K * C, dwh, beta, s)) != LAMP_OK) return st;
