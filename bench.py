@@ -12,9 +12,15 @@ the single conv block of the benchmark configuration -- Conv3d 3x3x3 (64 -> 64 c
     dW       = conv3d_wgrad(x, dz)         (fp32)
 
 Inputs are synthetic (N(0,1) activations and upstream gradient, Kaiming-normal weights), resident
-in HBM before the timed region.  Prints ONE JSON line.
+in HBM before the timed region.  Prints ONE JSON line.  Its top level is that headline workload
+(value, roofline, cpu_baseline); the object `configs` in the same line carries the other benchmark
+configurations -- the tiny fp32 net, the encoder partition at 192^3, the whole-net training step, the
+large-input inference in one pass and as sliding windows -- each timed through its network entry
+point, with the roofline of its dominant kernel (event-timed through the layer entry point on that
+layer's shape) and the CPU oracle timed on a stated small sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-configs]
+    python bench.py --workload unet_train ...      (one network workload alone, e.g. under a profiler)
 """
 from __future__ import annotations
 
@@ -40,8 +46,11 @@ def main():
     ap.add_argument("--size", type=int, default=128, help="cubic volume side (default: the benchmark's 128)")
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="headline workload only: skip the `configs` object")
+    ap.add_argument("--config-steps", type=int, default=5, help="timed steps of each workload in `configs`")
+    ap.add_argument("--config-warmup", type=int, default=2)
     ap.add_argument("--workload", default="block", choices=["block", "unet_train", "unet_infer", "sliding", "stage", "tiny", "unet_train_b64", "unet_train_b128",
-                             "unet_infer_whole", "unet_train_step", "unet_train_pipeline", "se_block"],
+                             "unet_infer_whole", "unet_train_step", "unet_train_pipeline", "se_block", "seunet_train"],
                     help="block (default): the headline conv block (config 2). The others time the network-level "
                          "entry points on the remaining configurations and report voxels/s.")
     ap.add_argument("--micro-batches", type=int, default=2, help="unet_train_pipeline: micro-batches the 2 samples are split into")
@@ -67,7 +76,10 @@ def main():
 
     L.lib()  # fails loudly when the HIP library is missing
     if args.workload != "block":
-        return net_bench(args, torch, np, S, L)
+        out = net_bench(args.workload, args, torch, np, S, L, max(1, args.steps), max(1, args.warmup),
+                        cpu=not args.no_cpu_baseline)
+        print(json.dumps(out))
+        return
     dev = "cuda:0"
     bf, f32 = torch.bfloat16, torch.float32
     N, D, C = 1, args.size, args.channels
@@ -146,21 +158,15 @@ def main():
     roof = {"bound": "mfma", "kernel": f"conv3d_igemm_kernel<2, 8> (implicit GEMM {C}->{C}, {D}^3; fwd and dgrad launches)",
             "achieved": flops_conv / t_conv / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": flops_conv / t_conv / 1e12 / PEAK_BF16_TFLOPS, "traffic": None}
-    traffic_file = os.path.join(ROOT, "profiles", "conv3d_igemm_c64_128_traffic_bytes.txt")
-    if os.path.exists(traffic_file) and args.size == 128 and args.channels == 64:
-        try:
-            roof["traffic"] = float(open(traffic_file).read().split()[0])
-        except Exception:
-            roof["traffic"] = None
+    # HBM bytes per launch of that kernel: a counter profile (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+    # copy of known size) cannot be taken inside this run; the figure is the one of the committed profile, with
+    # the commit it was taken at, and is null when that profile does not describe the workload.
+    if args.size == 128 and args.channels == 64:
+        roof["traffic"], roof["traffic_source"] = profile_traffic()
     # The rate of the bare matrix-core instruction stream on this chip, with zero and with normally
     # distributed operands (switching power sets the clock): context for `frac`, whose peak stays the
     # published one.
-    try:
-        roof["mfma_rate_zero_operands_tflops"] = L.lamp_probe_mfma_rate(0, 4000)
-        roof["mfma_rate_normal_operands_tflops"] = L.lamp_probe_mfma_rate(1, 4000)
-        roof["mfma_rate_lds_fed_kernel_mix_tflops"] = L.lamp_probe_mfma_rate(2, 4000)
-    except Exception:
-        pass
+    roof.update(mfma_probe())
     if args.copy_calibration:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
@@ -200,10 +206,64 @@ def main():
         O.conv3d_wgrad(xs, dzz)
         tc = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": 3 * 2.0 * s ** 3 * 27 * C * C / tc / 1e12, "unit": "TFLOP/s",
-                               "cores": O.num_threads(), "kind": "oracle",
+                               "cores": O.num_threads(), "kind": "oracle", "cpu_model": cpu_model(),
                                "sample": f"same conv block (fwd+dgrad+wgrad, fp64) on a {s}^3 sub-volume of the "
-                                         f"workload, C={C}, {tc:.1f} s"}
+                                         f"workload, C={C}, {tc:.1f} s; a rate measured on that bounded sample, not a "
+                                         f"full-size run (which would take about {tc * (D / s) ** 3:.0f} s)"}
+    if not args.no_configs and args.size == 128 and args.channels == 64:
+        del x, dy, z, y, dz, dx, ws
+        torch.cuda.empty_cache()
+        out["configs"] = {}
+        for key, wl in (("cfg1_tiny", "tiny"), ("cfg3_stage", "stage"), ("cfg4_unet_train", "unet_train"),
+                        ("cfg5a_unet_infer", "unet_infer"), ("cfg5b_sliding", "sliding")):
+            e = net_bench(wl, args, torch, np, S, L, max(1, args.config_steps), max(1, args.config_warmup),
+                          cpu=not args.no_cpu_baseline)
+            out["configs"][key] = {k: e[k] for k in ("config", "ms_per_step", "steps", "warmup", "dtype", "voxels_per_s", "tflops",
+                                                      "pct_mfma_peak", "roofline", "cpu_baseline", "final_loss") if k in e}
+            torch.cuda.empty_cache()
+        a, b = out["configs"]["cfg5a_unet_infer"], out["configs"]["cfg5b_sliding"]
+        out["configs"]["cfg5_sliding_over_one_pass_time_ratio"] = b["ms_per_step"] / a["ms_per_step"]
     print(json.dumps(out))
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def profile_traffic():
+    """(bytes per launch, source) of the headline conv kernel from the committed counter profile, or (None, reason)."""
+    f = os.path.join(ROOT, "profiles", "conv3d_igemm_c64_128_traffic_bytes.txt")
+    try:
+        txt = open(f).read()
+        val = float(txt.split()[0])
+        src = " ".join(txt.split()[1:])
+        return val, f"profiles/{os.path.basename(f)}: {src}"
+    except Exception as e:  # noqa: BLE001
+        return None, f"no usable profile ({e})"
+
+
+def mfma_probe():
+    """Bench-only helper library (its own .so: it allocates and synchronises, which the product ABI never does)."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2006_12575_amd", "benchprobe", "liblamp_benchprobe.so")
+    out = {}
+    try:
+        lib = ctypes.CDLL(path)
+        lib.benchprobe_mfma_rate.restype = ctypes.c_int
+        lib.benchprobe_mfma_rate.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_float)]
+        for pat, name in ((0, "mfma_rate_zero_operands_tflops"), (1, "mfma_rate_normal_operands_tflops")):
+            v = ctypes.c_float(0.0)
+            if lib.benchprobe_mfma_rate(pat, 4000, ctypes.byref(v)) == 0:
+                out[name] = float(v.value)
+    except OSError:
+        pass
+    return out
 
 
 def unet_flops(levels, base, in_ch, classes, n, d, h, w):
@@ -259,20 +319,120 @@ def se_bench(args, torch, np, S, L):
     tb = z.numel() * 2
     alg = 9 * tb   # forward: z twice, residual, y; backward: dy and z twice, dz
     V = D ** 3
-    print(json.dumps({
+    return ({
         "metric": "Conv3d fwd+bwd TFLOP/s (% MFMA peak); whole-U-Net voxels/sec at 1 GPU", "value": V / dtm, "unit": "voxels/s",
         "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": dtm * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"InstanceNorm+ReLU+squeeze-and-excitation (ratio 16)+residual, forward+backward, 1x{D}^3x{C}",
                    "voxels": V, "algorithmic_bytes_per_step": alg},
         "roofline": {"bound": "hbm", "achieved": alg / dtm / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": alg / dtm / 1e9 / PEAK_HBM_GBS, "traffic": None}}))
+                     "frac": alg / dtm / 1e9 / PEAK_HBM_GBS, "traffic": None}})
 
 
-def net_bench(args, torch, np, S, L):
+def unet_ideal_bytes(levels, base, in_ch, classes, n, d, h, w, es):
+    """Algorithmic HBM bytes of one forward pass with every elementwise step fused into a neighbour: each conv reads
+    its input and writes its output once (es bytes per element), pooling reads the fine and writes the coarse tensor,
+    the transposed conv reads coarse and writes fine, the head reads C_1 channels and writes fp32 logits."""
+    ch = [base << l for l in range(levels)]
+    vox = [n * (d >> l) * (h >> l) * (w >> l) for l in range(levels)]
+    b = 0.0
+    for l in range(levels):
+        cin = in_ch if l == 0 else ch[l - 1]
+        b += vox[l] * es * ((cin + ch[l]) + 2 * ch[l])
+        if l + 1 < levels:
+            b += es * ch[l] * (vox[l] + vox[l + 1])
+    for l in range(levels - 2, -1, -1):
+        b += es * (vox[l + 1] * ch[l + 1] + vox[l] * ch[l])
+        b += vox[l] * es * ((2 * ch[l] + ch[l]) + 2 * ch[l])
+    b += vox[0] * (es * ch[0] + 4 * classes)
+    return b
+
+
+def conv_layer_roofline(torch, S, L, n, d, h, w, ci, co, reps, seed):
+    """Roofline object of the matrix-core conv kernel on one layer shape: lamp_conv3d_fwd (statistics in the epilogue)
+    on seeded N(0,1) bf16 data, timed with events on the launch stream (torch's current stream, the one the binding
+    launches on).  The bracket holds the kernel, the weight repack and the statistics finalize (a few microseconds)."""
+    import ctypes
+    dev, bf, f32 = "cuda:0", torch.bfloat16, torch.float32
+    g = torch.Generator(dev).manual_seed(seed)
+    x = torch.randn((n, d, h, w, ci), device=dev, generator=g, dtype=f32).to(bf)
+    rw, = S.streams(seed, 1)
+    wt = torch.from_numpy(S.kaiming_conv(rw, co, ci)).to(bf).to(dev)
+    z = torch.empty((n, d, h, w, co), dtype=bf, device=dev)
+    st = torch.empty((n, co, 2), dtype=f32, device=dev)
+    xd, zd = L.desc(x), L.desc(z)
+    ws = torch.empty(int(L.lib().lamp_conv3d_fwd_workspace_bytes(ctypes.byref(xd), ctypes.byref(zd), 1)) + 256,
+                     dtype=torch.uint8, device=dev)
+    run = lambda: L.lamp_conv3d_fwd(x, wt, z, stats_out=st, ws=ws)
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) / reps * 1e-3
+    fl = 2.0 * n * d * h * w * 27 * ci * co
+    alg = 2.0 * n * d * h * w * (ci + co)
+    return {"bound": "mfma", "kernel": f"conv3d_igemm_kernel, 3x3x3 conv {ci}->{co} on {n}x{d}x{h}x{w} (the layer shape that takes the "
+                                       f"largest share of this workload's time; lamp_conv3d_fwd with the statistics epilogue)",
+            "achieved": fl / t / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": fl / t / 1e12 / PEAK_BF16_TFLOPS,
+            "traffic": None, "launch_ms": t * 1e3, "algorithmic_bytes": alg}
+
+
+def oracle_sample(wl, np, S, levels, base, K):
+    """The CPU oracle (fp64, as it stands) timed on a small sample of the workload: the same network on a 32^3 input
+    (the tiny net at full size).  Returns the cpu_baseline object; the rate is per input voxel, which is what the
+    work of these networks is proportional to, so it stands for the full-size rate and is labelled as extrapolated."""
+    import oracle as O
+    from oracle import sliding as OS
+    from oracle import unet as OU
+    rp, rx, rl = S.streams(4242, 3)
+    p = {k: v.astype(np.float64) for k, v in S.unet_params(rp, levels, base, 1, K, False).items()}
+    side = 32
+    O.num_threads()
+    if wl == "tiny":
+        x = S.normal(rx, (1, side, side, side, 1)).astype(np.float64)
+        t0 = time.perf_counter()
+        OU.forward(p, x, levels)
+        vox, what, extra = side ** 3, f"the whole workload at full size (1x{side}^3, forward)", False
+    elif wl == "stage":
+        x = S.ct_volume(rx, 1, side, side, side).astype(np.float64)
+        t0 = time.perf_counter()
+        (pooled, skips), cache = OU.forward(p, x, levels, first_level=1, last_level=2)
+        gp = S.normal(rl, pooled.shape).astype(np.float64)
+        gs = [S.normal(rl, t.shape).astype(np.float64) for t in skips]
+        OU.stage_backward(p, cache, gp, gs, 1, 2, levels)
+        vox, what, extra = side ** 3, f"the same partition (blocks 1-2, base {base}) forward+backward on a 1x{side}^3 volume", True
+    elif wl == "unet_train":
+        x = S.ct_volume(rx, 1, side, side, side).astype(np.float64)
+        lab = S.organ_labels(rl, 1, side, side, side, K)
+        t0 = time.perf_counter()
+        OU.loss_and_grads(p, x, lab, levels)
+        vox, what, extra = side ** 3, f"the same {levels}-level base-{base} net forward+backward on a 1x{side}^3 volume", True
+    elif wl == "unet_infer":
+        x = S.ct_volume(rx, 1, side, side, side).astype(np.float64)
+        t0 = time.perf_counter()
+        OU.forward(p, x, levels)
+        vox, what, extra = side ** 3, f"the same {levels}-level base-{base} net forward on a 1x{side}^3 volume", True
+    else:  # sliding: 32^3 windows at overlap 0.25 over a 56 x 56 x 32 volume = 2 x 2 x 1 windows
+        x = S.ct_volume(rx, 1, 56, 56, side).astype(np.float64)
+        t0 = time.perf_counter()
+        OS.sliding_window(lambda win: OU.forward(p, win, levels)[0], x, patch=side, overlap=0.25)
+        vox = 56 * 56 * side
+        what, extra = f"the same net as 4 sliding windows of {side}^3 (overlap 0.25, Gaussian blend) over a 56x56x{side} volume", True
+    tc = time.perf_counter() - t0
+    return {"value": vox / tc, "unit": "voxels/s", "cores": O.num_threads(), "kind": "oracle", "cpu_model": cpu_model(),
+            "extrapolated": extra, "sample": f"{what}, fp64, {tc:.1f} s" + ("; voxels per second of that sample, standing for the "
+                                                                            "full-size rate (the work is proportional to the voxel count)" if extra else "")}
+
+
+def net_bench(wl, args, torch, np, S, L, steps, warm, cpu=True):
+    """Times one network-level workload through its entry point and returns its result object."""
     dev = "cuda:0"
     bf, f32 = torch.bfloat16, torch.float32
-    wl = args.workload
     if wl == "se_block":
         return se_bench(args, torch, np, S, L)
     cfg = {
@@ -281,25 +441,27 @@ def net_bench(args, torch, np, S, L):
         "unet_train": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
         "unet_infer": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
         "sliding": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 256, 256, 160), dtype=bf, seed=1005),
-        # the wider nets of the paper's Sec. 3 (base 64 / 128: up to 1024 / 2048 channels) and a whole
-        # head-and-neck sized volume with unequal axes
         # forward + backward + RMSProp update of the fp32 masters and the bf16 working copies: one optimiser step
         "unet_train_step": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
         # the same mini-batch as two partitions on two streams, one sample per micro-batch, in the pipeline order
         "unet_train_pipeline": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1004),
+        # the wider nets of the paper's Sec. 3 (base 64 / 128: up to 1024 / 2048 channels) and a whole
+        # head-and-neck sized volume with unequal axes
         "unet_train_b64": dict(levels=5, base=64, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1006),
         "unet_train_b128": dict(levels=5, base=128, in_ch=1, classes=10, dims=(1, 128, 128, 128), dtype=bf, seed=1007),
         "unet_infer_whole": dict(levels=5, base=32, in_ch=1, classes=10, dims=(1, 352, 256, 288), dtype=bf, seed=1008),
+        # the squeeze-and-excitation variant of the training net (Sec. 1; Tables 2, 3, 5)
+        "seunet_train": dict(levels=5, base=32, in_ch=1, classes=10, dims=(2, 128, 128, 128), dtype=bf, seed=1010, se_ratio=16),
     }[wl]
     levels, base, K, dt = cfg["levels"], cfg["base"], cfg["classes"], cfg["dtype"]
+    se_ratio = cfg.get("se_ratio", 0)
     N, D, H, W = cfg["dims"]
     rp, rx, rl = S.streams(cfg["seed"], 3)
-    p = S.unet_params(rp, levels, base, 1, K, False)
-    names = list(p.keys())
-    params = [torch.from_numpy(v).to(f32 if k.endswith(".b") else dt).to(dev) for k, v in p.items()]
+    p = S.unet_params(rp, levels, base, 1, K, False, **({"se_ratio": se_ratio} if se_ratio else {}))
+    params = [torch.from_numpy(v).to(f32 if (k.endswith(".b") or ".se." in k) else dt).to(dev) for k, v in p.items()]
     x = torch.from_numpy(S.ct_volume(rx, N, D, H, W) if wl != "tiny" else S.normal(rx, (N, D, H, W, 1))).to(dt).to(dev)
     V = N * D * H * W
-    steps, warm = max(1, args.steps), max(1, args.warmup)
+    dom = None   # (n, d, h, w, ci, co) of the conv layer whose kernel dominates the workload
     if wl in ("tiny", "unet_infer", "unet_infer_whole"):
         ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
         logits = torch.empty((N, D, H, W, K), dtype=f32, device=dev)
@@ -307,14 +469,18 @@ def net_bench(args, torch, np, S, L):
         run = lambda: L.lamp_unet_fwd(ud, params, x, logits, ws=ws)
         flops = unet_flops(levels, base, 1, K, N, D, H, W)
         what = f"{levels}-level base-{base} U-Net forward, {N}x{D}x{H}x{W}"
-    elif wl.startswith("unet_train"):
-        ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
+        dom = (N, D, H, W, base, base)
+    elif wl.startswith("unet_train") or wl == "seunet_train":
+        ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt, **({"se_ratio": se_ratio} if se_ratio else {}))
         lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, K)).to(dev)
         grads = [torch.empty(t.shape, dtype=f32, device=dev) for t in params]
         loss = torch.empty((), dtype=f32, device=dev)
         ws = torch.empty(L.lamp_unet_workspace_bytes(ud, True), dtype=torch.uint8, device=dev)
         flops = 3.0 * unet_flops(levels, base, 1, K, N, D, H, W)
         what = f"{levels}-level base-{base} U-Net forward+backward (softmax CE), {N}x{D}x{H}x{W}"
+        if se_ratio:
+            what = f"squeeze-and-excitation variant (ratio {se_ratio}) of the " + what
+        dom = (N, D, H, W, base, base)
         if wl == "unet_train_step":
             masters = [t.to(f32).clone() for t in params]
             msq = [torch.zeros_like(t) for t in masters]
@@ -345,6 +511,7 @@ def net_bench(args, torch, np, S, L):
         run = lambda: L.lamp_sliding_window_fwd(pd, params, x, out, ws=ws)
         flops = unet_flops(levels, base, 1, K, cnt, P, P, P)
         what = f"{cnt} sliding windows of {P}^3 (overlap 0.25, Gaussian blend) over {D}x{H}x{W}, {levels}-level base-{base} U-Net"
+        dom = (cnt, P, P, P, base, base)
     else:  # stage: encoder blocks 1-2 of a base-64 net, forward + backward
         ud = L.unet_desc(levels, base, 1, K, N, D, H, W, dt)
         sp = params[:4]
@@ -363,6 +530,7 @@ def net_bench(args, torch, np, S, L):
         fwd = 2.0 * 27 * (v1 * (1 * base + base * base) + v2 * (base * 2 * base + 4 * base * base))
         flops = 3.0 * fwd - 2.0 * 27 * v1 * base  # no data gradient for the first conv
         what = f"encoder partition (blocks 1-2, base {base}) forward+backward, {N}x{D}x{H}x{W}"
+        dom = (N, D, H, W, base, base)
     for _ in range(warm):
         run()
     torch.cuda.synchronize()
@@ -393,13 +561,29 @@ def net_bench(args, torch, np, S, L):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if dt == bf else "f32", "data": "synthetic",
            "config": {"workload": what, "voxels": V, "flop_per_step": flops},
+           "voxels_per_s": V / dtm,
            "tflops": flops / dtm / 1e12, "pct_mfma_peak": 100.0 * flops / dtm / 1e12 / PEAK_BF16_TFLOPS}
-    if wl.startswith("unet_train"):
+    if wl.startswith("unet_train") or wl == "seunet_train":
         out["final_loss"] = float(loss.item())   # the timed steps ran on finite data (the optimiser workload moves the weights)
         if not np.isfinite(out["final_loss"]):
             print("bench.py: the loss is not finite after the timed steps", file=sys.stderr)
             sys.exit(1)
-    print(json.dumps(out))
+    del ws
+    torch.cuda.empty_cache()
+    if wl == "tiny":
+        # a chain of about 60 launches on 32^3 ... 8^3 voxels: bound by per-kernel latency; stated against the HBM
+        # roofline with the algorithmic bytes of the whole forward, timed through the entry point (no single
+        # kernel dominates)
+        alg = unet_ideal_bytes(levels, base, 1, K, N, D, H, W, 4)
+        out["roofline"] = {"bound": "hbm", "kernel": "whole forward (a chain of about 60 small fp32 kernels; latency-bound, no dominant kernel)",
+                           "achieved": alg / dtm / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": alg / dtm / 1e9 / PEAK_HBM_GBS,
+                           "traffic": None, "algorithmic_bytes": alg}
+    elif dom is not None:
+        out["roofline"] = conv_layer_roofline(torch, S, L, *dom, reps=max(3, steps), seed=cfg["seed"] + 50)
+        torch.cuda.empty_cache()
+    if cpu and wl in ("tiny", "stage", "unet_train", "unet_infer", "sliding"):
+        out["cpu_baseline"] = oracle_sample(wl, np, S, levels, base, K)
+    return out
 
 
 if __name__ == "__main__":

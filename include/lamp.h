@@ -30,6 +30,14 @@
  *     floating-point atomics; every reduction has a fixed order).
  *   - Workspace: each call states its need through the matching *_workspace_bytes query;
  *     pointers must be 16-byte aligned (hipMalloc / torch allocations are).
+ *   - One tuning switch, read once per process from the environment: LAMP_TUNE="key=value,...".
+ *     Results do not depend on it beyond floating-point summation order; it exists for measurements
+ *     and for tests that must reach a particular kernel instantiation on a small volume.  Keys:
+ *       tile_depth=4|8        depth of the matrix-core conv tile (default: chosen per shape)
+ *       no_pack=1             batches of tiny volumes are not packed into one volume
+ *       no_split=1            no input-channel split for few-tile, many-channel layers
+ *       cb_outer=1            output-channel blocks as grid.y instead of side by side on one XCD
+ *       materialise_concat=1  the network entry points keep one concat buffer per decoder level
  */
 #ifndef LAMP_H
 #define LAMP_H
@@ -91,19 +99,6 @@ const char *lamp_build_info(void);
  * LAMP_ERR_DTYPE (out_dtype), LAMP_ERR_HIP. */
 lamp_status lamp_rmsprop_step(int32_t count, const int64_t *numel, float *const *w, float *const *v, const float *const *g,
                               void *const *w_out, const int32_t *out_dtype, float lr, float alpha, float eps, void *stream);
-
-/* Diagnostic, not part of the method: the rate (TFLOP/s) at which this GPU executes a register-resident
- * loop of the bf16 32x32x16 matrix-core instruction the convolution kernels use (no memory traffic),
- * measured over `iters` x 24 instructions per wave with one wave per SIMD.  pattern selects the operand
- * values: 0 = zeros, 1 = standard-normal (seeded).  The rate depends on the data (switching power and
- * with it the clock), which bounds what any kernel can reach on real activations; bench.py reports it
- * beside the published peak.  pattern 2 = the same loop at the convolution kernel's design point:
- * standard-normal operands fetched fresh from LDS (12 fragment reads per 24 instructions), that kernel's
- * measured ratio of other vector / scalar instructions and 3 register-free global->LDS copies beside
- * them, no barriers and no exposed memory latency: what perfect scheduling of that instruction mix
- * reaches.  Allocates and frees a small device buffer; synchronises the stream.
- * Errors: LAMP_ERR_NULL (tflops), LAMP_ERR_SHAPE (pattern, iters < 1), LAMP_ERR_HIP. */
-lamp_status lamp_probe_mfma_rate(int32_t pattern, int32_t iters, float *tflops, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * 3x3x3 convolution, padding 1, stride 1 (the conv of every U-Net block, Sec. 2.2 / Sec. 3).

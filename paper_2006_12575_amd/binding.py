@@ -51,7 +51,6 @@ _VP = c_void_p
 _SIGS = {
     "lamp_status_string": (c_char_p, [c_int]),
     "lamp_build_info": (c_char_p, []),
-    "lamp_probe_mfma_rate": (c_int, [c_int, c_int, POINTER(c_float), _VP]),
     "lamp_rmsprop_step": (c_int, [c_int, POINTER(ctypes.c_int64), _VP, _VP, _VP, _VP, POINTER(c_int32), c_float, c_float,
                                   c_float, _VP]),
     "lamp_conv3d_fwd_workspace_bytes": (c_size_t, [_PD, _PD, c_int]),
@@ -124,14 +123,6 @@ def status_string(status: int) -> str:
 
 def build_info() -> str:
     return lib().lamp_build_info().decode()
-
-
-def lamp_probe_mfma_rate(pattern: int, iters: int = 4000) -> float:
-    """TFLOP/s of a bf16 MFMA loop, one wave per SIMD; pattern 0 = zero operands in registers, 1 = standard-normal
-    operands in registers, 2 = standard-normal operands fresh from LDS beside the conv kernel's instruction mix."""
-    out = c_float(0.0)
-    _check(lib().lamp_probe_mfma_rate(int(pattern), int(iters), ctypes.byref(out), _stream()), "lamp_probe_mfma_rate")
-    return float(out.value)
 
 
 def _check(status, where):

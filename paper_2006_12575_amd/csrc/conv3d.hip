@@ -821,7 +821,7 @@ extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x
         return LAMP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     if (mfma_conv_supported(xd, zd, xnorm, bias))
-        return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s);
+        return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s, nullptr, bias);
     if (cin1_fwd_ok(xd, zd, xnorm, bias, z)) {
         if (cin1_tile_ok(zd)) return cin1_tile_fwd(xd, x, w, zd, z, stats_out, eps, ws, ws_bytes, s);
         hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
@@ -880,15 +880,17 @@ extern "C" lamp_status lamp_conv3d_wgrad(const lamp_tensor_desc* xd, const void*
     if (!ws || ws_bytes < lamp_conv3d_wgrad_workspace_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int64_t O = (int64_t)dzd->c * 27 * xd->c;
+    // The bias gradient's partial sums take the (256-byte aligned) head of the workspace, everything else what follows.
     const size_t cs = colsum_ws_bytes(nvox(dzd), dzd->c);
-    char* wsb = (char*)ws;
     if (dbias) {
-        st = launch_colsum(dz, dzd->dtype, nvox(dzd), dzd->c, dzd->ldc, dbias, beta, wsb + (ws_bytes - cs), cs, s);
+        st = launch_colsum(dz, dzd->dtype, nvox(dzd), dzd->c, dzd->ldc, dbias, beta, ws, cs, s);
         if (st != LAMP_OK) return st;
     }
-    if (mfma_wgrad_supported(xd, dzd, xnorm)) return mfma_wgrad(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
+    ws = (char*)ws + cs;
+    ws_bytes -= cs;
+    if (mfma_wgrad_supported(xd, dzd, xnorm)) return mfma_wgrad(xd, x, dzd, dz, dw, beta, ws, ws_bytes, s);
     if (xd->dtype == LAMP_BF16 && xd->c == 1 && !(xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) && cin1_wtile_ok(xd, dzd, dz))
-        return cin1_wtile(xd, x, dzd, dz, dw, beta, ws, ws_bytes - cs, s);
+        return cin1_wtile(xd, x, dzd, dz, dw, beta, ws, ws_bytes, s);
     if (cin1_wgrad_ok(xd, dzd, xnorm)) {
         const int64_t groups = nvox(xd) / 16;
         const int blocks = cin1_wgrad_blocks(nvox(xd));

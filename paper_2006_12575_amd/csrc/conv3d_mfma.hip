@@ -79,8 +79,7 @@ __global__ __launch_bounds__(256) void repack_batch_kernel(RepackBatch b) {
     while (k + 1 < b.n && (int)blockIdx.x >= b.j[k + 1].blk0) ++k;
     const RepackBatch::J& q = b.j[k];
     const int64_t i = (int64_t)((int)blockIdx.x - q.blk0) * 256 + threadIdx.x;
-    if (q.kind <= 1) repack_tile_gran(q.w, q.wp, i, q.Cout, q.Cin, q.Cout % 64 == 0 ? 64 : 32, q.dgrad, q.kind);
-    else repack_ring_gran(q.w, q.wp, i, q.Cout, q.Cin, q.kind == 2 ? 64 : 32, q.dgrad);
+    repack_tile_gran(q.w, q.wp, i, q.Cout, q.Cin, q.Cout % 64 == 0 ? 64 : 32, q.dgrad, q.kind);
 }
 
 lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s) {
@@ -118,6 +117,7 @@ struct ConvArgs {
     float* part;        // [N][tiles_per_n][Cout][2] or nullptr
     int32_t* counts;    // [tiles_per_n] in-volume voxels per tile (written when part != nullptr)
     const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
+    const float* bias;     // [Cout] fp32 added to the accumulators before rounding and the statistics, or nullptr
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
     float* zpart;       // split reduction only: [splits][N*D*H*W][Cout] fp32 partial outputs
@@ -447,6 +447,19 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             // consecutive channels per register group
             static_assert(TDT == 4, "the split reduction uses the 4-deep tile");
             float* zp = a.zpart + (int64_t)blockIdx.z * ((int64_t)a.N * a.D * a.H * a.W) * a.Cout;
+            if (a.bias && blockIdx.z == 0) {   // the first split's partial carries the bias
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0 + cb * 32 + rg * 8 + half * 4);
+#pragma unroll
+                        for (int vb = 0; vb < NVB; ++vb) {
+                            acc[cb][vb][rg * 4 + 0] += bv.x; acc[cb][vb][rg * 4 + 1] += bv.y;
+                            acc[cb][vb][rg * 4 + 2] += bv.z; acc[cb][vb][rg * 4 + 3] += bv.w;
+                        }
+                    }
+            }
 #pragma unroll
             for (int vb = 0; vb < NVB; ++vb) {
                 const int gh = h0 + hs * NVB + vb + 4 * bh, gw = w0 + bw;
@@ -489,6 +502,19 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         const int vbvox = TDT == 8 ? a.H * a.W : a.W;   // voxels from block vb to vb + 1 (offsets inside a tile fit 32 bits)
         const bool full = gd0 + (TDT == 8 ? NVB : 1) <= a.D && h0 + TH <= a.H && w0 + TW <= a.W;
         const bool want_stats = a.part != nullptr;
+        if (a.bias) {   // fp32 bias on the accumulators: what is rounded, stored and summed is z + b
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const float4 bv = *reinterpret_cast<const float4*>(a.bias + co0 + cb * 32 + rg * 8 + half * 4);
+#pragma unroll
+                    for (int vb = 0; vb < NVB; ++vb) {
+                        acc[cb][vb][rg * 4 + 0] += bv.x; acc[cb][vb][rg * 4 + 1] += bv.y;
+                        acc[cb][vb][rg * 4 + 2] += bv.z; acc[cb][vb][rg * 4 + 3] += bv.w;
+                    }
+                }
+        }
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
@@ -577,7 +603,7 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
                          const float* bias) {
     if (xd->dtype != LAMP_BF16) return false;
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
-    if (bias) return false;
+    if (bias && (((uintptr_t)bias) & 15u)) return false;   // the epilogue reads it four floats at a time
     if (xd->c % 16 || zd->c % 32 || xd->ldc % 8 || zd->ldc % 8) return false;
     // element offsets inside a tile's halo (10 slices of H x W voxels) are kept in 32 bits
     const int64_t ldmax = xd->ldc > zd->ldc ? xd->ldc : zd->ldc;
@@ -589,13 +615,9 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
 // bytes and barriers per MFMA); the 4-deep tile yields twice the workgroup-tiles, which fills the chip
 // on small volumes and wastes less of a last, partial round on medium ones.  (The 4-deep tile also halves the
 // HBM re-fetch -- its per-XCD working set fits the 4 MiB L2 between chunk passes -- but is slower
-// per MFMA.)  LAMP_CONV_TILE_DEPTH=4|8 forces one for experiments.
+// per MFMA.)  LAMP_TUNE=tile_depth=4|8 forces one.
 static int conv_tile_depth(const lamp_tensor_desc* zd) {
-    static int forced = -1;
-    if (forced < 0) {
-        const char* e = getenv("LAMP_CONV_TILE_DEPTH");
-        forced = e ? atoi(e) : 0;
-    }
+    const int forced = tune("tile_depth", 0);
     if (forced == 4 || forced == 8) return forced;
     // Rounds of the chip: (tiles x output-channel blocks) workgroup-tiles over 256 CUs, rounded up; an 8-deep
     // tile costs 1.9 four-deep ones.  (Measured on 15 layer shapes from 32^3 to 176 x 128 x 144 with 32 to 256
@@ -604,21 +626,6 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
     const int64_t ncb = (zd->c + (zd->c % 64 == 0 ? 64 : 32) - 1) / (zd->c % 64 == 0 ? 64 : 32);
     const int64_t rounds8 = (hw * ((zd->d + 7) / 8) * ncb + 255) / 256, rounds4 = (hw * ((zd->d + 3) / 4) * ncb + 255) / 256;
     return 19 * rounds8 <= 10 * rounds4 ? 8 : 4;
-}
-
-// Kernel choice.  The tiled kernel (two waves per SIMD, twice the voxels per weight byte) serves every
-// shape.  The ring kernel was the faster one on long runs of 64-input-channel tiles until the tiled
-// kernel got its weights as a ready LDS image and the XCD-aware walk; it now trails it by 2-6 % there
-// (and by more elsewhere) and is kept for comparison: LAMP_CONV_KERNEL=ring selects it wherever its
-// shape constraints hold.
-static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
-    static int forced = -1;
-    if (forced < 0) {
-        const char* e = getenv("LAMP_CONV_KERNEL");
-        forced = !e ? 0 : (e[0] == 'r' ? 1 : 2);
-    }
-    (void)xd; (void)zd;
-    return forced == 1;
 }
 
 // ---- many small volumes: one packed volume ---------------------------------------------------------
@@ -631,9 +638,7 @@ static bool conv_use_ring(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 struct PackPlan { int gh, gw, hp, wp; };
 static int64_t pack_slots(int d, int h, int w) { return (int64_t)((d + 3) / 4) * ((h + TH - 1) / TH) * ((w + TW - 1) / TW); }
 static bool conv_pack_plan(const lamp_tensor_desc* zd, PackPlan& best) {
-    static int off = -1;
-    if (off < 0) off = getenv("LAMP_CONV_NO_PACK") ? 1 : 0;
-    if (off || zd->n < 4 || zd->w > 8 || zd->h > 16 || zd->d > 64 || zd->c > 4096) return false;
+    if (tune("no_pack", 0) || zd->n < 4 || zd->w > 8 || zd->h > 16 || zd->d > 64 || zd->c > 4096) return false;
     const int64_t plain = (int64_t)zd->n * pack_slots(zd->d, zd->h, zd->w);
     int64_t bs = plain;
     bool found = false;
@@ -720,15 +725,14 @@ __global__ __launch_bounds__(256) void conv_unpack_kernel(const bf16_t* __restri
     }
 }
 
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only, bool two_out) {
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool two_out) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return -1;
     PackPlan pp;
     if (!two_out && conv_pack_plan(zd, pp)) {   // the conv runs on the packed volume, as one contiguous tensor
         lamp_tensor_desc xp, zp;
         pack_descs(xd, zd, pp, xp, zp);
-        return conv_repack_kind(&xp, &zp, false, false);
+        return conv_repack_kind(&xp, &zp, false);
     }
-    if (!tiled_only && conv_use_ring(xd, zd)) return zd->c % 64 == 0 ? 2 : 3;
     return conv_tile_depth(zd) == 8 ? 1 : 0;
 }
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
@@ -738,9 +742,7 @@ size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd)
 // Number of input-channel splits for the tiled kernel (1 = none): only where the 4-deep tiling with 64
 // output channels per workgroup leaves at least half of the chip idle and there are chunks to share out.
 static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
-    static int off = -1;
-    if (off < 0) off = getenv("LAMP_CONV_NO_SPLIT") ? 1 : 0;
-    if (off || zd->c % 64 || conv_tile_depth(zd) != 4) return 1;
+    if (tune("no_split", 0) || zd->c % 64 || conv_tile_depth(zd) != 4) return 1;
     int td, th, tw;
     tile_dims(zd, 4, td, th, tw);
     const int64_t wgs = (int64_t)zd->n * td * th * tw * (zd->c / 64);
@@ -761,9 +763,8 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     // repacked weights + a run of zeros (source of the zero padding) + 16 bytes that absorb masked stores
     size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
     if (want_stats) {
-        // partial statistics: one per tile (tiled kernel) or one per wave of a workgroup (ring kernel, <= 1024)
-        const size_t parts = tiles > 1024 ? tiles : 1024;
-        b += align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * parts * sizeof(int32_t));
+        // partial statistics: one per tile
+        b += align_up((size_t)zd->n * tiles * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * tiles * sizeof(int32_t));
     }
     const int S = conv_splits(xd, zd);
     if (S > 1) b += align_up((size_t)S * nvox(zd) * zd->c * sizeof(float)) + stats_ws_bytes(zd) + 256;
@@ -780,13 +781,8 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 
 template <int COB, int TDT, bool SPLIT = false>
 static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
-    static bool attr_done = false;
     const int shm = Geo<TDT>::LDS_BYTES;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, shm) != hipSuccess)
-            return LAMP_ERR_HIP;
-        attr_done = true;
-    }
+    if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT>, shm) != LAMP_OK) return LAMP_ERR_HIP;
     hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT>), grid, dim3(512), shm, s, a);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
@@ -794,7 +790,7 @@ static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
 
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
-                          hipStream_t s, const ConvParts* parts) {
+                          hipStream_t s, const ConvParts* parts, const float* bias) {
     const bool two_in = parts && parts->x2, two_out = parts && parts->z2;
     if (two_in && ((((uintptr_t)parts->x2) & 15u) || parts->x_c1 % 16 || parts->x_c1 <= 0 || parts->x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
     if (two_out && ((((uintptr_t)parts->z2) & 15u) || parts->z_c1 % 32 || parts->z_c1 <= 0 || parts->z_c1 >= zd->c || parts->ldz2 % 8))
@@ -815,14 +811,13 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
                            two_in ? (const bf16_t*)parts->x2 : (const bf16_t*)x, two_in ? parts->x_c1 : xd->c, xpk, xd->n, xd->d,
                            xd->h, xd->w, xd->c, pp.gw, pp.hp, pp.wp);
         LAMP_CHECK_LAUNCH();
-        lamp_status st = mfma_conv_fwd(&xp, xpk, w, dgrad, &zp, zpk, nullptr, 0.f, iws, inner, s, nullptr);
+        lamp_status st = mfma_conv_fwd(&xp, xpk, w, dgrad, &zp, zpk, nullptr, 0.f, iws, inner, s, nullptr, bias);
         if (st != LAMP_OK) return st;
         hipLaunchKernelGGL(conv_unpack_kernel, dim3(zd->n, cdiv(zd->c, 64)), dim3(256), 0, s, zpk, (bf16_t*)z, zd->ldc, zd->n,
                            zd->d, zd->h, zd->w, zd->c, pp.gw, pp.hp, pp.wp, eps, stats_out);
         LAMP_CHECK_LAUNCH();
         return LAMP_OK;
     }
-    if (!two_in && !two_out && conv_use_ring(xd, zd)) return ring_conv_fwd(xd, x, w, dgrad, zd, z, stats_out, eps, ws, ws_bytes, s);
     const int TDT = conv_tile_depth(zd);
     int td, th, tw;
     tile_dims(zd, TDT, td, th, tw);
@@ -847,6 +842,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     ConvArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;
+    a.bias = bias;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
     a.tiles_total = tiles_per_n * zd->n;
@@ -875,8 +871,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         if (st != LAMP_OK) return st;
         return launch_splitk_reduce(a.zpart, S, zd, z, eps, stats_out, sws, stats_ws_bytes(zd), s, a.z2, a.ldz2, a.zsplit);
     }
-    static const bool cb_outer = getenv("LAMP_CONV_CB_OUTER") != nullptr;
-    if (!a.xcd_rot && grid.y > 1 && !cb_outer) {
+    if (!a.xcd_rot && grid.y > 1 && !tune("cb_outer", 0)) {
         a.cb_inner = (int)grid.y;
         grid.x *= grid.y;
         grid.y = 1;
@@ -1186,20 +1181,11 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
     if (!a.zero16) return LAMP_ERR_HIP;
     const int cob = (dzd->c % 64 == 0) ? 2 : 1;
     dim3 grid(S, xd->c / 32, dzd->c / (32 * cob));
-    static bool attr_done[2] = {false, false};
     if (cob == 2) {
-        if (!attr_done[1]) {
-            if (hipFuncSetAttribute((const void*)conv3d_wgrad_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_BYTES) != hipSuccess)
-                return LAMP_ERR_HIP;
-            attr_done[1] = true;
-        }
+        if (ensure_dyn_lds((const void*)conv3d_wgrad_kernel<2>, WG_LDS_BYTES) != LAMP_OK) return LAMP_ERR_HIP;
         hipLaunchKernelGGL((conv3d_wgrad_kernel<2>), grid, dim3(512), WG_LDS_BYTES, s, a);
     } else {
-        if (!attr_done[0]) {
-            if (hipFuncSetAttribute((const void*)conv3d_wgrad_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS_BYTES) != hipSuccess)
-                return LAMP_ERR_HIP;
-            attr_done[0] = true;
-        }
+        if (ensure_dyn_lds((const void*)conv3d_wgrad_kernel<1>, WG_LDS_BYTES) != LAMP_OK) return LAMP_ERR_HIP;
         hipLaunchKernelGGL((conv3d_wgrad_kernel<1>), grid, dim3(512), WG_LDS_BYTES, s, a);
     }
     LAMP_CHECK_LAUNCH();

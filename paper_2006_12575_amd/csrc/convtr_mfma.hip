@@ -667,12 +667,7 @@ lamp_status mfma_convtr_wgrad(const lamp_tensor_desc* xd, const void* x, const l
     a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w; a.Ci = xd->c; a.Co = dyd->c;
     const int64_t chunks = (nvox(xd) + 63) / 64;
     a.chunks_per_split = (int)((chunks + S - 1) / S);
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)convtr_wgrad_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * CTW_STAGE) != hipSuccess)
-            return LAMP_ERR_HIP;
-        attr_done = true;
-    }
+    if (ensure_dyn_lds((const void*)convtr_wgrad_mfma_kernel, 2 * CTW_STAGE) != LAMP_OK) return LAMP_ERR_HIP;
     dim3 grid(S, (xd->c + 63) / 64, dyd->c / 32);
     hipLaunchKernelGGL(convtr_wgrad_mfma_kernel, grid, dim3(256), 2 * CTW_STAGE, s, a);
     LAMP_CHECK_LAUNCH();

@@ -4,6 +4,12 @@
 
 namespace lamp {
 
+// ---- api.hip --------------------------------------------------------------------------------
+// Value of `key` in the LAMP_TUNE environment variable ("key=value,key=value"; a bare key means 1), else dflt.
+int tune(const char* key, int dflt);
+// Raises a kernel's dynamic-LDS limit once per (device, kernel); thread-safe.
+lamp_status ensure_dyn_lds(const void* fn, int bytes);
+
 // ---- norm.hip -------------------------------------------------------------------------------
 // Number of row chunks the stand-alone statistics pass uses for a tensor of `v` voxels per sample.
 int stats_chunks(int64_t v);
@@ -23,13 +29,12 @@ lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, 
 // ---- reduce.hip -----------------------------------------------------------------------------
 // out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.
 // ---- repacked conv weights prepared ahead of the calls that use them (network entry points) ----
-// kind: 0 tiled kernel (4-deep tile), 1 tiled kernel (8-deep tile, kh-major taps), 2 ring kernel with
-// 64 output channels per workgroup, 3 ring kernel with 32; -1: the shape does not take a matrix-core path.
+// kind: 0 tiled kernel with the 4-deep tile, 1 with the 8-deep tile (kh-major taps); -1: the shape does not take a
+// matrix-core path.
 struct RepackJob { const void* w; void* wp; int Cout, Cin, dgrad, kind; };
 struct RepackTable { int n; RepackJob e[64]; };
-// tiled_only: the conv reads or writes a two-part tensor; two_out: it writes one (then the batch of small
-// volumes is not packed into one volume).
-int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool tiled_only = false, bool two_out = false);
+// two_out: the conv writes a two-part tensor (then a batch of small volumes is not packed into one volume).
+int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, bool two_out = false);
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
 lamp_status launch_repack_batch(const RepackJob* jobs, int n, hipStream_t s);
 // The table the calling thread's conv calls consult (weight pointer + direction + kind must match);
@@ -68,18 +73,13 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 struct ConvParts { const void* x2; int x_c1; void* z2; int z_c1, ldz2; };
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
-                          void* ws, size_t ws_bytes, hipStream_t s, const ConvParts* parts = nullptr);
+                          void* ws, size_t ws_bytes, hipStream_t s, const ConvParts* parts = nullptr,
+                          const float* bias = nullptr);
 bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm);
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd);
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,
                        float* dw, float beta, void* ws, size_t ws_bytes, hipStream_t s, const void* x2 = nullptr,
                        int x_c1 = 0);
-
-// ---- conv3d_mfma_ring.hip -------------------------------------------------------------------
-// Ring variant of the matrix-core convolution (same contract and workspace as mfma_conv_fwd).
-lamp_status ring_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
-                          const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
-                          void* ws, size_t ws_bytes, hipStream_t s);
 
 // ---- convtr_mfma.hip ------------------------------------------------------------------------
 bool mfma_convtr_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* yd, const lamp_norm_in* xnorm);

@@ -1,4 +1,5 @@
 // Deterministic second-stage reductions shared by the weight-gradient paths.
+#include <mutex>
 #include "internal.h"
 #include "vec.h"
 
@@ -12,8 +13,10 @@ namespace lamp {
 __device__ __attribute__((used, aligned(16))) uint32_t lamp_zero16_storage[4] = {0u, 0u, 0u, 0u};
 const bf16_t* device_zero16() {
     static const bf16_t* cache[64] = {nullptr};
+    static std::mutex mu;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
     if (!cache[dev]) {
         void* p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(lamp_zero16_storage)) != hipSuccess || !p) return nullptr;

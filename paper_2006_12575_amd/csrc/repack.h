@@ -44,26 +44,4 @@ __device__ __forceinline__ void repack_tile_gran(const bf16_t* __restrict__ w, b
     *reinterpret_cast<uint4*>(wp + g * 8) = v;
 }
 
-// Ring kernel: wp[slab][chunk][j = kh*3+kw][kd][plane][co][8] with oc = slab*wrows + co,
-// ic = chunk*16 + plane*8 + e, t = kd*9 + j; Cin + 8 zero elements behind the weights.
-__device__ __forceinline__ void repack_ring_gran(const bf16_t* __restrict__ w, bf16_t* __restrict__ wp, int64_t g, int Cout,
-                                                 int Cin, int wrows, int dgrad) {
-    const int64_t total = (int64_t)27 * Cout * Cin;
-    if (g * 8 < Cin + 8) *reinterpret_cast<uint4*>(wp + total + g * 8) = make_uint4(0, 0, 0, 0);
-    if (g >= total / 8) return;
-    const int nchunks = Cin >> 4;
-    int64_t r = g;
-    const int co = (int)(r % wrows); r /= wrows;
-    const int plane = (int)(r % 2); r /= 2;
-    const int kd = (int)(r % 3); r /= 3;
-    const int j = (int)(r % 9); r /= 9;
-    const int chunk = (int)(r % nchunks);
-    const int slab = (int)(r / nchunks);
-    const int oc = slab * wrows + co, ic0 = chunk * 16 + plane * 8, t = kd * 9 + j;
-    uint4 v;
-    if (!dgrad) v = *reinterpret_cast<const uint4*>(w + ((int64_t)oc * 27 + t) * Cin + ic0);
-    else v = repack_gather8(w + ((int64_t)ic0 * 27 + (26 - t)) * Cout + oc, (int64_t)27 * Cout);
-    *reinterpret_cast<uint4*>(wp + g * 8) = v;
-}
-
 }  // namespace lamp

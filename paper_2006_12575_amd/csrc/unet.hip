@@ -149,9 +149,7 @@ static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole
 // The concat stays virtual when every decoder block's first conv (2C -> C) takes the matrix-core
 // kernels in all three directions.
 static bool vcat_ok(const Net& nt) {
-    static int off = -1;
-    if (off < 0) off = getenv("LAMP_MATERIALISE_CONCAT") ? 1 : 0;
-    if (off || nt.dt != LAMP_BF16 || nt.L < 2) return false;
+    if (tune("materialise_concat", 0) || nt.dt != LAMP_BF16 || nt.L < 2) return false;
     for (int l = 1; l < nt.L; ++l) {
         const int C = nt.chan(l);
         lamp_tensor_desc x2 = nt.td(l, 2 * C, C), z = nt.td(l, C, C);
@@ -286,7 +284,7 @@ static size_t repack_region_bytes(const Net& nt, int first, int last, bool whole
     size_t b = 0;
     for (const ConvSpec& c : v) {
         lamp_tensor_desc xi = nt.td(c.l, c.Cin, c.Cin), xo = nt.td(c.l, c.Cout, c.Cout);
-        if (conv_repack_kind(&xi, &xo, c.parts) >= 0) b += conv_repack_bytes(&xi, &xo);
+        if (conv_repack_kind(&xi, &xo, false) >= 0) b += conv_repack_bytes(&xi, &xo);
         if (bwd && conv_repack_kind(&xo, &xi, c.parts) >= 0) b += conv_repack_bytes(&xo, &xi);
     }
     return b;
@@ -307,7 +305,7 @@ static lamp_status prepare_repack(const Net& nt, const Layout& lay, int first, i
             if (dir == 0 ? !fwd : !(dgrad && c.dgrad)) continue;
             const lamp_tensor_desc* xd = dir == 0 ? &xi : &xo;   // the conv's input / output in this direction
             const lamp_tensor_desc* zd = dir == 0 ? &xo : &xi;
-            const int kind = conv_repack_kind(xd, zd, c.parts, c.parts && dir == 1);
+            const int kind = conv_repack_kind(xd, zd, c.parts && dir == 1);
             if (kind < 0 || tab.n >= 64 || !aligned16(P[c.pi])) continue;
             const size_t b = conv_repack_bytes(xd, zd);
             if (off + b > lay.repack_bytes) continue;

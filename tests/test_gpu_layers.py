@@ -511,14 +511,6 @@ def test_determinism_bitwise(L):
         assert torch.equal(a, b)
 
 
-def test_probe_mfma_rate(L):
-    """The diagnostic entry point runs for every operand pattern and rejects an unknown one."""
-    rates = [L.lamp_probe_mfma_rate(p, 200) for p in (0, 1, 2)]
-    assert all(r > 10.0 for r in rates), rates
-    with pytest.raises(Exception):
-        L.lamp_probe_mfma_rate(3, 200)
-
-
 def test_rmsprop_step(L):
     """RMSProp update of several tensors in one call (odd sizes, a zero-sized one, fp32 and bf16 working
     copies) against the fp64 oracle; the bf16 copy is the new master rounded to nearest even."""
@@ -542,40 +534,3 @@ def test_rmsprop_step(L):
         if outs[i] is not None:
             ref = O.round_bf16(as64(w[i])) if outs[i].dtype == BF else as64(w[i])
             np.testing.assert_array_equal(as64(outs[i]), ref)
-
-
-def test_ring_kernel_variant_in_a_child_process():
-    """The ring variant of the matrix-core conv is no longer selected automatically; LAMP_CONV_KERNEL=ring
-    (read once per process) still selects it.  A child process runs it on a shape with ragged tile edges,
-    forward with statistics and data gradient, against the oracle."""
-    import os
-    import subprocess
-    import sys
-    code = r'''
-import sys
-import numpy as np, torch
-sys.path.insert(0, "tests")
-import lamp_synth as S, oracle as O, paper_2006_12575_amd as L
-from gpu_util import DEV, as64, check, to_dev
-BF, F32 = torch.bfloat16, torch.float32
-r = np.random.Generator(np.random.PCG64(77))
-for (N, D, H, W, Ci, Co) in [(1, 12, 20, 36, 64, 64), (2, 5, 9, 17, 64, 128)]:
-    x = to_dev(S.normal(r, (N, D, H, W, Ci)), BF)
-    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
-    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
-    st = torch.empty((N, Co, 2), dtype=F32, device=DEV)
-    L.lamp_conv3d_fwd(x, w, z, stats_out=st)
-    check(as64(z), O.conv3d_fwd(as64(x), as64(w)), BF, "ring conv fwd")
-    _, st_ref = O.inorm_relu(as64(z))
-    check(as64(st)[..., 0], st_ref[..., 0], F32, "ring stats mean", tol=1e-4)
-    np.testing.assert_allclose(as64(st)[..., 1], st_ref[..., 1], rtol=2e-4)
-    dz = to_dev(S.normal(r, (N, D, H, W, Co)), BF)
-    dx = torch.empty_like(x)
-    L.lamp_conv3d_dgrad(dz, w, dx)
-    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), BF, "ring conv dgrad")
-print("ring ok")
-'''
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, LAMP_CONV_KERNEL="ring", PYTHONPATH=root + os.pathsep + os.environ.get("PYTHONPATH", ""))
-    res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=300)
-    assert res.returncode == 0 and "ring ok" in res.stdout, res.stdout[-2000:] + res.stderr[-2000:]
