@@ -258,17 +258,24 @@ def conv3d_dgrad_at(dz, w, coords):
 
 def conv3d_wgrad_at(x, dz, entries):
     """O3 evaluated only at the listed weight entries.  entries: [S,5] of (co,kd,kh,kw,ci).
-    Each is a full reduction over the volume (a shifted dot product)."""
+    Each is a full reduction over the volume (a shifted dot product of one channel of dz with one
+    channel of x); a channel's plane is gathered from the NDHWC tensor once and kept for the
+    entries that share it."""
     N, D, H, W, Ci = x.shape
     out = np.zeros(len(entries))
+    gp, xp = {}, {}
     for s, (co, kd, kh, kw, ci) in enumerate(entries):
+        if co not in gp:
+            gp[co] = np.ascontiguousarray(dz[..., co], dtype=np.float64)
+        if ci not in xp:
+            xp[ci] = np.ascontiguousarray(x[..., ci], dtype=np.float64)
         # output voxel (d,h,w) pairs with input voxel (d+kd-1, h+kh-1, w+kw-1)
         od0, od1 = max(0, 1 - kd), min(D, D + 1 - kd)
         oh0, oh1 = max(0, 1 - kh), min(H, H + 1 - kh)
         ow0, ow1 = max(0, 1 - kw), min(W, W + 1 - kw)
-        g = dz[:, od0:od1, oh0:oh1, ow0:ow1, co].astype(np.float64)
-        xx = x[:, od0 + kd - 1:od1 + kd - 1, oh0 + kh - 1:oh1 + kh - 1, ow0 + kw - 1:ow1 + kw - 1, ci].astype(np.float64)
-        out[s] = float(np.sum(g * xx))
+        g = gp[co][:, od0:od1, oh0:oh1, ow0:ow1]
+        xx = xp[ci][:, od0 + kd - 1:od1 + kd - 1, oh0 + kh - 1:oh1 + kh - 1, ow0 + kw - 1:ow1 + kw - 1]
+        out[s] = float(np.einsum("ndhw,ndhw->", g, xx))
     return out
 
 

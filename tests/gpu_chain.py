@@ -71,7 +71,7 @@ class Chain:
         """kind 'fwd': out = conv(a, w); 'dgrad': out = conv^T(a, w)."""
         # the oracle spends 27 * Ci * Co multiply-adds per sampled voxel: fewer voxels for very wide layers
         per_voxel = 27 * int(w.shape[0]) * int(w.shape[4])
-        coords = self._coords(out.shape[:4], max(24, min(self.nsample, int(3e9 // per_voxel))))
+        coords = self._coords(out.shape[:4], max(128, min(self.nsample, int(3e9 // per_voxel))))
         ah, oh = self._host(a), self._host(out)
         f = O.conv3d_fwd_at if kind == "fwd" else O.conv3d_dgrad_at
         ref = f(ah, as64(w), None, coords) if kind == "fwd" else f(ah, as64(w), coords)
@@ -80,20 +80,62 @@ class Chain:
         self.worst[f"conv {kind}"] = max(self.worst.get(f"conv {kind}", 0.0), e)
         self._count(f"conv {kind}")
 
+    @staticmethod
+    def _block_edges(C):
+        """Channel indices on both sides of every 32-channel block boundary (the matrix-core kernels' workgroup and
+        fragment blocks), plus the ends."""
+        e = {0, C - 1}
+        for b in range(32, C, 32):
+            e.update((b - 1, b))
+        return sorted(e)
+
+    def _wgrad_entries(self, Co, Ci, per_tap=10):
+        """>= 27 * per_tap entries (co, kd, kh, kw, ci): every one of the 27 taps, and across the taps every
+        32-channel block boundary of both channel axes (cycled through, so wide layers are covered too), then
+        random ones."""
+        eo, ei = self._block_edges(Co), self._block_edges(Ci)
+        # at most 10 distinct channels per axis (the oracle gathers one plane of the volume per channel): the two
+        # ends and a seeded choice of the block boundaries
+        pick = lambda e: sorted({e[0], e[-1], *[e[int(i)] for i in self.rng.choice(len(e), size=min(8, len(e)), replace=False)]})
+        eo, ei = pick(eo), pick(ei)
+        ro = [int(v) for v in self.rng.integers(Co, size=4)]
+        ri = [int(v) for v in self.rng.integers(Ci, size=4)]
+        ent = set()
+        io = ii = 0
+        for t in range(27):
+            kd, kh, kw = t // 9, (t // 3) % 3, t % 3
+            for j in range(per_tap):
+                if j < per_tap // 2:      # boundary x boundary
+                    co, ci = eo[io % len(eo)], ei[ii % len(ei)]
+                    io += 1
+                    ii += 3               # a different stride, so the pairs do not stay in step
+                elif j < per_tap - 2:     # boundary x random, random x boundary
+                    if j % 2:
+                        co, ci = eo[io % len(eo)], ri[int(self.rng.integers(4))]
+                        io += 1
+                    else:
+                        co, ci = ro[int(self.rng.integers(4))], ei[ii % len(ei)]
+                        ii += 1
+                else:
+                    co, ci = ro[int(self.rng.integers(4))], ri[int(self.rng.integers(4))]
+                ent.add((co, kd, kh, kw, ci))
+        allc, alli = eo + ro, ei + ri
+        while len(ent) < min(256, 27 * len(set(allc)) * len(set(alli))):   # duplicates of a narrow layer: top up
+            ent.add((allc[int(self.rng.integers(len(allc)))], int(self.rng.integers(3)), int(self.rng.integers(3)),
+                     int(self.rng.integers(3)), alli[int(self.rng.integers(len(alli)))]))
+        return sorted(ent)
+
     def _sampled_wgrad(self, name, x, dz, dw):
         Co, _, _, _, Ci = dw.shape
-        ent = {(0, 0, 0, 0, 0), (Co - 1, 2, 2, 2, Ci - 1), (Co - 1, 0, 2, 0, 0), (0, 1, 1, 1, Ci - 1)}
-        while len(ent) < 16:
-            ent.add((int(self.rng.integers(Co)), int(self.rng.integers(3)), int(self.rng.integers(3)),
-                     int(self.rng.integers(3)), int(self.rng.integers(Ci))))
-        ent = sorted(ent)
+        ent = self._wgrad_entries(Co, Ci) if Ci * Co * 27 >= 270 else [(co, t // 9, (t // 3) % 3, t % 3, ci)
+                                                                        for co in range(Co) for t in range(27) for ci in range(Ci)]
         ref = O.conv3d_wgrad_at(self._host(x), self._host(dz), ent)
         dwh = as64(dw)
         got = np.array([dwh[e] for e in ent])
         # scale: the largest entry of the whole gradient tensor (the metric of the full check)
         err = float(np.max(np.abs(got - ref)) / np.max(np.abs(dwh)))
         tol = 2e-3 if self.dtype != F32 else 1e-4
-        assert err <= tol, f"conv wgrad (sampled): {name}: E_inf = {err:.2e} > {tol:g}"
+        assert err <= tol, f"conv wgrad (sampled, {len(ent)} entries): {name}: E_inf = {err:.2e} > {tol:g}"
         self.worst["conv wgrad"] = max(self.worst.get("conv wgrad", 0.0), err)
         self._count("conv wgrad")
 

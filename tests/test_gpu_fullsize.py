@@ -117,9 +117,14 @@ def test_conv_wgrad_sampled(block):
     r = np.random.Generator(np.random.PCG64(33))
     x = block["x"].cpu().float().numpy()
     dz = block["dz"].cpu().float().numpy()
-    ent = [(0, 0, 0, 0, 0), (C - 1, 2, 2, 2, C - 1), (31, 1, 1, 1, 32), (32, 0, 2, 1, 31), (5, 2, 0, 0, 63)]
-    ent += [tuple(int(v) for v in (r.integers(0, C), r.integers(0, 3), r.integers(0, 3), r.integers(0, 3), r.integers(0, C)))
-            for _ in range(120)]
+    # every tap at every combination of the channels next to the 32-channel block boundaries (the weight-gradient
+    # kernel's workgroup blocks of input channels and fragment blocks of output channels), then random entries
+    edge = (0, 31, 32, C - 1)
+    ent = {(co, t // 9, (t // 3) % 3, t % 3, ci) for t in range(27) for co in edge for ci in edge}
+    rc = [int(v) for v in r.integers(0, C, 6)]
+    while len(ent) < 27 * 16 + 120:
+        ent.add((rc[int(r.integers(6))], int(r.integers(3)), int(r.integers(3)), int(r.integers(3)), rc[int(r.integers(6))]))
+    ent = sorted(ent)
     ref = O.conv3d_wgrad_at(x, dz, ent)
     dw = as64(block["dw"])
     got = np.array([dw[e] for e in ent])
@@ -425,3 +430,36 @@ def test_wide_unet_train_sampled(L, base, dims, seed):
     print("checked ops:", ch.checked)
     print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
     assert ch.checked["conv fwd"] == 18 and ch.checked["conv dgrad"] == 17 and ch.checked["conv wgrad"] == 18
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("shape", [(1, 8, 8, 8, 2048, 2048), (1, 16, 16, 16, 2048, 1024), (2, 8, 8, 8, 1024, 1024)],
+                         ids=["base128-level5", "base128-dec4", "base64-level5"])
+def test_wide_layers_at_bench_size(L, shape):
+    """The 1024- and 2048-channel convolutions of the wide nets at exactly the shapes bench.py times them on
+    (base 128 on 1 x 128^3: 8^3 and 16^3 voxels at levels 5 and 4; base 64 on 2 x 128^3: 2 x 8^3): forward with
+    fused statistics, data gradient and weight gradient through the layer entry points, checked on sampled
+    outputs (at least 128 voxels x all channels; every tap and block boundary of the weight gradient) that the
+    oracle computes one by one from the same inputs."""
+    from gpu_chain import Chain
+    N, D, H, W, Ci, Co = shape
+    r = np.random.Generator(np.random.PCG64(4000 + Ci + Co))
+    x = torch.from_numpy(S.normal(r, (N, D, H, W, Ci))).to(BF).to(DEV)
+    w = torch.from_numpy(S.kaiming_conv(r, Co, Ci)).to(BF).to(DEV)
+    dz = torch.from_numpy(S.normal(r, (N, D, H, W, Co))).to(BF).to(DEV)
+    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    st = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+    dx = torch.empty_like(x)
+    dw = torch.empty(w.shape, dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=st)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    L.lamp_conv3d_wgrad(x, dz, dw)
+    ch = Chain(L, 1, 32, 1, 2, False, BF, [], [], verify="sampled")
+    ch.nsample = 128
+    ch._sampled_conv("fwd", f"wide {shape}", x, w, z)
+    ch._sampled_conv("dgrad", f"wide {shape}", dz, w, dx)
+    ch._sampled_wgrad(f"wide {shape}", x, dz, dw)
+    _, st_ref = O.inorm_relu(as64(z))
+    np.testing.assert_allclose(as64(st)[..., 0], st_ref[..., 0], atol=1e-4 * np.abs(st_ref[..., 0]).max() + 1e-5)
+    np.testing.assert_allclose(as64(st)[..., 1], st_ref[..., 1], rtol=2e-4)
+    print("worst sampled E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})

@@ -534,3 +534,43 @@ def test_rmsprop_step(L):
         if outs[i] is not None:
             ref = O.round_bf16(as64(w[i])) if outs[i].dtype == BF else as64(w[i])
             np.testing.assert_array_equal(as64(outs[i]), ref)
+
+
+def test_deep_tile_instantiations_in_full_in_a_child_process():
+    """The 8-deep tile of the matrix-core conv (the instantiation the benchmark's large volumes take) is chosen
+    by the shape; small volumes never reach it, so the other tests see it only through samples of full-size
+    outputs.  LAMP_TUNE=tile_depth=8 (read once per process) forces it: a child process runs forward (with bias
+    and fused statistics) and data gradient on moderate volumes with ragged tile edges, for both widths of the
+    output-channel block, and compares EVERY output element with the oracle."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import sys
+import numpy as np, torch
+sys.path.insert(0, "tests")
+import lamp_synth as S, oracle as O, paper_2006_12575_amd as L
+from gpu_util import DEV, as64, check, to_dev
+BF, F32 = torch.bfloat16, torch.float32
+r = np.random.Generator(np.random.PCG64(177))
+for (N, D, H, W, Ci, Co) in [(1, 24, 24, 48, 64, 64), (2, 11, 9, 20, 32, 32), (1, 9, 17, 33, 64, 32), (1, 8, 8, 16, 32, 128)]:
+    x = to_dev(S.normal(r, (N, D, H, W, Ci)), BF)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
+    b = to_dev(S.normal(r, (Co,), 0.1), F32)
+    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    st = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, bias=b, stats_out=st)
+    check(as64(z), O.conv3d_fwd(as64(x), as64(w), as64(b)), BF, f"8-deep conv fwd {(N, D, H, W, Ci, Co)}")
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(st)[..., 0], st_ref[..., 0], F32, "8-deep stats mean", tol=1e-4)
+    np.testing.assert_allclose(as64(st)[..., 1], st_ref[..., 1], rtol=2e-4)
+    dz = to_dev(S.normal(r, (N, D, H, W, Co)), BF)
+    dx = torch.empty_like(x)
+    L.lamp_conv3d_dgrad(dz, w, dx)
+    check(as64(dx), O.conv3d_dgrad(as64(dz), as64(w)), BF, f"8-deep conv dgrad {(N, D, H, W, Ci, Co)}")
+print("deep tile ok")
+'''
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, LAMP_TUNE="tile_depth=8", PYTHONPATH=root + os.pathsep + os.environ.get("PYTHONPATH", ""))
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0 and "deep tile ok" in res.stdout, res.stdout[-2000:] + res.stderr[-2000:]

@@ -3,8 +3,10 @@ encoder partition, sliding-window inference) against the network oracle.
 
 bf16 runs are compared with the oracle that rounds every stored activation / gradient tensor to
 bf16 at the same tensor boundaries (storage emulation); fp32 runs with the pure fp64 oracle.
-End-to-end gradients are judged on the weight gradients (sums over >= 10^3 voxels, where an
-isolated ReLU-mask or arg-max flip at a near-tie averages out) and on the loss.
+End-to-end gradients are judged on the weight gradients and on the loss.  Two bf16 realisations of a deep net
+drift apart through ReLU-mask and arg-max flips at near-ties, by an amount the oracle itself can measure: the
+bound on each gradient tensor's relative L2 distance to the storage-emulating oracle is calibrated on the
+distance between perturbed runs of that oracle (gpu_util.realisation_spread).
 """
 import numpy as np
 import pytest
@@ -12,11 +14,14 @@ import torch
 
 import lamp_synth as S
 import oracle as O
-from gpu_util import DEV, TOL, as64, check, e2, to_dev
+from gpu_util import DEV, TOL, as64, check, check_e2_calibrated, e2, realisation_spread, to_dev
 from oracle import sliding, unet
 
 pytestmark = pytest.mark.gpu
 BF, F32 = torch.bfloat16, torch.float32
+# End-to-end weight gradients of the fp32 path against the pure fp64 oracle: the path's stated bound (E_inf relative to
+# the tensor's largest entry).  Measured on the MI355X: 5e-8 ... 1.5e-6 on every gradient tensor of the fp32 net.
+FP32_GRAD_TOL = 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -93,16 +98,19 @@ def test_unet_fwd_bwd(L, cfg):
     print("worst teacher-forced E_inf per op:", {k: f"{v:.1e}" for k, v in ch.worst.items()})
     # (c)
     store = O.round_bf16 if dtype == BF else (lambda a: a)
-    loss_ref, g_ref, lg_ref, _ = unet.loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, store=store)
+    run = lambda st: unet.loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, store=st)
+    loss_ref, g_ref, lg_ref, _ = run(store)
     check(as64(logits), lg_ref, dtype, "logits", tol=1e-2 if dtype == BF else 1e-4)
     assert abs(loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
-    for k, g in zip(names, grads):
-        a, b = as64(g).ravel(), g_ref[k].ravel()
-        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
-        if dtype == F32:
-            check(as64(g), g_ref[k], dtype, f"grad {k}", tol=1e-3)
-        else:
-            assert cos > 0.9, f"grad {k}: cosine {cos:.3f} to the storage-emulating oracle"
+    if dtype == F32:
+        for k, g in zip(names, grads):
+            check(as64(g), g_ref[k], dtype, f"grad {k}", tol=FP32_GRAD_TOL)
+    else:
+        spread = realisation_spread(lambda st: run(st)[1], g_ref)
+        rep = {}
+        for k, g in zip(names, grads):
+            rep[k] = check_e2_calibrated(as64(g), g_ref[k], spread[k], f"grad {k}")
+        print("end-to-end grad E2 (bound):", {k: f"{e:.1e} ({b:.1e})" for k, (e, b) in rep.items()})
     # forward-only entry point gives the same logits; beta=1 accumulates
     l2 = torch.empty_like(logits)
     L.lamp_unet_fwd(ud, dev, x, l2)
@@ -154,11 +162,13 @@ def test_stage_partition_fwd_bwd(L):
         g = ch.conv_bwd(c1, g, cg, l > 1)
     for k, gr in zip(names[:4], grads):
         assert torch.equal(gr, cg[k]), f"stage grad {k} differs from the chain"
-    g_ref, _ = unet.stage_backward(ora, cache, as64(gp), [as64(t) for t in gs], 1, 2, levels, store=O.round_bf16)
+    def stage_grads(st):
+        _, c = unet.forward(ora, as64(x), levels, store=st, first_level=1, last_level=2)
+        return unet.stage_backward(ora, c, as64(gp), [as64(t) for t in gs], 1, 2, levels, store=st)[0]
+    g_ref = stage_grads(O.round_bf16)
+    spread = realisation_spread(stage_grads, g_ref)
     for k, gr in zip(names[:4], grads):
-        a, b = as64(gr).ravel(), g_ref[k].ravel()
-        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
-        assert cos > 0.95, f"stage grad {k}: cosine {cos:.3f}"
+        check_e2_calibrated(as64(gr), g_ref[k], spread[k], f"stage grad {k}")
 
 
 def _stage_shapes(N, D, H, W, base, cut):
@@ -210,15 +220,16 @@ def test_tail_partition_fwd_bwd(L, cut, affine):
     for k, a, b in zip(names[:toff], gs, grads[:toff]):
         assert torch.equal(a, b), f"partition-0 grad {k} (from the tail's cut gradients) differs from the whole net's"
     # the cut-crossing gradients against the oracle's tail, fed with the GPU's partition-0 outputs
-    lg_ref, c1 = unet.tail_forward(ora, as64(pooled), [as64(t) for t in skips], cut + 1, levels, store=O.round_bf16)
+    def tail_cut_grads(st):
+        lg, c = unet.tail_forward(ora, as64(pooled), [as64(t) for t in skips], cut + 1, levels, store=st)
+        _, dl = O.cross_entropy(lg, lab.cpu().numpy())
+        _, gp_r, gsk_r = unet.tail_backward(ora, c, dl, cut + 1, levels, store=st)
+        return dict([("d_x", gp_r)] + [(f"d_skip{i + 1}", r) for i, r in enumerate(gsk_r)]), lg
+    cut_ref, lg_ref = tail_cut_grads(O.round_bf16)
     check(as64(lt), lg_ref, dtype, "tail logits")
-    _, dl = O.cross_entropy(lg_ref, lab.cpu().numpy())
-    _, gp_ref, gsk_ref = unet.tail_backward(ora, c1, dl, cut + 1, levels, store=O.round_bf16)
-    for nm, a, b in [("d_x", d_x, gp_ref)] + [(f"d_skip{i + 1}", t, r) for i, (t, r) in enumerate(zip(d_skips, gsk_ref))]:
-        a, b = as64(a).ravel(), b.ravel()
-        assert np.isfinite(a).all()
-        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
-        assert cos > 0.98, f"{nm}: cosine {cos:.4f} to the storage-emulating oracle"
+    spread = realisation_spread(lambda st: tail_cut_grads(st)[0], cut_ref)
+    for nm, a in [("d_x", d_x)] + [(f"d_skip{i + 1}", t) for i, t in enumerate(d_skips)]:
+        check_e2_calibrated(as64(a), cut_ref[nm], spread[nm], f"tail {nm}")
     # argument errors are found on the host
     with pytest.raises(RuntimeError):
         L.lamp_unet_tail_fwd(ud, 1, dev, pooled, skips, lt)          # first_level 1 is the whole net
@@ -274,16 +285,14 @@ def test_pipeline_two_partitions_micro_batches(L, cut, n, M, affine):
         # exact result, so twice the bound; gradients: direction, as against the oracle.
         check(as64(lg), as64(lg_full), dtype, "pipeline logits vs mini-batch run", tol=2 * TOL[dtype])
         assert abs(loss.item() - loss_full.item()) <= 1e-3 * abs(loss_full.item())
-        for k, a, b in zip(names, g, g_full):
-            a, b = as64(a).ravel(), as64(b).ravel()
-            cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
-            assert cos > 0.99, f"pipeline grad {k}: cosine {cos:.4f} to the mini-batch run"
-    loss_ref, g_ref = unet.pipeline_loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, cut, M, store=O.round_bf16)
+    pipe = lambda st: unet.pipeline_loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, cut, M, store=st)
+    loss_ref, g_ref = pipe(O.round_bf16)
     assert abs(loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
-    for k, a in zip(names, g):
-        a, b = as64(a).ravel(), g_ref[k].ravel()
-        cos = float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b) + 1e-300))
-        assert cos > 0.9, f"pipeline grad {k}: cosine {cos:.3f} to the oracle's pipeline"
+    spread = realisation_spread(lambda st: pipe(st)[1], g_ref)
+    for k, a, b in zip(names, g, g_full):
+        check_e2_calibrated(as64(a), g_ref[k], spread[k], f"pipeline grad {k}")
+        # the one-call mini-batch run is one more realisation of the same quantities
+        check_e2_calibrated(as64(b), g_ref[k], spread[k], f"mini-batch grad {k} against the oracle's pipeline")
     # beta = 1 accumulates onto what is there
     g2 = [t.clone() for t in g]
     L.lamp_unet_pipeline_fwd_bwd(mb, cut, M, dev, x, lab, loss, g2, aux, beta=1.0, ws=ws)
