@@ -153,6 +153,19 @@ lamp_status lamp_inorm_relu(const lamp_tensor_desc *zd, const void *z,
                             float *stats, int stats_given,
                             void *ws, size_t ws_bytes, void *stream);
 
+/* lamp_inorm_relu for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same operation with stats_given = 0 and no workspace argument.  The partial moments of
+ * the statistics pass live in a fixed device array of LAMP_NOALLOC_SCRATCH_BYTES (8 MiB) inside the library, one
+ * copy per GPU, held until the process ends; the call allocates and frees nothing.  The scratch's device address is
+ * looked up on the first call on each device (that first call must happen outside a stream capture).
+ * Limit: lamp_inorm_relu_workspace_bytes(zd) <= 8 MiB (e.g. 2 x 128^3 x 256 channels), else LAMP_ERR_WORKSPACE and
+ * nothing is launched.  Every call on one GPU shares the scratch: calls that overlap on one GPU (two streams, two
+ * threads) race; calls on one stream are ordered and need no clearing in between.
+ * Errors: as lamp_inorm_relu, plus LAMP_ERR_WORKSPACE (need above the limit), LAMP_ERR_HIP (symbol lookup). */
+#define LAMP_NOALLOC_SCRATCH_BYTES (8u << 20)
+lamp_status lamp_inorm_relu_noalloc(const lamp_tensor_desc *zd, const void *z, const float *gamma, const float *beta,
+                                    float eps, const lamp_tensor_desc *yd, void *y, float *stats, void *stream);
+
 /* Backward of InstanceNorm + ReLU.  With zh = (z-mean)*rstd, u = gamma*zh+beta, g = dy*[u>0]:
  *   dz = gamma*rstd*( g - mean_v(g) - zh*mean_v(g*zh) )        per (n,c)
  *   dgamma[c] = beta_acc*dgamma + sum_{n,v} g*zh ; dbeta[c] = beta_acc*dbeta + sum_{n,v} g   (nullable)

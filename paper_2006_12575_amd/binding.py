@@ -61,6 +61,7 @@ _SIGS = {
     "lamp_conv3d_wgrad": (c_int, [_PD, _VP, _PN, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_inorm_relu_workspace_bytes": (c_size_t, [_PD]),
     "lamp_inorm_relu": (c_int, [_PD, _VP, _VP, _VP, c_float, _PD, _VP, _VP, c_int, _VP, c_size_t, _VP]),
+    "lamp_inorm_relu_noalloc": (c_int, [_PD, _VP, _VP, _VP, c_float, _PD, _VP, _VP, _VP]),
     "lamp_inorm_relu_bwd_workspace_bytes": (c_size_t, [_PD]),
     "lamp_inorm_relu_bwd": (c_int, [_PD, _VP, _PD, _VP, _VP, _VP, _VP, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_maxpool2_fwd": (c_int, [_PD, _VP, _PN, _PD, _VP, _VP]),
@@ -232,6 +233,14 @@ def lamp_inorm_relu(z, y, stats, gamma=None, beta=None, eps=1e-5, stats_given=Fa
     ws = ws if ws is not None else _ws(need, z.device)
     _check(lib().lamp_inorm_relu(ctypes.byref(zd), _ptr(z), _ptr(gamma), _ptr(beta), eps, ctypes.byref(yd), _ptr(y),
                                  _ptr(stats), 1 if stats_given else 0, _ptr(ws), ws.numel(), _stream()), "lamp_inorm_relu")
+    return y
+
+
+def lamp_inorm_relu_noalloc(z, y, stats, gamma=None, beta=None, eps=1e-5):
+    """lamp_inorm_relu (statistics computed here) without a workspace: the library's fixed per-GPU scratch is used."""
+    zd, yd = desc(z), desc(y)
+    _check(lib().lamp_inorm_relu_noalloc(ctypes.byref(zd), _ptr(z), _ptr(gamma), _ptr(beta), eps, ctypes.byref(yd), _ptr(y),
+                                         _ptr(stats), _stream()), "lamp_inorm_relu_noalloc")
     return y
 
 

@@ -1,10 +1,34 @@
 // InstanceNorm + ReLU: statistics (two-stage, deterministic), apply, and backward.
 // Bandwidth-bound kernels on NDHWC tensors; fp32 arithmetic, fp64 merging of partial moments.
 #include <initializer_list>
+#include <mutex>
 #include "internal.h"
 #include "vec.h"
 
+// Scratch of the allocation-free entry point (lamp_inorm_relu_noalloc): partial moments and per-chunk counts of
+// the statistics pass (LAMP_NOALLOC_SCRATCH_BYTES of the public header).  One copy per GPU, held until the process
+// ends; every call on a GPU shares it.
+static __device__ __align__(256) unsigned char scratch[LAMP_NOALLOC_SCRATCH_BYTES];
+
 namespace lamp {
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a stand-in for
+// the symbol, never an address a kernel may get: the address is looked up once per device, with that device
+// current, and kept.
+static lamp_status noalloc_scratch(void** out) {
+    static std::mutex mu;
+    static void* cache[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LAMP_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cache[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LAMP_ERR_HIP;
+        cache[dev] = p;
+    }
+    *out = cache[dev];
+    return LAMP_OK;
+}
 
 
 // Rows of one partial sum: about 2048 chunks per sample so that small volumes still fill the chip,
@@ -471,6 +495,20 @@ extern "C" lamp_status lamp_inorm_relu(const lamp_tensor_desc* zd, const void* z
     });
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
+}
+
+extern "C" lamp_status lamp_inorm_relu_noalloc(const lamp_tensor_desc* zd, const void* z, const float* gamma,
+                                               const float* beta, float eps, const lamp_tensor_desc* yd, void* y,
+                                               float* stats, void* stream) {
+    if (!zd || !yd || !z || !y || !stats) return LAMP_ERR_NULL;
+    if (!desc_ok(zd) || !desc_ok(yd)) return LAMP_ERR_SHAPE;
+    if (stats_ws_bytes(zd) > (size_t)LAMP_NOALLOC_SCRATCH_BYTES) return LAMP_ERR_WORKSPACE;   // beyond the fixed scratch
+    void* ptr = nullptr;
+    lamp_status st = noalloc_scratch(&ptr);
+    if (st != LAMP_OK) return st;
+    // Nothing in the scratch has to start at zero: the statistics pass writes every partial and every count
+    // that its second stage reads, so what the previous call left there is never seen.
+    return lamp_inorm_relu(zd, z, gamma, beta, eps, yd, y, stats, 0, ptr, (size_t)LAMP_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" size_t lamp_inorm_relu_bwd_workspace_bytes(const lamp_tensor_desc* zd) {
