@@ -38,6 +38,8 @@
  *       no_split=1            no input-channel split for few-tile, many-channel layers
  *       cb_outer=1            output-channel blocks as grid.y instead of side by side on one XCD
  *       materialise_concat=1  the network entry points keep one concat buffer per decoder level
+ *       super_block=DHW       tiles of the matrix-core conv numbered in blocks of D x H x W tiles (decimal
+ *                             digits, default 244; 0: plain w-h-d order)
  */
 #ifndef LAMP_H
 #define LAMP_H
@@ -274,6 +276,11 @@ lamp_status lamp_head_ce(const lamp_tensor_desc *xd, const void *x, const lamp_n
  *                           dec l conv1 W [C_l][3][3][3][2C_l] [, gamma, beta], conv2 W [, gamma, beta]
  *   head Wh [classes][C_1], head bias [classes] (fp32)
  * gamma/beta entries exist only when affine != 0 (fp32 [C]).  W/Wt/Wh have dtype `dtype`.
+ * Squeeze-and-excitation variant (the SEU-Net that Sec. 1 names through its citations; se_ratio > 0): every block
+ * becomes  a1 = unit1(x),  a2 = ReLU(InstanceNorm(conv2(a1))),  out = a1 + gate(mean_v a2) * a2  with the gate of
+ * lamp_inorm_relu_se and cr = max(1, C_l / se_ratio) hidden units; four fp32 entries follow the block's two convs in
+ * the table: gate W1 [cr][C_l], b1 [cr], W2 [C_l][cr], b2 [C_l].  Served by lamp_unet_fwd and lamp_unet_fwd_bwd;
+ * the partition, tail, pipeline entry points return LAMP_ERR_UNSUPPORTED for it (lamp_sliding_window_fwd serves it).
  * `grads` has the same order; every entry fp32 with the parameter's shape; beta = 0 overwrites,
  * beta = 1 accumulates (micro-batch accumulation, Sec. 2.1).
  */
@@ -283,6 +290,7 @@ typedef struct {
     int32_t dtype; /* lamp_dtype of activations and weights */
     float eps;
     int32_t affine;
+    int32_t se_ratio; /* 0: plain U-Net; r > 0: squeeze-and-excitation blocks with reduction ratio r */
 } lamp_unet_desc;
 
 /* Number of entries of the parameter table, and the element count of entry idx (0 on bad idx). */

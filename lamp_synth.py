@@ -70,8 +70,9 @@ def organ_labels(rng, n, d, h, w, classes=10, n_organs=10):
     return out
 
 
-def unet_param_names(levels, affine):
-    """Parameter tensors of the U-Net in the library's documented order."""
+def unet_param_names(levels, affine, se_ratio=0):
+    """Parameter tensors of the U-Net in the library's documented order (se_ratio > 0: the squeeze-and-excitation
+    variant, four gate tensors behind each block's convs)."""
     names = []
 
     def block(prefix):
@@ -80,6 +81,8 @@ def unet_param_names(levels, affine):
             if affine:
                 names.append(f"{prefix}.conv{i}.gamma")
                 names.append(f"{prefix}.conv{i}.beta")
+        if se_ratio:
+            names.extend(f"{prefix}.se.{k}" for k in ("w1", "b1", "w2", "b2"))
 
     for l in range(1, levels + 1):
         block(f"enc{l}")
@@ -91,9 +94,10 @@ def unet_param_names(levels, affine):
     return names
 
 
-def unet_params(rng, levels, base, in_ch, classes, affine=False, test_mode=False, dtype=np.float32):
+def unet_params(rng, levels, base, in_ch, classes, affine=False, test_mode=False, dtype=np.float32, se_ratio=0):
     """Ordered dict name -> array.  Kaiming-normal weights; biases 0 (benchmarks) or N(0,0.1^2)
-    (test_mode); gamma U(0.5,1.5), beta U(-0.5,0.5) when affine."""
+    (test_mode); gamma U(0.5,1.5), beta U(-0.5,0.5) when affine.  se_ratio > 0 adds each block's gate:
+    w1 [C/r, C] ~ N(0, 1/C), w2 [C, C/r] ~ N(0, 1/(C/r)) in float32, biases 0 or N(0, 0.1^2)."""
     p = {}
     ch = [base * 2 ** (l - 1) for l in range(1, levels + 1)]
 
@@ -103,6 +107,12 @@ def unet_params(rng, levels, base, in_ch, classes, affine=False, test_mode=False
             if affine:
                 p[f"{prefix}.conv{i}.gamma"] = rng.uniform(0.5, 1.5, co).astype(np.float32)
                 p[f"{prefix}.conv{i}.beta"] = rng.uniform(-0.5, 0.5, co).astype(np.float32)
+        if se_ratio:
+            cr = max(1, co // se_ratio)
+            p[f"{prefix}.se.w1"] = normal(rng, (cr, co), np.sqrt(1.0 / co))
+            p[f"{prefix}.se.b1"] = normal(rng, (cr,), 0.1) if test_mode else np.zeros(cr, np.float32)
+            p[f"{prefix}.se.w2"] = normal(rng, (co, cr), np.sqrt(1.0 / cr))
+            p[f"{prefix}.se.b2"] = normal(rng, (co,), 0.1) if test_mode else np.zeros(co, np.float32)
 
     for l in range(1, levels + 1):
         block(f"enc{l}", in_ch if l == 1 else ch[l - 2], ch[l - 1])
@@ -112,5 +122,5 @@ def unet_params(rng, levels, base, in_ch, classes, affine=False, test_mode=False
         block(f"dec{l}", 2 * ch[l - 1], ch[l - 1])
     p["head.w"] = normal(rng, (classes, ch[0]), np.sqrt(2.0 / ch[0]), dtype)
     p["head.b"] = (normal(rng, (classes,), 0.1) if test_mode else np.zeros(classes, np.float32))
-    assert list(p.keys()) == unet_param_names(levels, affine)
+    assert list(p.keys()) == unet_param_names(levels, affine, se_ratio)
     return p

@@ -18,8 +18,16 @@ Readings where the paper is silent (each also listed in the design notes):
 `store` is applied to every activation / gradient tensor the GPU path keeps in its storage
 dtype (identity for the pure fp64 oracle, oracle.round_bf16 to emulate bf16 storage).
 
+The squeeze-and-excitation variant (Sec. 1 names "SEU-Net" through its citations only; Tables 2, 3 and 5 report
+it): a block whose parameters include `<block>.se.w1` is read as a squeeze-and-excitation residual block,
+    a1 = unit1(x),  a2 = ReLU(InstanceNorm(conv2(a1))),  out = a1 + gate(mean_v a2) * a2,
+with the gate of oracle.se_gate (FC C -> C/r, ReLU, FC C/r -> C, logistic sigmoid).  Where the cited network
+puts the gate and the shortcut inside its block is not in the paper: this placement is a reading
+(parity unpinned against the paper; pinned by finite differences in tests/test_oracle_unet.py).
+
 Parameters are a dict by name:
   enc{l}.conv{1,2}.w [Co,3,3,3,Ci]   (+ .gamma [Co], .beta [Co] when affine)
+  (+ <block>.se.w1 [C/r,C], .se.b1 [C/r], .se.w2 [C,C/r], .se.b2 [C] for the squeeze-and-excitation variant)
   dec{l}.up.w [2C_l,2,2,2,C_l], dec{l}.up.b [C_l], dec{l}.conv{1,2}.w (+ gamma/beta)
   head.w [classes,C_1], head.b [classes]
 """
@@ -34,11 +42,20 @@ def _ident(a):
     return a
 
 
+def _se(params, prefix):
+    return [params[f"{prefix}.se.{k}"] for k in ("w1", "b1", "w2", "b2")] if f"{prefix}.se.w1" in params else None
+
+
 def _block_fwd(params, prefix, a, eps, store, cache):
+    se = _se(params, prefix)
     for i in (1, 2):
         name = f"{prefix}.conv{i}"
         z = store(O.conv3d_fwd(a, params[name + ".w"]))
-        y, stats = O.inorm_relu(z, params.get(name + ".gamma"), params.get(name + ".beta"), eps)
+        if se is not None and i == 2:   # gate on the second unit, the first unit's output as the shortcut
+            y, _ = O.inorm_relu_se(z, params.get(name + ".gamma"), params.get(name + ".beta"), *se, residual=a, eps=eps)
+            stats = None
+        else:
+            y, stats = O.inorm_relu(z, params.get(name + ".gamma"), params.get(name + ".beta"), eps)
         y = store(y)
         cache[name] = dict(x=a, z=z, y=y, stats=stats)
         a = y
@@ -73,10 +90,19 @@ def forward(params, x, levels, eps=1e-5, store=_ident, first_level=1, last_level
 
 
 def _block_bwd(params, prefix, g, eps, store, cache, grads, need_dx=True):
+    se = _se(params, prefix)
+    shortcut = None
     for i in (2, 1):
         name = f"{prefix}.conv{i}"
         c = cache[name]
-        dz, dgam, dbet = O.inorm_relu_bwd(g, c["z"], params.get(name + ".gamma"), params.get(name + ".beta"), eps)
+        if se is not None and i == 2:
+            shortcut = g   # out = a1 + gate * a2: the block's upstream gradient reaches a1 unchanged
+            dz, dgam, dbet, dw1, db1, dw2, db2 = O.inorm_relu_se_bwd(g, c["z"], params.get(name + ".gamma"),
+                                                                     params.get(name + ".beta"), *se, eps=eps)
+            for k, v in zip(("w1", "b1", "w2", "b2"), (dw1, db1, dw2, db2)):
+                grads[f"{prefix}.se.{k}"] = v
+        else:
+            dz, dgam, dbet = O.inorm_relu_bwd(g, c["z"], params.get(name + ".gamma"), params.get(name + ".beta"), eps)
         dz = store(dz)
         if name + ".gamma" in params:
             grads[name + ".gamma"] = dgam
@@ -85,6 +111,8 @@ def _block_bwd(params, prefix, g, eps, store, cache, grads, need_dx=True):
         if i == 1 and not need_dx:
             return None
         g = store(O.conv3d_dgrad(dz, params[name + ".w"]))
+        if i == 2 and shortcut is not None:
+            g = store(g + shortcut)
     return g
 
 

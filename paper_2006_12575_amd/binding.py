@@ -38,7 +38,7 @@ class NormIn(Structure):
 class UnetDesc(Structure):
     _fields_ = [("levels", c_int32), ("base", c_int32), ("in_ch", c_int32), ("classes", c_int32),
                 ("n", c_int32), ("d", c_int32), ("h", c_int32), ("w", c_int32),
-                ("dtype", c_int32), ("eps", c_float), ("affine", c_int32)]
+                ("dtype", c_int32), ("eps", c_float), ("affine", c_int32), ("se_ratio", c_int32)]
 
 
 _lib = None
@@ -336,9 +336,9 @@ def lamp_head_ce(x, wh, bh, labels, loss, logits=None, dx=None, dwh=None, dbh=No
 
 # ---- network calls --------------------------------------------------------------------------------
 
-def unet_desc(levels, base, in_ch, classes, n, d, h, w, dtype, eps=1e-5, affine=False) -> UnetDesc:
+def unet_desc(levels, base, in_ch, classes, n, d, h, w, dtype, eps=1e-5, affine=False, se_ratio=0) -> UnetDesc:
     code = {torch.float32: F32, torch.bfloat16: BF16}[dtype]
-    return UnetDesc(levels, base, in_ch, classes, n, d, h, w, code, eps, 1 if affine else 0)
+    return UnetDesc(levels, base, in_ch, classes, n, d, h, w, code, eps, 1 if affine else 0, int(se_ratio))
 
 
 def lamp_unet_param_count(ud):

@@ -118,6 +118,10 @@ struct ConvArgs {
     int32_t* counts;    // [tiles_per_n] in-volume voxels per tile (written when part != nullptr)
     const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
     const float* bias;     // [Cout] fp32 added to the accumulators before rounding and the statistics, or nullptr
+    // Normalise + ReLU while loading (NORM instantiations): per (sample, input channel) the pair (a, b) of
+    // u = a*x + b, a = gamma*rstd, b = beta - mean*a; relu_floor = 0 (ReLU) or -inf (none).
+    const float2* ab;
+    float relu_floor;
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
     float* zpart;       // split reduction only: [splits][N*D*H*W][Cout] fp32 partial outputs
@@ -131,6 +135,11 @@ struct ConvArgs {
     // modulo 8 = blockIdx.x & 7: rotating the range a workgroup serves by its channel-block / split index
     // spreads the channel blocks of those few tiles over all eight XCDs.
     int xcd_rot;
+    // Tile numbering inside a sample.  sb_vol == 0: w fastest, then h, then d.  Otherwise the tiles are numbered
+    // super-block by super-block (sb_d x sb_h x sb_w tiles each, all three tile counts being multiples of these):
+    // the workgroups of an XCD, which hold consecutive tile numbers at any one time, then work on a compact
+    // block of the volume and share more of their halos through its L2.
+    int sb_d, sb_h, sb_w, sb_vol, nsb_h, nsb_w;
     // Output-channel blocks inside a one-dimensional grid: workgroup id = (walker * cb_inner + channel block) * 8 + XCD,
     // so the workgroups that read the same tiles for different output channels are resident on the same XCD at
     // the same time and share the input through its L2.  0: the channel block is blockIdx.y (they run one after
@@ -172,6 +181,43 @@ struct HaloTile {
     const bf16_t* origin;            // x at the halo origin (d0-1, h0-1, w0-1) of the tile (may be out of range)
     int dlo, dhi, hlo, hhi, wlo, whi;  // halo coords inside the volume: lo <= c <= hi
 };
+
+// Normalise + ReLU on load: the halo copies are register-free, so the transform is a read-modify-write pass over
+// the chunk once it has landed in LDS.  Every lane rewrites the 16-byte entries (8 channels of one voxel) that
+// its own copies brought in -- it knows whether each came from the volume or from the zero source, and the zero
+// padding applies AFTER the transform, so padding entries are written back as literal zeros.  The arithmetic is
+// the one of the stand-alone pass (fma, max, round to nearest even), so what the matrix cores read is bit for
+// bit the activated tensor that pass would have stored.  abp: the (a, b) pairs of this chunk's 16 channels
+// (wave-uniform: scalar loads).
+template <int TDT, int FIRST, int CNT>
+__device__ __forceinline__ void halo_norm(char* __restrict__ hb, const HaloLane& hl, const HaloTile& ht,
+                                          const float2* __restrict__ abp, float relu_floor, int wv, int lane) {
+    typedef Geo<TDT> GE;
+#pragma unroll
+    for (int sl = FIRST; sl < FIRST + CNT; ++sl) {
+        const int j = sl >> 1, plane = sl & 1;
+        const int blk = wv + 8 * j;
+        if (blk < GE::HBLK && blk * 64 + lane < GE::HALO_VOX) {
+            const int pk = hl.pk[j];
+            const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+            const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+            uint4* p = reinterpret_cast<uint4*>(hb + plane * GE::PLANE_BYTES + blk * 1024 + lane * 16);
+            const uint4 q = *p;
+            const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float2 c0 = abp[plane * 8 + 2 * e], c1 = abp[plane * 8 + 2 * e + 1];
+                float u0 = fmaf(__uint_as_float(r[e] << 16), c0.x, c0.y);
+                float u1 = fmaf(__uint_as_float(r[e] & 0xFFFF0000u), c1.x, c1.y);
+                u0 = u0 > relu_floor ? u0 : relu_floor;   // relu_floor = 0: max(u, 0) with -0 -> +0, as the stand-alone pass
+                u1 = u1 > relu_floor ? u1 : relu_floor;
+                o[e] = in ? pack_bf16(u0, u1) : 0u;
+            }
+            *p = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
 
 // One kd group of one chunk: issue this group's share of the prefetch (weights of the next group
 // first, then halo blocks of the next chunk), multiply 9 taps, wait for the weight copies and
@@ -357,6 +403,15 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
+        if (a.sb_vol) {
+            const int sbi = r / a.sb_vol, q = r - sbi * a.sb_vol;
+            const int c = q % a.sb_w, b = (q / a.sb_w) % a.sb_h, aa = q / (a.sb_w * a.sb_h);
+            const int sw = sbi % a.nsb_w, sh = (sbi / a.nsb_w) % a.nsb_h, sd = sbi / (a.nsb_w * a.nsb_h);
+            w0 = (sw * a.sb_w + c) * TW;
+            h0 = (sh * a.sb_h + b) * TH;
+            d0 = (sd * a.sb_d + aa) * TD;
+            return;
+        }
         w0 = (r % a.tiles_w) * TW;
         r /= a.tiles_w;
         h0 = (r % a.tiles_h) * TH;
@@ -847,6 +902,16 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
     a.tiles_total = tiles_per_n * zd->n;
     a.tiles_per_xcd = (a.tiles_total + 7) / 8;
+    a.sb_d = a.sb_h = a.sb_w = a.sb_vol = a.nsb_h = a.nsb_w = 0;
+    {
+        // 2 x 4 x 4 tiles per super-block: measured on 64 -> 64 at 128^3, 15 % fewer bytes fetched than with the
+        // plain numbering (4 x 4 x 2: 2 % fewer), same time.  LAMP_TUNE=super_block=<d h w as decimal digits>, 0 = plain.
+        const int sb = tune("super_block", 244);
+        const int sd = sb / 100, sh = (sb / 10) % 10, sw = sb % 10;
+        if (sd > 0 && sh > 0 && sw > 0 && td % sd == 0 && th % sh == 0 && tw % sw == 0) {
+            a.sb_d = sd; a.sb_h = sh; a.sb_w = sw; a.sb_vol = sd * sh * sw; a.nsb_h = th / sh; a.nsb_w = tw / sw;
+        }
+    }
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
     int wgx = 256;  // one persistent workgroup per CU (LDS-limited), 32 per XCD
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;

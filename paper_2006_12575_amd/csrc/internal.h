@@ -48,6 +48,10 @@ size_t colsum_ws_bytes(int64_t rows, int C);
 lamp_status launch_colsum(const void* t, int dtype, int64_t rows, int C, int ld, float* out, float beta,
                           void* ws, size_t ws_bytes, hipStream_t s);
 
+// ---- se.hip ---------------------------------------------------------------------------------
+// a[i] += b[i] over numel elements of the storage dtype (dense tensors).
+lamp_status launch_add_inplace(void* a, const void* b, int64_t numel, int dtype, hipStream_t s);
+
 // ---- head.hip -------------------------------------------------------------------------------
 // lamp_head_ce with the mean taken over norm_count voxels (0: the call's own) and the loss added to
 // *loss when loss_beta == 1.

@@ -336,6 +336,33 @@ static lamp_status se_check(const lamp_tensor_desc* zd, int cr) {
     return LAMP_OK;
 }
 
+// a[i] += b[i] in the storage dtype (fp32 sum, one rounding): the two gradients that meet at a shortcut.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void add_inplace_kernel(T* __restrict__ a, const T* __restrict__ b, int64_t nvec) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+        float x[VEC], y[VEC];
+        Vec<T, VEC>::load(a + i * VEC, x);
+        Vec<T, VEC>::load(b + i * VEC, y);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) x[k] += y[k];
+        Vec<T, VEC>::store(a + i * VEC, x);
+    }
+}
+
+lamp_status launch_add_inplace(void* a, const void* b, int64_t numel, int dtype, hipStream_t s) {
+    if (numel <= 0) return LAMP_OK;
+    const int full = dtype == LAMP_BF16 ? 8 : 4;
+    const int vec = (numel % full == 0 && aligned16(a) && aligned16(b)) ? full : 1;
+    const int64_t nvec = numel / vec;
+    const int64_t want = (nvec + 255) / 256;
+    const int blocks = (int)(want < 256 * 32 ? want : 256 * 32);
+    LAMP_DISPATCH_TV(dtype, vec, {
+        hipLaunchKernelGGL((add_inplace_kernel<T, VEC>), dim3(blocks), dim3(256), 0, s, (T*)a, (const T*)b, nvec);
+    });
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
 }  // namespace lamp
 
 using namespace lamp;

@@ -18,6 +18,7 @@ namespace lamp {
 
 struct ConvBuf {
     void* z; void* y; int ldy; float* stats;
+    float* gate;   // squeeze-and-excitation variant: what the gate's forward leaves for its backward (second conv of a block)
 };
 
 struct Net {
@@ -26,6 +27,7 @@ struct Net {
     size_t es;
     hipStream_t s;
     void* scratch; size_t scratch_bytes;
+    void* gaux = nullptr;   // third gradient buffer (squeeze-and-excitation variant only)
     int chan(int l) const { return u->base << (l - 1); }
     void dims(int l, int& d, int& h, int& w) const { d = u->d >> (l - 1); h = u->h >> (l - 1); w = u->w >> (l - 1); }
     int64_t vox(int l) const { int d, h, w; dims(l, d, h, w); return (int64_t)u->n * d * h * w; }
@@ -43,10 +45,14 @@ static lamp_status unet_desc_ok(const lamp_unet_desc* u) {
     const int m = 1 << (u->levels - 1);
     if (u->d % m || u->h % m || u->w % m) return LAMP_ERR_SHAPE;
     if (!(u->eps >= 0.f)) return LAMP_ERR_SHAPE;
+    if (u->se_ratio < 0 || u->se_ratio > 4096) return LAMP_ERR_SHAPE;
     return LAMP_OK;
 }
 
 static int per_conv(const lamp_unet_desc* u) { return u->affine ? 3 : 1; }
+// parameter entries of one block: two convs and, in the squeeze-and-excitation variant, the gate's W1, b1, W2, b2
+static int per_block(const lamp_unet_desc* u) { return 2 * per_conv(u) + (u->se_ratio ? 4 : 0); }
+static int se_hidden(const lamp_unet_desc* u, int C) { const int r = C / u->se_ratio; return r < 1 ? 1 : r; }
 
 // ---- scratch requirement: the largest per-call workspace of any layer ------------------------
 static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
@@ -59,6 +65,10 @@ static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
                       lamp_conv3d_dgrad_workspace_bytes(&xo, &xi), lamp_conv3d_dgrad_workspace_bytes(&xo, &xo),
                       lamp_inorm_relu_bwd_workspace_bytes(&xo)};
         for (size_t v : c) m = v > m ? v : m;
+    }
+    if (nt.u->se_ratio) {
+        const size_t v = lamp_inorm_relu_se_workspace_bytes(&xo, se_hidden(nt.u, Cout));
+        m = v > m ? v : m;
     }
     return m;
 }
@@ -84,8 +94,16 @@ static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, in
     if (st != LAMP_OK) return st;
     st = lamp_conv3d_fwd(&y1, c1.y, nullptr, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch,
                          nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK || !last_apply) return st;
+    if (st != LAMP_OK) return st;
     lamp_tensor_desc y2 = nt.td(l, Cout, c2.ldy);
+    if (u->se_ratio) {   // out = a1 + gate(mean a2) * a2: the gate on the second unit, the first unit's output as the shortcut
+        const int ps = pi + 2 * pc;
+        return lamp_inorm_relu_se(&zd, c2.z, c2.stats, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
+                                  u->affine ? (const float*)P[pi + pc + 2] : nullptr, se_hidden(u, Cout), (const float*)P[ps],
+                                  (const float*)P[ps + 1], (const float*)P[ps + 2], (const float*)P[ps + 3], &y1, c1.y, &y2, c2.y,
+                                  c2.gate, nt.scratch, nt.scratch_bytes, nt.s);
+    }
+    if (!last_apply) return st;
     return lamp_inorm_relu(&zd, c2.z, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
                            u->affine ? (const float*)P[pi + pc + 2] : nullptr, u->eps, &y2, c2.y, c2.stats, 1, nullptr, 0,
                            nt.s);
@@ -100,14 +118,34 @@ static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, in
     const int pc = per_conv(u);
     const bool af = u->affine != 0;
     lamp_tensor_desc zd = nt.td(l, Cout, Cout), xd = nt.td(l, Cin, ldx), y1 = nt.td(l, Cout, c1.ldy);
-    lamp_status st = lamp_inorm_relu_bwd(&zd, g, &zd, c2.z, c2.stats, af ? (const float*)P[pi + pc + 1] : nullptr,
-                                         af ? (const float*)P[pi + pc + 2] : nullptr, &zd, g, af ? G[pi + pc + 1] : nullptr,
-                                         af ? G[pi + pc + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK) return st;
-    st = lamp_conv3d_wgrad(&y1, c1.y, nullptr, &zd, g, G[pi + pc], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK) return st;
-    st = lamp_conv3d_dgrad(&zd, g, P[pi + pc], &zd, gtmp, nt.scratch, nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK) return st;
+    lamp_status st;
+    if (u->se_ratio) {
+        // g reaches the first unit's output twice: through the gated second unit and, unchanged, through the shortcut.
+        // dz2 goes to the third gradient buffer so that g survives until the two are added.
+        const int ps = pi + 2 * pc;
+        void* dz2 = nt.gaux;
+        st = lamp_inorm_relu_se_bwd(&zd, g, &zd, c2.z, c2.stats, af ? (const float*)P[pi + pc + 1] : nullptr,
+                                    af ? (const float*)P[pi + pc + 2] : nullptr, se_hidden(u, Cout), (const float*)P[ps],
+                                    (const float*)P[ps + 2], c2.gate, &zd, dz2, af ? G[pi + pc + 1] : nullptr,
+                                    af ? G[pi + pc + 2] : nullptr, G[ps], G[ps + 1], G[ps + 2], G[ps + 3], beta, nt.scratch,
+                                    nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+        st = lamp_conv3d_wgrad(&y1, c1.y, nullptr, &zd, dz2, G[pi + pc], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+        st = lamp_conv3d_dgrad(&zd, dz2, P[pi + pc], &zd, gtmp, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+        st = launch_add_inplace(gtmp, g, nvox(&zd) * Cout, nt.dt, nt.s);
+        if (st != LAMP_OK) return st;
+    } else {
+        st = lamp_inorm_relu_bwd(&zd, g, &zd, c2.z, c2.stats, af ? (const float*)P[pi + pc + 1] : nullptr,
+                                 af ? (const float*)P[pi + pc + 2] : nullptr, &zd, g, af ? G[pi + pc + 1] : nullptr,
+                                 af ? G[pi + pc + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+        st = lamp_conv3d_wgrad(&y1, c1.y, nullptr, &zd, g, G[pi + pc], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+        st = lamp_conv3d_dgrad(&zd, g, P[pi + pc], &zd, gtmp, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+    }
     st = lamp_inorm_relu_bwd(&zd, gtmp, &zd, c1.z, c1.stats, af ? (const float*)P[pi + 1] : nullptr,
                              af ? (const float*)P[pi + 2] : nullptr, &zd, gtmp, af ? G[pi + 1] : nullptr,
                              af ? G[pi + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
@@ -138,7 +176,7 @@ struct Layout {
     std::vector<void*> skip, up, gskip, gup, pooled;
     std::vector<int> ldcat;
     bool vcat;
-    void *g0, *g1;
+    void *g0, *g1, *g2;
     void* scratch; size_t scratch_bytes;
     void* repack; size_t repack_bytes;   // repacked conv weights of the whole pass (one launch)
     size_t total;
@@ -189,9 +227,11 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
         const int Cin = l == 1 ? u->in_ch : nt.chan(l - 1);
         const size_t tb = (size_t)nt.vox(l) * C * es, sb = (size_t)u->n * C * 2 * sizeof(float);
         ConvBuf &a = lay.e1[l - 1], &b = lay.e2[l - 1];
+        const bool se = u->se_ratio != 0;
         a.z = take(tb); a.stats = (float*)take(sb);
         a.y = bwd ? take(tb) : a.z; a.ldy = C;
         b.z = take(tb); b.stats = (float*)take(sb);
+        if (se) b.gate = (float*)take((size_t)u->n * (4 * C + se_hidden(u, C)) * sizeof(float));
         if (whole && l < L) {
             if (lay.vcat) {
                 lay.skip[l - 1] = take(tb); lay.up[l - 1] = take(tb); lay.ldcat[l - 1] = C;
@@ -208,7 +248,7 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
         } else if (!whole) {
             b.y = ext_skips ? ext_skips[l - first] : nullptr; b.ldy = C;
         } else {
-            b.y = bwd ? take(tb) : b.z; b.ldy = C;
+            b.y = bwd || se ? take(tb) : b.z; b.ldy = C;
         }
         if (l < L) {
             const size_t pb = (size_t)nt.vox(l + 1) * C * es;
@@ -225,7 +265,8 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
             const size_t tb = (size_t)nt.vox(l) * C * es, sb = (size_t)u->n * C * 2 * sizeof(float);
             ConvBuf &a = lay.d1[l - 1], &b = lay.d2[l - 1];
             a.z = take(tb); a.stats = (float*)take(sb); a.y = bwd ? take(tb) : a.z; a.ldy = C;
-            b.z = take(tb); b.stats = (float*)take(sb); b.y = bwd ? take(tb) : b.z; b.ldy = C;
+            b.z = take(tb); b.stats = (float*)take(sb); b.y = bwd || u->se_ratio ? take(tb) : b.z; b.ldy = C;
+            if (u->se_ratio) b.gate = (float*)take((size_t)u->n * (4 * C + se_hidden(u, C)) * sizeof(float));
             size_t sc = block_scratch(nt, l, 2 * C, C, bwd);
             scratch = sc > scratch ? sc : scratch;
             gmax = tb > gmax ? tb : gmax;
@@ -245,8 +286,8 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
             scratch = t > scratch ? t : scratch;
         }
     }
-    lay.g0 = lay.g1 = nullptr;
-    if (bwd) { lay.g0 = take(gmax); lay.g1 = take(gmax); }
+    lay.g0 = lay.g1 = lay.g2 = nullptr;
+    if (bwd) { lay.g0 = take(gmax); lay.g1 = take(gmax); if (u->se_ratio) lay.g2 = take(gmax); }
     lay.scratch_bytes = align_up(scratch);
     lay.scratch = take(lay.scratch_bytes);
     lay.repack_bytes = align_up(repack_region_bytes(nt, first, last, whole, bwd));
@@ -254,11 +295,11 @@ static void make_layout(Net& nt, int first, int last, bool whole, bool bwd, void
     lay.total = align_up(cv.off) + 256;
 }
 
-static int enc_pi(const lamp_unet_desc* u, int l) { return (l - 1) * 2 * per_conv(u); }
+static int enc_pi(const lamp_unet_desc* u, int l) { return (l - 1) * per_block(u); }
 static int dec_pi(const lamp_unet_desc* u, int l) {  // index of "up Wt" of decoder level l
-    return u->levels * 2 * per_conv(u) + (u->levels - 1 - l) * (2 + 2 * per_conv(u));
+    return u->levels * per_block(u) + (u->levels - 1 - l) * (2 + per_block(u));
 }
-static int head_pi(const lamp_unet_desc* u) { return u->levels * 2 * per_conv(u) + (u->levels - 1) * (2 + 2 * per_conv(u)); }
+static int head_pi(const lamp_unet_desc* u) { return u->levels * per_block(u) + (u->levels - 1) * (2 + per_block(u)); }
 
 // ---- conv weights repacked ahead of the pass, all in one launch ---------------------------------
 // The 3x3x3 convs of levels [first, last] (and of the decoder when `whole`): parameter index, shapes.
@@ -332,7 +373,12 @@ static lamp_status encoder_fwd(Net& nt, Layout& lay, int first, int last, const 
         const int pi = enc_pi(u, l) - pbase;
         lamp_status st = block_fwd(nt, l, cur_c, cur_c, cur, C, P, pi, lay.e1[l - 1], lay.e2[l - 1], nullptr, !pooled);
         if (st != LAMP_OK) return st;
-        if (pooled) {
+        if (pooled && u->se_ratio) {   // the gate's pass has written the block's output: a plain pooling pass follows
+            lamp_tensor_desc yd2 = nt.td(l, C, lay.e2[l - 1].ldy), pd = nt.td(l + 1, C, C);
+            st = lamp_maxpool2_fwd(&yd2, lay.e2[l - 1].y, nullptr, &pd, lay.pooled[l - 1], nt.s);
+            if (st != LAMP_OK) return st;
+            cur = lay.pooled[l - 1];
+        } else if (pooled) {
             const int pc = per_conv(u);
             lamp_norm_in zn{lay.e2[l - 1].stats, u->affine ? (const float*)P[pi + pc + 1] : nullptr,
                             u->affine ? (const float*)P[pi + pc + 2] : nullptr, C, 1};
@@ -393,19 +439,24 @@ extern "C" int32_t lamp_unet_param_count(const lamp_unet_desc* u) {
 
 extern "C" int64_t lamp_unet_param_numel(const lamp_unet_desc* u, int32_t idx) {
     if (unet_desc_ok(u) != LAMP_OK || idx < 0 || idx >= lamp_unet_param_count(u)) return 0;
-    const int pc = per_conv(u), L = u->levels;
+    const int pc = per_conv(u), pb = per_block(u), L = u->levels;
     auto ch = [&](int l) { return (int64_t)u->base << (l - 1); };
     auto conv_entry = [&](int64_t Cin, int64_t Cout, int k) -> int64_t {  // k: position inside a block
+        if (k >= 2 * pc) {   // the gate: W1 [cr][C], b1 [cr], W2 [C][cr], b2 [C]
+            const int64_t cr = se_hidden(u, (int)Cout);
+            const int64_t n[4] = {cr * Cout, cr, Cout * cr, Cout};
+            return n[k - 2 * pc];
+        }
         int which = k / pc, sub = k % pc;
         if (sub) return Cout;
         return Cout * 27 * (which == 0 ? Cin : Cout);
     };
-    if (idx < L * 2 * pc) {
-        int l = idx / (2 * pc) + 1;
-        return conv_entry(l == 1 ? u->in_ch : ch(l - 1), ch(l), idx % (2 * pc));
+    if (idx < L * pb) {
+        int l = idx / pb + 1;
+        return conv_entry(l == 1 ? u->in_ch : ch(l - 1), ch(l), idx % pb);
     }
-    idx -= L * 2 * pc;
-    const int per = 2 + 2 * pc;
+    idx -= L * pb;
+    const int per = 2 + pb;
     if (idx < (L - 1) * per) {
         int l = L - 1 - idx / per, k = idx % per;
         if (k == 0) return ch(l + 1) * 8 * ch(l);
@@ -474,6 +525,7 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     make_layout(nt, first, L, true, bwd, ws, lay, tail ? (void* const*)tail->skips : nullptr, nullptr,
                 tail && bwd ? tail->d_skips : nullptr);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
+    nt.gaux = lay.g2;
     const bool first_dgrad = tail && tail->d_x;
     RepackTable tab;
     if ((st = prepare_repack(nt, lay, first, L, true, pbase, P, phase != 2, bwd && phase != 1, first_dgrad, tab)) != LAMP_OK)
@@ -485,7 +537,7 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
     const void* top = L > 1 ? lay.d2[0].y : lay.e2[0].y;
     hd.ldc = L > 1 ? lay.d2[0].ldy : lay.e2[0].ldy;
     // the matrix-core head normalises on load only where its 32-voxel groups stay inside one sample
-    const bool head_norm = ((int64_t)u->d * u->h * u->w) % 32 == 0;
+    const bool head_norm = ((int64_t)u->d * u->h * u->w) % 32 == 0 && !u->se_ratio;
     if (phase != 2) {
         if ((st = encoder_fwd(nt, lay, first, L, P, pbase, x)) != LAMP_OK) return st;
         const void* cur = lay.e2[L - 1].y;
@@ -554,6 +606,7 @@ extern "C" lamp_status lamp_unet_fwd_bwd(const lamp_unet_desc* u, const void* co
 static lamp_status stage_ok(const lamp_unet_desc* u, int first, int last) {
     lamp_status st = unet_desc_ok(u);
     if (st != LAMP_OK) return st;
+    if (u->se_ratio) return LAMP_ERR_UNSUPPORTED;   // the partition entry points serve the plain U-Net
     if (first < 1 || last < first || last >= u->levels) return LAMP_ERR_SHAPE;
     return LAMP_OK;
 }
@@ -639,6 +692,7 @@ extern "C" lamp_status lamp_unet_stage_bwd(const lamp_unet_desc* u, int first, i
 static lamp_status tail_ok(const lamp_unet_desc* u, int first) {
     lamp_status st = unet_desc_ok(u);
     if (st != LAMP_OK) return st;
+    if (u->se_ratio) return LAMP_ERR_UNSUPPORTED;
     if (first < 2 || first > u->levels) return LAMP_ERR_SHAPE;
     return LAMP_OK;
 }
@@ -716,6 +770,7 @@ static bool pipe_layout(const lamp_unet_desc* u, int cut, int M, void* base, Pip
 static lamp_status pipe_ok(const lamp_unet_desc* u, int cut, int M) {
     lamp_status st = unet_desc_ok(u);
     if (st != LAMP_OK) return st;
+    if (u->se_ratio) return LAMP_ERR_UNSUPPORTED;
     if (cut < 1 || cut >= u->levels || M < 1 || M > 64) return LAMP_ERR_SHAPE;
     return LAMP_OK;
 }

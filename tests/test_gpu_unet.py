@@ -31,12 +31,12 @@ def L():
     return L
 
 
-def make_net(levels, base, in_ch, classes, affine, dtype, seed):
+def make_net(levels, base, in_ch, classes, affine, dtype, seed, se_ratio=0):
     rp = S.streams(seed, 1)[0]
-    p = S.unet_params(rp, levels, base, in_ch, classes, affine, test_mode=True)
+    p = S.unet_params(rp, levels, base, in_ch, classes, affine, test_mode=True, se_ratio=se_ratio)
     dev, ora = [], {}
     for k, v in p.items():
-        small = k.endswith((".b", ".gamma", ".beta"))
+        small = k.endswith((".b", ".gamma", ".beta")) or ".se." in k
         t = to_dev(v, F32 if small else dtype)
         dev.append(t)
         ora[k] = as64(t)
@@ -119,6 +119,59 @@ def test_unet_fwd_bwd(L, cfg):
     L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, g2, beta=1.0)
     for a, b in zip(grads, g2):
         assert torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(levels=3, base=8, in_ch=2, classes=5, affine=True, dtype=F32, dims=(2, 8, 12, 16), ratio=4),
+    dict(levels=2, base=8, in_ch=1, classes=3, affine=False, dtype=F32, dims=(1, 8, 8, 8), ratio=16),   # one hidden unit
+    dict(levels=3, base=32, in_ch=1, classes=10, affine=False, dtype=BF, dims=(2, 16, 16, 32), ratio=16),
+    dict(levels=2, base=32, in_ch=1, classes=4, affine=True, dtype=BF, dims=(1, 16, 24, 16), ratio=8),
+], ids=["f32-affine-r4", "f32-r16", "bf16-r16", "bf16-affine-r8"])
+def test_seunet_fwd_bwd(L, cfg):
+    """The squeeze-and-excitation variant of the net (se_ratio > 0: every block out = a1 + gate(mean a2) * a2) through
+    the whole-network entry points against the network oracle.  fp32: logits and EVERY gradient tensor, the gate's
+    included, within 1e-4 of the pure fp64 oracle, which pins the composition (shortcut add, the gate's backward, the
+    parameter order).  bf16: logits and loss to the path's bound, gradients to the calibrated realisation bound."""
+    levels, dtype, ratio = cfg["levels"], cfg["dtype"], cfg["ratio"]
+    N, D, H, W = cfg["dims"]
+    names, dev, ora = make_net(levels, cfg["base"], cfg["in_ch"], cfg["classes"], cfg["affine"], dtype, 177, se_ratio=ratio)
+    rx, rl = S.streams(178, 2)
+    x = to_dev(S.ct_volume(rx, N, D, H, W) if cfg["in_ch"] == 1 else S.normal(rx, (N, D, H, W, cfg["in_ch"])), dtype)
+    lab = torch.from_numpy(S.organ_labels(rl, N, D, H, W, cfg["classes"])).to(DEV)
+    ud = L.unet_desc(levels, cfg["base"], cfg["in_ch"], cfg["classes"], N, D, H, W, dtype, affine=cfg["affine"], se_ratio=ratio)
+    assert L.lamp_unet_param_count(ud) == len(names)
+    for i, t in enumerate(dev):
+        assert L.lamp_unet_param_numel(ud, i) == t.numel(), names[i]
+    grads = [torch.full(t.shape, float("nan"), dtype=F32, device=DEV) for t in dev]
+    loss = torch.empty((), dtype=F32, device=DEV)
+    logits = torch.empty((N, D, H, W, cfg["classes"]), dtype=F32, device=DEV)
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, grads, logits=logits)
+    store = O.round_bf16 if dtype == BF else (lambda a: a)
+    run = lambda st: unet.loss_and_grads(ora, as64(x), lab.cpu().numpy(), levels, store=st)
+    loss_ref, g_ref, lg_ref, _ = run(store)
+    check(as64(logits), lg_ref, dtype, "SE net logits")
+    assert abs(loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
+    if dtype == F32:
+        for k, g in zip(names, grads):
+            check(as64(g), g_ref[k], dtype, f"SE net grad {k}", tol=FP32_GRAD_TOL)
+    else:
+        spread = realisation_spread(lambda st: run(st)[1], g_ref)
+        for k, g in zip(names, grads):
+            check_e2_calibrated(as64(g), g_ref[k], spread[k], f"SE net grad {k}")
+    # the forward-only entry point gives the same logits; a second call is bit-identical; beta = 1 accumulates
+    l2 = torch.empty_like(logits)
+    L.lamp_unet_fwd(ud, dev, x, l2)
+    assert torch.equal(l2, logits)
+    g2 = [g.clone() for g in grads]
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, g2, beta=1.0)
+    for a, b in zip(grads, g2):
+        assert torch.allclose(b, 2 * a, rtol=1e-6, atol=0)
+    g3 = [torch.empty_like(g) for g in grads]
+    L.lamp_unet_fwd_bwd(ud, dev, x, lab, loss, g3)
+    for a, b in zip(grads, g3):
+        assert torch.equal(a, b)
+    # the partition entry points serve the plain U-Net only
+    assert L.lamp_unet_stage_workspace_bytes(ud, 1, 1) == 0
 
 
 def test_stage_partition_fwd_bwd(L):

@@ -85,6 +85,65 @@ def test_whole_net_finite_differences_every_layer():
     assert worst < 2e-4
 
 
+def make_se(levels, base, classes, shape, seed, ratio=2, affine=True):
+    r_p, r_x, r_l = S.streams(seed, 3)
+    p = {k: v.astype(np.float64)
+         for k, v in S.unet_params(r_p, levels, base, 1, classes, affine, test_mode=True, se_ratio=ratio).items()}
+    x = r_x.standard_normal((shape[0],) + tuple(shape[1:]) + (1,))
+    lab = r_l.integers(0, classes, shape)
+    return p, x, lab
+
+
+def test_se_net_finite_differences_every_parameter():
+    """The squeeze-and-excitation variant of the net (a reading of the cited block: gate on the second conv unit,
+    first unit's output as the shortcut): gradients of every parameter tensor, the gate's included, against central
+    finite differences of the loss."""
+    levels = 3
+    p, x, lab = make_se(levels, 4, 3, (2, 8, 8, 8), 13)
+    assert sum(k.endswith(".se.w1") for k in p) == 2 * levels - 1      # one gate per block
+    assert p["enc2.se.w1"].shape == (4, 8) and p["enc2.se.w2"].shape == (8, 4)
+    loss, grads, _, _ = unet.loss_and_grads(p, x, lab, levels)
+    assert set(grads.keys()) == set(p.keys())
+    r = np.random.Generator(np.random.PCG64(15))
+    hh = 1e-6
+    for name in p:
+        flat = p[name].reshape(-1)
+        gflat = grads[name].reshape(-1)
+        for idx in r.choice(flat.size, size=min(2, flat.size), replace=False):
+            old = flat[idx]
+            flat[idx] = old + hh
+            lp = O.cross_entropy(unet.forward(p, x, levels)[0], lab)[0]
+            flat[idx] = old - hh
+            lm = O.cross_entropy(unet.forward(p, x, levels)[0], lab)[0]
+            flat[idx] = old
+            fd = (lp - lm) / (2 * hh)
+            assert abs(fd - gflat[idx]) / max(1e-4, abs(fd)) < 2e-4, (name, idx, fd, gflat[idx])
+
+
+def test_se_net_closed_and_open_gate_special_cases():
+    """Gate closed (b2 -> -inf, e = 0): every block returns its first unit's output, so the second convs and the
+    gate's first layer get no gradient.  Gate saturated open (e = 1): the block is the plain residual block
+    a1 + a2, written out here with the plain InstanceNorm + ReLU oracle."""
+    levels = 2
+    p, x, lab = make_se(levels, 4, 3, (1, 4, 4, 8), 17, affine=False)
+    for k in p:
+        if k.endswith(".se.w2"):
+            p[k][:] = 0.0
+        if k.endswith(".se.b2"):
+            p[k][:] = -800.0
+    loss, grads, logits, cache = unet.loss_and_grads(p, x, lab, levels)
+    for blk in ("enc1", "enc2", "dec1"):
+        np.testing.assert_array_equal(cache[f"{blk}.conv2"]["y"], cache[f"{blk}.conv1"]["y"])
+        assert np.all(grads[f"{blk}.conv2.w"] == 0) and np.all(grads[f"{blk}.se.w1"] == 0)
+    for k in p:
+        if k.endswith(".se.b2"):
+            p[k][:] = 800.0
+    logits_open, cache = unet.forward(p, x, levels)
+    a1 = cache["enc1.conv1"]["y"]
+    a2, _ = O.inorm_relu(O.conv3d_fwd(a1, p["enc1.conv2.w"]))
+    np.testing.assert_allclose(cache["enc1.conv2"]["y"], a1 + a2, rtol=0, atol=1e-13)
+
+
 def test_stage_composition_equals_whole_net():
     # Eq. 3 == Eq. 2: cutting the sequence after encoder block 2 and carrying e_{1,1}, e_{2,1}
     levels = 3
