@@ -38,8 +38,8 @@
  *       no_split=1            no input-channel split for few-tile, many-channel layers
  *       cb_outer=1            output-channel blocks as grid.y instead of side by side on one XCD
  *       materialise_concat=1  the network entry points keep one concat buffer per decoder level
- *       super_block=DHW       tiles of the matrix-core conv numbered in blocks of D x H x W tiles (decimal
- *                             digits, default 244; 0: plain w-h-d order)
+ *       no_norm_on_load=1     the network entry points write every activated tensor instead of normalising
+ *                             a block's first conv output while the second conv loads it
  */
 #ifndef LAMP_H
 #define LAMP_H

@@ -821,7 +821,7 @@ extern "C" lamp_status lamp_conv3d_fwd(const lamp_tensor_desc* xd, const void* x
         return LAMP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     if (mfma_conv_supported(xd, zd, xnorm, bias))
-        return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s, nullptr, bias);
+        return mfma_conv_fwd(xd, x, w, false, zd, z, stats_out, eps, ws, ws_bytes, s, nullptr, bias, xnorm);
     if (cin1_fwd_ok(xd, zd, xnorm, bias, z)) {
         if (cin1_tile_ok(zd)) return cin1_tile_fwd(xd, x, w, zd, z, stats_out, eps, ws, ws_bytes, s);
         hipLaunchKernelGGL(conv3d_cin1_fwd_kernel, dim3(cdiv(nvox(zd), 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,

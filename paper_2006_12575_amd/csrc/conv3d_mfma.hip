@@ -135,11 +135,6 @@ struct ConvArgs {
     // modulo 8 = blockIdx.x & 7: rotating the range a workgroup serves by its channel-block / split index
     // spreads the channel blocks of those few tiles over all eight XCDs.
     int xcd_rot;
-    // Tile numbering inside a sample.  sb_vol == 0: w fastest, then h, then d.  Otherwise the tiles are numbered
-    // super-block by super-block (sb_d x sb_h x sb_w tiles each, all three tile counts being multiples of these):
-    // the workgroups of an XCD, which hold consecutive tile numbers at any one time, then work on a compact
-    // block of the volume and share more of their halos through its L2.
-    int sb_d, sb_h, sb_w, sb_vol, nsb_h, nsb_w;
     // Output-channel blocks inside a one-dimensional grid: workgroup id = (walker * cb_inner + channel block) * 8 + XCD,
     // so the workgroups that read the same tiles for different output channels are resident on the same XCD at
     // the same time and share the input through its L2.  0: the channel block is blockIdx.y (they run one after
@@ -197,25 +192,50 @@ __device__ __forceinline__ void halo_norm(char* __restrict__ hb, const HaloLane&
     for (int sl = FIRST; sl < FIRST + CNT; ++sl) {
         const int j = sl >> 1, plane = sl & 1;
         const int blk = wv + 8 * j;
-        if (blk < GE::HBLK && blk * 64 + lane < GE::HALO_VOX) {
-            const int pk = hl.pk[j];
-            const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
-            const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+        const int pk = hl.pk[j];
+        const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+        const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+        // Slots that every wave copies in full (j < HBLK / 8) are rewritten by straight-line code, which the
+        // scheduler can spread between the matrix instructions of the group; an entry from outside the volume is
+        // written back as it came (zeros: the zero padding applies after the transform).  The last block's slots
+        // exist for some waves and lanes only.
+        const bool mine = j < GE::HBLK / 8 || (blk < GE::HBLK && blk * 64 + lane < GE::HALO_VOX);
+        if (mine) {
             uint4* p = reinterpret_cast<uint4*>(hb + plane * GE::PLANE_BYTES + blk * 1024 + lane * 16);
             const uint4 q = *p;
             const uint32_t r[4] = {q.x, q.y, q.z, q.w};
             uint32_t o[4];
+            // the coefficients are the same for every lane: read through the scalar cache (a table no kernel
+            // writes while this one runs), 64 bytes per slot
+            typedef __attribute__((address_space(4))) const float cfloat;
+            const uint64_t ua = (uint64_t)(uintptr_t)(abp + plane * 8);
+            const uint32_t ulo = __builtin_amdgcn_readfirstlane((uint32_t)ua), uhi = __builtin_amdgcn_readfirstlane((uint32_t)(ua >> 32));
+            cfloat* cab = (cfloat*)(uintptr_t)(((uint64_t)uhi << 32) | ulo);   // (a, b) pairs of 8 channels
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float2 c0 = abp[plane * 8 + 2 * e], c1 = abp[plane * 8 + 2 * e + 1];
-                float u0 = fmaf(__uint_as_float(r[e] << 16), c0.x, c0.y);
-                float u1 = fmaf(__uint_as_float(r[e] & 0xFFFF0000u), c1.x, c1.y);
-                u0 = u0 > relu_floor ? u0 : relu_floor;   // relu_floor = 0: max(u, 0) with -0 -> +0, as the stand-alone pass
-                u1 = u1 > relu_floor ? u1 : relu_floor;
-                o[e] = in ? pack_bf16(u0, u1) : 0u;
+                const float2 c0 = make_float2(cab[4 * e], cab[4 * e + 1]), c1 = make_float2(cab[4 * e + 2], cab[4 * e + 3]);
+                // max(u, floor): for u = -0 the sign of the zero may differ from the stand-alone pass, which
+                // the matrix cores cannot see (both are zero)
+                const float u0 = fmaxf(fmaf(__uint_as_float(r[e] << 16), c0.x, c0.y), relu_floor);
+                const float u1 = fmaxf(fmaf(__uint_as_float(r[e] & 0xFFFF0000u), c1.x, c1.y), relu_floor);
+                o[e] = in ? pack_bf16(u0, u1) : r[e];
             }
             *p = make_uint4(o[0], o[1], o[2], o[3]);
         }
+    }
+}
+
+// Scheduling hint: NM MFMAs with NR LDS reads, NV vector-ALU instructions and NW LDS writes spread evenly behind them.
+template <int K, int NM, int NR, int NV, int NW> __device__ __forceinline__ void sched_interleave_v() {
+    if constexpr (K < NM) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        constexpr int R = (NR * (K + 1)) / NM - (NR * K) / NM;
+        if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+        constexpr int V = (NV * (K + 1)) / NM - (NV * K) / NM;
+        if constexpr (V > 0) __builtin_amdgcn_sched_group_barrier(0x002, V, 0);
+        constexpr int Wr = (NW * (K + 1)) / NM - (NW * K) / NM;
+        if constexpr (Wr > 0) __builtin_amdgcn_sched_group_barrier(0x200, Wr, 0);
+        sched_interleave_v<K + 1, NM, NR, NV, NW>();
     }
 }
 
@@ -225,12 +245,16 @@ __device__ __forceinline__ void halo_norm(char* __restrict__ hb, const HaloLane&
 // otherwise the compiler must assume the fragment reads alias the in-flight copies and waits for
 // them before the first read.
 //   HALO_FIRST, HALO_CNT : halo copy slots (block j = slot/2, plane = slot%2) issued in this group
-template <int COB, int TDT, int G, int HALO_FIRST, int HALO_CNT>
+//   NORM_FIRST, NORM_CNT : slots of the incoming chunk that this group normalises in LDS (normalise on load), after
+//                          waiting until at most NORM_WAIT of this wave's copies are in flight (< 0: no wait needed)
+//   DRAIN                : the group ends with every copy landed (its own halo copies are not issued by all waves)
+template <int COB, int TDT, int G, int HALO_FIRST, int HALO_CNT, int NORM_FIRST = 0, int NORM_CNT = 0, int NORM_WAIT = -1,
+          bool DRAIN = false>
 __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], const char* __restrict__ hb, const char* __restrict__ wb,
                                            char* __restrict__ hb_next, char* __restrict__ wb_next, bool pf_halo,
                                            bool pf_w, const HaloLane& hl, const HaloTile& ht, int64_t pf_choff,
                                            const bf16_t* zero16, const bf16_t* wsrc, const int (&wrel)[3], int wv,
-                                           int lane) {
+                                           int lane, const float2* __restrict__ abp = nullptr, float relu_floor = 0.f) {
     typedef Geo<TDT> GE;
     constexpr int NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES;
     constexpr int WROWS = 32 * COB;
@@ -259,6 +283,16 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    // Normalise on load: this group's NORM_CNT slots of the incoming chunk.  The first wave of every SIMD rewrites
+    // them before its multiply section, the second one after it (waves w and w + 4 share a SIMD): while one wave
+    // of a SIMD runs the vector-ALU work of the rewrite the other one feeds the matrix cores.
+    const bool rmw_early = wv < 4;
+    if constexpr (NORM_CNT > 0) {
+        if constexpr (NORM_WAIT >= 0) {
+            if (pf_halo) wait_vmcnt<NORM_WAIT>();
+        }
+        if (rmw_early) halo_norm<TDT, NORM_FIRST, NORM_CNT>(hb_next, hl, ht, abp, relu_floor, wv, lane);
+    }
     if constexpr (TDT == 8) {
         // ---- multiply, 8-deep tile: the group is the in-plane row G = kh.  A wave owns 4 d-slices of one
         // (2 h-rows x 16 w) block; for a tap column kw the input slice s = d + kd serves the output slices
@@ -325,10 +359,13 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
         if (t9 < 8) sched_interleave<0, NVB * COB, COB + NVB>();
     }
     }
+    if constexpr (NORM_CNT > 0) {
+        if (!rmw_early) halo_norm<TDT, NORM_FIRST, NORM_CNT>(hb_next, hl, ht, abp, relu_floor, wv, lane);
+    }
     // The weight copies are older than this group's halo copies: leaving HALO_CNT copies in flight
     // still guarantees the weights have landed.  (Every wave issues all HALO_CNT copies of groups
     // 0 and 1; the last group drains everything because the next stage reads the halo.)
-    if (G < 2 && pf_halo) wait_vmcnt<(G < 2 ? HALO_CNT : 0)>();
+    if (G < 2 && pf_halo && !DRAIN) wait_vmcnt<(G < 2 ? HALO_CNT : 0)>();
     else wait_vmcnt<0>();
     // bare barrier: __syncthreads() would add a release fence that drains every copy in flight
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
@@ -339,7 +376,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], co
 // SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
 // writes its fp32 partial sums; a second kernel adds them in a fixed order.  For small volumes with
 // many channels, where the tiles alone cannot fill the chip.
-template <int COB, int TDT, bool SPLIT = false>
+template <int COB, int TDT, bool SPLIT = false, bool NORM = false>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
     constexpr int TD = GE::TD, NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES,
@@ -403,15 +440,6 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
-        if (a.sb_vol) {
-            const int sbi = r / a.sb_vol, q = r - sbi * a.sb_vol;
-            const int c = q % a.sb_w, b = (q / a.sb_w) % a.sb_h, aa = q / (a.sb_w * a.sb_h);
-            const int sw = sbi % a.nsb_w, sh = (sbi / a.nsb_w) % a.nsb_h, sd = sbi / (a.nsb_w * a.nsb_h);
-            w0 = (sw * a.sb_w + c) * TW;
-            h0 = (sh * a.sb_h + b) * TH;
-            d0 = (sd * a.sb_d + aa) * TD;
-            return;
-        }
         w0 = (r % a.tiles_w) * TW;
         r /= a.tiles_w;
         h0 = (r % a.tiles_h) * TH;
@@ -448,6 +476,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         for (int i = 0; i < 3; ++i)
             if (wv + 8 * i < WINSTR) g2lds16(wbase + (int64_t)c_lo * (3 * wgstride) + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
         wait_vmcnt<0>();
+        if constexpr (NORM)
+            halo_norm<TDT, 0, 2 * HJ>(hbuf0, hl, t0, a.ab + (int64_t)(tile / a.tiles_per_n) * a.Cin + c_lo * 16, a.relu_floor, wv, lane);
         __syncthreads();
     }
 
@@ -481,12 +511,31 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             // halo copy slots per group (slot = block j * 2 + plane): 4 + 2 + 2 of 8, or 2 + 2 + 2 of 6
             constexpr int S0 = 2 * HJ - 4;
             const int64_t pf_off = choff(pf_chunk);
-            conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
-                                           wc + wgstride, wrel, wv, lane);
-            conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16,
-                                           wc + 2 * wgstride, wrel, wv, lane);
-            conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16,
-                                               wbase + (int64_t)pf_chunk * (3 * wgstride), wrel, wv, lane);
+            if constexpr (NORM) {
+                // Normalise on load: the copies go out early (the slots that every wave issues in group 0, the rest
+                // in group 1), the first slots are normalised in group 1 once they have landed -- behind them this
+                // wave has issued their two younger group-0 slots and at least WINSTR / 8 weight copies -- and the
+                // others in group 2, after group 1 has drained every copy.
+                constexpr int NS = 2 * HJ, FULLS = 2 * (HBLK / 8);
+                static_assert(FULLS >= 4 && FULLS <= NS, "slot split of the normalise-on-load variant");
+                const int n_pf = (last_chunk && next_tile < tile_hi ? next_tile : tile) / a.tiles_per_n;
+                const float2* abp = a.ab + (int64_t)n_pf * a.Cin + pf_chunk * 16;
+                conv_group<COB, TDT, 0, 0, FULLS>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
+                                                  wc + wgstride, wrel, wv, lane);
+                conv_group<COB, TDT, 1, FULLS, NS - FULLS, 0, FULLS - 2, 2 + WINSTR / 8, true>(
+                    acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16, wc + 2 * wgstride, wrel, wv, lane, abp,
+                    a.relu_floor);
+                conv_group<COB, TDT, 2, 0, 0, FULLS - 2, NS - (FULLS - 2), -1>(
+                    acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16, wbase + (int64_t)pf_chunk * (3 * wgstride), wrel,
+                    wv, lane, abp, a.relu_floor);
+            } else {
+                conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
+                                               wc + wgstride, wrel, wv, lane);
+                conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16,
+                                               wc + 2 * wgstride, wrel, wv, lane);
+                conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16,
+                                                   wbase + (int64_t)pf_chunk * (3 * wgstride), wrel, wv, lane);
+            }
             wpar ^= 1;
         }
 
@@ -650,19 +699,37 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     }
 }
 
+// (a, b) of the normalise-on-load for every (sample, channel): u = a*x + b with the library's one formula.
+__global__ __launch_bounds__(256) void norm_coeff_kernel(NormIn nm, int N, int C, float2* __restrict__ ab) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * C) return;
+    float a, b;
+    norm_coeffs(nm, i / C, i % C, a, b);
+    ab[i] = make_float2(a, b);
+}
+
 static void tile_dims(const lamp_tensor_desc* t, int TD, int& td, int& th, int& tw) {
     td = (t->d + TD - 1) / TD; th = (t->h + TH - 1) / TH; tw = (t->w + TW - 1) / TW;
 }
 
+struct PackPlan { int gh, gw, hp, wp; };
+static bool conv_pack_plan(const lamp_tensor_desc* zd, PackPlan& best);
+static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
+
 bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, const lamp_norm_in* xnorm,
                          const float* bias) {
     if (xd->dtype != LAMP_BF16) return false;
-    if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) return false;
     if (bias && (((uintptr_t)bias) & 15u)) return false;   // the epilogue reads it four floats at a time
     if (xd->c % 16 || zd->c % 32 || xd->ldc % 8 || zd->ldc % 8) return false;
     // element offsets inside a tile's halo (10 slices of H x W voxels) are kept in 32 bits
     const int64_t ldmax = xd->ldc > zd->ldc ? xd->ldc : zd->ldc;
     if ((int64_t)10 * zd->h * zd->w * ldmax >= ((int64_t)1 << 31)) return false;
+    if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) {
+        // normalise on load: every input channel normalised, on the plain tiled kernel (no packed batch of tiny
+        // volumes, no input-channel split: those layers are small and keep the generic path)
+        PackPlan pp;
+        if (xnorm->c_norm != xd->c || conv_pack_plan(zd, pp) || conv_splits(xd, zd) > 1) return false;
+    }
     return true;
 }
 
@@ -690,7 +757,6 @@ static int conv_tile_depth(const lamp_tensor_desc* zd) {
 // followed by one row / column of zeros, which is the zero padding of both neighbours.  The conv of
 // the packed volume equals the per-sample conv at every real voxel; the voxels in the gaps are
 // dropped when the result is copied back.
-struct PackPlan { int gh, gw, hp, wp; };
 static int64_t pack_slots(int d, int h, int w) { return (int64_t)((d + 3) / 4) * ((h + TH - 1) / TH) * ((w + TW - 1) / TW); }
 static bool conv_pack_plan(const lamp_tensor_desc* zd, PackPlan& best) {
     if (tune("no_pack", 0) || zd->n < 4 || zd->w > 8 || zd->h > 16 || zd->d > 64 || zd->c > 4096) return false;
@@ -812,6 +878,7 @@ static int conv_splits(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
 
 size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, int want_stats) {
     if (!mfma_conv_supported(xd, zd, nullptr, nullptr)) return 0;
+    const size_t ab_bytes = align_up((size_t)xd->n * xd->c * sizeof(float2));   // normalise-on-load coefficients
     int td, th, tw;
     tile_dims(zd, 4, td, th, tw);  // the finer tiling bounds the partial count
     const size_t tiles = (size_t)td * th * tw;
@@ -831,22 +898,24 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
                           mfma_conv_ws_bytes(&xp, &zp, 0) + 512;
         if (pb > b) b = pb;
     }
-    return b;
+    return b + ab_bytes;
 }
 
-template <int COB, int TDT, bool SPLIT = false>
+template <int COB, int TDT, bool SPLIT = false, bool NORM = false>
 static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
     const int shm = Geo<TDT>::LDS_BYTES;
-    if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT>, shm) != LAMP_OK) return LAMP_ERR_HIP;
-    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT>), grid, dim3(512), shm, s, a);
+    if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT, NORM>, shm) != LAMP_OK) return LAMP_ERR_HIP;
+    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT, NORM>), grid, dim3(512), shm, s, a);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
 
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
-                          hipStream_t s, const ConvParts* parts, const float* bias) {
+                          hipStream_t s, const ConvParts* parts, const float* bias, const lamp_norm_in* xnorm) {
     const bool two_in = parts && parts->x2, two_out = parts && parts->z2;
+    const bool norm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
+    if (norm && (two_in || !mfma_conv_supported(xd, zd, xnorm, bias))) return LAMP_ERR_UNSUPPORTED;
     if (two_in && ((((uintptr_t)parts->x2) & 15u) || parts->x_c1 % 16 || parts->x_c1 <= 0 || parts->x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
     if (two_out && ((((uintptr_t)parts->z2) & 15u) || parts->z_c1 % 32 || parts->z_c1 <= 0 || parts->z_c1 >= zd->c || parts->ldz2 % 8))
         return LAMP_ERR_ALIGN;
@@ -885,7 +954,13 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         part = (float*)cv.take((size_t)zd->n * tiles_per_n * zd->c * 2 * sizeof(float));
         counts = (int32_t*)cv.take((size_t)tiles_per_n * sizeof(int32_t));
     }
+    float2* ab = nullptr;
+    if (norm) ab = (float2*)cv.take((size_t)xd->n * xd->c * sizeof(float2));
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+    if (norm) {
+        hipLaunchKernelGGL(norm_coeff_kernel, dim3(cdiv((int64_t)xd->n * xd->c, 256)), dim3(256), 0, s, make_norm(xnorm), xd->n, xd->c, ab);
+        LAMP_CHECK_LAUNCH();
+    }
     const int64_t wtotal = (int64_t)27 * xd->c * zd->c;
     if (const bf16_t* pre = find_prepacked(w, dgrad, TDT == 8 ? 1 : 0, zd->c, xd->c)) {
         wp = const_cast<bf16_t*>(pre);
@@ -898,20 +973,12 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;
     a.bias = bias;
+    a.ab = ab;
+    a.relu_floor = norm && !xnorm->relu ? -__builtin_inff() : 0.f;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
     a.tiles_total = tiles_per_n * zd->n;
     a.tiles_per_xcd = (a.tiles_total + 7) / 8;
-    a.sb_d = a.sb_h = a.sb_w = a.sb_vol = a.nsb_h = a.nsb_w = 0;
-    {
-        // 2 x 4 x 4 tiles per super-block: measured on 64 -> 64 at 128^3, 15 % fewer bytes fetched than with the
-        // plain numbering (4 x 4 x 2: 2 % fewer), same time.  LAMP_TUNE=super_block=<d h w as decimal digits>, 0 = plain.
-        const int sb = tune("super_block", 244);
-        const int sd = sb / 100, sh = (sb / 10) % 10, sw = sb % 10;
-        if (sd > 0 && sh > 0 && sw > 0 && td % sd == 0 && th % sh == 0 && tw % sw == 0) {
-            a.sb_d = sd; a.sb_h = sh; a.sb_w = sw; a.sb_vol = sd * sh * sw; a.nsb_h = th / sh; a.nsb_w = tw / sw;
-        }
-    }
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
     int wgx = 256;  // one persistent workgroup per CU (LDS-limited), 32 per XCD
     while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
@@ -942,7 +1009,10 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         grid.y = 1;
     }
     lamp_status st;
-    if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
+    if (norm) {
+        if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8, false, true>(a, grid, s) : launch_igemm<1, 8, false, true>(a, grid, s);
+        else st = cob == 2 ? launch_igemm<2, 4, false, true>(a, grid, s) : launch_igemm<1, 4, false, true>(a, grid, s);
+    } else if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
     else st = cob == 2 ? launch_igemm<2, 4>(a, grid, s) : launch_igemm<1, 4>(a, grid, s);
     if (st != LAMP_OK) return st;
     if (stats_out) return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);

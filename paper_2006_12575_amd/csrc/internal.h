@@ -78,7 +78,7 @@ struct ConvParts { const void* x2; int x_c1; void* z2; int z_c1, ldz2; };
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
                           void* ws, size_t ws_bytes, hipStream_t s, const ConvParts* parts = nullptr,
-                          const float* bias = nullptr);
+                          const float* bias = nullptr, const lamp_norm_in* xnorm = nullptr);
 bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm);
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd);
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,

@@ -28,6 +28,7 @@ struct Net {
     hipStream_t s;
     void* scratch; size_t scratch_bytes;
     void* gaux = nullptr;   // third gradient buffer (squeeze-and-excitation variant only)
+    bool fwd_only = false;  // no backward follows: a block's first activated tensor feeds its second conv only
     int chan(int l) const { return u->base << (l - 1); }
     void dims(int l, int& d, int& h, int& w) const { d = u->d >> (l - 1); h = u->h >> (l - 1); w = u->w >> (l - 1); }
     int64_t vox(int l) const { int d, h, w; dims(l, d, h, w); return (int64_t)u->n * d * h * w; }
@@ -89,11 +90,17 @@ static lamp_status block_fwd(Net& nt, int l, int Cin, int ldx, const void* x, in
     }
     if (st != LAMP_OK) return st;
     lamp_tensor_desc y1 = nt.td(l, Cout, c1.ldy);
-    st = lamp_inorm_relu(&zd, c1.z, u->affine ? (const float*)P[pi + 1] : nullptr,
-                         u->affine ? (const float*)P[pi + 2] : nullptr, u->eps, &y1, c1.y, c1.stats, 1, nullptr, 0, nt.s);
-    if (st != LAMP_OK) return st;
-    st = lamp_conv3d_fwd(&y1, c1.y, nullptr, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch,
-                         nt.scratch_bytes, nt.s);
+    // Forward only, the first unit's activated tensor has one consumer, the second conv: where that conv takes the
+    // matrix-core kernel it normalises the raw tensor while it loads it, and the tensor is never written.
+    lamp_norm_in n1{c1.stats, u->affine ? (const float*)P[pi + 1] : nullptr, u->affine ? (const float*)P[pi + 2] : nullptr, Cout, 1};
+    if (nt.fwd_only && !u->se_ratio && !tune("no_norm_on_load", 0) && mfma_conv_supported(&zd, &zd, &n1, nullptr)) {
+        st = lamp_conv3d_fwd(&zd, c1.z, &n1, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch, nt.scratch_bytes, nt.s);
+    } else {
+        st = lamp_inorm_relu(&zd, c1.z, n1.gamma, n1.beta, u->eps, &y1, c1.y, c1.stats, 1, nullptr, 0, nt.s);
+        if (st != LAMP_OK) return st;
+        st = lamp_conv3d_fwd(&y1, c1.y, nullptr, P[pi + pc], nullptr, &zd, c2.z, c2.stats, u->eps, nt.scratch,
+                             nt.scratch_bytes, nt.s);
+    }
     if (st != LAMP_OK) return st;
     lamp_tensor_desc y2 = nt.td(l, Cout, c2.ldy);
     if (u->se_ratio) {   // out = a1 + gate(mean a2) * a2: the gate on the second unit, the first unit's output as the shortcut
@@ -526,6 +533,7 @@ static lamp_status unet_run(const lamp_unet_desc* u, const void* const* P, const
                 tail && bwd ? tail->d_skips : nullptr);
     nt.scratch = lay.scratch; nt.scratch_bytes = lay.scratch_bytes;
     nt.gaux = lay.g2;
+    nt.fwd_only = !bwd;
     const bool first_dgrad = tail && tail->d_x;
     RepackTable tab;
     if ((st = prepare_repack(nt, lay, first, L, true, pbase, P, phase != 2, bwd && phase != 1, first_dgrad, tab)) != LAMP_OK)

@@ -248,6 +248,45 @@ def test_conv3d_on_channel_slices_and_norm_on_load(L, dtype):
     assert torch.all(dxb[..., :16] == 0)
 
 
+@pytest.mark.parametrize("shape", [(1, 12, 20, 36, 64, 64), (2, 9, 17, 33, 32, 32), (1, 8, 24, 16, 64, 32), (2, 5, 8, 16, 32, 128)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("affine,relu", [(False, 1), (True, 1), (True, 0)], ids=["plain", "affine", "affine-norelu"])
+def test_conv3d_norm_on_load_matrix_core(L, shape, affine, relu):
+    """InstanceNorm + ReLU applied while the matrix-core conv loads its input (the activated tensor is never
+    written): the statistics come from lamp_inorm_relu on the raw tensor, the conv takes the raw tensor + lamp_norm_in.
+    What the matrix cores read must be bit for bit the activated tensor of the stand-alone pass, so output and fused
+    statistics are compared bitwise with the conv of the materialised tensor, and with the oracle.  Shapes span
+    several tiles with ragged edges in every axis (zero padding applies after the transform), two samples
+    (per-sample coefficients) and both output-channel block widths."""
+    N, D, H, W, Ci, Co = shape
+    r = rng(700 + Ci + Co + D)
+    xraw = to_dev(S.normal(r, (N, D, H, W, Ci)) * 1.3 + 0.4, BF)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
+    g = to_dev(r.uniform(0.5, 1.5, Ci), F32) if affine else None
+    bt = to_dev(r.uniform(-0.5, 0.5, Ci), F32) if affine else None
+    st = torch.empty((N, Ci, 2), dtype=F32, device=DEV)
+    y = torch.empty_like(xraw)
+    L.lamp_inorm_relu(xraw, y, st, gamma=g, beta=bt)
+    if not relu:   # the stand-alone pass always applies the ReLU: build the un-clamped tensor from the oracle's formula
+        s64 = as64(st)
+        u = (as64(xraw) - s64[:, None, None, None, :, 0]) * s64[:, None, None, None, :, 1]
+        u = u * (as64(g) if affine else 1.0) + (as64(bt) if affine else 0.0)
+        y = to_dev(u, BF)
+    z_ref = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    s_ref = torch.empty((N, Co, 2), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(y, w, z_ref, stats_out=s_ref)
+    z = torch.full_like(z_ref, float("nan"))
+    s_f = torch.empty_like(s_ref)
+    nm = dict(mean_rstd=st, gamma=g, beta=bt, c_norm=Ci, relu=relu)
+    L.lamp_conv3d_fwd(xraw, w, z, xnorm=nm, stats_out=s_f)
+    check(as64(z), O.conv3d_fwd(as64(y), as64(w)), BF, "conv fwd, normalise on load")
+    if relu:
+        assert torch.equal(z, z_ref), "normalise-on-load output differs from the conv of the materialised tensor"
+        assert torch.equal(s_f, s_ref)
+    else:   # the fp64-built tensor may round differently from the kernel's fp32 fma in the last bit
+        check(as64(z), as64(z_ref), BF, "conv fwd, normalise on load vs materialised", tol=5e-3)
+
+
 NORM_SHAPES = [(2, 3, 5, 7, 5), (1, 8, 8, 8, 8), (2, 16, 20, 24, 64), (1, 17, 9, 33, 32), (1, 4, 4, 4, 512), (1, 6, 6, 6, 24)]
 
 
