@@ -1026,8 +1026,9 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
 // needed K-major per lane but live channel-major (NDHWC) in LDS, so fragments are read with the
 // transposing LDS load (ds_read_b64_tr_b16): inside each 16-lane group, source lane s supplies
 // 4 channels of voxel row s/4 and lane t receives channel t of 4 consecutive voxel rows.
-// A workgroup (8 waves) owns one 32-wide ci block and 32*COB output channels for all 27 taps, the
-// taps dealt round-robin to the waves (<= 4 each, accumulators 2*4*16 registers), and walks a
+// A workgroup (8 waves) owns one 32-wide ci block and 32*COB output channels for all 27 taps, a
+// tap column (kd, kw) per wave plus one tap of the ninth column for three of them (<= 4 taps each,
+// accumulators 2*4*16 registers), and walks a
 // contiguous range of 2 x 8 x 16 voxel tiles, accumulating in registers; tiles are double
 // buffered in LDS.  Per-workgroup partials are summed by a second, fixed-order kernel.
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
@@ -1072,11 +1073,17 @@ struct WgradLane {
     int zpk[4];    // its tile coords
 };
 
+// One tile: copies of the next tile, 16 k-steps (one 16-voxel w-row of the tile each), barrier.
+// A wave owns one tap column (kd, kw) with its three taps kh = 0, 1, 2: at k-step (d, h) they read the x rows
+// h, h+1, h+2 of halo slice d + kd, so from one k-step to the next two of the three row fragments stay in
+// registers and one new row is read (three at the change of d): 20 row fragments per tile feed 48*COB matrix
+// instructions, where a fragment per tap and k-step would be 48.  The ninth column (2, 2) has no wave of its
+// own: waves 0, 1, 2 take one of its taps each (NT == 4), one more row fragment per k-step.
 template <int COB, int NT>
 __device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __restrict__ st, char* __restrict__ st_next,
                                            bool pf, const WgradLane& wl, const bf16_t* xorg, const bf16_t* zorg,
                                            int dlo, int dhi, int hlo, int hhi, int wlo, int whi, int zd, int zh, int zw,
-                                           const bf16_t* zero16, const uint32_t (&tapoff)[4], uint32_t loff, int wv) {
+                                           const bf16_t* zero16, uint32_t coloff, uint32_t extoff, uint32_t loff, int wv) {
     constexpr int XCOPIES = WX_VOX / 16;            // 45
     constexpr int ZCOPIES = COB * WTILE_VOX / 16;   // 32 or 16
     if (pf) {
@@ -1102,30 +1109,55 @@ __device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    const char* xb = st + loff;
+    const char* xb = st + loff + coloff;
+    const char* xe = st + loff + extoff;
     const char* dzb = st + WX_BYTES + loff;
-    // fragments of k-step k+1 are fetched while k-step k is multiplied
-    bf16x8 af[2][COB], bfr[2][NT];
-    auto load_frags = [&](int ks, int slot) {
-        const int d = ks >> 3, h = ks & 7;  // k-step = one 16-voxel w-row of the tile
-        const uint32_t rowoff = (uint32_t)((d * WHH + h) * WHW * 64);
+    // Row fragments of the column as one stream q = 10*d + r (r = halo row of slice d + kd); fragment q lives in
+    // register set q % 6, which its predecessor q - 6 has left two k-steps earlier.  Everything a k-step needs is
+    // read during the k-step before it.
+    bf16x8 af[2][COB], rb[6], eb[2];
+    auto row = [&](int q) __attribute__((always_inline)) {
+        return lds_frag_tr(xb + (uint32_t)(((q / 10) * WHH + (q % 10)) * WHW * 64));
+    };
+    auto ext = [&](int ks) __attribute__((always_inline)) {
+        return lds_frag_tr(xe + (uint32_t)(((ks >> 3) * WHH + (ks & 7)) * WHW * 64));
+    };
+    auto load_a = [&](int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
-#pragma unroll
-        for (int i = 0; i < NT; ++i) bfr[slot][i] = lds_frag_tr(xb + rowoff + tapoff[i]);
     };
-    load_frags(0, 0);
+    load_a(0, 0);
+    rb[0] = row(0);
+    rb[1] = row(1);
+    rb[2] = row(2);
+    if constexpr (NT == 4) eb[0] = ext(0);
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
-        if (ks < 15) load_frags(ks + 1, (ks + 1) & 1);
+        const int q0 = 10 * (ks >> 3) + (ks & 7);
+        if (ks < 15) {
+            load_a(ks + 1, (ks + 1) & 1);
+            const int qn = 10 * ((ks + 1) >> 3) + ((ks + 1) & 7);
+            if (((ks + 1) & 7) == 0) {   // next slice: three new rows
+                rb[qn % 6] = row(qn);
+                rb[(qn + 1) % 6] = row(qn + 1);
+            }
+            rb[(qn + 2) % 6] = row(qn + 2);
+            if constexpr (NT == 4) eb[(ks + 1) & 1] = ext(ks + 1);
+        }
 #pragma unroll
-        for (int i = 0; i < NT; ++i)
+        for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
-                acc[cb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], bfr[ks & 1][i], acc[cb][i], 0, 0, 0);
+                acc[cb][kh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], rb[(q0 + kh) % 6], acc[cb][kh], 0, 0, 0);
+        if constexpr (NT == 4) {
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb)
+                acc[cb][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], eb[ks & 1], acc[cb][3], 0, 0, 0);
+        }
         if (ks < 15) {
-            constexpr int NM = NT * COB, NR = 2 * (COB + NT);  // MFMAs and LDS reads per k-step
-            sched_interleave<0, NM, NR>();
+            constexpr int NM = NT * COB;   // MFMAs per k-step
+            if (((ks + 1) & 7) == 0) sched_interleave<0, NM, 2 * (COB + 3 + (NT == 4 ? 1 : 0))>();
+            else sched_interleave<0, NM, 2 * (COB + 1 + (NT == 4 ? 1 : 0))>();
         }
     }
     wait_vmcnt<0>();
@@ -1143,15 +1175,12 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     const int tile_lo = blockIdx.x * a.tiles_per_wg;
     const int tile_hi = min(tile_lo + a.tiles_per_wg, a.tiles_total);
 
-    // taps of this wave: wv, wv+8, wv+16, wv+24 (the last only for waves 0..2)
-    uint32_t tapoff[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int t = wv + 8 * i;
-        const int kd = t / 9, kh = (t / 3) % 3, kw = t % 3;
-        tapoff[i] = (uint32_t)(((kd * WHH + kh) * WHW + kw) * 64);
-    }
-    const bool has4 = wv + 24 < 27;
+    // taps of this wave: the column (kd, kw) = (wv / 3, wv % 3) with kh = 0, 1, 2 (accumulators 0..2); waves 0..2
+    // also take tap (2, kh = wv, 2) of the ninth column (accumulator 3)
+    const int col_kd = wv / 3, col_kw = wv % 3;
+    const uint32_t coloff = (uint32_t)((col_kd * WHH * WHW + col_kw) * 64);
+    const uint32_t extoff = (uint32_t)(((2 * WHH + wv) * WHW + 2) * 64);
+    const bool has4 = wv < 3;
 
     // lane part of a transposing fragment read: voxel row 8*(b/2) + s/4, channel bytes 32*(b%2) + 8*(s%4)
     const int b16 = lane >> 4, s16 = lane & 15;
@@ -1203,10 +1232,10 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
         if (has4)
             wgrad_tile<COB, 4>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
-                               a.D - d0, a.H - h0, a.W - w0, a.zero16, tapoff, loff, wv);
+                               a.D - d0, a.H - h0, a.W - w0, a.zero16, coloff, extoff, loff, wv);
         else
             wgrad_tile<COB, 3>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
-                               a.D - d0, a.H - h0, a.W - w0, a.zero16, tapoff, loff, wv);
+                               a.D - d0, a.H - h0, a.W - w0, a.zero16, coloff, extoff, loff, wv);
     };
 
     if (tile_lo < tile_hi) {
@@ -1248,8 +1277,8 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     const int l32 = lane & 31, half = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int t = wv + 8 * i;
-        if (t < 27) {
+        const int t = i < 3 ? col_kd * 9 + i * 3 + col_kw : 18 + wv * 3 + 2;
+        if (i < 3 || has4) {
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
