@@ -48,6 +48,40 @@ def test_param_table_matches_documented_order(L):
         assert L.lamp_unet_param_numel(ud, len(p)) == 0 and L.lamp_unet_param_numel(ud, -1) == 0
 
 
+def test_param_table_of_the_squeeze_and_excitation_variant(L):
+    """se_ratio > 0: four gate tensors behind each block's convs, cr = max(1, C / ratio) hidden units."""
+    for levels, base, affine, ratio in [(5, 32, False, 16), (3, 8, True, 4), (2, 8, False, 16)]:
+        ud = L.unet_desc(levels, base, 1, 4, 1, 16, 16, 16, torch.float32, affine=affine, se_ratio=ratio)
+        p = S.unet_params(S.streams(0, 1)[0], levels, base, 1, 4, affine, se_ratio=ratio)
+        assert L.lamp_unet_param_count(ud) == len(p)
+        for i, (k, v) in enumerate(p.items()):
+            assert L.lamp_unet_param_numel(ud, i) == v.size, (i, k)
+    bad = L.unet_desc(3, 8, 1, 4, 1, 16, 16, 16, torch.float32, se_ratio=-1)
+    assert L.lamp_unet_param_count(bad) == 0 and L.lamp_unet_workspace_bytes(bad, False) == 0
+    se = L.unet_desc(3, 32, 1, 4, 1, 16, 16, 16, torch.bfloat16, se_ratio=16)
+    plain = L.unet_desc(3, 32, 1, 4, 1, 16, 16, 16, torch.bfloat16)
+    assert L.lamp_unet_workspace_bytes(se, True) > L.lamp_unet_workspace_bytes(plain, True)
+    # the partition entry points serve the plain U-Net only
+    assert L.lamp_unet_stage_workspace_bytes(se, 1, 2) == 0 and L.lamp_unet_tail_workspace_bytes(se, 2) == 0
+    assert L.lamp_unet_pipeline_workspace_bytes(se, 1, 2) == 0
+
+
+def test_noalloc_entry_point_argument_errors(L):
+    """lamp_inorm_relu_noalloc: NULL pointers, bad descriptors and requests beyond the fixed scratch are
+    turned away on the host before the scratch is even looked up (no GPU needed)."""
+    lib = L.lib()
+    TD = L.binding.TensorDesc
+    ok = TD(1, 8, 8, 8, 32, 32, 1)
+    one = ctypes.c_void_p(16)
+    call = lambda zd, z, yd, y, st: lib.lamp_inorm_relu_noalloc(ctypes.byref(zd), z, None, None, 1e-5, ctypes.byref(yd), y, st, None)
+    assert call(ok, None, ok, one, one) == -1 and call(ok, one, ok, None, one) == -1 and call(ok, one, ok, one, None) == -1
+    assert call(TD(1, 0, 8, 8, 32, 32, 1), one, ok, one, one) == -2
+    assert call(TD(1, 8, 8, 8, 32, 16, 1), one, ok, one, one) == -2            # ldc < c
+    big = TD(64, 128, 128, 128, 4096, 4096, 1)
+    assert lib.lamp_inorm_relu_workspace_bytes(ctypes.byref(big)) > (8 << 20)
+    assert call(big, one, big, one, one) == -5
+
+
 def test_window_count(L):
     assert L.lamp_sliding_window_count(256, 256, 160, 64, 0.25) == 75
     assert L.lamp_sliding_window_count(64, 64, 64, 64, 0.25) == 1
