@@ -151,6 +151,13 @@ __device__ __forceinline__ void g2lds16(const void* g, char* lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m), "v"(g) : "memory", "m0");
 }
 
+// The same with the target given as an LDS byte address (kept as an integer from the start, so that no pointer
+// passes through the generic address space on its way here).
+__device__ __forceinline__ void g2lds16a(const void* g, uint32_t lds_addr) {
+    const uint32_t m = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m), "v"(g) : "memory", "m0");
+}
+
 // Scheduling hint: NM MFMAs with NR LDS reads spread evenly behind them.
 template <int K, int NM, int NR> __device__ __forceinline__ void sched_interleave() {
     if constexpr (K < NM) {
@@ -239,138 +246,254 @@ template <int K, int NM, int NR, int NV, int NW> __device__ __forceinline__ void
     }
 }
 
-// One kd group of one chunk: issue this group's share of the prefetch (weights of the next group
-// first, then halo blocks of the next chunk), multiply 9 taps, wait for the weight copies and
-// meet at the barrier.  The four LDS regions are distinct, and saying so (__restrict__) matters:
-// otherwise the compiler must assume the fragment reads alias the in-flight copies and waits for
-// them before the first read.
-//   HALO_FIRST, HALO_CNT : halo copy slots (block j = slot/2, plane = slot%2) issued in this group
-//   NORM_FIRST, NORM_CNT : slots of the incoming chunk that this group normalises in LDS (normalise on load), after
-//                          waiting until at most NORM_WAIT of this wave's copies are in flight (< 0: no wait needed)
-//   DRAIN                : the group ends with every copy landed (its own halo copies are not issued by all waves)
-template <int COB, int TDT, int G, int HALO_FIRST, int HALO_CNT, int NORM_FIRST = 0, int NORM_CNT = 0, int NORM_WAIT = -1,
-          bool DRAIN = false>
-__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], const char* __restrict__ hb, const char* __restrict__ wb,
-                                           char* __restrict__ hb_next, char* __restrict__ wb_next, bool pf_halo,
-                                           bool pf_w, const HaloLane& hl, const HaloTile& ht, int64_t pf_choff,
-                                           const bf16_t* zero16, const bf16_t* wsrc, const int (&wrel)[3], int wv,
-                                           int lane, const float2* __restrict__ abp = nullptr, float relu_floor = 0.f) {
-    typedef Geo<TDT> GE;
-    constexpr int NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES;
-    constexpr int WROWS = 32 * COB;
-    constexpr int WPLANE = WROWS * 16;
-    constexpr int WINSTR = 18 * WROWS / 64;
-    constexpr int WCOPY_ITERS = (WINSTR + 7) / 8;
-    if (pf_w) {
-#pragma unroll
-        for (int i = 0; i < WCOPY_ITERS; ++i) {
-            const int q = wv + 8 * i;
-            if (q < WINSTR) g2lds16(wsrc + wrel[i], wb_next + q * 1024);
-        }
-    }
-    if (pf_halo) {
-#pragma unroll
-        for (int sl = HALO_FIRST; sl < HALO_FIRST + HALO_CNT; ++sl) {
-            const int j = sl >> 1, plane = sl & 1;
-            const int blk = wv + 8 * j;
-            if (blk < HBLK && blk * 64 + lane < HALO_VOX) {
-                const int pk = hl.pk[j];
-                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
-                const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
-                const bf16_t* src = in ? ht.origin + hl.rel[j] + pf_choff + plane * 8 : zero16;
-                g2lds16(src, hb_next + plane * PLANE_BYTES + blk * 1024);
-            }
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // Normalise on load: this group's NORM_CNT slots of the incoming chunk.  The first wave of every SIMD rewrites
-    // them before its multiply section, the second one after it (waves w and w + 4 share a SIMD): while one wave
-    // of a SIMD runs the vector-ALU work of the rewrite the other one feeds the matrix cores.
-    const bool rmw_early = wv < 4;
-    if constexpr (NORM_CNT > 0) {
-        if constexpr (NORM_WAIT >= 0) {
-            if (pf_halo) wait_vmcnt<NORM_WAIT>();
-        }
-        if (rmw_early) halo_norm<TDT, NORM_FIRST, NORM_CNT>(hb_next, hl, ht, abp, relu_floor, wv, lane);
-    }
+// Fragment registers that live from one column of the multiply pipeline to the next (and from the last column of
+// a tile, across its epilogue, to the first column of the next tile).
+template <int COB, int TDT> struct Frags;
+template <int COB> struct Frags<COB, 8> {
+    bf16x8 a[2][3][COB];   // weight fragments of a tap column (kd = 0, 1, 2), two slots
+    bf16x8 b[2];           // input slices 0 and 1 of the current column
+};
+template <int COB> struct Frags<COB, 4> {
+    bf16x8 a[2][COB];                // weight fragments of a tap, two slots
+    bf16x8 b[2][Geo<4>::NVB];        // activation fragments of a tap, two slots
+};
+
+// The fragments of the first column (8-deep tile) / first tap (4-deep tile) of group G, into slot SLOT.
+template <int COB, int TDT, int G, int SLOT>
+__device__ __forceinline__ void load_first(Frags<COB, TDT>& f, const char* __restrict__ hb, const char* __restrict__ wb) {
+    constexpr int WPLANE = 32 * COB * 16;
     if constexpr (TDT == 8) {
-        // ---- multiply, 8-deep tile: the group is the in-plane row G = kh.  A wave owns 4 d-slices of one
-        // (2 h-rows x 16 w) block; for a tap column kw the input slice s = d + kd serves the output slices
-        // d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6 slice fragments and 3*COB weight fragments
-        // feed 12*COB MFMAs.  The weight fragments and the first two slices of the next column are fetched
-        // while this one is multiplied.
-        bf16x8 a[2][3][COB], b[6], nb[2];
-        auto load_a = [&](int kw, int slot) __attribute__((always_inline)) {
 #pragma unroll
-            for (int kd = 0; kd < 3; ++kd)
+        for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
-                for (int cb = 0; cb < COB; ++cb) a[slot][kd][cb] = lds_frag(wb + (kd * 3 + kw) * 2 * WPLANE + cb * 32 * 16);
-        };
-        auto frag_b = [&](int kw, int sl) __attribute__((always_inline)) { return lds_frag(hb + ((sl * HH + G) * HW + kw) * 16); };
-        load_a(0, 0);
-        b[0] = frag_b(0, 0);
-        b[1] = frag_b(0, 1);
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) {
-#pragma unroll
-            for (int sl = 2; sl < 6; ++sl) b[sl] = frag_b(kw, sl);
-            if (kw < 2) {
-                load_a(kw + 1, (kw + 1) & 1);
-                nb[0] = frag_b(kw + 1, 0);
-                nb[1] = frag_b(kw + 1, 1);
-            }
-#pragma unroll
-            for (int sl = 0; sl < 6; ++sl)
-#pragma unroll
-                for (int kd = 0; kd < 3; ++kd) {
-                    const int d = sl - kd;
-                    if (d >= 0 && d < 4) {
-#pragma unroll
-                        for (int cb = 0; cb < COB; ++cb)
-                            acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kw & 1][kd][cb], b[sl], acc[cb][d], 0, 0, 0);
-                    }
-                }
-            if (kw < 2) sched_interleave<0, 12 * COB, 6 + 3 * COB>();
-            else sched_interleave<0, 12 * COB, 4>();
-            b[0] = nb[0];
-            b[1] = nb[1];
-        }
+            for (int cb = 0; cb < COB; ++cb) f.a[SLOT][kd][cb] = lds_frag(wb + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
+        f.b[0] = lds_frag(hb + ((0 * HH + G) * HW) * 16);
+        f.b[1] = lds_frag(hb + ((1 * HH + G) * HW) * 16);
     } else {
-    // ---- multiply: 9 taps of this kd, one k-step each; fragments of tap t+1 are fetched while
-    // tap t is multiplied
-    bf16x8 af[2][COB], bfr[2][NVB];
-    auto load_frags = [&](int t9, int slot) {
-        const int kh = t9 / 3, kw = t9 - 3 * kh;
-        const int tapoff = ((G * HH + kh) * HW + kw) * 16;
 #pragma unroll
-        for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag(wb + t9 * 2 * WPLANE + cb * 32 * 16);
+        for (int cb = 0; cb < COB; ++cb) f.a[SLOT][cb] = lds_frag(wb + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) bfr[slot][vb] = lds_frag(hb + tapoff + vb * HW * 16);
+        for (int vb = 0; vb < Geo<4>::NVB; ++vb) f.b[SLOT][vb] = lds_frag(hb + (G * HH * HW) * 16 + vb * HW * 16);
+    }
+}
+
+// What the register-free copies and the normalise-on-load rewrite of a chunk stage need.
+struct CopyCtx {
+    char* hb_next;          // halo buffer of the incoming chunk
+    uint32_t hb_next_a;     // its LDS byte address
+    uint32_t wb_fill_a;     // LDS byte address of the weight buffer that this group has finished with
+    bool pf_halo, pf_w;     // whether there is an incoming chunk / a weight group to fetch
+    int64_t pf_choff;       // element offset of the incoming chunk's channels
+    const bf16_t* zero16;
+    const bf16_t* wsrc;     // weights of the group after next
+    const float2* abp;      // normalise on load: (a, b) pairs of the incoming chunk's channels
+    float relu_floor;
+    int wv, lane;
+};
+
+// One portion of a stage's copy work, placed in the middle of a column's matrix instructions (the global -> LDS
+// copies of a wave queue up behind each other: issued in one burst they hold up the wave, and with it the
+// workgroup's next barrier, for thousands of cycles; a few per column never fill the queue):
+//   WC          : the weight copies of the group after next
+//   HF, HC      : halo copy slots [HF, HF + HC) of the incoming chunk (slot = block j * 2 + plane)
+//   NF, NC, NW  : normalise on load: rewrite slots [NF, NF + NC) once at most NW of this wave's copies are in flight
+template <int COB, int TDT, bool WC, int HF, int HC, int NF, int NC, int NW>
+__device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+    typedef Geo<TDT> GE;
+    constexpr int WINSTR = 18 * 32 * COB / 64;
+    constexpr int WCOPY_ITERS = (WINSTR + 7) / 8;
+    if constexpr (NC > 0) {
+        if (c.pf_halo) {
+            wait_vmcnt<NW>();
+            halo_norm<TDT, NF, NC>(c.hb_next, hl, ht, c.abp, c.relu_floor, c.wv, c.lane);
+        }
+    }
+    if constexpr (WC) {
+        if (c.pf_w) {
+#pragma unroll
+            for (int i = 0; i < WCOPY_ITERS; ++i) {
+                const int q = c.wv + 8 * i;
+                if (q < WINSTR) g2lds16a(c.wsrc + wrel[i], c.wb_fill_a + q * 1024);
+            }
+        }
+    }
+    if constexpr (HC > 0) {
+        if (c.pf_halo) {
+#pragma unroll
+            for (int sl = HF; sl < HF + HC; ++sl) {
+                const int j = sl >> 1, plane = sl & 1;
+                const int blk = c.wv + 8 * j;
+                if (blk < GE::HBLK && blk * 64 + c.lane < GE::HALO_VOX) {
+                    const int pk = hl.pk[j];
+                    const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+                    const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+                    const bf16_t* src = in ? ht.origin + hl.rel[j] + c.pf_choff + plane * 8 : c.zero16;
+                    g2lds16a(src, c.hb_next_a + plane * GE::PLANE_BYTES + blk * 1024);
+                }
+            }
+        }
+    }
+}
+
+// Which portion goes where.  The halo of the incoming chunk may be written once every wave is past the barrier of the
+// chunk's group 0 (the previous chunk's halo, whose buffer it takes, is read up to the column before), and must have
+// landed at the barrier of group 2, so its slots go out from the last column of group 0 to the last column of
+// group 1, leaving the youngest ones three columns to land.  COL: column (8-deep tile) or tap (4-deep tile) of the group.
+template <int TDT, bool NORM, int G, int COL> struct Portion {
+    static constexpr int NS = 2 * Geo<TDT>::HJ, FULLS = 2 * (Geo<TDT>::HBLK / 8);
+    static constexpr int LASTC = TDT == 8 ? 2 : 8;                  // the column behind the barrier
+    static constexpr bool WC = COL == LASTC;
+    // copy slots.  Plain: 2 per column over the four columns from (group 0, last) on; 4-deep tile (6 slots): taps
+    // (0, 8), (1, 2), (1, 8).  Normalise on load: everything two columns earlier, so that the rewrite finds it landed.
+    static constexpr int HF = NORM ? (G == 0 && COL == LASTC ? 0 : G == 1 && COL == 0 ? 4 : 0)
+                                   : TDT == 8 ? (G == 0 && COL == 2 ? 0 : G == 1 ? 2 + 2 * COL : 0)
+                                              : (G == 0 && COL == 8 ? 0 : G == 1 && COL == 2 ? 2 : G == 1 && COL == 8 ? 4 : 0);
+    static constexpr int HC = NORM ? (G == 0 && COL == LASTC ? 4 : G == 1 && COL == 0 ? NS - 4 : 0)
+                                   : TDT == 8 ? ((G == 0 && COL == 2) || G == 1 ? 2 : 0)
+                                              : ((G == 0 && COL == 8) || (G == 1 && (COL == 2 || COL == 8)) ? 2 : 0);
+    // rewrite (normalise on load): slots [0, 4) in the first column / tap of group 2 -- younger than they are the
+    // all-wave slots from 4 on and the weight copies of (group 1, last column), of which every wave issues at least
+    // WINSTR / 8 >= 1 -- and the rest in the second column / fourth tap, with everything landed
+    static constexpr int NF = G == 2 && COL == 0 ? 0 : 4;
+    static constexpr int NC = !NORM ? 0 : G == 2 && COL == 0 ? 4 : G == 2 && COL == (TDT == 8 ? 1 : 4) ? NS - 4 : 0;
+    static constexpr int NW = G == 2 && COL == 0 ? (FULLS - 4) + 1 : 0;
+    // copies of a wave that may be in flight at the group's barrier without the next group's weights among them:
+    // group 1: the all-wave halo slots issued behind the weight copies of (group 0, last column)
+    static constexpr int BARRIER_WAIT = G == 1 ? FULLS : 0;
+};
+
+// 8-deep tile, one tap column kw = KW of the in-plane row G = kh.  A wave owns 4 d-slices of one (2 h-rows x 16 w)
+// block; the input slice s = d + kd serves the output slices d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6
+// slice fragments and 3*COB weight fragments feed 12*COB MFMAs.  The weight fragments and the first two slices of
+// the next column are fetched meanwhile: of column KW + 1, or (KW == 2) of the first column of the group GN that
+// follows, whose weights sit in wbn and whose halo is hbn.  The column's portion of the copy work follows its matrix
+// instructions.
+template <int COB, int G, int KW, int SLOT, int GN, bool NORM>
+__device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f, const char* __restrict__ hb,
+                                        const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
+                                        const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+    constexpr int WPLANE = 32 * COB * 16;
+    typedef Portion<8, NORM, G, KW> PO;
+    bf16x8 b[6], nb0, nb1;
+    b[0] = f.b[0];
+    b[1] = f.b[1];
+#pragma unroll
+    for (int sl = 2; sl < 6; ++sl) b[sl] = lds_frag(hb + ((sl * HH + G) * HW + KW) * 16);
+    if constexpr (KW < 2) {
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][kd][cb] = lds_frag(wb + (kd * 3 + KW + 1) * 2 * WPLANE + cb * 32 * 16);
+        nb0 = lds_frag(hb + ((0 * HH + G) * HW + KW + 1) * 16);
+        nb1 = lds_frag(hb + ((1 * HH + G) * HW + KW + 1) * 16);
+    } else {
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+            for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][kd][cb] = lds_frag(wbn + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
+        nb0 = lds_frag(hbn + ((0 * HH + GN) * HW) * 16);
+        nb1 = lds_frag(hbn + ((1 * HH + GN) * HW) * 16);
+    }
+    auto mul = [&](int sl) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd) {
+            const int d = sl - kd;
+            if (d >= 0 && d < 4) {
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb)
+                    acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][kd][cb], b[sl], acc[cb][d], 0, 0, 0);
+            }
+        }
     };
-    load_frags(0, 0);
 #pragma unroll
-    for (int t9 = 0; t9 < 9; ++t9) {
-        if (t9 < 8) load_frags(t9 + 1, (t9 + 1) & 1);
+    for (int sl = 0; sl < 6; ++sl) mul(sl);
+    sched_interleave<0, 12 * COB, 6 + 3 * COB>();
+    if constexpr (PO::WC || PO::HC > 0 || PO::NC > 0) {
+        // behind the column's last matrix instruction, where the fewest fragments are live
+        __builtin_amdgcn_sched_barrier(0);
+        copy_portion<COB, 8, PO::WC, PO::HF, PO::HC, PO::NF, PO::NC, PO::NW>(c, hl, ht, wrel);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    f.b[0] = nb0;
+    f.b[1] = nb1;
+}
+
+// 4-deep tile, tap T9 = kh*3 + kw of the slice group G = kd: one k-step for the wave's NVB blocks; the fragments of
+// the next tap (T9 == 8: of the first tap of the group GN that follows) are fetched meanwhile.  The tap's portion of
+// the copy work follows its matrix instructions.
+template <int COB, int G, int T9, int SLOT, int GN, bool NORM>
+__device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB, 4>& f, const char* __restrict__ hb,
+                                     const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
+                                     const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+    constexpr int WPLANE = 32 * COB * 16, NVB = Geo<4>::NVB;
+    typedef Portion<4, NORM, G, T9> PO;
+    if constexpr (T9 < 8) {
+        constexpr int kh = (T9 + 1) / 3, kw = (T9 + 1) % 3;
 #pragma unroll
-        for (int cb = 0; cb < COB; ++cb)
+        for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wb + (T9 + 1) * 2 * WPLANE + cb * 32 * 16);
 #pragma unroll
-            for (int vb = 0; vb < NVB; ++vb)
-                acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t9 & 1][cb], bfr[t9 & 1][vb], acc[cb][vb], 0, 0, 0);
-        if (t9 < 8) sched_interleave<0, NVB * COB, COB + NVB>();
+        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hb + ((G * HH + kh) * HW + kw) * 16 + vb * HW * 16);
+    } else {
+#pragma unroll
+        for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wbn + cb * 32 * 16);
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbn + (GN * HH * HW) * 16 + vb * HW * 16);
     }
+#pragma unroll
+    for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb)
+            acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][cb], f.b[SLOT][vb], acc[cb][vb], 0, 0, 0);
+    sched_interleave<0, NVB * COB, COB + NVB>();
+    if constexpr (PO::WC || PO::HC > 0 || PO::NC > 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        copy_portion<COB, 4, PO::WC, PO::HF, PO::HC, PO::NF, PO::NC, PO::NW>(c, hl, ht, wrel);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (NORM_CNT > 0) {
-        if (!rmw_early) halo_norm<TDT, NORM_FIRST, NORM_CNT>(hb_next, hl, ht, abp, relu_floor, wv, lane);
+}
+
+// One tap group of one chunk (9 taps: the in-plane row kh = G of the 8-deep tile, the slice kd = G of the 4-deep
+// one).  The multiply runs as one pipeline of columns / taps across groups, chunks and tiles: every column fetches
+// the fragments of the next one, so the matrix instructions that follow a barrier have their operands in registers.
+// The workgroup's barrier therefore sits BEFORE the group's last column (last tap): by then every wave has read the
+// last fragments of this group's weights, and all of the previous chunk's halo.  What is copied in behind the
+// barrier: the weights of the group after next, into the buffer this group has just finished with (the last column
+// fetches the first fragments of the next group from the other weight buffer, filled one group earlier), and
+// the next chunk's halo, into the buffer the previous chunk has left (see Portion).
+//   PAR        : fragment slot of the group's first column (it alternates from column to column)
+//   hbn, wbn   : halo (lane base included) and weights of the group that follows
+// The LDS regions are distinct, and saying so (__restrict__) matters: otherwise the compiler must assume the
+// fragment reads alias the in-flight copies and waits for them before the first read.
+template <int COB, int TDT, int G, int PAR, bool NORM>
+__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Frags<COB, TDT>& f, const char* __restrict__ hb,
+                                           const char* __restrict__ wb, const char* __restrict__ hbn,
+                                           const char* __restrict__ wbn, const CopyCtx& c, const HaloLane& hl,
+                                           const HaloTile& ht, const int (&wrel)[3]) {
+    constexpr int GN = (G + 1) % 3;
+    constexpr int WAIT = Portion<TDT, NORM, G, 0>::BARRIER_WAIT;
+    if constexpr (TDT == 8) {
+        column8<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        column8<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+    } else {
+        tap4<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 3, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 4, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 5, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 6, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 7, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
     }
-    // The weight copies are older than this group's halo copies: leaving HALO_CNT copies in flight
-    // still guarantees the weights have landed.  (Every wave issues all HALO_CNT copies of groups
-    // 0 and 1; the last group drains everything because the next stage reads the halo.)
-    if (G < 2 && pf_halo && !DRAIN) wait_vmcnt<(G < 2 ? HALO_CNT : 0)>();
+    // The weights of the next group were copied behind the previous barrier; the only younger copies are halo slots,
+    // of which every wave has issued WAIT (a wave that issued more waits for its oldest ones too).
+    if (WAIT > 0 && c.pf_halo) wait_vmcnt<WAIT>();
     else wait_vmcnt<0>();
     // bare barrier: __syncthreads() would add a release fence that drains every copy in flight
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    if constexpr (TDT == 8) column8<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+    else tap4<COB, G, 8, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
 }
 
 // SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
@@ -384,6 +507,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* hbuf0 = lds;
     char* wbuf0 = lds + 2 * HALO_BYTES;
+    // LDS byte addresses of the two, for the register-free copies
+    const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds, wbuf_a = lds_a + 2 * HALO_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int cbi = a.cb_inner ? (int)(blockIdx.x >> 3) % a.cb_inner : (int)blockIdx.y;   // output-channel block
@@ -459,7 +584,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
 
-    // ---- prologue: first halo chunk and first weight group
+    // ---- prologue: first halo chunk and the first two weight groups
     {
         const HaloTile t0 = halo_tile(tile);
 #pragma unroll
@@ -469,12 +594,15 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 const int pk = hl.pk[j];
                 const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
                 const bool in = hd >= t0.dlo && hd <= t0.dhi && hh >= t0.hlo && hh <= t0.hhi && hw >= t0.wlo && hw <= t0.whi;
-                g2lds16(in ? t0.origin + hl.rel[j] + choff(c_lo) + plane * 8 : a.zero16, hbuf0 + plane * PLANE_BYTES + blk * 1024);
+                g2lds16a(in ? t0.origin + hl.rel[j] + choff(c_lo) + plane * 8 : a.zero16, lds_a + plane * PLANE_BYTES + blk * 1024);
             }
         }
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
-            if (wv + 8 * i < WINSTR) g2lds16(wbase + (int64_t)c_lo * (3 * wgstride) + wrel[i], wbuf0 + (wv + 8 * i) * 1024);
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                if (wv + 8 * i < WINSTR)
+                    g2lds16a(wbase + (int64_t)c_lo * (3 * wgstride) + g * wgstride + wrel[i], wbuf_a + g * WBUF_BYTES + (wv + 8 * i) * 1024);
         wait_vmcnt<0>();
         if constexpr (NORM)
             halo_norm<TDT, 0, 2 * HJ>(hbuf0, hl, t0, a.ab + (int64_t)(tile / a.tiles_per_n) * a.Cin + c_lo * 16, a.relu_floor, wv, lane);
@@ -483,6 +611,44 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
 
     int stage = 0;  // parity selects the halo buffer
     int wpar = 0;   // parity selects the weight buffer
+    // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
+    Frags<COB, TDT> fr;
+    load_first<COB, TDT, 0, 0>(fr, hbuf0 + b_base, wbuf0 + a_base);
+    // One 16-channel chunk = three tap groups; P = fragment slot of its first column (a group has an odd number of
+    // columns / taps, so the slot alternates from group to group).
+    auto chunk_groups = [&](f32x16 (&acc)[COB][NVB], int chunk, int tile, int next_tile, const HaloTile& ht_cur,
+                            const HaloTile& ht_next) __attribute__((always_inline)) {
+        constexpr int P = 0;
+        const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
+        char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
+        const char* hbn = hb_next + b_base;
+        // what streams in during this stage: the next chunk of this tile, or chunk 0 of the next
+        const bool last_chunk = chunk + 1 == c_hi;
+        const int pf_chunk = last_chunk ? c_lo : chunk + 1;
+        const bool pf = !last_chunk || next_tile < tile_hi;
+        const HaloTile ht = last_chunk ? ht_next : ht_cur;   // a copy: a reference picked at run time would put both in memory
+        const char* w0p = wbuf0 + wpar * WBUF_BYTES + a_base;
+        const char* w1p = wbuf0 + (wpar ^ 1) * WBUF_BYTES + a_base;
+        const uint32_t hb_next_a = lds_a + ((stage + 1) & 1) * HALO_BYTES;
+        const uint32_t w0n = wbuf_a + wpar * WBUF_BYTES, w1n = wbuf_a + (wpar ^ 1) * WBUF_BYTES;
+        // weights copied behind the barriers of the three groups: group 2 of this chunk, groups 0 and 1 of the next
+        const bf16_t* wc2 = wbase + (int64_t)chunk * (3 * wgstride) + 2 * wgstride;
+        const bf16_t* wn0 = wbase + (int64_t)pf_chunk * (3 * wgstride);
+        CopyCtx cc;
+        cc.hb_next = hb_next; cc.hb_next_a = hb_next_a; cc.pf_halo = pf; cc.pf_choff = choff(pf_chunk); cc.zero16 = a.zero16;
+        cc.abp = nullptr; cc.relu_floor = a.relu_floor; cc.wv = wv; cc.lane = lane;
+        if constexpr (NORM) {
+            const int n_pf = (last_chunk && next_tile < tile_hi ? next_tile : tile) / a.tiles_per_n;
+            cc.abp = a.ab + (int64_t)n_pf * a.Cin + pf_chunk * 16;
+        }
+        cc.wb_fill_a = w0n; cc.pf_w = true; cc.wsrc = wc2;
+        conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, cc, hl, ht, wrel);
+        cc.wb_fill_a = w1n; cc.pf_w = pf; cc.wsrc = wn0;
+        conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, cc, hl, ht, wrel);
+        cc.wb_fill_a = w0n; cc.wsrc = wn0 + wgstride;
+        conv_group<COB, TDT, 2, P, NORM>(acc, fr, hb, w0p, hbn, w1p, cc, hl, ht, wrel);
+        wpar ^= 1;
+    };
     for (; tile < tile_hi; tile += wg_per_xcd) {
         f32x16 acc[COB][NVB];
 #pragma unroll
@@ -496,49 +662,26 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         const HaloTile ht_cur = halo_tile(tile);
         const HaloTile ht_next = halo_tile(next_tile < tile_hi ? next_tile : tile);
         for (int chunk = c_lo; chunk < c_hi; ++chunk, ++stage) {
-            const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
-            char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
-            // what streams in during this stage: the next chunk of this tile, or chunk 0 of the next
-            const bool last_chunk = chunk + 1 == c_hi;
-            const int pf_chunk = last_chunk ? c_lo : chunk + 1;
-            const bool pf = !last_chunk || next_tile < tile_hi;
-            const HaloTile& ht = last_chunk ? ht_next : ht_cur;
-            const char* w0p = wbuf0 + wpar * WBUF_BYTES + a_base;
-            const char* w1p = wbuf0 + (wpar ^ 1) * WBUF_BYTES + a_base;
-            char* w0n = wbuf0 + wpar * WBUF_BYTES;
-            char* w1n = wbuf0 + (wpar ^ 1) * WBUF_BYTES;
-            const bf16_t* wc = wbase + (int64_t)chunk * (3 * wgstride);
-            // halo copy slots per group (slot = block j * 2 + plane): 4 + 2 + 2 of 8, or 2 + 2 + 2 of 6
-            constexpr int S0 = 2 * HJ - 4;
-            const int64_t pf_off = choff(pf_chunk);
-            if constexpr (NORM) {
-                // Normalise on load: the copies go out early (the slots that every wave issues in group 0, the rest
-                // in group 1), the first slots are normalised in group 1 once they have landed -- behind them this
-                // wave has issued their two younger group-0 slots and at least WINSTR / 8 weight copies -- and the
-                // others in group 2, after group 1 has drained every copy.
-                constexpr int NS = 2 * HJ, FULLS = 2 * (HBLK / 8);
-                static_assert(FULLS >= 4 && FULLS <= NS, "slot split of the normalise-on-load variant");
-                const int n_pf = (last_chunk && next_tile < tile_hi ? next_tile : tile) / a.tiles_per_n;
-                const float2* abp = a.ab + (int64_t)n_pf * a.Cin + pf_chunk * 16;
-                conv_group<COB, TDT, 0, 0, FULLS>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
-                                                  wc + wgstride, wrel, wv, lane);
-                conv_group<COB, TDT, 1, FULLS, NS - FULLS, 0, FULLS - 2, 2 + WINSTR / 8, true>(
-                    acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16, wc + 2 * wgstride, wrel, wv, lane, abp,
-                    a.relu_floor);
-                conv_group<COB, TDT, 2, 0, 0, FULLS - 2, NS - (FULLS - 2), -1>(
-                    acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16, wbase + (int64_t)pf_chunk * (3 * wgstride), wrel,
-                    wv, lane, abp, a.relu_floor);
+            chunk_groups(acc, chunk, tile, next_tile, ht_cur, ht_next);
+            // a chunk has an odd number of columns: what its last column fetched sits in slot 1, and every chunk
+            // starts in slot 0 (two code paths, one per starting slot, cost the compiler a hundred registers)
+            if constexpr (TDT == 8) {
+#pragma unroll
+                for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                    for (int cb = 0; cb < COB; ++cb) fr.a[0][kd][cb] = fr.a[1][kd][cb];
             } else {
-                conv_group<COB, TDT, 0, 0, S0>(acc, hb, w0p, hb_next, w1n, pf, true, hl, ht, pf_off, a.zero16,
-                                               wc + wgstride, wrel, wv, lane);
-                conv_group<COB, TDT, 1, S0, 2>(acc, hb, w1p, hb_next, w0n, pf, true, hl, ht, pf_off, a.zero16,
-                                               wc + 2 * wgstride, wrel, wv, lane);
-                conv_group<COB, TDT, 2, S0 + 2, 2>(acc, hb, w0p, hb_next, w1n, pf, pf, hl, ht, pf_off, a.zero16,
-                                                   wbase + (int64_t)pf_chunk * (3 * wgstride), wrel, wv, lane);
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb) fr.a[0][cb] = fr.a[1][cb];
+#pragma unroll
+                for (int vb = 0; vb < NVB; ++vb) fr.b[0][vb] = fr.b[1][vb];
             }
-            wpar ^= 1;
         }
 
+        // every wave has read its last fragments of the finished chunk's halo before any wave's epilogue writes there
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
         // register group) into voxel rows through a private LDS patch, so that 8 lanes store one
         // full row of 64 channels; the channel sums of the stored values come from the same pass.
