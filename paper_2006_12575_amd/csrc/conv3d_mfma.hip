@@ -337,30 +337,41 @@ __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& h
 
 // Which portion goes where.  The halo of the incoming chunk may be written once every wave is past the barrier of the
 // chunk's group 0 (the previous chunk's halo, whose buffer it takes, is read up to the column before), and must have
-// landed at the barrier of group 2, so its slots go out from the last column of group 0 to the last column of
-// group 1, leaving the youngest ones three columns to land.  COL: column (8-deep tile) or tap (4-deep tile) of the group.
-template <int TDT, bool NORM, int G, int COL> struct Portion {
-    static constexpr int NS = 2 * Geo<TDT>::HJ, FULLS = 2 * (Geo<TDT>::HBLK / 8);
-    static constexpr int LASTC = TDT == 8 ? 2 : 8;                  // the column behind the barrier
-    static constexpr bool WC = COL == LASTC;
-    // copy slots.  Plain: 2 per column over the four columns from (group 0, last) on; 4-deep tile (6 slots): taps
-    // (0, 8), (1, 2), (1, 8).  Normalise on load: everything two columns earlier, so that the rewrite finds it landed.
-    static constexpr int HF = NORM ? (G == 0 && COL == LASTC ? 0 : G == 1 && COL == 0 ? 4 : 0)
-                                   : TDT == 8 ? (G == 0 && COL == 2 ? 0 : G == 1 ? 2 + 2 * COL : 0)
-                                              : (G == 0 && COL == 8 ? 0 : G == 1 && COL == 2 ? 2 : G == 1 && COL == 8 ? 4 : 0);
-    static constexpr int HC = NORM ? (G == 0 && COL == LASTC ? 4 : G == 1 && COL == 0 ? NS - 4 : 0)
-                                   : TDT == 8 ? ((G == 0 && COL == 2) || G == 1 ? 2 : 0)
-                                              : ((G == 0 && COL == 8) || (G == 1 && (COL == 2 || COL == 8)) ? 2 : 0);
-    // rewrite (normalise on load): slots [0, 4) in the first column / tap of group 2 -- younger than they are the
-    // all-wave slots from 4 on and the weight copies of (group 1, last column), of which every wave issues at least
-    // WINSTR / 8 >= 1 -- and the rest in the second column / fourth tap, with everything landed
-    static constexpr int NF = G == 2 && COL == 0 ? 0 : 4;
-    static constexpr int NC = !NORM ? 0 : G == 2 && COL == 0 ? 4 : G == 2 && COL == (TDT == 8 ? 1 : 4) ? NS - 4 : 0;
-    static constexpr int NW = G == 2 && COL == 0 ? (FULLS - 4) + 1 : 0;
-    // copies of a wave that may be in flight at the group's barrier without the next group's weights among them:
-    // group 1: the all-wave halo slots issued behind the weight copies of (group 0, last column)
-    static constexpr int BARRIER_WAIT = G == 1 ? FULLS : 0;
-};
+// landed at the barrier of group 2, so its slots go out between the last column of group 0 and the last column of
+// group 1, leaving the youngest ones three columns to land.  The column in front of a barrier carries nothing: the
+// wave that reaches the barrier last would do that work with the matrix cores idle.
+// COL: column (8-deep tile) or tap (4-deep tile) of the group.
+struct PortionSpec { bool wc; int hf, hc, nf, nc, nw; };
+template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL) {
+    constexpr int NS = 2 * Geo<TDT>::HJ;            // 8 / 6 slots, of which every wave issues the first 6 / 4
+    const int last = TDT == 8 ? 2 : 8;              // the column behind the barrier
+    PortionSpec p{COL == last, 0, 0, 0, 0, 0};
+    if (!NORM) {
+        if (TDT == 8) {
+            if (G == 0 && COL == 2) { p.hf = 0; p.hc = 2; }
+            if (G == 1 && COL == 0) { p.hf = 2; p.hc = 4; }
+            if (G == 1 && COL == 2) { p.hf = 6; p.hc = 2; }
+        } else {
+            if (G == 0 && COL == 8) { p.hf = 0; p.hc = 2; }
+            if (G == 1 && COL == 2) { p.hf = 2; p.hc = 2; }
+            if (G == 1 && COL == 8) { p.hf = 4; p.hc = 2; }
+        }
+    } else {
+        // Normalise on load: the copies go out earlier, and the entries they brought in are rewritten three columns
+        // later.  First rewrite: younger than slot 3 are the all-wave slots from 4 on; second one: the weight copies
+        // that went out with the first, of which every wave issues at least one.
+        if (G == 0 && COL == last) { p.hf = 0; p.hc = 4; }
+        if (G == 1 && COL == 0) { p.hf = 4; p.hc = NS - 4; }
+        if (G == 1 && COL == last) { p.nf = 0; p.nc = 4; p.nw = TDT == 8 ? 2 : 0; }
+        if (G == 2 && COL == (TDT == 8 ? 0 : 2)) { p.nf = 4; p.nc = NS - 4; p.nw = 1; }
+    }
+    return p;
+}
+// Copies of a wave that may be in flight at a group's barrier without the next group's weights among them: at the
+// barrier of group 1, the all-wave halo slots issued behind the weight copies of (group 0, last column).
+template <int TDT, bool NORM> constexpr int barrier_wait(int G) {
+    return G != 1 ? 0 : 2 * (Geo<TDT>::HBLK / 8);   // 6 / 4
+}
 
 // 8-deep tile, one tap column kw = KW of the in-plane row G = kh.  A wave owns 4 d-slices of one (2 h-rows x 16 w)
 // block; the input slice s = d + kd serves the output slices d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6
@@ -373,7 +384,7 @@ __device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f,
                                         const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
                                         const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
     constexpr int WPLANE = 32 * COB * 16;
-    typedef Portion<8, NORM, G, KW> PO;
+    constexpr PortionSpec PO = portion_spec<8, NORM>(G, KW);
     bf16x8 b[6], nb0, nb1;
     b[0] = f.b[0];
     b[1] = f.b[1];
@@ -408,10 +419,10 @@ __device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f,
 #pragma unroll
     for (int sl = 0; sl < 6; ++sl) mul(sl);
     sched_interleave<0, 12 * COB, 6 + 3 * COB>();
-    if constexpr (PO::WC || PO::HC > 0 || PO::NC > 0) {
+    if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
         // behind the column's last matrix instruction, where the fewest fragments are live
         __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 8, PO::WC, PO::HF, PO::HC, PO::NF, PO::NC, PO::NW>(c, hl, ht, wrel);
+        copy_portion<COB, 8, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw>(c, hl, ht, wrel);
         __builtin_amdgcn_sched_barrier(0);
     }
     f.b[0] = nb0;
@@ -426,7 +437,7 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
                                      const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
                                      const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
     constexpr int WPLANE = 32 * COB * 16, NVB = Geo<4>::NVB;
-    typedef Portion<4, NORM, G, T9> PO;
+    constexpr PortionSpec PO = portion_spec<4, NORM>(G, T9);
     if constexpr (T9 < 8) {
         constexpr int kh = (T9 + 1) / 3, kw = (T9 + 1) % 3;
 #pragma unroll
@@ -445,9 +456,9 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
         for (int vb = 0; vb < NVB; ++vb)
             acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][cb], f.b[SLOT][vb], acc[cb][vb], 0, 0, 0);
     sched_interleave<0, NVB * COB, COB + NVB>();
-    if constexpr (PO::WC || PO::HC > 0 || PO::NC > 0) {
+    if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
         __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 4, PO::WC, PO::HF, PO::HC, PO::NF, PO::NC, PO::NW>(c, hl, ht, wrel);
+        copy_portion<COB, 4, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw>(c, hl, ht, wrel);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -459,7 +470,7 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
 // last fragments of this group's weights, and all of the previous chunk's halo.  What is copied in behind the
 // barrier: the weights of the group after next, into the buffer this group has just finished with (the last column
 // fetches the first fragments of the next group from the other weight buffer, filled one group earlier), and
-// the next chunk's halo, into the buffer the previous chunk has left (see Portion).
+// the next chunk's halo, into the buffer the previous chunk has left (see portion_spec).
 //   PAR        : fragment slot of the group's first column (it alternates from column to column)
 //   hbn, wbn   : halo (lane base included) and weights of the group that follows
 // The LDS regions are distinct, and saying so (__restrict__) matters: otherwise the compiler must assume the
@@ -470,7 +481,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Fr
                                            const char* __restrict__ wbn, const CopyCtx& c, const HaloLane& hl,
                                            const HaloTile& ht, const int (&wrel)[3]) {
     constexpr int GN = (G + 1) % 3;
-    constexpr int WAIT = Portion<TDT, NORM, G, 0>::BARRIER_WAIT;
+    constexpr int WAIT = barrier_wait<TDT, NORM>(G);
     if constexpr (TDT == 8) {
         column8<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
         column8<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
@@ -762,49 +773,61 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     }
                 }
         }
+        // element offsets of this lane's rows inside a block (row = voxel index of the 32-voxel block, two h-rows 4 apart)
+        int rowoff[32 / RPI];
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) {
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = prow + i * RPI, rg8 = row >> 3;
+            rowoff[i] = (4 * ((rg8 ^ (rg8 >> 1)) & 1) * a.W + (row & 7) + 8 * (rg8 >> 1)) * ldo;
+        }
+        auto store_blocks = [&](auto FULLC) __attribute__((always_inline)) {
+            constexpr bool FULL = decltype(FULLC)::value;
 #pragma unroll
-            for (int cb = 0; cb < COB; ++cb)
+            for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const uint32_t p0 = pack_bf16(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1]);
-                    const uint32_t p1 = pack_bf16(acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
-                    *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
-                }
-            __builtin_amdgcn_wave_barrier();
+                for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
-                const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
-                const int rg8 = row >> 3;
-                const int rw = (row & 7) + 8 * (rg8 >> 1), rh = 4 * ((rg8 ^ (rg8 >> 1)) & 1);
-                bool ok = true;
-                if (!full) {
-                    const int gd = TDT == 8 ? gd0 + vb : gd0;
-                    const int gh = TDT == 8 ? hb0 + rh : hb0 + vb + rh, gw = w0 + rw;
-                    ok = gd < a.D && gh < a.H && gw < a.W;
-                }
-                if (ok) {
-                    // streaming store: the output is not read again by this kernel and should not displace
-                    // the input lines that the next chunk passes and the neighbouring tiles still need
-                    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-                    const u32x4 sv = {q.x, q.y, q.z, q.w};
-                    bf16_t* dst = tbase + (vb * vbvox + rh * a.W + rw) * ldo;
-                    __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(dst));
-                    if (want_stats) {
-                        const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const uint32_t p0 = pack_bf16(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1]);
+                        const uint32_t p1 = pack_bf16(acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
+                        *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
+                    }
+                __builtin_amdgcn_wave_barrier();
+                bf16_t* const bbase = tbase + (int64_t)vb * vbvox * ldo;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
-                            csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
-                            csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
+                for (int i = 0; i < 32 / RPI; ++i) {
+                    const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
+                    const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
+                    bool ok = true;
+                    if constexpr (!FULL) {
+                        const int rg8 = row >> 3;
+                        const int rw = (row & 7) + 8 * (rg8 >> 1), rh = 4 * ((rg8 ^ (rg8 >> 1)) & 1);
+                        const int gd = TDT == 8 ? gd0 + vb : gd0;
+                        const int gh = TDT == 8 ? hb0 + rh : hb0 + vb + rh, gw = w0 + rw;
+                        ok = gd < a.D && gh < a.H && gw < a.W;
+                    }
+                    if (ok) {
+                        // streaming store: the output is not read again by this kernel and should not displace
+                        // the input lines that the next chunk passes and the neighbouring tiles still need
+                        typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+                        const u32x4 sv = {q.x, q.y, q.z, q.w};
+                        __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(bbase + rowoff[i]));
+                        if (want_stats) {
+                            const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
+                                csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
+                                csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
+                            }
                         }
                     }
                 }
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
-        }
+        };
+        if (full) store_blocks(std::true_type{});
+        else store_blocks(std::false_type{});
         if (a.part) {
             // Lanes with equal `part` hold the same 8 channels.  Inside a row of 16 lanes they are folded by
             // rotations of the row (data-parallel primitives: no LDS traffic, where lane exchanges through the
@@ -827,7 +850,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     dst[2 * e + 1] = csq[e];
                 }
             }
-            __syncthreads();
+            // bare barrier (the LDS writes above are done): __syncthreads() would also wait for the tile's stores
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
             if (tid < WROWS * 2) {
                 const int c = tid >> 1, k = tid & 1;
                 float v = 0.f;
@@ -838,7 +864,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             if (a.counts && tid == 0 && n == 0 && cbi == 0)
                 a.counts[tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
         }
-        __syncthreads();  // the patch buffer is the next stage's prefetch target
+        // No barrier here: the next copies into this buffer go out behind the barrier of the next tile's first group,
+        // which the waves that still read the sums above reach after that.
     }
 }
 
