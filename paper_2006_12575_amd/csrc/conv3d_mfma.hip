@@ -1243,49 +1243,66 @@ struct WgradLane {
     int zpk[4];    // its tile coords
 };
 
-// One tile: copies of the next tile, 16 k-steps (one 16-voxel w-row of the tile each), barrier.
+// Fragment registers that live from one k-step to the next, and from a tile's last k-step to the first of the next tile.
+template <int COB> struct WFrags {
+    bf16x8 af[2][COB];   // dz fragments of a k-step, two slots
+    bf16x8 rb[6];        // x row fragments of the wave's tap column, a ring of six register sets
+    bf16x8 eb[2];        // x fragments of the extra tap (waves 0..2), two slots
+};
+
+// The fragments of k-step 0 of the tile in stage st: dz into slot 0, the first three rows into sets R0, R0+1, R0+2.
+template <int COB, int NT, int R0>
+__device__ __forceinline__ void wgrad_first(WFrags<COB>& f, const char* __restrict__ st, uint32_t coloff, uint32_t extoff, uint32_t loff) {
+    const char* xb = st + loff + coloff;
+#pragma unroll
+    for (int cb = 0; cb < COB; ++cb) f.af[0][cb] = lds_frag_tr(st + WX_BYTES + loff + cb * WDZ_HALF_BYTES);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) f.rb[R0 + r] = lds_frag_tr(xb + (uint32_t)(r * WHW * 64));
+    if constexpr (NT == 4) f.eb[0] = lds_frag_tr(st + loff + extoff);
+}
+
+// One tile: 16 k-steps (one 16-voxel w-row of the tile each), with the copies of the next tile going out one or two
+// per k-step behind the first ones (in one burst they hold the wave up while they queue).
 // A wave owns one tap column (kd, kw) with its three taps kh = 0, 1, 2: at k-step (d, h) they read the x rows
 // h, h+1, h+2 of halo slice d + kd, so from one k-step to the next two of the three row fragments stay in
 // registers and one new row is read (three at the change of d): 20 row fragments per tile feed 48*COB matrix
 // instructions, where a fragment per tap and k-step would be 48.  The ninth column (2, 2) has no wave of its
 // own: waves 0, 1, 2 take one of its taps each (NT == 4), one more row fragment per k-step.
+// Every k-step fetches the fragments of the next one, the last k-step those of the next tile's first: the workgroup's
+// barrier sits before the last k-step, whose operands are in registers by then, so the matrix instructions behind the
+// barrier start at once.  (At that barrier every wave has read the last fragments of this stage, which the copies
+// issued from the next tile on may overwrite, and has seen its own copies of the next tile land.)
 template <int COB, int NT>
-__device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __restrict__ st, char* __restrict__ st_next,
-                                           bool pf, const WgradLane& wl, const bf16_t* xorg, const bf16_t* zorg,
-                                           int dlo, int dhi, int hlo, int hhi, int wlo, int whi, int zd, int zh, int zw,
-                                           const bf16_t* zero16, uint32_t coloff, uint32_t extoff, uint32_t loff, int wv) {
+__device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], WFrags<COB>& f, const char* __restrict__ st,
+                                           char* __restrict__ st_next, bool pf, const WgradLane& wl, const bf16_t* xorg,
+                                           const bf16_t* zorg, int dlo, int dhi, int hlo, int hhi, int wlo, int whi, int zd,
+                                           int zh, int zw, const bf16_t* zero16, uint32_t coloff, uint32_t extoff, uint32_t loff,
+                                           int wv) {
     constexpr int XCOPIES = WX_VOX / 16;            // 45
     constexpr int ZCOPIES = COB * WTILE_VOX / 16;   // 32 or 16
-    if (pf) {
-        // x halo: copy q = wv + 8*i covers halo voxels 16q..16q+15
-#pragma unroll
-        for (int i = 0; i < 6; ++i) {
-            const int q = wv + 8 * i;
-            if (q < XCOPIES) {
-                const int pk = wl.xpk[i];
-                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
-                const bool in = hd >= dlo && hd <= dhi && hh >= hlo && hh <= hhi && hw >= wlo && hw <= whi;
-                g2lds16(in ? xorg + wl.xrel[i] : zero16, st_next + q * 1024);
-            }
+    // copy i of the x halo (q = wv + 8*i covers halo voxels 16q..16q+15) and of dz (half q / 16, voxels 16*(q%16) .. +15)
+    auto copy_x = [&](int i) __attribute__((always_inline)) {
+        const int q = wv + 8 * i;
+        if (q < XCOPIES) {
+            const int pk = wl.xpk[i];
+            const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+            const bool in = hd >= dlo && hd <= dhi && hh >= hlo && hh <= hhi && hw >= wlo && hw <= whi;
+            g2lds16(in ? xorg + wl.xrel[i] : zero16, st_next + q * 1024);
         }
-        // dz: copy q covers half q / 16, voxels 16*(q%16) .. +15
-#pragma unroll
-        for (int i = 0; i < ZCOPIES / 8; ++i) {
-            const int q = wv + 8 * i;
-            const int pk = wl.zpk[i];
-            const int d = pk & 255, h = (pk >> 8) & 255, w = pk >> 16;
-            const bool in = d < zd && h < zh && w < zw;
-            g2lds16(in ? zorg + wl.zrel[i] : zero16, st_next + WX_BYTES + q * 1024);
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    };
+    auto copy_z = [&](int i) __attribute__((always_inline)) {
+        const int q = wv + 8 * i;
+        const int pk = wl.zpk[i];
+        const int d = pk & 255, h = (pk >> 8) & 255, w = pk >> 16;
+        const bool in = d < zd && h < zh && w < zw;
+        g2lds16(in ? zorg + wl.zrel[i] : zero16, st_next + WX_BYTES + q * 1024);
+    };
     const char* xb = st + loff + coloff;
     const char* xe = st + loff + extoff;
     const char* dzb = st + WX_BYTES + loff;
     // Row fragments of the column as one stream q = 10*d + r (r = halo row of slice d + kd); fragment q lives in
     // register set q % 6, which its predecessor q - 6 has left two k-steps earlier.  Everything a k-step needs is
     // read during the k-step before it.
-    bf16x8 af[2][COB], rb[6], eb[2];
     auto row = [&](int q) __attribute__((always_inline)) {
         return lds_frag_tr(xb + (uint32_t)(((q / 10) * WHH + (q % 10)) * WHW * 64));
     };
@@ -1294,46 +1311,55 @@ __device__ __forceinline__ void wgrad_tile(f32x16 (&acc)[COB][4], const char* __
     };
     auto load_a = [&](int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int cb = 0; cb < COB; ++cb) af[slot][cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
+        for (int cb = 0; cb < COB; ++cb) f.af[slot][cb] = lds_frag_tr(dzb + cb * WDZ_HALF_BYTES + ks * 16 * 64);
     };
-    load_a(0, 0);
-    rb[0] = row(0);
-    rb[1] = row(1);
-    rb[2] = row(2);
-    if constexpr (NT == 4) eb[0] = ext(0);
 #pragma unroll
     for (int ks = 0; ks < 16; ++ks) {
         const int q0 = 10 * (ks >> 3) + (ks & 7);
-        if (ks < 15) {
+        if (ks == 15) {
+            // the copies of the next tile have landed, for every wave, and nobody reads this stage any more
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // first fragments of the next tile: k-step 15 multiplies with row sets 5, 0, 1, so the three rows go to
+            // sets 2, 3, 4 and move to 0, 1, 2 behind it
+            wgrad_first<COB, NT, 2>(f, st_next, coloff, extoff, loff);
+        } else {
             load_a(ks + 1, (ks + 1) & 1);
             const int qn = 10 * ((ks + 1) >> 3) + ((ks + 1) & 7);
             if (((ks + 1) & 7) == 0) {   // next slice: three new rows
-                rb[qn % 6] = row(qn);
-                rb[(qn + 1) % 6] = row(qn + 1);
+                f.rb[qn % 6] = row(qn);
+                f.rb[(qn + 1) % 6] = row(qn + 1);
             }
-            rb[(qn + 2) % 6] = row(qn + 2);
-            if constexpr (NT == 4) eb[(ks + 1) & 1] = ext(ks + 1);
+            f.rb[(qn + 2) % 6] = row(qn + 2);
+            if constexpr (NT == 4) f.eb[(ks + 1) & 1] = ext(ks + 1);
         }
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
-                acc[cb][kh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], rb[(q0 + kh) % 6], acc[cb][kh], 0, 0, 0);
+                acc[cb][kh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[ks & 1][cb], f.rb[(q0 + kh) % 6], acc[cb][kh], 0, 0, 0);
         if constexpr (NT == 4) {
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb)
-                acc[cb][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][cb], eb[ks & 1], acc[cb][3], 0, 0, 0);
+                acc[cb][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[ks & 1][cb], f.eb[ks & 1], acc[cb][3], 0, 0, 0);
         }
-        if (ks < 15) {
-            constexpr int NM = NT * COB;   // MFMAs per k-step
-            if (((ks + 1) & 7) == 0) sched_interleave<0, NM, 2 * (COB + 3 + (NT == 4 ? 1 : 0))>();
-            else sched_interleave<0, NM, 2 * (COB + 1 + (NT == 4 ? 1 : 0))>();
+        constexpr int NM = NT * COB;   // MFMAs per k-step
+        if (ks == 15 || ((ks + 1) & 7) == 0) sched_interleave<0, NM, 2 * (COB + 3 + (NT == 4 ? 1 : 0))>();
+        else sched_interleave<0, NM, 2 * (COB + 1 + (NT == 4 ? 1 : 0))>();
+        if (ks < 6) {   // this k-step's share of the next tile's copies: x copies 0..5, dz copies 0..3 (0..1)
+            __builtin_amdgcn_sched_barrier(0);
+            if (pf) {
+                copy_x(ks);
+                if (ks < ZCOPIES / 8) copy_z(ks);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    f.rb[0] = f.rb[2];
+    f.rb[1] = f.rb[3];
+    f.rb[2] = f.rb[4];
 }
 
 template <int COB>
@@ -1394,6 +1420,7 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         h0 = (r / a.tiles_w) * WTH;
     };
 
+    WFrags<COB> fr;
     // one tile's copies + multiply; `cur` selects the LDS stage holding `tile`
     auto run_tile = [&](int tile_to_fetch, bool pf, const char* st, char* st_next) {
         int n, d0, h0, w0;
@@ -1401,10 +1428,10 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
         const bf16_t* xorg = xpart + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
         const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
         if (has4)
-            wgrad_tile<COB, 4>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
+            wgrad_tile<COB, 4>(acc, fr, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
                                a.D - d0, a.H - h0, a.W - w0, a.zero16, coloff, extoff, loff, wv);
         else
-            wgrad_tile<COB, 3>(acc, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
+            wgrad_tile<COB, 3>(acc, fr, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
                                a.D - d0, a.H - h0, a.W - w0, a.zero16, coloff, extoff, loff, wv);
     };
 
@@ -1435,6 +1462,8 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     }
     wait_vmcnt<0>();
     __syncthreads();
+    if (has4) wgrad_first<COB, 4, 0>(fr, lds, coloff, extoff, loff);
+    else wgrad_first<COB, 3, 0>(fr, lds, coloff, extoff, loff);
 
     int par = 0;
     for (int tile = tile_lo; tile < tile_hi; ++tile, par ^= 1) {
