@@ -40,11 +40,13 @@ template <int TDT> struct Geo {
     static constexpr int HALO_BYTES = 2 * PLANE_BYTES;       // one 16-channel chunk
     static constexpr int HBLK = (HALO_VOX + 63) / 64;        // wave-wide copies per halo plane: 29 / 17
     static constexpr int HJ = (HBLK + 7) / 8;                // halo blocks per wave: 4 / 3
-    // epilogue scratch (8 wave patches of 32 rows x 144 bytes + channel sums of the 4 lane rows of each wave): the 8-deep tile reuses
-    // the halo buffer of the finished stage, the 4-deep one is too small for that and gets its own
-    static constexpr int EPI_BYTES = 8 * 32 * 144 + 8 * 4 * 64 * 2 * 4;
-    static constexpr bool EPI_OWN = HALO_BYTES < EPI_BYTES;
-    static constexpr int LDS_BYTES = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? EPI_BYTES : 0);
+    // epilogue scratch: 8 wave patches of 32 rows x 144 bytes (the 8-deep tile reuses the halo buffer of the finished
+    // stage, the 4-deep one is too small for that and gets its own), and the channel sums of each wave (64 channels x
+    // (sum, sum of squares)), which outlive the epilogue (they are added up during the next tile) and have a region of their own
+    static constexpr int PATCH_BYTES = 8 * 32 * 144, SUMS_BYTES = 8 * 64 * 2 * 4;
+    static constexpr bool EPI_OWN = HALO_BYTES < PATCH_BYTES;
+    static constexpr int SUMS_OFF = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? PATCH_BYTES : 0);
+    static constexpr int LDS_BYTES = SUMS_OFF + SUMS_BYTES;
 };
 
 // Two floats to a pair of bf16 (round to nearest even) with the hardware conversion.
@@ -622,6 +624,26 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
 
     int stage = 0;  // parity selects the halo buffer
     int wpar = 0;   // parity selects the weight buffer
+    // Statistics: the tile whose per-wave channel sums wait in LDS to be added up and written (-1: none).  Every wave
+    // writes its sums at the end of the tile's epilogue and goes on; the first 2 * WROWS threads add the 8 waves up
+    // behind the next barrier that every wave has passed with its rows written.
+    int pending_tile = -1;
+    auto flush_sums = [&]() __attribute__((always_inline)) {
+        if (tid < WROWS * 2) {
+            const float* sred = reinterpret_cast<const float*>(lds + GE::SUMS_OFF);
+            const int c = tid >> 1, k = tid & 1;
+            float v = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v += sred[q * 128 + c * 2 + k];
+            a.part[((int64_t)pending_tile * a.Cout + co0 + c) * 2 + k] = v;
+        }
+        if (a.counts && tid == 0 && cbi == 0 && pending_tile < a.tiles_per_n) {
+            int n, d0, h0, w0;
+            tile_origin(pending_tile, n, d0, h0, w0);
+            a.counts[pending_tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
+        }
+        pending_tile = -1;
+    };
     // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
     Frags<COB, TDT> fr;
     load_first<COB, TDT, 0, 0>(fr, hbuf0 + b_base, wbuf0 + a_base);
@@ -654,6 +676,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         }
         cc.wb_fill_a = w0n; cc.pf_w = true; cc.wsrc = wc2;
         conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, cc, hl, ht, wrel);
+        if (pending_tile >= 0) flush_sums();   // every wave is past this group's barrier, its sums of the last tile written
         cc.wb_fill_a = w1n; cc.pf_w = pf; cc.wsrc = wn0;
         conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, cc, hl, ht, wrel);
         cc.wb_fill_a = w0n; cc.wsrc = wn0 + wgstride;
@@ -739,7 +762,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
         constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
         char* patch = fbuf + wv * (32 * ROWB);
-        float* sred = reinterpret_cast<float*>(fbuf + 8 * 32 * (64 * 2 + 16));
+        float* sred = reinterpret_cast<float*>(lds + GE::SUMS_OFF);
         // The lane id enters the epilogue through an opaque copy: what is derived from it below would otherwise
         // be hoisted out of the tile loop and stay in registers across the multiply loop, which has none to spare.
         int lane_e = lane;
@@ -794,10 +817,11 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     }
                 __builtin_amdgcn_wave_barrier();
                 bf16_t* const bbase = tbase + (int64_t)vb * vbvox * ldo;
+                uint4 qv[32 / RPI];
 #pragma unroll
                 for (int i = 0; i < 32 / RPI; ++i) {
                     const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
-                    const uint4 q = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
+                    qv[i] = *reinterpret_cast<const uint4*>(patch + row * ROWB + part * 16);
                     bool ok = true;
                     if constexpr (!FULL) {
                         const int rg8 = row >> 3;
@@ -810,16 +834,31 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                         // streaming store: the output is not read again by this kernel and should not displace
                         // the input lines that the next chunk passes and the neighbouring tiles still need
                         typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-                        const u32x4 sv = {q.x, q.y, q.z, q.w};
+                        const u32x4 sv = {qv[i].x, qv[i].y, qv[i].z, qv[i].w};
                         __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(bbase + rowoff[i]));
-                        if (want_stats) {
-                            const uint32_t r4[4] = {q.x, q.y, q.z, q.w};
+                    } else {
+                        qv[i] = make_uint4(0u, 0u, 0u, 0u);   // outside the volume: nothing stored, nothing summed
+                    }
+                }
+                if (want_stats) {
+                    // Sums of the stored (rounded) values, two voxels at a time: a byte permute puts the same channel
+                    // of two voxels side by side, and one two-element dot product with (1, 1), one with the pair
+                    // itself, add both voxels to the channel's sum and sum of squares (1.5 instead of 3 vector
+                    // instructions per value).
+                    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+                    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3F803F80u);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float f0 = __uint_as_float(r4[e] << 16), f1 = __uint_as_float(r4[e] & 0xFFFF0000u);
-                                csum[2 * e] += f0; csq[2 * e] = fmaf(f0, f0, csq[2 * e]);
-                                csum[2 * e + 1] += f1; csq[2 * e + 1] = fmaf(f1, f1, csq[2 * e + 1]);
-                            }
+                    for (int i = 0; i < 32 / RPI; i += 2) {
+                        const uint32_t ra[4] = {qv[i].x, qv[i].y, qv[i].z, qv[i].w};
+                        const uint32_t rb[4] = {qv[i + 1].x, qv[i + 1].y, qv[i + 1].z, qv[i + 1].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bf16x2 lo = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(rb[e], ra[e], 0x05040100u));
+                            const bf16x2 hi = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(rb[e], ra[e], 0x07060302u));
+                            csum[2 * e] = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, csum[2 * e], false);
+                            csq[2 * e] = __builtin_amdgcn_fdot2_f32_bf16(lo, lo, csq[2 * e], false);
+                            csum[2 * e + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, csum[2 * e + 1], false);
+                            csq[2 * e + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, hi, csq[2 * e + 1], false);
                         }
                     }
                 }
@@ -842,30 +881,34 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     csq[e] += row_ror<4>(csq[e]);
                 }
             }
+            // the wave's four lane rows meet in its own patch (free again), one (channel, sum kind) pair per lane and turn
+            float* wrow = reinterpret_cast<float*>(patch);
             if ((lane_e & 15) < PARTS) {   // then part == lane & 15
-                float* dst = sred + ((wv * 4 + (lane_e >> 4)) * 64 + part * 8) * 2;
+                float* dst = wrow + ((lane_e >> 4) * 64 + part * 8) * 2;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     dst[2 * e + 0] = csum[e];
                     dst[2 * e + 1] = csq[e];
                 }
             }
-            // bare barrier (the LDS writes above are done): __syncthreads() would also wait for the tile's stores
-            __builtin_amdgcn_s_waitcnt(0xC07F);
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            if (tid < WROWS * 2) {
-                const int c = tid >> 1, k = tid & 1;
-                float v = 0.f;
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int q = 0; q < 32; ++q) v += sred[(q * 64 + c) * 2 + k];
-                a.part[(((int64_t)n * a.tiles_per_n + (tile - n * a.tiles_per_n)) * a.Cout + co0 + c) * 2 + k] = v;
+            for (int t = 0; t < WROWS * 2 / 64; ++t) {
+                const int ck = lane_e + 64 * t;
+                sred[wv * 128 + ck] = (wrow[ck] + wrow[128 + ck]) + (wrow[256 + ck] + wrow[384 + ck]);
             }
-            if (a.counts && tid == 0 && n == 0 && cbi == 0)
-                a.counts[tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
+            // No barrier: the sums are added up and written behind the first barrier of the next tile (after the
+            // last tile: behind a barrier of their own), which every wave reaches with its rows written.
+            pending_tile = tile;
         }
-        // No barrier here: the next copies into this buffer go out behind the barrier of the next tile's first group,
-        // which the waves that still read the sums above reach after that.
+        // No barrier here: the next copies into the patch buffer go out behind the barrier of the next tile's first
+        // group.
+    }
+    if (pending_tile >= 0) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        flush_sums();
     }
 }
 
