@@ -10,8 +10,10 @@
 // Tile: 8 x 8 x 16 output voxels (d,h,w); 8 waves (2 per SIMD); a wave owns 4 d-slices of one
 // (2 h-rows x 16 w) patch = 4 blocks of 32 voxels, so a 16-lane group always reads 16 consecutive
 // halo voxels and an input slice fragment serves up to three output slices (kd = 0, 1, 2).
-// LDS holds a halo chunk as two planes (channels 0-7 / 8-15 of the chunk) of 16-byte voxel
-// entries: every fragment read is a conflict-free 16-byte load at lane base + immediate offset.
+// LDS holds a halo chunk as 32-byte voxel entries (the two 16-byte halves = channels 0-7 / 8-15 of the chunk, in
+// swapped order where bit 3 of the halo w coordinate is set): a copy instruction fetches both halves of 32 voxels,
+// so two lanes share every line they touch, and every fragment read is a conflict-free 16-byte load at a lane base
+// (one per tap column kw) plus an immediate offset.
 // Two halo buffers (10 x 10 x 18 voxels) let the next chunk / next tile stream in while the
 // current one is multiplied; two weight buffers hold one tap group (9 taps x 64 co x 16 ci) each.
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
@@ -36,17 +38,19 @@ template <int TDT> struct Geo {
     static constexpr int TD = TDT, HD = TDT + 2;
     static constexpr int HSPLIT = 8 / TDT, NVB = 4 / HSPLIT;
     static constexpr int HALO_VOX = HD * HH * HW;            // 1800 / 1080
-    static constexpr int PLANE_BYTES = HALO_VOX * 16;        // 8 channels per voxel entry
-    static constexpr int HALO_BYTES = 2 * PLANE_BYTES;       // one 16-channel chunk
-    static constexpr int HBLK = (HALO_VOX + 63) / 64;        // wave-wide copies per halo plane: 29 / 17
-    static constexpr int HJ = (HBLK + 7) / 8;                // halo blocks per wave: 4 / 3
+    static constexpr int HALO_BYTES = HALO_VOX * 32;         // one 16-channel chunk, 32 bytes per voxel entry
+    static constexpr int HBLK = (HALO_VOX + 31) / 32;        // wave-wide copies per halo chunk (32 voxels each): 57 / 34
+    static constexpr int HJ = (HBLK + 7) / 8;                // copy slots per wave (slot j = block wv + 8*j): 8 / 5
+    static constexpr int ALLW = (HALO_VOX / 32) / 8;         // slots that every wave issues, in full: 7 / 4
     // epilogue scratch: 8 wave patches of 32 rows x 144 bytes (the 8-deep tile reuses the halo buffer of the finished
     // stage, the 4-deep one is too small for that and gets its own), and the channel sums of each wave (64 channels x
     // (sum, sum of squares)), which outlive the epilogue (they are added up during the next tile) and have a region of their own
     static constexpr int PATCH_BYTES = 8 * 32 * 144, SUMS_BYTES = 8 * 64 * 2 * 4;
     static constexpr bool EPI_OWN = HALO_BYTES < PATCH_BYTES;
     static constexpr int SUMS_OFF = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? PATCH_BYTES : 0);
-    static constexpr int LDS_BYTES = SUMS_OFF + SUMS_BYTES;
+    // normalise on load: the (a, b) pairs of the incoming chunk's 16 channels
+    static constexpr int TAB_OFF = SUMS_OFF + SUMS_BYTES, TAB_BYTES = 128;
+    static constexpr int LDS_BYTES = TAB_OFF + TAB_BYTES;
 };
 
 // Two floats to a pair of bf16 (round to nearest even) with the hardware conversion.
@@ -173,12 +177,21 @@ template <int K, int NM, int NR> __device__ __forceinline__ void sched_interleav
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 
-// Per-lane constants of the halo copies.  A wave copies halo blocks wv, wv+8, wv+16, wv+24 (64
-// voxels each, both planes back to back so the two 16-byte halves of a voxel's 32 bytes meet in
-// the L1): rel = element offset of the voxel from the tile's halo origin, pk = its halo coords.
+// Per-lane constants of the halo copies.  A wave copies halo blocks wv, wv + 8, ... (32 voxels each; lanes 2i and
+// 2i + 1 fetch the two 16-byte halves of voxel i's 32 bytes, in the order the LDS entry stores them): pk = the halo
+// coords of the lane's voxel and which half (plane) of the chunk's channels it fetches, d | h << 4 | w << 8 | plane << 13,
+// two slots to a register (slot j in the low or high half of pk[j / 2]).
 struct HaloLane {
-    int rel[4];
     int pk[4];
+    int rel[8];   // element offset of the lane's 16 bytes from the tile's halo origin (kernels with registers to spare)
+    template <bool LEAN> __device__ __forceinline__ void coords(int j, int& hd, int& hh, int& hw, int& plane) const {
+        int v = (j & 1) ? pk[j >> 1] >> 16 : pk[j >> 1];
+        // LEAN (the 64-channel kernel of the 8-deep tile, which has no register to spare): opaque, because what is
+        // derived from the coordinates (the voxel's offset in the tensor) is cheap to recompute at every use, where
+        // the compiler would rather compute all of it once and keep it in registers it has not got
+        if constexpr (LEAN) asm volatile("" : "+v"(v));
+        hd = v & 15; hh = (v >> 4) & 15; hw = (v >> 8) & 31; plane = (v >> 13) & 1;
+    }
 };
 // Per-tile constants of the halo copies.
 struct HaloTile {
@@ -187,46 +200,39 @@ struct HaloTile {
 };
 
 // Normalise + ReLU on load: the halo copies are register-free, so the transform is a read-modify-write pass over
-// the chunk once it has landed in LDS.  Every lane rewrites the 16-byte entries (8 channels of one voxel) that
+// the chunk once it has landed in LDS.  Every lane rewrites the 16-byte pieces (8 channels of one voxel) that
 // its own copies brought in -- it knows whether each came from the volume or from the zero source, and the zero
 // padding applies AFTER the transform, so padding entries are written back as literal zeros.  The arithmetic is
 // the one of the stand-alone pass (fma, max, round to nearest even), so what the matrix cores read is bit for
-// bit the activated tensor that pass would have stored.  abp: the (a, b) pairs of this chunk's 16 channels
-// (wave-uniform: scalar loads).
+// bit the activated tensor that pass would have stored.  tab: the (a, b) pairs of this chunk's 16 channels in LDS
+// (a lane's half of the channels depends on its voxel).
 template <int TDT, int FIRST, int CNT>
 __device__ __forceinline__ void halo_norm(char* __restrict__ hb, const HaloLane& hl, const HaloTile& ht,
-                                          const float2* __restrict__ abp, float relu_floor, int wv, int lane) {
+                                          const char* __restrict__ tab, float relu_floor, int wv, int lane) {
     typedef Geo<TDT> GE;
 #pragma unroll
-    for (int sl = FIRST; sl < FIRST + CNT; ++sl) {
-        const int j = sl >> 1, plane = sl & 1;
+    for (int j = FIRST; j < FIRST + CNT; ++j) {
         const int blk = wv + 8 * j;
-        const int pk = hl.pk[j];
-        const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
+        int hd, hh, hw, plane;
+        hl.template coords<true>(j, hd, hh, hw, plane);
         const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
-        // Slots that every wave copies in full (j < HBLK / 8) are rewritten by straight-line code, which the
-        // scheduler can spread between the matrix instructions of the group; an entry from outside the volume is
-        // written back as it came (zeros: the zero padding applies after the transform).  The last block's slots
-        // exist for some waves and lanes only.
-        const bool mine = j < GE::HBLK / 8 || (blk < GE::HBLK && blk * 64 + lane < GE::HALO_VOX);
+        // Slots that every wave copies in full are rewritten by straight-line code; an entry from outside the volume
+        // is written back as it came (zeros: the zero padding applies after the transform).  The last slots exist
+        // for some waves and lanes only.
+        const bool mine = j < GE::ALLW || (blk < GE::HBLK && blk * 32 + (lane >> 1) < GE::HALO_VOX);
         if (mine) {
-            uint4* p = reinterpret_cast<uint4*>(hb + plane * GE::PLANE_BYTES + blk * 1024 + lane * 16);
+            uint4* p = reinterpret_cast<uint4*>(hb + blk * 1024 + lane * 16);
             const uint4 q = *p;
             const uint32_t r[4] = {q.x, q.y, q.z, q.w};
             uint32_t o[4];
-            // the coefficients are the same for every lane: read through the scalar cache (a table no kernel
-            // writes while this one runs), 64 bytes per slot
-            typedef __attribute__((address_space(4))) const float cfloat;
-            const uint64_t ua = (uint64_t)(uintptr_t)(abp + plane * 8);
-            const uint32_t ulo = __builtin_amdgcn_readfirstlane((uint32_t)ua), uhi = __builtin_amdgcn_readfirstlane((uint32_t)(ua >> 32));
-            cfloat* cab = (cfloat*)(uintptr_t)(((uint64_t)uhi << 32) | ulo);   // (a, b) pairs of 8 channels
+            const float4* cab = reinterpret_cast<const float4*>(tab + plane * 64);   // (a, b) pairs of the lane's 8 channels
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float2 c0 = make_float2(cab[4 * e], cab[4 * e + 1]), c1 = make_float2(cab[4 * e + 2], cab[4 * e + 3]);
+                const float4 c = cab[e];
                 // max(u, floor): for u = -0 the sign of the zero may differ from the stand-alone pass, which
                 // the matrix cores cannot see (both are zero)
-                const float u0 = fmaxf(fmaf(__uint_as_float(r[e] << 16), c0.x, c0.y), relu_floor);
-                const float u1 = fmaxf(fmaf(__uint_as_float(r[e] & 0xFFFF0000u), c1.x, c1.y), relu_floor);
+                const float u0 = fmaxf(fmaf(__uint_as_float(r[e] << 16), c.x, c.y), relu_floor);
+                const float u1 = fmaxf(fmaf(__uint_as_float(r[e] & 0xFFFF0000u), c.z, c.w), relu_floor);
                 o[e] = in ? pack_bf16(u0, u1) : r[e];
             }
             *p = make_uint4(o[0], o[1], o[2], o[3]);
@@ -262,20 +268,22 @@ template <int COB> struct Frags<COB, 4> {
 
 // The fragments of the first column (8-deep tile) / first tap (4-deep tile) of group G, into slot SLOT.
 template <int COB, int TDT, int G, int SLOT>
-__device__ __forceinline__ void load_first(Frags<COB, TDT>& f, const char* __restrict__ hb, const char* __restrict__ wb) {
+__device__ __forceinline__ void load_first(Frags<COB, TDT>& f, const char* __restrict__ hbu, const char* __restrict__ wb,
+                                           const uint32_t (&boff)[3]) {
     constexpr int WPLANE = 32 * COB * 16;
+    const char* hb = hbu + boff[0];
     if constexpr (TDT == 8) {
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb) f.a[SLOT][kd][cb] = lds_frag(wb + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
-        f.b[0] = lds_frag(hb + ((0 * HH + G) * HW) * 16);
-        f.b[1] = lds_frag(hb + ((1 * HH + G) * HW) * 16);
+        f.b[0] = lds_frag(hb + ((0 * HH + G) * HW) * 32);
+        f.b[1] = lds_frag(hb + ((1 * HH + G) * HW) * 32);
     } else {
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) f.a[SLOT][cb] = lds_frag(wb + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < Geo<4>::NVB; ++vb) f.b[SLOT][vb] = lds_frag(hb + (G * HH * HW) * 16 + vb * HW * 16);
+        for (int vb = 0; vb < Geo<4>::NVB; ++vb) f.b[SLOT][vb] = lds_frag(hb + (G * HH * HW) * 32 + vb * HW * 32);
     }
 }
 
@@ -288,18 +296,37 @@ struct CopyCtx {
     int64_t pf_choff;       // element offset of the incoming chunk's channels
     const bf16_t* zero16;
     const bf16_t* wsrc;     // weights of the group after next
-    const float2* abp;      // normalise on load: (a, b) pairs of the incoming chunk's channels
+    const float2* abp;      // normalise on load: (a, b) pairs of the incoming chunk's channels (global memory)
+    const char* tab;        // ... and where they go in LDS
+    uint32_t tab_a;
     float relu_floor;
+    int H, W, ldx;          // strides of the input tensor
     int wv, lane;
 };
+
+// One halo copy slot: 32 voxels, both halves of their 32 bytes (lanes 2i, 2i + 1 = voxel i).
+template <int TDT, bool LEAN>
+__device__ __forceinline__ void halo_copy_slot(int j, const HaloLane& hl, const HaloTile& ht, int H, int W, int ldx, int64_t choff,
+                                               const bf16_t* zero16, uint32_t hb_a, int wv, int lane) {
+    typedef Geo<TDT> GE;
+    const int blk = wv + 8 * j;
+    if (blk < GE::HBLK && blk * 32 + (lane >> 1) < GE::HALO_VOX) {
+        int hd, hh, hw, plane;
+        hl.template coords<LEAN>(j, hd, hh, hw, plane);
+        const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+        const int rel = LEAN ? ((hd * H + hh) * W + hw) * ldx + plane * 8 : hl.rel[j];
+        const bf16_t* src = in ? ht.origin + rel + choff : zero16;
+        g2lds16a(src, hb_a + blk * 1024);
+    }
+}
 
 // One portion of a stage's copy work, placed in the middle of a column's matrix instructions (the global -> LDS
 // copies of a wave queue up behind each other: issued in one burst they hold up the wave, and with it the
 // workgroup's next barrier, for thousands of cycles; a few per column never fill the queue):
 //   WC          : the weight copies of the group after next
-//   HF, HC      : halo copy slots [HF, HF + HC) of the incoming chunk (slot = block j * 2 + plane)
+//   HF, HC      : halo copy slots [HF, HF + HC) of the incoming chunk (slot j = block wv + 8*j of 32 voxels)
 //   NF, NC, NW  : normalise on load: rewrite slots [NF, NF + NC) once at most NW of this wave's copies are in flight
-template <int COB, int TDT, bool WC, int HF, int HC, int NF, int NC, int NW>
+template <int COB, int TDT, bool WC, int HF, int HC, int NF, int NC, int NW, bool TABC>
 __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
     typedef Geo<TDT> GE;
     constexpr int WINSTR = 18 * 32 * COB / 64;
@@ -307,8 +334,13 @@ __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& h
     if constexpr (NC > 0) {
         if (c.pf_halo) {
             wait_vmcnt<NW>();
-            halo_norm<TDT, NF, NC>(c.hb_next, hl, ht, c.abp, c.relu_floor, c.wv, c.lane);
+            halo_norm<TDT, NF, NC>(c.hb_next, hl, ht, c.tab, c.relu_floor, c.wv, c.lane);
         }
+    }
+    if constexpr (TABC) {
+        // normalise on load: the incoming chunk's 16 (a, b) pairs, 128 bytes, older than every copy whose landing is
+        // counted (wave 0, lanes 0..7)
+        if (c.pf_halo && c.wv == 0 && c.lane < 8) g2lds16a(reinterpret_cast<const char*>(c.abp) + c.lane * 16, c.tab_a);
     }
     if constexpr (WC) {
         if (c.pf_w) {
@@ -322,17 +354,8 @@ __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& h
     if constexpr (HC > 0) {
         if (c.pf_halo) {
 #pragma unroll
-            for (int sl = HF; sl < HF + HC; ++sl) {
-                const int j = sl >> 1, plane = sl & 1;
-                const int blk = c.wv + 8 * j;
-                if (blk < GE::HBLK && blk * 64 + c.lane < GE::HALO_VOX) {
-                    const int pk = hl.pk[j];
-                    const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
-                    const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
-                    const bf16_t* src = in ? ht.origin + hl.rel[j] + c.pf_choff + plane * 8 : c.zero16;
-                    g2lds16a(src, c.hb_next_a + plane * GE::PLANE_BYTES + blk * 1024);
-                }
-            }
+            for (int j = HF; j < HF + HC; ++j)
+                halo_copy_slot<TDT, (COB == 2 && TDT == 8)>(j, hl, ht, c.H, c.W, c.ldx, c.pf_choff, c.zero16, c.hb_next_a, c.wv, c.lane);
         }
     }
 }
@@ -343,11 +366,11 @@ __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& h
 // group 1, leaving the youngest ones three columns to land.  The column in front of a barrier carries nothing: the
 // wave that reaches the barrier last would do that work with the matrix cores idle.
 // COL: column (8-deep tile) or tap (4-deep tile) of the group.
-struct PortionSpec { bool wc; int hf, hc, nf, nc, nw; };
+struct PortionSpec { bool wc; int hf, hc, nf, nc, nw; bool tab; };
 template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL) {
-    constexpr int NS = 2 * Geo<TDT>::HJ;            // 8 / 6 slots, of which every wave issues the first 6 / 4
+    constexpr int NS = Geo<TDT>::HJ, ALLW = Geo<TDT>::ALLW;   // 8 / 5 slots, of which every wave issues the first 7 / 4
     const int last = TDT == 8 ? 2 : 8;              // the column behind the barrier
-    PortionSpec p{COL == last, 0, 0, 0, 0, 0};
+    PortionSpec p{COL == last, 0, 0, 0, 0, 0, false};
     if (!NORM) {
         if (TDT == 8) {
             if (G == 0 && COL == 2) { p.hf = 0; p.hc = 2; }
@@ -356,15 +379,16 @@ template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL)
         } else {
             if (G == 0 && COL == 8) { p.hf = 0; p.hc = 2; }
             if (G == 1 && COL == 2) { p.hf = 2; p.hc = 2; }
-            if (G == 1 && COL == 8) { p.hf = 4; p.hc = 2; }
+            if (G == 1 && COL == 8) { p.hf = 4; p.hc = 1; }
         }
     } else {
         // Normalise on load: the copies go out earlier, and the entries they brought in are rewritten three columns
         // later.  First rewrite: younger than slot 3 are the all-wave slots from 4 on; second one: the weight copies
-        // that went out with the first, of which every wave issues at least one.
-        if (G == 0 && COL == last) { p.hf = 0; p.hc = 4; }
+        // that went out with the first, of which every wave issues at least one.  The coefficient table goes out with
+        // the first slots, ahead of the weight copies.
+        if (G == 0 && COL == last) { p.hf = 0; p.hc = 4; p.tab = true; }
         if (G == 1 && COL == 0) { p.hf = 4; p.hc = NS - 4; }
-        if (G == 1 && COL == last) { p.nf = 0; p.nc = 4; p.nw = TDT == 8 ? 2 : 0; }
+        if (G == 1 && COL == last) { p.nf = 0; p.nc = 4; p.nw = ALLW - 4; }
         if (G == 2 && COL == (TDT == 8 ? 0 : 2)) { p.nf = 4; p.nc = NS - 4; p.nw = 1; }
     }
     return p;
@@ -372,7 +396,7 @@ template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL)
 // Copies of a wave that may be in flight at a group's barrier without the next group's weights among them: at the
 // barrier of group 1, the all-wave halo slots issued behind the weight copies of (group 0, last column).
 template <int TDT, bool NORM> constexpr int barrier_wait(int G) {
-    return G != 1 ? 0 : 2 * (Geo<TDT>::HBLK / 8);   // 6 / 4
+    return G != 1 ? 0 : NORM ? Geo<TDT>::ALLW : TDT == 8 ? 6 : 4;
 }
 
 // 8-deep tile, one tap column kw = KW of the in-plane row G = kh.  A wave owns 4 d-slices of one (2 h-rows x 16 w)
@@ -382,30 +406,35 @@ template <int TDT, bool NORM> constexpr int barrier_wait(int G) {
 // follows, whose weights sit in wbn and whose halo is hbn.  The column's portion of the copy work follows its matrix
 // instructions.
 template <int COB, int G, int KW, int SLOT, int GN, bool NORM>
-__device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f, const char* __restrict__ hb,
-                                        const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
-                                        const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+__device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f, const char* __restrict__ hbu,
+                                        const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
+                                        const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
+                                        const int (&wrel)[3]) {
     constexpr int WPLANE = 32 * COB * 16;
+    // lane bases of this tap column and of the one fetched ahead (the half of a voxel's entry that holds the lane's
+    // channels depends on the voxel's w coordinate, and with it on kw)
+    const char* hb = hbu + boff[KW];
+    const char* hbx = KW < 2 ? hbu + boff[KW + 1] : hbnu + boff[0];
     constexpr PortionSpec PO = portion_spec<8, NORM>(G, KW);
     bf16x8 b[6], nb0, nb1;
     b[0] = f.b[0];
     b[1] = f.b[1];
 #pragma unroll
-    for (int sl = 2; sl < 6; ++sl) b[sl] = lds_frag(hb + ((sl * HH + G) * HW + KW) * 16);
+    for (int sl = 2; sl < 6; ++sl) b[sl] = lds_frag(hb + ((sl * HH + G) * HW) * 32);
     if constexpr (KW < 2) {
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][kd][cb] = lds_frag(wb + (kd * 3 + KW + 1) * 2 * WPLANE + cb * 32 * 16);
-        nb0 = lds_frag(hb + ((0 * HH + G) * HW + KW + 1) * 16);
-        nb1 = lds_frag(hb + ((1 * HH + G) * HW + KW + 1) * 16);
+        nb0 = lds_frag(hbx + ((0 * HH + G) * HW) * 32);
+        nb1 = lds_frag(hbx + ((1 * HH + G) * HW) * 32);
     } else {
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
             for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][kd][cb] = lds_frag(wbn + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
-        nb0 = lds_frag(hbn + ((0 * HH + GN) * HW) * 16);
-        nb1 = lds_frag(hbn + ((1 * HH + GN) * HW) * 16);
+        nb0 = lds_frag(hbx + ((0 * HH + GN) * HW) * 32);
+        nb1 = lds_frag(hbx + ((1 * HH + GN) * HW) * 32);
     }
     auto mul = [&](int sl) __attribute__((always_inline)) {
 #pragma unroll
@@ -424,7 +453,7 @@ __device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f,
     if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
         // behind the column's last matrix instruction, where the fewest fragments are live
         __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 8, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw>(c, hl, ht, wrel);
+        copy_portion<COB, 8, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw, PO.tab>(c, hl, ht, wrel);
         __builtin_amdgcn_sched_barrier(0);
     }
     f.b[0] = nb0;
@@ -435,9 +464,10 @@ __device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f,
 // the next tap (T9 == 8: of the first tap of the group GN that follows) are fetched meanwhile.  The tap's portion of
 // the copy work follows its matrix instructions.
 template <int COB, int G, int T9, int SLOT, int GN, bool NORM>
-__device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB, 4>& f, const char* __restrict__ hb,
-                                     const char* __restrict__ wb, const char* __restrict__ hbn, const char* __restrict__ wbn,
-                                     const CopyCtx& c, const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+__device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB, 4>& f, const char* __restrict__ hbu,
+                                     const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
+                                     const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
+                                     const int (&wrel)[3]) {
     constexpr int WPLANE = 32 * COB * 16, NVB = Geo<4>::NVB;
     constexpr PortionSpec PO = portion_spec<4, NORM>(G, T9);
     if constexpr (T9 < 8) {
@@ -445,12 +475,12 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wb + (T9 + 1) * 2 * WPLANE + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hb + ((G * HH + kh) * HW + kw) * 16 + vb * HW * 16);
+        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbu + boff[kw] + ((G * HH + kh) * HW) * 32 + vb * HW * 32);
     } else {
 #pragma unroll
         for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wbn + cb * 32 * 16);
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbn + (GN * HH * HW) * 16 + vb * HW * 16);
+        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbnu + boff[0] + (GN * HH * HW) * 32 + vb * HW * 32);
     }
 #pragma unroll
     for (int cb = 0; cb < COB; ++cb)
@@ -460,7 +490,7 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
     sched_interleave<0, NVB * COB, COB + NVB>();
     if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
         __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 4, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw>(c, hl, ht, wrel);
+        copy_portion<COB, 4, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw, PO.tab>(c, hl, ht, wrel);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -474,28 +504,29 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
 // fetches the first fragments of the next group from the other weight buffer, filled one group earlier), and
 // the next chunk's halo, into the buffer the previous chunk has left (see portion_spec).
 //   PAR        : fragment slot of the group's first column (it alternates from column to column)
-//   hbn, wbn   : halo (lane base included) and weights of the group that follows
+//   hb, hbn    : halo buffers of this group and of the group that follows (boff: lane bases per tap column kw)
+//   wb, wbn    : their weights (lane base included)
 // The LDS regions are distinct, and saying so (__restrict__) matters: otherwise the compiler must assume the
 // fragment reads alias the in-flight copies and waits for them before the first read.
 template <int COB, int TDT, int G, int PAR, bool NORM>
 __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Frags<COB, TDT>& f, const char* __restrict__ hb,
                                            const char* __restrict__ wb, const char* __restrict__ hbn,
-                                           const char* __restrict__ wbn, const CopyCtx& c, const HaloLane& hl,
-                                           const HaloTile& ht, const int (&wrel)[3]) {
+                                           const char* __restrict__ wbn, const uint32_t (&boff)[3], const CopyCtx& c,
+                                           const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
     constexpr int GN = (G + 1) % 3;
     constexpr int WAIT = barrier_wait<TDT, NORM>(G);
     if constexpr (TDT == 8) {
-        column8<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        column8<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        column8<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        column8<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
     } else {
-        tap4<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 3, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 4, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 5, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 6, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-        tap4<COB, G, 7, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+        tap4<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 3, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 4, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 5, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 6, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+        tap4<COB, G, 7, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
     }
     // The weights of the next group were copied behind the previous barrier; the only younger copies are halo slots,
     // of which every wave has issued WAIT (a wave that issued more waits for its oldest ones too).
@@ -505,8 +536,8 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Fr
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if constexpr (TDT == 8) column8<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
-    else tap4<COB, G, 8, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, c, hl, ht, wrel);
+    if constexpr (TDT == 8) column8<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+    else tap4<COB, G, 8, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
 }
 
 // SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
@@ -515,13 +546,13 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Fr
 template <int COB, int TDT, bool SPLIT = false, bool NORM = false>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
-    constexpr int TD = GE::TD, NVB = GE::NVB, HBLK = GE::HBLK, HALO_VOX = GE::HALO_VOX, PLANE_BYTES = GE::PLANE_BYTES,
-                  HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
+    constexpr int TD = GE::TD, NVB = GE::NVB, HALO_VOX = GE::HALO_VOX, HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* hbuf0 = lds;
     char* wbuf0 = lds + 2 * HALO_BYTES;
     // LDS byte addresses of the two, for the register-free copies
     const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds, wbuf_a = lds_a + 2 * HALO_BYTES;
+    const uint32_t tab_a = lds_a + GE::TAB_OFF;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int cbi = a.cb_inner ? (int)(blockIdx.x >> 3) % a.cb_inner : (int)blockIdx.y;   // output-channel block
@@ -544,37 +575,47 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     const int tile_lo = xcd * a.tiles_per_xcd;
     const int tile_hi = min(tile_lo + a.tiles_per_xcd, a.tiles_total);
 
-    // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read runs at full rate
-    // (measured: 4 cycles per wave instead of 8) when the 8-lane groups {0-7,24-31} and {8-15,16-23}
-    // (and the same in the upper half) fall into opposite 128-byte halves of the bank space AND all
-    // four groups start at the same offset modulo 128 bytes.  Groups of 8 lanes take (row0,w0-7)
-    // (row1,w0-7) (row1,w8-15) (row0,w8-15), and the two rows of a block are h and h+4: their distance,
-    // 4 halo rows of 288 bytes, is 128 modulo 256, where adjacent rows would differ by 32 modulo 128.
+    // ---- lane -> voxel of a 32-voxel block (2 h-rows x 16 w).  A 16-byte LDS read runs at full rate when the 16
+    // lanes served together -- the 8-lane groups {0-7,24-31}, then {8-15,16-23}, and the same in the upper half --
+    // hit 16 different 16-byte bank groups (a micro-benchmark of the patterns decides).  Groups of 8 lanes take
+    // (row0,w0-7) (row1,w0-7) (row1,w8-15) (row0,w8-15), so the lanes served together read 16 consecutive voxels of
+    // one halo row, 32 bytes apart: voxels w and w + 8 would meet in a bank group, which is why the two halves of an
+    // entry are stored in swapped order where bit 3 of the halo w coordinate is set.  The two rows of a block are h
+    // and h + 4 (4 halo rows of 576 bytes = 0 modulo 256; with adjacent rows the read takes a third longer).
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
     // this wave's part of the tile.  4-deep tile: d-slice ds, h-row pairs (2*hs + vb, 2*hs + vb + 4) for the
     // two blocks vb.  8-deep tile: d-slices 4*ds .. 4*ds+3 (one block each) of the h-row pair (hs, hs + 4).
     const int ds = TDT == 8 ? (wv & 1) : wv % TDT, hs = TDT == 8 ? (wv >> 1) : wv / TDT;
-    const uint32_t b_base = TDT == 8 ? (uint32_t)(half * PLANE_BYTES + ((4 * ds * HH + hs + 4 * bh) * HW + bw) * 16)
-                                     : (uint32_t)(half * PLANE_BYTES + ((ds * HH + hs * NVB + 4 * bh) * HW + bw) * 16);
+    // lane base per tap column kw: the entry of voxel (.., bw + kw) and, in it, the half that holds this lane's
+    // channels (lanes 0-31: channels 0-7 of the chunk, lanes 32-63: 8-15)
+    uint32_t boff[3];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+        const int vox = TDT == 8 ? (4 * ds * HH + hs + 4 * bh) * HW + bw + kw : (ds * HH + hs * NVB + 4 * bh) * HW + bw + kw;
+        boff[kw] = (uint32_t)(vox * 32 + 16 * (half ^ (((bw + kw) >> 3) & 1)));
+    }
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
 
     // ---- per-lane constants of the register-free global -> LDS copies
     HaloLane hl;
 #pragma unroll
+    for (int j = 0; j < 4; ++j) hl.pk[j] = 0;
+#pragma unroll
     for (int j = 0; j < HJ; ++j) {
-        int hv = (wv + 8 * j) * 64 + lane;
+        int hv = (wv + 8 * j) * 32 + (lane >> 1);
         if (hv >= HALO_VOX) hv = 0;
         const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
-        hl.rel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx;
-        hl.pk[j] = hd | (hh << 8) | (hw << 16);
+        const int plane = (lane & 1) ^ ((hw >> 3) & 1);
+        hl.pk[j >> 1] |= (hd | (hh << 4) | (hw << 8) | (plane << 13)) << (16 * (j & 1));
+        hl.rel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx + plane * 8;
     }
     // weight copy q = wv + 8*i of a group: 64 consecutive (entry,row) pairs, entry = tap9*2 + plane.  The
     // repacked weights are the LDS image itself, [co block][chunk][group][entry][row][8]: every copy reads 1 KB
     // of consecutive memory
     int wrel[3];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) wrel[i] = ((wv + 8 * i) * 64 + lane) * 8;
+    for (int i = 0; i < 3; ++i) wrel[i] = ((wv + 8 * i) * 64 + lane) * 8;   // (kept as wrel[0] + i * 4096 by the compiler)
     auto tile_origin = [&](int tile, int& n, int& d0, int& h0, int& w0) {
         n = tile / a.tiles_per_n;
         int r = tile - n * a.tiles_per_n;
@@ -601,14 +642,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     {
         const HaloTile t0 = halo_tile(tile);
 #pragma unroll
-        for (int sl = 0; sl < 2 * HJ; ++sl) {
-            const int j = sl >> 1, plane = sl & 1, blk = wv + 8 * j;
-            if (blk < HBLK && blk * 64 + lane < HALO_VOX) {
-                const int pk = hl.pk[j];
-                const int hd = pk & 255, hh = (pk >> 8) & 255, hw = pk >> 16;
-                const bool in = hd >= t0.dlo && hd <= t0.dhi && hh >= t0.hlo && hh <= t0.hhi && hw >= t0.wlo && hw <= t0.whi;
-                g2lds16a(in ? t0.origin + hl.rel[j] + choff(c_lo) + plane * 8 : a.zero16, lds_a + plane * PLANE_BYTES + blk * 1024);
-            }
+        for (int j = 0; j < HJ; ++j) halo_copy_slot<TDT, (COB == 2 && TDT == 8)>(j, hl, t0, a.H, a.W, a.ldx, choff(c_lo), a.zero16, lds_a, wv, lane);
+        if constexpr (NORM) {
+            if (wv == 0 && lane < 8)
+                g2lds16a(reinterpret_cast<const char*>(a.ab + (int64_t)(tile / a.tiles_per_n) * a.Cin + c_lo * 16) + lane * 16, tab_a);
         }
 #pragma unroll
         for (int g = 0; g < 2; ++g)
@@ -617,8 +654,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 if (wv + 8 * i < WINSTR)
                     g2lds16a(wbase + (int64_t)c_lo * (3 * wgstride) + g * wgstride + wrel[i], wbuf_a + g * WBUF_BYTES + (wv + 8 * i) * 1024);
         wait_vmcnt<0>();
-        if constexpr (NORM)
-            halo_norm<TDT, 0, 2 * HJ>(hbuf0, hl, t0, a.ab + (int64_t)(tile / a.tiles_per_n) * a.Cin + c_lo * 16, a.relu_floor, wv, lane);
+        if constexpr (NORM) {
+            __syncthreads();   // the coefficient table (wave 0's copy) is there for every wave
+            halo_norm<TDT, 0, HJ>(hbuf0, hl, t0, lds + GE::TAB_OFF, a.relu_floor, wv, lane);
+        }
         __syncthreads();
     }
 
@@ -646,15 +685,15 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     };
     // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
     Frags<COB, TDT> fr;
-    load_first<COB, TDT, 0, 0>(fr, hbuf0 + b_base, wbuf0 + a_base);
+    load_first<COB, TDT, 0, 0>(fr, hbuf0, wbuf0 + a_base, boff);
     // One 16-channel chunk = three tap groups; P = fragment slot of its first column (a group has an odd number of
     // columns / taps, so the slot alternates from group to group).
     auto chunk_groups = [&](f32x16 (&acc)[COB][NVB], int chunk, int tile, int next_tile, const HaloTile& ht_cur,
                             const HaloTile& ht_next) __attribute__((always_inline)) {
         constexpr int P = 0;
-        const char* hb = hbuf0 + (stage & 1) * HALO_BYTES + b_base;
+        const char* hb = hbuf0 + (stage & 1) * HALO_BYTES;
         char* hb_next = hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
-        const char* hbn = hb_next + b_base;
+        const char* hbn = hb_next;
         // what streams in during this stage: the next chunk of this tile, or chunk 0 of the next
         const bool last_chunk = chunk + 1 == c_hi;
         const int pf_chunk = last_chunk ? c_lo : chunk + 1;
@@ -670,17 +709,18 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         CopyCtx cc;
         cc.hb_next = hb_next; cc.hb_next_a = hb_next_a; cc.pf_halo = pf; cc.pf_choff = choff(pf_chunk); cc.zero16 = a.zero16;
         cc.abp = nullptr; cc.relu_floor = a.relu_floor; cc.wv = wv; cc.lane = lane;
+        cc.tab = lds + GE::TAB_OFF; cc.tab_a = tab_a; cc.H = a.H; cc.W = a.W; cc.ldx = a.ldx;
         if constexpr (NORM) {
             const int n_pf = (last_chunk && next_tile < tile_hi ? next_tile : tile) / a.tiles_per_n;
             cc.abp = a.ab + (int64_t)n_pf * a.Cin + pf_chunk * 16;
         }
         cc.wb_fill_a = w0n; cc.pf_w = true; cc.wsrc = wc2;
-        conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, cc, hl, ht, wrel);
+        conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, boff, cc, hl, ht, wrel);
         if (pending_tile >= 0) flush_sums();   // every wave is past this group's barrier, its sums of the last tile written
         cc.wb_fill_a = w1n; cc.pf_w = pf; cc.wsrc = wn0;
-        conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, cc, hl, ht, wrel);
+        conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, boff, cc, hl, ht, wrel);
         cc.wb_fill_a = w0n; cc.wsrc = wn0 + wgstride;
-        conv_group<COB, TDT, 2, P, NORM>(acc, fr, hb, w0p, hbn, w1p, cc, hl, ht, wrel);
+        conv_group<COB, TDT, 2, P, NORM>(acc, fr, hb, w0p, hbn, w1p, boff, cc, hl, ht, wrel);
         wpar ^= 1;
     };
     for (; tile < tile_hi; tile += wg_per_xcd) {
