@@ -40,6 +40,8 @@
  *       materialise_concat=1  the network entry points keep one concat buffer per decoder level
  *       no_norm_on_load=1     the network entry points write every activated tensor instead of normalising
  *                             a block's first conv output while the second conv loads it
+ *       no_bsum=1             lamp_conv3d_dgrad_inorm_relu_bwd runs its two steps as separate passes (the sums of
+ *                             the backward from a reduction pass instead of the data gradient's epilogue)
  */
 #ifndef LAMP_H
 #define LAMP_H
@@ -127,6 +129,25 @@ size_t lamp_conv3d_dgrad_workspace_bytes(const lamp_tensor_desc *dzd, const lamp
 lamp_status lamp_conv3d_dgrad(const lamp_tensor_desc *dzd, const void *dz, const void *w,
                               const lamp_tensor_desc *dxd, void *dx,
                               void *ws, size_t ws_bytes, void *stream);
+
+/* Data gradient of a conv followed by the InstanceNorm + ReLU backward of the layer below it -- the step from the
+ * second conv of a U-Net block to its first (Sec. 2.2; B_k of Sec. 2.1 through two layers):
+ *   g  = data gradient of the conv, as lamp_conv3d_dgrad(dz, w)        -> g  (described by gd)
+ *   dzb = InstanceNorm + ReLU backward of g, as lamp_inorm_relu_bwd(g, z, stats, gamma, beta) -> dzb (described by dzbd)
+ * z, stats, gamma, beta: raw conv output, statistics and affine parameters of the layer below, whose activated
+ * output was the conv's input in the forward (z has g's n,d,h,w,c).  dzb may be g itself (in place).  dgamma,
+ * dbeta, beta_acc as in lamp_inorm_relu_bwd.  On the matrix-core path (bf16, channel counts the tiled kernel takes,
+ * z with g's channel stride) the two sums of the backward are taken in the data gradient's epilogue, from the values
+ * it stores, and the separate reduction pass over (g, z) is not run; otherwise the two calls above run one after the
+ * other.  Either way the results are those of the two calls up to the summation order of the two sums. */
+size_t lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes(const lamp_tensor_desc *dzd, const lamp_tensor_desc *gd);
+lamp_status lamp_conv3d_dgrad_inorm_relu_bwd(const lamp_tensor_desc *dzd, const void *dz, const void *w,
+                                             const lamp_tensor_desc *gd, void *g,
+                                             const lamp_tensor_desc *zd, const void *z, const float *stats,
+                                             const float *gamma, const float *beta,
+                                             const lamp_tensor_desc *dzbd, void *dzb,
+                                             float *dgamma, float *dbeta, float beta_acc,
+                                             void *ws, size_t ws_bytes, void *stream);
 
 /* Weight gradient, always fp32:
  *   dW[co,kd,kh,kw,ci] = beta*dW + sum_{n,d,h,w} dz[n,d,h,w,co] * X[n,d+kd-1,h+kh-1,w+kw-1,ci]

@@ -57,6 +57,9 @@ _SIGS = {
     "lamp_conv3d_fwd": (c_int, [_PD, _VP, _PN, _VP, _VP, _PD, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_conv3d_dgrad_workspace_bytes": (c_size_t, [_PD, _PD]),
     "lamp_conv3d_dgrad": (c_int, [_PD, _VP, _VP, _PD, _VP, _VP, c_size_t, _VP]),
+    "lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes": (c_size_t, [_PD, _PD]),
+    "lamp_conv3d_dgrad_inorm_relu_bwd": (c_int, [_PD, _VP, _VP, _PD, _VP, _PD, _VP, _VP, _VP, _VP, _PD, _VP, _VP, _VP, c_float,
+                                                  _VP, c_size_t, _VP]),
     "lamp_conv3d_wgrad_workspace_bytes": (c_size_t, [_PD, _PD]),
     "lamp_conv3d_wgrad": (c_int, [_PD, _VP, _PN, _PD, _VP, _VP, _VP, c_float, _VP, c_size_t, _VP]),
     "lamp_inorm_relu_workspace_bytes": (c_size_t, [_PD]),
@@ -216,6 +219,19 @@ def lamp_conv3d_dgrad(dz, w, dx, ws=None):
     _check(lib().lamp_conv3d_dgrad(ctypes.byref(dzd), _ptr(dz), _ptr(w), ctypes.byref(dxd), _ptr(dx), _ptr(ws), ws.numel(),
                                    _stream()), "lamp_conv3d_dgrad")
     return dx
+
+
+def lamp_conv3d_dgrad_inorm_relu_bwd(dz, w, g, z, stats, dzb, gamma=None, beta=None, dgamma=None, dbeta=None, beta_acc=0.0, ws=None):
+    """g = data gradient of the conv (dz, w); dzb = InstanceNorm + ReLU backward of g through the layer below (z, stats);
+    dzb may be g."""
+    dzd, gd, zd, dzbd = desc(dz), desc(g), desc(z), desc(dzb)
+    need = lib().lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes(ctypes.byref(dzd), ctypes.byref(gd))
+    ws = ws if ws is not None else _ws(need, dz.device)
+    _check(lib().lamp_conv3d_dgrad_inorm_relu_bwd(ctypes.byref(dzd), _ptr(dz), _ptr(w), ctypes.byref(gd), _ptr(g), ctypes.byref(zd),
+                                                  _ptr(z), _ptr(stats), _ptr(gamma), _ptr(beta), ctypes.byref(dzbd), _ptr(dzb),
+                                                  _ptr(dgamma), _ptr(dbeta), beta_acc, _ptr(ws), ws.numel(), _stream()),
+           "lamp_conv3d_dgrad_inorm_relu_bwd")
+    return dzb
 
 
 def lamp_conv3d_wgrad(x, dz, dw, dbias=None, beta=0.0, xnorm=None, ws=None):

@@ -852,6 +852,47 @@ extern "C" lamp_status lamp_conv3d_dgrad(const lamp_tensor_desc* dzd, const void
     return launch_direct<true>(dzd, dz, make_norm(nullptr), w, nullptr, dxd, dx, s);
 }
 
+extern "C" size_t lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes(const lamp_tensor_desc* dzd, const lamp_tensor_desc* gd) {
+    if (!desc_ok(dzd) || !desc_ok(gd)) return 0;
+    size_t b = lamp_conv3d_dgrad_workspace_bytes(dzd, gd);
+    const size_t nb = lamp_inorm_relu_bwd_workspace_bytes(gd);
+    if (nb > b) b = nb;
+    if (mfma_conv_supported(dzd, gd, nullptr, nullptr)) {
+        const size_t f = mfma_bsum_ws_bytes(dzd, gd) + align_up((size_t)gd->n * gd->c * 2 * sizeof(float));
+        if (f > b) b = f;
+    }
+    return b;
+}
+
+extern "C" lamp_status lamp_conv3d_dgrad_inorm_relu_bwd(const lamp_tensor_desc* dzd, const void* dz, const void* w,
+                                                        const lamp_tensor_desc* gd, void* g, const lamp_tensor_desc* zd,
+                                                        const void* z, const float* stats, const float* gamma,
+                                                        const float* beta, const lamp_tensor_desc* dzbd, void* dzb,
+                                                        float* dgamma, float* dbeta, float beta_acc, void* ws,
+                                                        size_t ws_bytes, void* stream) {
+    lamp_status st = check_conv_pair(dzd, dz, gd, g);
+    if (st != LAMP_OK) return st;
+    if (!w || !zd || !z || !stats || !dzbd || !dzb) return LAMP_ERR_NULL;
+    if (!desc_ok(zd) || !desc_ok(dzbd) || !same_space(gd, zd) || !same_space(gd, dzbd) || zd->c != gd->c || dzbd->c != gd->c)
+        return LAMP_ERR_SHAPE;
+    if (zd->dtype != gd->dtype || dzbd->dtype != gd->dtype) return LAMP_ERR_DTYPE;
+    if (beta_acc != 0.f && beta_acc != 1.f) return LAMP_ERR_SHAPE;
+    if (!ws || ws_bytes < lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes(dzd, gd)) return LAMP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (mfma_bsum_supported(dzd, gd) && zd->ldc == gd->ldc && !(((uintptr_t)z) & 15u)) {
+        // the sums at the tail of the workspace, the data gradient's own workspace in front of them
+        const size_t cb = mfma_bsum_ws_bytes(dzd, gd);
+        float* sums = (float*)((char*)ws + cb);
+        ConvBsum bs{z, stats, gamma, beta, sums};
+        st = mfma_conv_fwd(dzd, dz, w, true, gd, g, nullptr, 0.f, ws, cb, s, nullptr, nullptr, nullptr, &bs);
+        if (st != LAMP_OK) return st;
+        return launch_inorm_bwd_apply(gd, g, zd, z, stats, gamma, beta, sums, dzbd, dzb, dgamma, dbeta, beta_acc, s);
+    }
+    st = lamp_conv3d_dgrad(dzd, dz, w, gd, g, ws, ws_bytes, stream);
+    if (st != LAMP_OK) return st;
+    return lamp_inorm_relu_bwd(gd, g, zd, z, stats, gamma, beta, dzbd, dzb, dgamma, dbeta, beta_acc, ws, ws_bytes, stream);
+}
+
 extern "C" size_t lamp_conv3d_wgrad_workspace_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
     if (!desc_ok(xd) || !desc_ok(dzd)) return 0;
     const int64_t O = (int64_t)dzd->c * 27 * xd->c;

@@ -128,6 +128,12 @@ struct ConvArgs {
     // u = a*x + b, a = gamma*rstd, b = beta - mean*a; relu_floor = 0 (ReLU) or -inf (none).
     const float2* ab;
     float relu_floor;
+    // Data gradient with the two sums of the InstanceNorm + ReLU backward of the layer below (BSUM instantiations):
+    // zb = that layer's raw conv output z, whose activation u = a*z + b (zab: the (a, b) pairs per (sample, channel))
+    // fed this conv in the forward -- the voxels, channels and channel stride of the tensor written here.  With
+    // g = [u > 0] * dx (dx = the value stored, after rounding) the per-tile partials hold (sum g, sum g*z).
+    const bf16_t* zb;
+    const float2* zab;
     int N, D, H, W, Cin, Cout;
     int tiles_d, tiles_h, tiles_w, tiles_per_n, tiles_total, tiles_per_xcd;
     float* zpart;       // split reduction only: [splits][N*D*H*W][Cout] fp32 partial outputs
@@ -543,7 +549,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Fr
 // SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
 // writes its fp32 partial sums; a second kernel adds them in a fixed order.  For small volumes with
 // many channels, where the tiles alone cannot fill the chip.
-template <int COB, int TDT, bool SPLIT = false, bool NORM = false>
+template <int COB, int TDT, bool SPLIT = false, bool NORM = false, bool BSUM = false>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
     constexpr int TD = GE::TD, NVB = GE::NVB, HALO_VOX = GE::HALO_VOX, HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
@@ -821,6 +827,19 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         bf16_t* const tbase = (second ? a.z2 + (ch - a.zsplit) : a.z + ch) +
                               ((((int64_t)n * a.D + gd0) * a.H + hb0) * a.W + w0) * ldo;
         const int vbvox = TDT == 8 ? a.H * a.W : a.W;   // voxels from block vb to vb + 1 (offsets inside a tile fit 32 bits)
+        // BSUM: the matching piece of the layer below's z (same offsets: same shape and channel stride), and this
+        // lane's 8 (a, b) pairs
+        const bf16_t* zbase = nullptr;
+        float za[8], zbb[8];
+        if constexpr (BSUM) {
+            zbase = a.zb + ch + ((((int64_t)n * a.D + gd0) * a.H + hb0) * a.W + w0) * ldo;
+            const float4* t = reinterpret_cast<const float4*>(a.zab + (int64_t)n * a.Cout + ch);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float4 v = t[e];
+                za[2 * e] = v.x; zbb[2 * e] = v.y; za[2 * e + 1] = v.z; zbb[2 * e + 1] = v.w;
+            }
+        }
         const bool full = gd0 + (TDT == 8 ? NVB : 1) <= a.D && h0 + TH <= a.H && w0 + TW <= a.W;
         const bool want_stats = a.part != nullptr;
         if (a.bias) {   // fp32 bias on the accumulators: what is rounded, stored and summed is z + b
@@ -858,6 +877,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 __builtin_amdgcn_wave_barrier();
                 bf16_t* const bbase = tbase + (int64_t)vb * vbvox * ldo;
                 uint4 qv[32 / RPI];
+                uint4 zv[BSUM ? 32 / RPI : 1];
 #pragma unroll
                 for (int i = 0; i < 32 / RPI; ++i) {
                     const int row = prow + i * RPI;          // voxel index inside the 32-voxel block
@@ -876,10 +896,27 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                         typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
                         const u32x4 sv = {qv[i].x, qv[i].y, qv[i].z, qv[i].w};
                         __builtin_nontemporal_store(sv, reinterpret_cast<u32x4*>(bbase + rowoff[i]));
+                        if constexpr (BSUM) zv[i] = *reinterpret_cast<const uint4*>(zbase + (int64_t)vb * vbvox * ldo + rowoff[i]);
                     } else {
                         qv[i] = make_uint4(0u, 0u, 0u, 0u);   // outside the volume: nothing stored, nothing summed
+                        if constexpr (BSUM) zv[i] = make_uint4(0u, 0u, 0u, 0u);
                     }
                 }
+                if constexpr (BSUM) {
+                    // sums of the InstanceNorm + ReLU backward below: g = [u > 0] * (stored value), (sum g, sum g*z)
+#pragma unroll
+                    for (int i = 0; i < 32 / RPI; ++i) {
+                        const uint32_t r4[4] = {qv[i].x, qv[i].y, qv[i].z, qv[i].w}, z4[4] = {zv[i].x, zv[i].y, zv[i].z, zv[i].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float z0 = __uint_as_float(z4[e] << 16), z1 = __uint_as_float(z4[e] & 0xFFFF0000u);
+                            const float g0 = norm_u(z0, za[2 * e], zbb[2 * e]) > 0.f ? __uint_as_float(r4[e] << 16) : 0.f;
+                            const float g1 = norm_u(z1, za[2 * e + 1], zbb[2 * e + 1]) > 0.f ? __uint_as_float(r4[e] & 0xFFFF0000u) : 0.f;
+                            csum[2 * e] += g0; csq[2 * e] = fmaf(g0, z0, csq[2 * e]);
+                            csum[2 * e + 1] += g1; csq[2 * e + 1] = fmaf(g1, z1, csq[2 * e + 1]);
+                        }
+                    }
+                } else
                 if (want_stats) {
                     // Sums of the stored (rounded) values, two voxels at a time: a byte permute puts the same channel
                     // of two voxels side by side, and one two-element dot product with (1, 1), one with the pair
@@ -1154,21 +1191,34 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     return b + ab_bytes;
 }
 
-template <int COB, int TDT, bool SPLIT = false, bool NORM = false>
+template <int COB, int TDT, bool SPLIT = false, bool NORM = false, bool BSUM = false>
 static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
     const int shm = Geo<TDT>::LDS_BYTES;
-    if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT, NORM>, shm) != LAMP_OK) return LAMP_ERR_HIP;
-    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT, NORM>), grid, dim3(512), shm, s, a);
+    if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT, NORM, BSUM>, shm) != LAMP_OK) return LAMP_ERR_HIP;
+    hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT, NORM, BSUM>), grid, dim3(512), shm, s, a);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
 
+// The data gradient can carry the sums of the InstanceNorm backward below it where it runs on the plain tiled kernel
+// and writes one tensor: no packed batch of tiny volumes, no input-channel split.
+bool mfma_bsum_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    if (tune("no_bsum", 0) || !mfma_conv_supported(xd, zd, nullptr, nullptr)) return false;
+    PackPlan pp;
+    return !conv_pack_plan(zd, pp) && conv_splits(xd, zd) == 1;
+}
+size_t mfma_bsum_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
+    return mfma_conv_ws_bytes(xd, zd, 1) + align_up((size_t)zd->n * zd->c * sizeof(float2));
+}
+
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps, void* ws, size_t ws_bytes,
-                          hipStream_t s, const ConvParts* parts, const float* bias, const lamp_norm_in* xnorm) {
+                          hipStream_t s, const ConvParts* parts, const float* bias, const lamp_norm_in* xnorm,
+                          const ConvBsum* bsum) {
     const bool two_in = parts && parts->x2, two_out = parts && parts->z2;
     const bool norm = xnorm && xnorm->mean_rstd && xnorm->c_norm > 0;
     if (norm && (two_in || !mfma_conv_supported(xd, zd, xnorm, bias))) return LAMP_ERR_UNSUPPORTED;
+    if (bsum && (two_out || norm || stats_out || !mfma_bsum_supported(xd, zd) || (((uintptr_t)bsum->z) & 15u))) return LAMP_ERR_UNSUPPORTED;
     if (two_in && ((((uintptr_t)parts->x2) & 15u) || parts->x_c1 % 16 || parts->x_c1 <= 0 || parts->x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
     if (two_out && ((((uintptr_t)parts->z2) & 15u) || parts->z_c1 % 32 || parts->z_c1 <= 0 || parts->z_c1 >= zd->c || parts->ldz2 % 8))
         return LAMP_ERR_ALIGN;
@@ -1209,7 +1259,16 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     }
     float2* ab = nullptr;
     if (norm) ab = (float2*)cv.take((size_t)xd->n * xd->c * sizeof(float2));
+    if (bsum) {   // per-tile partial sums, and the (a, b) table of the layer below (over this launch's output channels)
+        part = (float*)cv.take((size_t)zd->n * tiles_per_n * zd->c * 2 * sizeof(float));
+        ab = (float2*)cv.take((size_t)zd->n * zd->c * sizeof(float2));
+    }
     if (!cv.ok()) return LAMP_ERR_WORKSPACE;
+    if (bsum) {
+        lamp_norm_in nb{bsum->stats, bsum->gamma, bsum->beta, zd->c, 1};
+        hipLaunchKernelGGL(norm_coeff_kernel, dim3(cdiv((int64_t)zd->n * zd->c, 256)), dim3(256), 0, s, make_norm(&nb), zd->n, zd->c, ab);
+        LAMP_CHECK_LAUNCH();
+    }
     if (norm) {
         hipLaunchKernelGGL(norm_coeff_kernel, dim3(cdiv((int64_t)xd->n * xd->c, 256)), dim3(256), 0, s, make_norm(xnorm), xd->n, xd->c, ab);
         LAMP_CHECK_LAUNCH();
@@ -1226,7 +1285,9 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.wp = wp; a.z = (bf16_t*)z; a.ldz = zd->ldc; a.part = part; a.counts = counts;
     a.zero16 = wp + (size_t)27 * xd->c * zd->c;
     a.bias = bias;
-    a.ab = ab;
+    a.ab = norm ? ab : nullptr;
+    a.zb = bsum ? (const bf16_t*)bsum->z : nullptr;
+    a.zab = bsum ? ab : nullptr;
     a.relu_floor = norm && !xnorm->relu ? -__builtin_inff() : 0.f;
     a.N = zd->n; a.D = zd->d; a.H = zd->h; a.W = zd->w; a.Cin = xd->c; a.Cout = zd->c;
     a.tiles_d = td; a.tiles_h = th; a.tiles_w = tw; a.tiles_per_n = tiles_per_n;
@@ -1262,6 +1323,12 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         grid.y = 1;
     }
     lamp_status st;
+    if (bsum) {
+        if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8, false, false, true>(a, grid, s) : launch_igemm<1, 8, false, false, true>(a, grid, s);
+        else st = cob == 2 ? launch_igemm<2, 4, false, false, true>(a, grid, s) : launch_igemm<1, 4, false, false, true>(a, grid, s);
+        if (st != LAMP_OK) return st;
+        return launch_bsum_finalize(part, tiles_per_n, zd->n, zd->c, bsum->stats, bsum->sums_out, s);
+    }
     if (norm) {
         if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8, false, true>(a, grid, s) : launch_igemm<1, 8, false, true>(a, grid, s);
         else st = cob == 2 ? launch_igemm<2, 4, false, true>(a, grid, s) : launch_igemm<1, 4, false, true>(a, grid, s);

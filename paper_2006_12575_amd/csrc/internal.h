@@ -26,6 +26,14 @@ lamp_status launch_stats(const lamp_tensor_desc* zd, const void* z, float eps, f
 lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
                                   float eps, float* stats, hipStream_t s, bool counts_per_sample = false);
 
+// Per-tile partials (sum g, sum g*z) of a data-gradient epilogue to sums[N][C][2] = (sum g, sum g*zhat); fp64, fixed order.
+lamp_status launch_bsum_finalize(const float* partial, int parts, int N, int C, const float* zstats, float* sums, hipStream_t s);
+// The element-wise half of the InstanceNorm + ReLU backward for given sums[N][C][2] (and dgamma / dbeta from them).
+lamp_status launch_inorm_bwd_apply(const lamp_tensor_desc* dyd, const void* dy, const lamp_tensor_desc* zd, const void* z,
+                                   const float* stats, const float* gamma, const float* beta, const float* sums,
+                                   const lamp_tensor_desc* dzd, void* dz, float* dgamma, float* dbeta, float beta_acc,
+                                   hipStream_t s);
+
 // ---- reduce.hip -----------------------------------------------------------------------------
 // out[o] = beta*out[o] + sum_s part[s][o], s in fixed order, fp64 accumulation.
 // ---- repacked conv weights prepared ahead of the calls that use them (network entry points) ----
@@ -75,10 +83,16 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 // receiving the output channels from z_c1 on (channel stride ldz2, z_c1 % 32 == 0).  With parts the
 // tiled kernel is used whatever the shape.
 struct ConvParts { const void* x2; int x_c1; void* z2; int z_c1, ldz2; };
+// Data gradient that also takes the two sums of the InstanceNorm + ReLU backward of the layer below: z = that layer's
+// raw conv output (voxels, channels and channel stride of the tensor the data gradient writes), stats / gamma / beta
+// its statistics and affine parameters, sums_out [N][C][2] = (sum g, sum g*zhat) with g = [u > 0] * dx.
+struct ConvBsum { const void* z; const float* stats; const float* gamma; const float* beta; float* sums_out; };
+bool mfma_bsum_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
+size_t mfma_bsum_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd);
 lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void* w, bool dgrad,
                           const lamp_tensor_desc* zd, void* z, float* stats_out, float eps,
                           void* ws, size_t ws_bytes, hipStream_t s, const ConvParts* parts = nullptr,
-                          const float* bias = nullptr, const lamp_norm_in* xnorm = nullptr);
+                          const float* bias = nullptr, const lamp_norm_in* xnorm = nullptr, const ConvBsum* bsum = nullptr);
 bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, const lamp_norm_in* xnorm);
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd);
 lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_tensor_desc* dzd, const void* dz,

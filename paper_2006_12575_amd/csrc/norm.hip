@@ -370,8 +370,10 @@ __global__ __launch_bounds__(256) void inorm_bwd_partial_kernel(const T* __restr
 
 // sums[n][c][2] = (sum g, sum g*zh) over all parts, fp64, fixed order (strided per thread with four
 // parts in flight, then a fixed tree over lanes and waves).
+// zstats != nullptr: the second partial sum is over g*z (raw z, from the data-gradient epilogue) and is turned into
+// the sum over g*zhat here, in fp64: rstd * (sum g*z - mean * sum g).
 __global__ __launch_bounds__(256) void inorm_bwd_finalize_kernel(const float* __restrict__ partial, int parts, int C,
-                                                                 float* __restrict__ sums) {
+                                                                 float* __restrict__ sums, const float* __restrict__ zstats) {
     __shared__ double sh[4][2];
     const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float2* pp = reinterpret_cast<const float2*>(partial) + (size_t)n * parts * C + c;
@@ -397,6 +399,7 @@ __global__ __launch_bounds__(256) void inorm_bwd_finalize_kernel(const float* __
     __syncthreads();
     if (tid == 0) {
         for (int w = 1; w < 4; ++w) { s += sh[w][0]; q += sh[w][1]; }
+        if (zstats) q = (double)zstats[((size_t)n * C + c) * 2 + 1] * (q - (double)zstats[((size_t)n * C + c) * 2 + 0] * s);
         sums[((size_t)n * C + c) * 2 + 0] = (float)s;
         sums[((size_t)n * C + c) * 2 + 1] = (float)q;
     }
@@ -542,8 +545,24 @@ extern "C" lamp_status lamp_inorm_relu_bwd(const lamp_tensor_desc* dyd, const vo
                            stats, gamma, beta, partial);
     });
     LAMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(zd->c, zd->n), dim3(256), 0, s, partial, chunks, zd->c, sums);
+    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(zd->c, zd->n), dim3(256), 0, s, partial, chunks, zd->c, sums,
+                       (const float*)nullptr);
     LAMP_CHECK_LAUNCH();
+    return launch_inorm_bwd_apply(dyd, dy, zd, z, stats, gamma, beta, sums, dzd, dz, dgamma, dbeta, beta_acc, s);
+}
+
+lamp_status lamp::launch_bsum_finalize(const float* partial, int parts, int N, int C, const float* zstats, float* sums, hipStream_t s) {
+    hipLaunchKernelGGL(inorm_bwd_finalize_kernel, dim3(C, N), dim3(256), 0, s, partial, parts, C, sums, zstats);
+    LAMP_CHECK_LAUNCH();
+    return LAMP_OK;
+}
+
+lamp_status lamp::launch_inorm_bwd_apply(const lamp_tensor_desc* dyd, const void* dy, const lamp_tensor_desc* zd, const void* z,
+                                   const float* stats, const float* gamma, const float* beta, const float* sums,
+                                   const lamp_tensor_desc* dzd, void* dz, float* dgamma, float* dbeta, float beta_acc,
+                                   hipStream_t s) {
+    const int64_t V = (int64_t)zd->d * zd->h * zd->w;
+    const int vec = pick_vec(zd->dtype, zd->c, {zd->ldc, dyd->ldc, dzd->ldc}, {z, dy, dz});
     if (dgamma || dbeta) {
         hipLaunchKernelGGL(inorm_dgb_kernel, dim3(cdiv(zd->c, 64)), dim3(64), 0, s, sums, zd->n, zd->c, dgamma, dbeta,
                            beta_acc);

@@ -64,7 +64,7 @@ static size_t block_scratch(const Net& nt, int l, int Cin, int Cout, bool bwd) {
     if (bwd) {
         size_t c[] = {lamp_conv3d_wgrad_workspace_bytes(&xi, &xo), lamp_conv3d_wgrad_workspace_bytes(&xo, &xo),
                       lamp_conv3d_dgrad_workspace_bytes(&xo, &xi), lamp_conv3d_dgrad_workspace_bytes(&xo, &xo),
-                      lamp_inorm_relu_bwd_workspace_bytes(&xo)};
+                      lamp_inorm_relu_bwd_workspace_bytes(&xo), lamp_conv3d_dgrad_inorm_relu_bwd_workspace_bytes(&xo, &xo)};
         for (size_t v : c) m = v > m ? v : m;
     }
     if (nt.u->se_ratio) {
@@ -150,13 +150,20 @@ static lamp_status block_bwd(Net& nt, int l, int Cin, int ldx, const void* x, in
         if (st != LAMP_OK) return st;
         st = lamp_conv3d_wgrad(&y1, c1.y, nullptr, &zd, g, G[pi + pc], nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
         if (st != LAMP_OK) return st;
-        st = lamp_conv3d_dgrad(&zd, g, P[pi + pc], &zd, gtmp, nt.scratch, nt.scratch_bytes, nt.s);
+        // the data gradient of the second conv and the InstanceNorm + ReLU backward of the first as one call: the
+        // sums of the latter come out of the former's epilogue
+        st = lamp_conv3d_dgrad_inorm_relu_bwd(&zd, g, P[pi + pc], &zd, gtmp, &zd, c1.z, c1.stats,
+                                              af ? (const float*)P[pi + 1] : nullptr, af ? (const float*)P[pi + 2] : nullptr,
+                                              &zd, gtmp, af ? G[pi + 1] : nullptr, af ? G[pi + 2] : nullptr, beta, nt.scratch,
+                                              nt.scratch_bytes, nt.s);
         if (st != LAMP_OK) return st;
     }
-    st = lamp_inorm_relu_bwd(&zd, gtmp, &zd, c1.z, c1.stats, af ? (const float*)P[pi + 1] : nullptr,
-                             af ? (const float*)P[pi + 2] : nullptr, &zd, gtmp, af ? G[pi + 1] : nullptr,
-                             af ? G[pi + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
-    if (st != LAMP_OK) return st;
+    if (u->se_ratio) {
+        st = lamp_inorm_relu_bwd(&zd, gtmp, &zd, c1.z, c1.stats, af ? (const float*)P[pi + 1] : nullptr,
+                                 af ? (const float*)P[pi + 2] : nullptr, &zd, gtmp, af ? G[pi + 1] : nullptr,
+                                 af ? G[pi + 2] : nullptr, beta, nt.scratch, nt.scratch_bytes, nt.s);
+        if (st != LAMP_OK) return st;
+    }
     if (x2)   // two-part input (see block_fwd); the partial sums take the head of the scratch buffer
         st = mfma_wgrad(&xd, x, &zd, gtmp, G[pi], beta, nt.scratch, mfma_wgrad_ws_bytes(&xd, &zd), nt.s, x2, Cin / 2);
     else

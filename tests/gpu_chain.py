@@ -246,16 +246,17 @@ class Chain:
         return logits
 
     # ---- backward -----------------------------------------------------------------------------
-    def conv_bwd(self, c, g, grads, want_dx, dx_out=None):
-        """g: gradient w.r.t. c['y'] (overwritten with dz).  Returns dx (or None)."""
-        L, P, name = self.L, self.P, c["name"]
-        w = P[name + ".w"]
+    def _inorm_bwd(self, c, g, grads, run):
+        """The InstanceNorm + ReLU backward of conv unit c: run(dz_out, dgamma, dbeta) launches the library call that
+        turns the gradient g w.r.t. c['y'] into dz (written to dz_out, which may be g) -- the stand-alone call, or the
+        call fused with the data gradient that produced g; the result is checked against the oracle's backward of g."""
+        P, name = self.P, c["name"]
         gm, bt = P.get(name + ".gamma"), P.get(name + ".beta")
         dg = torch.empty_like(gm) if gm is not None else None
         db = torch.empty_like(bt) if bt is not None else None
         g_in = as64(g) if self.full else None
         g_dev = g.clone() if self.sampled else None
-        L.lamp_inorm_relu_bwd(g, c["z"], c["st"], g, gamma=gm, beta=bt, dgamma=dg, dbeta=db)
+        g = run(g, dg, db)
         if self.sampled:
             g64 = None if gm is None else as64(gm)
             b64 = None if bt is None else as64(bt)
@@ -281,6 +282,22 @@ class Chain:
             self._chk(g, dz_ref, f"inorm bwd: {name}", ignore=near)
         if gm is not None:
             grads[name + ".gamma"], grads[name + ".beta"] = dg, db
+        return g
+
+    def conv_bwd(self, c, g, grads, want_dx, dx_out=None, below=None, dz_ready=False):
+        """g: gradient w.r.t. c['y'] (overwritten with dz; dz_ready: g already is dz).  Returns dx (or None).
+        below: the conv unit whose activated output is this conv's input -- the data gradient and that unit's
+        InstanceNorm + ReLU backward then run as the one fused library call, as in the network entry points, and what
+        is returned is the gradient w.r.t. that unit's z (pass it on with dz_ready=True)."""
+        L, P, name = self.L, self.P, c["name"]
+        w = P[name + ".w"]
+        if not dz_ready:
+            gm, bt = P.get(name + ".gamma"), P.get(name + ".beta")
+
+            def run(gbuf, dg, db):
+                L.lamp_inorm_relu_bwd(gbuf, c["z"], c["st"], gbuf, gamma=gm, beta=bt, dgamma=dg, dbeta=db)
+                return gbuf
+            g = self._inorm_bwd(c, g, grads, run)
         dw = torch.empty(w.shape, dtype=F32, device=DEV)
         L.lamp_conv3d_wgrad(c["x"], g, dw)
         if self.sampled:
@@ -292,12 +309,31 @@ class Chain:
         if not want_dx:
             return None
         dx = dx_out if dx_out is not None else torch.empty_like(c["x"])
-        L.lamp_conv3d_dgrad(g, w, dx)
+        if below is None:
+            L.lamp_conv3d_dgrad(g, w, dx)
+        else:
+            # data gradient into dx, the backward of the unit below into a buffer of its own, so that both can be
+            # checked (the network runs the same call in place: the same bits, the backward being element-wise)
+            assert dx_out is None
+            gmb, btb = P.get(below["name"] + ".gamma"), P.get(below["name"] + ".beta")
+            dzb = torch.empty_like(dx)
+
+            def run_fused(gbuf, dg, db):
+                L.lamp_conv3d_dgrad_inorm_relu_bwd(g, w, dx, below["z"], below["st"], dzb, gamma=gmb, beta=btb, dgamma=dg, dbeta=db)
+                return dzb
+            # the stand-alone data gradient first: it gives the backward's input for the checks below, and the fused
+            # call, launched by _inorm_bwd, must write the same bits over it
+            L.lamp_conv3d_dgrad(g, w, dx)
         if self.sampled:
             self._sampled_conv("dgrad", name, g, w, dx)
         if self.full:
             self._chk(dx, O.conv3d_dgrad(as64(g), as64(w)), f"conv dgrad: {name}")
-        return dx
+        if below is None:
+            return dx
+        dx_alone = dx.clone()
+        out = self._inorm_bwd(below, dx, grads, run_fused)
+        assert torch.equal(dx, dx_alone), "the fused call's data gradient differs from lamp_conv3d_dgrad"
+        return out
 
     def backward(self, labels):
         L, Lv = self.L, self.levels
@@ -321,9 +357,9 @@ class Chain:
         for l in range(1, Lv):
             C = self.chan(l)
             c1, c2, upx = self.dec[l]
-            g = self.conv_bwd(c2, g, grads, True)
+            g = self.conv_bwd(c2, g, grads, True, below=c1)
             gcat = torch.empty_like(self.cat[l])
-            self.conv_bwd(c1, g, grads, True, dx_out=gcat)
+            self.conv_bwd(c1, g, grads, True, dx_out=gcat, dz_ready=True)
             skip_g[l] = gcat[..., :C]
             gup = gcat[..., C:]
             wt = self.P[f"dec{l}.up.w"]
@@ -350,6 +386,6 @@ class Chain:
                     ref = O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(skip_g[l])
                     self._chk(gy, ref, f"pool bwd: enc{l}", tol=4e-3 if self.dtype != F32 else 1e-6)
                 g = gy
-            g = self.conv_bwd(c2, g, grads, True)
-            g = self.conv_bwd(c1, g, grads, l > 1)
+            g = self.conv_bwd(c2, g, grads, True, below=c1)
+            g = self.conv_bwd(c1, g, grads, l > 1, dz_ready=True)
         return loss, grads

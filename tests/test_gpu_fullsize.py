@@ -383,8 +383,8 @@ def test_stage_fullsize_sampled(L):
         ref = O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(gs[l - 1])
         check(as64(gy), ref, BF, f"pool bwd: enc{l}", tol=4e-3)
         del ref
-        g = ch.conv_bwd(c2, gy, cg, True)
-        g = ch.conv_bwd(c1, g, cg, l > 1)
+        g = ch.conv_bwd(c2, gy, cg, True, below=c1)
+        g = ch.conv_bwd(c1, g, cg, l > 1, dz_ready=True)
     for kname, gr in zip(names[:4], grads):
         assert torch.equal(gr, cg[kname]), f"stage grad {kname} differs from the chain"
     print("checked ops:", ch.checked)

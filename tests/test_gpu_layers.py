@@ -287,6 +287,63 @@ def test_conv3d_norm_on_load_matrix_core(L, shape, affine, relu):
         check(as64(z), as64(z_ref), BF, "conv fwd, normalise on load vs materialised", tol=5e-3)
 
 
+# N, D, H, W, C of the layer below (= input channels of the conv), Co of the conv.  The bf16 cases with channel
+# counts that are multiples of 32 take the matrix-core kernel whose epilogue takes the sums (both tile depths, one
+# and two 32-channel blocks, ragged rims, a volume of several samples); the others the two-call sequence.
+DGRAD_IN_SHAPES = [(1, 5, 6, 7, 5, 3), (1, 8, 8, 16, 32, 32), (2, 9, 13, 21, 64, 32), (1, 16, 32, 32, 64, 64),
+                   (2, 6, 10, 18, 32, 64), (1, 24, 40, 48, 64, 64), (1, 4, 8, 16, 96, 96), (2, 16, 16, 16, 128, 128)]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", DGRAD_IN_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("affine", [False, True], ids=["plain", "affine"])
+def test_conv3d_dgrad_inorm_relu_bwd(L, dtype, shape, affine):
+    """Data gradient of a conv + InstanceNorm/ReLU backward of the layer below as one call: the data gradient against
+    the oracle's, the backward against the oracle's backward of the GPU's OWN data gradient (teacher forcing), and
+    both against the two separate library calls."""
+    N, D, H, W, C, Co = shape
+    r = rng(900 + sum(shape))
+    z = to_dev(S.normal(r, (N, D, H, W, C), 1.3) + 0.2, dtype)          # raw output of the layer below
+    dz2 = to_dev(S.normal(r, (N, D, H, W, Co)), dtype)                  # gradient w.r.t. the conv's output
+    w = to_dev(S.kaiming_conv(r, Co, C), dtype)
+    gm = to_dev(r.uniform(0.5, 1.5, C), F32) if affine else None
+    bt = to_dev(r.uniform(-0.5, 0.5, C), F32) if affine else None
+    y = torch.empty_like(z)
+    stats = torch.empty((N, C, 2), dtype=F32, device=DEV)
+    L.lamp_inorm_relu(z, y, stats, gamma=gm, beta=bt)
+    g = torch.empty_like(z)
+    dzb = torch.empty_like(z)
+    dg = torch.empty(C, dtype=F32, device=DEV) if affine else None
+    db = torch.empty(C, dtype=F32, device=DEV) if affine else None
+    L.lamp_conv3d_dgrad_inorm_relu_bwd(dz2, w, g, z, stats, dzb, gamma=gm, beta=bt, dgamma=dg, dbeta=db)
+    # the data gradient itself: the same bits as the stand-alone call, and the oracle's values
+    g_sep = torch.empty_like(z)
+    L.lamp_conv3d_dgrad(dz2, w, g_sep)
+    assert torch.equal(g, g_sep), "the fused call's data gradient differs from lamp_conv3d_dgrad"
+    check(as64(g), O.conv3d_dgrad(as64(dz2), as64(w)), dtype, "fused dgrad")
+    # the backward of the GPU's own g
+    g64 = as64(gm) if affine else None
+    b64 = as64(bt) if affine else None
+    dz_ref, dg_ref, db_ref = O.inorm_relu_bwd(as64(g), as64(z), g64, b64)
+    u_ref, _ = O.inorm_relu(as64(z), g64, b64, relu=False)
+    near = np.abs(u_ref) <= 1e-3
+    check(as64(dzb), dz_ref, dtype, "fused inorm bwd dz", ignore=near)
+    if affine:
+        V = N * D * H * W
+        slack = (np.abs(as64(g)) * near).reshape(-1, C).sum(0)
+        scale_b, scale_g = np.abs(db_ref).max(), np.abs(dg_ref).max()
+        assert np.all(np.abs(as64(db) - db_ref) <= 1e-4 * scale_b + slack + 1e-3 * np.sqrt(V) * (dtype == BF))
+        assert np.all(np.abs(as64(dg) - dg_ref) <= 1e-4 * scale_g + 3 * slack + 1e-3 * np.sqrt(V) * (dtype == BF))
+    # against the two separate calls: the sums are taken in another order, nothing else differs
+    dz_sep = torch.empty_like(z)
+    L.lamp_inorm_relu_bwd(g_sep, z, stats, dz_sep, gamma=gm, beta=bt)
+    check(as64(dzb), as64(dz_sep), dtype, "fused vs separate calls", tol=4e-3 if dtype == BF else 1e-5)
+    # in place (dzb = g), as the network entry points call it: the same bits
+    g2 = torch.empty_like(z)
+    L.lamp_conv3d_dgrad_inorm_relu_bwd(dz2, w, g2, z, stats, g2, gamma=gm, beta=bt)
+    assert torch.equal(g2, dzb)
+
+
 NORM_SHAPES = [(2, 3, 5, 7, 5), (1, 8, 8, 8, 8), (2, 16, 20, 24, 64), (1, 17, 9, 33, 32), (1, 4, 4, 4, 512), (1, 6, 6, 6, 24)]
 
 

@@ -211,8 +211,8 @@ def test_stage_partition_fwd_bwd(L):
         gy = torch.empty(c2["y"].shape, dtype=dtype, device=DEV)
         L.lamp_maxpool2_bwd(c2["y"], g, gy, add=gs[l - 1])
         np.testing.assert_allclose(as64(gy), O.maxpool2_bwd(as64(c2["y"]), as64(g)) + as64(gs[l - 1]), rtol=2 ** -8, atol=1e-30)
-        g = ch.conv_bwd(c2, gy, cg, True)
-        g = ch.conv_bwd(c1, g, cg, l > 1)
+        g = ch.conv_bwd(c2, gy, cg, True, below=c1)
+        g = ch.conv_bwd(c1, g, cg, l > 1, dz_ready=True)
     for k, gr in zip(names[:4], grads):
         assert torch.equal(gr, cg[k]), f"stage grad {k} differs from the chain"
     def stage_grads(st):
