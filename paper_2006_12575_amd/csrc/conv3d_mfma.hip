@@ -32,11 +32,12 @@ static constexpr int HH = TH + 2, HW = TW + 2;
 static constexpr int WPLANE_BYTES = 64 * 16;               // 64 co rows of 16 bytes
 static constexpr int WBUF_BYTES = 9 * 2 * WPLANE_BYTES;    // one kd group: 18432
 
-// Tile geometry for a tile depth of TDT (8 or 4) output d-slices.  The 8 waves split the tile as
-// TDT d-slices x (8/TDT) h-parts; a wave owns NVB blocks of 32 voxels (2 h-rows x 16 w).
+// Tile geometry for a tile depth of TDT (8 or 4) output d-slices.  The 8 waves split the tile as 2 halves in d x 4
+// pairs of h-rows (h, h + 4); a wave owns TDT/2 consecutive d-slices of its row pair, one block of 32 voxels
+// (2 h-rows x 16 w) each.
 template <int TDT> struct Geo {
     static constexpr int TD = TDT, HD = TDT + 2;
-    static constexpr int HSPLIT = 8 / TDT, NVB = 4 / HSPLIT;
+    static constexpr int ND = TDT / 2, NVB = ND;             // d-slices (= blocks of 32 voxels) per wave: 4 / 2
     static constexpr int HALO_VOX = HD * HH * HW;            // 1800 / 1080
     static constexpr int HALO_BYTES = HALO_VOX * 32;         // one 16-channel chunk, 32 bytes per voxel entry
     static constexpr int HBLK = (HALO_VOX + 31) / 32;        // wave-wide copies per halo chunk (32 voxels each): 57 / 34
@@ -262,35 +263,23 @@ template <int K, int NM, int NR, int NV, int NW> __device__ __forceinline__ void
 
 // Fragment registers that live from one column of the multiply pipeline to the next (and from the last column of
 // a tile, across its epilogue, to the first column of the next tile).
-template <int COB, int TDT> struct Frags;
-template <int COB> struct Frags<COB, 8> {
+template <int COB> struct Frags {
     bf16x8 a[2][3][COB];   // weight fragments of a tap column (kd = 0, 1, 2), two slots
     bf16x8 b[2];           // input slices 0 and 1 of the current column
 };
-template <int COB> struct Frags<COB, 4> {
-    bf16x8 a[2][COB];                // weight fragments of a tap, two slots
-    bf16x8 b[2][Geo<4>::NVB];        // activation fragments of a tap, two slots
-};
 
-// The fragments of the first column (8-deep tile) / first tap (4-deep tile) of group G, into slot SLOT.
-template <int COB, int TDT, int G, int SLOT>
-__device__ __forceinline__ void load_first(Frags<COB, TDT>& f, const char* __restrict__ hbu, const char* __restrict__ wb,
+// The fragments of the first column of group G, into slot SLOT.
+template <int COB, int G, int SLOT>
+__device__ __forceinline__ void load_first(Frags<COB>& f, const char* __restrict__ hbu, const char* __restrict__ wb,
                                            const uint32_t (&boff)[3]) {
     constexpr int WPLANE = 32 * COB * 16;
     const char* hb = hbu + boff[0];
-    if constexpr (TDT == 8) {
 #pragma unroll
-        for (int kd = 0; kd < 3; ++kd)
+    for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
-            for (int cb = 0; cb < COB; ++cb) f.a[SLOT][kd][cb] = lds_frag(wb + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
-        f.b[0] = lds_frag(hb + ((0 * HH + G) * HW) * 32);
-        f.b[1] = lds_frag(hb + ((1 * HH + G) * HW) * 32);
-    } else {
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb) f.a[SLOT][cb] = lds_frag(wb + cb * 32 * 16);
-#pragma unroll
-        for (int vb = 0; vb < Geo<4>::NVB; ++vb) f.b[SLOT][vb] = lds_frag(hb + (G * HH * HW) * 32 + vb * HW * 32);
-    }
+        for (int cb = 0; cb < COB; ++cb) f.a[SLOT][kd][cb] = lds_frag(wb + (kd * 3) * 2 * WPLANE + cb * 32 * 16);
+    f.b[0] = lds_frag(hb + ((0 * HH + G) * HW) * 32);
+    f.b[1] = lds_frag(hb + ((1 * HH + G) * HW) * 32);
 }
 
 // What the register-free copies and the normalise-on-load rewrite of a chunk stage need.
@@ -371,21 +360,19 @@ __device__ __forceinline__ void copy_portion(const CopyCtx& c, const HaloLane& h
 // landed at the barrier of group 2, so its slots go out between the last column of group 0 and the last column of
 // group 1, leaving the youngest ones three columns to land.  The column in front of a barrier carries nothing: the
 // wave that reaches the barrier last would do that work with the matrix cores idle.
-// COL: column (8-deep tile) or tap (4-deep tile) of the group.
+// COL: tap column of the group.
 struct PortionSpec { bool wc; int hf, hc, nf, nc, nw; bool tab; };
 template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL) {
     constexpr int NS = Geo<TDT>::HJ, ALLW = Geo<TDT>::ALLW;   // 8 / 5 slots, of which every wave issues the first 7 / 4
-    const int last = TDT == 8 ? 2 : 8;              // the column behind the barrier
+    const int last = 2;                             // the column behind the barrier
     PortionSpec p{COL == last, 0, 0, 0, 0, 0, false};
     if (!NORM) {
+        if (G == 0 && COL == 2) { p.hf = 0; p.hc = 2; }
         if (TDT == 8) {
-            if (G == 0 && COL == 2) { p.hf = 0; p.hc = 2; }
             if (G == 1 && COL == 0) { p.hf = 2; p.hc = 4; }
             if (G == 1 && COL == 2) { p.hf = 6; p.hc = 2; }
         } else {
-            if (G == 0 && COL == 8) { p.hf = 0; p.hc = 2; }
-            if (G == 1 && COL == 2) { p.hf = 2; p.hc = 2; }
-            if (G == 1 && COL == 8) { p.hf = 4; p.hc = 1; }
+            if (G == 1 && COL == 0) { p.hf = 2; p.hc = 3; }
         }
     } else {
         // Normalise on load: the copies go out earlier, and the entries they brought in are rewritten three columns
@@ -395,7 +382,7 @@ template <int TDT, bool NORM> constexpr PortionSpec portion_spec(int G, int COL)
         if (G == 0 && COL == last) { p.hf = 0; p.hc = 4; p.tab = true; }
         if (G == 1 && COL == 0) { p.hf = 4; p.hc = NS - 4; }
         if (G == 1 && COL == last) { p.nf = 0; p.nc = 4; p.nw = ALLW - 4; }
-        if (G == 2 && COL == (TDT == 8 ? 0 : 2)) { p.nf = 4; p.nc = NS - 4; p.nw = 1; }
+        if (G == 2 && COL == 0) { p.nf = 4; p.nc = NS - 4; p.nw = 1; }
     }
     return p;
 }
@@ -405,28 +392,28 @@ template <int TDT, bool NORM> constexpr int barrier_wait(int G) {
     return G != 1 ? 0 : NORM ? Geo<TDT>::ALLW : TDT == 8 ? 6 : 4;
 }
 
-// 8-deep tile, one tap column kw = KW of the in-plane row G = kh.  A wave owns 4 d-slices of one (2 h-rows x 16 w)
-// block; the input slice s = d + kd serves the output slices d = s, s-1, s-2 with the weights of kd = 0, 1, 2: 6
-// slice fragments and 3*COB weight fragments feed 12*COB MFMAs.  The weight fragments and the first two slices of
-// the next column are fetched meanwhile: of column KW + 1, or (KW == 2) of the first column of the group GN that
-// follows, whose weights sit in wbn and whose halo is hbn.  The column's portion of the copy work follows its matrix
-// instructions.
-template <int COB, int G, int KW, int SLOT, int GN, bool NORM>
-__device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f, const char* __restrict__ hbu,
-                                        const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
-                                        const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
-                                        const int (&wrel)[3]) {
-    constexpr int WPLANE = 32 * COB * 16;
+// One tap column kw = KW of the in-plane row G = kh.  A wave owns ND = 4 (8-deep tile) or 2 (4-deep tile) d-slices of
+// one (2 h-rows x 16 w) block; the input slice s = d + kd serves the output slices d = s, s-1, s-2 with the weights of
+// kd = 0, 1, 2: ND + 2 slice fragments and 3*COB weight fragments feed 3*ND*COB MFMAs.  The weight fragments and the
+// first two slices of the next column are fetched meanwhile: of column KW + 1, or (KW == 2) of the first column of the
+// group GN that follows, whose weights sit in wbn and whose halo is hbn.  The column's portion of the copy work
+// follows its matrix instructions.
+template <int COB, int TDT, int G, int KW, int SLOT, int GN, bool NORM>
+__device__ __forceinline__ void column(f32x16 (&acc)[COB][Geo<TDT>::ND], Frags<COB>& f, const char* __restrict__ hbu,
+                                       const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
+                                       const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
+                                       const int (&wrel)[3]) {
+    constexpr int WPLANE = 32 * COB * 16, ND = Geo<TDT>::ND;
     // lane bases of this tap column and of the one fetched ahead (the half of a voxel's entry that holds the lane's
     // channels depends on the voxel's w coordinate, and with it on kw)
     const char* hb = hbu + boff[KW];
     const char* hbx = KW < 2 ? hbu + boff[KW + 1] : hbnu + boff[0];
-    constexpr PortionSpec PO = portion_spec<8, NORM>(G, KW);
-    bf16x8 b[6], nb0, nb1;
+    constexpr PortionSpec PO = portion_spec<TDT, NORM>(G, KW);
+    bf16x8 b[ND + 2], nb0, nb1;
     b[0] = f.b[0];
     b[1] = f.b[1];
 #pragma unroll
-    for (int sl = 2; sl < 6; ++sl) b[sl] = lds_frag(hb + ((sl * HH + G) * HW) * 32);
+    for (int sl = 2; sl < ND + 2; ++sl) b[sl] = lds_frag(hb + ((sl * HH + G) * HW) * 32);
     if constexpr (KW < 2) {
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd)
@@ -442,69 +429,32 @@ __device__ __forceinline__ void column8(f32x16 (&acc)[COB][4], Frags<COB, 8>& f,
         nb0 = lds_frag(hbx + ((0 * HH + GN) * HW) * 32);
         nb1 = lds_frag(hbx + ((1 * HH + GN) * HW) * 32);
     }
-    auto mul = [&](int sl) __attribute__((always_inline)) {
+#pragma unroll
+    for (int sl = 0; sl < ND + 2; ++sl)
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd) {
             const int d = sl - kd;
-            if (d >= 0 && d < 4) {
+            if (d >= 0 && d < ND) {
 #pragma unroll
                 for (int cb = 0; cb < COB; ++cb)
                     acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][kd][cb], b[sl], acc[cb][d], 0, 0, 0);
             }
         }
-    };
-#pragma unroll
-    for (int sl = 0; sl < 6; ++sl) mul(sl);
-    sched_interleave<0, 12 * COB, 6 + 3 * COB>();
+    sched_interleave<0, 3 * ND * COB, ND + 2 + 3 * COB>();
     if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
         // behind the column's last matrix instruction, where the fewest fragments are live
         __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 8, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw, PO.tab>(c, hl, ht, wrel);
+        copy_portion<COB, TDT, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw, PO.tab>(c, hl, ht, wrel);
         __builtin_amdgcn_sched_barrier(0);
     }
     f.b[0] = nb0;
     f.b[1] = nb1;
 }
 
-// 4-deep tile, tap T9 = kh*3 + kw of the slice group G = kd: one k-step for the wave's NVB blocks; the fragments of
-// the next tap (T9 == 8: of the first tap of the group GN that follows) are fetched meanwhile.  The tap's portion of
-// the copy work follows its matrix instructions.
-template <int COB, int G, int T9, int SLOT, int GN, bool NORM>
-__device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB, 4>& f, const char* __restrict__ hbu,
-                                     const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
-                                     const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
-                                     const int (&wrel)[3]) {
-    constexpr int WPLANE = 32 * COB * 16, NVB = Geo<4>::NVB;
-    constexpr PortionSpec PO = portion_spec<4, NORM>(G, T9);
-    if constexpr (T9 < 8) {
-        constexpr int kh = (T9 + 1) / 3, kw = (T9 + 1) % 3;
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wb + (T9 + 1) * 2 * WPLANE + cb * 32 * 16);
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbu + boff[kw] + ((G * HH + kh) * HW) * 32 + vb * HW * 32);
-    } else {
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb) f.a[SLOT ^ 1][cb] = lds_frag(wbn + cb * 32 * 16);
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) f.b[SLOT ^ 1][vb] = lds_frag(hbnu + boff[0] + (GN * HH * HW) * 32 + vb * HW * 32);
-    }
-#pragma unroll
-    for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb)
-            acc[cb][vb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][cb], f.b[SLOT][vb], acc[cb][vb], 0, 0, 0);
-    sched_interleave<0, NVB * COB, COB + NVB>();
-    if constexpr (PO.wc || PO.hc > 0 || PO.nc > 0) {
-        __builtin_amdgcn_sched_barrier(0);
-        copy_portion<COB, 4, PO.wc, PO.hf, PO.hc, PO.nf, PO.nc, PO.nw, PO.tab>(c, hl, ht, wrel);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
-// One tap group of one chunk (9 taps: the in-plane row kh = G of the 8-deep tile, the slice kd = G of the 4-deep
-// one).  The multiply runs as one pipeline of columns / taps across groups, chunks and tiles: every column fetches
+// One tap group of one chunk (9 taps: the in-plane row kh = G, three tap columns kw).  The multiply runs as one
+// pipeline of columns across groups, chunks and tiles: every column fetches
 // the fragments of the next one, so the matrix instructions that follow a barrier have their operands in registers.
-// The workgroup's barrier therefore sits BEFORE the group's last column (last tap): by then every wave has read the
+// The workgroup's barrier therefore sits BEFORE the group's last column: by then every wave has read the
 // last fragments of this group's weights, and all of the previous chunk's halo.  What is copied in behind the
 // barrier: the weights of the group after next, into the buffer this group has just finished with (the last column
 // fetches the first fragments of the next group from the other weight buffer, filled one group earlier), and
@@ -515,25 +465,14 @@ __device__ __forceinline__ void tap4(f32x16 (&acc)[COB][Geo<4>::NVB], Frags<COB,
 // The LDS regions are distinct, and saying so (__restrict__) matters: otherwise the compiler must assume the
 // fragment reads alias the in-flight copies and waits for them before the first read.
 template <int COB, int TDT, int G, int PAR, bool NORM>
-__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Frags<COB, TDT>& f, const char* __restrict__ hb,
+__device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::ND], Frags<COB>& f, const char* __restrict__ hb,
                                            const char* __restrict__ wb, const char* __restrict__ hbn,
                                            const char* __restrict__ wbn, const uint32_t (&boff)[3], const CopyCtx& c,
                                            const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
     constexpr int GN = (G + 1) % 3;
     constexpr int WAIT = barrier_wait<TDT, NORM>(G);
-    if constexpr (TDT == 8) {
-        column8<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        column8<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-    } else {
-        tap4<COB, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 3, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 4, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 5, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 6, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-        tap4<COB, G, 7, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-    }
+    column<COB, TDT, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+    column<COB, TDT, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
     // The weights of the next group were copied behind the previous barrier; the only younger copies are halo slots,
     // of which every wave has issued WAIT (a wave that issued more waits for its oldest ones too).
     if (WAIT > 0 && c.pf_halo) wait_vmcnt<WAIT>();
@@ -542,8 +481,7 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::NVB], Fr
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), as a builtin so the compiler knows the reads are done
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if constexpr (TDT == 8) column8<COB, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
-    else tap4<COB, G, 8, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+    column<COB, TDT, G, 2, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
 }
 
 // SPLIT: the input-channel chunks are divided among gridDim.z workgroups per tile, each of which
@@ -590,15 +528,15 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     // and h + 4 (4 halo rows of 576 bytes = 0 modulo 256; with adjacent rows the read takes a third longer).
     const int g8 = l32 >> 3;
     const int bw = (l32 & 7) + 8 * (g8 >> 1), bh = (g8 ^ (g8 >> 1)) & 1;
-    // this wave's part of the tile.  4-deep tile: d-slice ds, h-row pairs (2*hs + vb, 2*hs + vb + 4) for the
-    // two blocks vb.  8-deep tile: d-slices 4*ds .. 4*ds+3 (one block each) of the h-row pair (hs, hs + 4).
-    const int ds = TDT == 8 ? (wv & 1) : wv % TDT, hs = TDT == 8 ? (wv >> 1) : wv / TDT;
+    // this wave's part of the tile: d-slices ND*ds .. ND*ds + ND - 1 (one block each) of the h-row pair (hs, hs + 4)
+    constexpr int ND = GE::ND;
+    const int ds = wv & 1, hs = wv >> 1;
     // lane base per tap column kw: the entry of voxel (.., bw + kw) and, in it, the half that holds this lane's
     // channels (lanes 0-31: channels 0-7 of the chunk, lanes 32-63: 8-15)
     uint32_t boff[3];
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) {
-        const int vox = TDT == 8 ? (4 * ds * HH + hs + 4 * bh) * HW + bw + kw : (ds * HH + hs * NVB + 4 * bh) * HW + bw + kw;
+        const int vox = (ND * ds * HH + hs + 4 * bh) * HW + bw + kw;
         boff[kw] = (uint32_t)(vox * 32 + 16 * (half ^ (((bw + kw) >> 3) & 1)));
     }
     const uint32_t a_base = (uint32_t)(half * WPLANE + l32 * 16);
@@ -690,8 +628,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         pending_tile = -1;
     };
     // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
-    Frags<COB, TDT> fr;
-    load_first<COB, TDT, 0, 0>(fr, hbuf0, wbuf0 + a_base, boff);
+    Frags<COB> fr;
+    load_first<COB, 0, 0>(fr, hbuf0, wbuf0 + a_base, boff);
     // One 16-channel chunk = three tap groups; P = fragment slot of its first column (a group has an odd number of
     // columns / taps, so the slot alternates from group to group).
     auto chunk_groups = [&](f32x16 (&acc)[COB][NVB], int chunk, int tile, int next_tile, const HaloTile& ht_cur,
@@ -745,17 +683,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             chunk_groups(acc, chunk, tile, next_tile, ht_cur, ht_next);
             // a chunk has an odd number of columns: what its last column fetched sits in slot 1, and every chunk
             // starts in slot 0 (two code paths, one per starting slot, cost the compiler a hundred registers)
-            if constexpr (TDT == 8) {
 #pragma unroll
-                for (int kd = 0; kd < 3; ++kd)
+            for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
-                    for (int cb = 0; cb < COB; ++cb) fr.a[0][kd][cb] = fr.a[1][kd][cb];
-            } else {
-#pragma unroll
-                for (int cb = 0; cb < COB; ++cb) fr.a[0][cb] = fr.a[1][cb];
-#pragma unroll
-                for (int vb = 0; vb < NVB; ++vb) fr.b[0][vb] = fr.b[1][vb];
-            }
+                for (int cb = 0; cb < COB; ++cb) fr.a[0][kd][cb] = fr.a[1][kd][cb];
         }
 
         // every wave has read its last fragments of the finished chunk's halo before any wave's epilogue writes there
@@ -768,7 +699,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         // Scratch: the halo buffer of the stage just finished (free until the next prefetch).
         int n, d0, h0, w0;
         tile_origin(tile, n, d0, h0, w0);
-        const int gd0 = TDT == 8 ? d0 + 4 * ds : d0 + ds;
+        const int gd0 = d0 + ND * ds;
         if constexpr (SPLIT) {
             // fp32 partial sums straight from the accumulators: lane = voxel (bh, bw) of block vb, four
             // consecutive channels per register group
@@ -789,9 +720,9 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             }
 #pragma unroll
             for (int vb = 0; vb < NVB; ++vb) {
-                const int gh = h0 + hs * NVB + vb + 4 * bh, gw = w0 + bw;
-                if (gd0 < a.D && gh < a.H && gw < a.W) {
-                    float* row = zp + ((((int64_t)n * a.D + gd0) * a.H + gh) * a.W + gw) * a.Cout + co0 + half * 4;
+                const int gd = gd0 + vb, gh = h0 + hs + 4 * bh, gw = w0 + bw;
+                if (gd < a.D && gh < a.H && gw < a.W) {
+                    float* row = zp + ((((int64_t)n * a.D + gd) * a.H + gh) * a.W + gw) * a.Cout + co0 + half * 4;
 #pragma unroll
                     for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
@@ -823,10 +754,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         const int ch = co0 + part * 8;
         const bool second = ch >= a.zsplit;
         const int ldo = second ? a.ldz2 : a.ldz;
-        const int hb0 = TDT == 8 ? h0 + hs : h0 + hs * NVB;
+        const int hb0 = h0 + hs;
         bf16_t* const tbase = (second ? a.z2 + (ch - a.zsplit) : a.z + ch) +
                               ((((int64_t)n * a.D + gd0) * a.H + hb0) * a.W + w0) * ldo;
-        const int vbvox = TDT == 8 ? a.H * a.W : a.W;   // voxels from block vb to vb + 1 (offsets inside a tile fit 32 bits)
+        const int vbvox = a.H * a.W;   // voxels from block vb to vb + 1 (offsets inside a tile fit 32 bits)
         // BSUM: the matching piece of the layer below's z (same offsets: same shape and channel stride), and this
         // lane's 8 (a, b) pairs
         const bf16_t* zbase = nullptr;
@@ -840,7 +771,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                 za[2 * e] = v.x; zbb[2 * e] = v.y; za[2 * e + 1] = v.z; zbb[2 * e + 1] = v.w;
             }
         }
-        const bool full = gd0 + (TDT == 8 ? NVB : 1) <= a.D && h0 + TH <= a.H && w0 + TW <= a.W;
+        const bool full = gd0 + ND <= a.D && h0 + TH <= a.H && w0 + TW <= a.W;
         const bool want_stats = a.part != nullptr;
         if (a.bias) {   // fp32 bias on the accumulators: what is rounded, stored and summed is z + b
 #pragma unroll
@@ -886,8 +817,8 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                     if constexpr (!FULL) {
                         const int rg8 = row >> 3;
                         const int rw = (row & 7) + 8 * (rg8 >> 1), rh = 4 * ((rg8 ^ (rg8 >> 1)) & 1);
-                        const int gd = TDT == 8 ? gd0 + vb : gd0;
-                        const int gh = TDT == 8 ? hb0 + rh : hb0 + vb + rh, gw = w0 + rw;
+                        const int gd = gd0 + vb;
+                        const int gh = hb0 + rh, gw = w0 + rw;
                         ok = gd < a.D && gh < a.H && gw < a.W;
                     }
                     if (ok) {
@@ -1144,7 +1075,7 @@ int conv_repack_kind(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd, boo
         pack_descs(xd, zd, pp, xp, zp);
         return conv_repack_kind(&xp, &zp, false);
     }
-    return conv_tile_depth(zd) == 8 ? 1 : 0;
+    return 1;   // one layout for both tile depths: tap groups by in-plane row kh
 }
 size_t conv_repack_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd) {
     return align_up((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
@@ -1274,11 +1205,11 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
         LAMP_CHECK_LAUNCH();
     }
     const int64_t wtotal = (int64_t)27 * xd->c * zd->c;
-    if (const bf16_t* pre = find_prepacked(w, dgrad, TDT == 8 ? 1 : 0, zd->c, xd->c)) {
+    if (const bf16_t* pre = find_prepacked(w, dgrad, 1, zd->c, xd->c)) {
         wp = const_cast<bf16_t*>(pre);
     } else {
         hipLaunchKernelGGL(repack_weights_kernel, dim3(cdiv(wtotal / 8, 256)), dim3(256), 0, s, (const bf16_t*)w, wp, zd->c, xd->c,
-                           dgrad ? 1 : 0, TDT == 8 ? 1 : 0);
+                           dgrad ? 1 : 0, 1);
         LAMP_CHECK_LAUNCH();
     }
     ConvArgs a;
