@@ -30,7 +30,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 static constexpr int TH = 8, TW = 16;
 static constexpr int HH = TH + 2, HW = TW + 2;
 static constexpr int WPLANE_BYTES = 64 * 16;               // 64 co rows of 16 bytes
-static constexpr int WBUF_BYTES = 9 * 2 * WPLANE_BYTES;    // one kd group: 18432
 
 // Tile geometry for a tile depth of TDT (8 or 4) output d-slices.  The 8 waves split the tile as 2 halves in d x 4
 // pairs of h-rows (h, h + 4); a wave owns TDT/2 consecutive d-slices of its row pair, one block of 32 voxels
@@ -43,15 +42,29 @@ template <int TDT> struct Geo {
     static constexpr int HBLK = (HALO_VOX + 31) / 32;        // wave-wide copies per halo chunk (32 voxels each): 57 / 34
     static constexpr int HJ = (HBLK + 7) / 8;                // copy slots per wave (slot j = block wv + 8*j): 8 / 5
     static constexpr int ALLW = (HALO_VOX / 32) / 8;         // slots that every wave issues, in full: 7 / 4
-    // epilogue scratch: 8 wave patches of 32 rows x 144 bytes (the 8-deep tile reuses the halo buffer of the finished
-    // stage, the 4-deep one is too small for that and gets its own), and the channel sums of each wave (64 channels x
-    // (sum, sum of squares)), which outlive the epilogue (they are added up during the next tile) and have a region of their own
-    static constexpr int PATCH_BYTES = 8 * 32 * 144, SUMS_BYTES = 8 * 64 * 2 * 4;
-    static constexpr bool EPI_OWN = HALO_BYTES < PATCH_BYTES;
-    static constexpr int SUMS_OFF = 2 * HALO_BYTES + 2 * WBUF_BYTES + (EPI_OWN ? PATCH_BYTES : 0);
+};
+
+// LDS layout of a workgroup: two halo buffers (one 16-channel chunk each), two weight buffers (one in-plane row of 9
+// taps x 16 input channels x the output-channel block), the epilogue's patches, the channel sums, the coefficient table.
+template <int TDT, int COB> struct Lds {
+    typedef Geo<TDT> GE;
+    static constexpr int WBUF_BYTES = 9 * 2 * (32 * COB) * 16;      // 9216 / 18432
+    static constexpr int W_OFF = 2 * GE::HALO_BYTES;
+    // Epilogue scratch: per wave a patch of 32 voxel rows (the output-channel block plus 16 bytes of padding each).
+    // With a 32-channel block the epilogue of a tile runs during the multiply of the next one, when both halo buffers
+    // are in use: its patches have a region of their own.  With 64 channels the patches take the halo buffer of the
+    // stage just finished, where that is large enough (the 8-deep tile).
+    static constexpr int ROWB = 32 * COB * 2 + 16;
+    static constexpr int PATCH_BYTES = 8 * 32 * ROWB;               // 20480 / 36864
+    static constexpr bool EPI_OWN = COB == 1 || GE::HALO_BYTES < PATCH_BYTES;
+    static constexpr int PATCH_OFF = W_OFF + 2 * WBUF_BYTES;
+    // the channel sums of each wave (64 channels x (sum, sum of squares)) outlive the epilogue: they are added up
+    // behind a later barrier
+    static constexpr int SUMS_OFF = PATCH_OFF + (EPI_OWN ? PATCH_BYTES : 0), SUMS_BYTES = 8 * 64 * 2 * 4;
     // normalise on load: the (a, b) pairs of the incoming chunk's 16 channels
     static constexpr int TAB_OFF = SUMS_OFF + SUMS_BYTES, TAB_BYTES = 128;
     static constexpr int LDS_BYTES = TAB_OFF + TAB_BYTES;
+    static_assert(LDS_BYTES <= 160 * 1024, "the layout fits the LDS of a compute unit");
 };
 
 // Two floats to a pair of bf16 (round to nearest even) with the hardware conversion.
@@ -490,13 +503,15 @@ __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::ND], Fra
 template <int COB, int TDT, bool SPLIT = false, bool NORM = false, bool BSUM = false>
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
+    typedef Lds<TDT, COB> LD;
+    constexpr int WBUF_BYTES = LD::WBUF_BYTES;
     constexpr int TD = GE::TD, NVB = GE::NVB, HALO_VOX = GE::HALO_VOX, HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* hbuf0 = lds;
-    char* wbuf0 = lds + 2 * HALO_BYTES;
+    char* wbuf0 = lds + LD::W_OFF;
     // LDS byte addresses of the two, for the register-free copies
-    const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds, wbuf_a = lds_a + 2 * HALO_BYTES;
-    const uint32_t tab_a = lds_a + GE::TAB_OFF;
+    const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds, wbuf_a = lds_a + LD::W_OFF;
+    const uint32_t tab_a = lds_a + LD::TAB_OFF;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int cbi = a.cb_inner ? (int)(blockIdx.x >> 3) % a.cb_inner : (int)blockIdx.y;   // output-channel block
@@ -568,12 +583,38 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         h0 = (r % a.tiles_h) * TH;
         d0 = (r / a.tiles_h) * TD;
     };
-    auto halo_tile = [&](int tile) {
-        int n, d0, h0, w0;
-        tile_origin(tile, n, d0, h0, w0);
+    struct TilePos { int n, d0, h0, w0; };
+    auto tile_pos = [&](int tile) {
+        TilePos p;
+        tile_origin(tile, p.n, p.d0, p.h0, p.w0);
+        return p;
+    };
+    // A workgroup's tiles lie wg_per_xcd apart: from one to the next the position advances by a fixed step, added
+    // digit by digit in the mixed radix (tiles_w, tiles_h, tiles_d) -- a dozen scalar instructions where the divisions
+    // of tile_origin take a hundred, in one dependent chain.
+    int step_n, step_d, step_h, step_w;
+    tile_origin(wg_per_xcd, step_n, step_d, step_h, step_w);
+    const int lim_d = a.tiles_d * TD, lim_h = a.tiles_h * TH, lim_w = a.tiles_w * TW;
+    auto tile_step = [&](const TilePos& p) {
+        TilePos q;
+        q.w0 = p.w0 + step_w;
+        int c = q.w0 >= lim_w ? 1 : 0;
+        q.w0 -= c ? lim_w : 0;
+        q.h0 = p.h0 + step_h + c * TH;
+        c = q.h0 >= lim_h ? 1 : 0;
+        q.h0 -= c ? lim_h : 0;
+        q.d0 = p.d0 + step_d + c * TD;
+        c = q.d0 >= lim_d ? 1 : 0;
+        q.d0 -= c ? lim_d : 0;
+        q.n = p.n + step_n + c;
+        return q;
+    };
+    auto halo_tile = [&](const TilePos& p) {
         HaloTile t;
-        t.origin = a.x + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
-        t.dlo = 1 - d0; t.dhi = a.D - d0; t.hlo = 1 - h0; t.hhi = a.H - h0; t.wlo = 1 - w0; t.whi = a.W - w0;
+        // (a position past the last tile is never read from: its origin only has to be computable)
+        const int vox = (((p.n * a.D + (p.d0 - 1)) * a.H + (p.h0 - 1)) * a.W + (p.w0 - 1));
+        t.origin = a.x + (int64_t)vox * a.ldx;
+        t.dlo = 1 - p.d0; t.dhi = a.D - p.d0; t.hlo = 1 - p.h0; t.hhi = a.H - p.h0; t.wlo = 1 - p.w0; t.whi = a.W - p.w0;
         return t;
     };
     constexpr int wgstride = 18 * WROWS * 8;                                       // elements of one group
@@ -582,14 +623,21 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     int tile = tile_lo + local;
     if (tile >= tile_hi) return;
 
+    // Where the tile of this pass and the one after it lie.  The position of the tile after those is worked out during
+    // the epilogue, whose LDS round trips leave the scalar unit idle: at the top of a pass it would hold up the first
+    // matrix instructions of every wave.
+    TilePos pos = tile_pos(tile);
+    TilePos pos_next = tile_step(pos);
+    HaloTile ht_cur = halo_tile(pos), ht_next = halo_tile(pos_next);
+
     // ---- prologue: first halo chunk and the first two weight groups
     {
-        const HaloTile t0 = halo_tile(tile);
+        const HaloTile t0 = ht_cur;
 #pragma unroll
         for (int j = 0; j < HJ; ++j) halo_copy_slot<TDT, (COB == 2 && TDT == 8)>(j, hl, t0, a.H, a.W, a.ldx, choff(c_lo), a.zero16, lds_a, wv, lane);
         if constexpr (NORM) {
             if (wv == 0 && lane < 8)
-                g2lds16a(reinterpret_cast<const char*>(a.ab + (int64_t)(tile / a.tiles_per_n) * a.Cin + c_lo * 16) + lane * 16, tab_a);
+                g2lds16a(reinterpret_cast<const char*>(a.ab + (int64_t)pos.n * a.Cin + c_lo * 16) + lane * 16, tab_a);
         }
 #pragma unroll
         for (int g = 0; g < 2; ++g)
@@ -600,7 +648,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         wait_vmcnt<0>();
         if constexpr (NORM) {
             __syncthreads();   // the coefficient table (wave 0's copy) is there for every wave
-            halo_norm<TDT, 0, HJ>(hbuf0, hl, t0, lds + GE::TAB_OFF, a.relu_floor, wv, lane);
+            halo_norm<TDT, 0, HJ>(hbuf0, hl, t0, lds + LD::TAB_OFF, a.relu_floor, wv, lane);
         }
         __syncthreads();
     }
@@ -610,26 +658,25 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     // Statistics: the tile whose per-wave channel sums wait in LDS to be added up and written (-1: none).  Every wave
     // writes its sums at the end of the tile's epilogue and goes on; the first 2 * WROWS threads add the 8 waves up
     // behind the next barrier that every wave has passed with its rows written.
-    int pending_tile = -1;
+    int pending_tile = -1, pending_count = 0;
     auto flush_sums = [&]() __attribute__((always_inline)) {
         if (tid < WROWS * 2) {
-            const float* sred = reinterpret_cast<const float*>(lds + GE::SUMS_OFF);
+            const float* sred = reinterpret_cast<const float*>(lds + LD::SUMS_OFF);
             const int c = tid >> 1, k = tid & 1;
             float v = 0.f;
 #pragma unroll
             for (int q = 0; q < 8; ++q) v += sred[q * 128 + c * 2 + k];
             a.part[((int64_t)pending_tile * a.Cout + co0 + c) * 2 + k] = v;
         }
-        if (a.counts && tid == 0 && cbi == 0 && pending_tile < a.tiles_per_n) {
-            int n, d0, h0, w0;
-            tile_origin(pending_tile, n, d0, h0, w0);
-            a.counts[pending_tile] = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
-        }
+        if (a.counts && tid == 0 && cbi == 0 && pending_tile < a.tiles_per_n) a.counts[pending_tile] = pending_count;
         pending_tile = -1;
     };
     // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
     Frags<COB> fr;
     load_first<COB, 0, 0>(fr, hbuf0, wbuf0 + a_base, boff);
+    constexpr int ROWB = LD::ROWB;                // padded row of the patch
+    constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
+    constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
     // One 16-channel chunk = three tap groups; P = fragment slot of its first column (a group has an odd number of
     // columns / taps, so the slot alternates from group to group).
     auto chunk_groups = [&](f32x16 (&acc)[COB][NVB], int chunk, int tile, int next_tile, const HaloTile& ht_cur,
@@ -653,32 +700,39 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         CopyCtx cc;
         cc.hb_next = hb_next; cc.hb_next_a = hb_next_a; cc.pf_halo = pf; cc.pf_choff = choff(pf_chunk); cc.zero16 = a.zero16;
         cc.abp = nullptr; cc.relu_floor = a.relu_floor; cc.wv = wv; cc.lane = lane;
-        cc.tab = lds + GE::TAB_OFF; cc.tab_a = tab_a; cc.H = a.H; cc.W = a.W; cc.ldx = a.ldx;
+        cc.tab = lds + LD::TAB_OFF; cc.tab_a = tab_a; cc.H = a.H; cc.W = a.W; cc.ldx = a.ldx;
         if constexpr (NORM) {
-            const int n_pf = (last_chunk && next_tile < tile_hi ? next_tile : tile) / a.tiles_per_n;
+            const int n_pf = last_chunk && next_tile < tile_hi ? pos_next.n : pos.n;
             cc.abp = a.ab + (int64_t)n_pf * a.Cin + pf_chunk * 16;
         }
         cc.wb_fill_a = w0n; cc.pf_w = true; cc.wsrc = wc2;
+        // (after group 0: every wave is past its barrier, its sums of the last tile written)
         conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, boff, cc, hl, ht, wrel);
-        if (pending_tile >= 0) flush_sums();   // every wave is past this group's barrier, its sums of the last tile written
+        if (pending_tile >= 0) flush_sums();
         cc.wb_fill_a = w1n; cc.pf_w = pf; cc.wsrc = wn0;
         conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, boff, cc, hl, ht, wrel);
         cc.wb_fill_a = w0n; cc.wsrc = wn0 + wgstride;
         conv_group<COB, TDT, 2, P, NORM>(acc, fr, hb, w0p, hbn, w1p, boff, cc, hl, ht, wrel);
         wpar ^= 1;
     };
+    // The accumulators start a pass at zero: cleared here, and then by the epilogue as it hands each block on.
+    f32x16 acc[COB][NVB];
+#pragma unroll
+    for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
     for (; tile < tile_hi; tile += wg_per_xcd) {
-        f32x16 acc[COB][NVB];
-#pragma unroll
-        for (int cb = 0; cb < COB; ++cb)
-#pragma unroll
-            for (int vb = 0; vb < NVB; ++vb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
-
         const int next_tile = tile + wg_per_xcd;
-        const HaloTile ht_cur = halo_tile(tile);
-        const HaloTile ht_next = halo_tile(next_tile < tile_hi ? next_tile : tile);
+        TilePos pos_nn = pos;
+        auto advance_pos = [&]() __attribute__((always_inline)) { pos_nn = tile_step(pos_next); };
+        auto end_pass = [&]() __attribute__((always_inline)) {
+            pos = pos_next;
+            pos_next = pos_nn;
+            ht_cur = ht_next;
+            ht_next = halo_tile(pos_nn);
+        };
         for (int chunk = c_lo; chunk < c_hi; ++chunk, ++stage) {
             chunk_groups(acc, chunk, tile, next_tile, ht_cur, ht_next);
             // a chunk has an odd number of columns: what its last column fetched sits in slot 1, and every chunk
@@ -688,17 +742,13 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
 #pragma unroll
                 for (int cb = 0; cb < COB; ++cb) fr.a[0][kd][cb] = fr.a[1][kd][cb];
         }
-
-        // every wave has read its last fragments of the finished chunk's halo before any wave's epilogue writes there
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
-        // register group) into voxel rows through a private LDS patch, so that 8 lanes store one
-        // full row of 64 channels; the channel sums of the stored values come from the same pass.
-        // Scratch: the halo buffer of the stage just finished (free until the next prefetch).
-        int n, d0, h0, w0;
-        tile_origin(tile, n, d0, h0, w0);
+        const int n = pos.n, d0 = pos.d0, h0 = pos.h0, w0 = pos.w0;
+        if constexpr (!LD::EPI_OWN) {
+            // every wave has read its last fragments of the finished chunk's halo before any wave's epilogue writes there
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
         const int gd0 = d0 + ND * ds;
         if constexpr (SPLIT) {
             // fp32 partial sums straight from the accumulators: lane = voxel (bh, bw) of block vb, four
@@ -730,20 +780,30 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                             *reinterpret_cast<float4*>(row + cb * 32 + rg * 8) =
                                 make_float4(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1], acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
                 }
+#pragma unroll
+                for (int cb = 0; cb < COB; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
             }
+            advance_pos();
+            end_pass();
             __syncthreads();
             continue;
         }
-        char* fbuf = GE::EPI_OWN ? lds + 2 * HALO_BYTES + 2 * WBUF_BYTES : hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
-        constexpr int ROWB = WROWS * 2 + 16;          // padded row of the patch
-        constexpr int PARTS = WROWS / 8;              // 16-byte parts per row: 8 or 4
-        constexpr int RPI = 64 / PARTS;               // rows covered per read instruction
+        // ---- epilogue.  Each wave turns its accumulators (lane = voxel, 4 consecutive channels per
+        // register group) into voxel rows through a private LDS patch, so that 8 (4) lanes store one
+        // full row of 64 (32) channels; the channel sums of the stored values come from the same pass.
+        // Scratch: the patch region, or (64-channel block, 8-deep tile) the halo buffer of the stage just finished,
+        // free until the next prefetch.
+        char* fbuf = LD::EPI_OWN ? lds + LD::PATCH_OFF : hbuf0 + ((stage + 1) & 1) * HALO_BYTES;
+        static_assert(LD::EPI_OWN || LD::PATCH_BYTES <= HALO_BYTES, "the patches fit the halo buffer");
         char* patch = fbuf + wv * (32 * ROWB);
-        float* sred = reinterpret_cast<float*>(lds + GE::SUMS_OFF);
-        // The lane id enters the epilogue through an opaque copy: what is derived from it below would otherwise
-        // be hoisted out of the tile loop and stay in registers across the multiply loop, which has none to spare.
+        float* sred = reinterpret_cast<float*>(lds + LD::SUMS_OFF);
+        // 64-channel block: the lane id enters the epilogue through an opaque copy, as what is derived from it below
+        // would otherwise be hoisted out of the tile loop and stay in registers across the multiply loop, which has
+        // none to spare.  The 32-channel block has them, and is the one whose epilogue weighs: there the hoisting is welcome.
         int lane_e = lane;
-        asm volatile("" : "+v"(lane_e));
+        if constexpr (COB == 2) asm volatile("" : "+v"(lane_e));
         const int part = lane_e % PARTS, prow = lane_e / PARTS;
         float csum[8], csq[8];
 #pragma unroll
@@ -804,8 +864,11 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                         const uint32_t p0 = pack_bf16(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1]);
                         const uint32_t p1 = pack_bf16(acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
                         *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[cb][vb][rg * 4 + r] = 0.f;
                     }
                 __builtin_amdgcn_wave_barrier();
+                if (vb == 0) advance_pos();   // scalar work in the shadow of the patch round trip
                 bf16_t* const bbase = tbase + (int64_t)vb * vbvox * ldo;
                 uint4 qv[32 / RPI];
                 uint4 zv[BSUM ? 32 / RPI : 1];
@@ -908,7 +971,9 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             // No barrier: the sums are added up and written behind the first barrier of the next tile (after the
             // last tile: behind a barrier of their own), which every wave reaches with its rows written.
             pending_tile = tile;
+            pending_count = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
         }
+        end_pass();
         // No barrier here: the next copies into the patch buffer go out behind the barrier of the next tile's first
         // group.
     }
@@ -945,6 +1010,7 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
     // element offsets inside a tile's halo (10 slices of H x W voxels) are kept in 32 bits
     const int64_t ldmax = xd->ldc > zd->ldc ? xd->ldc : zd->ldc;
     if ((int64_t)10 * zd->h * zd->w * ldmax >= ((int64_t)1 << 31)) return false;
+    if (nvox(xd) >= ((int64_t)1 << 31)) return false;   // the voxel index of a tile's origin is kept in 32 bits
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) {
         // normalise on load: every input channel normalised, on the plain tiled kernel (no packed batch of tiny
         // volumes, no input-channel split: those layers are small and keep the generic path)
@@ -1124,7 +1190,7 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
 
 template <int COB, int TDT, bool SPLIT = false, bool NORM = false, bool BSUM = false>
 static lamp_status launch_igemm(const ConvArgs& a, dim3 grid, hipStream_t s) {
-    const int shm = Geo<TDT>::LDS_BYTES;
+    const int shm = Lds<TDT, COB>::LDS_BYTES;
     if (ensure_dyn_lds((const void*)conv3d_igemm_kernel<COB, TDT, SPLIT, NORM, BSUM>, shm) != LAMP_OK) return LAMP_ERR_HIP;
     hipLaunchKernelGGL((conv3d_igemm_kernel<COB, TDT, SPLIT, NORM, BSUM>), grid, dim3(512), shm, s, a);
     LAMP_CHECK_LAUNCH();
