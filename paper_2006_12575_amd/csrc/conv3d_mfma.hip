@@ -5,17 +5,17 @@
 //
 // GEMM view per workgroup tile:  D[co][voxel] += sum_{tap, ci} Wp[tap][co][ci] * X[voxel + tap][ci]
 //   M = 32*COB output channels (A operand = weights), N = 1024 voxels (B operand = activations),
-//   K = 27 taps x Cin, walked as (Cin chunk of 16 = one MFMA k-step) x (3 groups of 9 taps: one kh
-//   each for the 8-deep tile, one kd each for the 4-deep tile).
-// Tile: 8 x 8 x 16 output voxels (d,h,w); 8 waves (2 per SIMD); a wave owns 4 d-slices of one
-// (2 h-rows x 16 w) patch = 4 blocks of 32 voxels, so a 16-lane group always reads 16 consecutive
+//   K = 27 taps x Cin, walked as (Cin chunk of 16 = one MFMA k-step) x (3 groups of 9 taps, one in-plane row kh
+//   each) x (3 tap columns kw of 3 taps kd).
+// Tile: 8 x 8 x 16 (or 4 x 8 x 16) output voxels (d,h,w); 8 waves (2 per SIMD); a wave owns 4 (2) d-slices of one
+// (2 h-rows x 16 w) patch = 4 (2) blocks of 32 voxels, so a 16-lane group always reads 16 consecutive
 // halo voxels and an input slice fragment serves up to three output slices (kd = 0, 1, 2).
 // LDS holds a halo chunk as 32-byte voxel entries (the two 16-byte halves = channels 0-7 / 8-15 of the chunk, in
 // swapped order where bit 3 of the halo w coordinate is set): a copy instruction fetches both halves of 32 voxels,
 // so two lanes share every line they touch, and every fragment read is a conflict-free 16-byte load at a lane base
 // (one per tap column kw) plus an immediate offset.
 // Two halo buffers (10 x 10 x 18 voxels) let the next chunk / next tile stream in while the
-// current one is multiplied; two weight buffers hold one tap group (9 taps x 64 co x 16 ci) each.
+// current one is multiplied; two weight buffers hold one tap group (9 taps x 64 or 32 co x 16 ci) each.
 // Workgroups are persistent and walk an XCD-contiguous range of tiles.
 #include <stdlib.h>
 #include "internal.h"
@@ -29,7 +29,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 static constexpr int TH = 8, TW = 16;
 static constexpr int HH = TH + 2, HW = TW + 2;
-static constexpr int WPLANE_BYTES = 64 * 16;               // 64 co rows of 16 bytes
 
 // Tile geometry for a tile depth of TDT (8 or 4) output d-slices.  The 8 waves split the tile as 2 halves in d x 4
 // pairs of h-rows (h, h + 4); a wave owns TDT/2 consecutive d-slices of its row pair, one block of 32 voxels
@@ -198,25 +197,36 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_
 
 
 // Per-lane constants of the halo copies.  A wave copies halo blocks wv, wv + 8, ... (32 voxels each; lanes 2i and
-// 2i + 1 fetch the two 16-byte halves of voxel i's 32 bytes, in the order the LDS entry stores them): pk = the halo
-// coords of the lane's voxel and which half (plane) of the chunk's channels it fetches, d | h << 4 | w << 8 | plane << 13,
-// two slots to a register (slot j in the low or high half of pk[j / 2]).
+// 2i + 1 fetch the two 16-byte halves of voxel i's 32 bytes, in the order the LDS entry stores them).  pk = the halo
+// coords of the lane's voxel, 16 bits a slot, two slots to a register (slot j in the low or high half of pk[j / 2]):
+// d in bits 0-3, h in bits 5-8, w in bits 10-14, and a guard bit above each field (bits 4, 9, 15), so that one
+// subtraction compares all three coordinates of both slots with a bound: a field's guard bit survives
+// (c + guard) - lo exactly when c >= lo, and (hi + guard) - c exactly when c <= hi, and never borrows from its
+// neighbour.  Six compares and five mask operations per slot become four instructions.
+static constexpr uint32_t HALO_GUARD = 0x8210u, HALO_GUARD2 = 0x82108210u;
+struct HaloTile {
+    const bf16_t* origin;   // x at the halo origin (d0-1, h0-1, w0-1) of the tile (may be out of range)
+    uint32_t lo2, hi2;      // halo coords inside the volume, lo <= c <= hi per field, packed like HaloLane::pk (no guards)
+};
 struct HaloLane {
     int pk[4];
     int rel[8];   // element offset of the lane's 16 bytes from the tile's halo origin (kernels with registers to spare)
-    template <bool LEAN> __device__ __forceinline__ void coords(int j, int& hd, int& hh, int& hw, int& plane) const {
+    // which half (plane) of the chunk's channels the lane fetches for slot j follows from its voxel's w
+    template <bool LEAN> __device__ __forceinline__ void coords(int j, int lane, int& hd, int& hh, int& hw, int& plane) const {
         int v = (j & 1) ? pk[j >> 1] >> 16 : pk[j >> 1];
         // LEAN (the 64-channel kernel of the 8-deep tile, which has no register to spare): opaque, because what is
         // derived from the coordinates (the voxel's offset in the tensor) is cheap to recompute at every use, where
         // the compiler would rather compute all of it once and keep it in registers it has not got
         if constexpr (LEAN) asm volatile("" : "+v"(v));
-        hd = v & 15; hh = (v >> 4) & 15; hw = (v >> 8) & 31; plane = (v >> 13) & 1;
+        hd = v & 15; hh = (v >> 5) & 15; hw = (v >> 10) & 31; plane = (lane & 1) ^ ((hw >> 3) & 1);
     }
-};
-// Per-tile constants of the halo copies.
-struct HaloTile {
-    const bf16_t* origin;            // x at the halo origin (d0-1, h0-1, w0-1) of the tile (may be out of range)
-    int dlo, dhi, hlo, hhi, wlo, whi;  // halo coords inside the volume: lo <= c <= hi
+    // whether the voxel of slot j lies inside the volume
+    __device__ __forceinline__ bool inside(int j, const HaloTile& ht) const {
+        const uint32_t p = (uint32_t)pk[j >> 1];
+        const uint32_t t = (p - ht.lo2) & ((ht.hi2 | HALO_GUARD2) - (p ^ HALO_GUARD2));
+        const uint32_t g = (j & 1) ? HALO_GUARD << 16 : HALO_GUARD;
+        return (t & g) == g;
+    }
 };
 
 // Normalise + ReLU on load: the halo copies are register-free, so the transform is a read-modify-write pass over
@@ -234,8 +244,8 @@ __device__ __forceinline__ void halo_norm(char* __restrict__ hb, const HaloLane&
     for (int j = FIRST; j < FIRST + CNT; ++j) {
         const int blk = wv + 8 * j;
         int hd, hh, hw, plane;
-        hl.template coords<true>(j, hd, hh, hw, plane);
-        const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+        hl.template coords<true>(j, lane, hd, hh, hw, plane);
+        const bool in = hl.inside(j, ht);
         // Slots that every wave copies in full are rewritten by straight-line code; an entry from outside the volume
         // is written back as it came (zeros: the zero padding applies after the transform).  The last slots exist
         // for some waves and lanes only.
@@ -320,8 +330,8 @@ __device__ __forceinline__ void halo_copy_slot(int j, const HaloLane& hl, const 
     const int blk = wv + 8 * j;
     if (blk < GE::HBLK && blk * 32 + (lane >> 1) < GE::HALO_VOX) {
         int hd, hh, hw, plane;
-        hl.template coords<LEAN>(j, hd, hh, hw, plane);
-        const bool in = hd >= ht.dlo && hd <= ht.dhi && hh >= ht.hlo && hh <= ht.hhi && hw >= ht.wlo && hw <= ht.whi;
+        hl.template coords<LEAN>(j, lane, hd, hh, hw, plane);
+        const bool in = hl.inside(j, ht);
         const int rel = LEAN ? ((hd * H + hh) * W + hw) * ldx + plane * 8 : hl.rel[j];
         const bf16_t* src = in ? ht.origin + rel + choff : zero16;
         g2lds16a(src, hb_a + blk * 1024);
@@ -566,7 +576,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         if (hv >= HALO_VOX) hv = 0;
         const int hw = hv % HW, hh = (hv / HW) % HH, hd = hv / (HW * HH);
         const int plane = (lane & 1) ^ ((hw >> 3) & 1);
-        hl.pk[j >> 1] |= (hd | (hh << 4) | (hw << 8) | (plane << 13)) << (16 * (j & 1));
+        hl.pk[j >> 1] |= (int)((uint32_t)(hd | (hh << 5) | (hw << 10) | HALO_GUARD) << (16 * (j & 1)));
         hl.rel[j] = ((hd * a.H + hh) * a.W + hw) * a.ldx + plane * 8;
     }
     // weight copy q = wv + 8*i of a group: 64 consecutive (entry,row) pairs, entry = tap9*2 + plane.  The
@@ -614,7 +624,11 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         // (a position past the last tile is never read from: its origin only has to be computable)
         const int vox = (((p.n * a.D + (p.d0 - 1)) * a.H + (p.h0 - 1)) * a.W + (p.w0 - 1));
         t.origin = a.x + (int64_t)vox * a.ldx;
-        t.dlo = 1 - p.d0; t.dhi = a.D - p.d0; t.hlo = 1 - p.h0; t.hhi = a.H - p.h0; t.wlo = 1 - p.w0; t.whi = a.W - p.w0;
+        // halo coords c = voxel coordinate - (origin - 1): inside the volume for 1 - origin <= c <= extent - origin
+        const uint32_t lo = (uint32_t)(max(1 - p.d0, 0) | (max(1 - p.h0, 0) << 5) | (max(1 - p.w0, 0) << 10));
+        const uint32_t hi = (uint32_t)(min(a.D - p.d0, 15) | (min(a.H - p.h0, 15) << 5) | (min(a.W - p.w0, 31) << 10));
+        t.lo2 = lo | (lo << 16);
+        t.hi2 = hi | (hi << 16);
         return t;
     };
     constexpr int wgstride = 18 * WROWS * 8;                                       // elements of one group
