@@ -421,7 +421,9 @@ template <int TDT, bool NORM> constexpr int barrier_wait(int G) {
 // first two slices of the next column are fetched meanwhile: of column KW + 1, or (KW == 2) of the first column of the
 // group GN that follows, whose weights sit in wbn and whose halo is hbn.  The column's portion of the copy work
 // follows its matrix instructions.
-template <int COB, int TDT, int G, int KW, int SLOT, int GN, bool NORM>
+// ZERO: the first column of a tile -- every accumulator's first matrix instruction (its tap kd = 0) takes zero as its
+// addend, so nothing has to clear the accumulators between tiles.
+template <int COB, int TDT, int G, int KW, int SLOT, int GN, bool NORM, bool ZERO = false>
 __device__ __forceinline__ void column(f32x16 (&acc)[COB][Geo<TDT>::ND], Frags<COB>& f, const char* __restrict__ hbu,
                                        const char* __restrict__ wb, const char* __restrict__ hbnu, const char* __restrict__ wbn,
                                        const uint32_t (&boff)[3], const CopyCtx& c, const HaloLane& hl, const HaloTile& ht,
@@ -459,8 +461,16 @@ __device__ __forceinline__ void column(f32x16 (&acc)[COB][Geo<TDT>::ND], Frags<C
             const int d = sl - kd;
             if (d >= 0 && d < ND) {
 #pragma unroll
-                for (int cb = 0; cb < COB; ++cb)
+                for (int cb = 0; cb < COB; ++cb) {
+                    if constexpr (ZERO) {
+                        if (kd == 0) {
+                            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][kd][cb], b[sl], zero, 0, 0, 0);
+                            continue;
+                        }
+                    }
                     acc[cb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[SLOT][kd][cb], b[sl], acc[cb][d], 0, 0, 0);
+                }
             }
         }
     sched_interleave<0, 3 * ND * COB, ND + 2 + 3 * COB>();
@@ -491,10 +501,11 @@ template <int COB, int TDT, int G, int PAR, bool NORM>
 __device__ __forceinline__ void conv_group(f32x16 (&acc)[COB][Geo<TDT>::ND], Frags<COB>& f, const char* __restrict__ hb,
                                            const char* __restrict__ wb, const char* __restrict__ hbn,
                                            const char* __restrict__ wbn, const uint32_t (&boff)[3], const CopyCtx& c,
-                                           const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3]) {
+                                           const HaloLane& hl, const HaloTile& ht, const int (&wrel)[3], bool first = false) {
     constexpr int GN = (G + 1) % 3;
     constexpr int WAIT = barrier_wait<TDT, NORM>(G);
-    column<COB, TDT, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+    if (G == 0 && first) column<COB, TDT, G, 0, PAR, GN, NORM, true>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
+    else column<COB, TDT, G, 0, PAR, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
     column<COB, TDT, G, 1, PAR ^ 1, GN, NORM>(acc, f, hb, wb, hbn, wbn, boff, c, hl, ht, wrel);
     // The weights of the next group were copied behind the previous barrier; the only younger copies are halo slots,
     // of which every wave has issued WAIT (a wave that issued more waits for its oldest ones too).
@@ -514,6 +525,7 @@ template <int COB, int TDT, bool SPLIT = false, bool NORM = false, bool BSUM = f
 __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     typedef Geo<TDT> GE;
     typedef Lds<TDT, COB> LD;
+    constexpr bool ZERO_START = COB == 1 && !BSUM;
     constexpr int WBUF_BYTES = LD::WBUF_BYTES;
     constexpr int TD = GE::TD, NVB = GE::NVB, HALO_VOX = GE::HALO_VOX, HALO_BYTES = GE::HALO_BYTES, HJ = GE::HJ;
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -721,7 +733,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         }
         cc.wb_fill_a = w0n; cc.pf_w = true; cc.wsrc = wc2;
         // (after group 0: every wave is past its barrier, its sums of the last tile written)
-        conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, boff, cc, hl, ht, wrel);
+        conv_group<COB, TDT, 0, P, NORM>(acc, fr, hb, w0p, hb, w1p, boff, cc, hl, ht, wrel, ZERO_START && chunk == c_lo);
         if (pending_tile >= 0) flush_sums();
         cc.wb_fill_a = w1n; cc.pf_w = pf; cc.wsrc = wn0;
         conv_group<COB, TDT, 1, P ^ 1, NORM>(acc, fr, hb, w1p, hb, w0p, boff, cc, hl, ht, wrel);
@@ -729,7 +741,9 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         conv_group<COB, TDT, 2, P, NORM>(acc, fr, hb, w0p, hbn, w1p, boff, cc, hl, ht, wrel);
         wpar ^= 1;
     };
-    // The accumulators start a pass at zero: cleared here, and then by the epilogue as it hands each block on.
+    // The accumulators start a tile at zero.  32-channel block: the first column of a tile gives every accumulator's
+    // first matrix instruction a zero addend (a second code path for that one column).  64-channel block: the
+    // epilogue clears them as it hands each block on -- the second code path costs that kernel registers it has not got.
     f32x16 acc[COB][NVB];
 #pragma unroll
     for (int cb = 0; cb < COB; ++cb)
@@ -794,10 +808,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                             *reinterpret_cast<float4*>(row + cb * 32 + rg * 8) =
                                 make_float4(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1], acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
                 }
+                if constexpr (!ZERO_START) {
 #pragma unroll
-                for (int cb = 0; cb < COB; ++cb)
+                    for (int cb = 0; cb < COB; ++cb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
+                        for (int r = 0; r < 16; ++r) acc[cb][vb][r] = 0.f;
+                }
             }
             advance_pos();
             end_pass();
@@ -878,8 +894,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
                         const uint32_t p0 = pack_bf16(acc[cb][vb][rg * 4 + 0], acc[cb][vb][rg * 4 + 1]);
                         const uint32_t p1 = pack_bf16(acc[cb][vb][rg * 4 + 2], acc[cb][vb][rg * 4 + 3]);
                         *reinterpret_cast<uint2*>(patch + l32 * ROWB + (cb * 32 + rg * 8 + half * 4) * 2) = make_uint2(p0, p1);
+                        if constexpr (!ZERO_START) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[cb][vb][rg * 4 + r] = 0.f;
+                            for (int r = 0; r < 4; ++r) acc[cb][vb][rg * 4 + r] = 0.f;
+                        }
                     }
                 __builtin_amdgcn_wave_barrier();
                 if (vb == 0) advance_pos();   // scalar work in the shadow of the patch round trip
