@@ -332,7 +332,9 @@ __device__ __forceinline__ void halo_copy_slot(int j, const HaloLane& hl, const 
         int hd, hh, hw, plane;
         hl.template coords<LEAN>(j, lane, hd, hh, hw, plane);
         const bool in = hl.inside(j, ht);
-        const int rel = LEAN ? ((hd * H + hh) * W + hw) * ldx + plane * 8 : hl.rel[j];
+        // ((hd*H + hh)*W + hw)*ldx with 24-bit multiply-adds (full rate, where a 32-bit multiply takes four passes):
+        // hd*H + hh and W*ldx stay below 2^24 (checked on the host)
+        const int rel = LEAN ? (int)(__umul24(__umul24(hd, H) + hh, W * ldx) + __umul24(hw, ldx) + plane * 8) : hl.rel[j];
         const bf16_t* src = in ? ht.origin + rel + choff : zero16;
         g2lds16a(src, hb_a + blk * 1024);
     }
@@ -1043,6 +1045,8 @@ bool mfma_conv_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd,
     const int64_t ldmax = xd->ldc > zd->ldc ? xd->ldc : zd->ldc;
     if ((int64_t)10 * zd->h * zd->w * ldmax >= ((int64_t)1 << 31)) return false;
     if (nvox(xd) >= ((int64_t)1 << 31)) return false;   // the voxel index of a tile's origin is kept in 32 bits
+    // the halo copies' address arithmetic uses 24-bit multiplies
+    if ((int64_t)10 * zd->h + 10 >= (1 << 24) || (int64_t)zd->w * xd->ldc >= (1 << 24)) return false;
     if (xnorm && xnorm->mean_rstd && xnorm->c_norm > 0) {
         // normalise on load: every input channel normalised, on the plain tiled kernel (no packed batch of tiny
         // volumes, no input-channel split: those layers are small and keep the generic path)
