@@ -1605,11 +1605,27 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
 
     WFrags<COB> fr;
     // one tile's copies + multiply; `cur` selects the LDS stage holding `tile`
-    auto run_tile = [&](int tile_to_fetch, bool pf, const char* st, char* st_next) {
-        int n, d0, h0, w0;
-        tile_coords(tile_to_fetch, n, d0, h0, w0);
-        const bf16_t* xorg = xpart + ((((int64_t)n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
-        const bf16_t* zorg = a.dz + ((((int64_t)n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
+    // (the position of the tile to fetch is stepped, not divided out, from tile to tile: the walk is contiguous)
+    int fn, fd0, fh0, fw0;
+    tile_coords(tile_lo, fn, fd0, fh0, fw0);
+    const int lim_d = a.tiles_d * WTD, lim_w = a.tiles_w * WTW, lim_h = a.tiles_h * WTH;
+    auto step_tile = [&]() __attribute__((always_inline)) {
+        fd0 += WTD;
+        if (fd0 >= lim_d) {
+            fd0 = 0;
+            fw0 += WTW;
+            if (fw0 >= lim_w) {
+                fw0 = 0;
+                fh0 += WTH;
+                if (fh0 >= lim_h) { fh0 = 0; ++fn; }
+            }
+        }
+    };
+    auto run_tile = [&](bool pf, const char* st, char* st_next) {
+        const int n = fn, d0 = fd0, h0 = fh0, w0 = fw0;
+        // (voxel indices fit 32 bits: checked on the host)
+        const bf16_t* xorg = xpart + (int64_t)(((n * a.D + (d0 - 1)) * a.H + (h0 - 1)) * a.W + (w0 - 1)) * a.ldx;
+        const bf16_t* zorg = a.dz + (int64_t)(((n * a.D + d0) * a.H + h0) * a.W + w0) * a.lddz + co0;
         if (has4)
             wgrad_tile<COB, 4>(acc, fr, st, st_next, pf, wl, xorg, zorg, 1 - d0, a.D - d0, 1 - h0, a.H - h0, 1 - w0, a.W - w0,
                                a.D - d0, a.H - h0, a.W - w0, a.zero16, coloff, extoff, loff, wv);
@@ -1651,7 +1667,8 @@ __global__ __launch_bounds__(512) void conv3d_wgrad_kernel(WgradArgs a) {
     int par = 0;
     for (int tile = tile_lo; tile < tile_hi; ++tile, par ^= 1) {
         const bool pf = tile + 1 < tile_hi;
-        run_tile(pf ? tile + 1 : tile, pf, lds + par * WBUF_STAGE, lds + (par ^ 1) * WBUF_STAGE);
+        if (pf) step_tile();
+        run_tile(pf, lds + par * WBUF_STAGE, lds + (par ^ 1) * WBUF_STAGE);
     }
 
     // ---- write this workgroup's partial: part[slot][co][tap][ci]
@@ -1696,6 +1713,7 @@ bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dz
     // element offsets inside a tile's halo (4 slices of H x W voxels) are kept in 32 bits
     const int64_t ldmax = xd->ldc > dzd->ldc ? xd->ldc : dzd->ldc;
     if ((int64_t)4 * xd->h * xd->w * ldmax + 4096 >= ((int64_t)1 << 31)) return false;
+    if (nvox(xd) >= ((int64_t)1 << 31)) return false;   // the voxel index of a tile's origin is kept in 32 bits
     return true;
 }
 
