@@ -1717,8 +1717,21 @@ bool mfma_wgrad_supported(const lamp_tensor_desc* xd, const lamp_tensor_desc* dz
     return true;
 }
 
+// A batch of tiny volumes is laid out as one volume with a row / column of zeros between the samples, like the
+// forward and data-gradient passes do (conv_pack_plan): the zeros are both neighbours' padding in x and contribute
+// nothing in dz, so the weight gradient of the packed pair is the sum of the samples' weight gradients, over far fewer,
+// fuller tiles.
+static bool wgrad_pack_plan(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd, PackPlan& pp) {
+    return xd->c % 8 == 0 && dzd->c % 8 == 0 && conv_pack_plan(dzd, pp);
+}
 size_t mfma_wgrad_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* dzd) {
     if (!mfma_wgrad_supported(xd, dzd, nullptr)) return 0;
+    PackPlan pp;
+    if (wgrad_pack_plan(xd, dzd, pp)) {
+        lamp_tensor_desc xp, zp;
+        pack_descs(xd, dzd, pp, xp, zp);
+        return align_up((size_t)nvox(&xp) * xp.c * 2) + align_up((size_t)nvox(&zp) * zp.c * 2) + mfma_wgrad_ws_bytes(&xp, &zp) + 512;
+    }
     return align_up((size_t)wgrad_slots(xd, dzd) * dzd->c * 27 * xd->c * sizeof(float)) + 256;
 }
 
@@ -1728,6 +1741,26 @@ lamp_status mfma_wgrad(const lamp_tensor_desc* xd, const void* x, const lamp_ten
     if ((((uintptr_t)x) & 15u) || (((uintptr_t)dz) & 15u) || (((uintptr_t)ws) & 15u)) return LAMP_ERR_ALIGN;
     if (x2 && ((((uintptr_t)x2) & 15u) || x_c1 % 32 || x_c1 <= 0 || x_c1 >= xd->c)) return LAMP_ERR_ALIGN;
     if (ws_bytes < mfma_wgrad_ws_bytes(xd, dzd)) return LAMP_ERR_WORKSPACE;
+    PackPlan pp;
+    if (wgrad_pack_plan(xd, dzd, pp)) {
+        lamp_tensor_desc xp, zp;
+        pack_descs(xd, dzd, pp, xp, zp);
+        Carver pc(ws, ws_bytes);
+        bf16_t* xpk = (bf16_t*)pc.take((size_t)nvox(&xp) * xp.c * 2);
+        bf16_t* zpk = (bf16_t*)pc.take((size_t)nvox(&zp) * zp.c * 2);
+        const size_t inner = mfma_wgrad_ws_bytes(&xp, &zp);
+        void* iws = pc.take(inner);
+        if (!pc.ok()) return LAMP_ERR_WORKSPACE;
+        const int64_t gx = nvox(&xp) * (xp.c / 8), gz = nvox(&zp) * (zp.c / 8);
+        hipLaunchKernelGGL(conv_pack_kernel, dim3(cdiv(gx, 256)), dim3(256), 0, s, (const bf16_t*)x, xd->ldc,
+                           x2 ? (const bf16_t*)x2 : (const bf16_t*)x, x2 ? x_c1 : xd->c, xpk, xd->n, xd->d, xd->h, xd->w, xd->c,
+                           pp.gw, pp.hp, pp.wp);
+        LAMP_CHECK_LAUNCH();
+        hipLaunchKernelGGL(conv_pack_kernel, dim3(cdiv(gz, 256)), dim3(256), 0, s, (const bf16_t*)dz, dzd->ldc, (const bf16_t*)dz,
+                           dzd->c, zpk, dzd->n, dzd->d, dzd->h, dzd->w, dzd->c, pp.gw, pp.hp, pp.wp);
+        LAMP_CHECK_LAUNCH();
+        return mfma_wgrad(&xp, xpk, &zp, zpk, dw, beta, iws, inner, s, nullptr, 0);
+    }
     WgradArgs a;
     a.x = (const bf16_t*)x; a.ldx = xd->ldc; a.dz = (const bf16_t*)dz; a.lddz = dzd->ldc; a.part = (float*)ws;
     a.x2 = (const bf16_t*)x2; a.xsplit = x2 ? x_c1 : 0x7fffffff;

@@ -156,7 +156,7 @@ def test_conv3d_many_small_volumes_bf16(L, shape):
     """A batch of tiny volumes (the deep levels of a batch of sliding windows): the library lays the
     samples out as one volume with zero gaps between them, so that tiles are filled; every sample must
     still see its own zero padding and its own statistics.  Forward with statistics, forward into a
-    channel slice, data gradient."""
+    channel slice, data gradient, weight gradient."""
     N, D, H, W, Ci, Co = shape
     r = rng(1500 + sum(shape))
     x = to_dev(S.normal(r, (N, D, H, W, Ci)) + 0.5, BF)   # non-zero mean: a neighbour leaking in would show
@@ -182,6 +182,21 @@ def test_conv3d_many_small_volumes_bf16(L, shape):
     for n in (0, N - 1):
         L.lamp_conv3d_fwd(x[n:n + 1], w, z1)
         assert torch.equal(z1[0], z[n]), f"sample {n} differs between the packed batch and a call of its own"
+    # weight gradient on the same layout: the sum over the samples (the gaps add nothing), plain and accumulated,
+    # and from an input that is a channel slice of a wider buffer
+    if Ci % 32 == 0:
+        dw = torch.full((Co, 3, 3, 3, Ci), float("nan"), dtype=F32, device=DEV)
+        L.lamp_conv3d_wgrad(x, dz, dw)
+        dw_ref, _ = O.conv3d_wgrad(as64(x), as64(dz), want_db=True)
+        check(as64(dw), dw_ref, BF, "conv wgrad (packed batch)", tol=2e-3)
+        dw2 = dw.clone()
+        L.lamp_conv3d_wgrad(x, dz, dw2, beta=1.0)
+        check(as64(dw2), 2 * dw_ref, BF, "conv wgrad beta=1 (packed batch)", tol=2e-3)
+        xbuf = torch.zeros((N, D, H, W, Ci + 8), dtype=BF, device=DEV)
+        xbuf[..., 8:] = x
+        dw3 = torch.empty_like(dw)
+        L.lamp_conv3d_wgrad(xbuf[..., 8:], dz, dw3)
+        assert torch.equal(dw3, dw), "weight gradient of a channel slice differs from that of the dense tensor"
 
 
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
