@@ -109,25 +109,28 @@ __global__ __launch_bounds__(256) void stats_partial_kernel(const T* __restrict_
 // fp64 in a fixed order (strided per thread, four parts in flight, then a fixed tree over lanes and
 // waves), and mean / variance follow from the totals in fp64: with fp32 part sums as the input this
 // loses nothing against merging per-part means and second moments.
-__global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __restrict__ partial,
-                                                             const int32_t* __restrict__ counts, int parts, int C,
-                                                             float eps, float* __restrict__ stats, int counts_per_sample) {
-    __shared__ double sh[4][3];
+// NT threads per (sample, channel): 256, or 1024 where there are thousands of parts (the loop over them is a chain of
+// strided loads: its length, not the bytes, is what the kernel takes).
+template <int NT>
+__global__ __launch_bounds__(NT) void stats_finalize_kernel(const float* __restrict__ partial,
+                                                            const int32_t* __restrict__ counts, int parts, int C,
+                                                            float eps, float* __restrict__ stats, int counts_per_sample) {
+    __shared__ double sh[NT / 64][3];
     const int c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int32_t* cnt = counts + (counts_per_sample ? (size_t)n * parts : (size_t)0);
     const float2* pp = reinterpret_cast<const float2*>(partial) + (size_t)n * parts * C + c;
     double k = 0.0, sm = 0.0, sq = 0.0;
     int p = tid;
-    for (; p + 768 < parts; p += 1024) {
+    for (; p + 3 * NT < parts; p += 4 * NT) {
         float2 v[4];
         int32_t kk[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { v[u] = pp[(size_t)(p + 256 * u) * C]; kk[u] = cnt[p + 256 * u]; }
+        for (int u = 0; u < 4; ++u) { v[u] = pp[(size_t)(p + NT * u) * C]; kk[u] = cnt[p + NT * u]; }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
             if (kk[u] > 0) { k += (double)kk[u]; sm += (double)v[u].x; sq += (double)v[u].y; }
     }
-    for (; p < parts; p += 256) {
+    for (; p < parts; p += NT) {
         const float2 v = pp[(size_t)p * C];
         const int32_t kk = cnt[p];
         if (kk > 0) { k += (double)kk; sm += (double)v.x; sq += (double)v.y; }
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __rest
     if (lane == 0) { sh[wv][0] = k; sh[wv][1] = sm; sh[wv][2] = sq; }
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 4; ++w) { k += sh[w][0]; sm += sh[w][1]; sq += sh[w][2]; }
+        for (int w = 1; w < NT / 64; ++w) { k += sh[w][0]; sm += sh[w][1]; sq += sh[w][2]; }
         double mean = 0.0, var = 0.0;
         if (k > 0.0) {
             mean = sm / k;
@@ -154,8 +157,12 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const float* __rest
 
 lamp_status launch_stats_finalize(const float* partials, const int32_t* counts, int parts, int N, int C,
                                   float eps, float* stats, hipStream_t s, bool counts_per_sample) {
-    hipLaunchKernelGGL(stats_finalize_kernel, dim3(C, N), dim3(256), 0, s, partials, counts, parts, C, eps, stats,
-                       counts_per_sample ? 1 : 0);
+    if (parts >= 4096)
+        hipLaunchKernelGGL(stats_finalize_kernel<1024>, dim3(C, N), dim3(1024), 0, s, partials, counts, parts, C, eps, stats,
+                           counts_per_sample ? 1 : 0);
+    else
+        hipLaunchKernelGGL(stats_finalize_kernel<256>, dim3(C, N), dim3(256), 0, s, partials, counts, parts, C, eps, stats,
+                           counts_per_sample ? 1 : 0);
     LAMP_CHECK_LAUNCH();
     return LAMP_OK;
 }
