@@ -40,8 +40,19 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     const int ol = threadIdx.x % OPB, sl = threadIdx.x / OPB;
     const int64_t o = (int64_t)blockIdx.x * OPB + ol;
     double acc = 0.0;
-    if (o < O)
-        for (int s = sl; s < S; s += SL) acc += (double)part[(int64_t)s * O + o];
+    if (o < O) {
+        // eight loads in flight, added in the order of the parts: a loop of load-then-add is a chain of memory
+        // latencies (32 of them for 256 parts), which is what this kernel's time was
+        int s = sl;
+        for (; s + 7 * SL < S; s += 8 * SL) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(s + u * SL) * O + o];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += (double)v[u];
+        }
+        for (; s < S; s += SL) acc += (double)part[(int64_t)s * O + o];
+    }
     sh[sl][ol] = acc;
     __syncthreads();
     if (sl == 0 && o < O) {
