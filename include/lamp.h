@@ -42,6 +42,8 @@
  *                             a block's first conv output while the second conv loads it
  *       no_bsum=1             lamp_conv3d_dgrad_inorm_relu_bwd runs its two steps as separate passes (the sums of
  *                             the backward from a reduction pass instead of the data gradient's epilogue)
+ *       no_walk_stats=1       the matrix-core conv writes its statistics partials per tile for every shape (default:
+ *                             per workgroup walk where the output-channel block is 32 wide and walks are long)
  */
 #ifndef LAMP_H
 #define LAMP_H

@@ -135,6 +135,9 @@ struct ConvArgs {
     bf16_t* z; int ldz;
     float* part;        // [N][tiles_per_n][Cout][2] or nullptr
     int32_t* counts;    // [tiles_per_n] in-volume voxels per tile (written when part != nullptr)
+    // 32-channel block with long walks: one partial per (sample, workgroup walk) instead of per tile -- part is
+    // [N][walk_parts][Cout][2], counts [N][walk_parts] (0 where a walk holds no tile of the sample); 0: per tile
+    int walk_parts;
     const bf16_t* zero16;  // 16 zero bytes in global memory (source of the zero padding)
     const float* bias;     // [Cout] fp32 added to the accumulators before rounding and the statistics, or nullptr
     // Normalise + ReLU while loading (NORM instantiations): per (sample, input channel) the pair (a, b) of
@@ -648,8 +651,23 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
     constexpr int wgstride = 18 * WROWS * 8;                                       // elements of one group
     const bf16_t* wbase = a.wp + (int64_t)cbi * nchunks * (3 * wgstride);    // + (chunk*3 + g) * wgstride
 
+    // Statistics per walk (32-channel block): the channel sums stay in registers from tile to tile, and are folded
+    // and written when the walk ends or moves on to the next sample -- not once per tile, where the fold and the
+    // write are a twentieth of that kernel's instructions.
+    constexpr bool WALK_OK = COB == 1 && !SPLIT && !BSUM;
+    const bool walk = WALK_OK && a.walk_parts > 0;
+    const int walker = xcd * wg_per_xcd + local;
     int tile = tile_lo + local;
-    if (tile >= tile_hi) return;
+    if (tile >= tile_hi) {
+        if (walk && a.counts && tid == 0 && cbi == 0)
+            for (int n = 0; n < a.N; ++n) a.counts[n * a.walk_parts + walker] = 0;
+        return;
+    }
+    const int first_n = tile / a.tiles_per_n;
+    int last_n = first_n, wcount = 0;
+    float ksum[WALK_OK ? 8 : 1], ksq[WALK_OK ? 8 : 1];
+#pragma unroll
+    for (int e = 0; e < (WALK_OK ? 8 : 1); ++e) { ksum[e] = 0.f; ksq[e] = 0.f; }
 
     // Where the tile of this pass and the one after it lie.  The position of the tile after those is worked out during
     // the epilogue, whose LDS round trips leave the scalar unit idle: at the top of a pass it would hold up the first
@@ -696,7 +714,7 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             for (int q = 0; q < 8; ++q) v += sred[q * 128 + c * 2 + k];
             a.part[((int64_t)pending_tile * a.Cout + co0 + c) * 2 + k] = v;
         }
-        if (a.counts && tid == 0 && cbi == 0 && pending_tile < a.tiles_per_n) a.counts[pending_tile] = pending_count;
+        if (a.counts && tid == 0 && cbi == 0 && (walk || pending_tile < a.tiles_per_n)) a.counts[pending_tile] = pending_count;
         pending_tile = -1;
     };
     // The multiply pipeline: every column fetches the fragments of the next one, across groups, chunks and tiles.
@@ -839,7 +857,10 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         const int part = lane_e % PARTS, prow = lane_e / PARTS;
         float csum[8], csq[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { csum[e] = 0.f; csq[e] = 0.f; }
+        for (int e = 0; e < 8; ++e) {
+            csum[e] = WALK_OK ? ksum[WALK_OK ? e : 0] : 0.f;
+            csq[e] = WALK_OK ? ksq[WALK_OK ? e : 0] : 0.f;
+        }
         // Where this lane's 16-byte pieces go.  Its 8 channels, and with them the tensor and the channel
         // stride, are fixed; the tile origin is wave-uniform; what is left per store is a small offset
         // inside the tile.  Tiles that lie inside the volume (all but the ragged rim) skip the bounds tests.
@@ -972,7 +993,18 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         };
         if (full) store_blocks(std::true_type{});
         else store_blocks(std::false_type{});
-        if (a.part) {
+        const int tile_count = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
+        bool fold_now = a.part != nullptr;
+        if constexpr (WALK_OK) {
+            wcount += tile_count;
+            last_n = n;
+            if (walk && next_tile < tile_hi && pos_next.n == n) {   // the walk goes on inside this sample
+                fold_now = false;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ksum[e] = csum[e]; ksq[e] = csq[e]; }
+            }
+        }
+        if (fold_now) {
             // Lanes with equal `part` hold the same 8 channels.  Inside a row of 16 lanes they are folded by
             // rotations of the row (data-parallel primitives: no LDS traffic, where lane exchanges through the
             // LDS cost more than the tile's whole transpose); the 4 rows of a wave and the 8 waves are added by
@@ -1004,8 +1036,13 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
             }
             // No barrier: the sums are added up and written behind the first barrier of the next tile (after the
             // last tile: behind a barrier of their own), which every wave reaches with its rows written.
-            pending_tile = tile;
-            pending_count = min(TD, a.D - d0) * min(TH, a.H - h0) * min(TW, a.W - w0);
+            pending_tile = walk ? n * a.walk_parts + walker : tile;
+            pending_count = walk ? wcount : tile_count;
+            if constexpr (WALK_OK) {
+                wcount = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ksum[e] = 0.f; ksq[e] = 0.f; }
+            }
         }
         end_pass();
         // No barrier here: the next copies into the patch buffer go out behind the barrier of the next tile's first
@@ -1016,6 +1053,12 @@ __global__ __launch_bounds__(512) void conv3d_igemm_kernel(ConvArgs a) {
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         flush_sums();
+    }
+    if constexpr (WALK_OK) {
+        // the samples this walk holds no tile of
+        if (walk && a.counts && tid == 0 && cbi == 0)
+            for (int n = 0; n < a.N; ++n)
+                if (n < first_n || n > last_n) a.counts[n * a.walk_parts + walker] = 0;
     }
 }
 
@@ -1208,8 +1251,9 @@ size_t mfma_conv_ws_bytes(const lamp_tensor_desc* xd, const lamp_tensor_desc* zd
     // repacked weights + a run of zeros (source of the zero padding) + 16 bytes that absorb masked stores
     size_t b = align_up((size_t)27 * xd->c * zd->c * 2 + 2 * xd->c + 64);
     if (want_stats) {
-        // partial statistics: one per tile
-        b += align_up((size_t)zd->n * tiles * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * tiles * sizeof(int32_t));
+        // partial statistics: one per tile, or one per (sample, workgroup walk) -- at most 256 walks
+        const size_t parts = tiles > 256 ? tiles : 256;
+        b += align_up((size_t)zd->n * parts * zd->c * 2 * sizeof(float)) + align_up((size_t)zd->n * parts * sizeof(int32_t));
     }
     const int S = conv_splits(xd, zd);
     if (S > 1) b += align_up((size_t)S * nvox(zd) * zd->c * sizeof(float)) + stats_ws_bytes(zd) + 256;
@@ -1286,9 +1330,16 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     bf16_t* wp = (bf16_t*)cv.take((size_t)27 * xd->c * zd->c * 2 + 16);
     float* part = nullptr;
     int32_t* counts = nullptr;
+    // one persistent workgroup per CU (LDS-limited), 32 per XCD; fewer where there are fewer tiles
+    int wgx = 256;
+    while (wgx > 8 && (wgx / 8) > (tiles_per_n * zd->n + 7) / 8) wgx -= 8;
+    // statistics per walk: 32-channel block, at least four tiles to a walk (below that the per-tile partials are as few)
+    const bool walk = stats_out && !bsum && zd->c % 64 != 0 && conv_splits(xd, zd) == 1 && !tune("no_walk_stats", 0) &&
+                      (int64_t)tiles_per_n * zd->n >= 4 * wgx;
     if (stats_out) {
-        part = (float*)cv.take((size_t)zd->n * tiles_per_n * zd->c * 2 * sizeof(float));
-        counts = (int32_t*)cv.take((size_t)tiles_per_n * sizeof(int32_t));
+        const size_t parts = walk ? (size_t)wgx : (size_t)tiles_per_n;
+        part = (float*)cv.take((size_t)zd->n * parts * zd->c * 2 * sizeof(float));
+        counts = (int32_t*)cv.take((walk ? (size_t)zd->n * wgx : (size_t)tiles_per_n) * sizeof(int32_t));
     }
     float2* ab = nullptr;
     if (norm) ab = (float2*)cv.take((size_t)xd->n * xd->c * sizeof(float2));
@@ -1327,8 +1378,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     a.tiles_total = tiles_per_n * zd->n;
     a.tiles_per_xcd = (a.tiles_total + 7) / 8;
     const int cob = (zd->c % 64 == 0) ? 2 : 1;
-    int wgx = 256;  // one persistent workgroup per CU (LDS-limited), 32 per XCD
-    while (wgx > 8 && (wgx / 8) > a.tiles_per_xcd) wgx -= 8;
+    a.walk_parts = walk ? wgx : 0;
     dim3 grid(wgx, zd->c / (32 * cob));
     a.zpart = nullptr; a.cps = 0;
     a.xcd_rot = a.tiles_total < 32 ? 1 : 0;
@@ -1368,7 +1418,7 @@ lamp_status mfma_conv_fwd(const lamp_tensor_desc* xd, const void* x, const void*
     } else if (TDT == 8) st = cob == 2 ? launch_igemm<2, 8>(a, grid, s) : launch_igemm<1, 8>(a, grid, s);
     else st = cob == 2 ? launch_igemm<2, 4>(a, grid, s) : launch_igemm<1, 4>(a, grid, s);
     if (st != LAMP_OK) return st;
-    if (stats_out) return launch_stats_finalize(part, counts, tiles_per_n, zd->n, zd->c, eps, stats_out, s);
+    if (stats_out) return launch_stats_finalize(part, counts, walk ? wgx : tiles_per_n, zd->n, zd->c, eps, stats_out, s, walk);
     return LAMP_OK;
 }
 

@@ -199,6 +199,51 @@ def test_conv3d_many_small_volumes_bf16(L, shape):
         assert torch.equal(dw3, dw), "weight gradient of a channel slice differs from that of the dense tensor"
 
 
+@pytest.mark.parametrize("shape", [(3, 48, 70, 110, 32, 32), (2, 64, 80, 112, 16, 96)], ids=lambda s: "x".join(map(str, s)))
+def test_conv3d_stats_per_walk(L, shape):
+    """Volumes large enough that the 32-channel block of the matrix-core conv writes its statistics partials per
+    workgroup walk instead of per tile (at least four 8-deep tiles to each of the 256 walks), with walks that cross
+    from one sample into the next (the XCD ranges of tiles do not end at sample boundaries) and samples of different
+    means: the statistics are those of the stored z of each sample -- against the oracle and against the stand-alone
+    statistics pass over the same tensor."""
+    N, D, H, W, Ci, Co = shape
+    r = rng(1700 + sum(shape))
+    xh = S.normal(r, (N, D, H, W, Ci))
+    for n in range(N):
+        xh[n] += 0.5 * (n + 1)          # a partial that landed in the wrong sample's slot would show
+    x = to_dev(xh, BF)
+    w = to_dev(S.kaiming_conv(r, Co, Ci), BF)
+    z = torch.empty((N, D, H, W, Co), dtype=BF, device=DEV)
+    stats = torch.full((N, Co, 2), float("nan"), dtype=F32, device=DEV)
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats)
+    _, st_ref = O.inorm_relu(as64(z))
+    check(as64(stats)[..., 0], st_ref[..., 0], F32, "stats mean (per walk)", tol=1e-4)
+    np.testing.assert_allclose(as64(stats)[..., 1], st_ref[..., 1], rtol=2e-4)
+    y = torch.empty_like(z)
+    stats2 = torch.empty_like(stats)
+    L.lamp_inorm_relu(z, y, stats2)
+    np.testing.assert_allclose(as64(stats)[..., 0], as64(stats2)[..., 0], atol=2e-5 * float(np.abs(st_ref[..., 0]).max() + 1.0))
+    np.testing.assert_allclose(as64(stats)[..., 1], as64(stats2)[..., 1], rtol=5e-5)
+    # a second call into the same buffers gives the same bits (slots of walks without a tile of a sample are not read)
+    stats3 = torch.full_like(stats, float("nan"))
+    L.lamp_conv3d_fwd(x, w, z, stats_out=stats3)
+    assert torch.equal(stats3, stats)
+    # sampled output voxels against the oracle's definition (the volume is too large for the full oracle conv in a test)
+    xs, ws_ = as64(x), as64(w)
+    rr = np.random.default_rng(7)
+    for _ in range(24):
+        n, d, h, ww = int(rr.integers(N)), int(rr.integers(D)), int(rr.integers(H)), int(rr.integers(W))
+        acc = np.zeros(Co)
+        for kd in range(3):
+            for kh in range(3):
+                for kw in range(3):
+                    dd, hh, wq = d + kd - 1, h + kh - 1, ww + kw - 1
+                    if 0 <= dd < D and 0 <= hh < H and 0 <= wq < W:
+                        acc += ws_[:, kd, kh, kw, :] @ xs[n, dd, hh, wq, :]
+        got = as64(z[n, d, h, ww])
+        assert np.max(np.abs(got - acc)) <= 1e-2 * max(1.0, float(np.max(np.abs(acc)))), (n, d, h, ww)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1, 32, 32), (1, 2, 2, 2, 64, 64), (3, 1, 1, 17, 16, 32), (2, 1, 3, 1, 1, 32), (1, 2, 1, 1, 128, 64)],
                          ids=lambda s: "x".join(map(str, s)))
